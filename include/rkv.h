@@ -1,0 +1,156 @@
+/*
+ * rkv - RotateKV's 2-bit KV-cache hot path for AMD MI355X (gfx950), C ABI.
+ *
+ * The library implements the write half and the read half of RotateKV (arXiv 2501.16383):
+ *   write  (Sec. 4.1, 4.2, 4.4; Eq. 6-9): grouped-head Walsh-Hadamard rotation of pre-RoPE keys,
+ *          calibrated channel reorder, per-token asymmetric 2-bit quantization in blocks of 128
+ *          with an fp16 scale and an fp16 integer zero-point per block, attention-sink tokens
+ *          kept in fp16 (Sec. 4.3);
+ *   read   (decoding phase, Eq. 4-5; Sec. 4.4 "inverse online reordering and rotation"):
+ *          dequantize, undo reorder and rotation, RoPE, softmax(q.K^T/sqrt(d)).V.
+ *
+ * General rules
+ *   - Every pointer named dev_* is DEVICE memory owned by the caller; host_* is host memory.
+ *     The library never allocates or frees device memory: the cache lives in a block the caller
+ *     hands to rkv_cache_create, work space comes in through dev_scratch.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Unless stated
+ *     otherwise a call only enqueues work on that stream and returns without synchronising.
+ *   - Every call returns RKV_OK (0) or a negative error code; nothing is thrown across the ABI.
+ *     On RKV_EHIP the HIP error is left readable through hipGetLastError.
+ *   - One cache object holds one layer.  All sequences of a cache have the same length.
+ *   - Tensors are dense, row-major, in the index order written next to each argument.
+ *     A token's keys/values are [n_kv_heads][head_dim] (head-major), E = n_kv_heads*head_dim.
+ *   - Keys are given and stored PRE-RoPE; RoPE is applied inside rkv_decode_attention to the
+ *     query (at q_pos) and to every cached key (at its 0-based token index).
+ */
+#ifndef RKV_H_
+#define RKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RKV_OK         0
+#define RKV_EINVAL    (-1)  /* null pointer, unsupported shape or option, size too small          */
+#define RKV_ECAPACITY (-2)  /* append past max_tokens                                            */
+#define RKV_EPERM     (-3)  /* reorder indices are not a permutation or leave their perm_span    */
+#define RKV_EHIP      (-4)  /* a HIP call or kernel launch failed                                */
+#define RKV_ESTATE    (-5)  /* call not valid in the cache's current state (e.g. empty cache)    */
+
+typedef struct rkv_config {
+  int32_t batch;        /* sequences per cache, >= 1                                             */
+  int32_t n_q_heads;    /* query heads; multiple of n_kv_heads (GQA: query head h reads KV head  */
+                        /* h / (n_q_heads / n_kv_heads))                                          */
+  int32_t n_kv_heads;
+  int32_t head_dim;     /* 128                                                                   */
+  int32_t max_tokens;   /* capacity per sequence                                                 */
+  int32_t max_sinks;    /* fp16 sink rows kept per sequence (0..64)                              */
+  int32_t rot_heads;    /* consecutive KV heads rotated together (Sec. 4.2): 1, 2, 4 or 8;       */
+                        /* must divide n_kv_heads                                                */
+  int32_t quant_group;  /* 128 (Sec. 5.1 quantization settings)                                  */
+  int32_t bits;         /* 2                                                                     */
+  int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
+                        /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
+                        /* printed sorts the whole row)                                           */
+  int32_t rope_style;   /* 0: channel j pairs with j+64; 1: channel 2j pairs with 2j+1          */
+  int32_t v_rotate;     /* 0: values are quantized as given (the caller has folded the value    */
+                        /* rotation of Sec. 4.4 into its weights); 1: the library applies a      */
+                        /* per-head Hadamard before quantizing and undoes it on the output       */
+  float   rope_theta;   /* RoPE base, e.g. 10000 or 500000                                       */
+  float   clip_ratio;   /* 1.0 (Eq. 8-9 with no clipping)                                        */
+} rkv_config;
+
+typedef struct rkv_cache rkv_cache;   /* opaque host object */
+
+/* Bytes of device memory a cache needs (cache_bytes, for rkv_cache_create) and bytes of work
+ * space rkv_decode_attention / rkv_calibrate_perm need (scratch_bytes).  Either out-pointer may
+ * be NULL.  RKV_EINVAL if cfg is unsupported. */
+int rkv_query_sizes(const rkv_config* cfg, size_t* cache_bytes, size_t* scratch_bytes);
+
+/* Bind a cache to caller-owned device memory (256-byte aligned, >= cache_bytes).  Zero-fills the
+ * block, writes the identity reorder and the RoPE angle table on `stream`.  *out is a small host
+ * object; free it with rkv_cache_destroy (which never touches dev_mem). */
+int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t bytes, void* stream, rkv_cache** out);
+void rkv_cache_destroy(rkv_cache* cache);
+
+/* Forget all tokens and sinks (length 0); keeps the reorder indices. */
+int rkv_cache_reset(rkv_cache* cache, void* stream);
+
+/* Tokens currently cached per sequence (host-side count), or RKV_EINVAL. */
+int rkv_cache_length(const rkv_cache* cache);
+
+/* Calibration for reordering indices (Alg. 1): rotate the calibration keys with the grouped-head
+ * Hadamard, sum every channel over all tokens (signed, float64), and sort channel indices by that
+ * sum - ascending, stable, inside each perm_span block.
+ *   dev_k_cal      [n_tok][n_kv_heads][head_dim] fp16, pre-RoPE
+ *   dev_perm_out   [E] int32: reordered channel i takes rotated channel perm[i]
+ *   dev_scratch    >= scratch_bytes of rkv_query_sizes
+ * cfg->batch, max_tokens and max_sinks are ignored. */
+int rkv_calibrate_perm(const rkv_config* cfg, const void* dev_k_cal, int32_t n_tok,
+                       int32_t* dev_perm_out, void* dev_scratch, void* stream);
+
+/* Install reorder indices (Sec. 4.1).  Only valid on an empty cache.  Copies the indices to the
+ * host to validate them (synchronises `stream`): RKV_EPERM if they are not a permutation of
+ * 0..E-1 or move a channel out of its perm_span block. */
+int rkv_set_perm(rkv_cache* cache, const int32_t* dev_perm, void* stream);
+
+/* Write half: compress n_new tokens per sequence and append them at the current length.
+ *   dev_k, dev_v    [batch][n_new][n_kv_heads][head_dim] fp16, keys pre-RoPE
+ *   dev_sink_mask   [batch][n_new] uint8 or NULL; a non-zero entry marks an attention-sink token
+ *                   (Sec. 4.3) whose original fp16 rows are kept.  While a sequence already holds
+ *                   max_sinks sinks, further marked tokens are treated as ordinary tokens.
+ * Works for one token (decode step) or many (prefill).  RKV_ECAPACITY past max_tokens. */
+int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, int32_t n_new,
+                        const uint8_t* dev_sink_mask, void* stream);
+
+/* Read half: one decode step of attention over the whole cache (Eq. 5).
+ *   dev_q      [batch][n_q_heads][head_dim] fp16, pre-RoPE
+ *   dev_q_pos  [batch] int32 position of the query token, or NULL for (length - 1)
+ *   dev_out    [batch][n_q_heads][head_dim] fp32
+ *   dev_lse    [batch][n_q_heads] fp32 log-sum-exp of the scaled scores, or NULL
+ *   dev_scratch >= scratch_bytes of rkv_query_sizes; calls sharing a scratch block must be
+ *              ordered on one stream.
+ * RKV_ESTATE on an empty cache. */
+int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos,
+                         float* dev_out, float* dev_lse, void* dev_scratch, void* stream);
+
+/* Choose the decode kernel: 0 = automatic (default), 1 = force the general kernel (any supported
+ * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
+ * the configuration is outside what it covers). */
+int rkv_set_decode_path(rkv_cache* cache, int32_t path);
+
+/* ---- test support: exact views of what the cache stores ------------------------------------- */
+
+/* Reconstructed keys and values (Eq. 7, inverse reorder, inverse rotation), original basis, keys
+ * pre-RoPE, fp32 [batch][length][n_kv_heads][head_dim].  Sink rows are NOT substituted.
+ * Either pointer may be NULL. */
+int rkv_dequantize(rkv_cache* cache, float* dev_k_hat, float* dev_v_hat, void* stream);
+
+/* The logical code array in canonical bytes, independent of the physical layout:
+ *   dev_k_codes, dev_v_codes  [batch][length][E/4] uint8: byte j of a token holds reordered
+ *                             channels 4j..4j+3, channel 4j+r in bits [2r, 2r+1]
+ *   dev_k_scale, dev_k_zero, dev_v_scale, dev_v_zero   [batch][length][E/128] fp32
+ * Any pointer may be NULL. */
+int rkv_export_codes(rkv_cache* cache, uint8_t* dev_k_codes, float* dev_k_scale, float* dev_k_zero,
+                     uint8_t* dev_v_codes, float* dev_v_scale, float* dev_v_zero, void* stream);
+
+/* Overwrite the cache contents with n_tokens tokens given in the same canonical form (scale and
+ * zero must be exactly representable in fp16); sets length = n_tokens, keeps sinks and perm. */
+int rkv_import_codes(rkv_cache* cache, int32_t n_tokens, const uint8_t* dev_k_codes,
+                     const float* dev_k_scale, const float* dev_k_zero, const uint8_t* dev_v_codes,
+                     const float* dev_v_scale, const float* dev_v_zero, void* stream);
+
+/* The sink store: dev_count [batch] int32, dev_pos [batch][max_sinks] int32 (token index, -1 if
+ * unused), dev_k / dev_v [batch][max_sinks][E] fp16.  Any pointer may be NULL. */
+int rkv_export_sinks(rkv_cache* cache, int32_t* dev_count, int32_t* dev_pos, void* dev_k, void* dev_v,
+                     void* stream);
+
+const char* rkv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RKV_H_ */

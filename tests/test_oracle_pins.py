@@ -1,0 +1,398 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, checked without the GPU.
+
+Each test is chosen so that a plausible slip in oracle/rkv_oracle.py (a dropped term, a wrong
+sign or index, a transposed operand, the wrong order of rotate and reorder) fails at least one.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import scipy.linalg
+
+from oracle import rkv_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                out.append(line.split())
+    return out
+
+
+# ----------------------------------------------------------------------------- Hadamard (Eq. 10)
+
+@pytest.mark.parametrize("n", [1, 2, 4, 128, 256, 512])
+def test_hadamard_closed_form_and_library(n):
+    H = O.hadamard(n)
+    i = np.arange(n)
+    pop = np.array([[bin(a & b).count("1") for b in i] for a in i])
+    closed = (-1.0) ** pop / np.sqrt(n)
+    assert np.allclose(H, closed, atol=1e-15)
+    assert np.allclose(H, scipy.linalg.hadamard(n) / np.sqrt(n), atol=1e-15)
+
+
+@pytest.mark.parametrize("n", [2, 128, 512])
+def test_hadamard_orthogonal_symmetric_self_inverse(n):
+    H = O.hadamard(n)
+    assert np.array_equal(H, H.T)
+    assert np.allclose(H @ H, np.eye(n), atol=1e-12)
+    Hi = np.rint(H * np.sqrt(n)).astype(np.int64)          # un-normalised: exactly n*I in integers
+    assert np.array_equal(Hi @ Hi, n * np.eye(n, dtype=np.int64))
+    e0 = np.zeros(n)
+    e0[0] = 1.0
+    assert np.allclose(H @ e0, 1.0 / np.sqrt(n))
+
+
+def test_rotation_parseval_and_group_locality():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((3, 1024))
+    y = O.rotate_groups(x, 256)
+    for r in range(4):
+        assert np.allclose((y[:, r * 256:(r + 1) * 256] ** 2).sum(1), (x[:, r * 256:(r + 1) * 256] ** 2).sum(1))
+    x2 = x.copy()
+    x2[:, 300] += 1.0                         # a change in group 1 must stay in group 1
+    d = O.rotate_groups(x2, 256) - y
+    assert np.all(d[:, :256] == 0) and np.all(d[:, 512:] == 0) and np.all(np.abs(d[:, 256:512]) > 0)
+
+
+def _fwht_counting(x):
+    """Textbook in-place butterfly FWHT (un-normalised) that counts its additions."""
+    x = np.array(x, dtype=np.float64)
+    n, h, adds = x.shape[0], 1, 0
+    while h < n:
+        for i in range(0, n, 2 * h):
+            for j in range(i, i + h):
+                a, b = x[j], x[j + h]
+                x[j], x[j + h] = a + b, a - b
+                adds += 2
+        h *= 2
+    return x, adds
+
+
+def test_fwht_cost_matches_paper_table():
+    """The dense rotation equals a butterfly FWHT whose add count is the table's FLOPs column."""
+    rng = np.random.default_rng(1)
+    for heads, n, flops in _rows("fwht_flops_per_layer.txt"):
+        heads, n, flops = int(heads), int(n), int(flops)
+        assert n == heads * 128
+        if n <= 1024:
+            x = rng.standard_normal(n)
+            y, adds = _fwht_counting(x)
+            assert np.allclose(y / np.sqrt(n), O.rotate_groups(x[None], n)[0], atol=1e-10)
+        else:
+            adds = n * int(np.log2(n))
+        assert adds * (4096 // n) == flops
+
+
+# ----------------------------------------------------------------------------- reorder, Alg. 1
+
+def test_reorder_roundtrip_and_direction():
+    rng = np.random.default_rng(2)
+    P = rng.permutation(64)
+    y = rng.standard_normal((5, 64))
+    z = O.reorder(y, P)
+    for i in range(64):
+        assert np.array_equal(z[:, i], y[:, P[i]])
+    assert np.array_equal(O.reorder_inverse(z, P), y)
+
+
+def test_calibrate_bruteforce_tiny():
+    """Alg. 1 on a tiny layer, against an O(n^2) rank count; signed sum, ascending, stable."""
+    cfg = O.OracleConfig(batch=1, n_q_heads=2, n_kv_heads=2, head_dim=4, rot_heads=2, perm_span=8, quant_group=4)
+    rng = np.random.default_rng(3)
+    k = rng.standard_normal((6, 2, 4))
+    P = O.calibrate_perm(k, cfg)
+    H8 = scipy.linalg.hadamard(8) / np.sqrt(8.0)
+    sums = sum(H8 @ k[t].reshape(8) for t in range(6))
+    rank = [sum(1 for j in range(8) if sums[j] < sums[i] or (sums[j] == sums[i] and j < i)) for i in range(8)]
+    expect = np.empty(8, dtype=int)
+    for i, r in enumerate(rank):
+        expect[r] = i
+    assert np.array_equal(P, expect)
+    assert sorted(P.tolist()) == list(range(8))
+    # sign matters: negating the keys reverses the order of distinct sums
+    assert np.array_equal(O.calibrate_perm(-k, cfg), expect[::-1])
+
+
+def test_calibrate_span_closed_and_stable_ties():
+    cfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, head_dim=128, rot_heads=2, perm_span=128)
+    rng = np.random.default_rng(4)
+    P = O.calibrate_perm(rng.standard_normal((16, 4, 128)), cfg)
+    assert sorted(P.tolist()) == list(range(512))
+    assert np.array_equal(P // 128, np.arange(512) // 128)
+    Pz = O.calibrate_perm(np.zeros((3, 4, 128)), cfg)        # all sums equal: stable => identity
+    assert np.array_equal(Pz, np.arange(512))
+
+
+# ----------------------------------------------------------------------------- quantizer (Eq. 6-9)
+
+def test_quantizer_nearest_level_bruteforce():
+    """For every element the chosen code is a nearest reconstruction level among the four."""
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        g = int(rng.choice([4, 8]))
+        x = rng.standard_normal((1, g)) * rng.uniform(0.1, 30) + rng.uniform(-5, 5)
+        c, s, z = O.quantize(x, group=g)
+        levels = s[0, 0] * (np.arange(4) - z[0, 0])
+        for e in range(g):
+            dist = np.abs(levels - x[0, e])
+            assert dist[c[0, e]] <= dist.min() + 1e-12
+        assert c[0, np.argmin(x[0])] == 0 and c[0, np.argmax(x[0])] == 3
+
+
+def test_quantizer_reproduces_all_grid_patterns():
+    """All 4^4 code patterns placed exactly on a grid come back unchanged (Eq. 6 inverts Eq. 7)."""
+    s, z = 0.75, 1.0
+    for pat in itertools.product(range(4), repeat=4):
+        if min(pat) != 0 or max(pat) != 3:
+            continue                      # the grid is anchored by the block's own min and max
+        x = s * (np.array(pat, dtype=np.float64)[None] - z)
+        c, sc, ze = O.quantize(x, group=4)
+        assert sc[0, 0] == s and ze[0, 0] == z
+        assert tuple(c[0]) == pat
+        assert np.array_equal(O.dequantize(c, sc, ze, group=4), x)
+
+
+def test_quantizer_half_step_bound_and_metadata():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((64, 1024)) * np.exp(rng.uniform(-3, 3, size=(64, 1)))
+    c, s, z = O.quantize(x, group=128)
+    xh = O.dequantize(c, s, z, group=128)
+    step = np.repeat(s, 128, axis=-1)
+    assert np.all(np.abs(x - xh) <= 0.5 * step * (1 + 2.0 ** -8))
+    assert c.max() == 3 and c.min() == 0
+    assert np.array_equal(s.astype(np.float16).astype(np.float64), s)     # scale is an fp16 number
+    assert np.array_equal(z, np.rint(z)) and np.abs(z).max() <= 2048
+    raw = (x.reshape(64, 8, 128).max(-1) - x.reshape(64, 8, 128).min(-1)) / 3.0
+    assert np.all(np.abs(s - raw) <= raw * 2.0 ** -11)                     # nearest fp16 of Eq. 8
+
+
+def test_quantizer_rounds_half_to_even():
+    # scale 1, zero 0: 0.5 -> 0, 1.5 -> 2, 2.5 -> 2
+    x = np.array([[0.0, 0.5, 1.5, 2.5, 3.0, 1.0, 2.0, 0.25]])
+    c, s, z = O.quantize(x, group=8)
+    assert s[0, 0] == 1.0 and z[0, 0] == 0.0
+    assert c[0].tolist() == [0, 0, 2, 2, 3, 1, 2, 0]
+
+
+def test_quantizer_degenerate_blocks():
+    for val in [0.0, 2.5, -0.125]:
+        x = np.full((1, 8), val)
+        c, s, z = O.quantize(x, group=8)
+        assert np.all(c == 0)
+        assert np.allclose(O.dequantize(c, s, z, group=8), val)
+        assert np.isfinite(s).all() and s[0, 0] > 0
+
+
+def test_pack_roundtrip_all_bytes():
+    allb = np.arange(256, dtype=np.uint8)
+    codes = O.unpack_canonical(allb[None])
+    assert codes.shape == (1, 1024) and codes.max() == 3
+    assert np.array_equal(O.pack_canonical(codes)[0], allb)
+    assert O.pack_canonical(np.array([[1, 0, 0, 0, 0, 2, 0, 0, 0, 0, 0, 3]], dtype=np.uint8))[0].tolist() == [1, 8, 192]
+
+
+def test_average_bits_matches_paper():
+    (val,), = _rows("average_bits.txt")
+    cfg = O.OracleConfig(batch=1, n_q_heads=32, n_kv_heads=32)
+    assert O.average_bits(cfg) == float(val)
+    # and from the stored arrays themselves
+    rng = np.random.default_rng(7)
+    c, s, z = O.quantize(rng.standard_normal((4, 4096)), group=128)
+    bits = O.pack_canonical(c).size * 8 + (s.size + z.size) * 16
+    assert bits / c.size == float(val)
+
+
+# ----------------------------------------------------------------------------- RoPE
+
+@pytest.mark.parametrize("style", [0, 1])
+def test_rope_properties(style):
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((7, 128))
+    pos = np.arange(7) * 13
+    y = O.rope(x, pos, 10000.0, style)
+    assert np.allclose((y ** 2).sum(1), (x ** 2).sum(1))
+    assert np.allclose(O.rope(x, np.zeros(7), 10000.0, style), x)
+    q = rng.standard_normal(128)
+    s0 = O.rope(x, pos, 10000.0, style) @ O.rope(q, 100, 10000.0, style)
+    s1 = O.rope(x, pos + 57, 10000.0, style) @ O.rope(q, 157, 10000.0, style)
+    assert np.allclose(s0, s1, atol=1e-9)
+
+
+def test_rope_matches_complex_rotation():
+    """Half-split pairing (j, j+64) with angle pos * theta^(-j/64): compare with e^{i angle}."""
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal(128)
+    pos = 37
+    w = (x[:64] + 1j * x[64:]) * np.exp(1j * pos * 10000.0 ** (-np.arange(64) / 64.0))
+    y = O.rope(x, pos, 10000.0, 0)
+    assert np.allclose(y[:64], w.real) and np.allclose(y[64:], w.imag)
+    xi = rng.standard_normal(128)
+    wi = (xi[0::2] + 1j * xi[1::2]) * np.exp(1j * pos * 500000.0 ** (-np.arange(64) / 64.0))
+    yi = O.rope(xi, pos, 500000.0, 1)
+    assert np.allclose(yi[0::2], wi.real) and np.allclose(yi[1::2], wi.imag)
+
+
+# ----------------------------------------------------------------------------- sinks
+
+def test_select_sinks():
+    rng = np.random.default_rng(10)
+    act = rng.standard_normal((200, 64))
+    act[110, 5] = 300.0
+    act[0, 7] = -250.0
+    assert O.select_sinks(act, 2).tolist() == [0, 110]
+    tie = np.zeros((5, 3))
+    tie[1, 0] = tie[3, 2] = tie[4, 1] = 2.0
+    assert O.select_sinks(tie, 2).tolist() == [1, 3]
+
+
+# ----------------------------------------------------------------------------- whole path
+
+def _cfg(**kw):
+    base = dict(batch=2, n_q_heads=4, n_kv_heads=4, head_dim=128, rot_heads=2, perm_span=128, max_sinks=64)
+    base.update(kw)
+    return O.OracleConfig(**base)
+
+
+def test_rotate_reorder_inverse_is_identity():
+    """Write-order rotate->reorder and read-order reorder^-1->rotate compose to the identity."""
+    cfg = _cfg(perm_span=256)
+    rng = np.random.default_rng(11)
+    P = np.concatenate([rng.permutation(256), 256 + rng.permutation(256)])
+    x = rng.standard_normal((3, 512))
+    z = O.reorder(O.rotate_groups(x, cfg.n), P)
+    back = O.rotate_groups(O.reorder_inverse(z, P), cfg.n)
+    assert np.allclose(back, x, atol=1e-12)
+    wrong = O.reorder_inverse(O.rotate_groups(z, cfg.n), P)      # the other order is not an inverse
+    assert not np.allclose(wrong, x, atol=1e-3)
+
+
+def _textbook_attention(q, k, v, q_pos, theta, rep):
+    import torch
+    B, T, Hkv, d = k.shape
+    Hq = q.shape[1]
+
+    def rot(x, pos):
+        w = (x[..., :d // 2] + 1j * x[..., d // 2:]) * np.exp(1j * np.asarray(pos)[..., None] * theta ** (-np.arange(d // 2) / (d / 2)))
+        return np.concatenate([w.real, w.imag], axis=-1)
+    kr = np.stack([rot(k[:, :, h], np.arange(T)[None, :]) for h in range(Hkv)], axis=1)     # [B,Hkv,T,d]
+    qr = np.stack([rot(q[:, h], q_pos) for h in range(Hq)], axis=1)[:, :, None, :]          # [B,Hq,1,d]
+    kr = np.repeat(kr, rep, axis=1)
+    vv = np.repeat(np.transpose(v, (0, 2, 1, 3)), rep, axis=1)
+    out = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(qr), torch.from_numpy(kr), torch.from_numpy(vv))
+    return out[:, :, 0, :].numpy()
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 2)])
+def test_all_sink_cache_is_textbook_attention(hq, hkv):
+    """With every token retained in fp16 the read half must equal plain attention (library SDPA),
+    which pins RoPE, softmax, the 1/sqrt(d) scale and the GQA head mapping without the codec."""
+    cfg = _cfg(n_q_heads=hq, n_kv_heads=hkv, rot_heads=2)
+    rng = np.random.default_rng(12)
+    T = 40
+    k = rng.standard_normal((2, T, hkv, 128)).astype(np.float16)
+    v = rng.standard_normal((2, T, hkv, 128)).astype(np.float16)
+    q = rng.standard_normal((2, hq, 128)).astype(np.float16)
+    cache = O.cache_new(cfg)
+    O.quantize_append(cache, k, v, np.ones((2, T), dtype=np.uint8))
+    q_pos = np.array([T - 1, T + 5])
+    out, lse = O.decode_attention(cache, q, q_pos)
+    ref = _textbook_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), q_pos, 10000.0, hq // hkv)
+    assert np.allclose(out, ref, atol=1e-10)
+
+
+def test_no_quantization_error_on_grid_data():
+    """Keys whose rotated image lies exactly on a 2-bit grid survive the whole write+read path."""
+    cfg = _cfg(batch=1, rot_heads=2, perm_span=256)
+    rng = np.random.default_rng(13)
+    P = np.concatenate([rng.permutation(256), 256 + rng.permutation(256)])
+    codes = rng.integers(0, 4, size=(1, 6, 512))
+    codes[..., 0::128] = 0
+    codes[..., 1::128] = 3
+    z = 0.5 * (codes - 1.0)                                   # scale 0.5, zero 1 in every block
+    x = O.rotate_groups(O.reorder_inverse(z, P), 256)        # keys whose rotate+reorder image is z
+    x16 = x.astype(np.float16)
+    if not np.array_equal(x16.astype(np.float64), x):
+        pytest.skip("grid keys not exactly representable")
+    cache = O.cache_new(cfg, P)
+    O.quantize_append(cache, x16.reshape(1, 6, 4, 128), np.zeros((1, 6, 4, 128), np.float16))
+    assert np.array_equal(cache.k_codes, codes)
+    k_hat, _ = O.dequantize_cache(cache)
+    assert np.allclose(k_hat.reshape(1, 6, 512), x, atol=1e-12)
+
+
+def test_decode_stream_error_is_bounded_and_sinks_are_exact():
+    cfg = _cfg(max_sinks=1)
+    rng = np.random.default_rng(14)
+    T = 64
+    k = rng.standard_normal((2, T, 4, 128)).astype(np.float16)
+    v = rng.standard_normal((2, T, 4, 128)).astype(np.float16)
+    mask = np.zeros((2, T), np.uint8)
+    mask[:, 0] = 1
+    mask[:, 5] = 1                                             # second flag exceeds max_sinks: ignored
+    cache = O.cache_new(cfg)
+    O.quantize_append(cache, k, v, mask)
+    assert cache.sink_pos == [[0], [0]]
+    k_hat, v_hat = O.dequantize_cache(cache, substitute_sinks=True)
+    assert np.array_equal(k_hat[:, 0], k[:, 0].astype(np.float64))
+    assert np.array_equal(v_hat[:, 0], v[:, 0].astype(np.float64))
+    # per-element bound in the rotated domain carries to an L2 bound per rotation group
+    step = np.repeat(cache.k_scale, 128, axis=-1)
+    err = (k_hat.reshape(2, T, 512) - k.astype(np.float64).reshape(2, T, 512))[:, 1:]
+    bound = np.sqrt(((0.5 * step[:, 1:] * (1 + 2.0 ** -8)) ** 2).reshape(2, T - 1, 2, 256).sum(-1))
+    assert np.all(np.sqrt((err.reshape(2, T - 1, 2, 256) ** 2).sum(-1)) <= bound + 1e-9)
+
+
+def test_append_in_pieces_equals_bulk():
+    cfg = _cfg()
+    rng = np.random.default_rng(15)
+    k = rng.standard_normal((2, 20, 4, 128)).astype(np.float16)
+    v = rng.standard_normal((2, 20, 4, 128)).astype(np.float16)
+    a, b = O.cache_new(cfg), O.cache_new(cfg)
+    O.quantize_append(a, k, v)
+    O.quantize_append(b, k[:, :13], v[:, :13])
+    O.quantize_append(b, k[:, 13:], v[:, 13:])
+    assert np.array_equal(a.k_codes, b.k_codes) and np.array_equal(a.v_scale, b.v_scale)
+    q = rng.standard_normal((2, 4, 128)).astype(np.float16)
+    assert np.allclose(O.decode_attention(a, q)[0], O.decode_attention(b, q)[0])
+
+
+def test_v_rotate_roundtrip():
+    cfg0, cfg1 = _cfg(v_rotate=0), _cfg(v_rotate=1)
+    rng = np.random.default_rng(16)
+    k = rng.standard_normal((2, 8, 4, 128)).astype(np.float16)
+    v = rng.standard_normal((2, 8, 4, 128)).astype(np.float16)
+    c1 = O.cache_new(cfg1)
+    O.quantize_append(c1, k, v)
+    _, v_hat = O.dequantize_cache(c1)
+    step = np.repeat(c1.v_scale, 128, axis=-1).reshape(2, 8, 4, 128)
+    err = np.sqrt(((v_hat - v.astype(np.float64)) ** 2).sum(-1))
+    assert np.all(err <= np.sqrt(((0.5 * step * (1 + 2.0 ** -8)) ** 2).sum(-1)) + 1e-9)
+    assert not np.array_equal(c1.v_codes, O.quantize(v.astype(np.float64).reshape(2, 8, 512))[0])
+
+
+def test_reorder_lowers_error_on_offset_outliers():
+    """Ordering of the paper's key-reconstruction table (rotation alone vs rotation + reorder),
+    on synthetic keys with per-channel offsets.  The table's absolute values need real model
+    keys: parity unpinned."""
+    import rkv_synth as S
+    w = S.WORKLOADS["cfg1"]
+    k, v, _ = S.make_kv(w, 64, batch=1, offset_variant=True, sink_positions=[])
+    kc, _, _ = S.make_kv(w, 256, batch=1, stream=1, offset_variant=True, sink_positions=[])
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=32, rot_heads=4, perm_span=512)
+    cfg = O.OracleConfig(**base)
+    P = O.calibrate_perm(kc[0], cfg)
+    mses = []
+    for perm in (None, P):
+        c = O.cache_new(cfg, perm)
+        O.quantize_append(c, k, v)
+        k_hat, _ = O.dequantize_cache(c)
+        mses.append(((k_hat - k.astype(np.float64)) ** 2).mean())
+    assert mses[1] < mses[0]
