@@ -1,0 +1,259 @@
+"""ctypes binding of librkv.so.  Argument marshalling only: every step of the path runs in the
+library's kernels.  torch supplies device memory and the current stream, nothing else.
+
+The library must be present (build it with `python -m paper_2501_16383_amd.build` or
+`__graft_entry__.build()`); there is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librkv.so")
+_lib = None
+
+RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, -3, -4, -5
+
+EXPORTS = [
+    "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
+    "rkv_calibrate_perm", "rkv_set_perm", "rkv_quantize_append", "rkv_decode_attention",
+    "rkv_set_decode_path", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks",
+    "rkv_strerror",
+]
+
+
+class RkvError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load_library().rkv_strerror(code).decode()
+        super().__init__(f"{where}: {msg} ({code})")
+
+
+class _CConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "batch", "n_q_heads", "n_kv_heads", "head_dim", "max_tokens", "max_sinks", "rot_heads",
+        "quant_group", "bits", "perm_span", "rope_style", "v_rotate")] + [
+        ("rope_theta", C.c_float), ("clip_ratio", C.c_float)]
+
+
+@dataclass
+class RkvConfig:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    max_tokens: int
+    head_dim: int = 128
+    max_sinks: int = 4
+    rot_heads: int = 4
+    quant_group: int = 128
+    bits: int = 2
+    perm_span: int = 128
+    rope_style: int = 0
+    v_rotate: int = 0
+    rope_theta: float = 10000.0
+    clip_ratio: float = 1.0
+
+    def to_c(self) -> _CConfig:
+        return _CConfig(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.max_tokens,
+                        self.max_sinks, self.rot_heads, self.quant_group, self.bits, self.perm_span,
+                        self.rope_style, self.v_rotate, self.rope_theta, self.clip_ratio)
+
+    @property
+    def E(self) -> int:
+        return self.n_kv_heads * self.head_dim
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load librkv.so (once).  Raises if it has not been built: the product has no other path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2501_16383_amd.build`")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    cfgp = C.POINTER(_CConfig)
+    lib.rkv_query_sizes.argtypes = [cfgp, C.POINTER(sz), C.POINTER(sz)]
+    lib.rkv_cache_create.argtypes = [cfgp, vp, sz, vp, C.POINTER(vp)]
+    lib.rkv_cache_destroy.argtypes = [vp]
+    lib.rkv_cache_destroy.restype = None
+    lib.rkv_cache_reset.argtypes = [vp, vp]
+    lib.rkv_cache_length.argtypes = [vp]
+    lib.rkv_calibrate_perm.argtypes = [cfgp, vp, i32, vp, vp, vp]
+    lib.rkv_set_perm.argtypes = [vp, vp, vp]
+    lib.rkv_quantize_append.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.rkv_set_decode_path.argtypes = [vp, i32]
+    lib.rkv_dequantize.argtypes = [vp, vp, vp, vp]
+    lib.rkv_export_codes.argtypes = [vp] * 8
+    lib.rkv_import_codes.argtypes = [vp, i32] + [vp] * 7
+    lib.rkv_export_sinks.argtypes = [vp] * 6
+    lib.rkv_strerror.argtypes = [C.c_int]
+    lib.rkv_strerror.restype = C.c_char_p
+    for name in EXPORTS:
+        if name not in ("rkv_cache_destroy", "rkv_strerror"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(code: int, where: str) -> None:
+    if code != RKV_OK:
+        raise RkvError(code, where)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t, dtype, what: str):
+    import torch
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{what} must be a contiguous CUDA tensor of dtype {dtype}")
+    return t
+
+
+def query_sizes(cfg: RkvConfig):
+    lib = load_library()
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    cc = cfg.to_c()
+    _check(lib.rkv_query_sizes(C.byref(cc), C.byref(a), C.byref(b)), "rkv_query_sizes")
+    return a.value, b.value
+
+
+def calibrate_perm(cfg: RkvConfig, k_cal, scratch=None):
+    """rkv_calibrate_perm: k_cal [n_tok, n_kv_heads, 128] fp16 on the device -> int32 [E] on the device."""
+    import torch
+    lib = load_library()
+    k_cal = _dev(k_cal, torch.float16, "k_cal")
+    if scratch is None:
+        scratch = torch.empty(cfg.E * 16 + 256, dtype=torch.uint8, device=k_cal.device)
+    perm = torch.empty(cfg.E, dtype=torch.int32, device=k_cal.device)
+    cc = cfg.to_c()
+    _check(lib.rkv_calibrate_perm(C.byref(cc), _ptr(k_cal), k_cal.shape[0], _ptr(perm), _ptr(scratch), _stream()),
+           "rkv_calibrate_perm")
+    return perm
+
+
+class RkvCache:
+    """One layer's compressed KV cache.  Owns the torch buffers that back it."""
+
+    def __init__(self, cfg: RkvConfig, device="cuda:0", scratch=None):
+        import torch
+        self.cfg = cfg
+        self.lib = load_library()
+        self.device = torch.device(device)
+        cache_bytes, scratch_bytes = query_sizes(cfg)
+        self.cache_bytes, self.scratch_bytes = cache_bytes, scratch_bytes
+        self.mem = torch.empty(cache_bytes, dtype=torch.uint8, device=self.device)
+        self.scratch = scratch if scratch is not None else torch.empty(scratch_bytes, dtype=torch.uint8, device=self.device)
+        if self.scratch.numel() < scratch_bytes:
+            raise ValueError("scratch too small")
+        h = C.c_void_p()
+        cc = cfg.to_c()
+        with torch.cuda.device(self.device):
+            _check(self.lib.rkv_cache_create(C.byref(cc), self.mem.data_ptr(), cache_bytes, _stream(), C.byref(h)),
+                   "rkv_cache_create")
+        self.handle = h
+
+    def __del__(self):
+        h = getattr(self, "handle", None)
+        if h:
+            self.lib.rkv_cache_destroy(h)
+            self.handle = None
+
+    @property
+    def length(self) -> int:
+        return self.lib.rkv_cache_length(self.handle)
+
+    def reset(self):
+        _check(self.lib.rkv_cache_reset(self.handle, _stream()), "rkv_cache_reset")
+
+    def set_perm(self, perm):
+        import torch
+        perm = _dev(perm, torch.int32, "perm")
+        _check(self.lib.rkv_set_perm(self.handle, _ptr(perm), _stream()), "rkv_set_perm")
+
+    def set_decode_path(self, path: int):
+        _check(self.lib.rkv_set_decode_path(self.handle, path), "rkv_set_decode_path")
+
+    def quantize_append(self, k, v, sink_mask=None):
+        import torch
+        k = _dev(k, torch.float16, "k")
+        v = _dev(v, torch.float16, "v")
+        sink_mask = _dev(sink_mask, torch.uint8, "sink_mask")
+        B, n_new = k.shape[0], k.shape[1]
+        if k.shape != (B, n_new, self.cfg.n_kv_heads, self.cfg.head_dim) or v.shape != k.shape or B != self.cfg.batch:
+            raise ValueError("k, v must be [batch, n_new, n_kv_heads, head_dim]")
+        if sink_mask is not None and sink_mask.shape != (B, n_new):
+            raise ValueError("sink_mask must be [batch, n_new]")
+        _check(self.lib.rkv_quantize_append(self.handle, _ptr(k), _ptr(v), n_new, _ptr(sink_mask), _stream()),
+               "rkv_quantize_append")
+
+    def decode_attention(self, q, q_pos=None, out=None, lse=None, want_lse=False):
+        import torch
+        q = _dev(q, torch.float16, "q")
+        q_pos = _dev(q_pos, torch.int32, "q_pos")
+        cfg = self.cfg
+        if q.shape != (cfg.batch, cfg.n_q_heads, cfg.head_dim):
+            raise ValueError("q must be [batch, n_q_heads, head_dim]")
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        if lse is None and want_lse:
+            lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+        _check(self.lib.rkv_decode_attention(self.handle, _ptr(q), _ptr(q_pos), _ptr(out), _ptr(lse),
+                                             _ptr(self.scratch), _stream()), "rkv_decode_attention")
+        return (out, lse) if want_lse else out
+
+    def dequantize(self):
+        import torch
+        cfg = self.cfg
+        shape = (cfg.batch, self.length, cfg.n_kv_heads, cfg.head_dim)
+        k = torch.empty(shape, dtype=torch.float32, device=self.device)
+        v = torch.empty(shape, dtype=torch.float32, device=self.device)
+        _check(self.lib.rkv_dequantize(self.handle, _ptr(k), _ptr(v), _stream()), "rkv_dequantize")
+        return k, v
+
+    def export_codes(self):
+        import torch
+        cfg, T, dev = self.cfg, self.length, self.device
+        kc = torch.empty((cfg.batch, T, cfg.E // 4), dtype=torch.uint8, device=dev)
+        vc = torch.empty_like(kc)
+        meta = [torch.empty((cfg.batch, T, cfg.E // 128), dtype=torch.float32, device=dev) for _ in range(4)]
+        _check(self.lib.rkv_export_codes(self.handle, _ptr(kc), _ptr(meta[0]), _ptr(meta[1]), _ptr(vc), _ptr(meta[2]),
+                                         _ptr(meta[3]), _stream()), "rkv_export_codes")
+        return dict(k_codes=kc, k_scale=meta[0], k_zero=meta[1], v_codes=vc, v_scale=meta[2], v_zero=meta[3])
+
+    def import_codes(self, k_codes, k_scale, k_zero, v_codes, v_scale, v_zero):
+        import torch
+        k_codes = _dev(k_codes, torch.uint8, "k_codes")
+        v_codes = _dev(v_codes, torch.uint8, "v_codes")
+        ms = [_dev(t, torch.float32, "meta") for t in (k_scale, k_zero, v_scale, v_zero)]
+        _check(self.lib.rkv_import_codes(self.handle, k_codes.shape[1], _ptr(k_codes), _ptr(ms[0]), _ptr(ms[1]),
+                                         _ptr(v_codes), _ptr(ms[2]), _ptr(ms[3]), _stream()), "rkv_import_codes")
+
+    def export_sinks(self):
+        import torch
+        cfg, dev = self.cfg, self.device
+        S = max(cfg.max_sinks, 1)
+        cnt = torch.zeros(cfg.batch, dtype=torch.int32, device=dev)
+        pos = torch.full((cfg.batch, S), -1, dtype=torch.int32, device=dev)
+        k = torch.zeros((cfg.batch, S, cfg.E), dtype=torch.float16, device=dev)
+        v = torch.zeros_like(k)
+        _check(self.lib.rkv_export_sinks(self.handle, _ptr(cnt), _ptr(pos), _ptr(k), _ptr(v), _stream()),
+               "rkv_export_sinks")
+        return dict(count=cnt, pos=pos, k=k, v=v)

@@ -1,0 +1,250 @@
+// Host side of the C ABI: argument checks, the cache object, dispatch to the kernels.
+#include "rkv_internal.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#define RKV_EXPORT extern "C" __attribute__((visibility("default")))
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int check_config(const rkv_config* c, bool need_capacity) {
+  if (!c) return RKV_EINVAL;
+  if (c->head_dim != RKV_D || c->quant_group != 128 || c->bits != 2) return RKV_EINVAL;
+  if (c->clip_ratio != 1.0f) return RKV_EINVAL;
+  if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads != 0) return RKV_EINVAL;
+  if (c->n_q_heads / c->n_kv_heads > 8) return RKV_EINVAL;
+  if (c->rot_heads != 1 && c->rot_heads != 2 && c->rot_heads != 4 && c->rot_heads != 8) return RKV_EINVAL;
+  if (c->n_kv_heads % c->rot_heads != 0) return RKV_EINVAL;
+  if (c->n_kv_heads > 128) return RKV_EINVAL;
+  const int n = c->rot_heads * RKV_D, E = c->n_kv_heads * RKV_D;
+  if (c->perm_span != RKV_D && c->perm_span != n && c->perm_span != E) return RKV_EINVAL;
+  if (c->rope_style != 0 && c->rope_style != 1) return RKV_EINVAL;
+  if (c->v_rotate != 0 && c->v_rotate != 1) return RKV_EINVAL;
+  if (!(c->rope_theta > 1.0f)) return RKV_EINVAL;
+  if (need_capacity) {
+    if (c->batch < 1 || c->max_tokens < 1 || c->max_sinks < 0 || c->max_sinks > 64) return RKV_EINVAL;
+    if ((int64_t)c->max_tokens > (1 << 22) || (int64_t)c->batch > 65535) return RKV_EINVAL;
+  }
+  return RKV_OK;
+}
+
+struct Offsets {
+  size_t kc, km, vc, vm, sk, sv, spos, scnt, tables, perm, pinv, gid, rope, total;
+  int Tpad;
+};
+
+static Offsets plan(const rkv_config* c) {
+  Offsets o;
+  const size_t B = c->batch, E = (size_t)c->n_kv_heads * RKV_D, NG = E / 128;
+  o.Tpad = (c->max_tokens + 127) & ~127;
+  const size_t T = o.Tpad, S = c->max_sinks > 0 ? c->max_sinks : 1;
+  size_t p = 0;
+  o.kc = p; p = align256(p + B * T * E / 4);
+  o.km = p; p = align256(p + B * T * NG * 4);
+  o.vc = p; p = align256(p + B * T * E / 4);
+  o.vm = p; p = align256(p + B * T * NG * 4);
+  o.sk = p; p = align256(p + B * S * E * 2);
+  o.sv = p; p = align256(p + B * S * E * 2);
+  o.spos = p; p = align256(p + B * S * 4);
+  o.scnt = p; p = align256(p + B * 4);
+  o.tables = p;
+  o.perm = p; p = align256(p + E * 4);
+  o.pinv = p; p = align256(p + E * 4);
+  o.gid = p; p = align256(p + E * 4);
+  o.rope = p; p = align256(p + T * 64 * 8);
+  o.total = p;
+  return o;
+}
+
+RKV_EXPORT int rkv_query_sizes(const rkv_config* cfg, size_t* cache_bytes, size_t* scratch_bytes) {
+  int rc = check_config(cfg, true);
+  if (rc != RKV_OK) return rc;
+  if (cache_bytes) *cache_bytes = plan(cfg).total;
+  if (scratch_bytes) {
+    size_t a = rkv_decode_scratch_bytes(cfg), b = rkv_calib_scratch_bytes(cfg);
+    *scratch_bytes = a > b ? a : b;
+  }
+  return RKV_OK;
+}
+
+RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t bytes, void* stream, rkv_cache** out) {
+  if (!out) return RKV_EINVAL;
+  *out = nullptr;
+  int rc = check_config(cfg, true);
+  if (rc != RKV_OK) return rc;
+  if (!dev_mem || ((uintptr_t)dev_mem & 255) != 0) return RKV_EINVAL;
+  Offsets o = plan(cfg);
+  if (bytes < o.total) return RKV_EINVAL;
+  rkv_cache* c = new (std::nothrow) rkv_cache();
+  if (!c) return RKV_EINVAL;
+  c->cfg = *cfg;
+  c->bytes = o.total;
+  c->base = (char*)dev_mem;
+  c->off_tables = o.tables;
+  c->blocks_aligned = 1;
+  c->decode_path = 0;
+  RkvView& v = c->v;
+  v.kc = (uint32_t*)(c->base + o.kc);
+  v.km = (uint32_t*)(c->base + o.km);
+  v.vc = (uint32_t*)(c->base + o.vc);
+  v.vm = (uint32_t*)(c->base + o.vm);
+  v.sink_k = (__half*)(c->base + o.sk);
+  v.sink_v = (__half*)(c->base + o.sv);
+  v.sink_pos = (int*)(c->base + o.spos);
+  v.sink_cnt = (int*)(c->base + o.scnt);
+  v.perm = (int*)(c->base + o.perm);
+  v.pinv = (int*)(c->base + o.pinv);
+  v.gid = (int*)(c->base + o.gid);
+  v.rope = (float2*)(c->base + o.rope);
+  v.B = cfg->batch;
+  v.Hq = cfg->n_q_heads;
+  v.Hkv = cfg->n_kv_heads;
+  v.g = cfg->rot_heads;
+  v.n = cfg->rot_heads * RKV_D;
+  v.E = cfg->n_kv_heads * RKV_D;
+  v.NRG = cfg->n_kv_heads / cfg->rot_heads;
+  v.NG = v.E / 128;
+  v.Tpad = o.Tpad;
+  v.max_sinks = cfg->max_sinks;
+  v.len = 0;
+  v.span = cfg->perm_span;
+  v.rope_style = cfg->rope_style;
+  v.v_rotate = cfg->v_rotate;
+  v.theta = cfg->rope_theta;
+  rc = rkv_launch_init(c, true, (hipStream_t)stream);
+  if (rc != RKV_OK) {
+    delete c;
+    return rc;
+  }
+  *out = c;
+  return RKV_OK;
+}
+
+RKV_EXPORT void rkv_cache_destroy(rkv_cache* cache) { delete cache; }
+
+RKV_EXPORT int rkv_cache_reset(rkv_cache* cache, void* stream) {
+  if (!cache) return RKV_EINVAL;
+  cache->v.len = 0;
+  return rkv_launch_init(cache, false, (hipStream_t)stream);
+}
+
+RKV_EXPORT int rkv_cache_length(const rkv_cache* cache) { return cache ? cache->v.len : RKV_EINVAL; }
+
+RKV_EXPORT int rkv_set_decode_path(rkv_cache* cache, int32_t path) {
+  if (!cache || path < 0 || path > 2) return RKV_EINVAL;
+  cache->decode_path = path;
+  return RKV_OK;
+}
+
+RKV_EXPORT int rkv_set_perm(rkv_cache* cache, const int32_t* dev_perm, void* stream) {
+  if (!cache || !dev_perm) return RKV_EINVAL;
+  if (cache->v.len != 0) return RKV_ESTATE;
+  const int E = cache->v.E, span = cache->v.span;
+  std::vector<int32_t> p(E), inv(E, -1), gid(E);
+  hipStream_t s = (hipStream_t)stream;
+  RKV_HIP_CHECK(hipMemcpyAsync(p.data(), dev_perm, (size_t)E * 4, hipMemcpyDeviceToHost, s));
+  RKV_HIP_CHECK(hipStreamSynchronize(s));
+  for (int i = 0; i < E; ++i) {
+    int c = p[i];
+    if (c < 0 || c >= E || inv[c] != -1) return RKV_EPERM;
+    if (c / span != i / span) return RKV_EPERM;
+    inv[c] = i;
+  }
+  int aligned = 1;
+  for (int c = 0; c < E; ++c) {
+    gid[c] = inv[c] / 128;
+    if (gid[c] != c / 128) aligned = 0;
+  }
+  RKV_HIP_CHECK(hipMemcpyAsync(cache->v.perm, p.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
+  RKV_HIP_CHECK(hipMemcpyAsync(cache->v.pinv, inv.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
+  RKV_HIP_CHECK(hipMemcpyAsync(cache->v.gid, gid.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
+  RKV_HIP_CHECK(hipStreamSynchronize(s));
+  cache->blocks_aligned = aligned;
+  return RKV_OK;
+}
+
+RKV_EXPORT int rkv_calibrate_perm(const rkv_config* cfg, const void* dev_k_cal, int32_t n_tok, int32_t* dev_perm_out,
+                                  void* dev_scratch, void* stream) {
+  int rc = check_config(cfg, false);
+  if (rc != RKV_OK) return rc;
+  if (!dev_k_cal || !dev_perm_out || !dev_scratch || n_tok < 1) return RKV_EINVAL;
+  return rkv_launch_calibrate(cfg, (const __half*)dev_k_cal, n_tok, dev_perm_out, dev_scratch, (hipStream_t)stream);
+}
+
+RKV_EXPORT int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, int32_t n_new,
+                                   const uint8_t* dev_sink_mask, void* stream) {
+  if (!cache || !dev_k || !dev_v || n_new < 0) return RKV_EINVAL;
+  if (n_new == 0) return RKV_OK;
+  if ((int64_t)cache->v.len + n_new > cache->cfg.max_tokens) return RKV_ECAPACITY;
+  int rc = rkv_launch_append(cache, (const __half*)dev_k, (const __half*)dev_v, n_new, dev_sink_mask, (hipStream_t)stream);
+  if (rc == RKV_OK) cache->v.len += n_new;
+  return rc;
+}
+
+RKV_EXPORT int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, float* dev_out,
+                                    float* dev_lse, void* dev_scratch, void* stream) {
+  if (!cache || !dev_q || !dev_out || !dev_scratch) return RKV_EINVAL;
+  if (cache->v.len < 1) return RKV_ESTATE;
+  bool fast = rkv_mfma_supported(cache);
+  if (cache->decode_path == 2 && !fast) return RKV_EINVAL;
+  if (cache->decode_path == 1) fast = false;
+  if (fast)
+    return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
+  return rkv_launch_decode_general(cache, (const __half*)dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
+}
+
+RKV_EXPORT int rkv_dequantize(rkv_cache* cache, float* dev_k_hat, float* dev_v_hat, void* stream) {
+  if (!cache) return RKV_EINVAL;
+  if (cache->v.len < 1) return RKV_ESTATE;
+  return rkv_launch_dequant(cache, dev_k_hat, dev_v_hat, (hipStream_t)stream);
+}
+
+RKV_EXPORT int rkv_export_codes(rkv_cache* cache, uint8_t* dev_k_codes, float* dev_k_scale, float* dev_k_zero,
+                                uint8_t* dev_v_codes, float* dev_v_scale, float* dev_v_zero, void* stream) {
+  if (!cache) return RKV_EINVAL;
+  if (cache->v.len < 1) return RKV_ESTATE;
+  return rkv_launch_export(cache, dev_k_codes, dev_k_scale, dev_k_zero, dev_v_codes, dev_v_scale, dev_v_zero,
+                           (hipStream_t)stream);
+}
+
+RKV_EXPORT int rkv_import_codes(rkv_cache* cache, int32_t n_tokens, const uint8_t* dev_k_codes, const float* dev_k_scale,
+                                const float* dev_k_zero, const uint8_t* dev_v_codes, const float* dev_v_scale,
+                                const float* dev_v_zero, void* stream) {
+  if (!cache || !dev_k_codes || !dev_k_scale || !dev_k_zero || !dev_v_codes || !dev_v_scale || !dev_v_zero) return RKV_EINVAL;
+  if (n_tokens < 1) return RKV_EINVAL;
+  if (n_tokens > cache->cfg.max_tokens) return RKV_ECAPACITY;
+  int rc = rkv_launch_import(cache, n_tokens, dev_k_codes, dev_k_scale, dev_k_zero, dev_v_codes, dev_v_scale, dev_v_zero,
+                             (hipStream_t)stream);
+  if (rc == RKV_OK) cache->v.len = n_tokens;
+  return rc;
+}
+
+RKV_EXPORT int rkv_export_sinks(rkv_cache* cache, int32_t* dev_count, int32_t* dev_pos, void* dev_k, void* dev_v,
+                                void* stream) {
+  if (!cache) return RKV_EINVAL;
+  const RkvView& v = cache->v;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t S = v.max_sinks;
+  if (dev_count) RKV_HIP_CHECK(hipMemcpyAsync(dev_count, v.sink_cnt, (size_t)v.B * 4, hipMemcpyDeviceToDevice, s));
+  if (S == 0) return RKV_OK;
+  if (dev_pos) RKV_HIP_CHECK(hipMemcpyAsync(dev_pos, v.sink_pos, (size_t)v.B * S * 4, hipMemcpyDeviceToDevice, s));
+  if (dev_k) RKV_HIP_CHECK(hipMemcpyAsync(dev_k, v.sink_k, (size_t)v.B * S * v.E * 2, hipMemcpyDeviceToDevice, s));
+  if (dev_v) RKV_HIP_CHECK(hipMemcpyAsync(dev_v, v.sink_v, (size_t)v.B * S * v.E * 2, hipMemcpyDeviceToDevice, s));
+  return RKV_OK;
+}
+
+RKV_EXPORT const char* rkv_strerror(int code) {
+  switch (code) {
+    case RKV_OK: return "ok";
+    case RKV_EINVAL: return "invalid argument or unsupported configuration";
+    case RKV_ECAPACITY: return "cache capacity exceeded";
+    case RKV_EPERM: return "reorder indices are not a permutation closed under perm_span";
+    case RKV_EHIP: return "HIP runtime error";
+    case RKV_ESTATE: return "call not valid in the cache's current state";
+    default: return "unknown error";
+  }
+}

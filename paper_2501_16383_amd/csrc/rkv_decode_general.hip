@@ -1,0 +1,285 @@
+// Read half, general kernel: any supported configuration, plain vector ALU.
+//   k_prep_q        RoPE of the query at q_pos, scaled by 1/sqrt(d)                 (Eq. 5)
+//   k_decode_gen    split-K over the context: one workgroup = (sequence, rotation group, chunk)
+//                   dequantize -> inverse reorder (gid) -> inverse rotation -> RoPE -> scores,
+//                   chunk-local softmax, p.V on the 2-bit values; writes (m, l, acc) partials
+//   k_merge         combines the partials with the fp16 sink rows (Sec. 4.3) -> out, lse
+#include "rkv_internal.h"
+
+#define GEN_CHUNK 128
+
+template <int PL, typename T>
+__device__ inline void fwht_lanes_d(T (&x)[PL], int lane, int xstages) {
+#pragma unroll
+  for (int h = 1; h < PL; h <<= 1) {
+#pragma unroll
+    for (int i = 0; i < PL; i += 2 * h) {
+#pragma unroll
+      for (int j = i; j < i + h; ++j) {
+        T a = x[j], b = x[j + h];
+        x[j] = a + b;
+        x[j + h] = a - b;
+      }
+    }
+  }
+  for (int s = 0; s < xstages; ++s) {
+    const int mask = 1 << s;
+    const bool up = (lane & mask) != 0;
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      T o = __shfl_xor(x[i], mask);
+      x[i] = up ? (o - x[i]) : (x[i] + o);
+    }
+  }
+}
+
+// q~[b][h][c] = RoPE(q, q_pos)[c] / sqrt(128), angles in double (q_pos may lie beyond the table).
+__global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restrict__ q, const int* __restrict__ q_pos,
+                                                float* __restrict__ qr) {
+  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
+  const int pos = q_pos ? q_pos[b] : v.len - 1;
+  const size_t base = ((size_t)b * v.Hq + h) * RKV_D;
+  int j, partner;
+  float sgn;
+  if (v.rope_style == 0) {
+    j = c & 63;
+    partner = c ^ 64;
+    sgn = c < 64 ? -1.f : 1.f;
+  } else {
+    j = c >> 1;
+    partner = c ^ 1;
+    sgn = (c & 1) ? 1.f : -1.f;
+  }
+  const double freq = pow((double)v.theta, -(double)j / 64.0);
+  double sn, cs;
+  sincos((double)pos * freq, &sn, &cs);
+  const float x = __half2float(q[base + c]), p = __half2float(q[base + partner]);
+  qr[base + c] = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
+}
+
+__device__ inline bool is_sink(const int* sp, int cnt, int t) {
+  bool s = false;
+  for (int i = 0; i < cnt; ++i) s |= (sp[i] == t);
+  return s;
+}
+
+template <int PL>
+__global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __restrict__ qr, float* __restrict__ part, int nch) {
+  // LDS: q~ of this group's query heads, scores / probabilities, V meta, per-head stats
+  extern __shared__ float sm[];
+  const int rep = v.Hq / v.Hkv, g = v.g, n = v.n;
+  const int nq = rep * g;                       // query heads served by this rotation group
+  float* s_q = sm;                              // [nq][128]
+  float* s_p = s_q + nq * RKV_D;                // [nq][GEN_CHUNK]
+  float* s_vs = s_p + nq * GEN_CHUNK;           // [g][GEN_CHUNK]
+  float* s_vz = s_vs + g * GEN_CHUNK;           // [g][GEN_CHUNK]
+  float* s_m = s_vz + g * GEN_CHUNK;            // [nq]
+  float* s_l = s_m + nq;                        // [nq]
+  __shared__ int s_sink[64];
+
+  const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t0 = chunk * GEN_CHUNK, t1 = min(t0 + GEN_CHUNK, v.len);
+  const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
+  if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
+  for (int i = tid; i < nq * RKV_D; i += 256) s_q[i] = qr[((size_t)b * v.Hq + (size_t)rg * nq) * RKV_D + i];
+  __syncthreads();
+
+  // ---- phase 1: scores.  One wave per token; lane holds rotated channels PL*lane .. +PL-1.
+  const int lanes_per_head = RKV_D / PL;
+  const int hh = lane / lanes_per_head;                       // KV head inside the group
+  const int idx0 = (PL * lane) & (RKV_D - 1);                 // first channel inside the head
+  const float rs = rsqrtf((float)n);
+  for (int t = t0 + wave; t < t1; t += 4) {
+    float x[PL];
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      const int c = PL * lane + i;
+      int sh;
+      const uint32_t w = v.kc[rkv_k_dword(v, b, rg, t, c, sh)];
+      float sc, zero;
+      rkv_unpack_meta(v.km[rkv_meta_index(v, b, t, v.gid[rg * n + c])], sc, zero);
+      x[i] = sc * ((float)((w >> sh) & 3u) - zero);             // Eq. 7
+    }
+    fwht_lanes_d<PL>(x, lane, 6);                               // inverse rotation (H is its own inverse)
+    float y[PL];
+    if (v.rope_style == 0) {
+      const float sgn = idx0 < 64 ? -1.f : 1.f;
+#pragma unroll
+      for (int i = 0; i < PL; ++i) {
+        const float p = __shfl_xor(x[i], 64 / PL);
+        const float2 cs = v.rope[(size_t)t * 64 + ((idx0 + i) & 63)];
+        y[i] = rs * (x[i] * cs.x + sgn * p * cs.y);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < PL; i += 2) {
+        const float2 cs = v.rope[(size_t)t * 64 + ((idx0 + i) >> 1)];
+        y[i] = rs * (x[i] * cs.x - x[i + 1] * cs.y);
+        y[i + 1] = rs * (x[i] * cs.y + x[i + 1] * cs.x);
+      }
+    }
+    const bool sink = is_sink(s_sink, cnt, t);
+    for (int r = 0; r < rep; ++r) {
+      const float* qh = s_q + (hh * rep + r) * RKV_D + idx0;
+      float d = 0.f;
+#pragma unroll
+      for (int i = 0; i < PL; ++i) d += y[i] * qh[i];
+      for (int s = 1; s < lanes_per_head; s <<= 1) d += __shfl_xor(d, s);
+      if ((lane & (lanes_per_head - 1)) == 0) s_p[(hh * rep + r) * GEN_CHUNK + (t - t0)] = sink ? -INFINITY : d;
+    }
+  }
+  for (int i = tid; i < g * GEN_CHUNK; i += 256) {
+    const int h = i / GEN_CHUNK, tt = i - h * GEN_CHUNK;
+    float sc = 0.f, zero = 0.f;
+    if (t0 + tt < t1) rkv_unpack_meta(v.vm[rkv_meta_index(v, b, t0 + tt, rg * g + h)], sc, zero);
+    s_vs[i] = sc;
+    s_vz[i] = zero;
+  }
+  __syncthreads();
+
+  // ---- phase 2: chunk-local softmax per query head
+  for (int h = wave; h < nq; h += 4) {
+    float* p = s_p + h * GEN_CHUNK;
+    float m = -INFINITY;
+    for (int tt = lane; tt < t1 - t0; tt += 64) m = fmaxf(m, p[tt]);
+    for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s));
+    float l = 0.f;
+    for (int tt = lane; tt < GEN_CHUNK; tt += 64) {
+      float e = 0.f;
+      if (tt < t1 - t0 && m > -INFINITY) e = __expf(p[tt] - m);
+      p[tt] = e;
+      l += e;
+    }
+    for (int s = 1; s < 64; s <<= 1) l += __shfl_xor(l, s);
+    if (lane == 0) {
+      s_m[h] = m;
+      s_l[h] = l;
+    }
+  }
+  __syncthreads();
+
+  // ---- phase 3: acc[c] = sum_t p_t * s_t * (code - zero)   (Eq. 7 folded into the weights)
+  for (int c = tid; c < n; c += 256) {
+    const int h = c >> 7;
+    float acc[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) acc[r] = 0.f;
+    for (int tt = 0; tt < t1 - t0; tt += 16) {
+      int sh;
+      const uint32_t w = v.vc[rkv_v_dword(v, b, rg, t0 + tt, c, sh)];
+      for (int k = 0; k < 16 && tt + k < t1 - t0; ++k) {
+        const float val = s_vs[h * GEN_CHUNK + tt + k] * ((float)((w >> rkv_v_shift(k)) & 3u) - s_vz[h * GEN_CHUNK + tt + k]);
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+          if (r < rep) acc[r] += s_p[(h * rep + r) * GEN_CHUNK + tt + k] * val;
+      }
+    }
+    for (int r = 0; r < rep; ++r) {
+      const int qh = rg * nq + h * rep + r;
+      float* dst = part + (((size_t)b * v.Hq + qh) * nch + chunk) * RKV_PART_STRIDE;
+      dst[4 + (c & 127)] = acc[r];
+      if ((c & 127) == 0) {
+        dst[0] = s_m[h * rep + r];
+        dst[1] = s_l[h * rep + r];
+      }
+    }
+  }
+}
+
+// One workgroup per (query head, sequence); thread = output channel.
+__global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restrict__ qr, const float* __restrict__ part,
+                                               int nch, float* __restrict__ out, float* __restrict__ lse) {
+  __shared__ float red[128];
+  __shared__ float s_score[64];
+  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
+  const int kvh = h / (v.Hq / v.Hkv);
+  const size_t qbase = ((size_t)b * v.Hq + h) * RKV_D;
+  const float* P = part + ((size_t)b * v.Hq + h) * nch * RKV_PART_STRIDE;
+  const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
+
+  // scores of the retained sink rows: exact fp16 keys, RoPE at their own position
+  int j, partner;
+  float sgn;
+  if (v.rope_style == 0) { j = c & 63; partner = c ^ 64; sgn = c < 64 ? -1.f : 1.f; }
+  else { j = c >> 1; partner = c ^ 1; sgn = (c & 1) ? 1.f : -1.f; }
+  const float qc = qr[qbase + c];
+  for (int s = 0; s < cnt; ++s) {
+    const int pos = v.sink_pos[b * v.max_sinks + s];
+    const __half* kr = v.sink_k + ((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D;
+    const float2 cs = v.rope[(size_t)pos * 64 + j];
+    const float x = __half2float(kr[c]), p = __half2float(kr[partner]);
+    red[c] = qc * (x * cs.x + sgn * p * cs.y);
+    __syncthreads();
+    for (int w = 64; w > 0; w >>= 1) {
+      if (c < w) red[c] += red[c + w];
+      __syncthreads();
+    }
+    if (c == 0) s_score[s] = red[0];
+    __syncthreads();
+  }
+
+  float M = -INFINITY;
+  for (int k = 0; k < nch; ++k) M = fmaxf(M, P[(size_t)k * RKV_PART_STRIDE]);
+  for (int s = 0; s < cnt; ++s) M = fmaxf(M, s_score[s]);
+  float L = 0.f, acc = 0.f;
+  for (int k = 0; k < nch; ++k) {
+    const float* pk = P + (size_t)k * RKV_PART_STRIDE;
+    const float mk = pk[0];
+    if (mk > -INFINITY) {
+      const float w = __expf(mk - M);
+      L += w * pk[1];
+      acc += w * pk[4 + c];
+    }
+  }
+  if (v.v_rotate) {   // the 2-bit stream holds rotated values: undo the per-head Hadamard once
+    red[c] = acc;
+    __syncthreads();
+    for (int hstep = 1; hstep < 128; hstep <<= 1) {
+      const float a = red[c], o = red[c ^ hstep];
+      __syncthreads();
+      red[c] = (c & hstep) ? (o - a) : (a + o);
+      __syncthreads();
+    }
+    acc = red[c] * 0.08838834764831845f;
+  }
+  for (int s = 0; s < cnt; ++s) {
+    const float w = __expf(s_score[s] - M);
+    L += w;
+    acc += w * __half2float(v.sink_v[((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D + c]);
+  }
+  out[qbase + c] = acc / L;
+  if (lse && c == 0) lse[(size_t)b * v.Hq + h] = M + logf(L);
+}
+
+size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
+  const size_t Tpad = (cfg->max_tokens + 127) & ~127;
+  const size_t nch = Tpad / 128;
+  const size_t qr = (size_t)cfg->batch * cfg->n_q_heads * RKV_D * 4;
+  return ((qr + 255) & ~(size_t)255) + (size_t)cfg->batch * cfg->n_q_heads * nch * RKV_PART_STRIDE * 4 + 256;
+}
+
+int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
+                              hipStream_t s) {
+  const RkvView& v = c->v;
+  float* qr = (float*)scratch;
+  const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4) + 255) & ~(size_t)255;
+  float* part = (float*)((char*)scratch + qbytes);
+  const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
+  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, qr);
+  const int rep = v.Hq / v.Hkv, nq = rep * v.g;
+  const size_t lds = ((size_t)nq * RKV_D + (size_t)nq * GEN_CHUNK + 2 * (size_t)v.g * GEN_CHUNK + 2 * nq) * 4;
+  dim3 grid(nch, v.NRG, v.B);
+  void (*fn)(RkvView, const float*, float*, int) = nullptr;
+  switch (v.n / 64) {
+    case 2: fn = k_decode_gen<2>; break;
+    case 4: fn = k_decode_gen<4>; break;
+    case 8: fn = k_decode_gen<8>; break;
+    case 16: fn = k_decode_gen<16>; break;
+    default: return RKV_EINVAL;
+  }
+  if (lds > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, qr, part, nch);
+  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, out, lse);
+  return rkv_check_launch();
+}

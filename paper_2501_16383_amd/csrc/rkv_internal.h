@@ -1,0 +1,132 @@
+// Internal declarations shared by the HIP translation units of librkv.
+//
+// Physical layout of one layer's cache (all inside the caller's block, 256-byte aligned parts).
+// "Rotated channel" c is a channel index after the grouped-head Hadamard, before the reorder;
+// "reordered position" i is its place after the reorder: reordered[i] = rotated[perm[i]].
+// Codes are stored by ROTATED channel, so the read half needs no gather; the reorder survives as
+// a table gid[] that says which quantization block (of 128 reordered positions) a rotated channel
+// belongs to.  The canonical byte image of the logical code array is produced by rkv_export_codes.
+//
+//   K codes   [batch][rot group][Tpad/16 tiles] of 16 tokens x n codes.  Inside a tile, for
+//             g = rot_heads >= 2: [block pair pr][q 0..3][token m 0..15][16 bytes], the 16 bytes
+//             being [block-in-pair][dword d 0..1]; for g = 1: [q][m][dword d].  Rotated channel
+//             128*blk + kap (kap = 32q + 8v + e) sits in dword d = v>>1 at bit 2*(2e + (v&1)).
+//             One wave-wide 16-byte load therefore fetches 1 KiB contiguous and leaves in every
+//             lane exactly the 2 x 32 codes it feeds to the FP4 matrix instruction.
+//   K meta    [batch][rot group][Tpad][g] x (fp16 scale, fp16 zero); entry (rg, j) is the
+//             quantization block G = rg*g + j of reordered positions [128G, 128G+128).
+//   V codes   [batch][rot group][Tpad/32 slabs] of 32 tokens x n channels, token-minor:
+//             [w 0..3][head-in-group hh][nn 0..15][ct 0..1][dword d 0..1]; channel
+//             128*hh + 32w + 16ct + nn, token tau of the slab in dword d = tau>>4 at bit
+//             2*(2*(tau&7) + ((tau>>3)&1)).
+//   V meta    as K meta (block G = KV head).
+//   sinks     fp16 rows [batch][max_sinks][E] for K and V, positions, counts.
+//   tables    perm, inverse perm, gid (int32 [E] each), RoPE angles float2 [Tpad][64].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include "../../include/rkv.h"
+
+#define RKV_D 128
+#define RKV_PART_STRIDE 132   // floats per split-K partial: m, l, 2 pad, acc[128]
+
+struct RkvView {
+  uint32_t* kc;
+  uint32_t* km;
+  uint32_t* vc;
+  uint32_t* vm;
+  __half* sink_k;
+  __half* sink_v;
+  int* sink_pos;
+  int* sink_cnt;
+  int* perm;
+  int* pinv;
+  int* gid;
+  float2* rope;
+  int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate;
+  float theta;
+};
+
+struct rkv_cache {
+  rkv_config cfg;
+  RkvView v;
+  size_t bytes;
+  char* base;
+  size_t off_tables;      // everything before this offset is cleared by reset
+  int blocks_aligned;     // 1 if gid[c] == c/128 for every rotated channel
+  int decode_path;
+};
+
+// offset (in dwords) of rotated channel c (within its rotation group) of token m inside a K tile
+__host__ __device__ inline int rkv_k_off(int g, int m, int c, int& shift) {
+  int blk = c >> 7, kap = c & 127;
+  int q = kap >> 5, r5 = kap & 31, vv = r5 >> 3, e = r5 & 7, d = vv >> 1;
+  shift = 2 * (2 * e + (vv & 1));
+  if (g == 1) return (q * 16 + m) * 2 + d;
+  return (((blk >> 1) * 4 + q) * 16 + m) * 4 + (blk & 1) * 2 + d;
+}
+__host__ __device__ inline size_t rkv_k_tilebase(const RkvView& v, int b, int rg, int tile) {
+  return ((size_t)(b * v.NRG + rg) * (size_t)(v.Tpad >> 4) + tile) * (size_t)(128 * v.g);
+}
+__host__ __device__ inline size_t rkv_k_dword(const RkvView& v, int b, int rg, int t, int c, int& shift) {
+  return rkv_k_tilebase(v, b, rg, t >> 4) + rkv_k_off(v.g, t & 15, c, shift);
+}
+// offset (in dwords) inside a K tile -> token m of the tile
+__host__ __device__ inline int rkv_k_tile_token(int g, int off) { return g == 1 ? ((off >> 1) & 15) : ((off >> 2) & 15); }
+
+__host__ __device__ inline int rkv_v_shift(int tau) { return 2 * (2 * (tau & 7) + ((tau >> 3) & 1)); }
+// offset (in dwords) of channel c (within its rotation group), token tau inside a V slab
+__host__ __device__ inline int rkv_v_off(int g, int c, int tau) {
+  int hh = c >> 7, ch = c & 127;
+  int w = ch >> 5, ct = (ch >> 4) & 1, nn = ch & 15, d = tau >> 4;
+  return ((((w * g + hh) * 16 + nn) * 2 + ct) * 2 + d);
+}
+__host__ __device__ inline size_t rkv_v_slabbase(const RkvView& v, int b, int rg, int slab) {
+  return ((size_t)(b * v.NRG + rg) * (size_t)(v.Tpad >> 5) + slab) * (size_t)(2 * v.n);
+}
+__host__ __device__ inline size_t rkv_v_dword(const RkvView& v, int b, int rg, int t, int c, int& shift) {
+  shift = rkv_v_shift(t & 31);
+  return rkv_v_slabbase(v, b, rg, t >> 5) + rkv_v_off(v.g, c, t & 31);
+}
+
+// meta entry of global quantization block G (0..E/128) of token t
+__host__ __device__ inline size_t rkv_meta_index(const RkvView& v, int b, int t, int G) {
+  int rg = G / v.g, j = G - rg * v.g;
+  return ((size_t)(b * v.NRG + rg) * (size_t)v.Tpad + t) * v.g + j;
+}
+
+__device__ inline uint32_t rkv_pack_meta(float scale, float zero) {
+  __half2 h = __halves2half2(__float2half_rn(scale), __float2half_rn(zero));
+  return *reinterpret_cast<uint32_t*>(&h);
+}
+__device__ inline void rkv_unpack_meta(uint32_t u, float& scale, float& zero) {
+  __half2 h = *reinterpret_cast<__half2*>(&u);
+  scale = __low2float(h);
+  zero = __high2float(h);
+}
+
+// kernels' host launchers (defined in the .hip files)
+int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s);
+int rkv_launch_set_perm_tables(rkv_cache* c, hipStream_t s);
+int rkv_launch_append(rkv_cache* c, const __half* k, const __half* v, int n_new, const uint8_t* mask, hipStream_t s);
+int rkv_launch_dequant(rkv_cache* c, float* k_hat, float* v_hat, hipStream_t s);
+int rkv_launch_export(rkv_cache* c, uint8_t* kc, float* ks, float* kz, uint8_t* vc, float* vs, float* vz, hipStream_t s);
+int rkv_launch_import(rkv_cache* c, int T, const uint8_t* kc, const float* ks, const float* kz, const uint8_t* vc,
+                      const float* vs, const float* vz, hipStream_t s);
+int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
+                              hipStream_t s);
+int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
+                           hipStream_t s);
+bool rkv_mfma_supported(const rkv_cache* c);
+int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s);
+size_t rkv_decode_scratch_bytes(const rkv_config* cfg);
+size_t rkv_calib_scratch_bytes(const rkv_config* cfg);
+
+#define RKV_HIP_CHECK(expr)                    \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) return RKV_EHIP;     \
+  } while (0)
+
+inline int rkv_check_launch() { return hipPeekAtLastError() == hipSuccess ? RKV_OK : RKV_EHIP; }

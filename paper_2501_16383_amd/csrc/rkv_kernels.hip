@@ -1,0 +1,545 @@
+// Write half (rotate, reorder, quantize, pack, sinks), calibration, and the exact views of the
+// cache used by tests (dequantize, export, import).
+#include "rkv_internal.h"
+
+// ---------------------------------------------------------------------------------------------
+// small device helpers
+// ---------------------------------------------------------------------------------------------
+
+// Walsh-Hadamard butterflies (Eq. 10 without the 1/sqrt(2) factors) over PL values per lane times
+// 2^XSTAGES lanes: element index = PL*lane + i, natural (Sylvester) order.
+template <int PL, typename T>
+__device__ inline void fwht_lanes(T (&x)[PL], int lane, int xstages) {
+#pragma unroll
+  for (int h = 1; h < PL; h <<= 1) {
+#pragma unroll
+    for (int i = 0; i < PL; i += 2 * h) {
+#pragma unroll
+      for (int j = i; j < i + h; ++j) {
+        T a = x[j], b = x[j + h];
+        x[j] = a + b;
+        x[j + h] = a - b;
+      }
+    }
+  }
+  for (int s = 0; s < xstages; ++s) {
+    const int mask = 1 << s;
+    const bool up = (lane & mask) != 0;
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      T o = __shfl_xor(x[i], mask);
+      x[i] = up ? (o - x[i]) : (x[i] + o);
+    }
+  }
+}
+
+template <int PL>
+__device__ inline void load_halves(const __half* p, float (&x)[PL]) {
+  if constexpr (PL >= 8) {
+#pragma unroll
+    for (int k = 0; k < PL / 8; ++k) {
+      uint4 u = reinterpret_cast<const uint4*>(p)[k];
+      const __half2* h = reinterpret_cast<const __half2*>(&u);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float2 f = __half22float2(h[i]);
+        x[8 * k + 2 * i] = f.x;
+        x[8 * k + 2 * i + 1] = f.y;
+      }
+    }
+  } else if constexpr (PL == 4) {
+    uint2 u = *reinterpret_cast<const uint2*>(p);
+    const __half2* h = reinterpret_cast<const __half2*>(&u);
+    float2 f0 = __half22float2(h[0]), f1 = __half22float2(h[1]);
+    x[0] = f0.x; x[1] = f0.y; x[2] = f1.x; x[3] = f1.y;
+  } else {
+    uint32_t u = *reinterpret_cast<const uint32_t*>(p);
+    float2 f = __half22float2(*reinterpret_cast<const __half2*>(&u));
+    x[0] = f.x; x[1] = f.y;
+  }
+}
+
+// Eq. 8-9 for one block of 128 given its min and max: fp16 scale actually stored, integer zero.
+__device__ inline void quant_params(float mn, float mx, float& s, float& zero) {
+  float raw = (mx - mn) / 3.0f;
+  s = __half2float(__float2half_rn(raw));
+  if (!(s <= 65504.0f)) s = 65504.0f;
+  if (s == 0.0f) {
+    s = __half2float(__float2half_rn(fabsf(mn)));
+    if (!(s <= 65504.0f)) s = 65504.0f;
+    if (s == 0.0f) s = 1.0f;
+  }
+  zero = -rintf(mn / s);
+  zero = fminf(fmaxf(zero, -2048.0f), 2048.0f);
+}
+// Eq. 6
+__device__ inline uint32_t quant_code(float x, float s, float zero) {
+  float q = rintf(x / s) + zero;
+  q = fminf(fmaxf(q, 0.0f), 3.0f);
+  return (uint32_t)q;
+}
+
+// ---------------------------------------------------------------------------------------------
+// init / reset
+// ---------------------------------------------------------------------------------------------
+
+__global__ void k_fill_zero(uint4* p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const uint4 z = make_uint4(0, 0, 0, 0);
+  for (; i < n16; i += stride) p[i] = z;
+}
+
+__global__ void k_init_small(RkvView v, int tables) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int S = v.max_sinks > 0 ? v.max_sinks : 1;
+  if (i < v.B * S) v.sink_pos[i] = -1;
+  if (tables && i < v.E) {
+    v.perm[i] = i;
+    v.pinv[i] = i;
+    v.gid[i] = i >> 7;
+  }
+}
+
+// RoPE angle table: rope[t][j] = (cos, sin)(t * theta^(-j/64)), evaluated in double.
+__global__ void k_init_rope(RkvView v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= v.Tpad * 64) return;
+  const int t = i >> 6, j = i & 63;
+  const double freq = pow((double)v.theta, -(double)j / 64.0);
+  double sn, cs;
+  sincos((double)t * freq, &sn, &cs);
+  v.rope[i] = make_float2((float)cs, (float)sn);
+}
+
+int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s) {
+  const size_t n16 = c->off_tables / 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)c->base, n16);
+  const RkvView& v = c->v;
+  int S = v.max_sinks > 0 ? v.max_sinks : 1;
+  int m = v.B * S > v.E ? v.B * S : v.E;
+  hipLaunchKernelGGL(k_init_small, dim3((m + 255) / 256), dim3(256), 0, s, v, tables ? 1 : 0);
+  if (tables) hipLaunchKernelGGL(k_init_rope, dim3((v.Tpad * 64 + 255) / 256), dim3(256), 0, s, v);
+  if (tables) c->blocks_aligned = 1;
+  return rkv_check_launch();
+}
+
+// ---------------------------------------------------------------------------------------------
+// sinks: keep the original fp16 rows of flagged tokens (Sec. 4.3), first come first kept
+// ---------------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restrict__ k, const __half* __restrict__ vv,
+                                               const uint8_t* __restrict__ mask, int n_new) {
+  __shared__ int s_count[256];
+  __shared__ int s_tok[64];
+  __shared__ int s_new;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int cnt0 = v.sink_cnt[b];
+  const int room = v.max_sinks - cnt0;
+  const int per = (n_new + 255) / 256;
+  const int lo = tid * per, hi = min(lo + per, n_new);
+  int mine = 0;
+  for (int t = lo; t < hi; ++t) mine += mask[(size_t)b * n_new + t] != 0;
+  s_count[tid] = mine;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int i = 0; i < 256; ++i) {
+      int c = s_count[i];
+      s_count[i] = run;
+      run += c;
+    }
+    s_new = run < room ? run : (room > 0 ? room : 0);
+  }
+  __syncthreads();
+  int slot = s_count[tid];
+  for (int t = lo; t < hi && slot < room; ++t) {
+    if (mask[(size_t)b * n_new + t] != 0) {
+      s_tok[slot] = t;
+      ++slot;
+    }
+  }
+  __syncthreads();
+  const int nn = s_new;
+  for (int i = 0; i < nn; ++i) {
+    const int t = s_tok[i];
+    const size_t src = ((size_t)b * n_new + t) * v.E, dst = ((size_t)b * v.max_sinks + cnt0 + i) * v.E;
+    for (int e = tid; e < v.E; e += 256) {
+      v.sink_k[dst + e] = k[src + e];
+      v.sink_v[dst + e] = vv[src + e];
+    }
+    if (tid == 0) v.sink_pos[b * v.max_sinks + cnt0 + i] = v.len + t;
+  }
+  if (tid == 0) v.sink_cnt[b] = cnt0 + nn;
+}
+
+// ---------------------------------------------------------------------------------------------
+// quantize-append
+//   One workgroup = (sequence, unit, tile of 16 token slots).  A unit is the smallest channel range
+//   closed under both the rotation and the reorder: max(perm_span, n) channels.  Each wave takes one
+//   token at a time: rotate in registers + lane exchanges (Sec. 4.2), scatter to reordered
+//   positions in LDS (Sec. 4.1), reduce min/max per block of 128, Eq. 6-9, and OR the codes into LDS
+//   images of the physical tile, which are then written with whole-dword stores.
+// ---------------------------------------------------------------------------------------------
+
+template <int PL>
+__global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+                                                int n_new, int tile0, int U) {
+  extern __shared__ uint32_t smem[];
+  float* zbuf = reinterpret_cast<float*>(smem);            // [4][U]
+  uint32_t* imgK = smem + 4 * U;                            // [U]  (16 tokens x U codes)
+  uint32_t* imgV = imgK + U;                                // [U]  (one dword per channel)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile = tile0 + blockIdx.x, unit = blockIdx.y, b = blockIdx.z;
+  const int ubase = unit * U, n = v.n, g = v.g;
+  const int rgs = U / n, rg0 = ubase / n;
+  const int t_lo = v.len, t_hi = v.len + n_new;
+  const float rs = rsqrtf((float)n);
+
+  for (int i = tid; i < 2 * U; i += 256) imgK[i] = 0;   // imgK and imgV are adjacent
+  __syncthreads();
+
+  float* zw = zbuf + wave * U;
+  for (int it = 0; it < 4; ++it) {
+    const int m = it * 4 + wave;
+    const int t = tile * 16 + m;
+    const bool active = (t >= t_lo) && (t < t_hi);
+    const size_t row = ((size_t)b * n_new + (active ? t - t_lo : 0)) * v.E;
+    if (active) {
+      for (int r = 0; r < rgs; ++r) {
+        float x[PL];
+        const int cbase = ubase + r * n + PL * lane;
+        load_halves<PL>(kin + row + cbase, x);
+        fwht_lanes<PL>(x, lane, 6);
+#pragma unroll
+        for (int i = 0; i < PL; ++i) zw[v.pinv[cbase + i] - ubase] = x[i] * rs;
+      }
+    }
+    __syncthreads();
+    if (active) {
+      for (int base = 0; base < U; base += 512) {
+        const int pos = base + 8 * lane;
+        const bool on = pos < U;
+        // ---- keys: reordered positions pos..pos+7, block of 128 = 16 lanes
+        float z[8];
+        float mn = 3.0e38f, mx = -3.0e38f;
+        if (on) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            z[i] = zw[pos + i];
+            mn = fminf(mn, z[i]);
+            mx = fmaxf(mx, z[i]);
+          }
+        }
+#pragma unroll
+        for (int s = 1; s < 16; s <<= 1) {
+          mn = fminf(mn, __shfl_xor(mn, s));
+          mx = fmaxf(mx, __shfl_xor(mx, s));
+        }
+        if (on) {
+          float sc, zero;
+          quant_params(mn, mx, sc, zero);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const uint32_t code = quant_code(z[i], sc, zero);
+            const int cr = v.perm[ubase + pos + i] - ubase;      // rotated channel, unit-local
+            const int r = cr / n, c = cr - r * n;
+            int sh;
+            const int off = rkv_k_off(g, m, c, sh);
+            atomicOr(&imgK[r * 128 * g + off], code << sh);
+          }
+          if ((lane & 15) == 0) v.km[rkv_meta_index(v, b, t, (ubase + pos) >> 7)] = rkv_pack_meta(sc, zero);
+        }
+        // ---- values: channels pos..pos+7 of the unit, block of 128 = one head
+        float u[8];
+        if (on) load_halves<8>(vin + row + ubase + pos, u);
+        else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) u[i] = 0.f;
+        }
+        if (v.v_rotate) {
+          fwht_lanes<8>(u, lane, 4);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) u[i] *= 0.08838834764831845f;   // 1/sqrt(128)
+        }
+        mn = 3.0e38f; mx = -3.0e38f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          mn = fminf(mn, u[i]);
+          mx = fmaxf(mx, u[i]);
+        }
+#pragma unroll
+        for (int s = 1; s < 16; s <<= 1) {
+          mn = fminf(mn, __shfl_xor(mn, s));
+          mx = fmaxf(mx, __shfl_xor(mx, s));
+        }
+        if (on) {
+          float sc, zero;
+          quant_params(mn, mx, sc, zero);
+          const int sh = rkv_v_shift(t & 31);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) atomicOr(&imgV[pos + i], quant_code(u[i], sc, zero) << sh);
+          if ((lane & 15) == 0) v.vm[rkv_meta_index(v, b, t, (ubase + pos) >> 7)] = rkv_pack_meta(sc, zero);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- write the images.  K: every 16-byte piece of a tile belongs to one token.
+  const int tile_dw = 128 * g;
+  for (int idx = tid; idx < U; idx += 256) {
+    const int r = idx / tile_dw, off = idx - r * tile_dw;
+    const int t = tile * 16 + rkv_k_tile_token(g, off);
+    if (t >= t_lo && t < t_hi) v.kc[rkv_k_tilebase(v, b, rg0 + r, tile) + off] = imgK[idx];
+  }
+  // V: a dword holds 16 token slots of one channel; keep the slots of tokens not in this call.
+  uint32_t keep = 0;
+  for (int m = 0; m < 16; ++m) {
+    const int t = tile * 16 + m;
+    if (!(t >= t_lo && t < t_hi)) keep |= 3u << rkv_v_shift(t & 31);
+  }
+  for (int idx = tid; idx < U; idx += 256) {
+    const int r = idx / n, c = idx - r * n;
+    const size_t a = rkv_v_slabbase(v, b, rg0 + r, tile >> 1) + rkv_v_off(g, c, (tile & 1) * 16);
+    uint32_t w = imgV[idx];
+    if (keep) w |= v.vc[a] & keep;
+    v.vc[a] = w;
+  }
+}
+
+int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new, const uint8_t* mask, hipStream_t s) {
+  const RkvView& v = c->v;
+  if (mask && v.max_sinks > 0) hipLaunchKernelGGL(k_sinks, dim3(v.B), dim3(256), 0, s, v, k, vv, mask, n_new);
+  const int U = v.span > v.n ? v.span : v.n;
+  const int tile0 = v.len >> 4, tile1 = (v.len + n_new - 1) >> 4;
+  dim3 grid(tile1 - tile0 + 1, v.E / U, v.B);
+  const size_t lds = (size_t)6 * U * 4;
+  void (*fn)(RkvView, const __half*, const __half*, int, int, int) = nullptr;
+  switch (v.n / 64) {
+    case 2: fn = k_append<2>; break;
+    case 4: fn = k_append<4>; break;
+    case 8: fn = k_append<8>; break;
+    case 16: fn = k_append<16>; break;
+    default: return RKV_EINVAL;
+  }
+  if (lds > 160 * 1024) return RKV_EINVAL;
+  if (lds > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, k, vv, n_new, tile0, U);
+  return rkv_check_launch();
+}
+
+// ---------------------------------------------------------------------------------------------
+// dequantize (test support): Eq. 7, inverse reorder (through gid), inverse rotation
+// ---------------------------------------------------------------------------------------------
+
+template <int PL>
+__global__ void __launch_bounds__(64) k_dequant(RkvView v, float* __restrict__ k_hat, float* __restrict__ v_hat) {
+  const int rg = blockIdx.x, t = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const int n = v.n;
+  const size_t row = ((size_t)b * v.len + t) * v.E + (size_t)rg * n;
+  if (k_hat) {
+    float x[PL];
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      const int c = PL * lane + i;
+      int sh;
+      const uint32_t w = v.kc[rkv_k_dword(v, b, rg, t, c, sh)];
+      float sc, zero;
+      rkv_unpack_meta(v.km[rkv_meta_index(v, b, t, v.gid[rg * n + c])], sc, zero);
+      x[i] = sc * ((float)((w >> sh) & 3u) - zero);
+    }
+    fwht_lanes<PL>(x, lane, 6);
+    const float rs = rsqrtf((float)n);
+#pragma unroll
+    for (int i = 0; i < PL; ++i) k_hat[row + PL * lane + i] = x[i] * rs;
+  }
+  if (v_hat) {
+    for (int base = 0; base < n; base += 512) {
+      const int c0 = base + 8 * lane;
+      const bool on = c0 < n;
+      float u[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        u[i] = 0.f;
+        if (on) {
+          int sh;
+          const uint32_t w = v.vc[rkv_v_dword(v, b, rg, t, c0 + i, sh)];
+          float sc, zero;
+          rkv_unpack_meta(v.vm[rkv_meta_index(v, b, t, (rg * n + c0) >> 7)], sc, zero);
+          u[i] = sc * ((float)((w >> sh) & 3u) - zero);
+        }
+      }
+      if (v.v_rotate) {
+        fwht_lanes<8>(u, lane, 4);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) u[i] *= 0.08838834764831845f;
+      }
+      if (on) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v_hat[row + c0 + i] = u[i];
+      }
+    }
+  }
+}
+
+int rkv_launch_dequant(rkv_cache* c, float* k_hat, float* v_hat, hipStream_t s) {
+  const RkvView& v = c->v;
+  dim3 grid(v.NRG, v.len, v.B);
+  switch (v.n / 64) {
+    case 2: hipLaunchKernelGGL(k_dequant<2>, grid, dim3(64), 0, s, v, k_hat, v_hat); break;
+    case 4: hipLaunchKernelGGL(k_dequant<4>, grid, dim3(64), 0, s, v, k_hat, v_hat); break;
+    case 8: hipLaunchKernelGGL(k_dequant<8>, grid, dim3(64), 0, s, v, k_hat, v_hat); break;
+    case 16: hipLaunchKernelGGL(k_dequant<16>, grid, dim3(64), 0, s, v, k_hat, v_hat); break;
+    default: return RKV_EINVAL;
+  }
+  return rkv_check_launch();
+}
+
+// ---------------------------------------------------------------------------------------------
+// export / import of the logical code array in canonical bytes (test support)
+// ---------------------------------------------------------------------------------------------
+
+__global__ void k_export(RkvView v, uint8_t* kc, float* ks, float* kz, uint8_t* vc, float* vs, float* vz) {
+  const size_t per_tok = v.E / 4;
+  const size_t total = (size_t)v.B * v.len * per_tok;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int j = idx % per_tok;
+    const size_t bt = idx / per_tok;
+    const int t = bt % v.len, b = bt / v.len;
+    uint32_t kb = 0, vb = 0;
+    for (int r = 0; r < 4; ++r) {
+      const int i = 4 * j + r;
+      int sh;
+      if (kc) {
+        const int cr = v.perm[i];
+        const uint32_t w = v.kc[rkv_k_dword(v, b, cr / v.n, t, cr % v.n, sh)];
+        kb |= ((w >> sh) & 3u) << (2 * r);
+      }
+      if (vc) {
+        const uint32_t w = v.vc[rkv_v_dword(v, b, i / v.n, t, i % v.n, sh)];
+        vb |= ((w >> sh) & 3u) << (2 * r);
+      }
+    }
+    if (kc) kc[idx] = (uint8_t)kb;
+    if (vc) vc[idx] = (uint8_t)vb;
+    if (j < v.NG) {
+      const size_t mi = rkv_meta_index(v, b, t, j), o = bt * v.NG + j;
+      float sc, zero;
+      rkv_unpack_meta(v.km[mi], sc, zero);
+      if (ks) ks[o] = sc;
+      if (kz) kz[o] = zero;
+      rkv_unpack_meta(v.vm[mi], sc, zero);
+      if (vs) vs[o] = sc;
+      if (vz) vz[o] = zero;
+    }
+  }
+}
+
+int rkv_launch_export(rkv_cache* c, uint8_t* kc, float* ks, float* kz, uint8_t* vc, float* vs, float* vz, hipStream_t s) {
+  const RkvView& v = c->v;
+  const size_t total = (size_t)v.B * v.len * (v.E / 4);
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 65535) blocks = 65535;
+  hipLaunchKernelGGL(k_export, dim3((unsigned)blocks), dim3(256), 0, s, v, kc, ks, kz, vc, vs, vz);
+  return rkv_check_launch();
+}
+
+__global__ void k_import(RkvView v, int T, const uint8_t* kc, const float* ks, const float* kz, const uint8_t* vc,
+                         const float* vs, const float* vz) {
+  const size_t per_tok = v.E / 4;
+  const size_t total = (size_t)v.B * T * per_tok;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int j = idx % per_tok;
+    const size_t bt = idx / per_tok;
+    const int t = bt % T, b = bt / T;
+    const uint32_t kb = kc[idx], vb = vc[idx];
+    for (int r = 0; r < 4; ++r) {
+      const int i = 4 * j + r;
+      int sh;
+      const int cr = v.perm[i];
+      size_t a = rkv_k_dword(v, b, cr / v.n, t, cr % v.n, sh);
+      atomicOr(&v.kc[a], ((kb >> (2 * r)) & 3u) << sh);
+      a = rkv_v_dword(v, b, i / v.n, t, i % v.n, sh);
+      atomicOr(&v.vc[a], ((vb >> (2 * r)) & 3u) << sh);
+    }
+    if (j < v.NG) {
+      const size_t mi = rkv_meta_index(v, b, t, j), o = bt * v.NG + j;
+      v.km[mi] = rkv_pack_meta(ks[o], kz[o]);
+      v.vm[mi] = rkv_pack_meta(vs[o], vz[o]);
+    }
+  }
+}
+
+int rkv_launch_import(rkv_cache* c, int T, const uint8_t* kc, const float* ks, const float* kz, const uint8_t* vc,
+                      const float* vs, const float* vz, hipStream_t s) {
+  const RkvView& v = c->v;
+  // clear the four code/meta regions (they are contiguous from the start of the block up to the sink store)
+  const size_t n16 = ((char*)v.sink_k - c->base) / 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)c->base, n16);
+  const size_t total = (size_t)v.B * T * (v.E / 4);
+  blocks = (total + 255) / 256;
+  if (blocks > 65535) blocks = 65535;
+  hipLaunchKernelGGL(k_import, dim3((unsigned)blocks), dim3(256), 0, s, v, T, kc, ks, kz, vc, vs, vz);
+  return rkv_check_launch();
+}
+
+// ---------------------------------------------------------------------------------------------
+// calibration (Alg. 1).  The rotation is linear, so the channel sums of the rotated keys are the
+// rotation of the channel sums: sum first (float64), rotate once, rank-sort inside each span.
+// ---------------------------------------------------------------------------------------------
+
+__global__ void k_calib_sum(const __half* __restrict__ k, int n_tok, int E, double* __restrict__ sums) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= E) return;
+  double acc = 0.0;
+  for (int t = 0; t < n_tok; ++t) acc += (double)__half2float(k[(size_t)t * E + c]);
+  sums[c] = acc;
+}
+
+__global__ void __launch_bounds__(256) k_calib_rotate(const double* __restrict__ sums, double* __restrict__ rot, int n) {
+  extern __shared__ double sh[];
+  const int rg = blockIdx.x, tid = threadIdx.x;
+  for (int i = tid; i < n; i += 256) sh[i] = sums[(size_t)rg * n + i];
+  __syncthreads();
+  for (int h = 1; h < n; h <<= 1) {
+    for (int p = tid; p < n / 2; p += 256) {
+      const int i = (p / h) * 2 * h + (p % h);
+      const double a = sh[i], b = sh[i + h];
+      sh[i] = a + b;
+      sh[i + h] = a - b;
+    }
+    __syncthreads();
+  }
+  const double rs = 1.0 / sqrt((double)n);
+  for (int i = tid; i < n; i += 256) rot[(size_t)rg * n + i] = sh[i] * rs;
+}
+
+__global__ void k_calib_rank(const double* __restrict__ rot, int E, int span, int* __restrict__ perm) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= E) return;
+  const int base = (c / span) * span;
+  const double x = rot[c];
+  int rank = 0;
+  for (int j = 0; j < span; ++j) {
+    const double y = rot[base + j];
+    rank += (y < x) || (y == x && base + j < c);
+  }
+  perm[base + rank] = c;
+}
+
+size_t rkv_calib_scratch_bytes(const rkv_config* cfg) { return (size_t)cfg->n_kv_heads * RKV_D * 8 * 2; }
+
+int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s) {
+  const int E = cfg->n_kv_heads * RKV_D, n = cfg->rot_heads * RKV_D;
+  double* sums = (double*)scratch;
+  double* rot = sums + E;
+  hipLaunchKernelGGL(k_calib_sum, dim3((E + 255) / 256), dim3(256), 0, s, k_cal, n_tok, E, sums);
+  hipLaunchKernelGGL(k_calib_rotate, dim3(E / n), dim3(256), (size_t)n * 8, s, sums, rot, n);
+  hipLaunchKernelGGL(k_calib_rank, dim3((E + 255) / 256), dim3(256), 0, s, rot, E, cfg->perm_span, perm_out);
+  return rkv_check_launch();
+}

@@ -1,0 +1,118 @@
+"""Helpers for the GPU-vs-oracle parity tests (the comparison protocol, not the method).
+
+Rounding ties.  The HIP path rotates in fp32, the oracle in float64; the two differ by ~1e-7
+relative.  A code or a stored scale can therefore differ only where the oracle's own value sits
+within a hair of a rounding boundary.  `compare_codes` recomputes those distances from the
+oracle's pre-quantization values and demands
+  * exact equality of scale, zero and codes everywhere else;
+  * inside the ambiguous set: |d scale| <= 1 fp16 ulp, |d zero| <= 1, |d code| <= 1, and the
+    half-step reconstruction bound against the GPU's own stored scale and zero.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import rkv_oracle as O
+import paper_2501_16383_amd as R
+import rkv_synth as S
+
+TAU_SCALE = 2.0 ** -19     # relative distance of (max-min)/3 from an fp16 rounding boundary
+TAU_ELEM = 2.0 ** -18      # absolute distance of x/scale (or min/scale) from a half-integer
+
+
+def oracle_cfg(cfg: R.RkvConfig) -> O.OracleConfig:
+    return O.OracleConfig(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                          rot_heads=cfg.rot_heads, quant_group=cfg.quant_group, bits=cfg.bits, perm_span=cfg.perm_span,
+                          rope_style=cfg.rope_style, v_rotate=cfg.v_rotate, rope_theta=cfg.rope_theta,
+                          max_sinks=cfg.max_sinks)
+
+
+def gpu(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def _fp16_boundary_distance(raw: np.ndarray) -> np.ndarray:
+    """Relative distance of raw (> 0) from the nearest midpoint between adjacent fp16 numbers."""
+    with np.errstate(over="ignore"):
+        s = raw.astype(np.float16)
+    up = np.nextafter(s, np.float16(np.inf)).astype(np.float64)
+    dn = np.nextafter(s, np.float16(-np.inf)).astype(np.float64)
+    s64 = s.astype(np.float64)
+    d = np.minimum(np.abs(raw - 0.5 * (s64 + up)), np.abs(raw - 0.5 * (s64 + dn)))
+    return d / np.maximum(raw, 1e-300)
+
+
+def compare_codes(pre: np.ndarray, o_codes, o_scale, o_zero, g_codes, g_scale, g_zero, what: str, group: int = 128):
+    """pre: oracle values entering Eq. 6 [.., C]; *_codes uint8 [.., C]; scale/zero [.., C/group]."""
+    blocks = pre.reshape(pre.shape[:-1] + (pre.shape[-1] // group, group))
+    mn, mx = blocks.min(-1), blocks.max(-1)
+    raw = (mx - mn) / 3.0
+    amb_group = (_fp16_boundary_distance(raw) < TAU_SCALE) | (raw < 6.2e-5) | (raw > 65000.0)
+    r0 = mn / o_scale
+    amb_group |= np.abs(np.abs(r0 - np.floor(r0)) - 0.5) < TAU_ELEM
+    r = blocks / o_scale[..., None]
+    amb_elem = np.abs((r - np.floor(r)) - 0.5) < TAU_ELEM
+    amb_elem |= amb_group[..., None]
+    oc = o_codes.reshape(blocks.shape).astype(np.int64)
+    gc = g_codes.reshape(blocks.shape).astype(np.int64)
+    strict_g = ~amb_group
+    assert np.array_equal(g_scale[strict_g], o_scale[strict_g]), f"{what}: scale differs outside rounding ties"
+    assert np.array_equal(g_zero[strict_g], o_zero[strict_g]), f"{what}: zero differs outside rounding ties"
+    bad = (oc != gc) & ~amb_elem
+    assert not bad.any(), f"{what}: {int(bad.sum())} codes differ outside rounding ties (of {bad.size})"
+    # inside the ambiguous set
+    ulp = np.spacing(o_scale.astype(np.float16)).astype(np.float64)
+    assert np.all(np.abs(g_scale - o_scale) <= np.abs(ulp) + 0.0), f"{what}: scale off by more than one fp16 ulp"
+    assert np.all(np.abs(g_zero - o_zero) <= 1.0), f"{what}: zero off by more than 1"
+    assert np.all(np.abs(oc - gc) <= 1), f"{what}: a code is off by more than 1"
+    recon = g_scale[..., None] * (gc - g_zero[..., None])
+    slack = 1e-5 * np.maximum(np.abs(mx), np.abs(mn))[..., None]
+    assert np.all(np.abs(blocks - recon) <= 0.5 * g_scale[..., None] * (1 + 2.0 ** -8) + slack), f"{what}: half-step bound"
+    n_amb = int(amb_elem.sum()) - int(amb_group.sum()) * group
+    stats = dict(groups=int(amb_group.size), ambiguous_groups=int(amb_group.sum()), elements=int(oc.size),
+                 ambiguous_elements=n_amb, mismatched_codes=int((oc != gc).sum()),
+                 mismatched_scales=int((g_scale != o_scale).sum()))
+    print(f"[parity] {what}: {stats}")
+    assert stats["ambiguous_groups"] <= max(4, 0.02 * stats["groups"])
+    return stats
+
+
+def export_numpy(cache: R.RkvCache):
+    e = cache.export_codes()
+    torch.cuda.synchronize()
+    out = {k: v.cpu().numpy() for k, v in e.items()}
+    out["k_codes"] = O.unpack_canonical(out["k_codes"])
+    out["v_codes"] = O.unpack_canonical(out["v_codes"])
+    for k in ("k_scale", "k_zero", "v_scale", "v_zero"):
+        out[k] = out[k].astype(np.float64)
+    return out
+
+
+def check_cache_against_oracle(cache: R.RkvCache, oc: O.OracleCache, tag: str):
+    g = export_numpy(cache)
+    assert g["k_codes"].shape == oc.k_codes.shape
+    sk = compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"], tag + " K")
+    sv = compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], tag + " V")
+    return g, sk, sv
+
+
+def import_oracle_codes(cache: R.RkvCache, oc: O.OracleCache):
+    cache.import_codes(gpu(O.pack_canonical(oc.k_codes)), gpu(oc.k_scale, torch.float32), gpu(oc.k_zero, torch.float32),
+                       gpu(O.pack_canonical(oc.v_codes)), gpu(oc.v_scale, torch.float32), gpu(oc.v_zero, torch.float32))
+
+
+def attention_error(out_gpu: np.ndarray, out_ref: np.ndarray) -> float:
+    """max over (sequence, head) of max|out - ref| / max|ref|."""
+    num = np.abs(out_gpu - out_ref).max(axis=-1)
+    den = np.abs(out_ref).max(axis=-1)
+    return float((num / den).max())
+
+
+def make_case(w: S.Workload, cfg: R.RkvConfig, T: int, sink_positions=None, layer: int = 0):
+    k, v, mask = S.make_kv(w, T, batch=cfg.batch, layer=layer, sink_positions=sink_positions)
+    q = S.make_q(w, batch=cfg.batch, layer=layer)
+    return k, v, mask, q

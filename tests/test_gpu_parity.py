@@ -1,0 +1,238 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle on the same
+seeded inputs.  Bars: codes, scales, zeros, permutations and sink rows bit-exact (rounding ties as
+documented in parity_utils); dequantized tensors within 1e-3 absolute (+2e-6 of the row's largest
+magnitude, for the x100 sink rows); attention outputs within 2e-3 of max|ref| per (sequence,
+head), log-sum-exp within 1e-3."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rkv_oracle as O
+import paper_2501_16383_amd as R
+import rkv_synth as S
+import parity_utils as P
+
+pytestmark = pytest.mark.gpu
+
+ATT_TOL = 2e-3
+LSE_TOL = 1e-3
+
+
+def small(wname, **kw):
+    return dataclasses.replace(S.WORKLOADS[wname], **kw)
+
+
+def build_pair(w, cfg, T, perm=None, sink_positions=None, chunks=None, layer=0):
+    """Fill a GPU cache and an oracle cache with the same tokens (optionally in several appends)."""
+    k, v, mask, q = P.make_case(w, cfg, T, sink_positions=sink_positions, layer=layer)
+    cache = R.RkvCache(cfg)
+    oc = O.cache_new(P.oracle_cfg(cfg), perm)
+    if perm is not None:
+        cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+    bounds = [0, T] if chunks is None else chunks
+    use_mask = cfg.max_sinks > 0
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        print(f"[case] append tokens {a}:{b} B={cfg.batch} Hkv={cfg.n_kv_heads} g={cfg.rot_heads} span={cfg.perm_span}", flush=True)
+        cache.quantize_append(P.gpu(k[:, a:b]), P.gpu(v[:, a:b]), P.gpu(mask[:, a:b]) if use_mask else None)
+        O.quantize_append(oc, k[:, a:b], v[:, a:b], mask[:, a:b] if use_mask else None)
+    torch.cuda.synchronize()
+    assert cache.length == T
+    return cache, oc, q
+
+
+def oracle_from_export(oc, g):
+    oc2 = O.cache_new(oc.cfg, oc.perm)
+    oc2.length = oc.length
+    for name in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero"):
+        setattr(oc2, name, g[name])
+    oc2.sink_pos, oc2.sink_k, oc2.sink_v = oc.sink_pos, oc.sink_k, oc.sink_v
+    return oc2
+
+
+def check_sinks(cache, oc):
+    s = {k: v.cpu().numpy() for k, v in cache.export_sinks().items()}
+    B, E = oc.cfg.batch, oc.cfg.E
+    for b in range(B):
+        assert s["count"][b] == len(oc.sink_pos[b])
+        for i, pos in enumerate(oc.sink_pos[b]):
+            assert s["pos"][b, i] == pos
+            assert np.array_equal(s["k"][b, i], oc.sink_k[b][i].reshape(E))
+            assert np.array_equal(s["v"][b, i], oc.sink_v[b][i].reshape(E))
+
+
+def check_dequant(cache, oc_same_codes):
+    kh, vh = cache.dequantize()
+    torch.cuda.synchronize()
+    kr, vr = O.dequantize_cache(oc_same_codes)
+    for got, ref, name in ((kh.cpu().numpy().astype(np.float64), kr, "K"), (vh.cpu().numpy().astype(np.float64), vr, "V")):
+        B, T = ref.shape[:2]
+        n = oc_same_codes.cfg.n if name == "K" else oc_same_codes.cfg.head_dim
+        rowmax = np.abs(ref).reshape(B, T, -1, n).max(-1, keepdims=True)
+        err = np.abs(got - ref).reshape(B, T, -1, n)
+        assert np.all(err <= 1e-3 + 2e-6 * rowmax), f"dequantized {name}: max err {err.max()}"
+        print(f"[parity] dequantized {name}: max abs err {err.max():.3e}")
+
+
+def check_decode(cache, oc_same_codes, q, q_pos=None, tag=""):
+    qp = None if q_pos is None else P.gpu(np.asarray(q_pos, dtype=np.int32))
+    out, lse = cache.decode_attention(P.gpu(q), qp, want_lse=True)
+    torch.cuda.synchronize()
+    ref, lse_ref = O.decode_attention(oc_same_codes, q, q_pos)
+    e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
+    le = float(np.abs(lse.cpu().numpy() - lse_ref).max())
+    print(f"[parity] decode {tag}: out err {e:.3e}  lse err {le:.3e}", flush=True)
+    assert e <= ATT_TOL and le <= LSE_TOL
+    return e
+
+
+def full_check(w, cfg, T, perm=None, sink_positions=None, chunks=None, q_pos=None, paths=(1,)):
+    cache, oc, q = build_pair(w, cfg, T, perm, sink_positions, chunks)
+    g, _, _ = P.check_cache_against_oracle(cache, oc, f"{w.name} T={T}")
+    check_sinks(cache, oc)
+    oc_g = oracle_from_export(oc, g)
+    check_dequant(cache, oc_g)
+    for path in paths:
+        cache.set_decode_path(path)
+        check_decode(cache, oc_g, q, q_pos, tag=f"own codes path={path}")
+    # the oracle's codes through the GPU read half
+    P.import_oracle_codes(cache, oc)
+    for path in paths:
+        cache.set_decode_path(path)
+        check_decode(cache, oc, q, q_pos, tag=f"oracle codes path={path}")
+    return cache, oc, q
+
+
+def calibrated_perm(w, cfg, offset_variant=False):
+    kc, _, _ = S.make_kv(w, 256, batch=1, stream=1, sink_positions=[], offset_variant=offset_variant)
+    perm_gpu = R.calibrate_perm(cfg, P.gpu(kc[0]))
+    torch.cuda.synchronize()
+    perm_ref = O.calibrate_perm(kc[0], P.oracle_cfg(cfg))
+    pg = perm_gpu.cpu().numpy()
+    assert sorted(pg.tolist()) == list(range(cfg.E))
+    if not np.array_equal(pg, perm_ref):
+        # only channels whose float64 sums are closer than 1e-9 relative may swap
+        rows = kc[0].astype(np.float64).reshape(-1, cfg.E)
+        sums = O.rotate_groups(rows, cfg.rot_heads * 128).sum(0)
+        diff = np.nonzero(pg != perm_ref)[0]
+        for i in diff:
+            a, b = sums[pg[i]], sums[perm_ref[i]]
+            assert abs(a - b) <= 1e-9 * max(abs(a), abs(b), 1e-300), "permutation differs beyond float64 ties"
+    return perm_ref
+
+
+def test_cfg0_full():
+    """Config 0 in full: 1 x 32 heads x 512 tokens, rotation over 2 heads, 1 sink, calibrated per-head reorder."""
+    w = S.WORKLOADS["cfg0"]
+    cfg = R.RkvConfig(batch=1, n_q_heads=32, n_kv_heads=32, max_tokens=512, max_sinks=1, rot_heads=2, perm_span=128)
+    perm = calibrated_perm(w, cfg)
+    full_check(w, cfg, 512, perm=perm, paths=(1, 0))
+
+
+def test_cfg1_slice_ragged():
+    """LLaMA-2-7B-shaped slice: rotation over 4 heads, 4 sinks, a ragged length spanning several tiles."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8)
+    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=4, perm_span=128)
+    perm = calibrated_perm(w, cfg)
+    full_check(w, cfg, 613, perm=perm, paths=(1, 0))
+
+
+def test_no_sinks_and_query_position():
+    """Without sinks nothing hides errors of the 2-bit stream; the query sits past the cache."""
+    w = small("cfg2", n_q_heads=8, n_kv_heads=8, n_sinks=0)
+    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=400, max_sinks=0, rot_heads=4, perm_span=128)
+    full_check(w, cfg, 389, sink_positions=[], q_pos=[400, 1234], paths=(1, 0))
+
+
+def test_sinks_at_other_positions_and_overflow():
+    """Sinks away from the start of the sequence, more flagged tokens than max_sinks."""
+    w = small("cfg1", n_q_heads=4, n_kv_heads=4)
+    cfg = R.RkvConfig(batch=2, n_q_heads=4, n_kv_heads=4, max_tokens=256, max_sinks=3, rot_heads=4, perm_span=128)
+    full_check(w, cfg, 200, sink_positions=[0, 17, 110, 150, 199], chunks=[0, 100, 200], paths=(1, 0))
+
+
+@pytest.mark.parametrize("span_kind", ["group", "row"])
+def test_reorder_across_blocks(span_kind):
+    """perm_span = rotation size and = whole row (Alg. 1 as printed): the reorder changes the blocks."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8)
+    span = 512 if span_kind == "group" else 1024
+    cfg = R.RkvConfig(batch=1, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=span)
+    perm = calibrated_perm(w, cfg, offset_variant=True)
+    assert not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
+    full_check(w, cfg, 100, perm=perm, paths=(1,))
+
+
+def test_gqa_llama3_shape():
+    """Config 4's geometry on a slice: 4 query heads per KV head, rope base 500000."""
+    w = small("cfg4", n_q_heads=16, n_kv_heads=4)
+    cfg = R.RkvConfig(batch=2, n_q_heads=16, n_kv_heads=4, max_tokens=300, max_sinks=4, rot_heads=4, perm_span=128,
+                      rope_theta=500000.0)
+    full_check(w, cfg, 270, paths=(1, 0))
+
+
+@pytest.mark.parametrize("g,style,vrot", [(1, 0, 1), (2, 1, 0), (8, 0, 1), (4, 1, 1)])
+def test_variants(g, style, vrot):
+    """Other rotation sizes, interleaved RoPE pairing, library-side value rotation."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8)
+    cfg = R.RkvConfig(batch=1, n_q_heads=8, n_kv_heads=8, max_tokens=160, max_sinks=2, rot_heads=g, perm_span=128,
+                      rope_style=style, v_rotate=vrot)
+    full_check(w, cfg, 150, sink_positions=[0, 3], paths=(1, 0))
+
+
+def test_incremental_append_matches_bulk():
+    """Prefill in uneven pieces, then single-token decode steps: same cache as one bulk append."""
+    w = small("cfg1", n_q_heads=4, n_kv_heads=4)
+    cfg = R.RkvConfig(batch=2, n_q_heads=4, n_kv_heads=4, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=128)
+    chunks = [0, 37] + list(range(38, 60)) + [111]
+    cache, oc, q = build_pair(w, cfg, 111, chunks=chunks)
+    bulk, oc_b, _ = build_pair(w, cfg, 111)
+    a, b = cache.export_codes(), bulk.export_codes()
+    torch.cuda.synchronize()
+    for name in a:
+        assert torch.equal(a[name], b[name]), name
+    P.check_cache_against_oracle(cache, oc, "incremental")
+    check_sinks(cache, oc)
+
+
+def test_reset_and_reuse():
+    w = small("cfg1", n_q_heads=4, n_kv_heads=4)
+    cfg = R.RkvConfig(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=64, max_sinks=4, rot_heads=4)
+    cache, oc, q = build_pair(w, cfg, 50)
+    cache.reset()
+    assert cache.length == 0
+    k, v, mask, q = P.make_case(w, cfg, 33, layer=3)
+    cache.quantize_append(P.gpu(k), P.gpu(v), P.gpu(mask))
+    oc2 = O.cache_new(P.oracle_cfg(cfg))
+    O.quantize_append(oc2, k, v, mask)
+    g, _, _ = P.check_cache_against_oracle(cache, oc2, "after reset")
+    check_sinks(cache, oc2)
+    check_decode(cache, oracle_from_export(oc2, g), q, tag="after reset")
+
+
+def test_error_codes():
+    w = small("cfg1", n_q_heads=4, n_kv_heads=4)
+    cfg = R.RkvConfig(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=20, max_sinks=1, rot_heads=4)
+    cache = R.RkvCache(cfg)
+    q = P.gpu(S.make_q(w, batch=1))
+    with pytest.raises(R.RkvError) as ei:
+        cache.decode_attention(q)
+    assert ei.value.code == -5
+    k, v, mask, _ = P.make_case(w, cfg, 21)
+    with pytest.raises(R.RkvError) as ei:
+        cache.quantize_append(P.gpu(k), P.gpu(v))
+    assert ei.value.code == -2
+    bad = np.arange(cfg.E, dtype=np.int32)
+    bad[0] = 1
+    with pytest.raises(R.RkvError) as ei:
+        cache.set_perm(P.gpu(bad))
+    assert ei.value.code == -3
+    cross = np.arange(cfg.E, dtype=np.int32)
+    cross[0], cross[200] = 200, 0
+    with pytest.raises(R.RkvError) as ei:
+        cache.set_perm(P.gpu(cross))
+    assert ei.value.code == -3
+    cache.quantize_append(P.gpu(k[:, :5]), P.gpu(v[:, :5]))
+    with pytest.raises(R.RkvError) as ei:
+        cache.set_perm(P.gpu(np.arange(cfg.E, dtype=np.int32)))
+    assert ei.value.code == -5

@@ -1,0 +1,67 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+unsupported configurations without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2501_16383_amd as R
+from paper_2501_16383_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(R.library_path()):
+        from paper_2501_16383_amd.build import build_library
+        build_library()
+    return R.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "rkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rkv_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert "rkv_quantize_append" in names and "rkv_decode_attention" in names and "rkv_calibrate_perm" in names
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_query_sizes_and_average_bits(lib):
+    cfg = R.RkvConfig(batch=16, n_q_heads=40, n_kv_heads=40, max_tokens=4096)
+    cache_bytes, scratch_bytes = R.query_sizes(cfg)
+    payload = 16 * 4096 * (2 * 5120 // 4 + 2 * 40 * 4)        # codes + fp16 scale/zero for K and V
+    assert payload * 8 / (2 * 16 * 4096 * 5120) == 2.25
+    assert payload <= cache_bytes <= payload * 1.03
+    assert scratch_bytes > 0
+
+
+@pytest.mark.parametrize("field,value", [
+    ("head_dim", 64), ("quant_group", 64), ("bits", 4), ("rot_heads", 3), ("rot_heads", 16), ("perm_span", 256),
+    ("clip_ratio", 0.9), ("max_sinks", 65), ("max_tokens", 0), ("batch", 0), ("rope_style", 2), ("v_rotate", 2),
+    ("n_q_heads", 41), ("rope_theta", 0.5),
+])
+def test_unsupported_configs_are_rejected(lib, field, value):
+    cfg = R.RkvConfig(batch=2, n_q_heads=40, n_kv_heads=40, max_tokens=128)
+    setattr(cfg, field, value)
+    with pytest.raises(R.RkvError) as ei:
+        R.query_sizes(cfg)
+    assert ei.value.code == binding.RKV_EINVAL
+
+
+def test_null_arguments(lib):
+    assert lib.rkv_cache_length(None) == binding.RKV_EINVAL
+    assert lib.rkv_cache_reset(None, None) == binding.RKV_EINVAL
+    assert lib.rkv_quantize_append(None, None, None, 1, None, None) == binding.RKV_EINVAL
+    assert lib.rkv_decode_attention(None, None, None, None, None, None, None) == binding.RKV_EINVAL
+    out = ctypes.c_void_p()
+    cc = R.RkvConfig(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=16).to_c()
+    assert lib.rkv_cache_create(ctypes.byref(cc), None, 1 << 30, None, ctypes.byref(out)) == binding.RKV_EINVAL
+    assert lib.rkv_strerror(binding.RKV_EPERM).decode().startswith("reorder")
