@@ -122,6 +122,12 @@ int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const int32_t* dev
  * the configuration is outside what it covers). */
 int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 
+/* Measurement hook: ev_start / ev_stop are hipEvent_t handles (as void*) or NULL.  While set,
+ * every rkv_decode_attention on this cache records ev_start immediately before and ev_stop
+ * immediately after its main (cache-streaming) kernel, on the call's stream; likewise
+ * rkv_quantize_append around its quantize kernel.  Pass NULLs to clear. */
+int rkv_set_profile_events(rkv_cache* cache, void* ev_start, void* ev_stop);
+
 /* ---- test support: exact views of what the cache stores ------------------------------------- */
 
 /* Reconstructed keys and values (Eq. 7, inverse reorder, inverse rotation), original basis, keys

@@ -20,7 +20,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
     "rkv_calibrate_perm", "rkv_set_perm", "rkv_quantize_append", "rkv_decode_attention",
-    "rkv_set_decode_path", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks",
+    "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks",
     "rkv_strerror",
 ]
 
@@ -91,6 +91,7 @@ def load_library():
     lib.rkv_quantize_append.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.rkv_set_decode_path.argtypes = [vp, i32]
+    lib.rkv_set_profile_events.argtypes = [vp, vp, vp]
     lib.rkv_dequantize.argtypes = [vp, vp, vp, vp]
     lib.rkv_export_codes.argtypes = [vp] * 8
     lib.rkv_import_codes.argtypes = [vp, i32] + [vp] * 7
@@ -190,6 +191,10 @@ class RkvCache:
 
     def set_decode_path(self, path: int):
         _check(self.lib.rkv_set_decode_path(self.handle, path), "rkv_set_decode_path")
+
+    def set_profile_events(self, ev_start, ev_stop):
+        """hipEvent_t handles (ints) recorded around the main kernel of the next calls, or None, None."""
+        _check(self.lib.rkv_set_profile_events(self.handle, ev_start, ev_stop), "rkv_set_profile_events")
 
     def quantize_append(self, k, v, sink_mask=None):
         import torch

@@ -87,6 +87,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   c->off_tables = o.tables;
   c->blocks_aligned = 1;
   c->decode_path = 0;
+  c->ev_start = c->ev_stop = nullptr;
   RkvView& v = c->v;
   v.kc = (uint32_t*)(c->base + o.kc);
   v.km = (uint32_t*)(c->base + o.km);
@@ -137,6 +138,13 @@ RKV_EXPORT int rkv_cache_length(const rkv_cache* cache) { return cache ? cache->
 RKV_EXPORT int rkv_set_decode_path(rkv_cache* cache, int32_t path) {
   if (!cache || path < 0 || path > 2) return RKV_EINVAL;
   cache->decode_path = path;
+  return RKV_OK;
+}
+
+RKV_EXPORT int rkv_set_profile_events(rkv_cache* cache, void* ev_start, void* ev_stop) {
+  if (!cache || ((ev_start == nullptr) != (ev_stop == nullptr))) return RKV_EINVAL;
+  cache->ev_start = (hipEvent_t)ev_start;
+  cache->ev_stop = (hipEvent_t)ev_stop;
   return RKV_OK;
 }
 

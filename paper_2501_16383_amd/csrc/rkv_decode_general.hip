@@ -279,7 +279,9 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
     default: return RKV_EINVAL;
   }
   if (lds > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, qr, part, nch);
+  if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, out, lse);
   return rkv_check_launch();
 }

@@ -327,7 +327,9 @@ int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new
   }
   if (lds > 160 * 1024) return RKV_EINVAL;
   if (lds > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, k, vv, n_new, tile0, U);
+  if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   return rkv_check_launch();
 }
 
