@@ -33,14 +33,14 @@ static int check_config(const rkv_config* c, bool need_capacity) {
 }
 
 struct Offsets {
-  size_t kc, km, vc, vm, sk, sv, spos, scnt, tables, perm, pinv, gid, rope, total;
+  size_t kc, km, vc, vm, sk, sv, spos, scnt, tables, perm, pinv, gid, rope, hop, total;
   int Tpad;
 };
 
 static Offsets plan(const rkv_config* c) {
   Offsets o;
   const size_t B = c->batch, E = (size_t)c->n_kv_heads * RKV_D, NG = E / 128;
-  o.Tpad = (c->max_tokens + 127) & ~127;
+  o.Tpad = (c->max_tokens + 255) & ~255;
   const size_t T = o.Tpad, S = c->max_sinks > 0 ? c->max_sinks : 1;
   size_t p = 0;
   o.kc = p; p = align256(p + B * T * E / 4);
@@ -56,6 +56,7 @@ static Offsets plan(const rkv_config* c) {
   o.pinv = p; p = align256(p + E * 4);
   o.gid = p; p = align256(p + E * 4);
   o.rope = p; p = align256(p + T * 64 * 8);
+  o.hop = p; p = align256(p + 8 * 64 * 4 * 4);
   o.total = p;
   return o;
 }
@@ -101,6 +102,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.pinv = (int*)(c->base + o.pinv);
   v.gid = (int*)(c->base + o.gid);
   v.rope = (float2*)(c->base + o.rope);
+  v.hop = (uint32_t*)(c->base + o.hop);
   v.B = cfg->batch;
   v.Hq = cfg->n_q_heads;
   v.Hkv = cfg->n_kv_heads;

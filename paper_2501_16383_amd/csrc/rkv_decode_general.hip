@@ -252,8 +252,15 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   if (lse && c == 0) lse[(size_t)b * v.Hq + h] = M + logf(L);
 }
 
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, float* qr, hipStream_t s) {
+  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, qr);
+}
+void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, float* out, float* lse, hipStream_t s) {
+  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, out, lse);
+}
+
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
-  const size_t Tpad = (cfg->max_tokens + 127) & ~127;
+  const size_t Tpad = (cfg->max_tokens + 255) & ~255;
   const size_t nch = Tpad / 128;
   const size_t qr = (size_t)cfg->batch * cfg->n_q_heads * RKV_D * 4;
   return ((qr + 255) & ~(size_t)255) + (size_t)cfg->batch * cfg->n_q_heads * nch * RKV_PART_STRIDE * 4 + 256;

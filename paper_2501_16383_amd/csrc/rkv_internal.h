@@ -21,7 +21,8 @@
 //             2*(2*(tau&7) + ((tau>>3)&1)).
 //   V meta    as K meta (block G = KV head).
 //   sinks     fp16 rows [batch][max_sinks][E] for K and V, positions, counts.
-//   tables    perm, inverse perm, gid (int32 [E] each), RoPE angles float2 [Tpad][64].
+//   tables    perm, inverse perm, gid (int32 [E] each), RoPE angles float2 [Tpad][64], the
+//             Hadamard operand image of the matrix-core kernel.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -44,6 +45,7 @@ struct RkvView {
   int* pinv;
   int* gid;
   float2* rope;
+  uint32_t* hop;     // Hadamard B-operand image for the FP4 matrix instruction: [8 tiles][64 lanes][4 dwords]
   int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate;
   float theta;
 };
@@ -120,6 +122,8 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
                            hipStream_t s);
 bool rkv_mfma_supported(const rkv_cache* c);
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, float* qr, hipStream_t s);
+void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, float* out, float* lse, hipStream_t s);
 int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s);
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg);
 size_t rkv_calib_scratch_bytes(const rkv_config* cfg);

@@ -112,6 +112,22 @@ __global__ void k_init_rope(RkvView v) {
   v.rope[i] = make_float2((float)cs, (float)sn);
 }
 
+// B operand of v_mfma_f32_16x16x128_f8f6f4 holding H_128 (entries +-1 as FP4 E2M1: 0x2 / 0xA).
+// Lane (n = lane & 15, q = lane >> 4) holds, in nibble e of dword v, input channel k = 32q + 8v + e
+// of output channel 16*tile + n.
+__global__ void k_init_hop(uint32_t* hop) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // (tile, lane, v)
+  if (i >= 8 * 64 * 4) return;
+  const int vreg = i & 3, lane = (i >> 2) & 63, tile = i >> 8;
+  const int n = lane & 15, q = lane >> 4;
+  uint32_t w = 0;
+  for (int e = 0; e < 8; ++e) {
+    const int k = 32 * q + 8 * vreg + e, col = 16 * tile + n;
+    w |= ((__popc(k & col) & 1) ? 0xAu : 0x2u) << (4 * e);
+  }
+  hop[i] = w;
+}
+
 int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s) {
   const size_t n16 = c->off_tables / 16;
   size_t blocks = (n16 + 255) / 256;
@@ -122,6 +138,7 @@ int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s) {
   int m = v.B * S > v.E ? v.B * S : v.E;
   hipLaunchKernelGGL(k_init_small, dim3((m + 255) / 256), dim3(256), 0, s, v, tables ? 1 : 0);
   if (tables) hipLaunchKernelGGL(k_init_rope, dim3((v.Tpad * 64 + 255) / 256), dim3(256), 0, s, v);
+  if (tables) hipLaunchKernelGGL(k_init_hop, dim3(8), dim3(256), 0, s, v.hop);
   if (tables) c->blocks_aligned = 1;
   return rkv_check_launch();
 }

@@ -127,7 +127,7 @@ def test_cfg0_full():
     w = S.WORKLOADS["cfg0"]
     cfg = R.RkvConfig(batch=1, n_q_heads=32, n_kv_heads=32, max_tokens=512, max_sinks=1, rot_heads=2, perm_span=128)
     perm = calibrated_perm(w, cfg)
-    full_check(w, cfg, 512, perm=perm, paths=(1, 0))
+    full_check(w, cfg, 512, perm=perm, paths=(1, 2))
 
 
 def test_cfg1_slice_ragged():
@@ -135,21 +135,21 @@ def test_cfg1_slice_ragged():
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=4, perm_span=128)
     perm = calibrated_perm(w, cfg)
-    full_check(w, cfg, 613, perm=perm, paths=(1, 0))
+    full_check(w, cfg, 613, perm=perm, paths=(1, 2))
 
 
 def test_no_sinks_and_query_position():
     """Without sinks nothing hides errors of the 2-bit stream; the query sits past the cache."""
     w = small("cfg2", n_q_heads=8, n_kv_heads=8, n_sinks=0)
     cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=400, max_sinks=0, rot_heads=4, perm_span=128)
-    full_check(w, cfg, 389, sink_positions=[], q_pos=[400, 1234], paths=(1, 0))
+    full_check(w, cfg, 389, sink_positions=[], q_pos=[400, 1234], paths=(1, 2))
 
 
 def test_sinks_at_other_positions_and_overflow():
     """Sinks away from the start of the sequence, more flagged tokens than max_sinks."""
     w = small("cfg1", n_q_heads=4, n_kv_heads=4)
     cfg = R.RkvConfig(batch=2, n_q_heads=4, n_kv_heads=4, max_tokens=256, max_sinks=3, rot_heads=4, perm_span=128)
-    full_check(w, cfg, 200, sink_positions=[0, 17, 110, 150, 199], chunks=[0, 100, 200], paths=(1, 0))
+    full_check(w, cfg, 200, sink_positions=[0, 17, 110, 150, 199], chunks=[0, 100, 200], paths=(1, 2))
 
 
 @pytest.mark.parametrize("span_kind", ["group", "row"])
