@@ -115,7 +115,7 @@ def main():
     torch.cuda.set_device(dev)
     hip = Hip()
 
-    cfg = R.RkvConfig(batch=B, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T + K + W, max_sinks=max(w.n_sinks, 1),
+    cfg = R.RkvConfig(batch=B, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=max(w.n_sinks, 1),
                       rot_heads=w.rot_heads, perm_span=128, rope_theta=w.rope_theta)
     E = cfg.E
     _, scratch_bytes = R.query_sizes(cfg)
@@ -123,7 +123,7 @@ def main():
 
     # ---- build the L caches: calibrate the reorder, then bulk-quantize T-1-W tokens (timed: append GB/s)
     caches, bulk_ms = [], []
-    n_pre = T - 1 - W
+    n_pre = T - K - W          # the last timed step decodes over exactly T tokens
     e0, e1 = hip.event(), hip.event()
     for l in range(L):
         c = R.RkvCache(cfg, device=dev, scratch=scratch)
@@ -168,7 +168,7 @@ def main():
     for s in range(W):
         one_step(s)
     torch.cuda.synchronize()
-    assert caches[0].length == T - 1
+    assert caches[0].length == T - K
 
     # timed region: exactly K steps, whole-job wall clock; the decode kernel of every launch is
     # bracketed by its own pair of HIP events (recorded by the library on the launch stream)
@@ -184,7 +184,7 @@ def main():
     kern_ms = [hip.elapsed_ms(a, b) for step in ev for (a, b) in step]
     avg_ms = sum(kern_ms) / len(kern_ms)
     min_ms = min(kern_ms)
-    ctx = T + (K - 1) / 2.0
+    ctx = T - (K - 1) / 2.0
     bytes_per_tok = 2 * E // 4 + 2 * (E // 128) * 4
     launch_bytes = B * ctx * bytes_per_tok
     achieved = launch_bytes / (avg_ms * 1e-3) / 1e9

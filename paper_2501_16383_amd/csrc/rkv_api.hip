@@ -89,6 +89,15 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   c->blocks_aligned = 1;
   c->decode_path = 0;
   c->ev_start = c->ev_stop = nullptr;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus < 1) {
+      delete c;
+      return RKV_EHIP;
+    }
+    c->n_cu = cus;
+  }
   RkvView& v = c->v;
   v.kc = (uint32_t*)(c->base + o.kc);
   v.km = (uint32_t*)(c->base + o.km);

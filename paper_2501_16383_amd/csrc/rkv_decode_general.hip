@@ -54,7 +54,16 @@ __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restr
   double sn, cs;
   sincos((double)pos * freq, &sn, &cs);
   const float x = __half2float(q[base + c]), p = __half2float(q[base + partner]);
-  qr[base + c] = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
+  const float val = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
+  qr[base + c] = val;
+  // second copy for the matrix-core kernel: [b][rot group][n 0..15][head a][8] with entry
+  // (p, half) = channel 16p + n + 64*half, pre-multiplied by 2/sqrt(rotation size)
+  // (FP4 nibbles hold code/2; 1/sqrt(n) is the normalisation of Eq. 10)
+  const int g = v.g, rg = h / g, a = h - rg * g;           // valid when one query head reads one KV head
+  float* qt = qr + (size_t)v.B * v.Hq * RKV_D;
+  const int nn = c & 15, pp = (c >> 4) & 3, half = c >> 6;
+  if (v.Hq == v.Hkv)
+    qt[((((size_t)b * v.NRG + rg) * 16 + nn) * g + a) * 8 + half * 4 + pp] = val * 2.0f * rsqrtf((float)v.n);
 }
 
 __device__ inline bool is_sink(const int* sp, int cnt, int t) {
@@ -262,7 +271,7 @@ void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int 
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
   const size_t Tpad = (cfg->max_tokens + 255) & ~255;
   const size_t nch = Tpad / 128;
-  const size_t qr = (size_t)cfg->batch * cfg->n_q_heads * RKV_D * 4;
+  const size_t qr = (size_t)cfg->batch * cfg->n_q_heads * RKV_D * 4 * 2;     // natural + lane-ordered copy
   return ((qr + 255) & ~(size_t)255) + (size_t)cfg->batch * cfg->n_q_heads * nch * RKV_PART_STRIDE * 4 + 256;
 }
 
@@ -270,7 +279,7 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
                               hipStream_t s) {
   const RkvView& v = c->v;
   float* qr = (float*)scratch;
-  const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4) + 255) & ~(size_t)255;
+  const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
   hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, qr);

@@ -98,269 +98,277 @@ __device__ __forceinline__ float row_transpose_reduce(float (&v)[NV], int n) {
 }
 
 template <int G>
-__global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* __restrict__ qr, float* __restrict__ part,
+__global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* __restrict__ qt, float* __restrict__ part,
                                                         int nch) {
   __shared__ float s_sc[G][MF_CH];
   __shared__ __attribute__((aligned(16))) uint8_t s_A[MF_CH / 32][2][16][4][32];   // [slab][digit set][row][lane group][bytes]
   __shared__ float s_m[4], s_l[4], s_zs[4], s_wsc[4];
   __shared__ int s_sink[64];
 
-  const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
-  const int t0 = chunk * MF_CH;
   const int len = v.len;
-  const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
-  if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
-  for (int i = tid; i < G * MF_CH; i += 256) (&s_sc[0][0])[i] = -INFINITY;
   {
     uint4* a4 = reinterpret_cast<uint4*>(&s_A[0][0][0][0][0]);
     for (int i = tid; i < (int)(sizeof(s_A) / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
   }
-  __syncthreads();
 
-  // ------------------------------------------------------------------ phase K
-  {
-    // Hadamard operand, query, RoPE state
-    v8i H[8];
+  // constants of the whole kernel: Hadamard operand, per-lane rows of H_g, RoPE step of 16 positions
+  v8i H[8];
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) {
-      const uint4 h = reinterpret_cast<const uint4*>(v.hop)[mt * 64 + lane];
-      H[mt][0] = (int)h.x; H[mt][1] = (int)h.y; H[mt][2] = (int)h.z; H[mt][3] = (int)h.w;
-      H[mt][4] = H[mt][5] = H[mt][6] = H[mt][7] = 0;
-    }
-    const float qs = 2.0f * rsqrtf((float)(G * RKV_D));      // FP4 nibble = code/2; 1/sqrt(n) of Eq. 10
-    float qlo[G][4], qhi[G][4];
+  for (int mt = 0; mt < 8; ++mt) {
+    const uint4 h = reinterpret_cast<const uint4*>(v.hop)[mt * 64 + lane];
+    H[mt][0] = (int)h.x; H[mt][1] = (int)h.y; H[mt][2] = (int)h.z; H[mt][3] = (int)h.w;
+    H[mt][4] = H[mt][5] = H[mt][6] = H[mt][7] = 0;
+  }
+  float st_c[4], st_s[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const float2 st = v.rope[16 * 64 + 16 * p + n];
+    st_c[p] = st.x;
+    st_s[p] = st.y;
+  }
+  const float zmask = (n == 0) ? -64.0f : 0.0f;           // H_128 of a constant block lives in channel 0
+
+  const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
+  const int t0 = chunk * MF_CH;
+  const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
+  if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
+  for (int i = tid; i < G * MF_CH; i += 256) (&s_sc[0][0])[i] = -INFINITY;
+  // query of this rotation group, already RoPE'd, scaled and laid out per lane by k_prep_q
+  float qlo[G][4], qhi[G][4];
+  {
+    const uint4* qp = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * 16 + n) * (G * 8));
 #pragma unroll
     for (int a = 0; a < G; ++a) {
-      const float* qh = qr + ((size_t)b * v.Hq + (size_t)rg * G + a) * RKV_D;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        qlo[a][p] = qh[16 * p + n] * qs;
-        qhi[a][p] = qh[16 * p + n + 64] * qs;
-      }
+      const uint4 u0 = qp[2 * a], u1 = qp[2 * a + 1];
+      qlo[a][0] = __uint_as_float(u0.x); qlo[a][1] = __uint_as_float(u0.y); qlo[a][2] = __uint_as_float(u0.z); qlo[a][3] = __uint_as_float(u0.w);
+      qhi[a][0] = __uint_as_float(u1.x); qhi[a][1] = __uint_as_float(u1.y); qhi[a][2] = __uint_as_float(u1.z); qhi[a][3] = __uint_as_float(u1.w);
     }
-    const int tw = t0 + wave * (16 * MF_TILES);
-    float cs_c[4][4], cs_s[4][4], st_c[4], st_s[4];
+  }
+  // V metadata of the four tokens this lane turns into weights in phase S (head = wave)
+  uint32_t vmeta[MF_CH / 64];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const float2 st = v.rope[16 * 64 + 16 * p + n];
-      st_c[p] = st.x;
-      st_s[p] = st.y;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float2 cs = v.rope[(size_t)(tw + 4 * q + r) * 64 + 16 * p + n];
-        cs_c[r][p] = cs.x;
-        cs_s[r][p] = cs.y;
-      }
-    }
-    const float zmask = (n == 0) ? -64.0f : 0.0f;     // H_128 of a constant block lives in channel 0
-
-    const uint4* ktiles = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tw >> 4));
-    const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * G;
-
-    uint4 cw[G / 2];
-    uint32_t mw[4][G];
-    auto load_tile = [&](int ti) {
-#pragma unroll
-      for (int pr = 0; pr < G / 2; ++pr) cw[pr] = ktiles[(size_t)ti * (32 * G) + pr * 64 + lane];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const uint32_t* mp = kmeta + (size_t)(ti * 16 + 4 * q + r) * G;
-        if constexpr (G == 4) {
-          const uint4 u = *reinterpret_cast<const uint4*>(mp);
-          mw[r][0] = u.x; mw[r][1] = u.y; mw[r][2] = u.z; mw[r][3] = u.w;
-        } else {
-          const uint2 u = *reinterpret_cast<const uint2*>(mp);
-          mw[r][0] = u.x; mw[r][1] = u.y;
-        }
-      }
-    };
-    load_tile(0);
-
-    for (int ti = 0; ti < MF_TILES; ++ti) {
-      const int tt = tw + ti * 16;
-      if (tt >= len) break;                              // wave-uniform
-      v8i A[G];
-      float sc[4][G], zc[4][G];
-#pragma unroll
-      for (int pr = 0; pr < G / 2; ++pr) {
-        A[2 * pr] = unpack_fp4(cw[pr].x, cw[pr].y);
-        A[2 * pr + 1] = unpack_fp4(cw[pr].z, cw[pr].w);
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int blk = 0; blk < G; ++blk) {
-          float s_, z_;
-          rkv_unpack_meta(mw[r][blk], s_, z_);
-          sc[r][blk] = s_;
-          zc[r][blk] = z_ * zmask;
-        }
-      if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
-
-      float pt[4 * G];                                   // [r][a]
-#pragma unroll
-      for (int i = 0; i < 4 * G; ++i) pt[i] = 0.f;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        float wlo[G][4], whi[G][4];
-#pragma unroll
-        for (int blk = 0; blk < G; ++blk) {
-          v4f c0 = {0.f, 0.f, 0.f, 0.f};
-          if (p == 0) { c0[0] = zc[0][blk]; c0[1] = zc[1][blk]; c0[2] = zc[2][blk]; c0[3] = zc[3][blk]; }
-          const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-          const v4f lo = mfma_fp4(A[blk], H[p], c0);
-          const v4f hi = mfma_fp4(A[blk], H[p + 4], zero4);
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            wlo[blk][r] = lo[r] * sc[r][blk];
-            whi[blk][r] = hi[r] * sc[r][blk];
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float klo[G], khi[G];
-          if constexpr (G == 4) {
-            const float a0 = wlo[0][r] + wlo[1][r], a1 = wlo[0][r] - wlo[1][r];
-            const float a2 = wlo[2][r] + wlo[3][r], a3 = wlo[2][r] - wlo[3][r];
-            klo[0] = a0 + a2; klo[1] = a1 + a3; klo[2] = a0 - a2; klo[3] = a1 - a3;
-            const float b0 = whi[0][r] + whi[1][r], b1 = whi[0][r] - whi[1][r];
-            const float b2 = whi[2][r] + whi[3][r], b3 = whi[2][r] - whi[3][r];
-            khi[0] = b0 + b2; khi[1] = b1 + b3; khi[2] = b0 - b2; khi[3] = b1 - b3;
-          } else {
-            klo[0] = wlo[0][r] + wlo[1][r]; klo[1] = wlo[0][r] - wlo[1][r];
-            khi[0] = whi[0][r] + whi[1][r]; khi[1] = whi[0][r] - whi[1][r];
-          }
-          const float c = cs_c[r][p], s = cs_s[r][p];
-#pragma unroll
-          for (int a = 0; a < G; ++a) {
-            const float xl = klo[a] * c - khi[a] * s;
-            const float xh = klo[a] * s + khi[a] * c;
-            pt[r * G + a] += xl * qlo[a][p] + xh * qhi[a][p];
-          }
-        }
-      }
-      // advance the RoPE state by 16 positions
+  for (int i = 0; i < MF_CH / 64; ++i)
+    vmeta[i] = wave < G ? v.vm[((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G + wave] : 0u;
+  __syncthreads();
+  {
+    // ------------------------------------------------------------------ phase K
+    {
+      const int tw = t0 + wave * (16 * MF_TILES);
+      float cs_c[4][4], cs_s[4][4];
 #pragma unroll
       for (int p = 0; p < 4; ++p)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float c = cs_c[r][p], s = cs_s[r][p];
-          cs_c[r][p] = c * st_c[p] - s * st_s[p];
-          cs_s[r][p] = s * st_c[p] + c * st_s[p];
+          const float2 cs = v.rope[(size_t)(tw + 4 * q + r) * 64 + 16 * p + n];
+          cs_c[r][p] = cs.x;
+          cs_s[r][p] = cs.y;
         }
-      // reduce over the 16 channel lanes: lane n gets (token 4q + n / G, head n % G)
-      const float tot = row_transpose_reduce<4 * G>(pt, n);
-      const int idx = n & (4 * G - 1);
-      const int tok = tt + 4 * q + idx / G, a = idx % G;
-      bool masked = tok >= len;
-      for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
-      if (n < 4 * G && !masked) s_sc[a][tok - t0] = tot;
-    }
-  }
-  __syncthreads();
+      const uint4* ktiles = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tw >> 4));
+      const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * G;
 
-  // ------------------------------------------------------------------ phase S
-  if (wave < G) {
-    const int a = wave;
-    float sv[MF_CH / 64], w[MF_CH / 64], zv[MF_CH / 64];
-    float m = -INFINITY;
+      uint4 cw[G / 2];
+      uint32_t mw[4][G];
+      auto load_tile = [&](int ti) {
 #pragma unroll
-    for (int i = 0; i < MF_CH / 64; ++i) {
-      sv[i] = s_sc[a][lane + 64 * i];
-      m = fmaxf(m, sv[i]);
-    }
-    for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s));
-    float l = 0.f, wmax = 0.f;
+        for (int pr = 0; pr < G / 2; ++pr) cw[pr] = ktiles[(size_t)ti * (32 * G) + pr * 64 + lane];
 #pragma unroll
-    for (int i = 0; i < MF_CH / 64; ++i) {
-      const int t = t0 + lane + 64 * i;
-      float p = 0.f;
-      if (sv[i] > -INFINITY) p = __expf(sv[i] - m);
-      float s_, z_;
-      rkv_unpack_meta(v.vm[((size_t)(b * v.NRG + rg) * v.Tpad + t) * G + a], s_, z_);
-      w[i] = p * s_;
-      zv[i] = z_;
-      l += p;
-      wmax = fmaxf(wmax, w[i]);
-    }
-    for (int s = 1; s < 64; s <<= 1) {
-      l += __shfl_xor(l, s);
-      wmax = fmaxf(wmax, __shfl_xor(wmax, s));
-    }
-    // 24-bit fixed point: largest weight lands in [2^23, 2^24); six base-16 digits, exact in E4M3
-    int ex = 0;
-    if (wmax > 0.f) frexpf(wmax, &ex);
-    const float up = ldexpf(1.0f, 24 - ex), down = ldexpf(1.0f, ex - 24);
-    float zs = 0.f;
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t* mp = kmeta + (size_t)(ti * 16 + 4 * q + r) * G;
+          if constexpr (G == 4) {
+            const uint4 u = *reinterpret_cast<const uint4*>(mp);
+            mw[r][0] = u.x; mw[r][1] = u.y; mw[r][2] = u.z; mw[r][3] = u.w;
+          } else {
+            const uint2 u = *reinterpret_cast<const uint2*>(mp);
+            mw[r][0] = u.x; mw[r][1] = u.y;
+          }
+        }
+      };
+      load_tile(0);
+
+      for (int ti = 0; ti < MF_TILES; ++ti) {
+        const int tt = tw + ti * 16;
+        if (tt >= len) break;                              // wave-uniform
+        v8i A[G];
+        float sc[4][G], zc[4][G];
 #pragma unroll
-    for (int i = 0; i < MF_CH / 64; ++i) {
-      const int tl = lane + 64 * i, slab = tl >> 5, tau = tl & 31;
-      const uint32_t W = (uint32_t)rintf(w[i] * up);
-      zs += (float)W * zv[i];
-      uint8_t* dst = &s_A[slab][0][4 * a][2 * (a & 1) + (tau >> 4)][16 * (a >> 1) + (tau & 15)];
+        for (int pr = 0; pr < G / 2; ++pr) {
+          A[2 * pr] = unpack_fp4(cw[pr].x, cw[pr].y);
+          A[2 * pr + 1] = unpack_fp4(cw[pr].z, cw[pr].w);
+        }
 #pragma unroll
-      for (int k = 0; k < 6; k += 2) {
-        // digits 5-k and 4-k (most significant first): rows 0..3 of set 0, rows 0..1 of set 1
-        const float d_hi = (float)(k == 0 ? (W >> 20) : ((W >> (20 - 4 * k)) & 15u));
-        const float d_lo = (float)((W >> (16 - 4 * k)) & 15u);
-        const int pk = __builtin_amdgcn_cvt_pk_fp8_f32(d_hi, d_lo, 0, false);
-        const int row = k & 3, set = k >> 2;
-        dst[set * (16 * 4 * 32) + row * (4 * 32)] = (uint8_t)(pk & 0xff);
-        dst[set * (16 * 4 * 32) + (row + 1) * (4 * 32)] = (uint8_t)((pk >> 8) & 0xff);
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int blk = 0; blk < G; ++blk) {
+            float s_, z_;
+            rkv_unpack_meta(mw[r][blk], s_, z_);
+            sc[r][blk] = s_;
+            zc[r][blk] = z_ * zmask;
+          }
+        if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
+
+        float pt[4 * G];                                   // [r][a]
+#pragma unroll
+        for (int i = 0; i < 4 * G; ++i) pt[i] = 0.f;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          v4f lo[G], hi[G];
+#pragma unroll
+          for (int blk = 0; blk < G; ++blk) {
+            v4f c0 = {0.f, 0.f, 0.f, 0.f};
+            if (p == 0) { c0[0] = zc[0][blk]; c0[1] = zc[1][blk]; c0[2] = zc[2][blk]; c0[3] = zc[3][blk]; }
+            const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+            lo[blk] = mfma_fp4(A[blk], H[p], c0);          // (H_128 c_blk - 128 z e_0) / 2, channels 16p + n
+            hi[blk] = mfma_fp4(A[blk], H[p + 4], zero4);   // channels 16p + n + 64
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            // k^[a] = sum_blk H_g[a][blk] * scale_blk * u_blk   (H_g butterfly over the blocks)
+            float klo[G], khi[G];
+            if constexpr (G == 4) {
+              const float w0 = lo[0][r] * sc[r][0], w1 = lo[1][r] * sc[r][1], w2 = lo[2][r] * sc[r][2], w3 = lo[3][r] * sc[r][3];
+              const float a0 = w0 + w1, a1 = w0 - w1, a2 = w2 + w3, a3 = w2 - w3;
+              klo[0] = a0 + a2; klo[1] = a1 + a3; klo[2] = a0 - a2; klo[3] = a1 - a3;
+              const float x0 = hi[0][r] * sc[r][0], x1 = hi[1][r] * sc[r][1], x2 = hi[2][r] * sc[r][2], x3 = hi[3][r] * sc[r][3];
+              const float b0 = x0 + x1, b1 = x0 - x1, b2 = x2 + x3, b3 = x2 - x3;
+              khi[0] = b0 + b2; khi[1] = b1 + b3; khi[2] = b0 - b2; khi[3] = b1 - b3;
+            } else {
+              const float w0 = lo[0][r] * sc[r][0], w1 = lo[1][r] * sc[r][1];
+              klo[0] = w0 + w1; klo[1] = w0 - w1;
+              const float x0 = hi[0][r] * sc[r][0], x1 = hi[1][r] * sc[r][1];
+              khi[0] = x0 + x1; khi[1] = x0 - x1;
+            }
+            const float c = cs_c[r][p], s = cs_s[r][p];
+#pragma unroll
+            for (int a = 0; a < G; ++a) {
+              const float xl = klo[a] * c - khi[a] * s;
+              const float xh = klo[a] * s + khi[a] * c;
+              pt[r * G + a] = fmaf(xh, qhi[a][p], fmaf(xl, qlo[a][p], pt[r * G + a]));
+            }
+          }
+        }
+        // advance the RoPE state by 16 positions
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float c = cs_c[r][p], s = cs_s[r][p];
+            cs_c[r][p] = c * st_c[p] - s * st_s[p];
+            cs_s[r][p] = s * st_c[p] + c * st_s[p];
+          }
+        // reduce over the 16 channel lanes: lane n gets (token 4q + n / G, head n % G)
+        const float tot = row_transpose_reduce<4 * G>(pt, n);
+        const int idx = n & (4 * G - 1);
+        const int tok = tt + 4 * q + idx / G, a = idx % G;
+        bool masked = tok >= len;
+        for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
+        if (n < 4 * G && !masked) s_sc[a][tok - t0] = tot;
       }
     }
-    for (int s = 1; s < 64; s <<= 1) zs += __shfl_xor(zs, s);
-    if (lane == 0) {
-      s_m[a] = m;
-      s_l[a] = l;
-      s_zs[a] = zs * down;
-      s_wsc[a] = down;
-    }
-  }
-  __syncthreads();
-
-  // ------------------------------------------------------------------ phase V
-  {
-    v4f acc[2][2];                                        // [channel tile][digit set]
-#pragma unroll
-    for (int i = 0; i < 2; ++i) acc[i][0] = acc[i][1] = (v4f){0.f, 0.f, 0.f, 0.f};
+    // first slab of V codes: in flight while the softmax phase runs
     const bool has_head = q < G;
     const uint4* vslab = reinterpret_cast<const uint4*>(v.vc + rkv_v_slabbase(v, b, rg, t0 >> 5));
     const int lidx = wave * (16 * G) + (has_head ? lane : 0);
     const int nslab = min(MF_CH / 32, (len - t0 + 31) >> 5);
     uint4 cur = make_uint4(0, 0, 0, 0);
     if (has_head && nslab > 0) cur = vslab[lidx];
-    for (int sl = 0; sl < nslab; ++sl) {
-      uint4 nxt = make_uint4(0, 0, 0, 0);
-      if (has_head && sl + 1 < nslab) nxt = vslab[(size_t)(sl + 1) * (64 * G) + lidx];
-      const v8i B0 = unpack_fp4(cur.x, cur.y), B1 = unpack_fp4(cur.z, cur.w);
+    __syncthreads();
+
+    // ------------------------------------------------------------------ phase S
+    if (wave < G) {
+      const int a = wave;
+      float sv[MF_CH / 64], w[MF_CH / 64], zv[MF_CH / 64];
+      float m = -INFINITY;
 #pragma unroll
-      for (int set = 0; set < 2; ++set) {
-        const uint4* ap = reinterpret_cast<const uint4*>(&s_A[sl][set][n][q][0]);
-        const uint4 a0 = ap[0], a1 = ap[1];
-        v8i A;
-        A[0] = (int)a0.x; A[1] = (int)a0.y; A[2] = (int)a0.z; A[3] = (int)a0.w;
-        A[4] = (int)a1.x; A[5] = (int)a1.y; A[6] = (int)a1.z; A[7] = (int)a1.w;
-        acc[0][set] = mfma_fp8_fp4(A, B0, acc[0][set]);
-        acc[1][set] = mfma_fp8_fp4(A, B1, acc[1][set]);
+      for (int i = 0; i < MF_CH / 64; ++i) {
+        sv[i] = s_sc[a][lane + 64 * i];
+        m = fmaxf(m, sv[i]);
       }
-      cur = nxt;
+      for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s));
+      float l = 0.f, wmax = 0.f;
+#pragma unroll
+      for (int i = 0; i < MF_CH / 64; ++i) {
+        float p = 0.f;
+        if (sv[i] > -INFINITY) p = __expf(sv[i] - m);
+        float s_, z_;
+        rkv_unpack_meta(vmeta[i], s_, z_);
+        w[i] = p * s_;
+        zv[i] = z_;
+        l += p;
+        wmax = fmaxf(wmax, w[i]);
+      }
+      for (int s = 1; s < 64; s <<= 1) {
+        l += __shfl_xor(l, s);
+        wmax = fmaxf(wmax, __shfl_xor(wmax, s));
+      }
+      // 24-bit fixed point: largest weight lands in [2^23, 2^24); six base-16 digits, exact in E4M3
+      int ex = 0;
+      if (wmax > 0.f) frexpf(wmax, &ex);
+      const float up = ldexpf(1.0f, 24 - ex), down = ldexpf(1.0f, ex - 24);
+      float zs = 0.f;
+#pragma unroll
+      for (int i = 0; i < MF_CH / 64; ++i) {
+        const int tl = lane + 64 * i, slab = tl >> 5, tau = tl & 31;
+        const uint32_t W = (uint32_t)rintf(w[i] * up);
+        zs += (float)W * zv[i];
+        uint8_t* dst = &s_A[slab][0][4 * a][2 * (a & 1) + (tau >> 4)][16 * (a >> 1) + (tau & 15)];
+#pragma unroll
+        for (int k = 0; k < 6; k += 2) {
+          // digits 5-k and 4-k (most significant first): rows 0..3 of set 0, rows 0..1 of set 1
+          const float d_hi = (float)(k == 0 ? (W >> 20) : ((W >> (20 - 4 * k)) & 15u));
+          const float d_lo = (float)((W >> (16 - 4 * k)) & 15u);
+          const int pk = __builtin_amdgcn_cvt_pk_fp8_f32(d_hi, d_lo, 0, false);
+          const int row = k & 3, set = k >> 2;
+          dst[set * (16 * 4 * 32) + row * (4 * 32)] = (uint8_t)(pk & 0xff);
+          dst[set * (16 * 4 * 32) + (row + 1) * (4 * 32)] = (uint8_t)((pk >> 8) & 0xff);
+        }
+      }
+      for (int s = 1; s < 64; s <<= 1) zs += __shfl_xor(zs, s);
+      if (lane == 0) {
+        s_m[a] = m;
+        s_l[a] = l;
+        s_zs[a] = zs * down;
+        s_wsc[a] = down;
+      }
     }
-    if (has_head) {
-      const int qh = rg * G + q;
-      float* dst = part + (((size_t)b * v.Hq + qh) * nch + chunk) * RKV_PART_STRIDE;
-      const float wsc = 2.0f * s_wsc[q];                  // FP4 nibble = code/2
+    __syncthreads();
+
+    // ------------------------------------------------------------------ phase V
+    {
+      v4f acc[2][2];                                        // [channel tile][digit set]
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const v4f hi = acc[ct][0], lo = acc[ct][1];
-        const float sum = ((((hi[0] * 16.0f + hi[1]) * 16.0f + hi[2]) * 16.0f + hi[3]) * 16.0f + lo[0]) * 16.0f + lo[1];
-        dst[4 + 16 * (2 * wave + ct) + n] = sum * wsc - s_zs[q];
+      for (int i = 0; i < 2; ++i) acc[i][0] = acc[i][1] = (v4f){0.f, 0.f, 0.f, 0.f};
+      for (int sl = 0; sl < nslab; ++sl) {
+        uint4 nxt = make_uint4(0, 0, 0, 0);
+        if (has_head && sl + 1 < nslab) nxt = vslab[(size_t)(sl + 1) * (64 * G) + lidx];
+        const v8i B0 = unpack_fp4(cur.x, cur.y), B1 = unpack_fp4(cur.z, cur.w);
+#pragma unroll
+        for (int set = 0; set < 2; ++set) {
+          const uint4* ap = reinterpret_cast<const uint4*>(&s_A[sl][set][n][q][0]);
+          const uint4 a0 = ap[0], a1 = ap[1];
+          v8i A;
+          A[0] = (int)a0.x; A[1] = (int)a0.y; A[2] = (int)a0.z; A[3] = (int)a0.w;
+          A[4] = (int)a1.x; A[5] = (int)a1.y; A[6] = (int)a1.z; A[7] = (int)a1.w;
+          acc[0][set] = mfma_fp8_fp4(A, B0, acc[0][set]);
+          acc[1][set] = mfma_fp8_fp4(A, B1, acc[1][set]);
+        }
+        cur = nxt;
       }
-      if (wave == 0 && n == 0) {
-        dst[0] = s_m[q];
-        dst[1] = s_l[q];
+      if (has_head) {
+        const int qh = rg * G + q;
+        float* dst = part + (((size_t)b * v.Hq + qh) * nch + chunk) * RKV_PART_STRIDE;
+        const float wsc = 2.0f * s_wsc[q];                  // FP4 nibble = code/2
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          const v4f hi = acc[ct][0], lo = acc[ct][1];
+          const float sum = ((((hi[0] * 16.0f + hi[1]) * 16.0f + hi[2]) * 16.0f + hi[3]) * 16.0f + lo[0]) * 16.0f + lo[1];
+          dst[4 + 16 * (2 * wave + ct) + n] = sum * wsc - s_zs[q];
+        }
+        if (wave == 0 && n == 0) {
+          dst[0] = s_m[q];
+          dst[1] = s_l[q];
+        }
       }
     }
   }
@@ -376,14 +384,15 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, floa
   const RkvView& v = c->v;
   if (!rkv_mfma_supported(c)) return RKV_EINVAL;
   float* qr = (float*)scratch;
-  const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4) + 255) & ~(size_t)255;
+  const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
   rkv_launch_prep_q(v, q, q_pos, qr, s);
+  float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   dim3 grid(nch, v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  if (v.g == 4) hipLaunchKernelGGL(k_decode_mfma<4>, grid, dim3(256), 0, s, v, qr, part, nch);
-  else hipLaunchKernelGGL(k_decode_mfma<2>, grid, dim3(256), 0, s, v, qr, part, nch);
+  if (v.g == 4) hipLaunchKernelGGL(k_decode_mfma<4>, grid, dim3(256), 0, s, v, qt, part, nch);
+  else hipLaunchKernelGGL(k_decode_mfma<2>, grid, dim3(256), 0, s, v, qt, part, nch);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   rkv_launch_merge(v, qr, part, nch, out, lse, s);
   return rkv_check_launch();

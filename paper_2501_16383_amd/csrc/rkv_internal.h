@@ -58,6 +58,7 @@ struct rkv_cache {
   size_t off_tables;      // everything before this offset is cleared by reset
   int blocks_aligned;     // 1 if gid[c] == c/128 for every rotated channel
   int decode_path;
+  int n_cu;               // compute units of the device the cache lives on
   hipEvent_t ev_start, ev_stop;   // optional measurement hook around the main kernels
 };
 
