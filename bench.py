@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--path", type=int, default=0, help="decode kernel: 0 auto, 1 general, 2 matrix-core")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -164,6 +166,14 @@ def main():
             c.set_profile_events(*events[l])
             c.decode_attention(step_q[l][s], out=outs[l])
             c.set_profile_events(None, None)
+
+    if args.calib_copy_mib > 0:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
 
     for s in range(W):
         one_step(s)

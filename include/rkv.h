@@ -46,7 +46,7 @@ typedef struct rkv_config {
                         /* h / (n_q_heads / n_kv_heads))                                          */
   int32_t n_kv_heads;
   int32_t head_dim;     /* 128                                                                   */
-  int32_t max_tokens;   /* capacity per sequence                                                 */
+  int32_t max_tokens;   /* capacity per sequence, 1..65536                                       */
   int32_t max_sinks;    /* fp16 sink rows kept per sequence (0..64)                              */
   int32_t rot_heads;    /* consecutive KV heads rotated together (Sec. 4.2): 1, 2, 4 or 8;       */
                         /* must divide n_kv_heads                                                */

@@ -27,7 +27,7 @@ static int check_config(const rkv_config* c, bool need_capacity) {
   if (!(c->rope_theta > 1.0f)) return RKV_EINVAL;
   if (need_capacity) {
     if (c->batch < 1 || c->max_tokens < 1 || c->max_sinks < 0 || c->max_sinks > 64) return RKV_EINVAL;
-    if ((int64_t)c->max_tokens > (1 << 22) || (int64_t)c->batch > 65535) return RKV_EINVAL;
+    if ((int64_t)c->max_tokens > 65536 || (int64_t)c->batch > 65535) return RKV_EINVAL;
   }
   return RKV_OK;
 }

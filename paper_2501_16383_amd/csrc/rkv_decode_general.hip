@@ -196,17 +196,26 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
   }
 }
 
-// One workgroup per (query head, sequence); thread = output channel.
+// One workgroup per (query head, sequence); thread = output channel.  All global loads whose
+// addresses do not depend on loaded data are issued up front (two dependent round trips in all).
+#define MERGE_MAX_CH 512
 __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restrict__ qr, const float* __restrict__ part,
                                                int nch, float* __restrict__ out, float* __restrict__ lse) {
-  __shared__ float red[128];
+  __shared__ float s_w[MERGE_MAX_CH];     // chunk maxima, then chunk weights
+  __shared__ float s_l[MERGE_MAX_CH];
+  __shared__ float s_part[2][64];         // per-wave partial sink scores
   __shared__ float s_score[64];
-  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
+  __shared__ float red[128];
+  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x, lane = c & 63, wave = c >> 6;
   const int kvh = h / (v.Hq / v.Hkv);
   const size_t qbase = ((size_t)b * v.Hq + h) * RKV_D;
   const float* P = part + ((size_t)b * v.Hq + h) * nch * RKV_PART_STRIDE;
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
 
+  for (int k = c; k < nch; k += 128) {
+    s_w[k] = P[(size_t)k * RKV_PART_STRIDE];
+    s_l[k] = P[(size_t)k * RKV_PART_STRIDE + 1];
+  }
   // scores of the retained sink rows: exact fp16 keys, RoPE at their own position
   int j, partner;
   float sgn;
@@ -218,28 +227,23 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
     const __half* kr = v.sink_k + ((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D;
     const float2 cs = v.rope[(size_t)pos * 64 + j];
     const float x = __half2float(kr[c]), p = __half2float(kr[partner]);
-    red[c] = qc * (x * cs.x + sgn * p * cs.y);
-    __syncthreads();
-    for (int w = 64; w > 0; w >>= 1) {
-      if (c < w) red[c] += red[c + w];
-      __syncthreads();
-    }
-    if (c == 0) s_score[s] = red[0];
-    __syncthreads();
+    float d = qc * (x * cs.x + sgn * p * cs.y);
+    for (int o = 32; o > 0; o >>= 1) d += __shfl_xor(d, o);
+    if (lane == 0) s_part[wave][s] = d;
   }
+  __syncthreads();
+  if (c < cnt) s_score[c] = s_part[0][c] + s_part[1][c];
+  __syncthreads();
 
   float M = -INFINITY;
-  for (int k = 0; k < nch; ++k) M = fmaxf(M, P[(size_t)k * RKV_PART_STRIDE]);
+  for (int k = 0; k < nch; ++k) M = fmaxf(M, s_w[k]);
   for (int s = 0; s < cnt; ++s) M = fmaxf(M, s_score[s]);
   float L = 0.f, acc = 0.f;
   for (int k = 0; k < nch; ++k) {
-    const float* pk = P + (size_t)k * RKV_PART_STRIDE;
-    const float mk = pk[0];
-    if (mk > -INFINITY) {
-      const float w = __expf(mk - M);
-      L += w * pk[1];
-      acc += w * pk[4 + c];
-    }
+    const float mk = s_w[k];
+    const float w = mk > -INFINITY ? __expf(mk - M) : 0.f;
+    L += w * s_l[k];
+    acc += w * P[(size_t)k * RKV_PART_STRIDE + 4 + c];     // partial sums are always finite
   }
   if (v.v_rotate) {   // the 2-bit stream holds rotated values: undo the per-head Hadamard once
     red[c] = acc;

@@ -97,13 +97,28 @@ __device__ __forceinline__ float row_transpose_reduce(float (&v)[NV], int n) {
   return keep + dpp_f<DPP_QUAD_SWAP>(send);
 }
 
+// All-lanes reduction over the 64 lanes of a wave: 4 DPP steps inside each row of 16, then the
+// four row results through scalar registers.
+template <bool IS_MAX>
+__device__ __forceinline__ float wave_allreduce(float x) {
+  auto op = [](float a, float b) { return IS_MAX ? fmaxf(a, b) : a + b; };
+  x = op(x, dpp_f<DPP_QUAD_SWAP>(x));
+  x = op(x, dpp_f<0x4E>(x));                 // quad_perm [2,3,0,1]
+  x = op(x, dpp_f<DPP_ROW_HALF_MIRROR>(x));
+  x = op(x, dpp_f<DPP_ROW_MIRROR>(x));
+  const int xi = __float_as_int(x);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(xi, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(xi, 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(xi, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(xi, 48));
+  return op(op(r0, r1), op(r2, r3));
+}
+
 template <int G>
 __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* __restrict__ qt, float* __restrict__ part,
                                                         int nch) {
   __shared__ float s_sc[G][MF_CH];
   __shared__ __attribute__((aligned(16))) uint8_t s_A[MF_CH / 32][2][16][4][32];   // [slab][digit set][row][lane group][bytes]
   __shared__ float s_m[4], s_l[4], s_zs[4], s_wsc[4];
-  __shared__ int s_sink[64];
+  __shared__ int s_sink[4][64];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -133,8 +148,11 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
   const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
   const int t0 = chunk * MF_CH;
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
-  if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
-  for (int i = tid; i < G * MF_CH; i += 256) (&s_sc[0][0])[i] = -INFINITY;
+  // every wave keeps its own copy of the sink list and clears its own 64 score slots, so that
+  // phase K needs no workgroup barrier before it
+  s_sink[wave][lane] = lane < cnt ? v.sink_pos[b * v.max_sinks + lane] : -1;
+#pragma unroll
+  for (int a = 0; a < G; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
   // query of this rotation group, already RoPE'd, scaled and laid out per lane by k_prep_q
   float qlo[G][4], qhi[G][4];
   {
@@ -151,7 +169,6 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
 #pragma unroll
   for (int i = 0; i < MF_CH / 64; ++i)
     vmeta[i] = wave < G ? v.vm[((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G + wave] : 0u;
-  __syncthreads();
   {
     // ------------------------------------------------------------------ phase K
     {
@@ -262,7 +279,7 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
         const int idx = n & (4 * G - 1);
         const int tok = tt + 4 * q + idx / G, a = idx % G;
         bool masked = tok >= len;
-        for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
+        for (int i = 0; i < cnt; ++i) masked |= (s_sink[wave][i] == tok);
         if (n < 4 * G && !masked) s_sc[a][tok - t0] = tot;
       }
     }
@@ -285,7 +302,7 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
         sv[i] = s_sc[a][lane + 64 * i];
         m = fmaxf(m, sv[i]);
       }
-      for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s));
+      m = wave_allreduce<true>(m);
       float l = 0.f, wmax = 0.f;
 #pragma unroll
       for (int i = 0; i < MF_CH / 64; ++i) {
@@ -298,10 +315,8 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
         l += p;
         wmax = fmaxf(wmax, w[i]);
       }
-      for (int s = 1; s < 64; s <<= 1) {
-        l += __shfl_xor(l, s);
-        wmax = fmaxf(wmax, __shfl_xor(wmax, s));
-      }
+      l = wave_allreduce<false>(l);
+      wmax = wave_allreduce<true>(wmax);
       // 24-bit fixed point: largest weight lands in [2^23, 2^24); six base-16 digits, exact in E4M3
       int ex = 0;
       if (wmax > 0.f) frexpf(wmax, &ex);
@@ -324,7 +339,7 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
           dst[set * (16 * 4 * 32) + (row + 1) * (4 * 32)] = (uint8_t)((pk >> 8) & 0xff);
         }
       }
-      for (int s = 1; s < 64; s <<= 1) zs += __shfl_xor(zs, s);
+      zs = wave_allreduce<false>(zs);
       if (lane == 0) {
         s_m[a] = m;
         s_l[a] = l;
@@ -339,19 +354,35 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
       v4f acc[2][2];                                        // [channel tile][digit set]
 #pragma unroll
       for (int i = 0; i < 2; ++i) acc[i][0] = acc[i][1] = (v4f){0.f, 0.f, 0.f, 0.f};
+      uint4 aw[2][2];
+#pragma unroll
+      for (int set = 0; set < 2; ++set) {
+        const uint4* ap = reinterpret_cast<const uint4*>(&s_A[0][set][n][q][0]);
+        aw[set][0] = ap[0];
+        aw[set][1] = ap[1];
+      }
       for (int sl = 0; sl < nslab; ++sl) {
         uint4 nxt = make_uint4(0, 0, 0, 0);
         if (has_head && sl + 1 < nslab) nxt = vslab[(size_t)(sl + 1) * (64 * G) + lidx];
+        v8i A[2];
+#pragma unroll
+        for (int set = 0; set < 2; ++set) {
+          A[set][0] = (int)aw[set][0].x; A[set][1] = (int)aw[set][0].y; A[set][2] = (int)aw[set][0].z; A[set][3] = (int)aw[set][0].w;
+          A[set][4] = (int)aw[set][1].x; A[set][5] = (int)aw[set][1].y; A[set][6] = (int)aw[set][1].z; A[set][7] = (int)aw[set][1].w;
+        }
+        if (sl + 1 < nslab) {
+#pragma unroll
+          for (int set = 0; set < 2; ++set) {
+            const uint4* ap = reinterpret_cast<const uint4*>(&s_A[sl + 1][set][n][q][0]);
+            aw[set][0] = ap[0];
+            aw[set][1] = ap[1];
+          }
+        }
         const v8i B0 = unpack_fp4(cur.x, cur.y), B1 = unpack_fp4(cur.z, cur.w);
 #pragma unroll
         for (int set = 0; set < 2; ++set) {
-          const uint4* ap = reinterpret_cast<const uint4*>(&s_A[sl][set][n][q][0]);
-          const uint4 a0 = ap[0], a1 = ap[1];
-          v8i A;
-          A[0] = (int)a0.x; A[1] = (int)a0.y; A[2] = (int)a0.z; A[3] = (int)a0.w;
-          A[4] = (int)a1.x; A[5] = (int)a1.y; A[6] = (int)a1.z; A[7] = (int)a1.w;
-          acc[0][set] = mfma_fp8_fp4(A, B0, acc[0][set]);
-          acc[1][set] = mfma_fp8_fp4(A, B1, acc[1][set]);
+          acc[0][set] = mfma_fp8_fp4(A[set], B0, acc[0][set]);
+          acc[1][set] = mfma_fp8_fp4(A[set], B1, acc[1][set]);
         }
         cur = nxt;
       }

@@ -218,11 +218,30 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
   for (int i = tid; i < 2 * U; i += 256) imgK[i] = 0;   // imgK and imgV are adjacent
   __syncthreads();
 
-  float* zw = zbuf + wave * U;
-  for (int it = 0; it < 4; ++it) {
-    const int m = it * 4 + wave;
+  // old V dwords of a partly filled tile are fetched now and merged at the end
+  uint32_t keep = 0;
+  for (int m = 0; m < 16; ++m) {
     const int t = tile * 16 + m;
-    const bool active = (t >= t_lo) && (t < t_hi);
+    if (!(t >= t_lo && t < t_hi)) keep |= 3u << rkv_v_shift(t & 31);
+  }
+  uint32_t oldv[4] = {0, 0, 0, 0};
+  if (keep && U <= 1024) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int idx = tid + 256 * k;
+      if (idx < U) {
+        const int r = idx / n, c = idx - r * n;
+        oldv[k] = v.vc[rkv_v_slabbase(v, b, rg0 + r, tile >> 1) + rkv_v_off(g, c, (tile & 1) * 16)];
+      }
+    }
+  }
+
+  float* zw = zbuf + wave * U;
+  const int m_first = max(0, t_lo - tile * 16), m_last = min(15, t_hi - 1 - tile * 16);
+  for (int m0 = m_first; m0 <= m_last; m0 += 4) {
+    const int m = m0 + wave;
+    const int t = tile * 16 + m;
+    const bool active = m <= m_last;
     const size_t row = ((size_t)b * n_new + (active ? t - t_lo : 0)) * v.E;
     if (active) {
       for (int r = 0; r < rgs; ++r) {
@@ -313,16 +332,11 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
     if (t >= t_lo && t < t_hi) v.kc[rkv_k_tilebase(v, b, rg0 + r, tile) + off] = imgK[idx];
   }
   // V: a dword holds 16 token slots of one channel; keep the slots of tokens not in this call.
-  uint32_t keep = 0;
-  for (int m = 0; m < 16; ++m) {
-    const int t = tile * 16 + m;
-    if (!(t >= t_lo && t < t_hi)) keep |= 3u << rkv_v_shift(t & 31);
-  }
-  for (int idx = tid; idx < U; idx += 256) {
+  for (int idx = tid, k = 0; idx < U; idx += 256, ++k) {
     const int r = idx / n, c = idx - r * n;
     const size_t a = rkv_v_slabbase(v, b, rg0 + r, tile >> 1) + rkv_v_off(g, c, (tile & 1) * 16);
     uint32_t w = imgV[idx];
-    if (keep) w |= v.vc[a] & keep;
+    if (keep) w |= (U <= 1024 ? oldv[k & 3] : v.vc[a]) & keep;
     v.vc[a] = w;
   }
 }
