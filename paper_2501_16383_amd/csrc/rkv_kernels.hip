@@ -341,9 +341,167 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// quantize-append, fast path for reorders that keep the 128-blocks of the rotated row
+// (gid[c] == c/128): the quantization blocks are then the rotated blocks themselves, codes are
+// stored by rotated channel, and the reorder indices are not needed at all.
+//   One workgroup = (sequence, rotation group, slab of 32 token slots) so that every V dword
+//   (16 tokens of one channel), every K tile and every metadata row it touches is written whole.
+//   Wave w takes tokens 8w..8w+7 of the slab, one at a time: lane holds PL = n/64 consecutive
+//   channels; rotation in registers + lane exchanges; min/max over the lanes of a block; Eq. 6-9.
+// ---------------------------------------------------------------------------------------------
+
+template <int PL>
+__global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+                                                     int n_new, int slab0) {
+  constexpr int G = PL / 2;                    // heads per rotation group
+  constexpr int LPB = 128 / PL;                // lanes per 128-block
+  __shared__ uint32_t imgK[2 * 128 * G];       // two K tiles
+  __shared__ uint32_t imgV[4][64 * PL];        // per wave: partial V dwords of its 8 tokens, [i][lane]
+  __shared__ uint32_t metaK[32 * G], metaV[32 * G];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int slab = slab0 + blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
+  const int n = 128 * G;
+  const int t_lo = v.len, t_hi = v.len + n_new;
+  const int ts = slab * 32;
+
+  // slots of this slab that belong to tokens outside this call are kept
+  uint32_t keep[2] = {0, 0};
+  for (int tau = 0; tau < 32; ++tau) {
+    const int t = ts + tau;
+    if (!(t >= t_lo && t < t_hi)) keep[tau >> 4] |= 3u << rkv_v_shift(tau);
+  }
+  const size_t vbase = rkv_v_slabbase(v, b, rg, slab);
+  uint32_t oldv[G];
+#pragma unroll
+  for (int k = 0; k < G; ++k) oldv[k] = 0;
+  if (keep[0] | keep[1]) {
+#pragma unroll
+    for (int k = 0; k < G; ++k) oldv[k] = v.vc[vbase + tid + 256 * k];
+  }
+  for (int i = tid; i < 2 * 128 * G; i += 256) imgK[i] = 0;
+  __syncthreads();
+
+  const float rs = rsqrtf((float)n);
+  const int blk = lane / LPB;                              // 128-block (= KV head) of this lane's channels
+  const int kap0 = (PL * lane) & 127;                      // first channel inside the block
+  uint32_t vword[PL];
+#pragma unroll
+  for (int i = 0; i < PL; ++i) vword[i] = 0;
+
+  const int tau_first = max(0, t_lo - ts), tau_last = min(31, t_hi - 1 - ts);
+  for (int k = 0; k < 8; ++k) {
+    const int tau = 8 * wave + k;
+    if (tau < tau_first || tau > tau_last) continue;       // wave-uniform
+    const int t = ts + tau;
+    const size_t row = ((size_t)b * n_new + (t - t_lo)) * v.E + (size_t)rg * n + PL * lane;
+    // ---- keys
+    float x[PL];
+    load_halves<PL>(kin + row, x);
+    fwht_lanes<PL>(x, lane, 6);
+    float mn = 3.0e38f, mx = -3.0e38f;
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      x[i] *= rs;
+      mn = fminf(mn, x[i]);
+      mx = fmaxf(mx, x[i]);
+    }
+#pragma unroll
+    for (int s = 1; s < LPB; s <<= 1) {
+      mn = fminf(mn, __shfl_xor(mn, s));
+      mx = fmaxf(mx, __shfl_xor(mx, s));
+    }
+    {
+      float sc, zero;
+      quant_params(mn, mx, sc, zero);
+      uint32_t part = 0;
+      int off = 0;
+#pragma unroll
+      for (int i = 0; i < PL; ++i) {
+        int sh;
+        const int o = rkv_k_off(G, tau & 15, 128 * blk + kap0 + i, sh);
+        if (i == 0) off = o;                               // the lane's channels share one dword
+        part |= quant_code(x[i], sc, zero) << sh;
+      }
+      atomicOr(&imgK[(tau >> 4) * (128 * G) + off], part);
+      if ((lane & (LPB - 1)) == 0) metaK[tau * G + blk] = rkv_pack_meta(sc, zero);
+    }
+    // ---- values
+    float u[PL];
+    load_halves<PL>(vin + row, u);
+    if (v.v_rotate) {
+      fwht_lanes<PL>(u, lane, PL == 8 ? 4 : (PL == 4 ? 5 : (PL == 2 ? 6 : 3)));
+#pragma unroll
+      for (int i = 0; i < PL; ++i) u[i] *= 0.08838834764831845f;
+    }
+    mn = 3.0e38f; mx = -3.0e38f;
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      mn = fminf(mn, u[i]);
+      mx = fmaxf(mx, u[i]);
+    }
+#pragma unroll
+    for (int s = 1; s < LPB; s <<= 1) {
+      mn = fminf(mn, __shfl_xor(mn, s));
+      mx = fmaxf(mx, __shfl_xor(mx, s));
+    }
+    {
+      float sc, zero;
+      quant_params(mn, mx, sc, zero);
+      const int sh = rkv_v_shift(tau);
+#pragma unroll
+      for (int i = 0; i < PL; ++i) vword[i] |= quant_code(u[i], sc, zero) << sh;
+      if ((lane & (LPB - 1)) == 0) metaV[tau * G + blk] = rkv_pack_meta(sc, zero);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < PL; ++i) imgV[wave][i * 64 + lane] = vword[i];
+  __syncthreads();
+
+  // ---- K tiles: every 16-byte piece belongs to one token
+#pragma unroll
+  for (int k = 0; k < G; ++k) {
+    const int idx = tid + 256 * k;                          // 0 .. 256G-1
+    const int ti = idx / (128 * G), off = idx - ti * (128 * G);
+    const int t = ts + ti * 16 + rkv_k_tile_token(G, off);
+    if (t >= t_lo && t < t_hi) v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off] = imgK[idx];
+  }
+  // ---- V slab: dword idx = (((w*G + hh)*16 + nn)*2 + ct)*2 + d, channel c = 128hh + 32w + 16ct + nn;
+  //      waves 2d and 2d+1 hold the two halves of its 16 token slots
+#pragma unroll
+  for (int k = 0; k < G; ++k) {
+    const int idx = tid + 256 * k;
+    const int d = idx & 1, ct = (idx >> 1) & 1, nn = (idx >> 2) & 15, rest = idx >> 6;
+    const int hh = rest % G, w = rest / G;
+    const int c = 128 * hh + 32 * w + 16 * ct + nn;
+    const int ln = c / PL, i = c - ln * PL;
+    uint32_t word = imgV[2 * d][i * 64 + ln] | imgV[2 * d + 1][i * 64 + ln];
+    if (keep[d]) word |= oldv[k] & keep[d];
+    if (keep[d] != 0xffffffffu) v.vc[vbase + idx] = word;
+  }
+  // ---- metadata rows of the tokens written
+  for (int i = tid; i < 32 * G; i += 256) {
+    const int tau = i / G;
+    if (tau >= tau_first && tau <= tau_last) {
+      const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + ts + tau) * G + (i - tau * G);
+      v.km[mi] = metaK[i];
+      v.vm[mi] = metaV[i];
+    }
+  }
+}
+
 int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new, const uint8_t* mask, hipStream_t s) {
   const RkvView& v = c->v;
   if (mask && v.max_sinks > 0) hipLaunchKernelGGL(k_sinks, dim3(v.B), dim3(256), 0, s, v, k, vv, mask, n_new);
+  if (c->blocks_aligned && (v.g == 2 || v.g == 4)) {
+    const int slab0 = v.len >> 5, slab1 = (v.len + n_new - 1) >> 5;
+    dim3 grid(slab1 - slab0 + 1, v.NRG, v.B);
+    if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
+    if (v.g == 4) hipLaunchKernelGGL(k_append_fast<8>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    else hipLaunchKernelGGL(k_append_fast<4>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
+    return rkv_check_launch();
+  }
   const int U = v.span > v.n ? v.span : v.n;
   const int tile0 = v.len >> 4, tile1 = (v.len + n_new - 1) >> 4;
   dim3 grid(tile1 - tile0 + 1, v.E / U, v.B);
