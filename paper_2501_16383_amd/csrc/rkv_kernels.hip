@@ -24,11 +24,11 @@ __device__ inline void fwht_lanes(T (&x)[PL], int lane, int xstages) {
   }
   for (int s = 0; s < xstages; ++s) {
     const int mask = 1 << s;
-    const bool up = (lane & mask) != 0;
+    const T sgn = (lane & mask) ? (T)-1 : (T)1;
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
       T o = __shfl_xor(x[i], mask);
-      x[i] = up ? (o - x[i]) : (x[i] + o);
+      x[i] = sgn * x[i] + o;
     }
   }
 }
@@ -59,8 +59,10 @@ __device__ inline void load_halves(const __half* p, float (&x)[PL]) {
   }
 }
 
-// Eq. 8-9 for one block of 128 given its min and max: fp16 scale actually stored, integer zero.
-__device__ inline void quant_params(float mn, float mx, float& s, float& zero) {
+// Eq. 8-9 for one block of 128 given its min and max: fp16 scale actually stored, integer zero,
+// and the reciprocal of the scale (one IEEE division per block; elements multiply by it, which
+// differs from x / s only within ~1.5 ulp, far inside the rounding-tie window of the parity tests).
+__device__ inline void quant_params(float mn, float mx, float& s, float& zero, float& inv_s) {
   float raw = (mx - mn) / 3.0f;
   s = __half2float(__float2half_rn(raw));
   if (!(s <= 65504.0f)) s = 65504.0f;
@@ -69,12 +71,13 @@ __device__ inline void quant_params(float mn, float mx, float& s, float& zero) {
     if (!(s <= 65504.0f)) s = 65504.0f;
     if (s == 0.0f) s = 1.0f;
   }
-  zero = -rintf(mn / s);
+  inv_s = 1.0f / s;
+  zero = -rintf(mn * inv_s);
   zero = fminf(fmaxf(zero, -2048.0f), 2048.0f);
 }
 // Eq. 6
-__device__ inline uint32_t quant_code(float x, float s, float zero) {
-  float q = rintf(x / s) + zero;
+__device__ inline uint32_t quant_code(float x, float inv_s, float zero) {
+  float q = rintf(x * inv_s) + zero;
   q = fminf(fmaxf(q, 0.0f), 3.0f);
   return (uint32_t)q;
 }
@@ -275,11 +278,11 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
           mx = fmaxf(mx, __shfl_xor(mx, s));
         }
         if (on) {
-          float sc, zero;
-          quant_params(mn, mx, sc, zero);
+          float sc, zero, inv;
+          quant_params(mn, mx, sc, zero, inv);
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
-            const uint32_t code = quant_code(z[i], sc, zero);
+            const uint32_t code = quant_code(z[i], inv, zero);
             const int cr = v.perm[ubase + pos + i] - ubase;      // rotated channel, unit-local
             const int r = cr / n, c = cr - r * n;
             int sh;
@@ -312,11 +315,11 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
           mx = fmaxf(mx, __shfl_xor(mx, s));
         }
         if (on) {
-          float sc, zero;
-          quant_params(mn, mx, sc, zero);
+          float sc, zero, inv;
+          quant_params(mn, mx, sc, zero, inv);
           const int sh = rkv_v_shift(t & 31);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) atomicOr(&imgV[pos + i], quant_code(u[i], sc, zero) << sh);
+          for (int i = 0; i < 8; ++i) atomicOr(&imgV[pos + i], quant_code(u[i], inv, zero) << sh);
           if ((lane & 15) == 0) v.vm[rkv_meta_index(v, b, t, (ubase + pos) >> 7)] = rkv_pack_meta(sc, zero);
         }
       }
@@ -412,8 +415,8 @@ __global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __
       mx = fmaxf(mx, __shfl_xor(mx, s));
     }
     {
-      float sc, zero;
-      quant_params(mn, mx, sc, zero);
+      float sc, zero, inv;
+      quant_params(mn, mx, sc, zero, inv);
       uint32_t part = 0;
       int off = 0;
 #pragma unroll
@@ -421,7 +424,7 @@ __global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __
         int sh;
         const int o = rkv_k_off(G, tau & 15, 128 * blk + kap0 + i, sh);
         if (i == 0) off = o;                               // the lane's channels share one dword
-        part |= quant_code(x[i], sc, zero) << sh;
+        part |= quant_code(x[i], inv, zero) << sh;
       }
       atomicOr(&imgK[(tau >> 4) * (128 * G) + off], part);
       if ((lane & (LPB - 1)) == 0) metaK[tau * G + blk] = rkv_pack_meta(sc, zero);
@@ -446,11 +449,11 @@ __global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __
       mx = fmaxf(mx, __shfl_xor(mx, s));
     }
     {
-      float sc, zero;
-      quant_params(mn, mx, sc, zero);
+      float sc, zero, inv;
+      quant_params(mn, mx, sc, zero, inv);
       const int sh = rkv_v_shift(tau);
 #pragma unroll
-      for (int i = 0; i < PL; ++i) vword[i] |= quant_code(u[i], sc, zero) << sh;
+      for (int i = 0; i < PL; ++i) vword[i] |= quant_code(u[i], inv, zero) << sh;
       if ((lane & (LPB - 1)) == 0) metaV[tau * G + blk] = rkv_pack_meta(sc, zero);
     }
   }
