@@ -24,7 +24,8 @@ __device__ inline void fwht_lanes(T (&x)[PL], int lane, int xstages) {
   }
   for (int s = 0; s < xstages; ++s) {
     const int mask = 1 << s;
-    const T sgn = (lane & mask) ? (T)-1 : (T)1;
+    T sgn = (lane & mask) ? (T)-1 : (T)1;
+    asm volatile("" : "+v"(sgn));     // keep it a register operand so each butterfly is one FMA
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
       T o = __shfl_xor(x[i], mask);

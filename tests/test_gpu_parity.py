@@ -236,3 +236,121 @@ def test_error_codes():
     with pytest.raises(R.RkvError) as ei:
         cache.set_perm(P.gpu(np.arange(cfg.E, dtype=np.int32)))
     assert ei.value.code == -5
+
+
+def test_full_size_config2_sampled():
+    """BASELINE configuration 2 at full size (batch 16, 40 heads, context 4096), in the launch
+    configuration bench.py times: bulk append of 4095 tokens, one single-token append, decode on
+    the matrix-core path.  The oracle recomputes sampled (sequence, rotation group) slices - a
+    rotation group's codes and attention outputs depend on nothing outside the slice."""
+    w = S.WORKLOADS["cfg2"]
+    T = w.context
+    cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=4,
+                      rot_heads=4, perm_span=128)
+    perm = calibrated_perm(w, cfg)
+    cache = R.RkvCache(cfg)
+    cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+    samples = [(0, 0), (7, 3), (15, 9)]
+    keep = {}
+    print("[case] full-size config 2: generating inputs per sequence", flush=True)
+    k_parts, v_parts, m_parts = [], [], []
+    rng_w = dataclasses.replace(w)
+    for b in range(w.batch):
+        kb, vb, mb = S.make_kv(dataclasses.replace(rng_w, seed=w.seed + 100 * b), T, batch=1)
+        for (sb, rg) in samples:
+            if sb == b:
+                keep[(sb, rg)] = (kb[:, :, 4 * rg:4 * rg + 4].copy(), vb[:, :, 4 * rg:4 * rg + 4].copy(), mb.copy())
+        k_parts.append(torch.from_numpy(kb))
+        v_parts.append(torch.from_numpy(vb))
+        m_parts.append(torch.from_numpy(mb))
+    k = torch.cat(k_parts).cuda()
+    v = torch.cat(v_parts).cuda()
+    mask = torch.cat(m_parts).cuda()
+    del k_parts, v_parts
+    q = S.make_q(w)
+    print("[case] full-size config 2: bulk append 4095 + single append + decode", flush=True)
+    cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous())
+    cache.quantize_append(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), mask[:, T - 1:].contiguous())
+    cache.set_decode_path(2)
+    out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
+    exp = cache.export_codes()
+    torch.cuda.synchronize()
+    assert cache.length == T
+    out = out.cpu().numpy().astype(np.float64)
+    lse = lse.cpu().numpy().astype(np.float64)
+    kc_all = exp["k_codes"].cpu().numpy()
+    ks_all = exp["k_scale"].cpu().numpy().astype(np.float64)
+    assert np.isfinite(out).all()
+    for (b, rg) in samples:
+        ks, vs, ms = keep[(b, rg)]
+        ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=4)
+        oc = O.cache_new(ocfg, perm[512 * rg:512 * (rg + 1)] - 512 * rg)
+        O.quantize_append(oc, ks, vs, ms)
+        g_codes = O.unpack_canonical(kc_all[b:b + 1, :, 128 * rg:128 * (rg + 1)])
+        P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g_codes, ks_all[b:b + 1, :, 4 * rg:4 * rg + 4],
+                        exp["k_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64), f"full-size b={b} rg={rg} K")
+        oc.k_codes = g_codes                                   # attention on the GPU's own codes
+        oc.k_scale = ks_all[b:b + 1, :, 4 * rg:4 * rg + 4]
+        oc.k_zero = exp["k_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64)
+        oc.v_codes = O.unpack_canonical(exp["v_codes"][b:b + 1, :, 128 * rg:128 * (rg + 1)].cpu().numpy())
+        oc.v_scale = exp["v_scale"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64)
+        oc.v_zero = exp["v_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64)
+        ref, lse_ref = O.decode_attention(oc, q[b:b + 1, 4 * rg:4 * rg + 4])
+        e = P.attention_error(out[b:b + 1, 4 * rg:4 * rg + 4], ref)
+        le = float(np.abs(lse[b:b + 1, 4 * rg:4 * rg + 4] - lse_ref).max())
+        print(f"[parity] full-size b={b} rg={rg}: out err {e:.3e} lse err {le:.3e}", flush=True)
+        assert e <= ATT_TOL and le <= LSE_TOL
+
+
+def test_full_size_long_context_sampled():
+    """Configuration 3's shape: one sequence of 32768 tokens, 32 heads; prefill-size quantize, then
+    split-K decode over 128 chunks.  One rotation group is recomputed by the oracle."""
+    w = S.WORKLOADS["cfg3"]
+    T = w.context
+    cfg = R.RkvConfig(batch=1, n_q_heads=32, n_kv_heads=32, max_tokens=T, max_sinks=4, rot_heads=4, perm_span=128)
+    cache = R.RkvCache(cfg)
+    k, v, mask = S.make_kv(w, T)
+    q = S.make_q(w)
+    print("[case] long context: bulk append 32768 + decode", flush=True)
+    cache.quantize_append(P.gpu(k), P.gpu(v), P.gpu(mask))
+    out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy().astype(np.float64)
+    rg = 5
+    ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=4)
+    oc = O.cache_new(ocfg)
+    O.quantize_append(oc, k[:, :, 4 * rg:4 * rg + 4], v[:, :, 4 * rg:4 * rg + 4], mask)
+    ref, lse_ref = O.decode_attention(oc, q[:, 4 * rg:4 * rg + 4])
+    e = P.attention_error(out[:, 4 * rg:4 * rg + 4], ref)
+    le = float(np.abs(lse.cpu().numpy()[:, 4 * rg:4 * rg + 4] - lse_ref).max())
+    print(f"[parity] long context rg={rg}: out err {e:.3e} lse err {le:.3e}", flush=True)
+    assert e <= ATT_TOL and le <= LSE_TOL
+
+
+def test_full_size_config1_shape_without_sinks():
+    """Configuration 1's full shape (batch 8, 32 heads, context 4096) with no sink tokens, so that
+    nothing hides the 2-bit stream's contribution; sampled slices against the oracle."""
+    w = small("cfg1", n_sinks=0)
+    T = w.context
+    cfg = R.RkvConfig(batch=w.batch, n_q_heads=32, n_kv_heads=32, max_tokens=T, max_sinks=0, rot_heads=4, perm_span=128)
+    cache = R.RkvCache(cfg)
+    k, v, _ = S.make_kv(w, T, sink_positions=[])
+    q = S.make_q(w)
+    print("[case] config 1 shape, no sinks: bulk append 4096 + decode", flush=True)
+    cache.quantize_append(P.gpu(k), P.gpu(v))
+    cache.set_decode_path(2)
+    out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy().astype(np.float64)
+    lse = lse.cpu().numpy().astype(np.float64)
+    for (b, rg) in [(0, 0), (3, 5), (7, 7)]:
+        ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=0)
+        oc = O.cache_new(ocfg)
+        O.quantize_append(oc, k[b:b + 1, :, 4 * rg:4 * rg + 4], v[b:b + 1, :, 4 * rg:4 * rg + 4])
+        ref, lse_ref = O.decode_attention(oc, q[b:b + 1, 4 * rg:4 * rg + 4])
+        e = P.attention_error(out[b:b + 1, 4 * rg:4 * rg + 4], ref)
+        le = float(np.abs(lse[b:b + 1, 4 * rg:4 * rg + 4] - lse_ref).max())
+        print(f"[parity] config 1 shape b={b} rg={rg}: out err {e:.3e} lse err {le:.3e}", flush=True)
+        # the GPU decodes its own codes, the oracle its own: the few codes that differ at rounding
+        # ties (see parity_utils) move the output by far less than the tolerance
+        assert e <= ATT_TOL and le <= LSE_TOL
