@@ -30,6 +30,12 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 #define MF_CH 256          // tokens per workgroup
 #define MF_TILES 4         // 16-token tiles per wave
+#ifndef MF_PIPE
+#define MF_PIPE 0          // 1: matrix products one step ahead of the vector work (needs 32 more registers)
+#endif
+#ifndef MF_OCC
+#define MF_OCC 2           // workgroups per compute unit the register budget is set for
+#endif
 
 __device__ __forceinline__ v4f mfma_fp4(const v8i& a, const v8i& b, const v4f& c) {
   return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, 0, 0, 0);
@@ -113,12 +119,14 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 }
 
 template <int G>
-__global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* __restrict__ qt, float* __restrict__ part,
+__global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt, float* __restrict__ part,
                                                         int nch) {
   __shared__ float s_sc[G][MF_CH];
   __shared__ __attribute__((aligned(16))) uint8_t s_A[MF_CH / 32][2][16][4][32];   // [slab][digit set][row][lane group][bytes]
   __shared__ float s_m[4], s_l[4], s_zs[4], s_wsc[4];
   __shared__ int s_sink[4][64];
+  __shared__ uint4 s_H[8][64];                   // Hadamard operand tiles
+  __shared__ __attribute__((aligned(16))) float s_q[16][4][2 * G];   // query [n][p][head][lo, hi]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -128,14 +136,8 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
     for (int i = tid; i < (int)(sizeof(s_A) / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
   }
 
-  // constants of the whole kernel: Hadamard operand, per-lane rows of H_g, RoPE step of 16 positions
-  v8i H[8];
-#pragma unroll
-  for (int mt = 0; mt < 8; ++mt) {
-    const uint4 h = reinterpret_cast<const uint4*>(v.hop)[mt * 64 + lane];
-    H[mt][0] = (int)h.x; H[mt][1] = (int)h.y; H[mt][2] = (int)h.z; H[mt][3] = (int)h.w;
-    H[mt][4] = H[mt][5] = H[mt][6] = H[mt][7] = 0;
-  }
+  // Hadamard operand tiles go to LDS once per workgroup; the key phase reads two of them per step
+  for (int i = tid; i < 8 * 64; i += 256) (&s_H[0][0])[i] = reinterpret_cast<const uint4*>(v.hop)[i];
   float st_c[4], st_s[4];
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
@@ -153,22 +155,15 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
   s_sink[wave][lane] = lane < cnt ? v.sink_pos[b * v.max_sinks + lane] : -1;
 #pragma unroll
   for (int a = 0; a < G; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
-  // query of this rotation group, already RoPE'd, scaled and laid out per lane by k_prep_q
-  float qlo[G][4], qhi[G][4];
-  {
-    const uint4* qp = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * 16 + n) * (G * 8));
-#pragma unroll
-    for (int a = 0; a < G; ++a) {
-      const uint4 u0 = qp[2 * a], u1 = qp[2 * a + 1];
-      qlo[a][0] = __uint_as_float(u0.x); qlo[a][1] = __uint_as_float(u0.y); qlo[a][2] = __uint_as_float(u0.z); qlo[a][3] = __uint_as_float(u0.w);
-      qhi[a][0] = __uint_as_float(u1.x); qhi[a][1] = __uint_as_float(u1.y); qhi[a][2] = __uint_as_float(u1.z); qhi[a][3] = __uint_as_float(u1.w);
-    }
-  }
+  // query of this rotation group, already RoPE'd, scaled and laid out [n][p][head][lo, hi] by k_prep_q
+  if (tid < 16 * 4 * 2 * G / 4)
+    reinterpret_cast<uint4*>(&s_q[0][0][0])[tid] = reinterpret_cast<const uint4*>(qt + ((size_t)b * v.NRG + rg) * (16 * 4 * 2 * G))[tid];
   // V metadata of the four tokens this lane turns into weights in phase S (head = wave)
   uint32_t vmeta[MF_CH / 64];
 #pragma unroll
   for (int i = 0; i < MF_CH / 64; ++i)
     vmeta[i] = wave < G ? v.vm[((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G + wave] : 0u;
+  __syncthreads();
   {
     // ------------------------------------------------------------------ phase K
     {
@@ -204,6 +199,7 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
       };
       load_tile(0);
 
+#pragma unroll
       for (int ti = 0; ti < MF_TILES; ++ti) {
         const int tt = tw + ti * 16;
         if (tt >= len) break;                              // wave-uniform
@@ -228,16 +224,43 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
         float pt[4 * G];                                   // [r][a]
 #pragma unroll
         for (int i = 0; i < 4 * G; ++i) pt[i] = 0.f;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          v4f lo[G], hi[G];
+        // matrix products run one step (16 + 16 channels) ahead of the vector work that consumes them
+        v4f lo2[2][G], hi2[2][G];
+        auto issue = [&](int p, int buf) {
+          v8i Hlo, Hhi;
+          {
+            const uint4 h0 = s_H[p][lane], h1 = s_H[p + 4][lane];
+            Hlo[0] = (int)h0.x; Hlo[1] = (int)h0.y; Hlo[2] = (int)h0.z; Hlo[3] = (int)h0.w; Hlo[4] = Hlo[5] = Hlo[6] = Hlo[7] = 0;
+            Hhi[0] = (int)h1.x; Hhi[1] = (int)h1.y; Hhi[2] = (int)h1.z; Hhi[3] = (int)h1.w; Hhi[4] = Hhi[5] = Hhi[6] = Hhi[7] = 0;
+          }
 #pragma unroll
           for (int blk = 0; blk < G; ++blk) {
             v4f c0 = {0.f, 0.f, 0.f, 0.f};
             if (p == 0) { c0[0] = zc[0][blk]; c0[1] = zc[1][blk]; c0[2] = zc[2][blk]; c0[3] = zc[3][blk]; }
             const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-            lo[blk] = mfma_fp4(A[blk], H[p], c0);          // (H_128 c_blk - 128 z e_0) / 2, channels 16p + n
-            hi[blk] = mfma_fp4(A[blk], H[p + 4], zero4);   // channels 16p + n + 64
+            lo2[buf][blk] = mfma_fp4(A[blk], Hlo, c0);          // (H_128 c_blk - 128 z e_0) / 2, channels 16p + n
+            hi2[buf][blk] = mfma_fp4(A[blk], Hhi, zero4);   // channels 16p + n + 64
+          }
+        };
+#if MF_PIPE
+        issue(0, 0);
+#endif
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+#if MF_PIPE
+          if (p < 3) issue(p + 1, (p + 1) & 1);
+          v4f (&lo)[G] = lo2[p & 1];
+          v4f (&hi)[G] = hi2[p & 1];
+#else
+          issue(p, 0);
+          v4f (&lo)[G] = lo2[0];
+          v4f (&hi)[G] = hi2[0];
+#endif
+          float qv[2 * G];
+#pragma unroll
+          for (int i = 0; i < 2 * G; i += 4) {
+            const uint4 u = *reinterpret_cast<const uint4*>(&s_q[n][p][i]);
+            qv[i] = __uint_as_float(u.x); qv[i + 1] = __uint_as_float(u.y); qv[i + 2] = __uint_as_float(u.z); qv[i + 3] = __uint_as_float(u.w);
           }
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
@@ -261,7 +284,7 @@ __global__ void __launch_bounds__(256, 2) k_decode_mfma(RkvView v, const float* 
             for (int a = 0; a < G; ++a) {
               const float xl = klo[a] * c - khi[a] * s;
               const float xh = klo[a] * s + khi[a] * c;
-              pt[r * G + a] = fmaf(xh, qhi[a][p], fmaf(xl, qlo[a][p], pt[r * G + a]));
+              pt[r * G + a] = fmaf(xh, qv[2 * a + 1], fmaf(xl, qv[2 * a], pt[r * G + a]));
             }
           }
         }
