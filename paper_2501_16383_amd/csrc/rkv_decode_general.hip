@@ -56,14 +56,15 @@ __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restr
   const float x = __half2float(q[base + c]), p = __half2float(q[base + partner]);
   const float val = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
   qr[base + c] = val;
-  // second copy for the matrix-core kernel: [b][rot group][n 0..15][p 0..3][head a][lo, hi] with
+  // second copy for the matrix-core kernel: [b][rot group][rr][n 0..15][p 0..3][KV head a][lo, hi]
+  // (rr = which of the query heads sharing KV head a) with
   // entry (n, p, half) = channel 16p + n + 64*half, pre-multiplied by 2/sqrt(rotation size)
   // (FP4 nibbles hold code/2; 1/sqrt(n) is the normalisation of Eq. 10)
-  const int g = v.g, rg = h / g, a = h - rg * g;           // valid when one query head reads one KV head
+  const int g = v.g, rep = v.Hq / v.Hkv;
+  const int kvh = h / rep, rr = h - kvh * rep, rg = kvh / g, a = kvh - rg * g;
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;
   const int nn = c & 15, pp = (c >> 4) & 3, half = c >> 6;
-  if (v.Hq == v.Hkv)
-    qt[(((((size_t)b * v.NRG + rg) * 16 + nn) * 4 + pp) * g + a) * 2 + half] = val * 2.0f * rsqrtf((float)v.n);
+  qt[((((((size_t)b * v.NRG + rg) * rep + rr) * 16 + nn) * 4 + pp) * g + a) * 2 + half] = val * 2.0f * rsqrtf((float)v.n);
 }
 
 __device__ inline bool is_sink(const int* sp, int cnt, int t) {

@@ -22,7 +22,8 @@
 //   phase V  wave w: channels 32w..32w+31 of every head; A = weight digits [16 x (4 heads x 32
 //            tokens)], block-diagonal over heads, B = codes [(4 heads x 32 tokens) x 16 channels].
 // Covers: reorder that keeps 128-blocks (gid[c] == c/128), rot_heads 2 or 4, half-split RoPE
-// pairs, one query head per KV head.  Everything else takes the general kernel.
+// pairs.  With GQA every group of query heads (one per KV head) gets its own workgroup, which
+// repeats the key-side work.  Everything else takes the general kernel.
 #include "rkv_internal.h"
 
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -147,7 +148,14 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   }
   const float zmask = (n == 0) ? -64.0f : 0.0f;           // H_128 of a constant block lives in channel 0
 
-  const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
+  // blockIdx.x = rr * nch8 + chunk, nch8 = chunk count rounded up to 8: the workgroups that serve
+  // the `rep` query heads sharing a KV head (GQA) re-read the same chunk, and with ids a multiple of
+  // 8 apart they land on the same XCD, whose L2 then holds the chunk for the later ones
+  const int nch8 = (nch + 7) & ~7;
+  const int rr = blockIdx.x / nch8, chunk = blockIdx.x - rr * nch8;
+  const int rg = blockIdx.y, b = blockIdx.z;
+  if (chunk >= nch) return;
+  const int rep = v.Hq / v.Hkv;
   const int t0 = chunk * MF_CH;
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
   // every wave keeps its own copy of the sink list and clears its own 64 score slots, so that
@@ -157,7 +165,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   for (int a = 0; a < G; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
   // query of this rotation group, already RoPE'd, scaled and laid out [n][p][head][lo, hi] by k_prep_q
   if (tid < 16 * 4 * 2 * G / 4)
-    reinterpret_cast<uint4*>(&s_q[0][0][0])[tid] = reinterpret_cast<const uint4*>(qt + ((size_t)b * v.NRG + rg) * (16 * 4 * 2 * G))[tid];
+    reinterpret_cast<uint4*>(&s_q[0][0][0])[tid] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * rep + rr) * (16 * 4 * 2 * G))[tid];
   // V metadata of the four tokens this lane turns into weights in phase S (head = wave)
   uint32_t vmeta[MF_CH / 64];
 #pragma unroll
@@ -410,7 +418,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         cur = nxt;
       }
       if (has_head) {
-        const int qh = rg * G + q;
+        const int qh = (rg * G + q) * rep + rr;                // query head served for KV head rg*G + q
         float* dst = part + (((size_t)b * v.Hq + qh) * nch + chunk) * RKV_PART_STRIDE;
         const float wsc = 2.0f * s_wsc[q];                  // FP4 nibble = code/2
 #pragma unroll
@@ -430,7 +438,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && (v.g == 2 || v.g == 4) && v.rope_style == 0 && v.Hq == v.Hkv;
+  return c->blocks_aligned && (v.g == 2 || v.g == 4) && v.rope_style == 0;
 }
 
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
@@ -443,7 +451,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, floa
   const int nch = (v.len + MF_CH - 1) / MF_CH;
   rkv_launch_prep_q(v, q, q_pos, qr, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
-  dim3 grid(nch, v.NRG, v.B);
+  dim3 grid(((nch + 7) & ~7) * (v.Hq / v.Hkv), v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (v.g == 4) hipLaunchKernelGGL(k_decode_mfma<4>, grid, dim3(256), 0, s, v, qt, part, nch);
   else hipLaunchKernelGGL(k_decode_mfma<2>, grid, dim3(256), 0, s, v, qt, part, nch);
