@@ -26,6 +26,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+SHAPES = {"cfg0": "single-layer toy", "cfg1": "LLaMA-2-7B-shaped", "cfg2": "LLaMA-2-13B-shaped", "cfg3": "long-context",
+          "cfg4": "LLaMA-3-8B-shaped (GQA)"}
 
 
 class Hip:
@@ -199,6 +201,14 @@ def main():
     launch_bytes = B * ctx * bytes_per_tok
     achieved = launch_bytes / (avg_ms * 1e-3) / 1e9
 
+    # measured HBM traffic of the decode kernel (rocprofv3 counters, calibrated; see profiles/)
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"decode_{w.name}_hbm_traffic.md")
+    if os.path.exists(tfile) and L == w.layers:
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+
     # sanity: finite outputs
     assert all(bool(torch.isfinite(o).all()) for o in outs)
 
@@ -211,11 +221,11 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u2 codes + fp16 scale/zero; fp4 matrix products and fp32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: LLaMA-2-13B-shaped decode, {L} layers x {w.n_kv_heads} heads x 128, batch {B}, "
-                               f"context {T}, rotation over {w.rot_heads} heads, 2-bit group-128, {w.n_sinks} fp16 sinks",
+        "config": {"workload": f"{w.name}: {SHAPES.get(w.name, 'custom')} decode, {L} layers x {w.n_q_heads} query / {w.n_kv_heads} KV heads x 128, "
+                               f"batch {B}, context {T}, rotation over {w.rot_heads} heads, 2-bit group-128, {w.n_sinks} fp16 sinks",
                    "decode_path": args.path},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "min_launch_ms": min_ms,
+                     "traffic": traffic, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "min_launch_ms": min_ms,
                      "algorithmic_bytes_per_launch": launch_bytes, "bytes_per_kv_token": bytes_per_tok},
         "append_bulk": {"GB/s_best": bulk_bytes / (bulk_best * 1e-3) / 1e9, "GB/s_avg": bulk_bytes / (bulk_avg * 1e-3) / 1e9,
                         "frac_of_hbm_peak_best": bulk_bytes / (bulk_best * 1e-3) / 1e9 / HBM_PEAK_GBS,
