@@ -28,11 +28,15 @@
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 
 #define MF_CH 256          // tokens per workgroup
 #define MF_TILES 4         // 16-token tiles per wave
 #ifndef MF_PIPE
 #define MF_PIPE 0          // 1: matrix products one step ahead of the vector work (needs 32 more registers)
+#endif
+#ifndef MF_BFLY_MFMA
+#define MF_BFLY_MFMA 1     // 1: scale + H_g butterfly on v_mfma_f32_4x4x4_16b_f16, 0: on the vector ALU
 #endif
 #ifndef MF_OCC
 #define MF_OCC 2           // workgroups per compute unit the register budget is set for
@@ -43,6 +47,21 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i& a, const v8i& b, const v4f& c
 }
 __device__ __forceinline__ v4f mfma_fp8_fp4(const v8i& a, const v8i& b, const v4f& c) {
   return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 4, 0, 0, 0, 0);
+}
+
+__device__ __forceinline__ v4h as_v4h(uint32_t a, uint32_t b) {
+  union { uint32_t u[2]; v4h h; } c;
+  c.u[0] = a;
+  c.u[1] = b;
+  return c.h;
+}
+// two floats that are exactly representable in fp16 -> packed pair
+__device__ __forceinline__ uint32_t pk_f16(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+// 16 independent 4x4x4 products: block = lane / 4, A row / B column = lane % 4, result column = lane % 4
+__device__ __forceinline__ v4f mfma_4x4x4(const v4h& a, const v4h& b, const v4f& c) {
+  return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 0, 0, 0);
 }
 
 // two dwords of 2-bit codes -> four dwords of FP4 nibbles (value = code / 2)
@@ -147,6 +166,14 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
     st_s[p] = st.y;
   }
   const float zmask = (n == 0) ? -64.0f : 0.0f;           // H_128 of a constant block lives in channel 0
+#if MF_BFLY_MFMA
+  // row (n & 3) of H_g as fp16 sign masks for the packed scale pairs (blocks 0,1) and (2,3);
+  // rows >= G are zero
+  const int hrow = n & 3;
+  const uint32_t keep_row = hrow < G ? 0xffffffffu : 0u;
+  const uint32_t sm01 = ((__popc(hrow & 1) & 1) ? 0x80000000u : 0u);
+  const uint32_t sm23 = ((__popc(hrow & 2) & 1) ? 0x00008000u : 0u) | ((__popc(hrow & 3) & 1) ? 0x80000000u : 0u);
+#endif
 
   // blockIdx.x = rr * nch8 + chunk, nch8 = chunk count rounded up to 8: the workgroups that serve
   // the `rep` query heads sharing a KV head (GQA) re-read the same chunk, and with ids a multiple of
@@ -227,6 +254,43 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
             sc[r][blk] = s_;
             zc[r][blk] = z_ * zmask;
           }
+#if MF_BFLY_MFMA
+        // The fp16 operand of the 4x4x4 products holds (H_128 c)/2 - 64 z exactly only while that
+        // stays below 1024, i.e. |zero| <= 12 (rotated keys: 0..3).  A tile with a larger zero-point
+        // anywhere (wave-uniform test) keeps the zero-point term out of the matrix products and adds
+        // sum_blk H_g[a][blk] * scale_blk * (-64 z_blk) to channel 0 as the accumulator of the 4x4 product.
+        float zbig = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int blk = 0; blk < G; ++blk) zbig = fmaxf(zbig, fabsf(zc[r][blk]));
+        v4f zcorr[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) zcorr[r] = (v4f){0.f, 0.f, 0.f, 0.f};
+        if (__ballot(zbig > 768.0f) != 0ull) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int a = 0; a < G; ++a) {
+              float acc = 0.f;
+#pragma unroll
+              for (int blk = 0; blk < G; ++blk) acc += ((__popc(a & blk) & 1) ? -1.f : 1.f) * sc[r][blk] * zc[r][blk];
+              zcorr[r][a] = acc;
+            }
+#pragma unroll
+            for (int blk = 0; blk < G; ++blk) zc[r][blk] = 0.f;
+          }
+        }
+        // scale rows of the 4x4 products: (+-s_0, +-s_1, +-s_2, +-s_3) of token 4q + r, signs of H_g row n & 3
+        v4h sA[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t a01 = (__builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x05040100u) ^ sm01) & keep_row;
+          uint32_t a23 = 0;
+          if constexpr (G == 4) a23 = (__builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x05040100u) ^ sm23) & keep_row;
+          sA[r] = as_v4h(a01, a23);
+        }
+#endif
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
 
         float pt[4 * G];                                   // [r][a]
@@ -273,6 +337,20 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             // k^[a] = sum_blk H_g[a][blk] * scale_blk * u_blk   (H_g butterfly over the blocks)
+#if MF_BFLY_MFMA
+            // as 16 independent 4x4x4 products per instruction: block = (token 4q + r, 4 channel
+            // lanes), A row a = signed fp16 scales, B = the four blocks' results (half-integers
+            // below 1024: exact in fp16), fp32 accumulate
+            const v4f z4 = {0.f, 0.f, 0.f, 0.f};
+            v4f klo, khi;
+            if constexpr (G == 4) {
+              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), p == 0 ? zcorr[r] : z4);
+              khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), pk_f16(hi[2][r], hi[3][r])), z4);
+            } else {
+              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), p == 0 ? zcorr[r] : z4);
+              khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), z4);
+            }
+#else
             float klo[G], khi[G];
             if constexpr (G == 4) {
               const float w0 = lo[0][r] * sc[r][0], w1 = lo[1][r] * sc[r][1], w2 = lo[2][r] * sc[r][2], w3 = lo[3][r] * sc[r][3];
@@ -287,6 +365,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
               const float x0 = hi[0][r] * sc[r][0], x1 = hi[1][r] * sc[r][1];
               khi[0] = x0 + x1; khi[1] = x0 - x1;
             }
+#endif
             const float c = cs_c[r][p], s = cs_s[r][p];
 #pragma unroll
             for (int a = 0; a < G; ++a) {

@@ -288,7 +288,8 @@ def test_full_size_config2_sampled():
         O.quantize_append(oc, ks, vs, ms)
         g_codes = O.unpack_canonical(kc_all[b:b + 1, :, 128 * rg:128 * (rg + 1)])
         P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g_codes, ks_all[b:b + 1, :, 4 * rg:4 * rg + 4],
-                        exp["k_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64), f"full-size b={b} rg={rg} K")
+                        exp["k_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64), f"full-size b={b} rg={rg} K",
+                        rot_span=512)
         oc.k_codes = g_codes                                   # attention on the GPU's own codes
         oc.k_scale = ks_all[b:b + 1, :, 4 * rg:4 * rg + 4]
         oc.k_zero = exp["k_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64)
@@ -354,3 +355,34 @@ def test_full_size_config1_shape_without_sinks():
         # the GPU decodes its own codes, the oracle its own: the few codes that differ at rounding
         # ties (see parity_utils) move the output by far less than the tolerance
         assert e <= ATT_TOL and le <= LSE_TOL
+
+
+def test_large_zero_points():
+    """Blocks whose rotated values all sit far from zero get zero-points in the hundreds; the
+    matrix-core kernel must treat them exactly (they do not fit its fp16 operand).  Keys are built
+    from a chosen rotated image: H is its own inverse, so rotating that image gives the keys."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8, n_sinks=0)
+    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=300, max_sinks=0, rot_heads=4, perm_span=128)
+    T = 290
+    rng = np.random.default_rng(77)
+    y = rng.standard_normal((2, T, 1024))
+    offs = rng.choice([0.0, 40.0, -75.0, 300.0], size=(2, T, 8), p=[0.4, 0.2, 0.2, 0.2])
+    y += np.repeat(offs, 128, axis=-1)
+    k = O.rotate_groups(y, 512).reshape(2, T, 8, 128).astype(np.float16)
+    v = (rng.standard_normal((2, T, 8, 128)) + 5.0).astype(np.float16)       # values with an offset too
+    q = S.make_q(w, batch=2)
+    cache = R.RkvCache(cfg)
+    oc = O.cache_new(P.oracle_cfg(cfg))
+    cache.quantize_append(P.gpu(k), P.gpu(v))
+    O.quantize_append(oc, k, v)
+    g = P.export_numpy(cache)
+    # values of magnitude 300 against block ranges of ~6: many more blocks sit inside the (wider) tie windows
+    P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"], "large zero-points K",
+                    rot_span=512, max_ambiguous=0.5)
+    P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], "large zero-points V")
+    assert np.abs(g["k_zero"]).max() > 100
+    oc_g = oracle_from_export(oc, g)
+    check_dequant(cache, oc_g)
+    for path in (1, 2):
+        cache.set_decode_path(path)
+        check_decode(cache, oc_g, q, tag=f"large zero-points path={path}")
