@@ -154,6 +154,14 @@ int rkv_import_codes(rkv_cache* cache, int32_t n_tokens, const uint8_t* dev_k_co
 int rkv_export_sinks(rkv_cache* cache, int32_t* dev_count, int32_t* dev_pos, void* dev_k, void* dev_v,
                      void* stream);
 
+/* Where the physical layout keeps a code (host-only arithmetic, no device access): the index of
+ * the 32-bit word inside the K-code (is_v = 0) or V-code (is_v = 1) region of a cache built from
+ * cfg, and the bit position of the 2-bit code of sequence b, token t, ROTATED channel c (0..E-1,
+ * i.e. before the reorder).  Also returns the number of words of the region in *n_words (may be
+ * NULL).  Used to test that the layout is a bijection. */
+int rkv_layout_locate(const rkv_config* cfg, int32_t is_v, int32_t b, int32_t t, int32_t c,
+                      size_t* word_index, int32_t* bit_shift, size_t* n_words);
+
 const char* rkv_strerror(int code);
 
 #ifdef __cplusplus

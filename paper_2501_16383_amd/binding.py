@@ -20,7 +20,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
     "rkv_calibrate_perm", "rkv_set_perm", "rkv_quantize_append", "rkv_decode_attention",
-    "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks",
+    "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
 
@@ -96,6 +96,7 @@ def load_library():
     lib.rkv_export_codes.argtypes = [vp] * 8
     lib.rkv_import_codes.argtypes = [vp, i32] + [vp] * 7
     lib.rkv_export_sinks.argtypes = [vp] * 6
+    lib.rkv_layout_locate.argtypes = [cfgp, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(i32), C.POINTER(sz)]
     lib.rkv_strerror.argtypes = [C.c_int]
     lib.rkv_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -134,6 +135,15 @@ def query_sizes(cfg: RkvConfig):
     cc = cfg.to_c()
     _check(lib.rkv_query_sizes(C.byref(cc), C.byref(a), C.byref(b)), "rkv_query_sizes")
     return a.value, b.value
+
+
+def layout_locate(cfg: RkvConfig, is_v: bool, b: int, t: int, c: int):
+    """(word index, bit shift, words in the region) of a code in the physical layout (host only)."""
+    lib = load_library()
+    w, sh, n = C.c_size_t(0), C.c_int32(0), C.c_size_t(0)
+    cc = cfg.to_c()
+    _check(lib.rkv_layout_locate(C.byref(cc), int(is_v), b, t, c, C.byref(w), C.byref(sh), C.byref(n)), "rkv_layout_locate")
+    return w.value, sh.value, n.value
 
 
 def calibrate_perm(cfg: RkvConfig, k_cal, scratch=None):

@@ -256,6 +256,27 @@ RKV_EXPORT int rkv_export_sinks(rkv_cache* cache, int32_t* dev_count, int32_t* d
   return RKV_OK;
 }
 
+RKV_EXPORT int rkv_layout_locate(const rkv_config* cfg, int32_t is_v, int32_t b, int32_t t, int32_t c, size_t* word_index,
+                                 int32_t* bit_shift, size_t* n_words) {
+  int rc = check_config(cfg, true);
+  if (rc != RKV_OK) return rc;
+  if (!word_index || !bit_shift) return RKV_EINVAL;
+  Offsets o = plan(cfg);
+  RkvView v{};
+  v.g = cfg->rot_heads;
+  v.n = cfg->rot_heads * RKV_D;
+  v.E = cfg->n_kv_heads * RKV_D;
+  v.NRG = cfg->n_kv_heads / cfg->rot_heads;
+  v.Tpad = o.Tpad;
+  if (b < 0 || b >= cfg->batch || t < 0 || t >= o.Tpad || c < 0 || c >= v.E) return RKV_EINVAL;
+  int sh = 0;
+  const int rg = c / v.n, cc = c % v.n;
+  *word_index = is_v ? rkv_v_dword(v, b, rg, t, cc, sh) : rkv_k_dword(v, b, rg, t, cc, sh);
+  *bit_shift = sh;
+  if (n_words) *n_words = (size_t)cfg->batch * o.Tpad * v.E / 16;
+  return RKV_OK;
+}
+
 RKV_EXPORT const char* rkv_strerror(int code) {
   switch (code) {
     case RKV_OK: return "ok";

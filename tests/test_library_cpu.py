@@ -65,3 +65,31 @@ def test_null_arguments(lib):
     cc = R.RkvConfig(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=16).to_c()
     assert lib.rkv_cache_create(ctypes.byref(cc), None, 1 << 30, None, ctypes.byref(out)) == binding.RKV_EINVAL
     assert lib.rkv_strerror(binding.RKV_EPERM).decode().startswith("reorder")
+
+
+@pytest.mark.parametrize("g,heads,tokens", [(1, 2, 40), (2, 4, 70), (4, 4, 300), (8, 8, 33)])
+def test_physical_layout_is_a_bijection(lib, g, heads, tokens):
+    """Every (sequence, token, rotated channel) owns its own 2 bits inside the K-code and the
+    V-code regions: no two codes share a slot and every slot index is in range."""
+    cfg = R.RkvConfig(batch=2, n_q_heads=heads, n_kv_heads=heads, max_tokens=tokens, rot_heads=g)
+    E = cfg.E
+    for is_v in (False, True):
+        seen = set()
+        n_words = None
+        for b in range(2):
+            for t in list(range(0, tokens, 7)) + [tokens - 1]:
+                for c in range(E):
+                    w, sh, n_words = R.layout_locate(cfg, is_v, b, t, c)
+                    assert 0 <= w < n_words and sh % 2 == 0 and 0 <= sh < 32
+                    key = (w, sh)
+                    assert key not in seen
+                    seen.add(key)
+        # one token's codes of one rotation group fill whole words: 16 codes per word
+        words = {}
+        for c in range(g * 128):
+            w, sh, _ = R.layout_locate(cfg, is_v, 0, 3, c)
+            words.setdefault(w, set()).add(sh)
+        if not is_v:
+            assert all(len(v) == 16 for v in words.values()) and len(words) == g * 128 // 16
+        else:
+            assert all(len(v) == 1 for v in words.values()) and len(words) == g * 128     # token-minor: one word per channel
