@@ -78,9 +78,12 @@ __device__ inline void quant_params(float mn, float mx, float& s, float& zero, f
 }
 // Eq. 6
 __device__ inline uint32_t quant_code(float x, float inv_s, float zero) {
-  float q = rintf(x * inv_s) + zero;
-  q = fminf(fmaxf(q, 0.0f), 3.0f);
-  return (uint32_t)q;
+  // adding 1.5 * 2^23 rounds x * inv_s to an integer (ties to even, as rintf) in the same FMA and
+  // leaves that integer in the low mantissa bits, which saves the float -> int conversion
+  const float magic = 12582912.0f;
+  float q = fmaf(x, inv_s, magic) + zero;
+  q = fminf(fmaxf(q, magic), magic + 3.0f);
+  return __float_as_uint(q) & 3u;
 }
 
 // ---------------------------------------------------------------------------------------------
