@@ -398,8 +398,13 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
     const uint4* vslab = reinterpret_cast<const uint4*>(v.vc + rkv_v_slabbase(v, b, rg, t0 >> 5));
     const int lidx = wave * (16 * G) + (has_head ? lane : 0);
     const int nslab = min(MF_CH / 32, (len - t0 + 31) >> 5);
-    uint4 cur = make_uint4(0, 0, 0, 0);
-    if (has_head && nslab > 0) cur = vslab[lidx];
+    // all V codes of the chunk (one 16-byte load per lane and slab): in flight while the softmax phase runs
+    uint4 vcodes[MF_CH / 32];
+#pragma unroll
+    for (int sl = 0; sl < MF_CH / 32; ++sl) {
+      vcodes[sl] = make_uint4(0, 0, 0, 0);
+      if (has_head && sl < nslab) vcodes[sl] = vslab[(size_t)sl * (64 * G) + lidx];
+    }
     __syncthreads();
 
     // ------------------------------------------------------------------ phase S
@@ -464,37 +469,24 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
       v4f acc[2][2];                                        // [channel tile][digit set]
 #pragma unroll
       for (int i = 0; i < 2; ++i) acc[i][0] = acc[i][1] = (v4f){0.f, 0.f, 0.f, 0.f};
-      uint4 aw[2][2];
 #pragma unroll
-      for (int set = 0; set < 2; ++set) {
-        const uint4* ap = reinterpret_cast<const uint4*>(&s_A[0][set][n][q][0]);
-        aw[set][0] = ap[0];
-        aw[set][1] = ap[1];
-      }
-      for (int sl = 0; sl < nslab; ++sl) {
-        uint4 nxt = make_uint4(0, 0, 0, 0);
-        if (has_head && sl + 1 < nslab) nxt = vslab[(size_t)(sl + 1) * (64 * G) + lidx];
-        v8i A[2];
-#pragma unroll
-        for (int set = 0; set < 2; ++set) {
-          A[set][0] = (int)aw[set][0].x; A[set][1] = (int)aw[set][0].y; A[set][2] = (int)aw[set][0].z; A[set][3] = (int)aw[set][0].w;
-          A[set][4] = (int)aw[set][1].x; A[set][5] = (int)aw[set][1].y; A[set][6] = (int)aw[set][1].z; A[set][7] = (int)aw[set][1].w;
-        }
-        if (sl + 1 < nslab) {
+      for (int sl = 0; sl < MF_CH / 32; ++sl) {
+        if (sl < nslab) {                                   // workgroup-uniform
+          v8i A[2];
 #pragma unroll
           for (int set = 0; set < 2; ++set) {
-            const uint4* ap = reinterpret_cast<const uint4*>(&s_A[sl + 1][set][n][q][0]);
-            aw[set][0] = ap[0];
-            aw[set][1] = ap[1];
+            const uint4* ap = reinterpret_cast<const uint4*>(&s_A[sl][set][n][q][0]);
+            const uint4 a0 = ap[0], a1 = ap[1];
+            A[set][0] = (int)a0.x; A[set][1] = (int)a0.y; A[set][2] = (int)a0.z; A[set][3] = (int)a0.w;
+            A[set][4] = (int)a1.x; A[set][5] = (int)a1.y; A[set][6] = (int)a1.z; A[set][7] = (int)a1.w;
+          }
+          const v8i B0 = unpack_fp4(vcodes[sl].x, vcodes[sl].y), B1 = unpack_fp4(vcodes[sl].z, vcodes[sl].w);
+#pragma unroll
+          for (int set = 0; set < 2; ++set) {
+            acc[0][set] = mfma_fp8_fp4(A[set], B0, acc[0][set]);
+            acc[1][set] = mfma_fp8_fp4(A[set], B1, acc[1][set]);
           }
         }
-        const v8i B0 = unpack_fp4(cur.x, cur.y), B1 = unpack_fp4(cur.z, cur.w);
-#pragma unroll
-        for (int set = 0; set < 2; ++set) {
-          acc[0][set] = mfma_fp8_fp4(A[set], B0, acc[0][set]);
-          acc[1][set] = mfma_fp8_fp4(A[set], B1, acc[1][set]);
-        }
-        cur = nxt;
       }
       if (has_head) {
         const int qh = (rg * G + q) * rep + rr;                // query head served for KV head rg*G + q
