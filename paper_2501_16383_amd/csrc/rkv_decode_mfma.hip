@@ -198,7 +198,6 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 #pragma unroll
   for (int i = 0; i < MF_CH / 64; ++i)
     vmeta[i] = wave < G ? v.vm[((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G + wave] : 0u;
-  __syncthreads();
   {
     // ------------------------------------------------------------------ phase K
     {
@@ -233,6 +232,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         }
       };
       load_tile(0);
+      __syncthreads();        // LDS copies of the Hadamard operand and the query are complete; first tile already in flight
 
 #pragma unroll
       for (int ti = 0; ti < MF_TILES; ++ti) {
