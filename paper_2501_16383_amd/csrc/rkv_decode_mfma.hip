@@ -171,6 +171,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   // rows >= G are zero
   const int hrow = n & 3;
   const uint32_t keep_row = hrow < G ? 0xffffffffu : 0u;
+  const uint32_t lane0_mask = (n == 0) ? 0xffffffffu : 0u;
   const uint32_t sm01 = ((__popc(hrow & 1) & 1) ? 0x80000000u : 0u);
   const uint32_t sm23 = ((__popc(hrow & 2) & 1) ? 0x00008000u : 0u) | ((__popc(hrow & 3) & 1) ? 0x80000000u : 0u);
 #endif
@@ -255,32 +256,6 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
             zc[r][blk] = z_ * zmask;
           }
 #if MF_BFLY_MFMA
-        // The fp16 operand of the 4x4x4 products holds (H_128 c)/2 - 64 z exactly only while that
-        // stays below 1024, i.e. |zero| <= 12 (rotated keys: 0..3).  A tile with a larger zero-point
-        // anywhere (wave-uniform test) keeps the zero-point term out of the matrix products and adds
-        // sum_blk H_g[a][blk] * scale_blk * (-64 z_blk) to channel 0 as the accumulator of the 4x4 product.
-        float zbig = 0.f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-          for (int blk = 0; blk < G; ++blk) zbig = fmaxf(zbig, fabsf(zc[r][blk]));
-        v4f zcorr[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) zcorr[r] = (v4f){0.f, 0.f, 0.f, 0.f};
-        if (__ballot(zbig > 768.0f) != 0ull) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-#pragma unroll
-            for (int a = 0; a < G; ++a) {
-              float acc = 0.f;
-#pragma unroll
-              for (int blk = 0; blk < G; ++blk) acc += ((__popc(a & blk) & 1) ? -1.f : 1.f) * sc[r][blk] * zc[r][blk];
-              zcorr[r][a] = acc;
-            }
-#pragma unroll
-            for (int blk = 0; blk < G; ++blk) zc[r][blk] = 0.f;
-          }
-        }
         // scale rows of the 4x4 products: (+-s_0, +-s_1, +-s_2, +-s_3) of token 4q + r, signs of H_g row n & 3
         v4h sA[4];
 #pragma unroll
@@ -289,6 +264,20 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
           uint32_t a23 = 0;
           if constexpr (G == 4) a23 = (__builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x05040100u) ^ sm23) & keep_row;
           sA[r] = as_v4h(a01, a23);
+        }
+        // zero-points: H_128 of a constant block is 128 z e_0, so they only touch channel 0 (lanes
+        // with n == 0).  sum_blk H_g[a][blk] * scale_blk * z_blk is one more 4x4x4 product (zero-points
+        // are integers up to 2048: exact in fp16); times -64 it becomes the accumulator of the
+        // channel-0 product below.
+        v4f zcorr[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t z01 = __builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x07060302u) & lane0_mask;
+          uint32_t z23 = 0;
+          if constexpr (G == 4) z23 = __builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x07060302u) & lane0_mask;
+          const v4f zz = {0.f, 0.f, 0.f, 0.f};
+          const v4f d = mfma_4x4x4(sA[r], as_v4h(z01, z23), zz);
+          zcorr[r] = d * -64.0f;
         }
 #endif
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
@@ -308,7 +297,9 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 #pragma unroll
           for (int blk = 0; blk < G; ++blk) {
             v4f c0 = {0.f, 0.f, 0.f, 0.f};
+#if !MF_BFLY_MFMA
             if (p == 0) { c0[0] = zc[0][blk]; c0[1] = zc[1][blk]; c0[2] = zc[2][blk]; c0[3] = zc[3][blk]; }
+#endif
             const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
             lo2[buf][blk] = mfma_fp4(A[blk], Hlo, c0);          // (H_128 c_blk - 128 z e_0) / 2, channels 16p + n
             hi2[buf][blk] = mfma_fp4(A[blk], Hhi, zero4);   // channels 16p + n + 64
