@@ -238,6 +238,40 @@ def test_error_codes():
     assert ei.value.code == -5
 
 
+def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag=""):
+    """One (sequence, rotation group of 4 heads) slice of a full-size run against the oracle: a
+    rotation group's codes and attention outputs depend on nothing outside the slice.  The codes
+    must equal the oracle's outside the documented rounding ties; the attention output is then
+    compared on the GPU's own codes, so that a tie cannot hide in (or leak into) the tolerance.
+    exp: export_codes() tensors already on the host (numpy)."""
+    ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=max_sinks)
+    oc = O.cache_new(ocfg, None if perm is None else perm[512 * rg:512 * (rg + 1)] - 512 * rg)
+    O.quantize_append(oc, ks, vs, ms)
+    sl_c, sl_m = slice(128 * rg, 128 * (rg + 1)), slice(4 * rg, 4 * rg + 4)
+    g = {}
+    for name in ("k", "v"):
+        g[name + "_codes"] = O.unpack_canonical(exp[name + "_codes"][b:b + 1, :, sl_c])
+        g[name + "_scale"] = exp[name + "_scale"][b:b + 1, :, sl_m].astype(np.float64)
+        g[name + "_zero"] = exp[name + "_zero"][b:b + 1, :, sl_m].astype(np.float64)
+    P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"],
+                    f"{tag} b={b} rg={rg} K", rot_span=512)
+    P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"],
+                    f"{tag} b={b} rg={rg} V")
+    for name, val in g.items():                                # attention on the GPU's own codes
+        setattr(oc, name, val)
+    ref, lse_ref = O.decode_attention(oc, q[b:b + 1, 4 * rg:4 * rg + 4])
+    e = P.attention_error(out[b:b + 1, 4 * rg:4 * rg + 4], ref)
+    le = float(np.abs(lse[b:b + 1, 4 * rg:4 * rg + 4] - lse_ref).max())
+    print(f"[parity] {tag} b={b} rg={rg}: out err {e:.3e} lse err {le:.3e}", flush=True)
+    assert e <= ATT_TOL and le <= LSE_TOL
+
+
+def export_host(cache):
+    exp = cache.export_codes()
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in exp.items()}
+
+
 def test_full_size_config2_sampled():
     """BASELINE configuration 2 at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, one single-token append, decode on
@@ -273,34 +307,14 @@ def test_full_size_config2_sampled():
     cache.quantize_append(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), mask[:, T - 1:].contiguous())
     cache.set_decode_path(2)
     out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
-    exp = cache.export_codes()
-    torch.cuda.synchronize()
+    exp = export_host(cache)
     assert cache.length == T
     out = out.cpu().numpy().astype(np.float64)
     lse = lse.cpu().numpy().astype(np.float64)
-    kc_all = exp["k_codes"].cpu().numpy()
-    ks_all = exp["k_scale"].cpu().numpy().astype(np.float64)
     assert np.isfinite(out).all()
     for (b, rg) in samples:
         ks, vs, ms = keep[(b, rg)]
-        ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=4)
-        oc = O.cache_new(ocfg, perm[512 * rg:512 * (rg + 1)] - 512 * rg)
-        O.quantize_append(oc, ks, vs, ms)
-        g_codes = O.unpack_canonical(kc_all[b:b + 1, :, 128 * rg:128 * (rg + 1)])
-        P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g_codes, ks_all[b:b + 1, :, 4 * rg:4 * rg + 4],
-                        exp["k_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64), f"full-size b={b} rg={rg} K",
-                        rot_span=512)
-        oc.k_codes = g_codes                                   # attention on the GPU's own codes
-        oc.k_scale = ks_all[b:b + 1, :, 4 * rg:4 * rg + 4]
-        oc.k_zero = exp["k_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64)
-        oc.v_codes = O.unpack_canonical(exp["v_codes"][b:b + 1, :, 128 * rg:128 * (rg + 1)].cpu().numpy())
-        oc.v_scale = exp["v_scale"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64)
-        oc.v_zero = exp["v_zero"][b:b + 1, :, 4 * rg:4 * rg + 4].cpu().numpy().astype(np.float64)
-        ref, lse_ref = O.decode_attention(oc, q[b:b + 1, 4 * rg:4 * rg + 4])
-        e = P.attention_error(out[b:b + 1, 4 * rg:4 * rg + 4], ref)
-        le = float(np.abs(lse[b:b + 1, 4 * rg:4 * rg + 4] - lse_ref).max())
-        print(f"[parity] full-size b={b} rg={rg}: out err {e:.3e} lse err {le:.3e}", flush=True)
-        assert e <= ATT_TOL and le <= LSE_TOL
+        check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag="full-size")
 
 
 def test_full_size_long_context_sampled():
@@ -315,17 +329,11 @@ def test_full_size_long_context_sampled():
     print("[case] long context: bulk append 32768 + decode", flush=True)
     cache.quantize_append(P.gpu(k), P.gpu(v), P.gpu(mask))
     out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
-    torch.cuda.synchronize()
+    exp = export_host(cache)
     out = out.cpu().numpy().astype(np.float64)
+    lse = lse.cpu().numpy().astype(np.float64)
     rg = 5
-    ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=4)
-    oc = O.cache_new(ocfg)
-    O.quantize_append(oc, k[:, :, 4 * rg:4 * rg + 4], v[:, :, 4 * rg:4 * rg + 4], mask)
-    ref, lse_ref = O.decode_attention(oc, q[:, 4 * rg:4 * rg + 4])
-    e = P.attention_error(out[:, 4 * rg:4 * rg + 4], ref)
-    le = float(np.abs(lse.cpu().numpy()[:, 4 * rg:4 * rg + 4] - lse_ref).max())
-    print(f"[parity] long context rg={rg}: out err {e:.3e} lse err {le:.3e}", flush=True)
-    assert e <= ATT_TOL and le <= LSE_TOL
+    check_slice(exp, out, lse, 0, rg, k[:, :, 4 * rg:4 * rg + 4], v[:, :, 4 * rg:4 * rg + 4], mask, q, tag="long context")
 
 
 def test_full_size_config1_shape_without_sinks():
@@ -341,20 +349,12 @@ def test_full_size_config1_shape_without_sinks():
     cache.quantize_append(P.gpu(k), P.gpu(v))
     cache.set_decode_path(2)
     out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
-    torch.cuda.synchronize()
+    exp = export_host(cache)
     out = out.cpu().numpy().astype(np.float64)
     lse = lse.cpu().numpy().astype(np.float64)
     for (b, rg) in [(0, 0), (3, 5), (7, 7)]:
-        ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=0)
-        oc = O.cache_new(ocfg)
-        O.quantize_append(oc, k[b:b + 1, :, 4 * rg:4 * rg + 4], v[b:b + 1, :, 4 * rg:4 * rg + 4])
-        ref, lse_ref = O.decode_attention(oc, q[b:b + 1, 4 * rg:4 * rg + 4])
-        e = P.attention_error(out[b:b + 1, 4 * rg:4 * rg + 4], ref)
-        le = float(np.abs(lse[b:b + 1, 4 * rg:4 * rg + 4] - lse_ref).max())
-        print(f"[parity] config 1 shape b={b} rg={rg}: out err {e:.3e} lse err {le:.3e}", flush=True)
-        # the GPU decodes its own codes, the oracle its own: the few codes that differ at rounding
-        # ties (see parity_utils) move the output by far less than the tolerance
-        assert e <= ATT_TOL and le <= LSE_TOL
+        check_slice(exp, out, lse, b, rg, k[b:b + 1, :, 4 * rg:4 * rg + 4], v[b:b + 1, :, 4 * rg:4 * rg + 4], None, q,
+                    max_sinks=0, tag="config 1 shape")
 
 
 def test_large_zero_points():
