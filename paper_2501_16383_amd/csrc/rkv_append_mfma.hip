@@ -1,0 +1,335 @@
+// Write half, matrix-core kernel for gfx950: quantize-append for reorders that keep the 128-blocks
+// of the rotated row (gid[c] == c/128), rot_heads 2 or 4, values quantized as given (v_rotate = 0).
+//
+// The grouped-head rotation of Sec. 4.2 is H_n = H_g (x) H_128 (Eq. 10).  The per-head factor H_128
+// is a dense product of the fp16 keys with a +-1 matrix and runs on v_mfma_f32_16x16x32_f16: the
+// products are exact, the accumulation is fp32 (measured: as accurate as a sequential fp32 sum).
+// The operand roles are chosen so that the result lands in the physical K layout with no
+// transpose: A = 16 rows of H_128, B = the keys of 16 tokens, so lane (token, q) of the result
+// holds rows 4q..4q+3; the 16 rows of product p are channels 32q + 8(p>>1) + 4(p&1) + r, which makes
+// the 32 channels a lane collects over 8 products exactly the 32 codes of its 16-byte piece of the
+// K tile.  The H_g factor is a 2- or 4-point butterfly over the heads inside the lane; Eq. 6-9
+// follow in registers.  Values take the vector path: lane = 2g consecutive channels of a token.
+//
+// One workgroup = (sequence, rotation group, slab of 32 token slots) so that every V dword (16
+// tokens of one channel), every K tile and every metadata row it touches is written whole.
+//   keys    wave w: K tile w>>1 of the slab (16 tokens), dword d = w&1 of every 16-byte piece
+//           (channels with bit 4 of the in-block index equal to d): 4 products per head, K = 128.
+//   values  wave w: tokens 8w..8w+7, one at a time.
+#include "rkv_internal.h"
+#include "rkv_quant.h"
+
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v8h as_v8h(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  union { uint32_t u[4]; v8h h; } x;
+  x.u[0] = a; x.u[1] = b; x.u[2] = c; x.u[3] = d;
+  return x.h;
+}
+__device__ __forceinline__ uint32_t parity_mask(int x, uint32_t m) { return (__popc(x) & 1) ? m : 0u; }
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ uint32_t as_u32(h2 h) { return __builtin_bit_cast(uint32_t, h); }
+// packed fp16 min / max as single instructions (the builtin forms add a canonicalizing instruction
+// per operand, which costs as much as the operation itself)
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, true);
+}
+
+// Eq. 8-9 for one block given its min and max, as quant_params but without IEEE divisions: the
+// division by 3 is a multiplication (error below 1.5 ulp of fp32, which can change the fp16 scale
+// only within 2^-23 of a rounding boundary) and the reciprocal of the scale is v_rcp_f32 refined by
+// one Newton step.
+__device__ __forceinline__ void quant_params_nodiv(float mn, float mx, float& s, float& zero, float& inv_s) {
+  const float raw = (mx - mn) * 0.33333334f;
+  s = __half2float(__float2half_rn(raw));
+  if (!(s <= 65504.0f)) s = 65504.0f;
+  if (s == 0.0f) {
+    s = __half2float(__float2half_rn(fabsf(mn)));
+    if (!(s <= 65504.0f)) s = 65504.0f;
+    if (s == 0.0f) s = 1.0f;
+  }
+  const float r0 = __builtin_amdgcn_rcpf(s);
+  inv_s = fmaf(fmaf(-s, r0, 1.0f), r0, r0);
+  zero = -rintf(mn * inv_s);
+  zero = fminf(fmaxf(zero, -2048.0f), 2048.0f);
+}
+
+template <int G>
+__global__ void __launch_bounds__(256) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+                                                     int n_new, int slab0) {
+  constexpr int PL = 2 * G;                    // value channels per lane
+  constexpr int LPB = 128 / PL;                // lanes per 128-block in the value phase
+  __shared__ uint32_t imgK[2 * 128 * G];       // two K tiles
+  __shared__ uint32_t imgV[4][64 * PL];        // per wave: partial V dwords of its 8 tokens, [i][lane]
+  __shared__ uint32_t metaK[32 * G], metaV[32 * G];
+  __shared__ float2 s_mm[2][2][16][G];         // [tile][dword half][token][head] (min, max) of half a block
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int slab = slab0 + blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
+  constexpr int n = 128 * G;
+  const int t_lo = v.len, t_hi = v.len + n_new;
+  const int ts = slab * 32;
+
+  // slots of this slab that belong to tokens outside this call are kept
+  uint32_t keep[2] = {0, 0};
+  for (int tau = 0; tau < 32; ++tau) {
+    const int t = ts + tau;
+    if (!(t >= t_lo && t < t_hi)) keep[tau >> 4] |= 3u << rkv_v_shift(tau);
+  }
+  const size_t vbase = rkv_v_slabbase(v, b, rg, slab);
+  uint32_t oldv[G];
+#pragma unroll
+  for (int k = 0; k < G; ++k) oldv[k] = 0;
+  if (keep[0] | keep[1]) {
+#pragma unroll
+    for (int k = 0; k < G; ++k) oldv[k] = v.vc[vbase + tid + 256 * k];
+  }
+  const float rs = rsqrtf((float)n);
+  const int tau_first = max(0, t_lo - ts), tau_last = min(31, t_hi - 1 - ts);
+
+  // every global load of the workgroup is issued here, before any arithmetic: the keys of this
+  // wave's tile (matrix operands), then the value rows of its 8 tokens
+  const int ti = wave >> 1, d = wave & 1;
+  const int col = lane & 15, q = lane >> 4;                // key result: token `col` of the tile, rows 4q..4q+3
+  const bool tile_on = (ts + 16 * ti < t_hi) && (ts + 16 * ti + 16 > t_lo);   // wave-uniform
+  uint4 xb[G][4];                                          // lane (token col, k-group q): keys 32ks + 8q .. +7 of head h
+  {
+    const int t = ts + 16 * ti + col;
+    const bool valid = t >= t_lo && t < t_hi;
+    const uint4* rowp = reinterpret_cast<const uint4*>(kin + ((size_t)b * n_new + (valid ? t - t_lo : 0)) * v.E + (size_t)rg * n + 8 * q);
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) xb[h][ks] = (tile_on && valid) ? rowp[16 * h + 4 * ks] : make_uint4(0, 0, 0, 0);
+  }
+  uint32_t vraw[8][PL / 2];                                // value rows: lane = PL consecutive channels
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int tau = 8 * wave + k;
+    const bool ok = tau >= tau_first && tau <= tau_last;
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(vin + ((size_t)b * n_new + (ok ? ts + tau - t_lo : 0)) * v.E + (size_t)rg * n + PL * lane);
+    if constexpr (PL == 8) {
+      const uint4 u = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+      vraw[k][0] = u.x; vraw[k][1] = u.y; vraw[k][2] = u.z; vraw[k][3] = u.w;
+    } else {
+      const uint2 u = ok ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
+      vraw[k][0] = u.x; vraw[k][1] = u.y;
+    }
+  }
+
+  // ------------------------------------------------------------------ keys
+  {
+    v4f acc[G][4];
+    if (tile_on) {
+      // A operands: lane (row m = lane & 15, k-group kg = lane >> 4) holds H_128[channel][32ks + 8kg + i],
+      // channel = 32(m>>2) + 8(2d + (pp>>1)) + 4(pp&1) + (m&3); the sign is the parity of (channel & k),
+      // which splits into (e & i), (v & kg) and ((m>>2) & ks)
+      const int m = lane & 15, kg = lane >> 4, r = m & 3, qa = m >> 2;
+      uint32_t base[2][4];
+#pragma unroll
+      for (int eb = 0; eb < 2; ++eb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int e = 4 * eb + r;
+          base[eb][j] = (0x3C003C00u ^ parity_mask(e & (2 * j), 0x00008000u)) ^ parity_mask(e & (2 * j + 1), 0x80000000u);
+        }
+      uint32_t maskv[2], maskq[4];
+#pragma unroll
+      for (int vb = 0; vb < 2; ++vb) maskv[vb] = parity_mask((2 * d + vb) & kg, 0x80008000u);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) maskq[ks] = parity_mask(qa & ks, 0x80008000u);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int pp = 0; pp < 4; ++pp) {
+          const uint32_t mk = maskv[pp >> 1] ^ maskq[ks];
+          const v8h a = as_v8h(base[pp & 1][0] ^ mk, base[pp & 1][1] ^ mk, base[pp & 1][2] ^ mk, base[pp & 1][3] ^ mk);
+#pragma unroll
+          for (int h = 0; h < G; ++h) {
+            const v8h x = as_v8h(xb[h][ks].x, xb[h][ks].y, xb[h][ks].z, xb[h][ks].w);
+            const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+            acc[h][pp] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, x, ks == 0 ? zero4 : acc[h][pp], 0, 0, 0);
+          }
+        }
+      // H_g over the heads (Sylvester order: the head index is the high part of the rotated channel)
+#pragma unroll
+      for (int pp = 0; pp < 4; ++pp)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          if constexpr (G == 4) {
+            const float x0 = acc[0][pp][rr], x1 = acc[1][pp][rr], x2 = acc[2][pp][rr], x3 = acc[3][pp][rr];
+            const float a0 = x0 + x1, a1 = x0 - x1, a2 = x2 + x3, a3 = x2 - x3;
+            acc[0][pp][rr] = a0 + a2; acc[1][pp][rr] = a1 + a3; acc[2][pp][rr] = a0 - a2; acc[3][pp][rr] = a1 - a3;
+          } else {
+            const float x0 = acc[0][pp][rr], x1 = acc[1][pp][rr];
+            acc[0][pp][rr] = x0 + x1; acc[1][pp][rr] = x0 - x1;
+          }
+        }
+      // min / max of this wave's half of every block: 16 values in the lane, then the four q groups
+#pragma unroll
+      for (int a = 0; a < G; ++a) {
+        float mn = acc[a][0][0], mx = mn;
+#pragma unroll
+        for (int pp = 0; pp < 4; ++pp)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            mn = fminf(mn, acc[a][pp][rr]);
+            mx = fmaxf(mx, acc[a][pp][rr]);
+          }
+        mn = fminf(mn, __shfl_xor(mn, 16)); mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mn = fminf(mn, __shfl_xor(mn, 32)); mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (q == 0) s_mm[ti][d][col][a] = make_float2(mn, mx);
+      }
+    }
+    __syncthreads();
+    if (tile_on) {
+      // Eq. 6-9 on y = (raw rotation) / sqrt(n): min and max scale exactly (rounding is monotone),
+      // the elements take the factor inside the reciprocal scale.  Lane group q works out the
+      // parameters of head q & (G-1) for its token; the others fetch them with lane exchanges.
+      constexpr uint32_t kBias = 0x4B400000u * 0x55555555u;    // what the float bit patterns add up to, mod 2^32
+      const int ah = q & (G - 1);
+      const float2 m0 = s_mm[ti][0][col][ah], m1 = s_mm[ti][1][col][ah];
+      float sc, zero_h, inv;
+      quant_params_nodiv(fminf(m0.x, m1.x) * rs, fmaxf(m0.y, m1.y) * rs, sc, zero_h, inv);
+      const float inv2_h = inv * rs;
+      if (d == 0 && q < G) metaK[(16 * ti + col) * G + ah] = rkv_pack_meta(sc, zero_h);
+      const float magic = 12582912.0f;
+#pragma unroll
+      for (int a = 0; a < G; ++a) {
+        const float inv2 = __shfl(inv2_h, col + 16 * a), zero = __shfl(zero_h, col + 16 * a);
+        uint32_t word = 0;
+#pragma unroll
+        for (int pp = 0; pp < 4; ++pp)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            float c = fmaf(acc[a][pp][rr], inv2, magic) + zero;
+            c = fminf(fmaxf(c, magic), magic + 3.0f);
+            word += __float_as_uint(c) << (16 * (pp & 1) + 4 * rr + 2 * (pp >> 1));
+          }
+        imgK[ti * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = word - kBias;
+      }
+    }
+  }
+
+  // ------------------------------------------------------------------ values
+  // min and max of a block travel together as one packed pair (min, -max), so that one packed
+  // fp16 minimum per step reduces both (fp16 min/max of fp16 inputs is exact)
+  const int blk = lane / LPB;                              // 128-block (= KV head) of this lane's channels
+  uint32_t mm[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    uint32_t lo = vraw[k][0], hi = vraw[k][0];
+#pragma unroll
+    for (int i = 1; i < PL / 2; ++i) {
+      lo = pk_min(lo, vraw[k][i]);
+      hi = pk_max(hi, vraw[k][i]);
+    }
+    lo = pk_min(lo, __builtin_amdgcn_perm(lo, lo, 0x01000302u));          // both halves = min of the lane's channels
+    hi = pk_max(hi, __builtin_amdgcn_perm(hi, hi, 0x01000302u));
+    uint32_t p = __builtin_amdgcn_perm(hi, lo, 0x05040100u) ^ 0x80000000u;   // (min, -max)
+    p = pk_min(p, dpp_u<0xB1>(p));                                        // quad_perm [1,0,3,2]
+    p = pk_min(p, dpp_u<0x4E>(p));                                        // quad_perm [2,3,0,1]
+    p = pk_min(p, dpp_u<0x141>(p));                                       // row_half_mirror
+    p = pk_min(p, dpp_u<0x140>(p));                                       // row_mirror
+    if constexpr (LPB == 32) p = pk_min(p, (uint32_t)__shfl_xor((int)p, 16));
+    mm[k] = p;
+  }
+  // lane k of every block works out the parameters of token 8 wave + k; the others fetch them
+  uint32_t mine = mm[0];
+#pragma unroll
+  for (int k = 1; k < 8; ++k) mine = ((lane & (LPB - 1)) == k) ? mm[k] : mine;
+  float sc_v, zero_v, inv_v;
+  {
+    const h2 pr = as_h2(mine);
+    quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v);
+    const int tau = 8 * wave + (lane & (LPB - 1));
+    if ((lane & (LPB - 1)) < 8) metaV[tau * G + blk] = rkv_pack_meta(sc_v, zero_v);
+  }
+  uint32_t vword[PL];
+#pragma unroll
+  for (int i = 0; i < PL; ++i) vword[i] = 0;
+  uint32_t bias = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int tau = 8 * wave + k;
+    if (tau < tau_first || tau > tau_last) continue;       // wave-uniform
+    const int src = (lane & ~(LPB - 1)) | k;
+    const float inv = __shfl(inv_v, src), zero = __shfl(zero_v, src);
+    const int sh = rkv_v_shift(tau);
+    const float magic = 12582912.0f;
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      const h2 pr = as_h2(vraw[k][i >> 1]);
+      float c = fmaf((float)pr[i & 1], inv, magic) + zero;
+      c = fminf(fmaxf(c, magic), magic + 3.0f);
+      vword[i] += __float_as_uint(c) << sh;
+    }
+    bias += 0x4B400000u << sh;
+  }
+#pragma unroll
+  for (int i = 0; i < PL; ++i) vword[i] -= bias;
+#pragma unroll
+  for (int i = 0; i < PL; ++i) imgV[wave][i * 64 + lane] = vword[i];
+  __syncthreads();
+
+  // ---- K tiles: every 16-byte piece belongs to one token
+#pragma unroll
+  for (int k = 0; k < G; ++k) {
+    const int idx = tid + 256 * k;                          // 0 .. 256G-1
+    const int ti = idx / (128 * G), off = idx - ti * (128 * G);
+    const int t = ts + ti * 16 + rkv_k_tile_token(G, off);
+    if (t >= t_lo && t < t_hi) v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off] = imgK[idx];
+  }
+  // ---- V slab: dword idx = (((w*G + hh)*16 + nn)*2 + ct)*2 + d, channel c = 128hh + 32w + 16ct + nn;
+  //      waves 2d and 2d+1 hold the two halves of its 16 token slots
+#pragma unroll
+  for (int k = 0; k < G; ++k) {
+    const int idx = tid + 256 * k;
+    const int d = idx & 1, ct = (idx >> 1) & 1, nn = (idx >> 2) & 15, rest = idx >> 6;
+    const int hh = rest % G, w = rest / G;
+    const int c = 128 * hh + 32 * w + 16 * ct + nn;
+    const int ln = c / PL, i = c - ln * PL;
+    uint32_t word = imgV[2 * d][i * 64 + ln] | imgV[2 * d + 1][i * 64 + ln];
+    if (keep[d]) word |= oldv[k] & keep[d];
+    if (keep[d] != 0xffffffffu) v.vc[vbase + idx] = word;
+  }
+  // ---- metadata rows of the tokens written
+  for (int i = tid; i < 32 * G; i += 256) {
+    const int tau = i / G;
+    if (tau >= tau_first && tau <= tau_last) {
+      const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + ts + tau) * G + (i - tau * G);
+      v.km[mi] = metaK[i];
+      v.vm[mi] = metaV[i];
+    }
+  }
+}
+
+bool rkv_append_mfma_supported(const rkv_cache* c) {
+  const RkvView& v = c->v;
+  return c->blocks_aligned && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
+}
+
+int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int n_new, hipStream_t s) {
+  const RkvView& v = c->v;
+  if (!rkv_append_mfma_supported(c)) return RKV_EINVAL;
+  const int slab0 = v.len >> 5, slab1 = (v.len + n_new - 1) >> 5;
+  dim3 grid(slab1 - slab0 + 1, v.NRG, v.B);
+  if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
+  if (v.g == 4) hipLaunchKernelGGL(k_append_mfma<4>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  else hipLaunchKernelGGL(k_append_mfma<2>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
+  return rkv_check_launch();
+}

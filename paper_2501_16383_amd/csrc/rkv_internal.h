@@ -114,6 +114,8 @@ __device__ inline void rkv_unpack_meta(uint32_t u, float& scale, float& zero) {
 int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s);
 int rkv_launch_set_perm_tables(rkv_cache* c, hipStream_t s);
 int rkv_launch_append(rkv_cache* c, const __half* k, const __half* v, int n_new, const uint8_t* mask, hipStream_t s);
+bool rkv_append_mfma_supported(const rkv_cache* c);
+int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* v, int n_new, hipStream_t s);
 int rkv_launch_dequant(rkv_cache* c, float* k_hat, float* v_hat, hipStream_t s);
 int rkv_launch_export(rkv_cache* c, uint8_t* kc, float* ks, float* kz, uint8_t* vc, float* vs, float* vz, hipStream_t s);
 int rkv_launch_import(rkv_cache* c, int T, const uint8_t* kc, const float* ks, const float* kz, const uint8_t* vc,

@@ -1,6 +1,7 @@
 // Write half (rotate, reorder, quantize, pack, sinks), calibration, and the exact views of the
 // cache used by tests (dequantize, export, import).
 #include "rkv_internal.h"
+#include "rkv_quant.h"
 
 // ---------------------------------------------------------------------------------------------
 // small device helpers
@@ -32,58 +33,6 @@ __device__ inline void fwht_lanes(T (&x)[PL], int lane, int xstages) {
       x[i] = sgn * x[i] + o;
     }
   }
-}
-
-template <int PL>
-__device__ inline void load_halves(const __half* p, float (&x)[PL]) {
-  if constexpr (PL >= 8) {
-#pragma unroll
-    for (int k = 0; k < PL / 8; ++k) {
-      uint4 u = reinterpret_cast<const uint4*>(p)[k];
-      const __half2* h = reinterpret_cast<const __half2*>(&u);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float2 f = __half22float2(h[i]);
-        x[8 * k + 2 * i] = f.x;
-        x[8 * k + 2 * i + 1] = f.y;
-      }
-    }
-  } else if constexpr (PL == 4) {
-    uint2 u = *reinterpret_cast<const uint2*>(p);
-    const __half2* h = reinterpret_cast<const __half2*>(&u);
-    float2 f0 = __half22float2(h[0]), f1 = __half22float2(h[1]);
-    x[0] = f0.x; x[1] = f0.y; x[2] = f1.x; x[3] = f1.y;
-  } else {
-    uint32_t u = *reinterpret_cast<const uint32_t*>(p);
-    float2 f = __half22float2(*reinterpret_cast<const __half2*>(&u));
-    x[0] = f.x; x[1] = f.y;
-  }
-}
-
-// Eq. 8-9 for one block of 128 given its min and max: fp16 scale actually stored, integer zero,
-// and the reciprocal of the scale (one IEEE division per block; elements multiply by it, which
-// differs from x / s only within ~1.5 ulp, far inside the rounding-tie window of the parity tests).
-__device__ inline void quant_params(float mn, float mx, float& s, float& zero, float& inv_s) {
-  float raw = (mx - mn) / 3.0f;
-  s = __half2float(__float2half_rn(raw));
-  if (!(s <= 65504.0f)) s = 65504.0f;
-  if (s == 0.0f) {
-    s = __half2float(__float2half_rn(fabsf(mn)));
-    if (!(s <= 65504.0f)) s = 65504.0f;
-    if (s == 0.0f) s = 1.0f;
-  }
-  inv_s = 1.0f / s;
-  zero = -rintf(mn * inv_s);
-  zero = fminf(fmaxf(zero, -2048.0f), 2048.0f);
-}
-// Eq. 6
-__device__ inline uint32_t quant_code(float x, float inv_s, float zero) {
-  // adding 1.5 * 2^23 rounds x * inv_s to an integer (ties to even, as rintf) in the same FMA and
-  // leaves that integer in the low mantissa bits, which saves the float -> int conversion
-  const float magic = 12582912.0f;
-  float q = fmaf(x, inv_s, magic) + zero;
-  q = fminf(fmaxf(q, magic), magic + 3.0f);
-  return __float_as_uint(q) & 3u;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -500,6 +449,7 @@ __global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __
 int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new, const uint8_t* mask, hipStream_t s) {
   const RkvView& v = c->v;
   if (mask && v.max_sinks > 0) hipLaunchKernelGGL(k_sinks, dim3(v.B), dim3(256), 0, s, v, k, vv, mask, n_new);
+  if (rkv_append_mfma_supported(c)) return rkv_launch_append_mfma(c, k, vv, n_new, s);
   if (c->blocks_aligned && (v.g == 2 || v.g == 4)) {
     const int slab0 = v.len >> 5, slab1 = (v.len + n_new - 1) >> 5;
     dim3 grid(slab1 - slab0 + 1, v.NRG, v.B);
