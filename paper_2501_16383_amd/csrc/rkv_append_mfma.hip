@@ -11,11 +11,13 @@
 // K tile.  The H_g factor is a 2- or 4-point butterfly over the heads inside the lane; Eq. 6-9
 // follow in registers.  Values take the vector path: lane = 2g consecutive channels of a token.
 //
-// One workgroup = (sequence, rotation group, slab of 32 token slots) so that every V dword (16
-// tokens of one channel), every K tile and every metadata row it touches is written whole.
+// One workgroup = (sequence, rotation group, slab of 32 token slots, role) so that every V dword
+// (16 tokens of one channel), every K tile and every metadata row it touches is written whole.
+// Even workgroups take the keys of a slab, odd ones its values, so that matrix-heavy and
+// load-heavy workgroups share a compute unit and each kind only holds its own operands.
 //   keys    wave w: K tile w>>1 of the slab (16 tokens), dword d = w&1 of every 16-byte piece
 //           (channels with bit 4 of the in-block index equal to d): 4 products per head, K = 128.
-//   values  wave w: tokens 8w..8w+7, one at a time.
+//   values  wave w: tokens 8w..8w+7.
 #include "rkv_internal.h"
 #include "rkv_quant.h"
 
@@ -69,71 +71,54 @@ __device__ __forceinline__ void quant_params_nodiv(float mn, float mx, float& s,
 }
 
 template <int G>
-__global__ void __launch_bounds__(256) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+__global__ void __launch_bounds__(256, 3) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                      int n_new, int slab0) {
   constexpr int PL = 2 * G;                    // value channels per lane
-  constexpr int LPB = 128 / PL;                // lanes per 128-block in the value phase
-  __shared__ uint32_t imgK[2 * 128 * G];       // two K tiles
-  __shared__ uint32_t imgV[4][64 * PL];        // per wave: partial V dwords of its 8 tokens, [i][lane]
-  __shared__ uint32_t metaK[32 * G], metaV[32 * G];
+  constexpr int LPB = 128 / PL;                // lanes per 128-block in the value role
+  constexpr int n = 128 * G;
+  constexpr int ROW16 = 16 * G;                // 16-byte pieces per token row of the rotation group
+  constexpr int STRIDE16 = ROW16 + 1;          // padded row: the matrix operand reads then touch every LDS bank once
+  // key role: the slab's fp16 keys, [32 tokens][STRIDE16] pieces, later overwritten by the two K tiles
+  // (2 x 128 G dwords); value role: per wave the partial V dwords of its 8 tokens, [wave][i][lane]
+  __shared__ __attribute__((aligned(16))) uint32_t lds[32 * STRIDE16 * 4];
+  uint32_t* img = lds;
+  __shared__ uint32_t meta[32 * G];
   __shared__ float2 s_mm[2][2][16][G];         // [tile][dword half][token][head] (min, max) of half a block
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int slab = slab0 + blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
-  constexpr int n = 128 * G;
+  const int role = blockIdx.x & 1;             // even workgroups take the keys of a slab, odd ones its values
+  const int slab = slab0 + (blockIdx.x >> 1), rg = blockIdx.y, b = blockIdx.z;
   const int t_lo = v.len, t_hi = v.len + n_new;
   const int ts = slab * 32;
-
-  // slots of this slab that belong to tokens outside this call are kept
-  uint32_t keep[2] = {0, 0};
-  for (int tau = 0; tau < 32; ++tau) {
-    const int t = ts + tau;
-    if (!(t >= t_lo && t < t_hi)) keep[tau >> 4] |= 3u << rkv_v_shift(tau);
-  }
-  const size_t vbase = rkv_v_slabbase(v, b, rg, slab);
-  uint32_t oldv[G];
-#pragma unroll
-  for (int k = 0; k < G; ++k) oldv[k] = 0;
-  if (keep[0] | keep[1]) {
-#pragma unroll
-    for (int k = 0; k < G; ++k) oldv[k] = v.vc[vbase + tid + 256 * k];
-  }
-  const float rs = rsqrtf((float)n);
   const int tau_first = max(0, t_lo - ts), tau_last = min(31, t_hi - 1 - ts);
+  const size_t mrow = ((size_t)(b * v.NRG + rg) * v.Tpad + ts) * G;     // metadata row of the slab's first token
 
-  // every global load of the workgroup is issued here, before any arithmetic: the keys of this
-  // wave's tile (matrix operands), then the value rows of its 8 tokens
-  const int ti = wave >> 1, d = wave & 1;
-  const int col = lane & 15, q = lane >> 4;                // key result: token `col` of the tile, rows 4q..4q+3
-  const bool tile_on = (ts + 16 * ti < t_hi) && (ts + 16 * ti + 16 > t_lo);   // wave-uniform
-  uint4 xb[G][4];                                          // lane (token col, k-group q): keys 32ks + 8q .. +7 of head h
-  {
-    const int t = ts + 16 * ti + col;
-    const bool valid = t >= t_lo && t < t_hi;
-    const uint4* rowp = reinterpret_cast<const uint4*>(kin + ((size_t)b * n_new + (valid ? t - t_lo : 0)) * v.E + (size_t)rg * n + 8 * q);
+  if (role == 0) {
+    // ================================================================== keys
+    const int ti = wave >> 1, d = wave & 1;
+    const int col = lane & 15, q = lane >> 4;              // result: token `col` of the tile, rows 4q..4q+3
+    const bool tile_on = (ts + 16 * ti < t_hi) && (ts + 16 * ti + 16 > t_lo);   // wave-uniform
+    const float rs = rsqrtf((float)n);
+    // the slab's keys go to LDS once, whole rows at a time (wave w: tokens 8w..8w+7)
+    {
+      constexpr int TPI = 64 / ROW16;                      // token rows per wave-wide 16-byte load
+      uint4 st[8 / TPI];
 #pragma unroll
-    for (int h = 0; h < G; ++h)
+      for (int k = 0; k < 8 / TPI; ++k) {
+        const int tau = 8 * wave + TPI * k + lane / ROW16;
+        const bool ok = tau >= tau_first && tau <= tau_last;
+        const uint4* rowp = reinterpret_cast<const uint4*>(kin + ((size_t)b * n_new + (ok ? ts + tau - t_lo : 0)) * v.E + (size_t)rg * n);
+        st[k] = ok ? rowp[lane % ROW16] : make_uint4(0, 0, 0, 0);
+      }
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) xb[h][ks] = (tile_on && valid) ? rowp[16 * h + 4 * ks] : make_uint4(0, 0, 0, 0);
-  }
-  uint32_t vraw[8][PL / 2];                                // value rows: lane = PL consecutive channels
-#pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const int tau = 8 * wave + k;
-    const bool ok = tau >= tau_first && tau <= tau_last;
-    const uint32_t* p = reinterpret_cast<const uint32_t*>(vin + ((size_t)b * n_new + (ok ? ts + tau - t_lo : 0)) * v.E + (size_t)rg * n + PL * lane);
-    if constexpr (PL == 8) {
-      const uint4 u = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
-      vraw[k][0] = u.x; vraw[k][1] = u.y; vraw[k][2] = u.z; vraw[k][3] = u.w;
-    } else {
-      const uint2 u = ok ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
-      vraw[k][0] = u.x; vraw[k][1] = u.y;
+      for (int k = 0; k < 8 / TPI; ++k) {
+        const int tau = 8 * wave + TPI * k + lane / ROW16;
+        reinterpret_cast<uint4*>(lds)[tau * STRIDE16 + lane % ROW16] = st[k];
+      }
     }
-  }
-
-  // ------------------------------------------------------------------ keys
-  {
+    __syncthreads();
     v4f acc[G][4];
     if (tile_on) {
+      const uint4* xrow = reinterpret_cast<const uint4*>(lds) + (16 * ti + col) * STRIDE16 + q;   // lane (token col, k-group q)
       // A operands: lane (row m = lane & 15, k-group kg = lane >> 4) holds H_128[channel][32ks + 8kg + i],
       // channel = 32(m>>2) + 8(2d + (pp>>1)) + 4(pp&1) + (m&3); the sign is the parity of (channel & k),
       // which splits into (e & i), (v & kg) and ((m>>2) & ks)
@@ -159,7 +144,8 @@ __global__ void __launch_bounds__(256) k_append_mfma(RkvView v, const __half* __
           const v8h a = as_v8h(base[pp & 1][0] ^ mk, base[pp & 1][1] ^ mk, base[pp & 1][2] ^ mk, base[pp & 1][3] ^ mk);
 #pragma unroll
           for (int h = 0; h < G; ++h) {
-            const v8h x = as_v8h(xb[h][ks].x, xb[h][ks].y, xb[h][ks].z, xb[h][ks].w);
+            const uint4 xb = xrow[16 * h + 4 * ks];                      // keys 32ks + 8q .. +7 of head h
+            const v8h x = as_v8h(xb.x, xb.y, xb.z, xb.w);
             const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
             acc[h][pp] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, x, ks == 0 ? zero4 : acc[h][pp], 0, 0, 0);
           }
@@ -205,7 +191,7 @@ __global__ void __launch_bounds__(256) k_append_mfma(RkvView v, const __half* __
       float sc, zero_h, inv;
       quant_params_nodiv(fminf(m0.x, m1.x) * rs, fmaxf(m0.y, m1.y) * rs, sc, zero_h, inv);
       const float inv2_h = inv * rs;
-      if (d == 0 && q < G) metaK[(16 * ti + col) * G + ah] = rkv_pack_meta(sc, zero_h);
+      if (d == 0 && q < G) meta[(16 * ti + col) * G + ah] = rkv_pack_meta(sc, zero_h);
       const float magic = 12582912.0f;
 #pragma unroll
       for (int a = 0; a < G; ++a) {
@@ -219,12 +205,54 @@ __global__ void __launch_bounds__(256) k_append_mfma(RkvView v, const __half* __
             c = fminf(fmaxf(c, magic), magic + 3.0f);
             word += __float_as_uint(c) << (16 * (pp & 1) + 4 * rr + 2 * (pp >> 1));
           }
-        imgK[ti * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = word - kBias;
+        img[ti * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = word - kBias;
       }
     }
+    __syncthreads();
+    // K tiles: every 16-byte piece belongs to one token
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      const int idx = tid + 256 * k;                        // 0 .. 256G-1
+      const int tl = idx / (128 * G), off = idx - tl * (128 * G);
+      const int t = ts + tl * 16 + rkv_k_tile_token(G, off);
+      if (t >= t_lo && t < t_hi) v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + tl) + off] = img[idx];
+    }
+    for (int i = tid; i < 32 * G; i += 256) {
+      const int tau = i / G;
+      if (tau >= tau_first && tau <= tau_last) v.km[mrow + i] = meta[i];
+    }
+    return;
   }
 
-  // ------------------------------------------------------------------ values
+  // ==================================================================== values
+  // slots of this slab that belong to tokens outside this call are kept
+  uint32_t keep[2] = {0, 0};
+  for (int tau = 0; tau < 32; ++tau) {
+    const int t = ts + tau;
+    if (!(t >= t_lo && t < t_hi)) keep[tau >> 4] |= 3u << rkv_v_shift(tau);
+  }
+  const size_t vbase = rkv_v_slabbase(v, b, rg, slab);
+  uint32_t oldv[G];
+#pragma unroll
+  for (int k = 0; k < G; ++k) oldv[k] = 0;
+  if (keep[0] | keep[1]) {
+#pragma unroll
+    for (int k = 0; k < G; ++k) oldv[k] = v.vc[vbase + tid + 256 * k];
+  }
+  uint32_t vraw[8][PL / 2];                                // rows of this wave's 8 tokens: lane = PL consecutive channels
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int tau = 8 * wave + k;
+    const bool ok = tau >= tau_first && tau <= tau_last;
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(vin + ((size_t)b * n_new + (ok ? ts + tau - t_lo : 0)) * v.E + (size_t)rg * n + PL * lane);
+    if constexpr (PL == 8) {
+      const uint4 u = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+      vraw[k][0] = u.x; vraw[k][1] = u.y; vraw[k][2] = u.z; vraw[k][3] = u.w;
+    } else {
+      const uint2 u = ok ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
+      vraw[k][0] = u.x; vraw[k][1] = u.y;
+    }
+  }
   // min and max of a block travel together as one packed pair (min, -max), so that one packed
   // fp16 minimum per step reduces both (fp16 min/max of fp16 inputs is exact)
   const int blk = lane / LPB;                              // 128-block (= KV head) of this lane's channels
@@ -256,7 +284,7 @@ __global__ void __launch_bounds__(256) k_append_mfma(RkvView v, const __half* __
     const h2 pr = as_h2(mine);
     quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v);
     const int tau = 8 * wave + (lane & (LPB - 1));
-    if ((lane & (LPB - 1)) < 8) metaV[tau * G + blk] = rkv_pack_meta(sc_v, zero_v);
+    if ((lane & (LPB - 1)) < 8) meta[tau * G + blk] = rkv_pack_meta(sc_v, zero_v);
   }
   uint32_t vword[PL];
 #pragma unroll
@@ -280,21 +308,10 @@ __global__ void __launch_bounds__(256) k_append_mfma(RkvView v, const __half* __
     bias += 0x4B400000u << sh;
   }
 #pragma unroll
-  for (int i = 0; i < PL; ++i) vword[i] -= bias;
-#pragma unroll
-  for (int i = 0; i < PL; ++i) imgV[wave][i * 64 + lane] = vword[i];
+  for (int i = 0; i < PL; ++i) img[(wave * PL + i) * 64 + lane] = vword[i] - bias;
   __syncthreads();
-
-  // ---- K tiles: every 16-byte piece belongs to one token
-#pragma unroll
-  for (int k = 0; k < G; ++k) {
-    const int idx = tid + 256 * k;                          // 0 .. 256G-1
-    const int ti = idx / (128 * G), off = idx - ti * (128 * G);
-    const int t = ts + ti * 16 + rkv_k_tile_token(G, off);
-    if (t >= t_lo && t < t_hi) v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off] = imgK[idx];
-  }
-  // ---- V slab: dword idx = (((w*G + hh)*16 + nn)*2 + ct)*2 + d, channel c = 128hh + 32w + 16ct + nn;
-  //      waves 2d and 2d+1 hold the two halves of its 16 token slots
+  // V slab: dword idx = (((w*G + hh)*16 + nn)*2 + ct)*2 + d, channel c = 128hh + 32w + 16ct + nn;
+  // waves 2d and 2d+1 hold the two halves of its 16 token slots
 #pragma unroll
   for (int k = 0; k < G; ++k) {
     const int idx = tid + 256 * k;
@@ -302,18 +319,13 @@ __global__ void __launch_bounds__(256) k_append_mfma(RkvView v, const __half* __
     const int hh = rest % G, w = rest / G;
     const int c = 128 * hh + 32 * w + 16 * ct + nn;
     const int ln = c / PL, i = c - ln * PL;
-    uint32_t word = imgV[2 * d][i * 64 + ln] | imgV[2 * d + 1][i * 64 + ln];
+    uint32_t word = img[((2 * d) * PL + i) * 64 + ln] | img[((2 * d + 1) * PL + i) * 64 + ln];
     if (keep[d]) word |= oldv[k] & keep[d];
     if (keep[d] != 0xffffffffu) v.vc[vbase + idx] = word;
   }
-  // ---- metadata rows of the tokens written
   for (int i = tid; i < 32 * G; i += 256) {
     const int tau = i / G;
-    if (tau >= tau_first && tau <= tau_last) {
-      const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + ts + tau) * G + (i - tau * G);
-      v.km[mi] = metaK[i];
-      v.vm[mi] = metaV[i];
-    }
+    if (tau >= tau_first && tau <= tau_last) v.vm[mrow + i] = meta[i];
   }
 }
 
@@ -326,7 +338,7 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   const RkvView& v = c->v;
   if (!rkv_append_mfma_supported(c)) return RKV_EINVAL;
   const int slab0 = v.len >> 5, slab1 = (v.len + n_new - 1) >> 5;
-  dim3 grid(slab1 - slab0 + 1, v.NRG, v.B);
+  dim3 grid(2 * (slab1 - slab0 + 1), v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (v.g == 4) hipLaunchKernelGGL(k_append_mfma<4>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   else hipLaunchKernelGGL(k_append_mfma<2>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
