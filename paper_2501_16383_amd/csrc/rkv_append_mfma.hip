@@ -13,10 +13,12 @@
 //
 // One workgroup = (sequence, rotation group, slab of 32 token slots, role) so that every V dword
 // (16 tokens of one channel), every K tile and every metadata row it touches is written whole.
-// Even workgroups take the keys of a slab, odd ones its values, so that matrix-heavy and
-// load-heavy workgroups share a compute unit and each kind only holds its own operands.
-//   keys    wave w: K tile w>>1 of the slab (16 tokens), dword d = w&1 of every 16-byte piece
-//           (channels with bit 4 of the in-block index equal to d): 4 products per head, K = 128.
+// Three workgroups share a slab: one per K tile and one for the values, so that matrix-heavy and
+// load-heavy workgroups share a compute unit, each kind holds only its own operands, and the
+// register count leaves room for six waves per SIMD.
+//   keys    the tile's fp16 rows are staged in LDS (whole-row loads); wave w computes dword
+//           d = w&1 of every 16-byte piece (channels with bit 4 of the in-block index equal to d)
+//           and of its 4 products per head the two with pp>>1 == w>>1, K = 128 each.
 //   values  wave w: tokens 8w..8w+7.
 #include "rkv_internal.h"
 #include "rkv_quant.h"
@@ -70,57 +72,69 @@ __device__ __forceinline__ void quant_params_nodiv(float mn, float mx, float& s,
   zero = fminf(fmaxf(zero, -2048.0f), 2048.0f);
 }
 
+// Eq. 6 with one FMA per element.  Adding 1.5 * 2^23 rounds to an integer, ties to even, as rintf;
+// adding the (integer) zero-point in the same FMA keeps that rounding only if the constant added is
+// even, so an odd zero-point is raised by one and the clamp bounds and the packing bias move with
+// it.  `base` = 1.5 * 2^23 + (zero & 1); `add` = base + zero; codes are float_bits - bits(base).
+__device__ __forceinline__ void fused_round_consts(float zero, float& base, float& add) {
+  const float odd = (float)((int)zero & 1);
+  base = 12582912.0f + odd;
+  add = base + zero;
+}
+
 template <int G>
-__global__ void __launch_bounds__(256, 3) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+__global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                      int n_new, int slab0) {
   constexpr int PL = 2 * G;                    // value channels per lane
   constexpr int LPB = 128 / PL;                // lanes per 128-block in the value role
   constexpr int n = 128 * G;
   constexpr int ROW16 = 16 * G;                // 16-byte pieces per token row of the rotation group
   constexpr int STRIDE16 = ROW16 + 1;          // padded row: the matrix operand reads then touch every LDS bank once
-  // key role: the slab's fp16 keys, [32 tokens][STRIDE16] pieces, later overwritten by the two K tiles
-  // (2 x 128 G dwords); value role: per wave the partial V dwords of its 8 tokens, [wave][i][lane]
-  __shared__ __attribute__((aligned(16))) uint32_t lds[32 * STRIDE16 * 4];
+  // key roles: the fp16 keys of one K tile, [16 tokens][STRIDE16] pieces, later overwritten by the two
+  // halves of the tile image (2 x 128 G dwords); value role: per wave the partial V dwords of its 8
+  // tokens, [wave][i][lane]
+  __shared__ __attribute__((aligned(16))) uint32_t lds[16 * STRIDE16 * 4 > 4 * 64 * PL ? 16 * STRIDE16 * 4 : 4 * 64 * PL];
   uint32_t* img = lds;
   __shared__ uint32_t meta[32 * G];
-  __shared__ float2 s_mm[2][2][16][G];         // [tile][dword half][token][head] (min, max) of half a block
+  __shared__ float2 s_mm[2][2][16][G];         // [dword half][product pair][token][head] (min, max) of a quarter block
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int role = blockIdx.x & 1;             // even workgroups take the keys of a slab, odd ones its values
-  const int slab = slab0 + (blockIdx.x >> 1), rg = blockIdx.y, b = blockIdx.z;
+  const int role = blockIdx.x % 3;             // 0, 1: the keys of K tile 0 / 1 of a slab; 2: the slab's values
+  const int slab = slab0 + blockIdx.x / 3, rg = blockIdx.y, b = blockIdx.z;
   const int t_lo = v.len, t_hi = v.len + n_new;
   const int ts = slab * 32;
   const int tau_first = max(0, t_lo - ts), tau_last = min(31, t_hi - 1 - ts);
   const size_t mrow = ((size_t)(b * v.NRG + rg) * v.Tpad + ts) * G;     // metadata row of the slab's first token
 
-  if (role == 0) {
-    // ================================================================== keys
-    const int ti = wave >> 1, d = wave & 1;
+  if (role < 2) {
+    // ================================================================== keys of one tile
+    const int ti = role;
+    if (!((ts + 16 * ti < t_hi) && (ts + 16 * ti + 16 > t_lo))) return;   // no token of this call in the tile
+    const int d = wave & 1, pph = wave >> 1;               // this wave: products pp = 2 pph + {0, 1} of dword half d
     const int col = lane & 15, q = lane >> 4;              // result: token `col` of the tile, rows 4q..4q+3
-    const bool tile_on = (ts + 16 * ti < t_hi) && (ts + 16 * ti + 16 > t_lo);   // wave-uniform
     const float rs = rsqrtf((float)n);
-    // the slab's keys go to LDS once, whole rows at a time (wave w: tokens 8w..8w+7)
+    // the tile's keys go to LDS once, whole rows at a time (wave w: tokens 4w..4w+3)
     {
       constexpr int TPI = 64 / ROW16;                      // token rows per wave-wide 16-byte load
-      uint4 st[8 / TPI];
+      uint4 st[4 / TPI];
 #pragma unroll
-      for (int k = 0; k < 8 / TPI; ++k) {
-        const int tau = 8 * wave + TPI * k + lane / ROW16;
+      for (int k = 0; k < 4 / TPI; ++k) {
+        const int m = 4 * wave + TPI * k + lane / ROW16, tau = 16 * ti + m;
         const bool ok = tau >= tau_first && tau <= tau_last;
         const uint4* rowp = reinterpret_cast<const uint4*>(kin + ((size_t)b * n_new + (ok ? ts + tau - t_lo : 0)) * v.E + (size_t)rg * n);
-        st[k] = ok ? rowp[lane % ROW16] : make_uint4(0, 0, 0, 0);
+        st[k] = ok ? rkv_ld_stream(rowp + lane % ROW16) : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
-      for (int k = 0; k < 8 / TPI; ++k) {
-        const int tau = 8 * wave + TPI * k + lane / ROW16;
-        reinterpret_cast<uint4*>(lds)[tau * STRIDE16 + lane % ROW16] = st[k];
+      for (int k = 0; k < 4 / TPI; ++k) {
+        const int m = 4 * wave + TPI * k + lane / ROW16;
+        reinterpret_cast<uint4*>(lds)[m * STRIDE16 + lane % ROW16] = st[k];
       }
     }
     __syncthreads();
-    v4f acc[G][4];
-    if (tile_on) {
-      const uint4* xrow = reinterpret_cast<const uint4*>(lds) + (16 * ti + col) * STRIDE16 + q;   // lane (token col, k-group q)
+    v4f acc[G][2];
+    {
+      const uint4* xrow = reinterpret_cast<const uint4*>(lds) + col * STRIDE16 + q;   // lane (token col, k-group q)
       // A operands: lane (row m = lane & 15, k-group kg = lane >> 4) holds H_128[channel][32ks + 8kg + i],
-      // channel = 32(m>>2) + 8(2d + (pp>>1)) + 4(pp&1) + (m&3); the sign is the parity of (channel & k),
+      // channel = 32(m>>2) + 8(2d + pph) + 4 ppl + (m&3); the sign is the parity of (channel & k),
       // which splits into (e & i), (v & kg) and ((m>>2) & ks)
       const int m = lane & 15, kg = lane >> 4, r = m & 3, qa = m >> 2;
       uint32_t base[2][4];
@@ -131,95 +145,96 @@ __global__ void __launch_bounds__(256, 3) k_append_mfma(RkvView v, const __half*
           const int e = 4 * eb + r;
           base[eb][j] = (0x3C003C00u ^ parity_mask(e & (2 * j), 0x00008000u)) ^ parity_mask(e & (2 * j + 1), 0x80000000u);
         }
-      uint32_t maskv[2], maskq[4];
+      const uint32_t maskv = parity_mask((2 * d + pph) & kg, 0x80008000u);
 #pragma unroll
-      for (int vb = 0; vb < 2; ++vb) maskv[vb] = parity_mask((2 * d + vb) & kg, 0x80008000u);
+      for (int ks = 0; ks < 4; ++ks) {
+        const uint32_t mk = maskv ^ parity_mask(qa & ks, 0x80008000u);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) maskq[ks] = parity_mask(qa & ks, 0x80008000u);
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-        for (int pp = 0; pp < 4; ++pp) {
-          const uint32_t mk = maskv[pp >> 1] ^ maskq[ks];
-          const v8h a = as_v8h(base[pp & 1][0] ^ mk, base[pp & 1][1] ^ mk, base[pp & 1][2] ^ mk, base[pp & 1][3] ^ mk);
+        for (int ppl = 0; ppl < 2; ++ppl) {
+          const v8h a = as_v8h(base[ppl][0] ^ mk, base[ppl][1] ^ mk, base[ppl][2] ^ mk, base[ppl][3] ^ mk);
 #pragma unroll
           for (int h = 0; h < G; ++h) {
             const uint4 xb = xrow[16 * h + 4 * ks];                      // keys 32ks + 8q .. +7 of head h
             const v8h x = as_v8h(xb.x, xb.y, xb.z, xb.w);
             const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-            acc[h][pp] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, x, ks == 0 ? zero4 : acc[h][pp], 0, 0, 0);
+            acc[h][ppl] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, x, ks == 0 ? zero4 : acc[h][ppl], 0, 0, 0);
           }
         }
+      }
       // H_g over the heads (Sylvester order: the head index is the high part of the rotated channel)
 #pragma unroll
-      for (int pp = 0; pp < 4; ++pp)
+      for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           if constexpr (G == 4) {
-            const float x0 = acc[0][pp][rr], x1 = acc[1][pp][rr], x2 = acc[2][pp][rr], x3 = acc[3][pp][rr];
+            const float x0 = acc[0][ppl][rr], x1 = acc[1][ppl][rr], x2 = acc[2][ppl][rr], x3 = acc[3][ppl][rr];
             const float a0 = x0 + x1, a1 = x0 - x1, a2 = x2 + x3, a3 = x2 - x3;
-            acc[0][pp][rr] = a0 + a2; acc[1][pp][rr] = a1 + a3; acc[2][pp][rr] = a0 - a2; acc[3][pp][rr] = a1 - a3;
+            acc[0][ppl][rr] = a0 + a2; acc[1][ppl][rr] = a1 + a3; acc[2][ppl][rr] = a0 - a2; acc[3][ppl][rr] = a1 - a3;
           } else {
-            const float x0 = acc[0][pp][rr], x1 = acc[1][pp][rr];
-            acc[0][pp][rr] = x0 + x1; acc[1][pp][rr] = x0 - x1;
+            const float x0 = acc[0][ppl][rr], x1 = acc[1][ppl][rr];
+            acc[0][ppl][rr] = x0 + x1; acc[1][ppl][rr] = x0 - x1;
           }
         }
-      // min / max of this wave's half of every block: 16 values in the lane, then the four q groups
+      // min / max of this wave's quarter of every block: 8 values in the lane, then the four q groups
 #pragma unroll
       for (int a = 0; a < G; ++a) {
         float mn = acc[a][0][0], mx = mn;
 #pragma unroll
-        for (int pp = 0; pp < 4; ++pp)
+        for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
-            mn = fminf(mn, acc[a][pp][rr]);
-            mx = fmaxf(mx, acc[a][pp][rr]);
+            mn = fminf(mn, acc[a][ppl][rr]);
+            mx = fmaxf(mx, acc[a][ppl][rr]);
           }
         mn = fminf(mn, __shfl_xor(mn, 16)); mx = fmaxf(mx, __shfl_xor(mx, 16));
         mn = fminf(mn, __shfl_xor(mn, 32)); mx = fmaxf(mx, __shfl_xor(mx, 32));
-        if (q == 0) s_mm[ti][d][col][a] = make_float2(mn, mx);
+        if (q == 0) s_mm[d][pph][col][a] = make_float2(mn, mx);
       }
     }
     __syncthreads();
-    if (tile_on) {
+    {
       // Eq. 6-9 on y = (raw rotation) / sqrt(n): min and max scale exactly (rounding is monotone),
       // the elements take the factor inside the reciprocal scale.  Lane group q works out the
       // parameters of head q & (G-1) for its token; the others fetch them with lane exchanges.
-      constexpr uint32_t kBias = 0x4B400000u * 0x55555555u;    // what the float bit patterns add up to, mod 2^32
       const int ah = q & (G - 1);
-      const float2 m0 = s_mm[ti][0][col][ah], m1 = s_mm[ti][1][col][ah];
+      const float2 m0 = s_mm[0][0][col][ah], m1 = s_mm[0][1][col][ah], m2 = s_mm[1][0][col][ah], m3 = s_mm[1][1][col][ah];
       float sc, zero_h, inv;
-      quant_params_nodiv(fminf(m0.x, m1.x) * rs, fmaxf(m0.y, m1.y) * rs, sc, zero_h, inv);
+      quant_params_nodiv(fminf(fminf(m0.x, m1.x), fminf(m2.x, m3.x)) * rs, fmaxf(fmaxf(m0.y, m1.y), fmaxf(m2.y, m3.y)) * rs, sc,
+                         zero_h, inv);
       const float inv2_h = inv * rs;
-      if (d == 0 && q < G) meta[(16 * ti + col) * G + ah] = rkv_pack_meta(sc, zero_h);
-      const float magic = 12582912.0f;
+      if (wave == 0 && q < G) meta[col * G + ah] = rkv_pack_meta(sc, zero_h);
+      float base_h, add_h;
+      fused_round_consts(zero_h, base_h, add_h);
 #pragma unroll
       for (int a = 0; a < G; ++a) {
-        const float inv2 = __shfl(inv2_h, col + 16 * a), zero = __shfl(zero_h, col + 16 * a);
+        const float inv2 = __shfl(inv2_h, col + 16 * a), add = __shfl(add_h, col + 16 * a), base = __shfl(base_h, col + 16 * a);
+        const float top = base + 3.0f;
         uint32_t word = 0;
 #pragma unroll
-        for (int pp = 0; pp < 4; ++pp)
+        for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
-            float c = fmaf(acc[a][pp][rr], inv2, magic) + zero;
-            c = fminf(fmaxf(c, magic), magic + 3.0f);
-            word += __float_as_uint(c) << (16 * (pp & 1) + 4 * rr + 2 * (pp >> 1));
+            const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], inv2, add), base, top);
+            word += __float_as_uint(c) << (16 * ppl + 4 * rr);
           }
-        img[ti * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = word - kBias;
+        // the 8 float bit patterns add up to bits(base) * 0x11111111 plus the packed codes, mod 2^32;
+        // this wave's codes sit 2 pph bits up in the dword it shares with the wave of the other pph
+        img[pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = (word - __float_as_uint(base) * 0x11111111u) << (2 * pph);
       }
     }
     __syncthreads();
-    // K tiles: every 16-byte piece belongs to one token
+    // the K tile: every 16-byte piece belongs to one token
 #pragma unroll
-    for (int k = 0; k < G; ++k) {
-      const int idx = tid + 256 * k;                        // 0 .. 256G-1
-      const int tl = idx / (128 * G), off = idx - tl * (128 * G);
-      const int t = ts + tl * 16 + rkv_k_tile_token(G, off);
-      if (t >= t_lo && t < t_hi) v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + tl) + off] = img[idx];
+    for (int k = 0; k < (128 * G + 255) / 256; ++k) {
+      const int off = tid + 256 * k;
+      if (off < 128 * G) {
+        const int t = ts + ti * 16 + rkv_k_tile_token(G, off);
+        if (t >= t_lo && t < t_hi) rkv_st_stream(&v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], img[off] | img[128 * G + off]);
+      }
     }
-    for (int i = tid; i < 32 * G; i += 256) {
-      const int tau = i / G;
-      if (tau >= tau_first && tau <= tau_last) v.km[mrow + i] = meta[i];
+    for (int i = tid; i < 16 * G; i += 256) {
+      const int tau = 16 * ti + i / G;
+      if (tau >= tau_first && tau <= tau_last) v.km[mrow + 16 * ti * G + i] = meta[i];
     }
     return;
   }
@@ -246,10 +261,10 @@ __global__ void __launch_bounds__(256, 3) k_append_mfma(RkvView v, const __half*
     const bool ok = tau >= tau_first && tau <= tau_last;
     const uint32_t* p = reinterpret_cast<const uint32_t*>(vin + ((size_t)b * n_new + (ok ? ts + tau - t_lo : 0)) * v.E + (size_t)rg * n + PL * lane);
     if constexpr (PL == 8) {
-      const uint4 u = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+      const uint4 u = ok ? rkv_ld_stream(reinterpret_cast<const uint4*>(p)) : make_uint4(0, 0, 0, 0);
       vraw[k][0] = u.x; vraw[k][1] = u.y; vraw[k][2] = u.z; vraw[k][3] = u.w;
     } else {
-      const uint2 u = ok ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
+      const uint2 u = ok ? rkv_ld_stream(reinterpret_cast<const uint2*>(p)) : make_uint2(0, 0);
       vraw[k][0] = u.x; vraw[k][1] = u.y;
     }
   }
@@ -279,10 +294,11 @@ __global__ void __launch_bounds__(256, 3) k_append_mfma(RkvView v, const __half*
   uint32_t mine = mm[0];
 #pragma unroll
   for (int k = 1; k < 8; ++k) mine = ((lane & (LPB - 1)) == k) ? mm[k] : mine;
-  float sc_v, zero_v, inv_v;
+  float sc_v, zero_v, inv_v, base_v, add_v;
   {
     const h2 pr = as_h2(mine);
     quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v);
+    fused_round_consts(zero_v, base_v, add_v);
     const int tau = 8 * wave + (lane & (LPB - 1));
     if ((lane & (LPB - 1)) < 8) meta[tau * G + blk] = rkv_pack_meta(sc_v, zero_v);
   }
@@ -295,17 +311,16 @@ __global__ void __launch_bounds__(256, 3) k_append_mfma(RkvView v, const __half*
     const int tau = 8 * wave + k;
     if (tau < tau_first || tau > tau_last) continue;       // wave-uniform
     const int src = (lane & ~(LPB - 1)) | k;
-    const float inv = __shfl(inv_v, src), zero = __shfl(zero_v, src);
+    const float inv = __shfl(inv_v, src), add = __shfl(add_v, src), base = __shfl(base_v, src);
+    const float top = base + 3.0f;
     const int sh = rkv_v_shift(tau);
-    const float magic = 12582912.0f;
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
       const h2 pr = as_h2(vraw[k][i >> 1]);
-      float c = fmaf((float)pr[i & 1], inv, magic) + zero;
-      c = fminf(fmaxf(c, magic), magic + 3.0f);
+      const float c = __builtin_amdgcn_fmed3f(fmaf((float)pr[i & 1], inv, add), base, top);
       vword[i] += __float_as_uint(c) << sh;
     }
-    bias += 0x4B400000u << sh;
+    bias += __float_as_uint(base) << sh;
   }
 #pragma unroll
   for (int i = 0; i < PL; ++i) img[(wave * PL + i) * 64 + lane] = vword[i] - bias;
@@ -321,7 +336,7 @@ __global__ void __launch_bounds__(256, 3) k_append_mfma(RkvView v, const __half*
     const int ln = c / PL, i = c - ln * PL;
     uint32_t word = img[((2 * d) * PL + i) * 64 + ln] | img[((2 * d + 1) * PL + i) * 64 + ln];
     if (keep[d]) word |= oldv[k] & keep[d];
-    if (keep[d] != 0xffffffffu) v.vc[vbase + idx] = word;
+    if (keep[d] != 0xffffffffu) rkv_st_stream(&v.vc[vbase + idx], word);
   }
   for (int i = tid; i < 32 * G; i += 256) {
     const int tau = i / G;
@@ -338,7 +353,7 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   const RkvView& v = c->v;
   if (!rkv_append_mfma_supported(c)) return RKV_EINVAL;
   const int slab0 = v.len >> 5, slab1 = (v.len + n_new - 1) >> 5;
-  dim3 grid(2 * (slab1 - slab0 + 1), v.NRG, v.B);
+  dim3 grid(3 * (slab1 - slab0 + 1), v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (v.g == 4) hipLaunchKernelGGL(k_append_mfma<4>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   else hipLaunchKernelGGL(k_append_mfma<2>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
