@@ -72,6 +72,11 @@ __device__ __forceinline__ void quant_params_nodiv(float mn, float mx, float& s,
   zero = fminf(fmaxf(zero, -2048.0f), 2048.0f);
 }
 
+// value of x in lane `src_lane` (the address operand is the lane number times 4)
+__device__ __forceinline__ float lane_read(float x, int src_lane4) {
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane4, __float_as_int(x)));
+}
+
 // Eq. 6 with one FMA per element.  Adding 1.5 * 2^23 rounds to an integer, ties to even, as rintf;
 // adding the (integer) zero-point in the same FMA keeps that rounding only if the constant added is
 // even, so an odd zero-point is raised by one and the clamp bounds and the packing bias move with
@@ -97,7 +102,8 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
   uint32_t* img = lds;
   __shared__ uint32_t meta[32 * G];
   __shared__ float2 s_mm[2][2][16][G];         // [dword half][product pair][token][head] (min, max) of a quarter block
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: everything that depends only on it stays scalar
   const int role = blockIdx.x % 3;             // 0, 1: the keys of K tile 0 / 1 of a slab; 2: the slab's values
   const int slab = slab0 + blockIdx.x / 3, rg = blockIdx.y, b = blockIdx.z;
   const int t_lo = v.len, t_hi = v.len + n_new;
@@ -118,10 +124,10 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
       uint4 st[4 / TPI];
 #pragma unroll
       for (int k = 0; k < 4 / TPI; ++k) {
-        const int m = 4 * wave + TPI * k + lane / ROW16, tau = 16 * ti + m;
-        const bool ok = tau >= tau_first && tau <= tau_last;
-        const uint4* rowp = reinterpret_cast<const uint4*>(kin + ((size_t)b * n_new + (ok ? ts + tau - t_lo : 0)) * v.E + (size_t)rg * n);
-        st[k] = ok ? rkv_ld_stream(rowp + lane % ROW16) : make_uint4(0, 0, 0, 0);
+        // rows of tokens outside this call are replaced by a row inside it (their codes are never stored)
+        const int tau = min(max(16 * ti + 4 * wave + TPI * k + lane / ROW16, tau_first), tau_last);
+        const uint4* rowp = reinterpret_cast<const uint4*>(kin + ((size_t)b * n_new + (ts + tau - t_lo)) * v.E + (size_t)rg * n);
+        st[k] = rkv_ld_stream(rowp + lane % ROW16);
       }
 #pragma unroll
       for (int k = 0; k < 4 / TPI; ++k) {
@@ -207,7 +213,8 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
       fused_round_consts(zero_h, base_h, add_h);
 #pragma unroll
       for (int a = 0; a < G; ++a) {
-        const float inv2 = __shfl(inv2_h, col + 16 * a), add = __shfl(add_h, col + 16 * a), base = __shfl(base_h, col + 16 * a);
+        const int src4 = 4 * (col + 16 * a);
+        const float inv2 = lane_read(inv2_h, src4), add = lane_read(add_h, src4), base = lane_read(base_h, src4);
         const float top = base + 3.0f;
         uint32_t word = 0;
 #pragma unroll
@@ -257,14 +264,14 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
   uint32_t vraw[8][PL / 2];                                // rows of this wave's 8 tokens: lane = PL consecutive channels
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
-    const int tau = 8 * wave + k;
-    const bool ok = tau >= tau_first && tau <= tau_last;
-    const uint32_t* p = reinterpret_cast<const uint32_t*>(vin + ((size_t)b * n_new + (ok ? ts + tau - t_lo : 0)) * v.E + (size_t)rg * n + PL * lane);
+    // a token outside this call is replaced by one inside it (its codes are never used)
+    const int tau = min(max(8 * wave + k, tau_first), tau_last);
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(vin + ((size_t)b * n_new + (ts + tau - t_lo)) * v.E + (size_t)rg * n + PL * lane);
     if constexpr (PL == 8) {
-      const uint4 u = ok ? rkv_ld_stream(reinterpret_cast<const uint4*>(p)) : make_uint4(0, 0, 0, 0);
+      const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(p));
       vraw[k][0] = u.x; vraw[k][1] = u.y; vraw[k][2] = u.z; vraw[k][3] = u.w;
     } else {
-      const uint2 u = ok ? rkv_ld_stream(reinterpret_cast<const uint2*>(p)) : make_uint2(0, 0);
+      const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(p));
       vraw[k][0] = u.x; vraw[k][1] = u.y;
     }
   }
@@ -310,8 +317,8 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
   for (int k = 0; k < 8; ++k) {
     const int tau = 8 * wave + k;
     if (tau < tau_first || tau > tau_last) continue;       // wave-uniform
-    const int src = (lane & ~(LPB - 1)) | k;
-    const float inv = __shfl(inv_v, src), add = __shfl(add_v, src), base = __shfl(base_v, src);
+    const int src4 = 4 * ((lane & ~(LPB - 1)) | k);
+    const float inv = lane_read(inv_v, src4), add = lane_read(add_v, src4), base = lane_read(base_v, src4);
     const float top = base + 3.0f;
     const int sh = rkv_v_shift(tau);
 #pragma unroll
