@@ -219,15 +219,15 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
       uint32_t mw[4][G];
       auto load_tile = [&](int ti) {
 #pragma unroll
-        for (int pr = 0; pr < G / 2; ++pr) cw[pr] = ktiles[(size_t)ti * (32 * G) + pr * 64 + lane];
+        for (int pr = 0; pr < G / 2; ++pr) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const uint32_t* mp = kmeta + (size_t)(ti * 16 + 4 * q + r) * G;
           if constexpr (G == 4) {
-            const uint4 u = *reinterpret_cast<const uint4*>(mp);
+            const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(mp));
             mw[r][0] = u.x; mw[r][1] = u.y; mw[r][2] = u.z; mw[r][3] = u.w;
           } else {
-            const uint2 u = *reinterpret_cast<const uint2*>(mp);
+            const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(mp));
             mw[r][0] = u.x; mw[r][1] = u.y;
           }
         }
@@ -394,7 +394,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 #pragma unroll
     for (int sl = 0; sl < MF_CH / 32; ++sl) {
       vcodes[sl] = make_uint4(0, 0, 0, 0);
-      if (has_head && sl < nslab) vcodes[sl] = vslab[(size_t)sl * (64 * G) + lidx];
+      if (has_head && sl < nslab) vcodes[sl] = rkv_ld_stream(vslab + (size_t)sl * (64 * G) + lidx);
     }
     __syncthreads();
 
