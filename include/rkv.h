@@ -97,6 +97,18 @@ int rkv_calibrate_perm(const rkv_config* cfg, const void* dev_k_cal, int32_t n_t
  * 0..E-1 or move a channel out of its perm_span block. */
 int rkv_set_perm(rkv_cache* cache, const int32_t* dev_perm, void* stream);
 
+/* Attention-sink identification (Sec. 4.3, Fig. 3): the k tokens of every sequence with the most
+ * massive activations in a caller-chosen activation tensor (the paper uses the output of the
+ * previous decoder block).  A token's score is its largest |activation|; ties go to the lower token
+ * index; indices come back in ascending order.
+ *   dev_x         [batch][n_tok][width] fp16, width a multiple of 8
+ *   dev_idx_out   [batch][k] int32, 1 <= k <= min(64, n_tok)
+ *   dev_mask_out  [batch][n_tok] uint8 or NULL: 1 at the chosen tokens, 0 elsewhere - the form
+ *                 rkv_quantize_append takes as dev_sink_mask
+ *   dev_scratch   >= batch * n_tok * 4 bytes */
+int rkv_select_sinks(const void* dev_x, int32_t batch, int32_t n_tok, int32_t width, int32_t k, int32_t* dev_idx_out,
+                     uint8_t* dev_mask_out, void* dev_scratch, void* stream);
+
 /* Write half: compress n_new tokens per sequence and append them at the current length.
  *   dev_k, dev_v    [batch][n_new][n_kv_heads][head_dim] fp16, keys pre-RoPE
  *   dev_sink_mask   [batch][n_new] uint8 or NULL; a non-zero entry marks an attention-sink token

@@ -19,7 +19,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
-    "rkv_calibrate_perm", "rkv_set_perm", "rkv_quantize_append", "rkv_decode_attention",
+    "rkv_calibrate_perm", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention",
     "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
@@ -88,6 +88,7 @@ def load_library():
     lib.rkv_cache_length.argtypes = [vp]
     lib.rkv_calibrate_perm.argtypes = [cfgp, vp, i32, vp, vp, vp]
     lib.rkv_set_perm.argtypes = [vp, vp, vp]
+    lib.rkv_select_sinks.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.rkv_quantize_append.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.rkv_set_decode_path.argtypes = [vp, i32]
@@ -158,6 +159,22 @@ def calibrate_perm(cfg: RkvConfig, k_cal, scratch=None):
     _check(lib.rkv_calibrate_perm(C.byref(cc), _ptr(k_cal), k_cal.shape[0], _ptr(perm), _ptr(scratch), _stream()),
            "rkv_calibrate_perm")
     return perm
+
+
+def select_sinks(x, k: int, want_mask: bool = True):
+    """rkv_select_sinks: x [batch, n_tok, width] fp16 on the device -> (int32 [batch, k], uint8 [batch, n_tok] or None)."""
+    import torch
+    lib = load_library()
+    x = _dev(x, torch.float16, "x")
+    if x.dim() != 3:
+        raise ValueError("x must be [batch, n_tok, width]")
+    batch, n_tok, width = x.shape
+    idx = torch.empty(batch, k, dtype=torch.int32, device=x.device)
+    mask = torch.empty(batch, n_tok, dtype=torch.uint8, device=x.device) if want_mask else None
+    scratch = torch.empty(batch * n_tok * 4, dtype=torch.uint8, device=x.device)
+    _check(lib.rkv_select_sinks(_ptr(x), batch, n_tok, width, k, _ptr(idx), _ptr(mask), _ptr(scratch), _stream()),
+           "rkv_select_sinks")
+    return idx, mask
 
 
 class RkvCache:

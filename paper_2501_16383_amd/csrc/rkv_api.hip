@@ -194,6 +194,14 @@ RKV_EXPORT int rkv_calibrate_perm(const rkv_config* cfg, const void* dev_k_cal, 
   return rkv_launch_calibrate(cfg, (const __half*)dev_k_cal, n_tok, dev_perm_out, dev_scratch, (hipStream_t)stream);
 }
 
+RKV_EXPORT int rkv_select_sinks(const void* dev_x, int32_t batch, int32_t n_tok, int32_t width, int32_t k, int32_t* dev_idx_out,
+                                uint8_t* dev_mask_out, void* dev_scratch, void* stream) {
+  if (!dev_x || !dev_idx_out || !dev_scratch) return RKV_EINVAL;
+  if (batch < 1 || n_tok < 1 || width < 8 || (width & 7) || k < 1 || k > 64 || k > n_tok) return RKV_EINVAL;
+  return rkv_launch_select_sinks((const __half*)dev_x, batch, n_tok, width, k, dev_idx_out, dev_mask_out, (float*)dev_scratch,
+                                 (hipStream_t)stream);
+}
+
 RKV_EXPORT int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, int32_t n_new,
                                    const uint8_t* dev_sink_mask, void* stream) {
   if (!cache || !dev_k || !dev_v || n_new < 0) return RKV_EINVAL;

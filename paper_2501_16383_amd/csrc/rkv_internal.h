@@ -143,6 +143,8 @@ bool rkv_mfma_supported(const rkv_cache* c);
 void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, float* qr, hipStream_t s);
 void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, float* out, float* lse, hipStream_t s);
 int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s);
+int rkv_launch_select_sinks(const __half* x, int batch, int n_tok, int width, int k, int32_t* idx_out, uint8_t* mask_out,
+                            float* scratch, hipStream_t s);
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg);
 size_t rkv_calib_scratch_bytes(const rkv_config* cfg);
 

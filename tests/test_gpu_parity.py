@@ -386,3 +386,44 @@ def test_large_zero_points():
     for path in (1, 2):
         cache.set_decode_path(path)
         check_decode(cache, oc_g, q, tag=f"large zero-points path={path}")
+
+
+def test_select_sinks_matches_oracle():
+    """rkv_select_sinks against the oracle's selector: planted massive-activation tokens (also at
+    non-initial positions), exact ties between tokens (lower index wins), k = 1 .. 8, and the mask
+    form that rkv_quantize_append takes.  fp16 maxima are exact, so indices must be equal."""
+    rng = np.random.default_rng(77)
+    B, T, C = 3, 1003, 4096
+    x = rng.standard_normal((B, T, C)).astype(np.float16)
+    x[0, 0] *= 100.0
+    x[0, 517] *= 100.0
+    x[1, 3, 100] = np.float16(900.0)
+    x[1, 999, 7] = np.float16(-900.0)          # same score as token 3: the lower index must win first
+    x[1, 400, 9] = np.float16(900.0)
+    x[2, T - 1] *= 50.0
+    xg = P.gpu(x)
+    for k in (1, 2, 3, 4, 8):
+        print(f"[case] select sinks k={k}", flush=True)
+        idx, mask = R.select_sinks(xg, k)
+        torch.cuda.synchronize()
+        idx, mask = idx.cpu().numpy(), mask.cpu().numpy()
+        for b in range(B):
+            ref = O.select_sinks(x[b], k)
+            assert idx[b].tolist() == ref.tolist(), (k, b, idx[b], ref)
+            want = np.zeros(T, dtype=np.uint8)
+            want[ref] = 1
+            assert np.array_equal(mask[b], want)
+    with pytest.raises(R.RkvError):
+        R.select_sinks(xg, 65)
+    # the mask feeds the write half directly
+    w = small("cfg1", n_q_heads=4, n_kv_heads=4)
+    cfg = R.RkvConfig(batch=2, n_q_heads=4, n_kv_heads=4, max_tokens=64, max_sinks=4, rot_heads=4)
+    k_, v_, _, _ = P.make_case(w, cfg, 40, sink_positions=[])
+    act = rng.standard_normal((2, 40, 512)).astype(np.float16)
+    act[0, 5] *= 100.0
+    act[1, 17] *= 100.0
+    idx, mask = R.select_sinks(P.gpu(act), 1)
+    cache = R.RkvCache(cfg)
+    cache.quantize_append(P.gpu(k_), P.gpu(v_), mask)
+    s = {kk: vv.cpu().numpy() for kk, vv in cache.export_sinks().items()}
+    assert s["count"].tolist() == [1, 1] and s["pos"][0, 0] == 5 and s["pos"][1, 0] == 17

@@ -397,3 +397,24 @@ def test_reorder_lowers_error_on_offset_outliers():
         k_hat, _ = O.dequantize_cache(c)
         mses.append(((k_hat - k.astype(np.float64)) ** 2).mean())
     assert mses[1] < mses[0]
+
+
+def test_select_sinks_brute_force():
+    """The selector against a literal reading of its definition on tiny inputs: score = largest
+    |activation| of a token; take the k best, lower index first among equals; return ascending."""
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        T, C = int(rng.integers(1, 9)), int(rng.integers(1, 5))
+        x = rng.integers(-3, 4, size=(T, C)).astype(np.float64)      # many exact ties
+        k = int(rng.integers(1, T + 1))
+        scores = [max(abs(v) for v in row) for row in x]
+        chosen = []
+        for _ in range(k):
+            best = None
+            for t in range(T):
+                if t in chosen:
+                    continue
+                if best is None or scores[t] > scores[best]:
+                    best = t
+            chosen.append(best)
+        assert O.select_sinks(x, k).tolist() == sorted(chosen)
