@@ -158,12 +158,16 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 
   // Hadamard operand tiles go to LDS once per workgroup; the key phase reads two of them per step
   for (int i = tid; i < 8 * 64; i += 256) (&s_H[0][0])[i] = reinterpret_cast<const uint4*>(v.hop)[i];
-  float st_c[4], st_s[4];
+  // RoPE angles are kept for the first of a lane's four tokens only; the other three follow by
+  // rotating one position at a time, the next tile by rotating 16 positions (table rows 1 and 16)
+  float st_c[4], st_s[4], s1_c[4], s1_s[4];
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    const float2 st = v.rope[16 * 64 + 16 * p + n];
+    const float2 st = v.rope[16 * 64 + 16 * p + n], s1 = v.rope[64 + 16 * p + n];
     st_c[p] = st.x;
     st_s[p] = st.y;
+    s1_c[p] = s1.x;
+    s1_s[p] = s1.y;
   }
   const float zmask = (n == 0) ? -64.0f : 0.0f;           // H_128 of a constant block lives in channel 0
 #if MF_BFLY_MFMA
@@ -203,15 +207,13 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
     // ------------------------------------------------------------------ phase K
     {
       const int tw = t0 + wave * (16 * MF_TILES);
-      float cs_c[4][4], cs_s[4][4];
+      float cs_c[4], cs_s[4];
 #pragma unroll
-      for (int p = 0; p < 4; ++p)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float2 cs = v.rope[(size_t)(tw + 4 * q + r) * 64 + 16 * p + n];
-          cs_c[r][p] = cs.x;
-          cs_s[r][p] = cs.y;
-        }
+      for (int p = 0; p < 4; ++p) {
+        const float2 cs = v.rope[(size_t)(tw + 4 * q) * 64 + 16 * p + n];
+        cs_c[p] = cs.x;
+        cs_s[p] = cs.y;
+      }
       const uint4* ktiles = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tw >> 4));
       const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * G;
 
@@ -269,15 +271,13 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         // with n == 0).  sum_blk H_g[a][blk] * scale_blk * z_blk is one more 4x4x4 product (zero-points
         // are integers up to 2048: exact in fp16); times -64 it becomes the accumulator of the
         // channel-0 product below.
-        v4f zcorr[4];
+        v4h zB[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const uint32_t z01 = __builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x07060302u) & lane0_mask;
           uint32_t z23 = 0;
           if constexpr (G == 4) z23 = __builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x07060302u) & lane0_mask;
-          const v4f zz = {0.f, 0.f, 0.f, 0.f};
-          const v4f d = mfma_4x4x4(sA[r], as_v4h(z01, z23), zz);
-          zcorr[r] = d * -64.0f;
+          zB[r] = as_v4h(z01, z23);
         }
 #endif
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
@@ -325,6 +325,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
             const uint4 u = *reinterpret_cast<const uint4*>(&s_q[n][p][i]);
             qv[i] = __uint_as_float(u.x); qv[i + 1] = __uint_as_float(u.y); qv[i + 2] = __uint_as_float(u.z); qv[i + 3] = __uint_as_float(u.w);
           }
+          float c = cs_c[p], s = cs_s[p];                      // token 4q: r = 0
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             // k^[a] = sum_blk H_g[a][blk] * scale_blk * u_blk   (H_g butterfly over the blocks)
@@ -334,11 +335,13 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
             // below 1024: exact in fp16), fp32 accumulate
             const v4f z4 = {0.f, 0.f, 0.f, 0.f};
             v4f klo, khi;
+            v4f zc = z4;
+            if (p == 0) zc = mfma_4x4x4(sA[r], zB[r], z4) * -64.0f;
             if constexpr (G == 4) {
-              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), p == 0 ? zcorr[r] : z4);
+              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), zc);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), pk_f16(hi[2][r], hi[3][r])), z4);
             } else {
-              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), p == 0 ? zcorr[r] : z4);
+              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), zc);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), z4);
             }
 #else
@@ -357,24 +360,26 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
               khi[0] = x0 + x1; khi[1] = x0 - x1;
             }
 #endif
-            const float c = cs_c[r][p], s = cs_s[r][p];
 #pragma unroll
             for (int a = 0; a < G; ++a) {
               const float xl = klo[a] * c - khi[a] * s;
               const float xh = klo[a] * s + khi[a] * c;
               pt[r * G + a] = fmaf(xh, qv[2 * a + 1], fmaf(xl, qv[2 * a], pt[r * G + a]));
             }
+            if (r < 3) {                                       // next token: one position further
+              const float c1 = c * s1_c[p] - s * s1_s[p];
+              s = s * s1_c[p] + c * s1_s[p];
+              c = c1;
+            }
           }
         }
         // advance the RoPE state by 16 positions
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float c = cs_c[r][p], s = cs_s[r][p];
-            cs_c[r][p] = c * st_c[p] - s * st_s[p];
-            cs_s[r][p] = s * st_c[p] + c * st_s[p];
-          }
+        for (int p = 0; p < 4; ++p) {
+          const float c = cs_c[p], s = cs_s[p];
+          cs_c[p] = c * st_c[p] - s * st_s[p];
+          cs_s[p] = s * st_c[p] + c * st_s[p];
+        }
         // reduce over the 16 channel lanes: lane n gets (token 4q + n / G, head n % G)
         const float tot = row_transpose_reduce<4 * G>(pt, n);
         const int idx = n & (4 * G - 1);
