@@ -39,7 +39,7 @@ typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 #define MF_BFLY_MFMA 1     // 1: scale + H_g butterfly on v_mfma_f32_4x4x4_16b_f16, 0: on the vector ALU
 #endif
 #ifndef MF_OCC
-#define MF_OCC 2           // workgroups per compute unit the register budget is set for
+#define MF_OCC 3           // workgroups per compute unit the register budget is set for
 #endif
 
 __device__ __forceinline__ v4f mfma_fp4(const v8i& a, const v8i& b, const v4f& c) {
