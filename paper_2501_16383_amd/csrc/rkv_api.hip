@@ -204,8 +204,9 @@ RKV_EXPORT int rkv_select_sinks(const void* dev_x, int32_t batch, int32_t n_tok,
 
 RKV_EXPORT int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, int32_t n_new,
                                    const uint8_t* dev_sink_mask, void* stream) {
-  if (!cache || !dev_k || !dev_v || n_new < 0) return RKV_EINVAL;
-  if (n_new == 0) return RKV_OK;
+  if (!cache || n_new < 0) return RKV_EINVAL;
+  if (n_new == 0) return RKV_OK;                      // nothing to read: the pointers may be null
+  if (!dev_k || !dev_v) return RKV_EINVAL;
   if ((int64_t)cache->v.len + n_new > cache->cfg.max_tokens) return RKV_ECAPACITY;
   int rc = rkv_launch_append(cache, (const __half*)dev_k, (const __half*)dev_v, n_new, dev_sink_mask, (hipStream_t)stream);
   if (rc == RKV_OK) cache->v.len += n_new;

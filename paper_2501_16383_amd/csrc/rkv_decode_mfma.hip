@@ -30,8 +30,10 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 
-#define MF_CH 256          // tokens per workgroup
+#ifndef MF_TILES
 #define MF_TILES 4         // 16-token tiles per wave
+#endif
+#define MF_CH (64 * MF_TILES)   // tokens per workgroup (4 waves)
 #ifndef MF_PIPE
 #define MF_PIPE 0          // 1: matrix products one step ahead of the vector work (needs 32 more registers)
 #endif

@@ -427,3 +427,41 @@ def test_select_sinks_matches_oracle():
     cache.quantize_append(P.gpu(k_), P.gpu(v_), mask)
     s = {kk: vv.cpu().numpy() for kk, vv in cache.export_sinks().items()}
     assert s["count"].tolist() == [1, 1] and s["pos"][0, 0] == 5 and s["pos"][1, 0] == 17
+
+
+@pytest.mark.parametrize("T,sinks", [(1, []), (1, [0]), (2, [1]), (17, [0, 16])])
+def test_tiny_caches(T, sinks):
+    """Degenerate lengths: a cache of one or two tokens, the only token being a sink, a sink on a
+    tile boundary."""
+    w = small("cfg1", n_q_heads=4, n_kv_heads=4)
+    cfg = R.RkvConfig(batch=2, n_q_heads=4, n_kv_heads=4, max_tokens=32, max_sinks=2, rot_heads=4)
+    full_check(w, cfg, T, sink_positions=sinks, paths=(1, 2))
+
+
+def test_cache_filled_to_capacity_and_many_sinks():
+    """A capacity that is no multiple of any tile size, filled exactly; the maximum number of sink
+    rows (64), spread over the sequence; one more token must be refused without changing the cache."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8)
+    T = 333
+    cfg = R.RkvConfig(batch=1, n_q_heads=8, n_kv_heads=8, max_tokens=T, max_sinks=64, rot_heads=4)
+    sinks = list(range(0, 5 * 64, 5))
+    cache, oc, q = full_check(w, cfg, T, sink_positions=sinks, chunks=[0, 100, 332, 333], paths=(1, 2))
+    k, v, mask, _ = P.make_case(w, cfg, 1, layer=9)
+    before = cache.export_codes()
+    with pytest.raises(R.RkvError) as ei:
+        cache.quantize_append(P.gpu(k), P.gpu(v))
+    assert ei.value.code == -2 and cache.length == T
+    after = cache.export_codes()
+    torch.cuda.synchronize()
+    for name in before:
+        assert torch.equal(before[name], after[name]), name
+
+
+def test_empty_append_is_a_no_op():
+    w = small("cfg1", n_q_heads=4, n_kv_heads=4)
+    cfg = R.RkvConfig(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=64, max_sinks=1, rot_heads=4)
+    cache, oc, q = build_pair(w, cfg, 9)
+    empty = torch.empty(1, 0, 4, 128, dtype=torch.float16, device="cuda")
+    cache.quantize_append(empty, empty)
+    assert cache.length == 9
+    P.check_cache_against_oracle(cache, oc, "after empty append")
