@@ -3,11 +3,14 @@
 // The inverse rotation of the keys is a dense contraction with a +-1 matrix, and 2-bit codes are
 // exactly representable in FP4 (E2M1: a nibble holding the integer c in its two low bits is the
 // value c/2), so the per-head Hadamard H_128 of the raw codes runs on
-// v_mfma_f32_16x16x128_f8f6f4 with exact small-integer results in fp32.  What is left for the
-// vector ALU is linear in those results:
+// v_mfma_f32_16x16x128_f8f6f4 with exact small-integer results in fp32.  The rest is linear in
+// those results:
 //     k^[head a][j] = (1/sqrt(n)) * sum_blk H_g[a][blk] * scale_blk * (H_128 c_blk - 128 zero_blk e_0)[j]
-// (H_n = H_g (x) H_128 for the grouped-head rotation of Sec. 4.2; Eq. 7 folded in), then RoPE and
-// the dot with the query (Eq. 5).  p.V runs on the same instruction with the codes as the FP4
+// (H_n = H_g (x) H_128 for the grouped-head rotation of Sec. 4.2; Eq. 7 folded in).  The sum over
+// the blocks is a second, tiny matrix product on v_mfma_f32_4x4x4_16b_f16 (16 independent 4x4x4
+// products per instruction): rows = the token's fp16 scales signed by a row of H_g, columns = the
+// blocks' results, which are exact in fp16; the zero-point term is one more such product.  The
+// vector ALU does RoPE and the dot with the query (Eq. 5).  p.V runs on the same instruction with the codes as the FP4
 // operand and the softmax weights p_t * scale_t as the other: each weight is scaled by a power of
 // two per (head, chunk) to a 24-bit integer and split into six base-16 digits, which FP8 (E4M3)
 // holds exactly.  All products are then small half-integers of similar size, so the instruction's
@@ -34,12 +37,6 @@ typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 #define MF_TILES 4         // 16-token tiles per wave
 #endif
 #define MF_CH (64 * MF_TILES)   // tokens per workgroup (4 waves)
-#ifndef MF_PIPE
-#define MF_PIPE 0          // 1: matrix products one step ahead of the vector work (needs 32 more registers)
-#endif
-#ifndef MF_BFLY_MFMA
-#define MF_BFLY_MFMA 1     // 1: scale + H_g butterfly on v_mfma_f32_4x4x4_16b_f16, 0: on the vector ALU
-#endif
 #ifndef MF_OCC
 #define MF_OCC 3           // workgroups per compute unit the register budget is set for
 #endif
@@ -171,8 +168,6 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
     s1_c[p] = s1.x;
     s1_s[p] = s1.y;
   }
-  const float zmask = (n == 0) ? -64.0f : 0.0f;           // H_128 of a constant block lives in channel 0
-#if MF_BFLY_MFMA
   // row (n & 3) of H_g as fp16 sign masks for the packed scale pairs (blocks 0,1) and (2,3);
   // rows >= G are zero
   const int hrow = n & 3;
@@ -180,7 +175,6 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   const uint32_t lane0_mask = (n == 0) ? 0xffffffffu : 0u;
   const uint32_t sm01 = ((__popc(hrow & 1) & 1) ? 0x80000000u : 0u);
   const uint32_t sm23 = ((__popc(hrow & 2) & 1) ? 0x00008000u : 0u) | ((__popc(hrow & 3) & 1) ? 0x80000000u : 0u);
-#endif
 
   // blockIdx.x = rr * nch8 + chunk, nch8 = chunk count rounded up to 8: the workgroups that serve
   // the `rep` query heads sharing a KV head (GQA) re-read the same chunk, and with ids a multiple of
@@ -244,22 +238,11 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         const int tt = tw + ti * 16;
         if (tt >= len) break;                              // wave-uniform
         v8i A[G];
-        float sc[4][G], zc[4][G];
 #pragma unroll
         for (int pr = 0; pr < G / 2; ++pr) {
           A[2 * pr] = unpack_fp4(cw[pr].x, cw[pr].y);
           A[2 * pr + 1] = unpack_fp4(cw[pr].z, cw[pr].w);
         }
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-          for (int blk = 0; blk < G; ++blk) {
-            float s_, z_;
-            rkv_unpack_meta(mw[r][blk], s_, z_);
-            sc[r][blk] = s_;
-            zc[r][blk] = z_ * zmask;
-          }
-#if MF_BFLY_MFMA
         // scale rows of the 4x4 products: (+-s_0, +-s_1, +-s_2, +-s_3) of token 4q + r, signs of H_g row n & 3
         v4h sA[4];
 #pragma unroll
@@ -281,46 +264,27 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
           if constexpr (G == 4) z23 = __builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x07060302u) & lane0_mask;
           zB[r] = as_v4h(z01, z23);
         }
-#endif
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
 
         float pt[4 * G];                                   // [r][a]
 #pragma unroll
         for (int i = 0; i < 4 * G; ++i) pt[i] = 0.f;
-        // matrix products run one step (16 + 16 channels) ahead of the vector work that consumes them
-        v4f lo2[2][G], hi2[2][G];
-        auto issue = [&](int p, int buf) {
-          v8i Hlo, Hhi;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          // H_128 of the raw codes for channels 16p + n (lo) and 16p + n + 64 (hi): half-integers, exact
+          v4f lo[G], hi[G];
           {
+            v8i Hlo, Hhi;
             const uint4 h0 = s_H[p][lane], h1 = s_H[p + 4][lane];
             Hlo[0] = (int)h0.x; Hlo[1] = (int)h0.y; Hlo[2] = (int)h0.z; Hlo[3] = (int)h0.w; Hlo[4] = Hlo[5] = Hlo[6] = Hlo[7] = 0;
             Hhi[0] = (int)h1.x; Hhi[1] = (int)h1.y; Hhi[2] = (int)h1.z; Hhi[3] = (int)h1.w; Hhi[4] = Hhi[5] = Hhi[6] = Hhi[7] = 0;
-          }
-#pragma unroll
-          for (int blk = 0; blk < G; ++blk) {
-            v4f c0 = {0.f, 0.f, 0.f, 0.f};
-#if !MF_BFLY_MFMA
-            if (p == 0) { c0[0] = zc[0][blk]; c0[1] = zc[1][blk]; c0[2] = zc[2][blk]; c0[3] = zc[3][blk]; }
-#endif
             const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-            lo2[buf][blk] = mfma_fp4(A[blk], Hlo, c0);          // (H_128 c_blk - 128 z e_0) / 2, channels 16p + n
-            hi2[buf][blk] = mfma_fp4(A[blk], Hhi, zero4);   // channels 16p + n + 64
-          }
-        };
-#if MF_PIPE
-        issue(0, 0);
-#endif
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-#if MF_PIPE
-          if (p < 3) issue(p + 1, (p + 1) & 1);
-          v4f (&lo)[G] = lo2[p & 1];
-          v4f (&hi)[G] = hi2[p & 1];
-#else
-          issue(p, 0);
-          v4f (&lo)[G] = lo2[0];
-          v4f (&hi)[G] = hi2[0];
-#endif
+            for (int blk = 0; blk < G; ++blk) {
+              lo[blk] = mfma_fp4(A[blk], Hlo, zero4);
+              hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
+            }
+          }
           float qv[2 * G];
 #pragma unroll
           for (int i = 0; i < 2 * G; i += 4) {
@@ -331,7 +295,6 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             // k^[a] = sum_blk H_g[a][blk] * scale_blk * u_blk   (H_g butterfly over the blocks)
-#if MF_BFLY_MFMA
             // as 16 independent 4x4x4 products per instruction: block = (token 4q + r, 4 channel
             // lanes), A row a = signed fp16 scales, B = the four blocks' results (half-integers
             // below 1024: exact in fp16), fp32 accumulate
@@ -346,22 +309,6 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
               klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), zc);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), z4);
             }
-#else
-            float klo[G], khi[G];
-            if constexpr (G == 4) {
-              const float w0 = lo[0][r] * sc[r][0], w1 = lo[1][r] * sc[r][1], w2 = lo[2][r] * sc[r][2], w3 = lo[3][r] * sc[r][3];
-              const float a0 = w0 + w1, a1 = w0 - w1, a2 = w2 + w3, a3 = w2 - w3;
-              klo[0] = a0 + a2; klo[1] = a1 + a3; klo[2] = a0 - a2; klo[3] = a1 - a3;
-              const float x0 = hi[0][r] * sc[r][0], x1 = hi[1][r] * sc[r][1], x2 = hi[2][r] * sc[r][2], x3 = hi[3][r] * sc[r][3];
-              const float b0 = x0 + x1, b1 = x0 - x1, b2 = x2 + x3, b3 = x2 - x3;
-              khi[0] = b0 + b2; khi[1] = b1 + b3; khi[2] = b0 - b2; khi[3] = b1 - b3;
-            } else {
-              const float w0 = lo[0][r] * sc[r][0], w1 = lo[1][r] * sc[r][1];
-              klo[0] = w0 + w1; klo[1] = w0 - w1;
-              const float x0 = hi[0][r] * sc[r][0], x1 = hi[1][r] * sc[r][1];
-              khi[0] = x0 + x1; khi[1] = x0 - x1;
-            }
-#endif
 #pragma unroll
             for (int a = 0; a < G; ++a) {
               const float xl = klo[a] * c - khi[a] * s;
