@@ -145,6 +145,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   __shared__ float s_m[4], s_l[4], s_zs[4], s_wsc[4];
   __shared__ int s_sink[4][64];
   __shared__ uint4 s_H[8][64];                   // Hadamard operand tiles
+  __shared__ float2 s_step[64];                  // RoPE rotation by 16 positions, per channel pair
   __shared__ __attribute__((aligned(16))) float s_q[16][4][2 * G];   // query [n][p][head][lo, hi]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -159,12 +160,12 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   for (int i = tid; i < 8 * 64; i += 256) (&s_H[0][0])[i] = reinterpret_cast<const uint4*>(v.hop)[i];
   // RoPE angles are kept for the first of a lane's four tokens only; the other three follow by
   // rotating one position at a time, the next tile by rotating 16 positions (table rows 1 and 16)
-  float st_c[4], st_s[4], s1_c[4], s1_s[4];
+  // (the 16-position step is used once per tile and is read from LDS there)
+  if (tid < 64) s_step[tid] = v.rope[16 * 64 + tid];
+  float s1_c[4], s1_s[4];
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    const float2 st = v.rope[16 * 64 + 16 * p + n], s1 = v.rope[64 + 16 * p + n];
-    st_c[p] = st.x;
-    st_s[p] = st.y;
+    const float2 s1 = v.rope[64 + 16 * p + n];
     s1_c[p] = s1.x;
     s1_s[p] = s1.y;
   }
@@ -194,11 +195,6 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   // query of this rotation group, already RoPE'd, scaled and laid out [n][p][head][lo, hi] by k_prep_q
   if (tid < 16 * 4 * 2 * G / 4)
     reinterpret_cast<uint4*>(&s_q[0][0][0])[tid] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * rep + rr) * (16 * 4 * 2 * G))[tid];
-  // V metadata of the four tokens this lane turns into weights in phase S (head = wave)
-  uint32_t vmeta[MF_CH / 64];
-#pragma unroll
-  for (int i = 0; i < MF_CH / 64; ++i)
-    vmeta[i] = wave < G ? v.vm[((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G + wave] : 0u;
   {
     // ------------------------------------------------------------------ phase K
     {
@@ -326,8 +322,9 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const float c = cs_c[p], s = cs_s[p];
-          cs_c[p] = c * st_c[p] - s * st_s[p];
-          cs_s[p] = s * st_c[p] + c * st_s[p];
+          const float2 st = s_step[16 * p + n];
+          cs_c[p] = c * st.x - s * st.y;
+          cs_s[p] = s * st.x + c * st.y;
         }
         // reduce over the 16 channel lanes: lane n gets (token 4q + n / G, head n % G)
         const float tot = row_transpose_reduce<4 * G>(pt, n);
@@ -338,7 +335,13 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         if (n < 4 * G && !masked) s_sc[a][tok - t0] = tot;
       }
     }
-    // first slab of V codes: in flight while the softmax phase runs
+    // V metadata of the four tokens this lane turns into weights in phase S (head = wave); requested
+    // here and not before the key phase, where four more live registers would mean spills - and
+    // with them a scratch allocation, which keeps some shader engines from holding three workgroups
+    uint32_t vmeta[MF_CH / 64];
+#pragma unroll
+    for (int i = 0; i < MF_CH / 64; ++i)
+      vmeta[i] = wave < G ? v.vm[((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G + wave] : 0u;
     const bool has_head = q < G;
     const uint4* vslab = reinterpret_cast<const uint4*>(v.vc + rkv_v_slabbase(v, b, rg, t0 >> 5));
     const int lidx = wave * (16 * G) + (has_head ? lane : 0);
