@@ -277,9 +277,28 @@ def _cat(a, b):
     return b if a is None else np.concatenate([a, b], axis=1)
 
 
+def fold_rotation(w: np.ndarray, cfg: OracleConfig, perm: Optional[np.ndarray] = None) -> np.ndarray:
+    """Offline folding of the key rotation and reorder into a projection (Sec. 4.2, Sec. 4.4).
+
+    w: [rows, E], the key projection with the E output channels along the last axis, so that
+    keys = x @ w.  Returns w' with x @ w' = reorder(rotate(x @ w)): rotation and reorder are
+    linear maps on the output channels, so they act on every row of w.  (For the value rotation
+    call it with rot_heads = 1 and no perm.)
+    """
+    w = np.asarray(w, dtype=np.float64)
+    out = rotate_groups(w, cfg.n)
+    if perm is not None:
+        out = reorder(out, np.asarray(perm))
+    return out
+
+
 def quantize_append(cache: OracleCache, k: np.ndarray, v: np.ndarray,
-                    sink_mask: Optional[np.ndarray] = None) -> None:
+                    sink_mask: Optional[np.ndarray] = None, keys_rotated: bool = False) -> None:
     """Write half.  k, v: [B, n_new, Hkv, d] holding fp16 values, keys pre-RoPE.
+
+    keys_rotated: the keys come from a projection with the rotation and the reorder folded in
+    (fold_rotation), i.e. they already are what enters Eq. 6; a retained sink row is then brought
+    back to the original basis (inverse reorder, the same rotation again) and rounded to fp16.
 
     Keys: grouped-head rotation, then reorder, then Eq. 6-9 per token per block (Sec. 4.1-4.2,
     Table `tab:smooth`: rotate first, reorder second).  Values: optional per-head rotation, then
@@ -294,8 +313,14 @@ def quantize_append(cache: OracleCache, k: np.ndarray, v: np.ndarray,
     k16 = np.asarray(k, dtype=np.float16)
     v16 = np.asarray(v, dtype=np.float16)
     x = k16.astype(np.float64).reshape(B, n_new, E)
-    y = rotate_groups(x, cfg.n)
-    z = reorder(y, cache.perm)
+    if keys_rotated:
+        z = x
+        k_orig = rotate_groups(reorder_inverse(z, cache.perm), cfg.n)
+        k_sink16 = k_orig.astype(np.float16).reshape(k16.shape)
+    else:
+        y = rotate_groups(x, cfg.n)
+        z = reorder(y, cache.perm)
+        k_sink16 = k16
     kc, ks, kz = quantize(z, cfg.quant_group, cfg.bits)
     u = v16.astype(np.float64).reshape(B, n_new, E)
     if cfg.v_rotate:
@@ -307,7 +332,7 @@ def quantize_append(cache: OracleCache, k: np.ndarray, v: np.ndarray,
             for t in range(n_new):
                 if m[b, t] and len(cache.sink_pos[b]) < cfg.max_sinks:
                     cache.sink_pos[b].append(cache.length + t)
-                    cache.sink_k[b].append(k16[b, t].copy())
+                    cache.sink_k[b].append(k_sink16[b, t].copy())
                     cache.sink_v[b].append(v16[b, t].copy())
     cache.k_codes, cache.k_scale, cache.k_zero = _cat(cache.k_codes, kc), _cat(cache.k_scale, ks), _cat(cache.k_zero, kz)
     cache.v_codes, cache.v_scale, cache.v_zero = _cat(cache.v_codes, vc), _cat(cache.v_scale, vs), _cat(cache.v_zero, vz)

@@ -418,3 +418,55 @@ def test_select_sinks_brute_force():
                     best = t
             chosen.append(best)
         assert O.select_sinks(x, k).tolist() == sorted(chosen)
+
+
+def test_fold_rotation_is_the_rotation_moved_into_the_weights():
+    """Linearity pin: projecting with the folded matrix equals projecting, rotating and reordering
+    (matrix products associate), for each rotation size and with a reorder."""
+    rng = np.random.default_rng(21)
+    for g in (1, 2, 4):
+        cfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=g)
+        E = cfg.E
+        w = rng.standard_normal((24, E))
+        x = rng.standard_normal((5, 24))
+        perm = np.concatenate([128 * blk + rng.permutation(128) for blk in range(E // 128)])
+        direct = O.reorder(O.rotate_groups(x @ w, cfg.n), perm)
+        folded = x @ O.fold_rotation(w, cfg, perm)
+        assert np.allclose(direct, folded, rtol=0, atol=1e-12)
+        # folding twice with the inverse order gives the matrix back (H is an involution)
+        back = O.rotate_groups(O.reorder_inverse(O.fold_rotation(w, cfg, perm), perm), cfg.n)
+        assert np.allclose(back, w, rtol=0, atol=1e-12)
+
+
+def test_append_of_rotated_keys_equals_append_of_plain_keys():
+    """With a rotation over 2 heads the Hadamard entries are +-1/16, so keys that are multiples of
+    16 have rotated images that are integers below 2048, exact in fp16: the folded-weights path fed
+    with them must build the very same cache, sink rows included."""
+    rng = np.random.default_rng(22)
+    cfg = O.OracleConfig(batch=2, n_q_heads=4, n_kv_heads=4, rot_heads=2, max_sinks=2)
+    E = cfg.E
+    perm = np.concatenate([128 * blk + rng.permutation(128) for blk in range(E // 128)])
+    k = (16.0 * rng.integers(-40, 41, size=(2, 9, 4, 128))).astype(np.float16)    # a wide range keeps x / scale off exact ties
+    v = rng.standard_normal((2, 9, 4, 128)).astype(np.float16)
+    mask = np.zeros((2, 9), dtype=np.uint8)
+    mask[0, 0] = mask[1, 4] = 1
+    a = O.cache_new(cfg, perm)
+    O.quantize_append(a, k, v, mask)
+    rot = O.reorder(O.rotate_groups(k.astype(np.float64).reshape(2, 9, E), cfg.n), perm)
+    assert np.abs(rot - np.rint(rot)).max() < 1e-12          # integers, up to the recursion's 1/sqrt(2) factors
+    rot = np.rint(rot)
+    assert np.array_equal(rot, rot.astype(np.float16).astype(np.float64))        # exact in fp16
+    b = O.cache_new(cfg, perm)
+    O.quantize_append(b, rot.reshape(2, 9, 4, 128).astype(np.float16), v, mask, keys_rotated=True)
+    for name in ("k_scale", "k_zero", "v_codes", "v_scale", "v_zero"):
+        assert np.array_equal(getattr(a, name), getattr(b, name)), name
+    # codes: equal, except where the exact integer key sits on a rounding tie of Eq. 6 (x / scale
+    # an exact half-integer), which the 1e-13 noise of the plain path's rotation may tip either way
+    ratio = b.k_rot / np.repeat(b.k_scale, 128, axis=-1)
+    tie = (ratio - np.floor(ratio)) == 0.5
+    assert np.array_equal(a.k_codes[~tie], b.k_codes[~tie]) and tie.mean() < 0.01
+    assert np.abs(a.k_codes.astype(int) - b.k_codes.astype(int)).max() <= 1
+    for s in range(2):
+        assert a.sink_pos[s] == b.sink_pos[s]
+        for ra, rb in zip(a.sink_k[s], b.sink_k[s]):
+            assert np.array_equal(ra, rb)
