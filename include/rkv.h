@@ -61,6 +61,12 @@ typedef struct rkv_config {
                         /* per-head Hadamard before quantizing and undoes it on the output       */
   float   rope_theta;   /* RoPE base, e.g. 10000 or 500000                                       */
   float   clip_ratio;   /* 1.0 (Eq. 8-9 with no clipping)                                        */
+  int32_t keys_rotated; /* 0: keys arrive in the original basis and are rotated and reordered    */
+                        /* here; 1: they come from a projection with rotation and reorder folded */
+                        /* in (Sec. 4.2; rkv_fold_rotation) and already are what enters Eq. 6.   */
+                        /* Needs rot_heads 2 or 4, perm_span = head_dim, v_rotate = 0.  A        */
+                        /* retained sink row is brought back to the original basis and rounded   */
+                        /* to fp16                                                               */
 } rkv_config;
 
 typedef struct rkv_cache rkv_cache;   /* opaque host object */
@@ -91,6 +97,16 @@ int rkv_cache_length(const rkv_cache* cache);
  * cfg->batch, max_tokens and max_sinks are ignored. */
 int rkv_calibrate_perm(const rkv_config* cfg, const void* dev_k_cal, int32_t n_tok,
                        int32_t* dev_perm_out, void* dev_scratch, void* stream);
+
+/* Offline folding of the key rotation and reorder into a projection (Sec. 4.2, Sec. 4.4): for a
+ * matrix with the E key channels along its rows' last axis (keys = x . W), every row is rotated by
+ * the grouped-head Hadamard and reordered, so that x . W' = reorder(rotate(x . W)).
+ *   dev_w, dev_w_out  [rows][E] fp32 (may be the same buffer)
+ *   dev_perm          [E] int32 reorder indices, or NULL for none
+ * Only n_kv_heads, head_dim and rot_heads of cfg are used (rot_heads = 1 and no perm fold the value
+ * rotation).  RKV_EINVAL if E * 4 bytes exceed the LDS of a compute unit. */
+int rkv_fold_rotation(const rkv_config* cfg, const float* dev_w, int32_t rows, const int32_t* dev_perm, float* dev_w_out,
+                      void* stream);
 
 /* Install reorder indices (Sec. 4.1).  Only valid on an empty cache.  Copies the indices to the
  * host to validate them (synchronises `stream`): RKV_EPERM if they are not a permutation of

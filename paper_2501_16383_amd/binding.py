@@ -19,7 +19,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
-    "rkv_calibrate_perm", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention",
+    "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention",
     "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
@@ -36,7 +36,7 @@ class _CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "max_tokens", "max_sinks", "rot_heads",
         "quant_group", "bits", "perm_span", "rope_style", "v_rotate")] + [
-        ("rope_theta", C.c_float), ("clip_ratio", C.c_float)]
+        ("rope_theta", C.c_float), ("clip_ratio", C.c_float), ("keys_rotated", C.c_int32)]
 
 
 @dataclass
@@ -55,11 +55,12 @@ class RkvConfig:
     v_rotate: int = 0
     rope_theta: float = 10000.0
     clip_ratio: float = 1.0
+    keys_rotated: int = 0
 
     def to_c(self) -> _CConfig:
         return _CConfig(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.max_tokens,
                         self.max_sinks, self.rot_heads, self.quant_group, self.bits, self.perm_span,
-                        self.rope_style, self.v_rotate, self.rope_theta, self.clip_ratio)
+                        self.rope_style, self.v_rotate, self.rope_theta, self.clip_ratio, self.keys_rotated)
 
     @property
     def E(self) -> int:
@@ -88,6 +89,7 @@ def load_library():
     lib.rkv_cache_length.argtypes = [vp]
     lib.rkv_calibrate_perm.argtypes = [cfgp, vp, i32, vp, vp, vp]
     lib.rkv_set_perm.argtypes = [vp, vp, vp]
+    lib.rkv_fold_rotation.argtypes = [cfgp, vp, i32, vp, vp, vp]
     lib.rkv_select_sinks.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.rkv_quantize_append.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
@@ -159,6 +161,20 @@ def calibrate_perm(cfg: RkvConfig, k_cal, scratch=None):
     _check(lib.rkv_calibrate_perm(C.byref(cc), _ptr(k_cal), k_cal.shape[0], _ptr(perm), _ptr(scratch), _stream()),
            "rkv_calibrate_perm")
     return perm
+
+
+def fold_rotation(cfg: RkvConfig, w, perm=None):
+    """rkv_fold_rotation: w [rows, E] fp32 on the device -> the same shape with rotation (and reorder) folded in."""
+    import torch
+    lib = load_library()
+    w = _dev(w, torch.float32, "w")
+    perm = _dev(perm, torch.int32, "perm")
+    if w.dim() != 2 or w.shape[1] != cfg.E:
+        raise ValueError("w must be [rows, E]")
+    out = torch.empty_like(w)
+    cc = cfg.to_c()
+    _check(lib.rkv_fold_rotation(C.byref(cc), _ptr(w), w.shape[0], _ptr(perm), _ptr(out), _stream()), "rkv_fold_rotation")
+    return out
 
 
 def select_sinks(x, k: int, want_mask: bool = True):

@@ -24,6 +24,8 @@ static int check_config(const rkv_config* c, bool need_capacity) {
   if (c->perm_span != RKV_D && c->perm_span != n && c->perm_span != E) return RKV_EINVAL;
   if (c->rope_style != 0 && c->rope_style != 1) return RKV_EINVAL;
   if (c->v_rotate != 0 && c->v_rotate != 1) return RKV_EINVAL;
+  if (c->keys_rotated != 0 && c->keys_rotated != 1) return RKV_EINVAL;
+  if (c->keys_rotated && ((c->rot_heads != 2 && c->rot_heads != 4) || c->perm_span != RKV_D || c->v_rotate)) return RKV_EINVAL;
   if (!(c->rope_theta > 1.0f)) return RKV_EINVAL;
   if (need_capacity) {
     if (c->batch < 1 || c->max_tokens < 1 || c->max_sinks < 0 || c->max_sinks > 64) return RKV_EINVAL;
@@ -126,6 +128,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.span = cfg->perm_span;
   v.rope_style = cfg->rope_style;
   v.v_rotate = cfg->v_rotate;
+  v.keys_rotated = cfg->keys_rotated;
   v.theta = cfg->rope_theta;
   rc = rkv_launch_init(c, true, (hipStream_t)stream);
   if (rc != RKV_OK) {
@@ -192,6 +195,15 @@ RKV_EXPORT int rkv_calibrate_perm(const rkv_config* cfg, const void* dev_k_cal, 
   if (rc != RKV_OK) return rc;
   if (!dev_k_cal || !dev_perm_out || !dev_scratch || n_tok < 1) return RKV_EINVAL;
   return rkv_launch_calibrate(cfg, (const __half*)dev_k_cal, n_tok, dev_perm_out, dev_scratch, (hipStream_t)stream);
+}
+
+RKV_EXPORT int rkv_fold_rotation(const rkv_config* cfg, const float* dev_w, int32_t rows, const int32_t* dev_perm,
+                                 float* dev_w_out, void* stream) {
+  if (!cfg || !dev_w || !dev_w_out || rows < 1) return RKV_EINVAL;
+  if (cfg->head_dim != RKV_D || cfg->n_kv_heads < 1 || cfg->n_kv_heads > 128) return RKV_EINVAL;
+  if (cfg->rot_heads != 1 && cfg->rot_heads != 2 && cfg->rot_heads != 4 && cfg->rot_heads != 8) return RKV_EINVAL;
+  if (cfg->n_kv_heads % cfg->rot_heads != 0) return RKV_EINVAL;
+  return rkv_launch_fold_rotation(cfg, dev_w, rows, dev_perm, dev_w_out, (hipStream_t)stream);
 }
 
 RKV_EXPORT int rkv_select_sinks(const void* dev_x, int32_t batch, int32_t n_tok, int32_t width, int32_t k, int32_t* dev_idx_out,

@@ -117,7 +117,7 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
     if (!((ts + 16 * ti < t_hi) && (ts + 16 * ti + 16 > t_lo))) return;   // no token of this call in the tile
     const int d = wave & 1, pph = wave >> 1;               // this wave: products pp = 2 pph + {0, 1} of dword half d
     const int col = lane & 15, q = lane >> 4;              // result: token `col` of the tile, rows 4q..4q+3
-    const float rs = rsqrtf((float)n);
+    const float rs = v.keys_rotated ? 1.0f : rsqrtf((float)n);   // rotated keys arrive normalised
     // the tile's keys go to LDS once, whole rows at a time (wave w: tokens 4w..4w+3)
     {
       constexpr int TPI = 64 / ROW16;                      // token rows per wave-wide 16-byte load
@@ -137,7 +137,20 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
     }
     __syncthreads();
     v4f acc[G][2];
-    {
+    if (v.keys_rotated) {
+      // the keys already are what enters Eq. 6, in reordered order: the lane only picks up, for each
+      // rotated channel it packs, the value at that channel's reordered position
+      const __half* xh = reinterpret_cast<const __half*>(lds) + col * (STRIDE16 * 8);
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const int chan = 128 * h + 32 * q + 8 * (2 * d + pph) + 4 * ppl + rr;
+            acc[h][ppl][rr] = __half2float(xh[v.pinv[rg * n + chan] - rg * n]);
+          }
+    } else {
       const uint4* xrow = reinterpret_cast<const uint4*>(lds) + col * STRIDE16 + q;   // lane (token col, k-group q)
       // A operands: lane (row m = lane & 15, k-group kg = lane >> 4) holds H_128[channel][32ks + 8kg + i],
       // channel = 32(m>>2) + 8(2d + pph) + 4 ppl + (m&3); the sign is the parity of (channel & k),
@@ -181,6 +194,8 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
             acc[0][ppl][rr] = x0 + x1; acc[1][ppl][rr] = x0 - x1;
           }
         }
+    }
+    {
       // min / max of this wave's quarter of every block: 8 values in the lane, then the four q groups
 #pragma unroll
       for (int a = 0; a < G; ++a) {

@@ -46,7 +46,7 @@ struct RkvView {
   int* gid;
   float2* rope;
   uint32_t* hop;     // Hadamard B-operand image for the FP4 matrix instruction: [8 tiles][64 lanes][4 dwords]
-  int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate;
+  int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate, keys_rotated;
   float theta;
 };
 
@@ -143,6 +143,7 @@ bool rkv_mfma_supported(const rkv_cache* c);
 void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, float* qr, hipStream_t s);
 void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, float* out, float* lse, hipStream_t s);
 int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s);
+int rkv_launch_fold_rotation(const rkv_config* cfg, const float* w, int rows, const int* perm, float* out, hipStream_t s);
 int rkv_launch_select_sinks(const __half* x, int batch, int n_tok, int width, int k, int32_t* idx_out, uint8_t* mask_out,
                             float* scratch, hipStream_t s);
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg);

@@ -108,6 +108,7 @@ __global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restri
   __shared__ int s_count[256];
   __shared__ int s_tok[64];
   __shared__ int s_new;
+  __shared__ float s_row[512];
   const int b = blockIdx.x, tid = threadIdx.x;
   const int cnt0 = v.sink_cnt[b];
   const int room = v.max_sinks - cnt0;
@@ -140,8 +141,29 @@ __global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restri
     const int t = s_tok[i];
     const size_t src = ((size_t)b * n_new + t) * v.E, dst = ((size_t)b * v.max_sinks + cnt0 + i) * v.E;
     for (int e = tid; e < v.E; e += 256) {
-      v.sink_k[dst + e] = k[src + e];
+      if (!v.keys_rotated) v.sink_k[dst + e] = k[src + e];
       v.sink_v[dst + e] = vv[src + e];
+    }
+    if (v.keys_rotated) {
+      // the keys arrived rotated and reordered: undo the reorder, rotate again (H is its own
+      // inverse), round to fp16 - group by group, butterflies in LDS (n <= 512 in this mode)
+      for (int rg = 0; rg < v.NRG; ++rg) {
+        const int gb = rg * v.n;
+        for (int c = tid; c < v.n; c += 256) s_row[c] = __half2float(k[src + v.pinv[gb + c]]);
+        __syncthreads();
+        for (int h = 1; h < v.n; h <<= 1) {
+          for (int j = tid; j < v.n / 2; j += 256) {
+            const int lo = ((j / h) * 2 * h) + (j % h), hi = lo + h;
+            const float a = s_row[lo], c2 = s_row[hi];
+            s_row[lo] = a + c2;
+            s_row[hi] = a - c2;
+          }
+          __syncthreads();
+        }
+        const float rs = rsqrtf((float)v.n);
+        for (int c = tid; c < v.n; c += 256) v.sink_k[dst + gb + c] = __float2half_rn(s_row[c] * rs);
+        __syncthreads();
+      }
     }
     if (tid == 0) v.sink_pos[b * v.max_sinks + cnt0 + i] = v.len + t;
   }

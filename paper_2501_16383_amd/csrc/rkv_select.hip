@@ -81,3 +81,37 @@ int rkv_launch_select_sinks(const __half* x, int batch, int n_tok, int width, in
   hipLaunchKernelGGL(k_topk_tokens, dim3(batch), dim3(256), 0, s, scratch, n_tok, k, idx_out, mask_out);
   return rkv_check_launch();
 }
+
+// ---------------------------------------------------------------------------------------------
+// Offline folding of rotation and reorder into a projection (Sec. 4.2, Sec. 4.4): each row of the
+// matrix is rotated group by group (butterflies in LDS, fp32) and gathered through the reorder
+// indices.  One workgroup per row; cold path.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_fold_rotation(const float* __restrict__ w, const int* __restrict__ perm, float* __restrict__ out,
+                                                       int E, int n) {
+  extern __shared__ float row[];
+  const size_t base = (size_t)blockIdx.x * E;
+  for (int c = threadIdx.x; c < E; c += 256) row[c] = w[base + c];
+  __syncthreads();
+  for (int h = 1; h < n; h <<= 1) {                 // Eq. 10 without the 1/sqrt(2) factors; h < n keeps a pair inside its group
+    for (int i = threadIdx.x; i < E / 2; i += 256) {
+      const int lo = ((i / h) * 2 * h) + (i % h), hi = lo + h;
+      const float a = row[lo], b = row[hi];
+      row[lo] = a + b;
+      row[hi] = a - b;
+    }
+    __syncthreads();
+  }
+  const float rs = rsqrtf((float)n);
+  for (int c = threadIdx.x; c < E; c += 256) out[base + c] = row[perm ? perm[c] : c] * rs;
+}
+
+int rkv_launch_fold_rotation(const rkv_config* cfg, const float* w, int rows, const int* perm, float* out, hipStream_t s) {
+  const int E = cfg->n_kv_heads * RKV_D, n = cfg->rot_heads * RKV_D;
+  const size_t lds = (size_t)E * 4;
+  if (lds > 64 * 1024) return RKV_EINVAL;
+  if (lds > 48 * 1024)
+    RKV_HIP_CHECK(hipFuncSetAttribute((const void*)k_fold_rotation, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(k_fold_rotation, dim3(rows), dim3(256), lds, s, w, perm, out, E, n);
+  return rkv_check_launch();
+}

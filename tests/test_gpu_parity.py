@@ -465,3 +465,76 @@ def test_empty_append_is_a_no_op():
     cache.quantize_append(empty, empty)
     assert cache.length == 9
     P.check_cache_against_oracle(cache, oc, "after empty append")
+
+
+def test_fold_rotation_matches_oracle():
+    """rkv_fold_rotation against the oracle: a projection with rotation and reorder folded in, for
+    the key rotation over 4 and 2 heads with a calibrated-style reorder and for the per-head value
+    rotation (rot_heads = 1, no reorder); fp32 butterflies against float64."""
+    rng = np.random.default_rng(31)
+    for g, hkv, with_perm in ((4, 8, True), (2, 4, True), (1, 4, False)):
+        cfg = R.RkvConfig(batch=1, n_q_heads=hkv, n_kv_heads=hkv, max_tokens=16, rot_heads=g)
+        E = cfg.E
+        w = rng.standard_normal((37, E)).astype(np.float32)
+        perm = np.concatenate([128 * blk + rng.permutation(128) for blk in range(E // 128)]).astype(np.int32) if with_perm else None
+        print(f"[case] fold rotation g={g} E={E} perm={with_perm}", flush=True)
+        got = R.fold_rotation(cfg, P.gpu(w), None if perm is None else P.gpu(perm))
+        torch.cuda.synchronize()
+        ref = O.fold_rotation(w.astype(np.float64), P.oracle_cfg(cfg), perm)
+        err = np.abs(got.cpu().numpy().astype(np.float64) - ref).max()
+        print(f"[parity] fold rotation: max abs err {err:.3e}")
+        assert err <= 2e-6 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("g", [4, 2])
+def test_rotated_keys_path(g):
+    """The deployment shape of Sec. 4.2: keys arrive already rotated and reordered (folded weights),
+    the write half only quantizes and packs.  Codes under the tie protocol (the input is exact, so
+    only exact ties of Eq. 6 remain), sink rows brought back to the original basis (fp32 on the
+    GPU, float64 in the oracle: equal up to one fp16 ulp at rounding ties), decode on both paths."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8)
+    T = 150
+    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=T, max_sinks=4, rot_heads=g, keys_rotated=1)
+    ocfg = P.oracle_cfg(cfg)
+    rng = np.random.default_rng(32)
+    perm = np.concatenate([128 * blk + rng.permutation(128) for blk in range(cfg.E // 128)]).astype(np.int32)
+    k, v, mask, q = P.make_case(w, cfg, T, sink_positions=[0, 1, 77, 149])
+    # what a projection with folded weights would emit: rotated, reordered, rounded to fp16
+    k_rot = O.reorder(O.rotate_groups(k.astype(np.float64).reshape(2, T, cfg.E), ocfg.n), perm).astype(np.float16)
+    k_rot = k_rot.reshape(k.shape)
+    cache = R.RkvCache(cfg)
+    cache.set_perm(P.gpu(perm))
+    oc = O.cache_new(ocfg, perm)
+    for a, b in ((0, 70), (70, 71), (71, T)):
+        print(f"[case] rotated keys g={g}: append {a}:{b}", flush=True)
+        cache.quantize_append(P.gpu(k_rot[:, a:b]), P.gpu(v[:, a:b]), P.gpu(mask[:, a:b]))
+        O.quantize_append(oc, k_rot[:, a:b], v[:, a:b], mask[:, a:b], keys_rotated=True)
+    torch.cuda.synchronize()
+    gexp, sk, sv = P.check_cache_against_oracle(cache, oc, f"rotated keys g={g}")
+    assert sk["mismatched_scales"] == 0
+    s = {kk: vv.cpu().numpy() for kk, vv in cache.export_sinks().items()}
+    for b in range(2):
+        assert s["count"][b] == len(oc.sink_pos[b])
+        for i, pos in enumerate(oc.sink_pos[b]):
+            assert s["pos"][b, i] == pos
+            ref16 = oc.sink_k[b][i].reshape(cfg.E)
+            got16 = s["k"][b, i]
+            ulp = np.abs(np.spacing(ref16)).astype(np.float64)
+            assert np.all(np.abs(got16.astype(np.float64) - ref16.astype(np.float64)) <= ulp), "sink key row off by more than one fp16 ulp"
+            assert np.mean(got16 != ref16) < 0.05        # sums of fp16 values often sit exactly on fp16 ties
+            assert np.array_equal(s["v"][b, i], oc.sink_v[b][i].reshape(cfg.E))
+    # decode: the oracle takes the GPU's codes and the GPU's sink rows
+    oc_g = oracle_from_export(oc, gexp)
+    oc_g.sink_k = [[s["k"][b, i].reshape(8, 128) for i in range(len(oc.sink_pos[b]))] for b in range(2)]
+    check_dequant(cache, oc_g)
+    for path in (1, 2):
+        cache.set_decode_path(path)
+        check_decode(cache, oc_g, q, tag=f"rotated keys path={path}")
+
+
+def test_rotated_keys_config_is_checked():
+    for bad in (dict(rot_heads=1), dict(rot_heads=8, n_kv_heads=8, n_q_heads=8), dict(v_rotate=1), dict(perm_span=512)):
+        kw = dict(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=16, rot_heads=4, keys_rotated=1)
+        kw.update(bad)
+        with pytest.raises(R.RkvError):
+            R.RkvCache(R.RkvConfig(**kw))
