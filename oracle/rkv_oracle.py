@@ -364,8 +364,14 @@ def dequantize_cache(cache: OracleCache, substitute_sinks: bool = False):
     return k_hat, v_hat
 
 
-def decode_attention(cache: OracleCache, q: np.ndarray, q_pos: Optional[np.ndarray] = None):
+def decode_attention(cache: OracleCache, q: np.ndarray, q_pos: Optional[np.ndarray] = None,
+                     k_cur: Optional[np.ndarray] = None, v_cur: Optional[np.ndarray] = None):
     """Read half: Eq. 5 over the cache as stored.
+
+    k_cur, v_cur ([B, Hkv, d] fp16 values, key pre-RoPE), if given, are the token being decoded,
+    not yet in the cache: it is attended in full precision at position T (the decoding procedure
+    that concatenates the new key and value to the dequantized cache before quantizing them);
+    q_pos then defaults to T.
 
     q: [B, Hq, d] fp16 values, pre-RoPE.  Keys are reconstructed (dequantize_cache), retained
     sink rows replace their reconstructions, RoPE is applied to every key at its token index and
@@ -378,6 +384,12 @@ def decode_attention(cache: OracleCache, q: np.ndarray, q_pos: Optional[np.ndarr
     B, T = cache.k_codes.shape[0], cache.length
     d = cfg.head_dim
     k_hat, v_hat = dequantize_cache(cache, substitute_sinks=True)
+    if k_cur is not None:
+        kc = np.asarray(k_cur, dtype=np.float16).astype(np.float64).reshape(B, 1, cfg.n_kv_heads, d)
+        vc = np.asarray(v_cur, dtype=np.float16).astype(np.float64).reshape(B, 1, cfg.n_kv_heads, d)
+        k_hat = np.concatenate([k_hat, kc], axis=1)
+        v_hat = np.concatenate([v_hat, vc], axis=1)
+        T = T + 1
     if q_pos is None:
         q_pos = np.full(B, T - 1, dtype=np.int64)
     q_pos = np.asarray(q_pos, dtype=np.int64)

@@ -470,3 +470,29 @@ def test_append_of_rotated_keys_equals_append_of_plain_keys():
         assert a.sink_pos[s] == b.sink_pos[s]
         for ra, rb in zip(a.sink_k[s], b.sink_k[s]):
             assert np.array_equal(ra, rb)
+
+
+def test_current_token_operand_equals_a_retained_row():
+    """Attending the token being decoded in full precision is the same as having appended it as a
+    retained (fp16) row: both put its exact key and value at position T."""
+    rng = np.random.default_rng(23)
+    cfg = O.OracleConfig(batch=2, n_q_heads=8, n_kv_heads=4, rot_heads=2, max_sinks=3)
+    k = rng.standard_normal((2, 21, 4, 128)).astype(np.float16)
+    v = rng.standard_normal((2, 21, 4, 128)).astype(np.float16)
+    q = rng.standard_normal((2, 8, 128)).astype(np.float16)
+    mask = np.zeros((2, 21), dtype=np.uint8)
+    mask[:, 0] = 1
+    a = O.cache_new(cfg)
+    O.quantize_append(a, k[:, :20], v[:, :20], mask[:, :20])
+    out_a, lse_a = O.decode_attention(a, q, None, k[:, 20], v[:, 20])
+    b = O.cache_new(cfg)
+    mask[:, 20] = 1
+    O.quantize_append(b, k, v, mask)
+    out_b, lse_b = O.decode_attention(b, q)
+    assert np.allclose(out_a, out_b, rtol=0, atol=1e-12) and np.allclose(lse_a, lse_b, rtol=0, atol=1e-12)
+    # and it differs from attending the quantized token
+    c = O.cache_new(cfg)
+    mask[:, 20] = 0
+    O.quantize_append(c, k, v, mask)
+    out_c, _ = O.decode_attention(c, q)
+    assert np.abs(out_c - out_a).max() > 1e-4
