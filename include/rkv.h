@@ -145,6 +145,16 @@ int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, 
 int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos,
                          float* dev_out, float* dev_lse, void* dev_scratch, void* stream);
 
+/* The same, with the token being decoded attended in full precision (the decoding procedure that
+ * concatenates the new key and value to the dequantized cache before they are quantized): the
+ * token is not in the cache yet; its fp16 key (pre-RoPE) and value take part as an exact row at
+ * position `length`, and dev_q_pos == NULL means `length`.  Call rkv_quantize_append for the token
+ * afterwards.  Works on an empty cache (the first decode step).
+ *   dev_k_cur, dev_v_cur  [batch][n_kv_heads][head_dim] fp16 */
+int rkv_decode_attention_with_current(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos,
+                                      const void* dev_k_cur, const void* dev_v_cur, float* dev_out,
+                                      float* dev_lse, void* dev_scratch, void* stream);
+
 /* Choose the decode kernel: 0 = automatic (default), 1 = force the general kernel (any supported
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
  * the configuration is outside what it covers). */

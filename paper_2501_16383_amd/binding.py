@@ -19,7 +19,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
-    "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention",
+    "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention", "rkv_decode_attention_with_current",
     "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
@@ -93,6 +93,7 @@ def load_library():
     lib.rkv_select_sinks.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.rkv_quantize_append.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.rkv_decode_attention_with_current.argtypes = [vp] * 9
     lib.rkv_set_decode_path.argtypes = [vp, i32]
     lib.rkv_set_profile_events.argtypes = [vp, vp, vp]
     lib.rkv_dequantize.argtypes = [vp, vp, vp, vp]
@@ -252,17 +253,28 @@ class RkvCache:
         _check(self.lib.rkv_quantize_append(self.handle, _ptr(k), _ptr(v), n_new, _ptr(sink_mask), _stream()),
                "rkv_quantize_append")
 
-    def decode_attention(self, q, q_pos=None, out=None, lse=None, want_lse=False):
+    def decode_attention(self, q, q_pos=None, out=None, lse=None, want_lse=False, k_cur=None, v_cur=None):
         import torch
         q = _dev(q, torch.float16, "q")
         q_pos = _dev(q_pos, torch.int32, "q_pos")
+        k_cur = _dev(k_cur, torch.float16, "k_cur")
+        v_cur = _dev(v_cur, torch.float16, "v_cur")
         cfg = self.cfg
+        if (k_cur is None) != (v_cur is None):
+            raise ValueError("k_cur and v_cur go together")
+        if k_cur is not None and (k_cur.shape != (cfg.batch, cfg.n_kv_heads, cfg.head_dim) or v_cur.shape != k_cur.shape):
+            raise ValueError("k_cur, v_cur must be [batch, n_kv_heads, head_dim]")
         if q.shape != (cfg.batch, cfg.n_q_heads, cfg.head_dim):
             raise ValueError("q must be [batch, n_q_heads, head_dim]")
         if out is None:
             out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
         if lse is None and want_lse:
             lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+        if k_cur is not None:
+            _check(self.lib.rkv_decode_attention_with_current(self.handle, _ptr(q), _ptr(q_pos), _ptr(k_cur), _ptr(v_cur), _ptr(out),
+                                                              _ptr(lse), _ptr(self.scratch), _stream()),
+                   "rkv_decode_attention_with_current")
+            return (out, lse) if want_lse else out
         _check(self.lib.rkv_decode_attention(self.handle, _ptr(q), _ptr(q_pos), _ptr(out), _ptr(lse),
                                              _ptr(self.scratch), _stream()), "rkv_decode_attention")
         return (out, lse) if want_lse else out

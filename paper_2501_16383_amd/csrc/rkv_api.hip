@@ -225,10 +225,21 @@ RKV_EXPORT int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const vo
   return rc;
 }
 
+RKV_EXPORT int rkv_decode_attention_with_current(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos,
+                                                 const void* dev_k_cur, const void* dev_v_cur, float* dev_out,
+                                                 float* dev_lse, void* dev_scratch, void* stream) {
+  if (!cache || !dev_k_cur || !dev_v_cur) return RKV_EINVAL;
+  cache->cur_k = (const __half*)dev_k_cur;
+  cache->cur_v = (const __half*)dev_v_cur;
+  const int rc = rkv_decode_attention(cache, dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, stream);
+  cache->cur_k = cache->cur_v = nullptr;
+  return rc;
+}
+
 RKV_EXPORT int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, float* dev_out,
                                     float* dev_lse, void* dev_scratch, void* stream) {
   if (!cache || !dev_q || !dev_out || !dev_scratch) return RKV_EINVAL;
-  if (cache->v.len < 1) return RKV_ESTATE;
+  if (cache->v.len < 1 && !cache->cur_k) return RKV_ESTATE;
   bool fast = rkv_mfma_supported(cache);
   if (cache->decode_path == 2 && !fast) return RKV_EINVAL;
   if (cache->decode_path == 1) fast = false;

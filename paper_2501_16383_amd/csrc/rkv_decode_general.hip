@@ -35,9 +35,9 @@ __device__ inline void fwht_lanes_d(T (&x)[PL], int lane, int xstages) {
 
 // q~[b][h][c] = RoPE(q, q_pos)[c] / sqrt(128), angles in double (q_pos may lie beyond the table).
 __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restrict__ q, const int* __restrict__ q_pos,
-                                                float* __restrict__ qr) {
+                                                int default_pos, float* __restrict__ qr) {
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
-  const int pos = q_pos ? q_pos[b] : v.len - 1;
+  const int pos = q_pos ? q_pos[b] : default_pos;
   const size_t base = ((size_t)b * v.Hq + h) * RKV_D;
   int j, partner;
   float sgn;
@@ -201,11 +201,13 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
 // addresses do not depend on loaded data are issued up front (two dependent round trips in all).
 #define MERGE_MAX_CH 512
 __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restrict__ qr, const float* __restrict__ part,
-                                               int nch, float* __restrict__ out, float* __restrict__ lse) {
+                                               int nch, const __half* __restrict__ k_cur, const __half* __restrict__ v_cur,
+                                               float* __restrict__ out, float* __restrict__ lse) {
   __shared__ float s_w[MERGE_MAX_CH];     // chunk maxima, then chunk weights
   __shared__ float s_l[MERGE_MAX_CH];
   __shared__ float s_part[2][64];         // per-wave partial sink scores
   __shared__ float s_score[64];
+  __shared__ float s_cur[2];
   __shared__ float red[128];
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x, lane = c & 63, wave = c >> 6;
   const int kvh = h / (v.Hq / v.Hkv);
@@ -232,13 +234,27 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
     for (int o = 32; o > 0; o >>= 1) d += __shfl_xor(d, o);
     if (lane == 0) s_part[wave][s] = d;
   }
+  // the token being decoded, if it is attended in full precision: an exact row at position len
+  // (which may lie one past the angle table, so its angles are computed here)
+  float cur_score = -INFINITY;
+  if (k_cur) {
+    const __half* kr = k_cur + ((size_t)b * v.Hkv + kvh) * RKV_D;
+    double sn, cs;
+    sincos((double)v.len * pow((double)v.theta, -(double)j / 64.0), &sn, &cs);
+    const float x = __half2float(kr[c]), p = __half2float(kr[partner]);
+    float d = qc * (x * (float)cs + sgn * p * (float)sn);
+    for (int o = 32; o > 0; o >>= 1) d += __shfl_xor(d, o);
+    if (lane == 0) s_cur[wave] = d;
+  }
   __syncthreads();
   if (c < cnt) s_score[c] = s_part[0][c] + s_part[1][c];
+  if (k_cur) cur_score = s_cur[0] + s_cur[1];
   __syncthreads();
 
   float M = -INFINITY;
   for (int k = 0; k < nch; ++k) M = fmaxf(M, s_w[k]);
   for (int s = 0; s < cnt; ++s) M = fmaxf(M, s_score[s]);
+  M = fmaxf(M, cur_score);
   float L = 0.f, acc = 0.f;
   for (int k = 0; k < nch; ++k) {
     const float mk = s_w[k];
@@ -262,15 +278,21 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
     L += w;
     acc += w * __half2float(v.sink_v[((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D + c]);
   }
+  if (k_cur) {
+    const float w = __expf(cur_score - M);
+    L += w;
+    acc += w * __half2float(v_cur[((size_t)b * v.Hkv + kvh) * RKV_D + c]);
+  }
   out[qbase + c] = acc / L;
   if (lse && c == 0) lse[(size_t)b * v.Hq + h] = M + logf(L);
 }
 
-void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, float* qr, hipStream_t s) {
-  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, qr);
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, hipStream_t s) {
+  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, default_pos, qr);
 }
-void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, float* out, float* lse, hipStream_t s) {
-  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, out, lse);
+void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, const __half* k_cur, const __half* v_cur,
+                      float* out, float* lse, hipStream_t s) {
+  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, k_cur, v_cur, out, lse);
 }
 
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
@@ -287,7 +309,7 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
-  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, qr);
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, s);
   const int rep = v.Hq / v.Hkv, nq = rep * v.g;
   const size_t lds = ((size_t)nq * RKV_D + (size_t)nq * GEN_CHUNK + 2 * (size_t)v.g * GEN_CHUNK + 2 * nq) * 4;
   dim3 grid(nch, v.NRG, v.B);
@@ -301,8 +323,8 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   }
   if (lds > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, qr, part, nch);
+  if (nch > 0) hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, qr, part, nch);   // an empty cache has only the current token
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
-  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, out, lse);
+  rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, out, lse, s);
   return rkv_check_launch();
 }

@@ -468,13 +468,14 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, floa
   const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
-  rkv_launch_prep_q(v, q, q_pos, qr, s);
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   dim3 grid(((nch + 7) & ~7) * (v.Hq / v.Hkv), v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  if (v.g == 4) hipLaunchKernelGGL(k_decode_mfma<4>, grid, dim3(256), 0, s, v, qt, part, nch);
+  if (nch == 0) {}                                          // an empty cache has only the current token
+  else if (v.g == 4) hipLaunchKernelGGL(k_decode_mfma<4>, grid, dim3(256), 0, s, v, qt, part, nch);
   else hipLaunchKernelGGL(k_decode_mfma<2>, grid, dim3(256), 0, s, v, qt, part, nch);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
-  rkv_launch_merge(v, qr, part, nch, out, lse, s);
+  rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, out, lse, s);
   return rkv_check_launch();
 }

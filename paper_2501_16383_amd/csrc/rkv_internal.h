@@ -60,6 +60,8 @@ struct rkv_cache {
   int decode_path;
   int n_cu;               // compute units of the device the cache lives on
   hipEvent_t ev_start, ev_stop;   // optional measurement hook around the main kernels
+  const __half* cur_k;    // set for the duration of a decode call that attends the token being decoded
+  const __half* cur_v;    // in full precision ([batch][n_kv_heads][128] fp16 each), else null
 };
 
 // offset (in dwords) of rotated channel c (within its rotation group) of token m inside a K tile
@@ -140,8 +142,9 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
                            hipStream_t s);
 bool rkv_mfma_supported(const rkv_cache* c);
-void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, float* qr, hipStream_t s);
-void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, float* out, float* lse, hipStream_t s);
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, hipStream_t s);
+void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, const __half* k_cur, const __half* v_cur,
+                      float* out, float* lse, hipStream_t s);
 int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s);
 int rkv_launch_fold_rotation(const rkv_config* cfg, const float* w, int rows, const int* perm, float* out, hipStream_t s);
 int rkv_launch_select_sinks(const __half* x, int batch, int n_tok, int width, int k, int32_t* idx_out, uint8_t* mask_out,

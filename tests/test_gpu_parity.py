@@ -538,3 +538,37 @@ def test_rotated_keys_config_is_checked():
         kw.update(bad)
         with pytest.raises(R.RkvError):
             R.RkvCache(R.RkvConfig(**kw))
+
+
+@pytest.mark.parametrize("T", [0, 1, 77])
+def test_current_token_attended_in_full_precision(T):
+    """rkv_decode_attention_with_current: the token being decoded takes part as an exact fp16 row at
+    position `length`, also on an empty cache and with GQA; then it is appended and the next step
+    sees it quantized."""
+    w = small("cfg1", n_q_heads=16, n_kv_heads=8)
+    cfg = R.RkvConfig(batch=2, n_q_heads=16, n_kv_heads=8, max_tokens=128, max_sinks=2, rot_heads=4)
+    k, v, mask, q = P.make_case(w, cfg, T + 1, sink_positions=[0] if T > 0 else [])
+    cache = R.RkvCache(cfg)
+    oc = O.cache_new(P.oracle_cfg(cfg))
+    if T > 0:
+        cache.quantize_append(P.gpu(k[:, :T]), P.gpu(v[:, :T]), P.gpu(mask[:, :T]))
+        O.quantize_append(oc, k[:, :T], v[:, :T], mask[:, :T])
+        gexp = P.export_numpy(cache)
+        oc = oracle_from_export(oc, gexp)                      # same codes on both sides
+    kc, vc = k[:, T], v[:, T]
+    for path in (1, 2):
+        cache.set_decode_path(path)
+        print(f"[case] current token T={T} path={path}", flush=True)
+        out, lse = cache.decode_attention(P.gpu(q), want_lse=True, k_cur=P.gpu(kc), v_cur=P.gpu(vc))
+        torch.cuda.synchronize()
+        if T == 0:
+            ref = np.repeat(vc.astype(np.float64), 2, axis=1)  # softmax over one row: the value itself
+            assert np.abs(out.cpu().numpy() - ref).max() <= 1e-6 * np.abs(ref).max() + 1e-7
+            continue
+        ref, lse_ref = O.decode_attention(oc, q, None, kc, vc)
+        e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
+        le = float(np.abs(lse.cpu().numpy() - lse_ref).max())
+        print(f"[parity] current token T={T} path={path}: out err {e:.3e} lse err {le:.3e}", flush=True)
+        assert e <= ATT_TOL and le <= LSE_TOL
+    cache.quantize_append(P.gpu(k[:, T:]), P.gpu(v[:, T:]))
+    assert cache.length == T + 1
