@@ -50,9 +50,16 @@ __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restr
     partner = c ^ 1;
     sgn = (c & 1) ? 1.f : -1.f;
   }
-  const double freq = pow((double)v.theta, -(double)j / 64.0);
+  // angles: from the table (computed in double, stored as float) when the position lies inside
+  // it - the usual case -, else computed here
   double sn, cs;
-  sincos((double)pos * freq, &sn, &cs);
+  if (pos >= 0 && pos < v.Tpad) {
+    const float2 t = v.rope[(size_t)pos * 64 + j];
+    cs = t.x;
+    sn = t.y;
+  } else {
+    sincos((double)pos * pow((double)v.theta, -(double)j / 64.0), &sn, &cs);
+  }
   const float x = __half2float(q[base + c]), p = __half2float(q[base + partner]);
   const float val = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
   qr[base + c] = val;
