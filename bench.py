@@ -196,6 +196,7 @@ def main():
     kern_ms = [hip.elapsed_ms(a, b) for step in ev for (a, b) in step]
     avg_ms = sum(kern_ms) / len(kern_ms)
     min_ms = min(kern_ms)
+    med_ms = sorted(kern_ms)[len(kern_ms) // 2]
     ctx = T - (K - 1) / 2.0
     bytes_per_tok = 2 * E // 4 + 2 * (E // 128) * 4
     launch_bytes = B * ctx * bytes_per_tok
@@ -219,13 +220,15 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": wall / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u2 codes + fp16 scale/zero; fp4 matrix products and fp32 accumulate",
+        "dtype": "f32",   # what the path accumulates in; storage is u2 codes + fp16 scale/zero, the rotations are exact fp4 / fp16 matrix products
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {SHAPES.get(w.name, 'custom')} decode, {L} layers x {w.n_q_heads} query / {w.n_kv_heads} KV heads x 128, "
                                f"batch {B}, context {T}, rotation over {w.rot_heads} heads, 2-bit group-128, {w.n_sinks} fp16 sinks",
-                   "decode_path": args.path},
+                   "decode_path": args.path,
+                   "storage": "u2 codes + fp16 scale / fp16 zero per 128 (2.25 bits per element)",
+                   "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "min_launch_ms": min_ms,
+                     "traffic": traffic, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms, "launches_timed": len(kern_ms),
                      "algorithmic_bytes_per_launch": launch_bytes, "bytes_per_kv_token": bytes_per_tok},
         "append_bulk": {"GB/s_best": bulk_bytes / (bulk_best * 1e-3) / 1e9, "GB/s_avg": bulk_bytes / (bulk_avg * 1e-3) / 1e9,
                         "frac_of_hbm_peak_best": bulk_bytes / (bulk_best * 1e-3) / 1e9 / HBM_PEAK_GBS,
