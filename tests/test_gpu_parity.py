@@ -273,7 +273,7 @@ def export_host(cache):
 
 
 def test_full_size_config2_sampled():
-    """BASELINE configuration 2 at full size (batch 16, 40 heads, context 4096), in the launch
+    """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, one single-token append, decode on
     the matrix-core path.  The oracle recomputes sampled (sequence, rotation group) slices - a
     rotation group's codes and attention outputs depend on nothing outside the slice."""
