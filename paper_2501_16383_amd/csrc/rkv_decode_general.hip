@@ -35,7 +35,7 @@ __device__ inline void fwht_lanes_d(T (&x)[PL], int lane, int xstages) {
 
 // q~[b][h][c] = RoPE(q, q_pos)[c] / sqrt(128), angles in double (q_pos may lie beyond the table).
 __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restrict__ q, const int* __restrict__ q_pos,
-                                                int default_pos, float* __restrict__ qr) {
+                                                int default_pos, float* __restrict__ qr, int share) {
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
   const int pos = q_pos ? q_pos[b] : default_pos;
   const size_t base = ((size_t)b * v.Hq + h) * RKV_D;
@@ -63,15 +63,17 @@ __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restr
   const float x = __half2float(q[base + c]), p = __half2float(q[base + partner]);
   const float val = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
   qr[base + c] = val;
-  // second copy for the matrix-core kernel: [b][rot group][rr][n 0..15][p 0..3][KV head a][lo, hi]
-  // (rr = which of the query heads sharing KV head a) with
+  // second copy for the matrix-core kernel: [b][rot group][rr / share][n 0..15][p 0..3][KV head a][rr % share][lo, hi]
+  // (rr = which of the query heads sharing KV head a; one workgroup serves `share` of them) with
   // entry (n, p, half) = channel 16p + n + 64*half, pre-multiplied by 2/sqrt(rotation size)
   // (FP4 nibbles hold code/2; 1/sqrt(n) is the normalisation of Eq. 10)
   const int g = v.g, rep = v.Hq / v.Hkv;
   const int kvh = h / rep, rr = h - kvh * rep, rg = kvh / g, a = kvh - rg * g;
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;
   const int nn = c & 15, pp = (c >> 4) & 3, half = c >> 6;
-  qt[((((((size_t)b * v.NRG + rg) * rep + rr) * 16 + nn) * 4 + pp) * g + a) * 2 + half] = val * 2.0f * rsqrtf((float)v.n);
+  const int rrg = rr / share, rri = rr - rrg * share;
+  qt[(((((((size_t)b * v.NRG + rg) * (rep / share) + rrg) * 16 + nn) * 4 + pp) * g + a) * share + rri) * 2 + half] =
+      val * 2.0f * rsqrtf((float)v.n);
 }
 
 __device__ inline bool is_sink(const int* sp, int cnt, int t) {
@@ -294,8 +296,8 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   if (lse && c == 0) lse[(size_t)b * v.Hq + h] = M + logf(L);
 }
 
-void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, hipStream_t s) {
-  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, default_pos, qr);
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, int share, hipStream_t s) {
+  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, default_pos, qr, share);
 }
 void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, const __half* k_cur, const __half* v_cur,
                       float* out, float* lse, hipStream_t s) {
@@ -316,7 +318,7 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
-  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, s);
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, 1, s);
   const int rep = v.Hq / v.Hkv, nq = rep * v.g;
   const size_t lds = ((size_t)nq * RKV_D + (size_t)nq * GEN_CHUNK + 2 * (size_t)v.g * GEN_CHUNK + 2 * nq) * 4;
   dim3 grid(nch, v.NRG, v.B);

@@ -25,8 +25,9 @@
 //   phase V  wave w: channels 32w..32w+31 of every head; A = weight digits [16 x (4 heads x 32
 //            tokens)], block-diagonal over heads, B = codes [(4 heads x 32 tokens) x 16 channels].
 // Covers: reorder that keeps 128-blocks (gid[c] == c/128), rot_heads 2 or 4, half-split RoPE
-// pairs.  With GQA every group of query heads (one per KV head) gets its own workgroup, which
-// repeats the key-side work.  Everything else takes the general kernel.
+// pairs.  With GQA a workgroup serves up to 4 of the query heads that share a KV head: unpacking,
+// rotation and RoPE of the keys are done once for them, the softmax and value phases once per
+// query head.  Everything else takes the general kernel.
 #include "rkv_internal.h"
 
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -137,16 +138,18 @@ __device__ __forceinline__ float wave_allreduce(float x) {
   return op(op(r0, r1), op(r2, r3));
 }
 
-template <int G>
-__global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt, float* __restrict__ part,
-                                                        int nch) {
-  __shared__ float s_sc[G][MF_CH];
+template <int G, int REP>
+__global__ void __launch_bounds__(256, REP > 1 ? 2 : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
+                                                                       float* __restrict__ part, int nch) {
+  constexpr int NH = G * REP;                    // query heads served by this workgroup: REP per KV head
+  constexpr int AP = (4 / REP < G) ? 4 / REP : G; // KV heads per pass of the key phase: 16 score accumulators at most
+  __shared__ float s_sc[NH][MF_CH];
   __shared__ __attribute__((aligned(16))) uint8_t s_A[MF_CH / 32][2][16][4][32];   // [slab][digit set][row][lane group][bytes]
   __shared__ float s_m[4], s_l[4], s_zs[4], s_wsc[4];
   __shared__ int s_sink[4][64];
   __shared__ uint4 s_H[8][64];                   // Hadamard operand tiles
   __shared__ float2 s_step[64];                  // RoPE rotation by 16 positions, per channel pair
-  __shared__ __attribute__((aligned(16))) float s_q[16][4][2 * G];   // query [n][p][head][lo, hi]
+  __shared__ __attribute__((aligned(16))) float s_q[16][4][2 * NH];  // query [n][p][KV head][query head of it][lo, hi]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -177,11 +180,13 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   const uint32_t sm01 = ((__popc(hrow & 1) & 1) ? 0x80000000u : 0u);
   const uint32_t sm23 = ((__popc(hrow & 2) & 1) ? 0x00008000u : 0u) | ((__popc(hrow & 3) & 1) ? 0x80000000u : 0u);
 
-  // blockIdx.x = rr * nch8 + chunk, nch8 = chunk count rounded up to 8: the workgroups that serve
-  // the `rep` query heads sharing a KV head (GQA) re-read the same chunk, and with ids a multiple of
-  // 8 apart they land on the same XCD, whose L2 then holds the chunk for the later ones
+  // Of the `rep` query heads that share a KV head (GQA) one workgroup serves REP, so that unpacking,
+  // rotation and RoPE of the keys are done once for them.  blockIdx.x = rrg * nch8 + chunk, nch8 =
+  // chunk count rounded up to 8: if rep > REP the workgroups of the other query-head groups re-read
+  // the same chunk, and with ids a multiple of 8 apart they land on the same XCD, whose L2 then
+  // holds the chunk for the later ones
   const int nch8 = (nch + 7) & ~7;
-  const int rr = blockIdx.x / nch8, chunk = blockIdx.x - rr * nch8;
+  const int rrg = blockIdx.x / nch8, chunk = blockIdx.x - rrg * nch8;
   const int rg = blockIdx.y, b = blockIdx.z;
   if (chunk >= nch) return;
   const int rep = v.Hq / v.Hkv;
@@ -191,10 +196,10 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   // phase K needs no workgroup barrier before it
   s_sink[wave][lane] = lane < cnt ? v.sink_pos[b * v.max_sinks + lane] : -1;
 #pragma unroll
-  for (int a = 0; a < G; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
-  // query of this rotation group, already RoPE'd, scaled and laid out [n][p][head][lo, hi] by k_prep_q
-  if (tid < 16 * 4 * 2 * G / 4)
-    reinterpret_cast<uint4*>(&s_q[0][0][0])[tid] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * rep + rr) * (16 * 4 * 2 * G))[tid];
+  for (int a = 0; a < NH; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
+  // queries of this rotation group, already RoPE'd, scaled and laid out as s_q by k_prep_q
+  for (int i = tid; i < 16 * 4 * 2 * NH / 4; i += 256)
+    reinterpret_cast<uint4*>(&s_q[0][0][0])[i] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (16 * 4 * 2 * NH))[i];
   {
     // ------------------------------------------------------------------ phase K
     {
@@ -262,9 +267,16 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         }
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
 
-        float pt[4 * G];                                   // [r][a]
+        const float* sq = &s_q[n][0][0];
+        // The key phase runs in passes over AP of the G KV heads, so that the score accumulators
+        // (4 tokens x AP heads x REP query heads) stay within 16 registers - more of them and the
+        // compiler's allocation leaves the 256-register budget; a pass repeats the matrix products
+        // and the packing, which costs less than repeating RoPE per query head.
 #pragma unroll
-        for (int i = 0; i < 4 * G; ++i) pt[i] = 0.f;
+        for (int a0 = 0; a0 < G; a0 += AP) {
+        float pt[4 * AP * REP];                            // [r][KV head of the pass][query head of it]
+#pragma unroll
+        for (int i = 0; i < 4 * AP * REP; ++i) pt[i] = 0.f;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           // H_128 of the raw codes for channels 16p + n (lo) and 16p + n + 64 (hi): half-integers, exact
@@ -281,10 +293,10 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
               hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
             }
           }
-          float qv[2 * G];
+          float qv[2 * AP * REP];                            // [KV head of the pass][query head][lo, hi]
 #pragma unroll
-          for (int i = 0; i < 2 * G; i += 4) {
-            const uint4 u = *reinterpret_cast<const uint4*>(&s_q[n][p][i]);
+          for (int i = 0; i < 2 * AP * REP; i += 4) {
+            const uint4 u = *reinterpret_cast<const uint4*>(sq + p * (2 * NH) + 2 * REP * a0 + i);
             qv[i] = __uint_as_float(u.x); qv[i + 1] = __uint_as_float(u.y); qv[i + 2] = __uint_as_float(u.z); qv[i + 3] = __uint_as_float(u.w);
           }
           float c = cs_c[p], s = cs_s[p];                      // token 4q: r = 0
@@ -306,10 +318,14 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), z4);
             }
 #pragma unroll
-            for (int a = 0; a < G; ++a) {
-              const float xl = klo[a] * c - khi[a] * s;
-              const float xh = klo[a] * s + khi[a] * c;
-              pt[r * G + a] = fmaf(xh, qv[2 * a + 1], fmaf(xl, qv[2 * a], pt[r * G + a]));
+            for (int al = 0; al < AP; ++al) {
+              const float xl = klo[a0 + al] * c - khi[a0 + al] * s;
+              const float xh = klo[a0 + al] * s + khi[a0 + al] * c;
+#pragma unroll
+              for (int rri = 0; rri < REP; ++rri) {
+                const int o = (r * AP + al) * REP + rri, qo = 2 * (al * REP + rri);
+                pt[o] = fmaf(xh, qv[qo + 1], fmaf(xl, qv[qo], pt[o]));
+              }
             }
             if (r < 3) {                                       // next token: one position further
               const float c1 = c * s1_c[p] - s * s1_s[p];
@@ -318,21 +334,41 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
             }
           }
         }
-        // advance the RoPE state by 16 positions
+        if (a0 + AP >= G) {
+          // after the last pass: advance the RoPE state by 16 positions
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const float c = cs_c[p], s = cs_s[p];
-          const float2 st = s_step[16 * p + n];
-          cs_c[p] = c * st.x - s * st.y;
-          cs_s[p] = s * st.x + c * st.y;
+          for (int p = 0; p < 4; ++p) {
+            const float c = cs_c[p], s = cs_s[p];
+            const float2 st = s_step[16 * p + n];
+            cs_c[p] = c * st.x - s * st.y;
+            cs_s[p] = s * st.x + c * st.y;
+          }
         }
-        // reduce over the 16 channel lanes: lane n gets (token 4q + n / G, head n % G)
-        const float tot = row_transpose_reduce<4 * G>(pt, n);
-        const int idx = n & (4 * G - 1);
-        const int tok = tt + 4 * q + idx / G, a = idx % G;
-        bool masked = tok >= len;
-        for (int i = 0; i < cnt; ++i) masked |= (s_sink[wave][i] == tok);
-        if (n < 4 * G && !masked) s_sc[a][tok - t0] = tot;
+        // reduce over the 16 channel lanes, 16 values at a time: value idx = (r * AP + al) * REP + rri
+        // ends in lane idx % 16 (token 4q + r, query head (a0 + al) * REP + rri)
+        constexpr int NV = 4 * AP * REP;
+        if constexpr (NV > 16) {
+#pragma unroll
+          for (int j = 0; j < NV / 16; ++j) {
+            float grp[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) grp[i] = pt[16 * j + i];
+            const float tot = row_transpose_reduce<16>(grp, n);
+            const int idx = 16 * j + n;
+            const int tok = tt + 4 * q + idx / (AP * REP), hq = (a0 + (idx / REP) % AP) * REP + idx % REP;
+            bool masked = tok >= len;
+            for (int i = 0; i < cnt; ++i) masked |= (s_sink[wave][i] == tok);
+            if (!masked) s_sc[hq][tok - t0] = tot;
+          }
+        } else {
+          const float tot = row_transpose_reduce<NV>(pt, n);
+          const int idx = n & (NV - 1);
+          const int tok = tt + 4 * q + idx / (AP * REP), hq = (a0 + (idx / REP) % AP) * REP + idx % REP;
+          bool masked = tok >= len;
+          for (int i = 0; i < cnt; ++i) masked |= (s_sink[wave][i] == tok);
+          if (n < NV && !masked) s_sc[hq][tok - t0] = tot;
+        }
+        }
       }
     }
     // V metadata of the four tokens this lane turns into weights in phase S (head = wave); requested
@@ -346,6 +382,10 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
     const uint4* vslab = reinterpret_cast<const uint4*>(v.vc + rkv_v_slabbase(v, b, rg, t0 >> 5));
     const int lidx = wave * (16 * G) + (has_head ? lane : 0);
     const int nslab = min(MF_CH / 32, (len - t0 + 31) >> 5);
+    // the softmax and value phases run once per query head of a KV head; the V codes are requested
+    // again each time (from L2 after the first), which is cheaper than holding them across the loop
+#pragma unroll 1
+    for (int rri = 0; rri < REP; ++rri) {
     // all V codes of the chunk (one 16-byte load per lane and slab): in flight while the softmax phase runs
     uint4 vcodes[MF_CH / 32];
 #pragma unroll
@@ -362,7 +402,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
       float m = -INFINITY;
 #pragma unroll
       for (int i = 0; i < MF_CH / 64; ++i) {
-        sv[i] = s_sc[a][lane + 64 * i];
+        sv[i] = s_sc[a * REP + rri][lane + 64 * i];
         m = fmaxf(m, sv[i]);
       }
       m = wave_allreduce<true>(m);
@@ -437,7 +477,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         }
       }
       if (has_head) {
-        const int qh = (rg * G + q) * rep + rr;                // query head served for KV head rg*G + q
+        const int qh = (rg * G + q) * rep + rrg * REP + rri;   // query head served for KV head rg*G + q
         float* dst = part + (((size_t)b * v.Hq + qh) * nch + chunk) * RKV_PART_STRIDE;
         const float wsc = 2.0f * s_wsc[q];                  // FP4 nibble = code/2
 #pragma unroll
@@ -451,6 +491,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
           dst[1] = s_l[q];
         }
       }
+    }
     }
   }
 }
@@ -468,13 +509,19 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, floa
   const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
-  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, s);
+  const int rep = v.Hq / v.Hkv;
+  const int share = rep % 4 == 0 ? 4 : (rep % 2 == 0 ? 2 : 1);   // query heads of a KV head served by one workgroup
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, share, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
-  dim3 grid(((nch + 7) & ~7) * (v.Hq / v.Hkv), v.NRG, v.B);
+  dim3 grid(((nch + 7) & ~7) * (rep / share), v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch == 0) {}                                          // an empty cache has only the current token
-  else if (v.g == 4) hipLaunchKernelGGL(k_decode_mfma<4>, grid, dim3(256), 0, s, v, qt, part, nch);
-  else hipLaunchKernelGGL(k_decode_mfma<2>, grid, dim3(256), 0, s, v, qt, part, nch);
+  else if (v.g == 4 && share == 1) hipLaunchKernelGGL((k_decode_mfma<4, 1>), grid, dim3(256), 0, s, v, qt, part, nch);
+  else if (v.g == 4 && share == 2) hipLaunchKernelGGL((k_decode_mfma<4, 2>), grid, dim3(256), 0, s, v, qt, part, nch);
+  else if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 4>), grid, dim3(256), 0, s, v, qt, part, nch);
+  else if (share == 1) hipLaunchKernelGGL((k_decode_mfma<2, 1>), grid, dim3(256), 0, s, v, qt, part, nch);
+  else if (share == 2) hipLaunchKernelGGL((k_decode_mfma<2, 2>), grid, dim3(256), 0, s, v, qt, part, nch);
+  else hipLaunchKernelGGL((k_decode_mfma<2, 4>), grid, dim3(256), 0, s, v, qt, part, nch);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, out, lse, s);
   return rkv_check_launch();

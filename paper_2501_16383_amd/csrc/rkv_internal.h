@@ -142,7 +142,7 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
                            hipStream_t s);
 bool rkv_mfma_supported(const rkv_cache* c);
-void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, hipStream_t s);
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, int share, hipStream_t s);
 void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, const __half* k_cur, const __half* v_cur,
                       float* out, float* lse, hipStream_t s);
 int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s);
