@@ -572,3 +572,32 @@ def test_current_token_attended_in_full_precision(T):
         assert e <= ATT_TOL and le <= LSE_TOL
     cache.quantize_append(P.gpu(k[:, T:]), P.gpu(v[:, T:]))
     assert cache.length == T + 1
+
+
+def test_maximum_context_length():
+    """The largest cache the library accepts (65536 tokens): 256 chunks on the matrix-core path and
+    512 - the merge kernel's limit - on the general one; one rotation group, both paths against
+    the oracle on the GPU's own codes, and one more token must be refused."""
+    w = small("cfg3", n_q_heads=4, n_kv_heads=4)
+    T = 65536
+    cfg = R.RkvConfig(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=T, max_sinks=4, rot_heads=4)
+    with pytest.raises(R.RkvError):
+        R.RkvCache(R.RkvConfig(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=T + 1, max_sinks=4, rot_heads=4))
+    k, v, mask = S.make_kv(w, T, batch=1)
+    q = S.make_q(w, batch=1)
+    cache = R.RkvCache(cfg)
+    print("[case] 65536 tokens: bulk append 65535 + 1", flush=True)
+    cache.quantize_append(P.gpu(k[:, :T - 1]), P.gpu(v[:, :T - 1]), P.gpu(mask[:, :T - 1]))
+    cache.quantize_append(P.gpu(k[:, T - 1:]), P.gpu(v[:, T - 1:]), P.gpu(mask[:, T - 1:]))
+    assert cache.length == T
+    with pytest.raises(R.RkvError) as ei:
+        cache.quantize_append(P.gpu(k[:, :1]), P.gpu(v[:, :1]))
+    assert ei.value.code == -2
+    exp = export_host(cache)
+    for path in (2, 1):
+        cache.set_decode_path(path)
+        print(f"[case] 65536 tokens: decode path {path}", flush=True)
+        out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
+        torch.cuda.synchronize()
+        check_slice(exp, out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64), 0, 0, k, v, mask, q,
+                    tag=f"65536 tokens path={path}")
