@@ -234,14 +234,28 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   if (v.rope_style == 0) { j = c & 63; partner = c ^ 64; sgn = c < 64 ? -1.f : 1.f; }
   else { j = c >> 1; partner = c ^ 1; sgn = (c & 1) ? 1.f : -1.f; }
   const float qc = qr[qbase + c];
-  for (int s = 0; s < cnt; ++s) {
-    const int pos = v.sink_pos[b * v.max_sinks + s];
-    const __half* kr = v.sink_k + ((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D;
-    const float2 cs = v.rope[(size_t)pos * 64 + j];
-    const float x = __half2float(kr[c]), p = __half2float(kr[partner]);
-    float d = qc * (x * cs.x + sgn * p * cs.y);
-    for (int o = 32; o > 0; o >>= 1) d += __shfl_xor(d, o);
-    if (lane == 0) s_part[wave][s] = d;
+  // the first partial sums of this channel are requested now: they do not depend on anything
+  // computed here, and the latency of the sink rows below hides theirs
+  constexpr int PRE = 16;
+  float pv[PRE];
+#pragma unroll
+  for (int k = 0; k < PRE; ++k) pv[k] = k < nch ? P[(size_t)k * RKV_PART_STRIDE + 4 + c] : 0.f;
+  for (int s0 = 0; s0 < cnt; s0 += 4) {                    // four sink rows at a time: their loads overlap
+    float d[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int s = min(s0 + i, cnt - 1);
+      const int pos = v.sink_pos[b * v.max_sinks + s];
+      const __half* kr = v.sink_k + ((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D;
+      const float2 cs = v.rope[(size_t)pos * 64 + j];
+      const float x = __half2float(kr[c]), p = __half2float(kr[partner]);
+      d[i] = qc * (x * cs.x + sgn * p * cs.y);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      for (int o = 32; o > 0; o >>= 1) d[i] += __shfl_xor(d[i], o);
+      if (lane == 0 && s0 + i < cnt) s_part[wave][s0 + i] = d[i];
+    }
   }
   // the token being decoded, if it is attended in full precision: an exact row at position len
   // (which may lie one past the angle table, so its angles are computed here)
@@ -265,11 +279,28 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   for (int s = 0; s < cnt; ++s) M = fmaxf(M, s_score[s]);
   M = fmaxf(M, cur_score);
   float L = 0.f, acc = 0.f;
-  for (int k = 0; k < nch; ++k) {
-    const float mk = s_w[k];
-    const float w = mk > -INFINITY ? __expf(mk - M) : 0.f;
-    L += w * s_l[k];
-    acc += w * P[(size_t)k * RKV_PART_STRIDE + 4 + c];     // partial sums are always finite
+#pragma unroll
+  for (int k = 0; k < PRE; ++k) {
+    if (k < nch) {
+      const float mk = s_w[k];
+      const float w = mk > -INFINITY ? __expf(mk - M) : 0.f;
+      L += w * s_l[k];
+      acc += w * pv[k];                                      // partial sums are always finite
+    }
+  }
+  for (int k0 = PRE; k0 < nch; k0 += 8) {                    // longer contexts: eight loads in flight at a time
+    float pw[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pw[i] = k0 + i < nch ? P[(size_t)(k0 + i) * RKV_PART_STRIDE + 4 + c] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (k0 + i < nch) {
+        const float mk = s_w[k0 + i];
+        const float w = mk > -INFINITY ? __expf(mk - M) : 0.f;
+        L += w * s_l[k0 + i];
+        acc += w * pw[i];
+      }
+    }
   }
   if (v.v_rotate) {   // the 2-bit stream holds rotated values: undo the per-head Hadamard once
     red[c] = acc;
