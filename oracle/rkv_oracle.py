@@ -412,6 +412,33 @@ def decode_attention(cache: OracleCache, q: np.ndarray, q_pos: Optional[np.ndarr
     return out, lse
 
 
+def decode_attention_multi(cache: OracleCache, q: np.ndarray, q_pos: np.ndarray):
+    """Several query tokens per sequence in one step (speculative or chunked decoding): query i of
+    sequence b sits at position q_pos[b, i] and attends the cached tokens 0 .. q_pos[b, i] - Eq. 5
+    with the causal mask of the decoding phase.  q: [B, nq, Hq, d]; returns (out [B, nq, Hq, d],
+    lse [B, nq, Hq]).  Each query is one single-query read of the cache cut at its position.
+    """
+    cfg = cache.cfg
+    q = np.asarray(q)
+    q_pos = np.asarray(q_pos, dtype=np.int64)
+    B, nq = q.shape[0], q.shape[1]
+    out = np.empty((B, nq, cfg.n_q_heads, cfg.head_dim))
+    lse = np.empty((B, nq, cfg.n_q_heads))
+    for b in range(B):
+        for i in range(nq):
+            T = int(q_pos[b, i]) + 1
+            cut = OracleCache(cfg=OracleConfig(**{**cfg.__dict__, "batch": 1}), perm=cache.perm, length=T)
+            for name in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero"):
+                setattr(cut, name, getattr(cache, name)[b:b + 1, :T])
+            keep = [s for s, pos in enumerate(cache.sink_pos[b]) if pos < T]
+            cut.sink_pos = [[cache.sink_pos[b][s] for s in keep]]
+            cut.sink_k = [[cache.sink_k[b][s] for s in keep]]
+            cut.sink_v = [[cache.sink_v[b][s] for s in keep]]
+            o, l = decode_attention(cut, q[b:b + 1, i], np.array([q_pos[b, i]]))
+            out[b, i], lse[b, i] = o[0], l[0]
+    return out, lse
+
+
 def average_bits(cfg: OracleConfig) -> float:
     """Stored bits per cached element: codes plus one fp16 scale and one fp16 zero per block."""
     return cfg.bits + 32.0 / cfg.quant_group

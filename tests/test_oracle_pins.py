@@ -496,3 +496,30 @@ def test_current_token_operand_equals_a_retained_row():
     O.quantize_append(c, k, v, mask)
     out_c, _ = O.decode_attention(c, q)
     assert np.abs(out_c - out_a).max() > 1e-4
+
+
+def test_multi_query_decode_is_a_sequence_of_single_steps():
+    """Decoding several tokens at once must give what token-by-token decoding gives: append token
+    i, decode with query i over the cache so far - for every i."""
+    rng = np.random.default_rng(24)
+    cfg = O.OracleConfig(batch=2, n_q_heads=4, n_kv_heads=2, rot_heads=2, max_sinks=2)
+    T0, nq = 13, 3
+    k = rng.standard_normal((2, T0 + nq, 2, 128)).astype(np.float16)
+    v = rng.standard_normal((2, T0 + nq, 2, 128)).astype(np.float16)
+    q = rng.standard_normal((2, nq, 4, 128)).astype(np.float16)
+    mask = np.zeros((2, T0 + nq), dtype=np.uint8)
+    mask[:, 0] = 1
+    mask[0, T0 + 1] = 1                       # a retained row among the new tokens: later queries see it, earlier ones do not
+    step = O.cache_new(cfg)
+    O.quantize_append(step, k[:, :T0], v[:, :T0], mask[:, :T0])
+    ref = []
+    for i in range(nq):
+        O.quantize_append(step, k[:, T0 + i:T0 + i + 1], v[:, T0 + i:T0 + i + 1], mask[:, T0 + i:T0 + i + 1])
+        ref.append(O.decode_attention(step, q[:, i]))
+    full = O.cache_new(cfg)
+    O.quantize_append(full, k, v, mask)
+    pos = np.tile(np.arange(T0, T0 + nq), (2, 1))
+    out, lse = O.decode_attention_multi(full, q, pos)
+    for i in range(nq):
+        assert np.allclose(out[:, i], ref[i][0], rtol=0, atol=1e-12)
+        assert np.allclose(lse[:, i], ref[i][1], rtol=0, atol=1e-12)
