@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--path", type=int, default=0, help="decode kernel: 0 auto, 1 general, 2 matrix-core")
+    ap.add_argument("--queries", type=int, default=1,
+                    help="query tokens per sequence and step (above 1: that many tokens are appended, then read the cache in one multi-query call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -114,7 +116,7 @@ def main():
     w = S.WORKLOADS[args.workload]
     L = args.layers or w.layers
     B, T = w.batch, w.context
-    K, W = args.steps, args.warmup
+    K, W, NQ = args.steps, args.warmup, args.queries
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     hip = Hip()
@@ -123,11 +125,11 @@ def main():
                       rot_heads=w.rot_heads, perm_span=128, rope_theta=w.rope_theta)
     E = cfg.E
     _, scratch_bytes = R.query_sizes(cfg)
-    scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device=dev)
+    scratch = torch.empty(scratch_bytes * NQ, dtype=torch.uint8, device=dev)
 
     # ---- build the L caches: calibrate the reorder, then bulk-quantize T-1-W tokens (timed: append GB/s)
     caches, bulk_ms = [], []
-    n_pre = T - K - W          # the last timed step decodes over exactly T tokens
+    n_pre = T - (K + W) * NQ   # the last timed step decodes over exactly T tokens
     e0, e1 = hip.event(), hip.event()
     for l in range(L):
         c = R.RkvCache(cfg, device=dev, scratch=scratch)
@@ -148,17 +150,28 @@ def main():
 
     # ---- per-step inputs, resident before the timed region
     n_total = K + W
-    new_k = [S.make_kv_torch(w, n_total, dev, layer=l, stream=2) for l in range(L)]
-    qs = [torch.stack([S.make_q_torch(w, dev, layer=l, step=s) for s in range(n_total)]) for l in range(L)]
+    new_k = [S.make_kv_torch(w, n_total * NQ, dev, layer=l, stream=2) for l in range(L)]
+    qs = [torch.stack([S.make_q_torch(w, dev, layer=l, step=s) for s in range(n_total * NQ)]) for l in range(L)]
     outs = [torch.empty((B, w.n_q_heads, 128), dtype=torch.float32, device=dev) for _ in range(L)]
-    step_k = [[new_k[l][0][:, s:s + 1].contiguous() for s in range(n_total)] for l in range(L)]
-    step_v = [[new_k[l][1][:, s:s + 1].contiguous() for s in range(n_total)] for l in range(L)]
-    step_q = [[qs[l][s].contiguous() for s in range(n_total)] for l in range(L)]
+    step_k = [[new_k[l][0][:, s * NQ:(s + 1) * NQ].contiguous() for s in range(n_total)] for l in range(L)]
+    step_v = [[new_k[l][1][:, s * NQ:(s + 1) * NQ].contiguous() for s in range(n_total)] for l in range(L)]
+    if NQ == 1:
+        step_q = [[qs[l][s].contiguous() for s in range(n_total)] for l in range(L)]
+    else:   # [B, NQ, Hq, 128] per step, positions = the NQ tokens just appended
+        step_q = [[qs[l][s * NQ:(s + 1) * NQ].transpose(0, 1).contiguous() for s in range(n_total)] for l in range(L)]
+        step_pos = [(torch.arange(NQ, dtype=torch.int32, device=dev) + (n_pre + s * NQ)).repeat(B, 1).contiguous()
+                    for s in range(n_total)]
+
+    def decode(c, l, s):
+        if NQ == 1:
+            c.decode_attention(step_q[l][s], out=outs[l])
+        else:
+            outs[l] = c.decode_attention_multi(step_q[l][s], step_pos[s])
 
     def one_step(s):
         for l in range(L):
             caches[l].quantize_append(step_k[l][s], step_v[l][s])
-            caches[l].decode_attention(step_q[l][s], out=outs[l])
+            decode(caches[l], l, s)
 
     def decode_only_events(s, events):
         for l in range(L):
@@ -166,7 +179,7 @@ def main():
             c.set_profile_events(None, None)
             c.quantize_append(step_k[l][s], step_v[l][s])
             c.set_profile_events(*events[l])
-            c.decode_attention(step_q[l][s], out=outs[l])
+            decode(c, l, s)
             c.set_profile_events(None, None)
 
     if args.calib_copy_mib > 0:
@@ -180,7 +193,7 @@ def main():
     for s in range(W):
         one_step(s)
     torch.cuda.synchronize()
-    assert caches[0].length == T - K
+    assert caches[0].length == T - K * NQ
 
     # timed region: exactly K steps, whole-job wall clock; the decode kernel of every launch is
     # bracketed by its own pair of HIP events (recorded by the library on the launch stream)
@@ -197,7 +210,7 @@ def main():
     avg_ms = sum(kern_ms) / len(kern_ms)
     min_ms = min(kern_ms)
     med_ms = sorted(kern_ms)[len(kern_ms) // 2]
-    ctx = T - (K - 1) / 2.0
+    ctx = T - (K - 1) * NQ / 2.0
     bytes_per_tok = 2 * E // 4 + 2 * (E // 128) * 4
     launch_bytes = B * ctx * bytes_per_tok
     achieved = launch_bytes / (avg_ms * 1e-3) / 1e9
@@ -214,7 +227,8 @@ def main():
     assert all(bool(torch.isfinite(o).all()) for o in outs)
 
     result = {
-        "metric": "2-bit decode-attention KV-tokens/s (one appended token per sequence plus decode attention over the full cache, per layer)",
+        "metric": "2-bit decode-attention KV-tokens/s (one appended token per sequence plus decode attention over the full cache, per layer)"
+                  if NQ == 1 else f"2-bit decode-attention KV-tokens/s ({NQ} appended tokens per sequence, then {NQ} causal queries over the full cache in one call, per layer)",
         "value": kv_tokens / wall,
         "unit": "KV-tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W,
@@ -224,7 +238,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {SHAPES.get(w.name, 'custom')} decode, {L} layers x {w.n_q_heads} query / {w.n_kv_heads} KV heads x 128, "
                                f"batch {B}, context {T}, rotation over {w.rot_heads} heads, 2-bit group-128, {w.n_sinks} fp16 sinks",
-                   "decode_path": args.path,
+                   "decode_path": args.path, "queries_per_step": NQ,
                    "storage": "u2 codes + fp16 scale / fp16 zero per 128 (2.25 bits per element)",
                    "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

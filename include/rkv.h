@@ -155,6 +155,24 @@ int rkv_decode_attention_with_current(rkv_cache* cache, const void* dev_q, const
                                       const void* dev_k_cur, const void* dev_v_cur, float* dev_out,
                                       float* dev_lse, void* dev_scratch, void* stream);
 
+/* Several query tokens per sequence in one call (Eq. 5 with the causal mask): the tokens of a
+ * multi-token step - verification of drafted tokens, a prefill continued in pieces - are appended
+ * first and then read the cache together, so that the cache streams from memory once for all of
+ * them.  Query i of sequence b sits at position dev_q_pos[b][i] (its RoPE angle) and attends the
+ * cached tokens at positions <= min(dev_q_pos[b][i], length - 1), retained sink rows included.
+ *   dev_q      [batch][n_queries][n_q_heads][head_dim] fp16, pre-RoPE
+ *   dev_q_pos  [batch][n_queries] int32, required, every entry >= 0 (a query that sees no token
+ *              has no defined output)
+ *   n_queries  1 .. RKV_MAX_QUERIES
+ *   dev_out    [batch][n_queries][n_q_heads][head_dim] fp32
+ *   dev_lse    [batch][n_queries][n_q_heads] fp32, or NULL
+ *   dev_scratch >= n_queries * scratch_bytes of rkv_query_sizes
+ * Matrix-core decode path only: RKV_EINVAL for a configuration it does not cover (see
+ * rkv_set_decode_path) or when the general kernel is forced; RKV_ESTATE on an empty cache. */
+#define RKV_MAX_QUERIES 64
+int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, int32_t n_queries,
+                               float* dev_out, float* dev_lse, void* dev_scratch, void* stream);
+
 /* Choose the decode kernel: 0 = automatic (default), 1 = force the general kernel (any supported
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
  * the configuration is outside what it covers). */

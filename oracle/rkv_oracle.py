@@ -416,7 +416,8 @@ def decode_attention_multi(cache: OracleCache, q: np.ndarray, q_pos: np.ndarray)
     """Several query tokens per sequence in one step (speculative or chunked decoding): query i of
     sequence b sits at position q_pos[b, i] and attends the cached tokens 0 .. q_pos[b, i] - Eq. 5
     with the causal mask of the decoding phase.  q: [B, nq, Hq, d]; returns (out [B, nq, Hq, d],
-    lse [B, nq, Hq]).  Each query is one single-query read of the cache cut at its position.
+    lse [B, nq, Hq]).  Each query is one single-query read of the cache cut at its position (a
+    position past the last cached token sees the whole cache and only sets the RoPE angle).
     """
     cfg = cache.cfg
     q = np.asarray(q)
@@ -426,7 +427,7 @@ def decode_attention_multi(cache: OracleCache, q: np.ndarray, q_pos: np.ndarray)
     lse = np.empty((B, nq, cfg.n_q_heads))
     for b in range(B):
         for i in range(nq):
-            T = int(q_pos[b, i]) + 1
+            T = min(int(q_pos[b, i]) + 1, cache.length)
             cut = OracleCache(cfg=OracleConfig(**{**cfg.__dict__, "batch": 1}), perm=cache.perm, length=T)
             for name in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero"):
                 setattr(cut, name, getattr(cache, name)[b:b + 1, :T])

@@ -20,6 +20,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
     "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention", "rkv_decode_attention_with_current",
+    "rkv_decode_attention_multi",
     "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
@@ -94,6 +95,7 @@ def load_library():
     lib.rkv_quantize_append.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.rkv_decode_attention_with_current.argtypes = [vp] * 9
+    lib.rkv_decode_attention_multi.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp, vp]
     lib.rkv_set_decode_path.argtypes = [vp, i32]
     lib.rkv_set_profile_events.argtypes = [vp, vp, vp]
     lib.rkv_dequantize.argtypes = [vp, vp, vp, vp]
@@ -277,6 +279,29 @@ class RkvCache:
             return (out, lse) if want_lse else out
         _check(self.lib.rkv_decode_attention(self.handle, _ptr(q), _ptr(q_pos), _ptr(out), _ptr(lse),
                                              _ptr(self.scratch), _stream()), "rkv_decode_attention")
+        return (out, lse) if want_lse else out
+
+    def decode_attention_multi(self, q, q_pos, want_lse=False):
+        """rkv_decode_attention_multi: q [batch, n_queries, n_q_heads, 128] fp16, q_pos [batch, n_queries] int32."""
+        import torch
+        q = _dev(q, torch.float16, "q")
+        q_pos = _dev(q_pos, torch.int32, "q_pos")
+        cfg = self.cfg
+        if q.dim() != 4 or q.shape[0] != cfg.batch or q.shape[2:] != (cfg.n_q_heads, cfg.head_dim):
+            raise ValueError("q must be [batch, n_queries, n_q_heads, head_dim]")
+        nq = q.shape[1]
+        if q_pos is None or q_pos.shape != (cfg.batch, nq):
+            raise ValueError("q_pos must be [batch, n_queries]")
+        need = nq * self.scratch_bytes
+        scratch = self.scratch
+        if scratch.numel() < need:
+            scratch = getattr(self, "_scratch_multi", None)
+            if scratch is None or scratch.numel() < need:
+                scratch = self._scratch_multi = torch.empty(need, dtype=torch.uint8, device=self.device)
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device) if want_lse else None
+        _check(self.lib.rkv_decode_attention_multi(self.handle, _ptr(q), _ptr(q_pos), nq, _ptr(out), _ptr(lse), _ptr(scratch),
+                                                   _stream()), "rkv_decode_attention_multi")
         return (out, lse) if want_lse else out
 
     def dequantize(self):

@@ -244,8 +244,18 @@ RKV_EXPORT int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const i
   if (cache->decode_path == 2 && !fast) return RKV_EINVAL;
   if (cache->decode_path == 1) fast = false;
   if (fast)
-    return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
+    return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, 0, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
   return rkv_launch_decode_general(cache, (const __half*)dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
+}
+
+RKV_EXPORT int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, int32_t n_queries,
+                                          float* dev_out, float* dev_lse, void* dev_scratch, void* stream) {
+  if (!cache || !dev_q || !dev_q_pos || !dev_out || !dev_scratch) return RKV_EINVAL;
+  if (n_queries < 1 || n_queries > RKV_MAX_QUERIES) return RKV_EINVAL;
+  if (cache->v.len < 1) return RKV_ESTATE;
+  if (!rkv_mfma_supported(cache) || cache->decode_path == 1) return RKV_EINVAL;   // matrix-core path only
+  return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, n_queries, dev_out, dev_lse, dev_scratch,
+                                (hipStream_t)stream);
 }
 
 RKV_EXPORT int rkv_dequantize(rkv_cache* cache, float* dev_k_hat, float* dev_v_hat, void* stream) {

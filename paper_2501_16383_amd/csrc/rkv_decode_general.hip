@@ -35,10 +35,13 @@ __device__ inline void fwht_lanes_d(T (&x)[PL], int lane, int xstages) {
 
 // q~[b][h][c] = RoPE(q, q_pos)[c] / sqrt(128), angles in double (q_pos may lie beyond the table).
 __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restrict__ q, const int* __restrict__ q_pos,
-                                                int default_pos, float* __restrict__ qr, int share) {
+                                                int default_pos, float* __restrict__ qr, int share, int nq) {
+  // v.Hq counts virtual heads when nq > 1 (several query tokens, each at its own position)
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
-  const int pos = q_pos ? q_pos[b] : default_pos;
-  const size_t base = ((size_t)b * v.Hq + h) * RKV_D;
+  const RkvVHead vh = rkv_virtual_head(v, h, nq);
+  const int pos = q_pos ? q_pos[b * nq + vh.qi] : default_pos;
+  const size_t base = ((size_t)b * v.Hq + h) * RKV_D;                       // where the rotated query goes
+  const size_t src = (((size_t)b * nq + vh.qi) * (v.Hq / nq) + vh.h) * RKV_D; // where the raw query is
   int j, partner;
   float sgn;
   if (v.rope_style == 0) {
@@ -60,7 +63,7 @@ __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restr
   } else {
     sincos((double)pos * pow((double)v.theta, -(double)j / 64.0), &sn, &cs);
   }
-  const float x = __half2float(q[base + c]), p = __half2float(q[base + partner]);
+  const float x = __half2float(q[src + c]), p = __half2float(q[src + partner]);
   const float val = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
   qr[base + c] = val;
   // second copy for the matrix-core kernel: [b][rot group][rr / share][n 0..15][p 0..3][KV head a][rr % share][lo, hi]
@@ -211,7 +214,8 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
 #define MERGE_MAX_CH 512
 __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restrict__ qr, const float* __restrict__ part,
                                                int nch, const __half* __restrict__ k_cur, const __half* __restrict__ v_cur,
-                                               float* __restrict__ out, float* __restrict__ lse) {
+                                               const int* __restrict__ q_lim, int nq, float* __restrict__ out,
+                                               float* __restrict__ lse) {
   __shared__ float s_w[MERGE_MAX_CH];     // chunk maxima, then chunk weights
   __shared__ float s_l[MERGE_MAX_CH];
   __shared__ float s_part[2][64];         // per-wave partial sink scores
@@ -223,6 +227,9 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   const size_t qbase = ((size_t)b * v.Hq + h) * RKV_D;
   const float* P = part + ((size_t)b * v.Hq + h) * nch * RKV_PART_STRIDE;
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
+  // with several query tokens (q_lim set) a query only sees tokens up to its own position
+  const RkvVHead vh = rkv_virtual_head(v, h, nq);
+  const int lim = q_lim ? min(q_lim[b * nq + vh.qi], v.len - 1) : v.len - 1;
 
   for (int k = c; k < nch; k += 128) {
     s_w[k] = P[(size_t)k * RKV_PART_STRIDE];
@@ -254,7 +261,7 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       for (int o = 32; o > 0; o >>= 1) d[i] += __shfl_xor(d[i], o);
-      if (lane == 0 && s0 + i < cnt) s_part[wave][s0 + i] = d[i];
+      if (lane == 0 && s0 + i < cnt) s_part[wave][s0 + i] = v.sink_pos[b * v.max_sinks + s0 + i] <= lim ? d[i] : -INFINITY;
     }
   }
   // the token being decoded, if it is attended in full precision: an exact row at position len
@@ -314,7 +321,7 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
     acc = red[c] * 0.08838834764831845f;
   }
   for (int s = 0; s < cnt; ++s) {
-    const float w = __expf(s_score[s] - M);
+    const float w = s_score[s] > -INFINITY ? __expf(s_score[s] - M) : 0.f;
     L += w;
     acc += w * __half2float(v.sink_v[((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D + c]);
   }
@@ -323,16 +330,18 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
     L += w;
     acc += w * __half2float(v_cur[((size_t)b * v.Hkv + kvh) * RKV_D + c]);
   }
-  out[qbase + c] = acc / L;
-  if (lse && c == 0) lse[(size_t)b * v.Hq + h] = M + logf(L);
+  const size_t orow = ((size_t)b * nq + vh.qi) * (v.Hq / nq) + vh.h;        // [batch][query token][real head]
+  out[orow * RKV_D + c] = acc / L;
+  if (lse && c == 0) lse[orow] = M + logf(L);
 }
 
-void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, int share, hipStream_t s) {
-  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, default_pos, qr, share);
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, int share, int nq,
+                       hipStream_t s) {
+  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, default_pos, qr, share, nq);
 }
 void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, const __half* k_cur, const __half* v_cur,
-                      float* out, float* lse, hipStream_t s) {
-  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, k_cur, v_cur, out, lse);
+                      const int* q_lim, int nq, float* out, float* lse, hipStream_t s) {
+  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, k_cur, v_cur, q_lim, nq, out, lse);
 }
 
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
@@ -349,7 +358,7 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
-  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, 1, s);
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, 1, 1, s);
   const int rep = v.Hq / v.Hkv, nq = rep * v.g;
   const size_t lds = ((size_t)nq * RKV_D + (size_t)nq * GEN_CHUNK + 2 * (size_t)v.g * GEN_CHUNK + 2 * nq) * 4;
   dim3 grid(nch, v.NRG, v.B);
@@ -365,6 +374,6 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch > 0) hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, qr, part, nch);   // an empty cache has only the current token
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
-  rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, out, lse, s);
+  rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, nullptr, 1, out, lse, s);
   return rkv_check_launch();
 }

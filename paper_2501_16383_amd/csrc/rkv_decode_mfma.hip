@@ -138,9 +138,12 @@ __device__ __forceinline__ float wave_allreduce(float x) {
   return op(op(r0, r1), op(r2, r3));
 }
 
-template <int G, int REP>
-__global__ void __launch_bounds__(256, REP > 1 ? 2 : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
-                                                                       float* __restrict__ part, int nch) {
+// MULTI: several query tokens per sequence.  v.Hq then counts virtual heads (nq per real head, see
+// rkv_virtual_head) and virtual head hv only attends tokens at positions <= q_lim[b][query token of hv].
+template <int G, int REP, bool MULTI>
+__global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
+                                                                       float* __restrict__ part, int nch,
+                                                                       const int* __restrict__ q_lim, int nq) {
   constexpr int NH = G * REP;                    // query heads served by this workgroup: REP per KV head
   constexpr int AP = (4 / REP < G) ? 4 / REP : G; // KV heads per pass of the key phase: 16 score accumulators at most
   __shared__ float s_sc[NH][MF_CH];
@@ -149,6 +152,7 @@ __global__ void __launch_bounds__(256, REP > 1 ? 2 : MF_OCC) k_decode_mfma(RkvVi
   __shared__ int s_sink[4][64];
   __shared__ uint4 s_H[8][64];                   // Hadamard operand tiles
   __shared__ float2 s_step[64];                  // RoPE rotation by 16 positions, per channel pair
+  __shared__ int s_lim[MULTI ? NH : 1];          // last position each served query head may attend
   __shared__ __attribute__((aligned(16))) float s_q[16][4][2 * NH];  // query [n][p][KV head][query head of it][lo, hi]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -197,6 +201,10 @@ __global__ void __launch_bounds__(256, REP > 1 ? 2 : MF_OCC) k_decode_mfma(RkvVi
   s_sink[wave][lane] = lane < cnt ? v.sink_pos[b * v.max_sinks + lane] : -1;
 #pragma unroll
   for (int a = 0; a < NH; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
+  if constexpr (MULTI) {
+    // served head a * REP + rri is virtual head rrg * REP + rri of its KV head: query token (that / heads per token)
+    if (tid < NH) s_lim[tid] = min(q_lim[b * nq + (rrg * REP + tid % REP) / (rep / nq)], len - 1);
+  }
   // queries of this rotation group, already RoPE'd, scaled and laid out as s_q by k_prep_q
   for (int i = tid; i < 16 * 4 * 2 * NH / 4; i += 256)
     reinterpret_cast<uint4*>(&s_q[0][0][0])[i] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (16 * 4 * 2 * NH))[i];
@@ -357,6 +365,7 @@ __global__ void __launch_bounds__(256, REP > 1 ? 2 : MF_OCC) k_decode_mfma(RkvVi
             const int idx = 16 * j + n;
             const int tok = tt + 4 * q + idx / (AP * REP), hq = (a0 + (idx / REP) % AP) * REP + idx % REP;
             bool masked = tok >= len;
+            if constexpr (MULTI) masked = tok > s_lim[hq];
             for (int i = 0; i < cnt; ++i) masked |= (s_sink[wave][i] == tok);
             if (!masked) s_sc[hq][tok - t0] = tot;
           }
@@ -365,6 +374,7 @@ __global__ void __launch_bounds__(256, REP > 1 ? 2 : MF_OCC) k_decode_mfma(RkvVi
           const int idx = n & (NV - 1);
           const int tok = tt + 4 * q + idx / (AP * REP), hq = (a0 + (idx / REP) % AP) * REP + idx % REP;
           bool masked = tok >= len;
+          if constexpr (MULTI) masked = tok > s_lim[hq];
           for (int i = 0; i < cnt; ++i) masked |= (s_sink[wave][i] == tok);
           if (n < NV && !masked) s_sc[hq][tok - t0] = tot;
         }
@@ -501,28 +511,45 @@ bool rkv_mfma_supported(const rkv_cache* c) {
   return c->blocks_aligned && (v.g == 2 || v.g == 4) && v.rope_style == 0;
 }
 
-int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
+template <bool MULTI>
+static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* qt, float* part, int nch, const int* q_lim,
+                          int nq, hipStream_t s) {
+#define RKV_MF_LAUNCH(G_, R_) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq)
+  if (v.g == 4 && share == 1) RKV_MF_LAUNCH(4, 1);
+  else if (v.g == 4 && share == 2) RKV_MF_LAUNCH(4, 2);
+  else if (v.g == 4) RKV_MF_LAUNCH(4, 4);
+  else if (share == 1) RKV_MF_LAUNCH(2, 1);
+  else if (share == 2) RKV_MF_LAUNCH(2, 2);
+  else RKV_MF_LAUNCH(2, 4);
+#undef RKV_MF_LAUNCH
+}
+
+// nq == 0: the usual step, one query token that attends the whole cache (and, if set, the current
+// token's exact row).  nq >= 1: nq query tokens per sequence, token i at position q_pos[b][i] and
+// blind to cached tokens behind it; q, out and lse are then [batch][nq][heads][...] and the scratch
+// buffer holds nq times the single-query size.
+int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int nq, float* out, float* lse, void* scratch,
                            hipStream_t s) {
-  const RkvView& v = c->v;
   if (!rkv_mfma_supported(c)) return RKV_EINVAL;
+  const bool multi = nq > 0;
+  if (multi && (c->cur_k || !q_pos)) return RKV_EINVAL;
+  if (!multi) nq = 1;
+  RkvView v = c->v;
+  v.Hq *= nq;                                               // virtual heads
   float* qr = (float*)scratch;
   const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
   const int rep = v.Hq / v.Hkv;
   const int share = rep % 4 == 0 ? 4 : (rep % 2 == 0 ? 2 : 1);   // query heads of a KV head served by one workgroup
-  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, share, s);
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   dim3 grid(((nch + 7) & ~7) * (rep / share), v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch == 0) {}                                          // an empty cache has only the current token
-  else if (v.g == 4 && share == 1) hipLaunchKernelGGL((k_decode_mfma<4, 1>), grid, dim3(256), 0, s, v, qt, part, nch);
-  else if (v.g == 4 && share == 2) hipLaunchKernelGGL((k_decode_mfma<4, 2>), grid, dim3(256), 0, s, v, qt, part, nch);
-  else if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 4>), grid, dim3(256), 0, s, v, qt, part, nch);
-  else if (share == 1) hipLaunchKernelGGL((k_decode_mfma<2, 1>), grid, dim3(256), 0, s, v, qt, part, nch);
-  else if (share == 2) hipLaunchKernelGGL((k_decode_mfma<2, 2>), grid, dim3(256), 0, s, v, qt, part, nch);
-  else hipLaunchKernelGGL((k_decode_mfma<2, 4>), grid, dim3(256), 0, s, v, qt, part, nch);
+  else if (multi) launch_kernel<true>(v, share, grid, qt, part, nch, q_pos, nq, s);
+  else launch_kernel<false>(v, share, grid, qt, part, nch, nullptr, 1, s);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
-  rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, out, lse, s);
+  rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, multi ? q_pos : nullptr, nq, out, lse, s);
   return rkv_check_launch();
 }

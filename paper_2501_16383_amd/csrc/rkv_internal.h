@@ -127,6 +127,20 @@ __device__ __forceinline__ uint2 rkv_ld_stream(const uint2* p) {
 }
 __device__ __forceinline__ void rkv_st_stream(uint32_t* p, uint32_t x) { __builtin_nontemporal_store(x, p); }
 
+// Several query tokens per sequence in one step: the kernels then run on a view whose Hq counts
+// "virtual" query heads, nq per real one.  Virtual head hv of KV head kvh = hv / rep' (rep' = virtual
+// heads per KV head) is query token qi = (hv % rep') / rep of real head kvh * rep + (hv % rep') % rep,
+// where rep = rep' / nq.  Tensors are [batch][nq][real heads][...].
+struct RkvVHead { int qi, h; };
+__device__ inline RkvVHead rkv_virtual_head(const RkvView& v, int hv, int nq) {
+  const int repv = v.Hq / v.Hkv, rep = repv / nq;
+  const int kvh = hv / repv, vr = hv - kvh * repv;
+  RkvVHead r;
+  r.qi = vr / rep;
+  r.h = kvh * rep + (vr - r.qi * rep);
+  return r;
+}
+
 // kernels' host launchers (defined in the .hip files)
 int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s);
 int rkv_launch_set_perm_tables(rkv_cache* c, hipStream_t s);
@@ -139,12 +153,13 @@ int rkv_launch_import(rkv_cache* c, int T, const uint8_t* kc, const float* ks, c
                       const float* vs, const float* vz, hipStream_t s);
 int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
                               hipStream_t s);
-int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
+int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int nq, float* out, float* lse, void* scratch,
                            hipStream_t s);
 bool rkv_mfma_supported(const rkv_cache* c);
-void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, int share, hipStream_t s);
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, int share, int nq,
+                       hipStream_t s);
 void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, const __half* k_cur, const __half* v_cur,
-                      float* out, float* lse, hipStream_t s);
+                      const int* q_lim, int nq, float* out, float* lse, hipStream_t s);
 int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s);
 int rkv_launch_fold_rotation(const rkv_config* cfg, const float* w, int rows, const int* perm, float* out, hipStream_t s);
 int rkv_launch_select_sinks(const __half* x, int batch, int n_tok, int width, int k, int32_t* idx_out, uint8_t* mask_out,

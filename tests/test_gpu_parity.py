@@ -601,3 +601,38 @@ def test_maximum_context_length():
         torch.cuda.synchronize()
         check_slice(exp, out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64), 0, 0, k, v, mask, q,
                     tag=f"65536 tokens path={path}")
+
+
+@pytest.mark.parametrize("hq,hkv,g,nq", [(8, 8, 4, 4), (8, 8, 4, 3), (16, 4, 4, 2), (4, 4, 2, 2), (8, 8, 4, 1)])
+def test_several_query_tokens_per_step(hq, hkv, g, nq):
+    """rkv_decode_attention_multi: the tokens of a multi-token step are appended, then all of them
+    read the cache in one call, each blind to what lies behind its own position (one of the new
+    tokens is a retained sink row, which the earlier ones must not see).  Checked against the
+    oracle on the GPU's own codes; sequence 1 uses scattered positions, one past the cache."""
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
+    T = 333
+    cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=hkv, max_tokens=400, max_sinks=4, rot_heads=g)
+    sinks = [0, T - 2] if nq > 1 else [0]
+    cache, oc, _ = build_pair(w, cfg, T, sink_positions=sinks, chunks=[0, T - nq, T])
+    oc_g = oracle_from_export(oc, P.export_numpy(cache))
+    q = np.stack([S.make_q(w, batch=2, step=i) for i in range(nq)], axis=1)          # [B, nq, Hq, d]
+    q_pos = np.stack([np.arange(T - nq, T), np.array([5, 255, 256, 700])[:nq]]).astype(np.int32)
+    if nq == 1:
+        q_pos = np.array([[T - 1], [T - 1]], dtype=np.int32)
+    print(f"[case] multi-query Hq={hq} Hkv={hkv} g={g} nq={nq} q_pos={q_pos.tolist()}", flush=True)
+    out, lse = cache.decode_attention_multi(P.gpu(q), P.gpu(q_pos), want_lse=True)
+    torch.cuda.synchronize()
+    ref, lse_ref = O.decode_attention_multi(oc_g, q, q_pos)
+    e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
+    le = float(np.abs(lse.cpu().numpy() - lse_ref).max())
+    print(f"[parity] multi-query nq={nq}: out err {e:.3e} lse err {le:.3e}", flush=True)
+    assert e <= ATT_TOL and le <= LSE_TOL
+    if nq == 1:   # one query at the last position is the ordinary decode step
+        cache.set_decode_path(2)
+        out1 = cache.decode_attention(P.gpu(q[:, 0]))
+        torch.cuda.synchronize()
+        assert float((out1 - out[:, 0]).abs().max()) <= 1e-6 * float(out1.abs().max())
+    # what the entry point refuses
+    cache.set_decode_path(1)
+    with pytest.raises(R.RkvError):
+        cache.decode_attention_multi(P.gpu(q), P.gpu(q_pos))
