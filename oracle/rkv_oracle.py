@@ -24,6 +24,12 @@ Conventions shared by all functions
   * scale is stored in fp16 and the stored value is the one used to quantize, so that the write
     and the read agree; zero-point is an integer kept in fp16 (|zero| <= 2048).  16 + 16 bits of
     metadata per 128 two-bit codes is the 2.25 average bits of Table `tab:gsm8k`.
+  * meta_format = 1 is the storage named in Sec. 5.1 (quantization settings) and the last row of
+    Table `tab:ablation`: scale in FP8, zero-point in INT8, 2.125 average bits.  The paper names
+    neither the FP8 flavour nor the rounding; here it is E4M3 (the OCP format with 448 as its
+    largest number) and the scale is rounded UP to the next representable number, so that
+    2^bits - 1 steps still cover the block's range and the half-step error bound of the rounding
+    in Eq. 6 holds with the stored scale.  Zero-points beyond the INT8 range are clamped.
 
 Parity pins: tests/test_oracle_*.py.  Unpinned (needs real model keys, absent here): the
 absolute reconstruction-MSE values of Table `tab:quantizeerror`; only their ordering is checked.
@@ -37,6 +43,7 @@ import numpy as np
 
 F16_MAX = 65504.0
 ZERO_LIMIT = 2048.0
+E4M3_MAX = 448.0
 
 
 @dataclass
@@ -53,6 +60,7 @@ class OracleConfig:
     v_rotate: int = 0            # 1: per-head Hadamard on V before quantization
     rope_theta: float = 10000.0
     max_sinks: int = 4
+    meta_format: int = 0         # 0: fp16 scale + fp16 zero; 1: FP8 (E4M3) scale + INT8 zero
 
     @property
     def E(self) -> int:
@@ -137,7 +145,26 @@ def _to_f16(x: np.ndarray) -> np.ndarray:
         return np.asarray(x, dtype=np.float64).astype(np.float16).astype(np.float64)
 
 
-def quantize(z: np.ndarray, group: int = 128, bits: int = 2):
+def e4m3_values() -> np.ndarray:
+    """The 127 non-negative finite numbers of FP8 E4M3 in ascending order, from the format's
+    definition: 1 sign, 4 exponent bits (bias 7), 3 mantissa bits; exponent field 0 holds the
+    subnormals m * 2^-9; the all-ones pattern is NaN, so the largest number is 1.75 * 2^8 = 448."""
+    vals = []
+    for code in range(0x7F):
+        e, m = code >> 3, code & 7
+        vals.append(m * 2.0 ** -9 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7))
+    return np.array(vals)
+
+
+def _to_e4m3_up(x: np.ndarray) -> np.ndarray:
+    """Smallest E4M3 number >= x (x >= 0), saturating at 448; returned as float64."""
+    tab = e4m3_values()
+    x = np.asarray(x, dtype=np.float64)
+    idx = np.searchsorted(tab, x, side="left")
+    return tab[np.minimum(idx, len(tab) - 1)]
+
+
+def quantize(z: np.ndarray, group: int = 128, bits: int = 2, meta_format: int = 0):
     """Eq. 6, 8, 9 on blocks of `group` consecutive elements of the last axis.
 
     Returns (codes uint8 [..., C], scale float64 [..., C/group], zero float64 [..., C/group]).
@@ -146,6 +173,10 @@ def quantize(z: np.ndarray, group: int = 128, bits: int = 2):
     A block whose scale rounds to 0 (constant block, or a range below fp16's smallest number)
     takes scale = fp16(|min|), or 1 if that is 0 too: every code is then 0 and the block
     reconstructs to its own (fp16-rounded) constant.
+
+    meta_format = 1: scale = the same quotient rounded up to the next E4M3 number (at most 448; a
+    positive range never rounds to 0, so only a constant block takes the |min| rule, with |min|
+    rounded up the same way), zero clamped to the INT8 range -128 .. 127.
     """
     z = np.asarray(z, dtype=np.float64)
     C = z.shape[-1]
@@ -155,12 +186,18 @@ def quantize(z: np.ndarray, group: int = 128, bits: int = 2):
     blocks = z.reshape(z.shape[:-1] + (C // group, group))
     mn = blocks.min(axis=-1)
     mx = blocks.max(axis=-1)
-    scale = np.minimum(_to_f16((mx - mn) / qmax), F16_MAX)            # Eq. 8
+    if meta_format == 1:
+        scale = _to_e4m3_up((mx - mn) / qmax)                         # Eq. 8, stored in FP8
+        alt = _to_e4m3_up(np.abs(mn))
+        zlo, zhi = -128.0, 127.0
+    else:
+        scale = np.minimum(_to_f16((mx - mn) / qmax), F16_MAX)        # Eq. 8, stored in fp16
+        alt = np.minimum(_to_f16(np.abs(mn)), F16_MAX)
+        zlo, zhi = -ZERO_LIMIT, ZERO_LIMIT
     degenerate = scale == 0.0
-    alt = np.minimum(_to_f16(np.abs(mn)), F16_MAX)
     alt = np.where(alt == 0.0, 1.0, alt)
     scale = np.where(degenerate, alt, scale)
-    zero = np.clip(-np.rint(mn / scale), -ZERO_LIMIT, ZERO_LIMIT)      # Eq. 9
+    zero = np.clip(-np.rint(mn / scale), zlo, zhi)                     # Eq. 9
     q = np.rint(blocks / scale[..., None]) + zero[..., None]           # Eq. 6
     codes = np.clip(q, 0.0, qmax).astype(np.uint8)
     return codes.reshape(z.shape), scale, zero + 0.0
@@ -321,11 +358,11 @@ def quantize_append(cache: OracleCache, k: np.ndarray, v: np.ndarray,
         y = rotate_groups(x, cfg.n)
         z = reorder(y, cache.perm)
         k_sink16 = k16
-    kc, ks, kz = quantize(z, cfg.quant_group, cfg.bits)
+    kc, ks, kz = quantize(z, cfg.quant_group, cfg.bits, cfg.meta_format)
     u = v16.astype(np.float64).reshape(B, n_new, E)
     if cfg.v_rotate:
         u = rotate_groups(u, cfg.head_dim)
-    vc, vs, vz = quantize(u, cfg.quant_group, cfg.bits)
+    vc, vs, vz = quantize(u, cfg.quant_group, cfg.bits, cfg.meta_format)
     if sink_mask is not None:
         m = np.asarray(sink_mask).astype(bool)
         for b in range(B):
@@ -441,5 +478,6 @@ def decode_attention_multi(cache: OracleCache, q: np.ndarray, q_pos: np.ndarray)
 
 
 def average_bits(cfg: OracleConfig) -> float:
-    """Stored bits per cached element: codes plus one fp16 scale and one fp16 zero per block."""
-    return cfg.bits + 32.0 / cfg.quant_group
+    """Stored bits per cached element: codes plus the scale and the zero-point of each block (fp16
+    each, or FP8 and INT8 with meta_format = 1)."""
+    return cfg.bits + (16.0 if cfg.meta_format == 1 else 32.0) / cfg.quant_group

@@ -209,6 +209,121 @@ def test_average_bits_matches_paper():
     assert bits / c.size == float(val)
 
 
+# ----------------------------------------------------------------------------- FP8 scale + INT8 zero (Sec. 5.1, Table tab:ablation last row)
+
+def test_e4m3_table_matches_the_library_format():
+    """The oracle's table, built from the format's definition, against torch's float8_e4m3fn
+    decoding of the same bit patterns (a library routine the oracle does not use)."""
+    import torch
+    tab = O.e4m3_values()
+    lib = torch.arange(0, 127, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(tab, lib)
+    assert tab[0] == 0.0 and tab[1] == 2.0 ** -9 and tab[-1] == 448.0 and np.all(np.diff(tab) > 0)
+    assert bool(torch.isnan(torch.tensor([0x7F], dtype=torch.uint8).view(torch.float8_e4m3fn).float()).all())
+
+
+def test_fp8_scale_is_the_quotient_rounded_up():
+    rng = np.random.default_rng(60)
+    x = rng.standard_normal((64, 1024)) * np.exp(rng.uniform(-4, 4, size=(64, 1)))
+    c, s, z = O.quantize(x, group=128, meta_format=1)
+    tab = O.e4m3_values()
+    raw = (x.reshape(64, 8, 128).max(-1) - x.reshape(64, 8, 128).min(-1)) / 3.0
+    idx = np.searchsorted(tab, s)
+    assert np.array_equal(tab[idx], s)                                # an E4M3 number ...
+    assert np.all(s >= raw) and np.all(tab[idx - 1] < raw)            # ... the smallest one that covers the range
+    assert np.all(s <= raw * 1.125 + 2.0 ** -9)                       # at most one 3-bit-mantissa step above
+    assert np.array_equal(z, np.rint(z)) and z.min() >= -128 and z.max() <= 127
+    xh = O.dequantize(c, s, z, group=128)
+    assert np.all(np.abs(x - xh) <= 0.5 * np.repeat(s, 128, axis=-1) * (1 + 1e-12))     # half-step bound, stored scale
+    assert c.min() == 0 and c.max() == 3
+    # the block minimum always takes code 0; the maximum 3, or 2 when the scale was rounded up far enough
+    blocks_c = c.reshape(64, 8, 128)
+    am, aM = x.reshape(64, 8, 128).argmin(-1), x.reshape(64, 8, 128).argmax(-1)
+    assert np.all(np.take_along_axis(blocks_c, am[..., None], -1) == 0)
+    assert np.all(np.take_along_axis(blocks_c, aM[..., None], -1) >= 2)
+
+
+def test_fp8_quantizer_nearest_level_bruteforce():
+    rng = np.random.default_rng(61)
+    for trial in range(200):
+        g = int(rng.choice([4, 8]))
+        x = rng.standard_normal((1, g)) * rng.uniform(0.1, 30) + rng.uniform(-5, 5)
+        c, s, z = O.quantize(x, group=g, meta_format=1)
+        levels = s[0, 0] * (np.arange(4) - z[0, 0])
+        for e in range(g):
+            dist = np.abs(levels - x[0, e])
+            assert dist[c[0, e]] <= dist.min() + 1e-12
+
+
+def test_fp8_saturation_and_clamps():
+    tab = O.e4m3_values()
+    # a range beyond 3 * 448: the scale saturates
+    c, s, z = O.quantize(np.array([[0.0, 3000.0, 10.0, 20.0]]), group=4, meta_format=1)
+    assert s[0, 0] == 448.0 and z[0, 0] == 0 and c[0].tolist() == [0, 3, 0, 0]
+    # a tiny positive range rounds up to the smallest subnormal instead of to 0
+    c, s, z = O.quantize(np.array([[0.0, 1e-6, 0.0, 0.0]]), group=4, meta_format=1)
+    assert s[0, 0] == 2.0 ** -9 and np.all(c == 0)
+    # a block far from 0 compared with its range: the zero-point leaves INT8 and is clamped
+    c, s, z = O.quantize(np.array([[1000.0, 1001.0, 1000.5, 1000.25]]), group=4, meta_format=1)
+    assert s[0, 0] == tab[np.searchsorted(tab, 1.0 / 3.0)] and z[0, 0] == -128 and np.all(c == 3)
+    c, s, z = O.quantize(-np.array([[1000.0, 1001.0, 1000.5, 1000.25]]), group=4, meta_format=1)
+    assert z[0, 0] == 127 and np.all(c == 0)
+    # constant blocks: |min| rounded up, code 0, reconstruction exact when |min| is an E4M3 number
+    for val, exact in [(0.0, True), (2.5, True), (-0.125, True), (2.3, False)]:
+        c, s, z = O.quantize(np.full((1, 8), val), group=8, meta_format=1)
+        xh = O.dequantize(c, s, z, group=8)
+        assert np.all(c == 0) and s[0, 0] > 0
+        assert np.all(np.abs(xh - val) <= 0.5 * s[0, 0])
+        if exact:
+            assert np.all(xh == val)
+
+
+def test_fp8_average_bits_and_effect_on_the_error():
+    """2 bits + (8 + 8) / 128 = 2.125 from the stored arrays; and the coarser scale changes the
+    reconstruction error only a little (the ablation table's last row reports no change in
+    perplexity): between 1x and 1.3x the mean squared error of the fp16 metadata."""
+    rng = np.random.default_rng(62)
+    x = rng.standard_normal((64, 4096))
+    c, s, z = O.quantize(x, group=128, meta_format=1)
+    bits = O.pack_canonical(c).size * 8 + (s.size + z.size) * 8
+    assert bits / c.size == 2.125
+    cfg = O.OracleConfig(batch=1, n_q_heads=32, n_kv_heads=32, meta_format=1)
+    assert O.average_bits(cfg) == 2.125
+    c0, s0, z0 = O.quantize(x, group=128)
+    e8 = np.mean((O.dequantize(c, s, z) - x) ** 2)
+    e16 = np.mean((O.dequantize(c0, s0, z0) - x) ** 2)
+    assert 1.0 <= e8 / e16 <= 1.3
+
+
+def test_fp8_cache_roundtrip_and_attention():
+    """End to end with meta_format = 1: the cache's metadata are E4M3 / INT8 numbers, the
+    reconstruction obeys the half-step bound in the rotated basis, and with every token retained
+    as a sink the read half is still the textbook attention (the format touches only the 2-bit
+    stream)."""
+    cfg = O.OracleConfig(batch=2, n_q_heads=4, n_kv_heads=4, rot_heads=2, max_sinks=40, meta_format=1)
+    rng = np.random.default_rng(63)
+    k = rng.standard_normal((2, 40, 4, 128)).astype(np.float16)
+    v = rng.standard_normal((2, 40, 4, 128)).astype(np.float16)
+    q = rng.standard_normal((2, 4, 128)).astype(np.float16)
+    c = O.cache_new(cfg)
+    O.quantize_append(c, k, v)
+    tab = O.e4m3_values()
+    assert np.isin(c.k_scale, tab).all() and np.isin(c.v_scale, tab).all()
+    assert np.abs(c.k_zero).max() <= 128 and np.abs(c.v_zero).max() <= 128
+    zq = O.dequantize(c.k_codes, c.k_scale, c.k_zero)
+    assert np.all(np.abs(zq - c.k_rot) <= 0.5 * np.repeat(c.k_scale, 128, axis=-1) * (1 + 1e-12))
+    q_pos = np.array([39, 39])
+    out, _ = O.decode_attention(c, q)
+    k_hat, v_hat = O.dequantize_cache(c)
+    ref = _textbook_attention(q.astype(np.float64), k_hat, v_hat, q_pos, 10000.0, 1)
+    assert np.abs(out - ref).max() <= 1e-9
+    c2 = O.cache_new(cfg)
+    O.quantize_append(c2, k, v, np.ones((2, 40), dtype=np.uint8))
+    out2, _ = O.decode_attention(c2, q)
+    ref2 = _textbook_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), q_pos, 10000.0, 1)
+    assert np.abs(out2 - ref2).max() <= 1e-9
+
+
 # ----------------------------------------------------------------------------- RoPE
 
 @pytest.mark.parametrize("style", [0, 1])
