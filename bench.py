@@ -96,6 +96,7 @@ def main():
     ap.add_argument("--path", type=int, default=0, help="decode kernel: 0 auto, 1 general, 2 matrix-core")
     ap.add_argument("--queries", type=int, default=1,
                     help="query tokens per sequence and step (above 1: that many tokens are appended, then read the cache in one multi-query call)")
+    ap.add_argument("--meta-format", type=int, default=0, help="0: fp16 scale and zero-point (2.25 bits); 1: FP8 scale, INT8 zero-point (2.125 bits)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -122,7 +123,8 @@ def main():
     hip = Hip()
 
     cfg = R.RkvConfig(batch=B, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=max(w.n_sinks, 1),
-                      rot_heads=w.rot_heads, perm_span=128, rope_theta=w.rope_theta)
+                      rot_heads=w.rot_heads, perm_span=128, rope_theta=w.rope_theta, meta_format=args.meta_format)
+    MB = 2 if args.meta_format == 1 else 4       # bytes of metadata per (token, block of 128)
     E = cfg.E
     _, scratch_bytes = R.query_sizes(cfg)
     scratch = torch.empty(scratch_bytes * NQ, dtype=torch.uint8, device=dev)
@@ -144,7 +146,7 @@ def main():
         c.set_decode_path(args.path)
         caches.append(c)
         del k, v, mask
-    bulk_bytes = B * n_pre * (2 * E * 2 + 2 * E // 4 + 2 * (E // 128) * 4)
+    bulk_bytes = B * n_pre * (2 * E * 2 + 2 * E // 4 + 2 * (E // 128) * MB)
     bulk_best = min(bulk_ms)
     bulk_avg = sum(bulk_ms) / len(bulk_ms)
 
@@ -211,7 +213,7 @@ def main():
     min_ms = min(kern_ms)
     med_ms = sorted(kern_ms)[len(kern_ms) // 2]
     ctx = T - (K - 1) * NQ / 2.0
-    bytes_per_tok = 2 * E // 4 + 2 * (E // 128) * 4
+    bytes_per_tok = 2 * E // 4 + 2 * (E // 128) * MB
     launch_bytes = B * ctx * bytes_per_tok
     achieved = launch_bytes / (avg_ms * 1e-3) / 1e9
 
@@ -239,7 +241,7 @@ def main():
         "config": {"workload": f"{w.name}: {SHAPES.get(w.name, 'custom')} decode, {L} layers x {w.n_q_heads} query / {w.n_kv_heads} KV heads x 128, "
                                f"batch {B}, context {T}, rotation over {w.rot_heads} heads, 2-bit group-128, {w.n_sinks} fp16 sinks",
                    "decode_path": args.path, "queries_per_step": NQ,
-                   "storage": "u2 codes + fp16 scale / fp16 zero per 128 (2.25 bits per element)",
+                   "storage": "u2 codes + fp16 scale / fp16 zero per 128 (2.25 bits per element)" if MB == 4 else "u2 codes + FP8 E4M3 scale / INT8 zero per 128 (2.125 bits per element)",
                    "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms, "launches_timed": len(kern_ms),

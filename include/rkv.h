@@ -67,6 +67,12 @@ typedef struct rkv_config {
                         /* Needs rot_heads 2 or 4, perm_span = head_dim, v_rotate = 0.  A        */
                         /* retained sink row is brought back to the original basis and rounded   */
                         /* to fp16                                                               */
+  int32_t meta_format;  /* storage of each block's scale and zero-point (Eq. 8-9):               */
+                        /* 0: fp16 + fp16, 2.25 bits per element with the codes;                 */
+                        /* 1: FP8 + INT8 (Sec. 5.1 quantization settings), 2.125 bits: the scale */
+                        /* is rounded UP to the next FP8 E4M3 number (at most 448) and is the    */
+                        /* one Eq. 6 divides by, so 3 steps still cover the block; zero-points   */
+                        /* are clamped to -128..127 (+-2048 with format 0)                       */
 } rkv_config;
 
 typedef struct rkv_cache rkv_cache;   /* opaque host object */

@@ -37,7 +37,7 @@ class _CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "max_tokens", "max_sinks", "rot_heads",
         "quant_group", "bits", "perm_span", "rope_style", "v_rotate")] + [
-        ("rope_theta", C.c_float), ("clip_ratio", C.c_float), ("keys_rotated", C.c_int32)]
+        ("rope_theta", C.c_float), ("clip_ratio", C.c_float), ("keys_rotated", C.c_int32), ("meta_format", C.c_int32)]
 
 
 @dataclass
@@ -57,11 +57,12 @@ class RkvConfig:
     rope_theta: float = 10000.0
     clip_ratio: float = 1.0
     keys_rotated: int = 0
+    meta_format: int = 0
 
     def to_c(self) -> _CConfig:
         return _CConfig(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.max_tokens,
                         self.max_sinks, self.rot_heads, self.quant_group, self.bits, self.perm_span,
-                        self.rope_style, self.v_rotate, self.rope_theta, self.clip_ratio, self.keys_rotated)
+                        self.rope_style, self.v_rotate, self.rope_theta, self.clip_ratio, self.keys_rotated, self.meta_format)
 
     @property
     def E(self) -> int:

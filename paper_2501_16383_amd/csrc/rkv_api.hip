@@ -25,6 +25,7 @@ static int check_config(const rkv_config* c, bool need_capacity) {
   if (c->rope_style != 0 && c->rope_style != 1) return RKV_EINVAL;
   if (c->v_rotate != 0 && c->v_rotate != 1) return RKV_EINVAL;
   if (c->keys_rotated != 0 && c->keys_rotated != 1) return RKV_EINVAL;
+  if (c->meta_format != 0 && c->meta_format != 1) return RKV_EINVAL;
   if (c->keys_rotated && ((c->rot_heads != 2 && c->rot_heads != 4) || c->perm_span != RKV_D || c->v_rotate)) return RKV_EINVAL;
   if (!(c->rope_theta > 1.0f)) return RKV_EINVAL;
   if (need_capacity) {
@@ -44,11 +45,12 @@ static Offsets plan(const rkv_config* c) {
   const size_t B = c->batch, E = (size_t)c->n_kv_heads * RKV_D, NG = E / 128;
   o.Tpad = (c->max_tokens + 255) & ~255;
   const size_t T = o.Tpad, S = c->max_sinks > 0 ? c->max_sinks : 1;
+  const size_t MB = c->meta_format == 1 ? 2 : 4;           // bytes per (token, block) metadata entry
   size_t p = 0;
   o.kc = p; p = align256(p + B * T * E / 4);
-  o.km = p; p = align256(p + B * T * NG * 4);
+  o.km = p; p = align256(p + B * T * NG * MB);
   o.vc = p; p = align256(p + B * T * E / 4);
-  o.vm = p; p = align256(p + B * T * NG * 4);
+  o.vm = p; p = align256(p + B * T * NG * MB);
   o.sk = p; p = align256(p + B * S * E * 2);
   o.sv = p; p = align256(p + B * S * E * 2);
   o.spos = p; p = align256(p + B * S * 4);
@@ -129,6 +131,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.rope_style = cfg->rope_style;
   v.v_rotate = cfg->v_rotate;
   v.keys_rotated = cfg->keys_rotated;
+  v.meta8 = cfg->meta_format == 1;
   v.theta = cfg->rope_theta;
   rc = rkv_launch_init(c, true, (hipStream_t)stream);
   if (rc != RKV_OK) {

@@ -57,19 +57,28 @@ __device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
 // division by 3 is a multiplication (error below 1.5 ulp of fp32, which can change the fp16 scale
 // only within 2^-23 of a rounding boundary) and the reciprocal of the scale is v_rcp_f32 refined by
 // one Newton step.
-__device__ __forceinline__ void quant_params_nodiv(float mn, float mx, float& s, float& zero, float& inv_s) {
+// meta8: FP8 E4M3 scale rounded up, INT8 zero-point.
+__device__ __forceinline__ void quant_params_nodiv(float mn, float mx, float& s, float& zero, float& inv_s, bool meta8) {
   const float raw = (mx - mn) * 0.33333334f;
-  s = __half2float(__float2half_rn(raw));
-  if (!(s <= 65504.0f)) s = 65504.0f;
-  if (s == 0.0f) {
-    s = __half2float(__float2half_rn(fabsf(mn)));
+  if (meta8) {
+    s = rkv_e4m3_round_up(raw);
+    if (s == 0.0f) {
+      s = rkv_e4m3_round_up(fabsf(mn));
+      if (s == 0.0f) s = 1.0f;
+    }
+  } else {
+    s = __half2float(__float2half_rn(raw));
     if (!(s <= 65504.0f)) s = 65504.0f;
-    if (s == 0.0f) s = 1.0f;
+    if (s == 0.0f) {
+      s = __half2float(__float2half_rn(fabsf(mn)));
+      if (!(s <= 65504.0f)) s = 65504.0f;
+      if (s == 0.0f) s = 1.0f;
+    }
   }
   const float r0 = __builtin_amdgcn_rcpf(s);
   inv_s = fmaf(fmaf(-s, r0, 1.0f), r0, r0);
   zero = -rintf(mn * inv_s);
-  zero = fminf(fmaxf(zero, -2048.0f), 2048.0f);
+  zero = meta8 ? fminf(fmaxf(zero, -128.0f), 127.0f) : fminf(fmaxf(zero, -2048.0f), 2048.0f);
 }
 
 // value of x in lane `src_lane` (the address operand is the lane number times 4)
@@ -221,7 +230,7 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
       const float2 m0 = s_mm[0][0][col][ah], m1 = s_mm[0][1][col][ah], m2 = s_mm[1][0][col][ah], m3 = s_mm[1][1][col][ah];
       float sc, zero_h, inv;
       quant_params_nodiv(fminf(fminf(m0.x, m1.x), fminf(m2.x, m3.x)) * rs, fmaxf(fmaxf(m0.y, m1.y), fmaxf(m2.y, m3.y)) * rs, sc,
-                         zero_h, inv);
+                         zero_h, inv, v.meta8);
       const float inv2_h = inv * rs;
       if (wave == 0 && q < G) meta[col * G + ah] = rkv_pack_meta(sc, zero_h);
       float base_h, add_h;
@@ -256,7 +265,7 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
     }
     for (int i = tid; i < 16 * G; i += 256) {
       const int tau = 16 * ti + i / G;
-      if (tau >= tau_first && tau <= tau_last) v.km[mrow + 16 * ti * G + i] = meta[i];
+      if (tau >= tau_first && tau <= tau_last) rkv_store_meta_word(v, v.km, mrow + 16 * ti * G + i, meta[i]);
     }
     return;
   }
@@ -319,7 +328,7 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
   float sc_v, zero_v, inv_v, base_v, add_v;
   {
     const h2 pr = as_h2(mine);
-    quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v);
+    quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v, v.meta8);
     fused_round_consts(zero_v, base_v, add_v);
     const int tau = 8 * wave + (lane & (LPB - 1));
     if ((lane & (LPB - 1)) < 8) meta[tau * G + blk] = rkv_pack_meta(sc_v, zero_v);
@@ -362,7 +371,7 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
   }
   for (int i = tid; i < 32 * G; i += 256) {
     const int tau = i / G;
-    if (tau >= tau_first && tau <= tau_last) v.vm[mrow + i] = meta[i];
+    if (tau >= tau_first && tau <= tau_last) rkv_store_meta_word(v, v.vm, mrow + i, meta[i]);
   }
 }
 

@@ -120,7 +120,7 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
       int sh;
       const uint32_t w = v.kc[rkv_k_dword(v, b, rg, t, c, sh)];
       float sc, zero;
-      rkv_unpack_meta(v.km[rkv_meta_index(v, b, t, v.gid[rg * n + c])], sc, zero);
+      rkv_load_meta(v, v.km, rkv_meta_index(v, b, t, v.gid[rg * n + c]), sc, zero);
       x[i] = sc * ((float)((w >> sh) & 3u) - zero);             // Eq. 7
     }
     fwht_lanes_d<PL>(x, lane, 6);                               // inverse rotation (H is its own inverse)
@@ -154,7 +154,7 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
   for (int i = tid; i < g * GEN_CHUNK; i += 256) {
     const int h = i / GEN_CHUNK, tt = i - h * GEN_CHUNK;
     float sc = 0.f, zero = 0.f;
-    if (t0 + tt < t1) rkv_unpack_meta(v.vm[rkv_meta_index(v, b, t0 + tt, rg * g + h)], sc, zero);
+    if (t0 + tt < t1) rkv_load_meta(v, v.vm, rkv_meta_index(v, b, t0 + tt, rg * g + h), sc, zero);
     s_vs[i] = sc;
     s_vz[i] = zero;
   }

@@ -33,6 +33,7 @@
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 
 #ifndef MF_TILES
 #define MF_TILES 4         // 16-token tiles per wave
@@ -140,7 +141,9 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 
 // MULTI: several query tokens per sequence.  v.Hq then counts virtual heads (nq per real head, see
 // rkv_virtual_head) and virtual head hv only attends tokens at positions <= q_lim[b][query token of hv].
-template <int G, int REP, bool MULTI>
+// META8: scales in FP8 E4M3 and zero-points in 8 bits (rkv_load_meta describes the layout); they
+// are widened to the fp16 operands of the small matrix products right after loading.
+template <int G, int REP, bool MULTI, bool META8>
 __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq) {
@@ -220,22 +223,36 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
         cs_s[p] = cs.y;
       }
       const uint4* ktiles = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tw >> 4));
-      const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * G;
+      const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * (META8 ? G / 2 : G);
 
       uint4 cw[G / 2];
-      uint32_t mw[4][G];
+      constexpr int MW = META8 ? G / 2 : G;              // metadata dwords per token and rotation group
+      uint32_t mw[4][MW];
       auto load_tile = [&](int ti) {
 #pragma unroll
         for (int pr = 0; pr < G / 2; ++pr) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const uint32_t* mp = kmeta + (size_t)(ti * 16 + 4 * q + r) * G;
+        if constexpr (META8) {
+          // the lane's four tokens are consecutive: 4 x 2G bytes in one piece
+          const uint4* mp = reinterpret_cast<const uint4*>(kmeta + (size_t)(ti * 16 + 4 * q) * MW);
+          const uint4 u0 = rkv_ld_stream(mp);
           if constexpr (G == 4) {
-            const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(mp));
-            mw[r][0] = u.x; mw[r][1] = u.y; mw[r][2] = u.z; mw[r][3] = u.w;
+            const uint4 u1 = rkv_ld_stream(mp + 1);
+            mw[0][0] = u0.x; mw[0][1] = u0.y; mw[1][0] = u0.z; mw[1][1] = u0.w;
+            mw[2][0] = u1.x; mw[2][1] = u1.y; mw[3][0] = u1.z; mw[3][1] = u1.w;
           } else {
-            const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(mp));
-            mw[r][0] = u.x; mw[r][1] = u.y;
+            mw[0][0] = u0.x; mw[1][0] = u0.y; mw[2][0] = u0.z; mw[3][0] = u0.w;
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t* mp = kmeta + (size_t)(ti * 16 + 4 * q + r) * G;
+            if constexpr (G == 4) {
+              const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(mp));
+              mw[r][0] = u.x; mw[r][1] = u.y; mw[r][2] = u.z; mw[r][3] = u.w;
+            } else {
+              const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(mp));
+              mw[r][0] = u.x; mw[r][1] = u.y;
+            }
           }
         }
       };
@@ -256,9 +273,19 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
         v4h sA[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const uint32_t a01 = (__builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x05040100u) ^ sm01) & keep_row;
-          uint32_t a23 = 0;
-          if constexpr (G == 4) a23 = (__builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x05040100u) ^ sm23) & keep_row;
+          uint32_t a01, a23 = 0;
+          if constexpr (META8) {
+            // scale bytes 0..G-1 of the token's first dword: FP8 -> fp32 -> fp16, all exact
+            const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8((int)mw[r][0], false);
+            a01 = (pk_f16(f01[0], f01[1]) ^ sm01) & keep_row;
+            if constexpr (G == 4) {
+              const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8((int)mw[r][0], true);
+              a23 = (pk_f16(f23[0], f23[1]) ^ sm23) & keep_row;
+            }
+          } else {
+            a01 = (__builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x05040100u) ^ sm01) & keep_row;
+            if constexpr (G == 4) a23 = (__builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x05040100u) ^ sm23) & keep_row;
+          }
           sA[r] = as_v4h(a01, a23);
         }
         // zero-points: H_128 of a constant block is 128 z e_0, so they only touch channel 0 (lanes
@@ -268,9 +295,21 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
         v4h zB[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const uint32_t z01 = __builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x07060302u) & lane0_mask;
-          uint32_t z23 = 0;
-          if constexpr (G == 4) z23 = __builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x07060302u) & lane0_mask;
+          uint32_t z01, z23 = 0;
+          if constexpr (META8) {
+            // a zero-point byte u = z + 128 under the high byte 0x64 is the fp16 number 1024 + u
+            const uint32_t dz = mw[r][MW - 1];
+            const v2h off = {(_Float16)1152.0f, (_Float16)1152.0f};
+            const uint32_t w01 = __builtin_amdgcn_perm(0x64646464u, dz, G == 4 ? 0x04010400u : 0x04030402u);
+            z01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, w01) - off) & lane0_mask;
+            if constexpr (G == 4) {
+              const uint32_t w23 = __builtin_amdgcn_perm(0x64646464u, dz, 0x04030402u);
+              z23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, w23) - off) & lane0_mask;
+            }
+          } else {
+            z01 = __builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x07060302u) & lane0_mask;
+            if constexpr (G == 4) z23 = __builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x07060302u) & lane0_mask;
+          }
           zB[r] = as_v4h(z01, z23);
         }
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
@@ -386,8 +425,15 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
     // with them a scratch allocation, which keeps some shader engines from holding three workgroups
     uint32_t vmeta[MF_CH / 64];
 #pragma unroll
-    for (int i = 0; i < MF_CH / 64; ++i)
-      vmeta[i] = wave < G ? v.vm[((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G + wave] : 0u;
+    for (int i = 0; i < MF_CH / 64; ++i) {
+      const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G;
+      if constexpr (META8) {
+        const uint8_t* vm8 = reinterpret_cast<const uint8_t*>(v.vm) + 2 * mi;
+        vmeta[i] = wave < G ? ((uint32_t)vm8[wave] | ((uint32_t)vm8[G + wave] << 8)) : 0x8000u;
+      } else {
+        vmeta[i] = wave < G ? v.vm[mi + wave] : 0u;
+      }
+    }
     const bool has_head = q < G;
     const uint4* vslab = reinterpret_cast<const uint4*>(v.vc + rkv_v_slabbase(v, b, rg, t0 >> 5));
     const int lidx = wave * (16 * G) + (has_head ? lane : 0);
@@ -422,7 +468,12 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
         float p = 0.f;
         if (sv[i] > -INFINITY) p = __expf(sv[i] - m);
         float s_, z_;
-        rkv_unpack_meta(vmeta[i], s_, z_);
+        if constexpr (META8) {
+          s_ = __builtin_amdgcn_cvt_f32_fp8((int)vmeta[i], 0);
+          z_ = (float)((vmeta[i] >> 8) & 0xffu) - 128.0f;
+        } else {
+          rkv_unpack_meta(vmeta[i], s_, z_);
+        }
         w[i] = p * s_;
         zv[i] = z_;
         l += p;
@@ -514,7 +565,11 @@ bool rkv_mfma_supported(const rkv_cache* c) {
 template <bool MULTI>
 static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* qt, float* part, int nch, const int* q_lim,
                           int nq, hipStream_t s) {
-#define RKV_MF_LAUNCH(G_, R_) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq)
+#define RKV_MF_LAUNCH(G_, R_)                                                                                              \
+  do {                                                                                                                   \
+    if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+    else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);  \
+  } while (0)
   if (v.g == 4 && share == 1) RKV_MF_LAUNCH(4, 1);
   else if (v.g == 4 && share == 2) RKV_MF_LAUNCH(4, 2);
   else if (v.g == 4) RKV_MF_LAUNCH(4, 4);

@@ -47,6 +47,7 @@ struct RkvView {
   float2* rope;
   uint32_t* hop;     // Hadamard B-operand image for the FP4 matrix instruction: [8 tiles][64 lanes][4 dwords]
   int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate, keys_rotated;
+  int meta8;         // 1: km / vm hold, per (token, rotation group), g FP8 E4M3 scales followed by g 8-bit zero-points (value + 128)
   float theta;
 };
 
@@ -110,6 +111,57 @@ __device__ inline void rkv_unpack_meta(uint32_t u, float& scale, float& zero) {
   __half2 h = *reinterpret_cast<__half2*>(&u);
   scale = __low2float(h);
   zero = __high2float(h);
+}
+
+// FP8 E4M3 (1-4-3, bias 7, subnormals m * 2^-9, largest number 448) written out from the format's
+// definition; x must be one of its non-negative numbers.
+__device__ inline uint32_t rkv_e4m3_encode(float x) {
+  if (x < 0.015625f) return (uint32_t)(x * 512.0f);                    // subnormal (or 0)
+  const uint32_t b = __float_as_uint(x);
+  return ((((b >> 23) & 0xffu) - 120u) << 3) | ((b >> 20) & 7u);
+}
+__device__ inline float rkv_e4m3_decode(uint32_t byte) {
+  const uint32_t e = (byte >> 3) & 15u, m = byte & 7u;
+  if (e == 0) return (float)m * 0.001953125f;
+  return __uint_as_float(((e + 120u) << 23) | (m << 20));
+}
+// smallest E4M3 number >= x (x >= 0), at most 448
+__device__ inline float rkv_e4m3_round_up(float x) {
+  if (!(x < 448.0f)) return 448.0f;
+  if (x < 0.015625f) return ceilf(x * 512.0f) * 0.001953125f;          // multiples of 2^-9 (2^-6 itself is the first normal)
+  return __uint_as_float((__float_as_uint(x) + 0x000fffffu) & 0xfff00000u);   // three mantissa bits, carry into the exponent
+}
+// Entry idx (rkv_meta_index) of a metadata array in the cache's format.  The 8-bit format keeps,
+// for each (token, rotation group), the g scale bytes first and the g zero-point bytes after them
+// (the matrix-core decode kernel converts either kind four at a time); a zero-point z in -128..127
+// is stored as the unsigned byte z + 128.
+__device__ inline void rkv_load_meta(const RkvView& v, const uint32_t* m, size_t idx, float& scale, float& zero) {
+  if (v.meta8) {
+    const uint8_t* p = reinterpret_cast<const uint8_t*>(m) + 2 * (idx - idx % v.g) + idx % v.g;
+    scale = rkv_e4m3_decode(p[0]);
+    zero = (float)p[v.g] - 128.0f;
+  } else {
+    rkv_unpack_meta(m[idx], scale, zero);
+  }
+}
+__device__ inline void rkv_store_meta(const RkvView& v, uint32_t* m, size_t idx, float scale, float zero) {
+  if (v.meta8) {
+    uint8_t* p = reinterpret_cast<uint8_t*>(m) + 2 * (idx - idx % v.g) + idx % v.g;
+    p[0] = (uint8_t)rkv_e4m3_encode(scale);
+    p[v.g] = (uint8_t)((int)zero + 128);
+  } else {
+    m[idx] = rkv_pack_meta(scale, zero);
+  }
+}
+// the same from a staged fp16 pair (scale and zero are exact in fp16 in either format)
+__device__ inline void rkv_store_meta_word(const RkvView& v, uint32_t* m, size_t idx, uint32_t word) {
+  if (v.meta8) {
+    float s, z;
+    rkv_unpack_meta(word, s, z);
+    rkv_store_meta(v, m, idx, s, z);
+  } else {
+    m[idx] = word;
+  }
 }
 
 // Streaming accesses: data that is read or written once per launch (new keys and values, the

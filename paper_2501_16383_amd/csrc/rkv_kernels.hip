@@ -254,7 +254,7 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
         }
         if (on) {
           float sc, zero, inv;
-          quant_params(mn, mx, sc, zero, inv);
+          quant_params(mn, mx, sc, zero, inv, v.meta8);
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             const uint32_t code = quant_code(z[i], inv, zero);
@@ -264,7 +264,7 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
             const int off = rkv_k_off(g, m, c, sh);
             atomicOr(&imgK[r * 128 * g + off], code << sh);
           }
-          if ((lane & 15) == 0) v.km[rkv_meta_index(v, b, t, (ubase + pos) >> 7)] = rkv_pack_meta(sc, zero);
+          if ((lane & 15) == 0) rkv_store_meta(v, v.km, rkv_meta_index(v, b, t, (ubase + pos) >> 7), sc, zero);
         }
         // ---- values: channels pos..pos+7 of the unit, block of 128 = one head
         float u[8];
@@ -291,11 +291,11 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
         }
         if (on) {
           float sc, zero, inv;
-          quant_params(mn, mx, sc, zero, inv);
+          quant_params(mn, mx, sc, zero, inv, v.meta8);
           const int sh = rkv_v_shift(t & 31);
 #pragma unroll
           for (int i = 0; i < 8; ++i) atomicOr(&imgV[pos + i], quant_code(u[i], inv, zero) << sh);
-          if ((lane & 15) == 0) v.vm[rkv_meta_index(v, b, t, (ubase + pos) >> 7)] = rkv_pack_meta(sc, zero);
+          if ((lane & 15) == 0) rkv_store_meta(v, v.vm, rkv_meta_index(v, b, t, (ubase + pos) >> 7), sc, zero);
         }
       }
     }
@@ -391,7 +391,7 @@ __global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __
     }
     {
       float sc, zero, inv;
-      quant_params(mn, mx, sc, zero, inv);
+      quant_params(mn, mx, sc, zero, inv, v.meta8);
       uint32_t part = 0;
       int off = 0;
 #pragma unroll
@@ -425,7 +425,7 @@ __global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __
     }
     {
       float sc, zero, inv;
-      quant_params(mn, mx, sc, zero, inv);
+      quant_params(mn, mx, sc, zero, inv, v.meta8);
       const int sh = rkv_v_shift(tau);
 #pragma unroll
       for (int i = 0; i < PL; ++i) vword[i] |= quant_code(u[i], inv, zero) << sh;
@@ -462,8 +462,8 @@ __global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __
     const int tau = i / G;
     if (tau >= tau_first && tau <= tau_last) {
       const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + ts + tau) * G + (i - tau * G);
-      v.km[mi] = metaK[i];
-      v.vm[mi] = metaV[i];
+      rkv_store_meta_word(v, v.km, mi, metaK[i]);
+      rkv_store_meta_word(v, v.vm, mi, metaV[i]);
     }
   }
 }
@@ -518,7 +518,7 @@ __global__ void __launch_bounds__(64) k_dequant(RkvView v, float* __restrict__ k
       int sh;
       const uint32_t w = v.kc[rkv_k_dword(v, b, rg, t, c, sh)];
       float sc, zero;
-      rkv_unpack_meta(v.km[rkv_meta_index(v, b, t, v.gid[rg * n + c])], sc, zero);
+      rkv_load_meta(v, v.km, rkv_meta_index(v, b, t, v.gid[rg * n + c]), sc, zero);
       x[i] = sc * ((float)((w >> sh) & 3u) - zero);
     }
     fwht_lanes<PL>(x, lane, 6);
@@ -538,7 +538,7 @@ __global__ void __launch_bounds__(64) k_dequant(RkvView v, float* __restrict__ k
           int sh;
           const uint32_t w = v.vc[rkv_v_dword(v, b, rg, t, c0 + i, sh)];
           float sc, zero;
-          rkv_unpack_meta(v.vm[rkv_meta_index(v, b, t, (rg * n + c0) >> 7)], sc, zero);
+          rkv_load_meta(v, v.vm, rkv_meta_index(v, b, t, (rg * n + c0) >> 7), sc, zero);
           u[i] = sc * ((float)((w >> sh) & 3u) - zero);
         }
       }
@@ -598,10 +598,10 @@ __global__ void k_export(RkvView v, uint8_t* kc, float* ks, float* kz, uint8_t* 
     if (j < v.NG) {
       const size_t mi = rkv_meta_index(v, b, t, j), o = bt * v.NG + j;
       float sc, zero;
-      rkv_unpack_meta(v.km[mi], sc, zero);
+      rkv_load_meta(v, v.km, mi, sc, zero);
       if (ks) ks[o] = sc;
       if (kz) kz[o] = zero;
-      rkv_unpack_meta(v.vm[mi], sc, zero);
+      rkv_load_meta(v, v.vm, mi, sc, zero);
       if (vs) vs[o] = sc;
       if (vz) vz[o] = zero;
     }
@@ -637,8 +637,8 @@ __global__ void k_import(RkvView v, int T, const uint8_t* kc, const float* ks, c
     }
     if (j < v.NG) {
       const size_t mi = rkv_meta_index(v, b, t, j), o = bt * v.NG + j;
-      v.km[mi] = rkv_pack_meta(ks[o], kz[o]);
-      v.vm[mi] = rkv_pack_meta(vs[o], vz[o]);
+      rkv_store_meta(v, v.km, mi, ks[o], kz[o]);
+      rkv_store_meta(v, v.vm, mi, vs[o], vz[o]);
     }
   }
 }

@@ -31,8 +31,20 @@ __device__ inline void load_halves(const __half* p, float (&x)[PL]) {
 // Eq. 8-9 for one block of 128 given its min and max: fp16 scale actually stored, integer zero,
 // and the reciprocal of the scale (one IEEE division per block; elements multiply by it, which
 // differs from x / s only within ~1.5 ulp, far inside the rounding-tie window of the parity tests).
-__device__ inline void quant_params(float mn, float mx, float& s, float& zero, float& inv_s) {
+// meta8: the scale is stored in FP8 E4M3 rounded up (a positive range then never rounds to 0) and
+// the zero-point in INT8.
+__device__ inline void quant_params(float mn, float mx, float& s, float& zero, float& inv_s, bool meta8 = false) {
   float raw = (mx - mn) / 3.0f;
+  if (meta8) {
+    s = rkv_e4m3_round_up(raw);
+    if (s == 0.0f) {
+      s = rkv_e4m3_round_up(fabsf(mn));
+      if (s == 0.0f) s = 1.0f;
+    }
+    inv_s = 1.0f / s;
+    zero = fminf(fmaxf(-rintf(mn * inv_s), -128.0f), 127.0f);
+    return;
+  }
   s = __half2float(__float2half_rn(raw));
   if (!(s <= 65504.0f)) s = 65504.0f;
   if (s == 0.0f) {

@@ -28,7 +28,7 @@ def oracle_cfg(cfg: R.RkvConfig) -> O.OracleConfig:
     return O.OracleConfig(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                           rot_heads=cfg.rot_heads, quant_group=cfg.quant_group, bits=cfg.bits, perm_span=cfg.perm_span,
                           rope_style=cfg.rope_style, v_rotate=cfg.v_rotate, rope_theta=cfg.rope_theta,
-                          max_sinks=cfg.max_sinks)
+                          max_sinks=cfg.max_sinks, meta_format=cfg.meta_format)
 
 
 def gpu(x, dtype=None):
@@ -49,8 +49,16 @@ def _fp16_boundary_distance(raw: np.ndarray) -> np.ndarray:
     return d / np.maximum(raw, 1e-300)
 
 
+def _e4m3_boundary_distance(raw: np.ndarray) -> np.ndarray:
+    """Relative distance of raw (> 0) from the nearest E4M3 number: rounding up changes there."""
+    tab = O.e4m3_values()
+    i = np.clip(np.searchsorted(tab, raw), 1, len(tab) - 1)
+    d = np.minimum(np.abs(raw - tab[i]), np.abs(raw - tab[i - 1]))
+    return d / np.maximum(raw, 1e-300)
+
+
 def compare_codes(pre: np.ndarray, o_codes, o_scale, o_zero, g_codes, g_scale, g_zero, what: str, group: int = 128,
-                  rot_span: int = 128, max_ambiguous: float = 0.02):
+                  rot_span: int = 128, max_ambiguous: float = 0.02, meta_format: int = 0):
     """pre: oracle values entering Eq. 6 [.., C]; *_codes uint8 [.., C]; scale/zero [.., C/group].
     rot_span: channels rotated together (the fp32 rotation's error scales with the largest
     magnitude among them, not with a block's range)."""
@@ -60,7 +68,10 @@ def compare_codes(pre: np.ndarray, o_codes, o_scale, o_zero, g_codes, g_scale, g
     span = np.abs(pre).reshape(pre.shape[:-1] + (pre.shape[-1] // rot_span, rot_span)).max(-1)
     mag = np.repeat(span, rot_span // group, axis=-1)                     # per block
     abs_err = TAU_MAG * mag                                               # fp32 rotation error bound
-    amb_group = (_fp16_boundary_distance(raw) < TAU_SCALE + abs_err / np.maximum(raw, 1e-300)) | (raw < 6.2e-5) | (raw > 65000.0)
+    if meta_format == 1:
+        amb_group = (_e4m3_boundary_distance(raw) < TAU_SCALE + abs_err / np.maximum(raw, 1e-300)) | (raw < 1e-6)
+    else:
+        amb_group = (_fp16_boundary_distance(raw) < TAU_SCALE + abs_err / np.maximum(raw, 1e-300)) | (raw < 6.2e-5) | (raw > 65000.0)
     r0 = mn / o_scale
     amb_group |= np.abs(np.abs(r0 - np.floor(r0)) - 0.5) < TAU_ELEM + abs_err / o_scale
     r = blocks / o_scale[..., None]
@@ -74,13 +85,25 @@ def compare_codes(pre: np.ndarray, o_codes, o_scale, o_zero, g_codes, g_scale, g
     bad = (oc != gc) & ~amb_elem
     assert not bad.any(), f"{what}: {int(bad.sum())} codes differ outside rounding ties (of {bad.size})"
     # inside the ambiguous set
-    ulp = np.spacing(o_scale.astype(np.float16)).astype(np.float64)
-    assert np.all(np.abs(g_scale - o_scale) <= np.abs(ulp) + 0.0), f"{what}: scale off by more than one fp16 ulp"
-    assert np.all(np.abs(g_zero - o_zero) <= 1.0), f"{what}: zero off by more than 1"
+    if meta_format == 1:
+        # one E4M3 step is up to 1/8 of the scale, and the zero-point moves with the scale
+        tab = O.e4m3_values()
+        assert np.isin(g_scale, tab).all(), f"{what}: a stored scale is not an E4M3 number"
+        assert np.all(np.abs(np.searchsorted(tab, g_scale) - np.searchsorted(tab, o_scale)) <= 1), f"{what}: scale off by more than one E4M3 step"
+        assert np.all(np.abs(g_zero - o_zero) <= 1.0 + 0.15 * np.abs(o_zero)), f"{what}: zero off by more than a scale step allows"
+        assert g_zero.min() >= -128 and g_zero.max() <= 127
+    else:
+        ulp = np.spacing(o_scale.astype(np.float16)).astype(np.float64)
+        assert np.all(np.abs(g_scale - o_scale) <= np.abs(ulp) + 0.0), f"{what}: scale off by more than one fp16 ulp"
+        assert np.all(np.abs(g_zero - o_zero) <= 1.0), f"{what}: zero off by more than 1"
     assert np.all(np.abs(oc - gc) <= 1), f"{what}: a code is off by more than 1"
     recon = g_scale[..., None] * (gc - g_zero[..., None])
     slack = 1e-5 * np.maximum(np.abs(mx), np.abs(mn))[..., None]
-    assert np.all(np.abs(blocks - recon) <= 0.5 * g_scale[..., None] * (1 + 2.0 ** -8) + slack), f"{what}: half-step bound"
+    bounded = np.ones(g_scale.shape, dtype=bool)
+    if meta_format == 1:      # a saturated scale or a clamped zero-point gives the bound up (on both sides alike)
+        bounded = (raw <= O.E4M3_MAX) & (g_zero > -128) & (g_zero < 127)
+    ok = np.abs(blocks - recon) <= 0.5 * g_scale[..., None] * (1 + 2.0 ** -8) + slack
+    assert np.all(ok | ~bounded[..., None]), f"{what}: half-step bound"
     n_amb = int(amb_elem.sum()) - int(amb_group.sum()) * group
     stats = dict(groups=int(amb_group.size), ambiguous_groups=int(amb_group.sum()), elements=int(oc.size),
                  ambiguous_elements=n_amb, mismatched_codes=int((oc != gc).sum()),
@@ -105,8 +128,9 @@ def check_cache_against_oracle(cache: R.RkvCache, oc: O.OracleCache, tag: str):
     g = export_numpy(cache)
     assert g["k_codes"].shape == oc.k_codes.shape
     sk = compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"], tag + " K",
-                       rot_span=oc.cfg.n)
-    sv = compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], tag + " V")
+                       rot_span=oc.cfg.n, meta_format=oc.cfg.meta_format)
+    sv = compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], tag + " V",
+                       meta_format=oc.cfg.meta_format)
     return g, sk, sv
 
 

@@ -238,13 +238,14 @@ def test_error_codes():
     assert ei.value.code == -5
 
 
-def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag=""):
+def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag="", meta_format=0):
     """One (sequence, rotation group of 4 heads) slice of a full-size run against the oracle: a
     rotation group's codes and attention outputs depend on nothing outside the slice.  The codes
     must equal the oracle's outside the documented rounding ties; the attention output is then
     compared on the GPU's own codes, so that a tie cannot hide in (or leak into) the tolerance.
     exp: export_codes() tensors already on the host (numpy)."""
-    ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=max_sinks)
+    ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=max_sinks,
+                          meta_format=meta_format)
     oc = O.cache_new(ocfg, None if perm is None else perm[512 * rg:512 * (rg + 1)] - 512 * rg)
     O.quantize_append(oc, ks, vs, ms)
     sl_c, sl_m = slice(128 * rg, 128 * (rg + 1)), slice(4 * rg, 4 * rg + 4)
@@ -254,9 +255,9 @@ def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag
         g[name + "_scale"] = exp[name + "_scale"][b:b + 1, :, sl_m].astype(np.float64)
         g[name + "_zero"] = exp[name + "_zero"][b:b + 1, :, sl_m].astype(np.float64)
     P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"],
-                    f"{tag} b={b} rg={rg} K", rot_span=512)
+                    f"{tag} b={b} rg={rg} K", rot_span=512, meta_format=meta_format)
     P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"],
-                    f"{tag} b={b} rg={rg} V")
+                    f"{tag} b={b} rg={rg} V", meta_format=meta_format)
     for name, val in g.items():                                # attention on the GPU's own codes
         setattr(oc, name, val)
     ref, lse_ref = O.decode_attention(oc, q[b:b + 1, 4 * rg:4 * rg + 4])
@@ -272,15 +273,17 @@ def export_host(cache):
     return {k: v.cpu().numpy() for k, v in exp.items()}
 
 
-def test_full_size_config2_sampled():
+@pytest.mark.parametrize("meta_format", [0, 1])
+def test_full_size_config2_sampled(meta_format):
     """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, one single-token append, decode on
     the matrix-core path.  The oracle recomputes sampled (sequence, rotation group) slices - a
-    rotation group's codes and attention outputs depend on nothing outside the slice."""
+    rotation group's codes and attention outputs depend on nothing outside the slice.  Once with
+    fp16 metadata, once with the FP8 scale / INT8 zero-point storage."""
     w = S.WORKLOADS["cfg2"]
     T = w.context
     cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=4,
-                      rot_heads=4, perm_span=128)
+                      rot_heads=4, perm_span=128, meta_format=meta_format)
     perm = calibrated_perm(w, cfg)
     cache = R.RkvCache(cfg)
     cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
@@ -314,7 +317,7 @@ def test_full_size_config2_sampled():
     assert np.isfinite(out).all()
     for (b, rg) in samples:
         ks, vs, ms = keep[(b, rg)]
-        check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag="full-size")
+        check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag=f"full-size meta_format={meta_format}", meta_format=meta_format)
 
 
 def test_full_size_long_context_sampled():
@@ -636,3 +639,51 @@ def test_several_query_tokens_per_step(hq, hkv, g, nq):
     cache.set_decode_path(1)
     with pytest.raises(R.RkvError):
         cache.decode_attention_multi(P.gpu(q), P.gpu(q_pos))
+
+
+@pytest.mark.parametrize("hq,hkv,g,style", [(8, 8, 4, 0), (4, 4, 2, 0), (16, 4, 4, 0), (8, 8, 1, 0), (8, 8, 4, 1), (8, 8, 8, 0)])
+def test_fp8_scale_int8_zero_metadata(hq, hkv, g, style):
+    """meta_format = 1 (FP8 E4M3 scale rounded up, INT8 zero-point: Sec. 5.1 quantization settings)
+    through every write and read kernel: matrix-core and general decode, GQA, rotation sizes that
+    take the general append kernels, interleaved RoPE pairs; appended in pieces with single-token
+    steps; the smaller cache is checked through rkv_query_sizes."""
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
+    kw = dict(batch=2, n_q_heads=hq, n_kv_heads=hkv, max_tokens=700, max_sinks=4, rot_heads=g, rope_style=style)
+    cfg = R.RkvConfig(meta_format=1, **kw)
+    b8, _ = R.query_sizes(cfg)
+    b16, _ = R.query_sizes(R.RkvConfig(**kw))
+    Tpad = 768
+    assert b16 - b8 == 2 * 2 * Tpad * hkv * 2                     # K and V, 2 bytes less per (token, block)
+    paths = (1, 2) if (g in (2, 4) and style == 0) else (1, 0)
+    full_check(w, cfg, 613, chunks=[0, 300, 301, 302, 613], paths=paths)
+
+
+def test_fp8_metadata_saturation_and_clamps():
+    """Blocks whose range or offset leaves what FP8 / INT8 hold: scale saturates at 448, zero-points
+    clamp at -128 / 127, a tiny range rounds up to the smallest subnormal; the GPU must store the
+    same metadata and codes as the oracle (inputs are exact in fp32 and far from rounding ties)."""
+    cfg = R.RkvConfig(batch=1, n_q_heads=4, n_kv_heads=4, max_tokens=16, max_sinks=0, rot_heads=4, v_rotate=0, meta_format=1)
+    rng = np.random.default_rng(77)
+    T = 8
+    v = rng.standard_normal((1, T, 4, 128)).astype(np.float16)
+    v[0, 0, 0] = (v[0, 0, 0].astype(np.float32) * 600).astype(np.float16)        # range ~4000: scale saturates
+    v[0, 1, 1] = (1000.0 + rng.integers(0, 3, 128)).astype(np.float16)         # offset >> range: zero clamps at -128
+    v[0, 2, 2] = (-1000.0 - rng.integers(0, 3, 128)).astype(np.float16)        # ... and at 127
+    v[0, 3, 3] = (rng.integers(0, 2, 128) * 2.0 ** -12).astype(np.float16)     # tiny range: smallest subnormal scale
+    v[0, 4, 0] = np.float16(2.3)                                               # constant block
+    v[0, 5, 1] = np.float16(0.0)
+    k = rng.standard_normal((1, T, 4, 128)).astype(np.float16)
+    cache = R.RkvCache(cfg)
+    oc = O.cache_new(P.oracle_cfg(cfg))
+    cache.quantize_append(P.gpu(k), P.gpu(v))
+    O.quantize_append(oc, k, v)
+    g = P.export_numpy(cache)
+    assert np.array_equal(g["v_scale"], oc.v_scale)
+    assert np.array_equal(g["v_zero"], oc.v_zero)
+    P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], "special blocks V",
+                    meta_format=1)
+    gc = g["v_codes"].reshape(1, T, 4, 128)
+    assert np.all(gc[0, 1, 1] == 3) and np.all(gc[0, 2, 2] == 0) and np.all(gc[0, 3, 3] == 0)
+    assert np.all(gc[0, 4, 0] == 0) and np.all(gc[0, 5, 1] == 0)
+    assert oc.v_scale[0, 0, 0] == 448.0 and oc.v_zero[0, 1, 1] == -128 and oc.v_zero[0, 2, 2] == 127
+    assert oc.v_scale[0, 3, 3] == 2.0 ** -9
