@@ -53,30 +53,43 @@ __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restr
     partner = c ^ 1;
     sgn = (c & 1) ? 1.f : -1.f;
   }
-  // angles: from the table (computed in double, stored as float) when the position lies inside
-  // it - the usual case -, else computed here
-  double sn, cs;
-  if (pos >= 0 && pos < v.Tpad) {
-    const float2 t = v.rope[(size_t)pos * 64 + j];
-    cs = t.x;
-    sn = t.y;
-  } else {
-    sincos((double)pos * pow((double)v.theta, -(double)j / 64.0), &sn, &cs);
-  }
   const float x = __half2float(q[src + c]), p = __half2float(q[src + partner]);
-  const float val = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
-  qr[base + c] = val;
-  // second copy for the matrix-core kernel: [b][rot group][rr / share][n 0..15][p 0..3][KV head a][rr % share][lo, hi]
-  // (rr = which of the query heads sharing KV head a; one workgroup serves `share` of them) with
+  // The matrix-core kernel keeps RoPE angles for the first of a lane's four consecutive tokens only
+  // and rotates all four keys by them; the difference is put on the query side, which is exact:
+  // <R(t + r) k, R(pos) q> = <R(t) k, R(pos - r) q>.  So it gets the query at positions pos - r,
+  // r = 0..3, in its own layout:
+  //   [b][rot group][rr / share][r][p 0..3][f / 4][n 0..15][f % 4],  f = (KV head a * share + rr % share) * 2 + half
+  // (rr = which of the query heads sharing KV head a; one workgroup serves `share` of them; the 16
+  // channel lanes n read consecutive 16-byte pieces, which LDS serves without bank conflicts) with
   // entry (n, p, half) = channel 16p + n + 64*half, pre-multiplied by 2/sqrt(rotation size)
-  // (FP4 nibbles hold code/2; 1/sqrt(n) is the normalisation of Eq. 10)
+  // (FP4 nibbles hold code/2; 1/sqrt(n) is the normalisation of Eq. 10).
   const int g = v.g, rep = v.Hq / v.Hkv;
   const int kvh = h / rep, rr = h - kvh * rep, rg = kvh / g, a = kvh - rg * g;
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;
   const int nn = c & 15, pp = (c >> 4) & 3, half = c >> 6;
   const int rrg = rr / share, rri = rr - rrg * share;
-  qt[(((((((size_t)b * v.NRG + rg) * (rep / share) + rrg) * 16 + nn) * 4 + pp) * g + a) * share + rri) * 2 + half] =
-      val * 2.0f * rsqrtf((float)v.n);
+  const float lane_scale = 2.0f * rsqrtf((float)v.n);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    // angles: from the table (computed in double, stored as float) when the position lies inside
+    // it - the usual case -, else computed here
+    const int pr = pos - r;
+    double sn, cs;
+    if (pr >= 0 && pr < v.Tpad) {
+      const float2 t = v.rope[(size_t)pr * 64 + j];
+      cs = t.x;
+      sn = t.y;
+    } else {
+      sincos((double)pr * pow((double)v.theta, -(double)j / 64.0), &sn, &cs);
+    }
+    const float val = (float)(((double)x * cs + (double)sgn * (double)p * sn) * 0.08838834764831845);
+    if (r == 0) qr[base + c] = val;
+    const int f = (a * share + rri) * 2 + half, nh2 = g * share / 2;
+    size_t o = ((size_t)b * v.NRG + rg) * (rep / share) + rrg;
+    o = (o * 4 + r) * 4 + pp;
+    o = (o * nh2 + (f >> 2)) * 16 + nn;
+    qt[o * 4 + (f & 3)] = val * lane_scale;
+  }
 }
 
 __device__ inline bool is_sink(const int* sp, int cnt, int t) {
@@ -347,15 +360,14 @@ void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int 
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
   const size_t Tpad = (cfg->max_tokens + 255) & ~255;
   const size_t nch = Tpad / 128;
-  const size_t qr = (size_t)cfg->batch * cfg->n_q_heads * RKV_D * 4 * 2;     // natural + lane-ordered copy
-  return ((qr + 255) & ~(size_t)255) + (size_t)cfg->batch * cfg->n_q_heads * nch * RKV_PART_STRIDE * 4 + 256;
+  return rkv_query_scratch_bytes(cfg->batch, cfg->n_q_heads) + (size_t)cfg->batch * cfg->n_q_heads * nch * RKV_PART_STRIDE * 4 + 256;
 }
 
 int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
                               hipStream_t s) {
   const RkvView& v = c->v;
   float* qr = (float*)scratch;
-  const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
+  const size_t qbytes = rkv_query_scratch_bytes(v.B, v.Hq);
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
   rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, 1, 1, s);

@@ -150,34 +150,44 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
   constexpr int NH = G * REP;                    // query heads served by this workgroup: REP per KV head
   constexpr int AP = (4 / REP < G) ? 4 / REP : G; // KV heads per pass of the key phase: 16 score accumulators at most
   __shared__ float s_sc[NH][MF_CH];
-  __shared__ __attribute__((aligned(16))) uint8_t s_A[MF_CH / 32][2][16][4][32];   // [slab][digit set][row][lane group][bytes]
+  // Weight digits of phase S for the matrix products of phase V.  The operand [16 rows = 4 heads x
+  // 4 digits][128 = 4 heads x 32 tokens] is block-diagonal over the heads, so only the 32 token
+  // bytes of each row are kept, [slab][digit set][row][token], followed by one 16-byte piece of
+  // zeros that the lanes holding the operand's empty parts read instead.
+  constexpr int SA_ZERO = 16 * 32, SA_SET = SA_ZERO + 16;
+  __shared__ __attribute__((aligned(16))) uint8_t s_A[MF_CH / 32][2][SA_SET];
   __shared__ float s_m[4], s_l[4], s_zs[4], s_wsc[4];
-  __shared__ int s_sink[4][64];
+  __shared__ int s_sink[64];
   __shared__ uint4 s_H[8][64];                   // Hadamard operand tiles
   __shared__ float2 s_step[64];                  // RoPE rotation by 16 positions, per channel pair
   __shared__ int s_lim[MULTI ? NH : 1];          // last position each served query head may attend
-  __shared__ __attribute__((aligned(16))) float s_q[16][4][2 * NH];  // query [n][p][KV head][query head of it][lo, hi]
+  constexpr int QV = REP == 1 ? 4 : 1;            // query versions held (positions pos - r); with REP > 1 only r = 0
+  __shared__ uint4 s_q[QV][4][NH / 2][16];        // [r][p][f / 4][n] x 4 floats f % 4, f = (KV head * REP + query head of it) * 2 + (lo, hi)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
   const int len = v.len;
   {
-    uint4* a4 = reinterpret_cast<uint4*>(&s_A[0][0][0][0][0]);
+    uint4* a4 = reinterpret_cast<uint4*>(&s_A[0][0][0]);
     for (int i = tid; i < (int)(sizeof(s_A) / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
   }
 
   // Hadamard operand tiles go to LDS once per workgroup; the key phase reads two of them per step
   for (int i = tid; i < 8 * 64; i += 256) (&s_H[0][0])[i] = reinterpret_cast<const uint4*>(v.hop)[i];
-  // RoPE angles are kept for the first of a lane's four tokens only; the other three follow by
-  // rotating one position at a time, the next tile by rotating 16 positions (table rows 1 and 16)
-  // (the 16-position step is used once per tile and is read from LDS there)
+  // RoPE angles are kept for the first of a lane's four tokens only.  With one query head per KV
+  // head they rotate all four keys and the query comes rotated back by 0..3 positions to make up
+  // for it (k_prep_q); with several (REP > 1: the extra query copies would not fit the register
+  // budget) the other three tokens follow by rotating one position at a time (table row 1).  The
+  // next tile follows by rotating 16 positions (table row 16; used once per tile, read from LDS)
   if (tid < 64) s_step[tid] = v.rope[16 * 64 + tid];
   float s1_c[4], s1_s[4];
+  if constexpr (REP > 1) {
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const float2 s1 = v.rope[64 + 16 * p + n];
-    s1_c[p] = s1.x;
-    s1_s[p] = s1.y;
+    for (int p = 0; p < 4; ++p) {
+      const float2 s1 = v.rope[64 + 16 * p + n];
+      s1_c[p] = s1.x;
+      s1_s[p] = s1.y;
+    }
   }
   // row (n & 3) of H_g as fp16 sign masks for the packed scale pairs (blocks 0,1) and (2,3);
   // rows >= G are zero
@@ -199,9 +209,9 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
   const int rep = v.Hq / v.Hkv;
   const int t0 = chunk * MF_CH;
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
-  // every wave keeps its own copy of the sink list and clears its own 64 score slots, so that
-  // phase K needs no workgroup barrier before it
-  s_sink[wave][lane] = lane < cnt ? v.sink_pos[b * v.max_sinks + lane] : -1;
+  // the sink list (complete after the barrier that precedes the key phase); every wave clears
+  // its own 64 score slots
+  if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
 #pragma unroll
   for (int a = 0; a < NH; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
   if constexpr (MULTI) {
@@ -209,8 +219,8 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
     if (tid < NH) s_lim[tid] = min(q_lim[b * nq + (rrg * REP + tid % REP) / (rep / nq)], len - 1);
   }
   // queries of this rotation group, already RoPE'd, scaled and laid out as s_q by k_prep_q
-  for (int i = tid; i < 16 * 4 * 2 * NH / 4; i += 256)
-    reinterpret_cast<uint4*>(&s_q[0][0][0])[i] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (16 * 4 * 2 * NH))[i];
+  for (int i = tid; i < QV * 16 * 4 * 2 * NH / 4; i += 256)
+    (&s_q[0][0][0][0])[i] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (4 * 16 * 4 * 2 * NH))[i];
   {
     // ------------------------------------------------------------------ phase K
     {
@@ -314,7 +324,6 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
         }
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
 
-        const float* sq = &s_q[n][0][0];
         // The key phase runs in passes over AP of the G KV heads, so that the score accumulators
         // (4 tokens x AP heads x REP query heads) stay within 16 registers - more of them and the
         // compiler's allocation leaves the 256-register budget; a pass repeats the matrix products
@@ -340,15 +349,28 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
               hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
             }
           }
-          float qv[2 * AP * REP];                            // [KV head of the pass][query head][lo, hi]
+          float c = cs_c[p], s = cs_s[p];                      // angles of token 4q
+          float qv0[2 * AP * REP];                           // [KV head of the pass][query head][lo, hi]
+          if constexpr (REP > 1) {
 #pragma unroll
-          for (int i = 0; i < 2 * AP * REP; i += 4) {
-            const uint4 u = *reinterpret_cast<const uint4*>(sq + p * (2 * NH) + 2 * REP * a0 + i);
-            qv[i] = __uint_as_float(u.x); qv[i + 1] = __uint_as_float(u.y); qv[i + 2] = __uint_as_float(u.z); qv[i + 3] = __uint_as_float(u.w);
+            for (int i = 0; i < 2 * AP * REP; i += 4) {
+              const uint4 u = s_q[0][p][(2 * REP * a0 + i) / 4][n];
+              qv0[i] = __uint_as_float(u.x); qv0[i + 1] = __uint_as_float(u.y); qv0[i + 2] = __uint_as_float(u.z); qv0[i + 3] = __uint_as_float(u.w);
+            }
           }
-          float c = cs_c[p], s = cs_s[p];                      // token 4q: r = 0
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
+            float qv[2 * AP * REP];
+            if constexpr (REP == 1) {                        // the query at position - r
+#pragma unroll
+              for (int i = 0; i < 2 * AP * REP; i += 4) {
+                const uint4 u = s_q[r][p][(2 * REP * a0 + i) / 4][n];
+                qv[i] = __uint_as_float(u.x); qv[i + 1] = __uint_as_float(u.y); qv[i + 2] = __uint_as_float(u.z); qv[i + 3] = __uint_as_float(u.w);
+              }
+            } else {
+#pragma unroll
+              for (int i = 0; i < 2 * AP * REP; ++i) qv[i] = qv0[i];
+            }
             // k^[a] = sum_blk H_g[a][blk] * scale_blk * u_blk   (H_g butterfly over the blocks)
             // as 16 independent 4x4x4 products per instruction: block = (token 4q + r, 4 channel
             // lanes), A row a = signed fp16 scales, B = the four blocks' results (half-integers
@@ -374,10 +396,12 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
                 pt[o] = fmaf(xh, qv[qo + 1], fmaf(xl, qv[qo], pt[o]));
               }
             }
-            if (r < 3) {                                       // next token: one position further
-              const float c1 = c * s1_c[p] - s * s1_s[p];
-              s = s * s1_c[p] + c * s1_s[p];
-              c = c1;
+            if constexpr (REP > 1) {
+              if (r < 3) {                                     // next token: one position further
+                const float c1 = c * s1_c[p] - s * s1_s[p];
+                s = s * s1_c[p] + c * s1_s[p];
+                c = c1;
+              }
             }
           }
         }
@@ -405,7 +429,7 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
             const int tok = tt + 4 * q + idx / (AP * REP), hq = (a0 + (idx / REP) % AP) * REP + idx % REP;
             bool masked = tok >= len;
             if constexpr (MULTI) masked = tok > s_lim[hq];
-            for (int i = 0; i < cnt; ++i) masked |= (s_sink[wave][i] == tok);
+            for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
             if (!masked) s_sc[hq][tok - t0] = tot;
           }
         } else {
@@ -414,7 +438,7 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
           const int tok = tt + 4 * q + idx / (AP * REP), hq = (a0 + (idx / REP) % AP) * REP + idx % REP;
           bool masked = tok >= len;
           if constexpr (MULTI) masked = tok > s_lim[hq];
-          for (int i = 0; i < cnt; ++i) masked |= (s_sink[wave][i] == tok);
+          for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
           if (n < NV && !masked) s_sc[hq][tok - t0] = tot;
         }
         }
@@ -491,7 +515,7 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
         const int tl = lane + 64 * i, slab = tl >> 5, tau = tl & 31;
         const uint32_t W = (uint32_t)rintf(w[i] * up);
         zs += (float)W * zv[i];
-        uint8_t* dst = &s_A[slab][0][4 * a][2 * (a & 1) + (tau >> 4)][16 * (a >> 1) + (tau & 15)];
+        uint8_t* dst = &s_A[slab][0][(4 * a) * 32 + tau];
 #pragma unroll
         for (int k = 0; k < 6; k += 2) {
           // digits 5-k and 4-k (most significant first): rows 0..3 of set 0, rows 0..1 of set 1
@@ -499,8 +523,8 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
           const float d_lo = (float)((W >> (16 - 4 * k)) & 15u);
           const int pk = __builtin_amdgcn_cvt_pk_fp8_f32(d_hi, d_lo, 0, false);
           const int row = k & 3, set = k >> 2;
-          dst[set * (16 * 4 * 32) + row * (4 * 32)] = (uint8_t)(pk & 0xff);
-          dst[set * (16 * 4 * 32) + (row + 1) * (4 * 32)] = (uint8_t)((pk >> 8) & 0xff);
+          dst[set * SA_SET + row * 32] = (uint8_t)(pk & 0xff);
+          dst[set * SA_SET + (row + 1) * 32] = (uint8_t)((pk >> 8) & 0xff);
         }
       }
       zs = wave_allreduce<false>(zs);
@@ -515,6 +539,15 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
 
     // ------------------------------------------------------------------ phase V
     {
+      // Operand lane (row n = 4 * head + digit, lane group q) covers contraction indices 32q..32q+31,
+      // which the V codes' layout assigns to head 2 * (second half of the 32) + (q >> 1), tokens
+      // 16 * (q & 1) .. + 15 of the slab: its first or second 16 bytes are that head's row, the
+      // rest of the operand is zero
+      const int arow = n >> 2;
+      const bool ause = (q >> 1) == (arow & 1);
+      const int adata = n * 32 + 16 * (q & 1);
+      const int aoff0 = (ause && (arow >> 1) == 0) ? adata : SA_ZERO;
+      const int aoff1 = (ause && (arow >> 1) == 1) ? adata : SA_ZERO;
       v4f acc[2][2];                                        // [channel tile][digit set]
 #pragma unroll
       for (int i = 0; i < 2; ++i) acc[i][0] = acc[i][1] = (v4f){0.f, 0.f, 0.f, 0.f};
@@ -524,8 +557,8 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
           v8i A[2];
 #pragma unroll
           for (int set = 0; set < 2; ++set) {
-            const uint4* ap = reinterpret_cast<const uint4*>(&s_A[sl][set][n][q][0]);
-            const uint4 a0 = ap[0], a1 = ap[1];
+            const uint4 a0 = *reinterpret_cast<const uint4*>(&s_A[sl][set][aoff0]);
+            const uint4 a1 = *reinterpret_cast<const uint4*>(&s_A[sl][set][aoff1]);
             A[set][0] = (int)a0.x; A[set][1] = (int)a0.y; A[set][2] = (int)a0.z; A[set][3] = (int)a0.w;
             A[set][4] = (int)a1.x; A[set][5] = (int)a1.y; A[set][6] = (int)a1.z; A[set][7] = (int)a1.w;
           }
@@ -592,7 +625,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   RkvView v = c->v;
   v.Hq *= nq;                                               // virtual heads
   float* qr = (float*)scratch;
-  const size_t qbytes = (((size_t)v.B * v.Hq * RKV_D * 4 * 2) + 255) & ~(size_t)255;
+  const size_t qbytes = rkv_query_scratch_bytes(v.B, v.Hq);
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
   const int rep = v.Hq / v.Hkv;

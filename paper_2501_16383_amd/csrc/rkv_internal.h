@@ -193,6 +193,12 @@ __device__ inline RkvVHead rkv_virtual_head(const RkvView& v, int hv, int nq) {
   return r;
 }
 
+// bytes at the start of the decode scratch block that hold the prepared queries: the natural
+// layout once, the matrix-core kernel's lane-ordered layout four times (see k_prep_q)
+inline size_t rkv_query_scratch_bytes(size_t batch, size_t n_q_heads) {
+  return (batch * n_q_heads * RKV_D * 4 * 5 + 255) & ~(size_t)255;
+}
+
 // kernels' host launchers (defined in the .hip files)
 int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s);
 int rkv_launch_set_perm_tables(rkv_cache* c, hipStream_t s);
