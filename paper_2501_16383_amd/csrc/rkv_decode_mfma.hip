@@ -25,9 +25,9 @@
 //   phase V  wave w: channels 32w..32w+31 of every head; A = weight digits [16 x (4 heads x 32
 //            tokens)], block-diagonal over heads, B = codes [(4 heads x 32 tokens) x 16 channels].
 // Covers: reorder that keeps 128-blocks (gid[c] == c/128), rot_heads 2 or 4, half-split RoPE
-// pairs.  With GQA a workgroup serves up to 4 of the query heads that share a KV head: unpacking,
-// rotation and RoPE of the keys are done once for them, the softmax and value phases once per
-// query head.  Everything else takes the general kernel.
+// pairs.  With GQA (or several query tokens per step) a workgroup serves two of the query heads
+// that share a KV head: unpacking, rotation and RoPE of the keys are done once for them, the
+// softmax and value phases once per query head.  Everything else takes the general kernel.
 #include "rkv_internal.h"
 
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -39,6 +39,9 @@ typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 #define MF_TILES 4         // 16-token tiles per wave
 #endif
 #define MF_CH (64 * MF_TILES)   // tokens per workgroup (4 waves)
+#ifndef MF_ACC
+#define MF_ACC 16         // score accumulators per lane and pass of the key phase
+#endif
 #ifndef MF_OCC
 #define MF_OCC 3           // workgroups per compute unit the register budget is set for
 #endif
@@ -144,11 +147,11 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // META8: scales in FP8 E4M3 and zero-points in 8 bits (rkv_load_meta describes the layout); they
 // are widened to the fp16 operands of the small matrix products right after loading.
 template <int G, int REP, bool MULTI, bool META8>
-__global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
+__global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq) {
   constexpr int NH = G * REP;                    // query heads served by this workgroup: REP per KV head
-  constexpr int AP = (4 / REP < G) ? 4 / REP : G; // KV heads per pass of the key phase: 16 score accumulators at most
+  constexpr int RP = (MF_ACC / (G * REP) < 4) ? MF_ACC / (G * REP) : 4;   // tokens (of a lane's four) per pass of the key phase: MF_ACC score accumulators at most
   __shared__ float s_sc[NH][MF_CH];
   // Weight digits of phase S for the matrix products of phase V.  The operand [16 rows = 4 heads x
   // 4 digits][128 = 4 heads x 32 tokens] is block-diagonal over the heads, so only the 32 token
@@ -179,7 +182,7 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
   // for it (k_prep_q); with several (REP > 1: the extra query copies would not fit the register
   // budget) the other three tokens follow by rotating one position at a time (table row 1).  The
   // next tile follows by rotating 16 positions (table row 16; used once per tile, read from LDS)
-  if (tid < 64) s_step[tid] = v.rope[16 * 64 + tid];
+  if (tid < 64) s_step[tid] = v.rope[(REP == 1 ? 16 : 12) * 64 + tid];
   float s1_c[4], s1_s[4];
   if constexpr (REP > 1) {
 #pragma unroll
@@ -324,15 +327,16 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
         }
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
 
-        // The key phase runs in passes over AP of the G KV heads, so that the score accumulators
-        // (4 tokens x AP heads x REP query heads) stay within 16 registers - more of them and the
-        // compiler's allocation leaves the 256-register budget; a pass repeats the matrix products
-        // and the packing, which costs less than repeating RoPE per query head.
+        // The key phase runs in passes over RP of the lane's four tokens, so that the score
+        // accumulators (RP tokens x G heads x REP query heads) stay within 16 registers - more of
+        // them and the compiler's allocation leaves the 256-register budget.  A pass repeats the big
+        // matrix products (every one yields all four tokens), which costs less than repeating the
+        // small ones, the packing or RoPE.
 #pragma unroll
-        for (int a0 = 0; a0 < G; a0 += AP) {
-        float pt[4 * AP * REP];                            // [r][KV head of the pass][query head of it]
+        for (int r0 = 0; r0 < 4; r0 += RP) {
+        float pt[RP * G * REP];                            // [token of the pass][KV head][query head of it]
 #pragma unroll
-        for (int i = 0; i < 4 * AP * REP; ++i) pt[i] = 0.f;
+        for (int i = 0; i < RP * G * REP; ++i) pt[i] = 0.f;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           // H_128 of the raw codes for channels 16p + n (lo) and 16p + n + 64 (hi): half-integers, exact
@@ -349,28 +353,10 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
               hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
             }
           }
-          float c = cs_c[p], s = cs_s[p];                      // angles of token 4q
-          float qv0[2 * AP * REP];                           // [KV head of the pass][query head][lo, hi]
-          if constexpr (REP > 1) {
+          float c = cs_c[p], s = cs_s[p];                      // angles of the pass's first token (REP == 1: of token 4q)
 #pragma unroll
-            for (int i = 0; i < 2 * AP * REP; i += 4) {
-              const uint4 u = s_q[0][p][(2 * REP * a0 + i) / 4][n];
-              qv0[i] = __uint_as_float(u.x); qv0[i + 1] = __uint_as_float(u.y); qv0[i + 2] = __uint_as_float(u.z); qv0[i + 3] = __uint_as_float(u.w);
-            }
-          }
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            float qv[2 * AP * REP];
-            if constexpr (REP == 1) {                        // the query at position - r
-#pragma unroll
-              for (int i = 0; i < 2 * AP * REP; i += 4) {
-                const uint4 u = s_q[r][p][(2 * REP * a0 + i) / 4][n];
-                qv[i] = __uint_as_float(u.x); qv[i + 1] = __uint_as_float(u.y); qv[i + 2] = __uint_as_float(u.z); qv[i + 3] = __uint_as_float(u.w);
-              }
-            } else {
-#pragma unroll
-              for (int i = 0; i < 2 * AP * REP; ++i) qv[i] = qv0[i];
-            }
+          for (int rr = 0; rr < RP; ++rr) {
+            const int r = r0 + rr;
             // k^[a] = sum_blk H_g[a][blk] * scale_blk * u_blk   (H_g butterfly over the blocks)
             // as 16 independent 4x4x4 products per instruction: block = (token 4q + r, 4 channel
             // lanes), A row a = signed fp16 scales, B = the four blocks' results (half-integers
@@ -386,27 +372,43 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
               klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), zc);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), z4);
             }
+            // the query: with REP == 1 the copy rotated back by r positions, else the plain one
+            // (floats 2 * REP * a .. of the row belong to KV head a: [query head of it][lo, hi])
+            constexpr int QF = (2 * REP * G < 8) ? 2 * REP * G : 8;   // floats fetched at a time
 #pragma unroll
-            for (int al = 0; al < AP; ++al) {
-              const float xl = klo[a0 + al] * c - khi[a0 + al] * s;
-              const float xh = klo[a0 + al] * s + khi[a0 + al] * c;
+            for (int f0 = 0; f0 < 2 * REP * G; f0 += QF) {
+              float qv[QF];
 #pragma unroll
-              for (int rri = 0; rri < REP; ++rri) {
-                const int o = (r * AP + al) * REP + rri, qo = 2 * (al * REP + rri);
-                pt[o] = fmaf(xh, qv[qo + 1], fmaf(xl, qv[qo], pt[o]));
+              for (int i = 0; i < QF; i += 4) {
+                const uint4 u = s_q[REP == 1 ? r : 0][p][(f0 + i) / 4][n];
+                qv[i] = __uint_as_float(u.x); qv[i + 1] = __uint_as_float(u.y); qv[i + 2] = __uint_as_float(u.z); qv[i + 3] = __uint_as_float(u.w);
+              }
+#pragma unroll
+              for (int fa = 0; fa < QF; fa += 2 * REP) {
+                const int a = (f0 + fa) / (2 * REP);
+                const float xl = klo[a] * c - khi[a] * s;
+                const float xh = klo[a] * s + khi[a] * c;
+#pragma unroll
+                for (int rri = 0; rri < REP; ++rri) {
+                  const int o = (rr * G + a) * REP + rri;
+                  pt[o] = fmaf(xh, qv[fa + 2 * rri + 1], fmaf(xl, qv[fa + 2 * rri], pt[o]));
+                }
               }
             }
-            if constexpr (REP > 1) {
-              if (r < 3) {                                     // next token: one position further
-                const float c1 = c * s1_c[p] - s * s1_s[p];
-                s = s * s1_c[p] + c * s1_s[p];
-                c = c1;
-              }
+            if constexpr (REP > 1) {                           // next token: one position further
+              const float c1 = c * s1_c[p] - s * s1_s[p];
+              s = s * s1_c[p] + c * s1_s[p];
+              c = c1;
             }
           }
+          if constexpr (REP > 1) {                             // the state moves on with the passes
+            cs_c[p] = c;
+            cs_s[p] = s;
+          }
         }
-        if (a0 + AP >= G) {
-          // after the last pass: advance the RoPE state by 16 positions
+        if (r0 + RP >= 4) {
+          // after the last pass: on to the next tile's first token (16 positions from this tile's;
+          // with REP > 1 the passes have covered 4 of them)
 #pragma unroll
           for (int p = 0; p < 4; ++p) {
             const float c = cs_c[p], s = cs_s[p];
@@ -415,31 +417,22 @@ __global__ void __launch_bounds__(256, (REP > 1 || MULTI) ? 2 : MF_OCC) k_decode
             cs_s[p] = s * st.x + c * st.y;
           }
         }
-        // reduce over the 16 channel lanes, 16 values at a time: value idx = (r * AP + al) * REP + rri
-        // ends in lane idx % 16 (token 4q + r, query head (a0 + al) * REP + rri)
-        constexpr int NV = 4 * AP * REP;
-        if constexpr (NV > 16) {
+        // reduce over the 16 channel lanes: value idx = (rr * G + a) * REP + rri ends in lane idx
+        // (token 4q + r0 + rr, query head a * REP + rri)
+        constexpr int NV = RP * G * REP;
+        constexpr int NR = NV < 16 ? NV : 16;              // values per transposing reduction
 #pragma unroll
-          for (int j = 0; j < NV / 16; ++j) {
-            float grp[16];
+        for (int j = 0; j < NV / NR; ++j) {
+          float grp[NR];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) grp[i] = pt[16 * j + i];
-            const float tot = row_transpose_reduce<16>(grp, n);
-            const int idx = 16 * j + n;
-            const int tok = tt + 4 * q + idx / (AP * REP), hq = (a0 + (idx / REP) % AP) * REP + idx % REP;
-            bool masked = tok >= len;
-            if constexpr (MULTI) masked = tok > s_lim[hq];
-            for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
-            if (!masked) s_sc[hq][tok - t0] = tot;
-          }
-        } else {
-          const float tot = row_transpose_reduce<NV>(pt, n);
-          const int idx = n & (NV - 1);
-          const int tok = tt + 4 * q + idx / (AP * REP), hq = (a0 + (idx / REP) % AP) * REP + idx % REP;
+          for (int i = 0; i < NR; ++i) grp[i] = pt[NR * j + i];
+          const float tot = row_transpose_reduce<NR>(grp, n);
+          const int idx = NR * j + (n & (NR - 1));
+          const int tok = tt + 4 * q + r0 + idx / (G * REP), hq = idx % (G * REP);
           bool masked = tok >= len;
           if constexpr (MULTI) masked = tok > s_lim[hq];
           for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
-          if (n < NV && !masked) s_sc[hq][tok - t0] = tot;
+          if (n < NR && !masked) s_sc[hq][tok - t0] = tot;
         }
         }
       }
@@ -604,11 +597,9 @@ static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* q
     else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);  \
   } while (0)
   if (v.g == 4 && share == 1) RKV_MF_LAUNCH(4, 1);
-  else if (v.g == 4 && share == 2) RKV_MF_LAUNCH(4, 2);
-  else if (v.g == 4) RKV_MF_LAUNCH(4, 4);
+  else if (v.g == 4) RKV_MF_LAUNCH(4, 2);
   else if (share == 1) RKV_MF_LAUNCH(2, 1);
-  else if (share == 2) RKV_MF_LAUNCH(2, 2);
-  else RKV_MF_LAUNCH(2, 4);
+  else RKV_MF_LAUNCH(2, 2);
 #undef RKV_MF_LAUNCH
 }
 
@@ -629,7 +620,10 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
   const int rep = v.Hq / v.Hkv;
-  const int share = rep % 4 == 0 ? 4 : (rep % 2 == 0 ? 2 : 1);   // query heads of a KV head served by one workgroup
+  // query heads of a KV head served by one workgroup: two where the ratio is even (four per
+  // workgroup measured slower: 158 against 151 us on the GQA configuration - the variant needs
+  // more registers than three workgroups per compute unit leave)
+  const int share = rep % 2 == 0 ? 2 : 1;
   rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   dim3 grid(((nch + 7) & ~7) * (rep / share), v.NRG, v.B);
