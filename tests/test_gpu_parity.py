@@ -687,3 +687,35 @@ def test_fp8_metadata_saturation_and_clamps():
     assert np.all(gc[0, 4, 0] == 0) and np.all(gc[0, 5, 1] == 0)
     assert oc.v_scale[0, 0, 0] == 448.0 and oc.v_zero[0, 1, 1] == -128 and oc.v_zero[0, 2, 2] == 127
     assert oc.v_scale[0, 3, 3] == 2.0 ** -9
+
+
+def test_shared_scratch_reused_across_caches():
+    """Two caches with different contents share one scratch block (as the layers of a model do) and
+    are decoded alternately, many times: every result must equal the first one bit for bit and
+    agree with the general kernel - partial results or prepared queries left over from the other
+    cache's call must never leak into a result."""
+    w = small("cfg2", n_q_heads=16, n_kv_heads=16)
+    T = 4096
+    cfg = R.RkvConfig(batch=8, n_q_heads=16, n_kv_heads=16, max_tokens=T, max_sinks=4, rot_heads=4)
+    dev = torch.device("cuda:0")
+    _, scratch_bytes = R.query_sizes(cfg)
+    scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device=dev)
+    caches, qs, refs = [], [], []
+    for i in range(2):
+        c = R.RkvCache(cfg, scratch=scratch)
+        k, v, mask = S.make_kv_torch(w, T, dev, batch=8, layer=i)
+        c.quantize_append(k, v, mask)
+        q = S.make_q_torch(w, dev, batch=8, layer=i)
+        c.set_decode_path(1)
+        ref = c.decode_attention(q).clone()
+        c.set_decode_path(2)
+        first = c.decode_attention(q).clone()
+        torch.cuda.synchronize()
+        err = float((first - ref).abs().max() / ref.abs().max())
+        print(f"[parity] cache {i}: matrix-core vs general kernel {err:.3e}", flush=True)
+        assert err <= 1e-4
+        caches.append(c); qs.append(q); refs.append(first)
+    for rep in range(40):
+        for i in range(2):
+            out = caches[i].decode_attention(qs[i])
+            assert torch.equal(out, refs[i]), f"repetition {rep}, cache {i}"
