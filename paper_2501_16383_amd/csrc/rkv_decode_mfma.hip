@@ -271,6 +271,14 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
       };
       load_tile(0);
       __syncthreads();        // LDS copies of the Hadamard operand and the query are complete; first tile already in flight
+      // which of the wave's tiles hold a retained sink token (a wave-uniform bit mask): the others
+      // skip the comparison with the sink list
+      uint32_t sink_tiles = 0;
+      for (int i = 0; i < cnt; ++i) {
+        const int d = s_sink[i] - tw;
+        if (d >= 0 && d < 16 * MF_TILES) sink_tiles |= 1u << (d >> 4);
+      }
+      sink_tiles = __builtin_amdgcn_readfirstlane(sink_tiles);
 
 #pragma unroll
       for (int ti = 0; ti < MF_TILES; ++ti) {
@@ -431,7 +439,8 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
           const int tok = tt + 4 * q + r0 + idx / (G * REP), hq = idx % (G * REP);
           bool masked = tok >= len;
           if constexpr (MULTI) masked = tok > s_lim[hq];
-          for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
+          if (sink_tiles & (1u << ti))
+            for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
           if (n < NR && !masked) s_sc[hq][tok - t0] = tot;
         }
         }
