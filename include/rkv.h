@@ -91,8 +91,12 @@ void rkv_cache_destroy(rkv_cache* cache);
 /* Forget all tokens and sinks (length 0); keeps the reorder indices. */
 int rkv_cache_reset(rkv_cache* cache, void* stream);
 
-/* Tokens currently cached per sequence (host-side count), or RKV_EINVAL. */
+/* Tokens currently cached per sequence (host-side count; of the longest sequence once lengths
+ * differ), or RKV_EINVAL. */
 int rkv_cache_length(const rkv_cache* cache);
+
+/* The same per sequence: host_lengths [batch] int32 (host memory). */
+int rkv_cache_lengths(const rkv_cache* cache, int32_t* host_lengths);
 
 /* Calibration for reordering indices (Alg. 1): rotate the calibration keys with the grouped-head
  * Hadamard, sum every channel over all tokens (signed, float64), and sort channel indices by that
@@ -139,6 +143,22 @@ int rkv_select_sinks(const void* dev_x, int32_t batch, int32_t n_tok, int32_t wi
  * Works for one token (decode step) or many (prefill).  RKV_ECAPACITY past max_tokens. */
 int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, int32_t n_new,
                         const uint8_t* dev_sink_mask, void* stream);
+
+/* The same for sequences of different lengths (a batch of prompts, sequences that join a running
+ * batch): sequence b appends the first host_n_new[b] of its n_new_max rows at its own length.
+ * From then on every sequence has its own length: appends go to each sequence's own end, decode
+ * attention reads each sequence's own tokens (default query position: its own last token), and
+ * a sequence of length 0 makes decode return RKV_ESTATE.
+ *   dev_k, dev_v    [batch][n_new_max][n_kv_heads][head_dim] fp16; rows beyond host_n_new[b] are not read
+ *   host_n_new      [batch] int32 in host memory, 0 <= host_n_new[b] <= n_new_max; read before the call returns
+ *   dev_sink_mask   [batch][n_new_max] uint8 or NULL
+ * Needs a configuration the matrix-core append kernel covers (reorder inside blocks of 128,
+ * rot_heads 2 or 4, v_rotate 0), else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
+ * max_tokens (nothing is appended then).  rkv_import_codes returns RKV_ESTATE on such a cache;
+ * the export and dequantize views cover rkv_cache_length tokens for every sequence, and what they
+ * show past a sequence's own length is unspecified. */
+int rkv_quantize_append_ragged(rkv_cache* cache, const void* dev_k, const void* dev_v, int32_t n_new_max,
+                               const int32_t* host_n_new, const uint8_t* dev_sink_mask, void* stream);
 
 /* Read half: one decode step of attention over the whole cache (Eq. 5).
  *   dev_q      [batch][n_q_heads][head_dim] fp16, pre-RoPE

@@ -20,7 +20,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
     "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention", "rkv_decode_attention_with_current",
-    "rkv_decode_attention_multi",
+    "rkv_decode_attention_multi", "rkv_quantize_append_ragged", "rkv_cache_lengths",
     "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
@@ -97,6 +97,8 @@ def load_library():
     lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.rkv_decode_attention_with_current.argtypes = [vp] * 9
     lib.rkv_decode_attention_multi.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp, vp]
+    lib.rkv_quantize_append_ragged.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp]
+    lib.rkv_cache_lengths.argtypes = [vp, vp]
     lib.rkv_set_decode_path.argtypes = [vp, i32]
     lib.rkv_set_profile_events.argtypes = [vp, vp, vp]
     lib.rkv_dequantize.argtypes = [vp, vp, vp, vp]
@@ -255,6 +257,30 @@ class RkvCache:
             raise ValueError("sink_mask must be [batch, n_new]")
         _check(self.lib.rkv_quantize_append(self.handle, _ptr(k), _ptr(v), n_new, _ptr(sink_mask), _stream()),
                "rkv_quantize_append")
+
+    @property
+    def lengths(self):
+        """Tokens cached per sequence (list of ints)."""
+        arr = (C.c_int32 * self.cfg.batch)()
+        _check(self.lib.rkv_cache_lengths(self.handle, arr), "rkv_cache_lengths")
+        return list(arr)
+
+    def quantize_append_ragged(self, k, v, n_new, sink_mask=None):
+        """rkv_quantize_append_ragged: k, v [batch, n_new_max, n_kv_heads, 128] fp16; n_new: ints per sequence."""
+        import torch
+        k = _dev(k, torch.float16, "k")
+        v = _dev(v, torch.float16, "v")
+        sink_mask = _dev(sink_mask, torch.uint8, "sink_mask")
+        B, n_max = k.shape[0], k.shape[1]
+        if k.shape != (B, n_max, self.cfg.n_kv_heads, self.cfg.head_dim) or v.shape != k.shape or B != self.cfg.batch:
+            raise ValueError("k, v must be [batch, n_new_max, n_kv_heads, head_dim]")
+        if sink_mask is not None and sink_mask.shape != (B, n_max):
+            raise ValueError("sink_mask must be [batch, n_new_max]")
+        if len(n_new) != B:
+            raise ValueError("n_new must hold one count per sequence")
+        arr = (C.c_int32 * B)(*[int(x) for x in n_new])
+        _check(self.lib.rkv_quantize_append_ragged(self.handle, _ptr(k), _ptr(v), n_max, arr, _ptr(sink_mask), _stream()),
+               "rkv_quantize_append_ragged")
 
     def decode_attention(self, q, q_pos=None, out=None, lse=None, want_lse=False, k_cur=None, v_cur=None):
         import torch

@@ -36,7 +36,7 @@ static int check_config(const rkv_config* c, bool need_capacity) {
 }
 
 struct Offsets {
-  size_t kc, km, vc, vm, sk, sv, spos, scnt, tables, perm, pinv, gid, rope, hop, total;
+  size_t kc, km, vc, vm, sk, sv, spos, scnt, lens, nnew, tables, perm, pinv, gid, rope, hop, total;
   int Tpad;
 };
 
@@ -55,6 +55,8 @@ static Offsets plan(const rkv_config* c) {
   o.sv = p; p = align256(p + B * S * E * 2);
   o.spos = p; p = align256(p + B * S * 4);
   o.scnt = p; p = align256(p + B * 4);
+  o.lens = p; p = align256(p + B * 4);
+  o.nnew = p; p = align256(p + B * 4);
   o.tables = p;
   o.perm = p; p = align256(p + E * 4);
   o.pinv = p; p = align256(p + E * 4);
@@ -93,6 +95,15 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   c->blocks_aligned = 1;
   c->decode_path = 0;
   c->ev_start = c->ev_stop = nullptr;
+  c->cur_k = c->cur_v = nullptr;
+  c->ragged = 0;
+  c->hlens = new (std::nothrow) int32_t[cfg->batch]();
+  if (!c->hlens) {
+    delete c;
+    return RKV_EINVAL;
+  }
+  c->dev_lens = (int*)(c->base + o.lens);
+  c->dev_nnew = (int*)(c->base + o.nnew);
   {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
@@ -132,6 +143,8 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.v_rotate = cfg->v_rotate;
   v.keys_rotated = cfg->keys_rotated;
   v.meta8 = cfg->meta_format == 1;
+  v.lens = nullptr;
+  v.nnew = nullptr;
   v.theta = cfg->rope_theta;
   rc = rkv_launch_init(c, true, (hipStream_t)stream);
   if (rc != RKV_OK) {
@@ -142,15 +155,27 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   return RKV_OK;
 }
 
-RKV_EXPORT void rkv_cache_destroy(rkv_cache* cache) { delete cache; }
+RKV_EXPORT void rkv_cache_destroy(rkv_cache* cache) {
+  if (cache) delete[] cache->hlens;
+  delete cache;
+}
 
 RKV_EXPORT int rkv_cache_reset(rkv_cache* cache, void* stream) {
   if (!cache) return RKV_EINVAL;
   cache->v.len = 0;
+  cache->v.lens = nullptr;
+  cache->ragged = 0;
+  for (int b = 0; b < cache->v.B; ++b) cache->hlens[b] = 0;
   return rkv_launch_init(cache, false, (hipStream_t)stream);
 }
 
 RKV_EXPORT int rkv_cache_length(const rkv_cache* cache) { return cache ? cache->v.len : RKV_EINVAL; }
+
+RKV_EXPORT int rkv_cache_lengths(const rkv_cache* cache, int32_t* host_lengths) {
+  if (!cache || !host_lengths) return RKV_EINVAL;
+  for (int b = 0; b < cache->v.B; ++b) host_lengths[b] = cache->hlens[b];
+  return RKV_OK;
+}
 
 RKV_EXPORT int rkv_set_decode_path(rkv_cache* cache, int32_t path) {
   if (!cache || path < 0 || path > 2) return RKV_EINVAL;
@@ -222,9 +247,58 @@ RKV_EXPORT int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const vo
   if (!cache || n_new < 0) return RKV_EINVAL;
   if (n_new == 0) return RKV_OK;                      // nothing to read: the pointers may be null
   if (!dev_k || !dev_v) return RKV_EINVAL;
-  if ((int64_t)cache->v.len + n_new > cache->cfg.max_tokens) return RKV_ECAPACITY;
+  if ((int64_t)cache->v.len + n_new > cache->cfg.max_tokens) return RKV_ECAPACITY;   // v.len: the longest sequence
+  if (cache->ragged && !rkv_append_mfma_supported(cache)) return RKV_EINVAL;
   int rc = rkv_launch_append(cache, (const __half*)dev_k, (const __half*)dev_v, n_new, dev_sink_mask, (hipStream_t)stream);
-  if (rc == RKV_OK) cache->v.len += n_new;
+  if (rc == RKV_OK && cache->ragged) rc = rkv_launch_lens(cache, -1, n_new, (hipStream_t)stream);
+  if (rc == RKV_OK) {
+    cache->v.len += n_new;
+    for (int b = 0; b < cache->v.B; ++b) cache->hlens[b] += n_new;
+  }
+  return rc;
+}
+
+RKV_EXPORT int rkv_quantize_append_ragged(rkv_cache* cache, const void* dev_k, const void* dev_v, int32_t n_new_max,
+                                          const int32_t* host_n_new, const uint8_t* dev_sink_mask, void* stream) {
+  if (!cache || !host_n_new || n_new_max < 0) return RKV_EINVAL;
+  const int B = cache->v.B;
+  int hi = 0, lo = n_new_max, new_max = 0, max_slabs = 0;
+  for (int b = 0; b < B; ++b) {
+    const int nb = host_n_new[b], lb = cache->hlens[b];
+    if (nb < 0 || nb > n_new_max) return RKV_EINVAL;
+    if ((int64_t)lb + nb > cache->cfg.max_tokens) return RKV_ECAPACITY;
+    hi = nb > hi ? nb : hi;
+    lo = nb < lo ? nb : lo;
+    new_max = lb + nb > new_max ? lb + nb : new_max;
+    if (nb > 0) {
+      const int slabs = ((lb + nb - 1) >> 5) - (lb >> 5) + 1;
+      max_slabs = slabs > max_slabs ? slabs : max_slabs;
+    }
+  }
+  if (hi == 0) return RKV_OK;
+  if (!dev_k || !dev_v) return RKV_EINVAL;
+  // every sequence appends the same number of rows, packed as the uniform call expects them
+  if (lo == hi && hi == n_new_max) return rkv_quantize_append(cache, dev_k, dev_v, n_new_max, dev_sink_mask, stream);
+  if (!rkv_append_mfma_supported(cache)) return RKV_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  int rc = RKV_OK;
+  if (!cache->ragged) {
+    rc = rkv_launch_lens(cache, cache->v.len, 0, s);          // device lengths start from the common length
+    if (rc != RKV_OK) return rc;
+    cache->ragged = 1;
+    cache->v.lens = cache->dev_lens;
+  }
+  RKV_HIP_CHECK(hipMemcpyAsync(cache->dev_nnew, host_n_new, (size_t)B * 4, hipMemcpyHostToDevice, s));
+  cache->v.nnew = cache->dev_nnew;
+  if (dev_sink_mask && cache->v.max_sinks > 0)
+    rc = rkv_launch_sinks(cache, (const __half*)dev_k, (const __half*)dev_v, dev_sink_mask, n_new_max, s);
+  if (rc == RKV_OK) rc = rkv_launch_append_mfma(cache, (const __half*)dev_k, (const __half*)dev_v, n_new_max, max_slabs, s);
+  if (rc == RKV_OK) rc = rkv_launch_lens(cache, -1, 0, s);      // lengths += the staged counts
+  cache->v.nnew = nullptr;
+  if (rc == RKV_OK) {
+    for (int b = 0; b < B; ++b) cache->hlens[b] += host_n_new[b];
+    cache->v.len = new_max;
+  }
   return rc;
 }
 
@@ -243,6 +317,9 @@ RKV_EXPORT int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const i
                                     float* dev_lse, void* dev_scratch, void* stream) {
   if (!cache || !dev_q || !dev_out || !dev_scratch) return RKV_EINVAL;
   if (cache->v.len < 1 && !cache->cur_k) return RKV_ESTATE;
+  if (cache->ragged && !cache->cur_k)
+    for (int b = 0; b < cache->v.B; ++b)
+      if (cache->hlens[b] < 1) return RKV_ESTATE;           // a sequence with nothing to attend
   bool fast = rkv_mfma_supported(cache);
   if (cache->decode_path == 2 && !fast) return RKV_EINVAL;
   if (cache->decode_path == 1) fast = false;
@@ -256,6 +333,9 @@ RKV_EXPORT int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, c
   if (!cache || !dev_q || !dev_q_pos || !dev_out || !dev_scratch) return RKV_EINVAL;
   if (n_queries < 1 || n_queries > RKV_MAX_QUERIES) return RKV_EINVAL;
   if (cache->v.len < 1) return RKV_ESTATE;
+  if (cache->ragged)
+    for (int b = 0; b < cache->v.B; ++b)
+      if (cache->hlens[b] < 1) return RKV_ESTATE;
   if (!rkv_mfma_supported(cache) || cache->decode_path == 1) return RKV_EINVAL;   // matrix-core path only
   return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, n_queries, dev_out, dev_lse, dev_scratch,
                                 (hipStream_t)stream);
@@ -281,9 +361,13 @@ RKV_EXPORT int rkv_import_codes(rkv_cache* cache, int32_t n_tokens, const uint8_
   if (!cache || !dev_k_codes || !dev_k_scale || !dev_k_zero || !dev_v_codes || !dev_v_scale || !dev_v_zero) return RKV_EINVAL;
   if (n_tokens < 1) return RKV_EINVAL;
   if (n_tokens > cache->cfg.max_tokens) return RKV_ECAPACITY;
+  if (cache->ragged) return RKV_ESTATE;                       // the import gives every sequence the same length: reset first
   int rc = rkv_launch_import(cache, n_tokens, dev_k_codes, dev_k_scale, dev_k_zero, dev_v_codes, dev_v_scale, dev_v_zero,
                              (hipStream_t)stream);
-  if (rc == RKV_OK) cache->v.len = n_tokens;
+  if (rc == RKV_OK) {
+    cache->v.len = n_tokens;
+    for (int b = 0; b < cache->v.B; ++b) cache->hlens[b] = n_tokens;
+  }
   return rc;
 }
 

@@ -114,9 +114,14 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: everything that depends only on it stays scalar
   const int role = blockIdx.x % 3;             // 0, 1: the keys of K tile 0 / 1 of a slab; 2: the slab's values
-  const int slab = slab0 + blockIdx.x / 3, rg = blockIdx.y, b = blockIdx.z;
-  const int t_lo = v.len, t_hi = v.len + n_new;
+  // n_new: rows per sequence in kin and vin; sequence b holds len_b tokens and appends the first
+  // n_b rows (all of them, at the common length, unless the view carries per-sequence arrays)
+  const int rg = blockIdx.y, b = blockIdx.z;
+  const int len_b = rkv_len(v, b), n_b = v.nnew ? v.nnew[b] : n_new;
+  const int slab = (v.lens ? (len_b >> 5) : slab0) + blockIdx.x / 3;
+  const int t_lo = len_b, t_hi = len_b + n_b;
   const int ts = slab * 32;
+  if (ts >= t_hi || n_b <= 0) return;                 // the grid covers the longest append: nothing here for this sequence
   const int tau_first = max(0, t_lo - ts), tau_last = min(31, t_hi - 1 - ts);
   const size_t mrow = ((size_t)(b * v.NRG + rg) * v.Tpad + ts) * G;     // metadata row of the slab's first token
 
@@ -380,11 +385,21 @@ bool rkv_append_mfma_supported(const rkv_cache* c) {
   return c->blocks_aligned && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 
-int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int n_new, hipStream_t s) {
+// max_slabs: most 32-token slabs any sequence's new tokens touch, or 0 to work it out for n_new
+// tokens per sequence
+int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int n_new, int max_slabs, hipStream_t s) {
   const RkvView& v = c->v;
   if (!rkv_append_mfma_supported(c)) return RKV_EINVAL;
   const int slab0 = v.len >> 5, slab1 = (v.len + n_new - 1) >> 5;
-  dim3 grid(3 * (slab1 - slab0 + 1), v.NRG, v.B);
+  if (max_slabs <= 0) {
+    max_slabs = slab1 - slab0 + 1;
+    if (c->ragged)
+      for (int b = 0; b < v.B; ++b) {
+        const int sl = ((c->hlens[b] + n_new - 1) >> 5) - (c->hlens[b] >> 5) + 1;
+        max_slabs = sl > max_slabs ? sl : max_slabs;
+      }
+  }
+  dim3 grid(3 * max_slabs, v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (v.g == 4) hipLaunchKernelGGL(k_append_mfma<4>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   else hipLaunchKernelGGL(k_append_mfma<2>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);

@@ -35,11 +35,12 @@ __device__ inline void fwht_lanes_d(T (&x)[PL], int lane, int xstages) {
 
 // q~[b][h][c] = RoPE(q, q_pos)[c] / sqrt(128), angles in double (q_pos may lie beyond the table).
 __global__ void __launch_bounds__(128) k_prep_q(RkvView v, const __half* __restrict__ q, const int* __restrict__ q_pos,
-                                                int default_pos, float* __restrict__ qr, int share, int nq) {
+                                                int cur, float* __restrict__ qr, int share, int nq) {
   // v.Hq counts virtual heads when nq > 1 (several query tokens, each at its own position)
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
   const RkvVHead vh = rkv_virtual_head(v, h, nq);
-  const int pos = q_pos ? q_pos[b * nq + vh.qi] : default_pos;
+  // default position: the last cached token's, or one past it when the token being decoded is not in the cache yet (cur = 1)
+  const int pos = q_pos ? q_pos[b * nq + vh.qi] : rkv_len(v, b) - 1 + cur;
   const size_t base = ((size_t)b * v.Hq + h) * RKV_D;                       // where the rotated query goes
   const size_t src = (((size_t)b * nq + vh.qi) * (v.Hq / nq) + vh.h) * RKV_D; // where the raw query is
   int j, partner;
@@ -114,7 +115,8 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
 
   const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int t0 = chunk * GEN_CHUNK, t1 = min(t0 + GEN_CHUNK, v.len);
+  const int t0 = chunk * GEN_CHUNK, t1 = min(t0 + GEN_CHUNK, rkv_len(v, b));
+  if (t0 >= t1) return;                              // the grid covers the longest sequence
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
   if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
   for (int i = tid; i < nq * RKV_D; i += 256) s_q[i] = qr[((size_t)b * v.Hq + (size_t)rg * nq) * RKV_D + i];
@@ -226,9 +228,9 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
 // addresses do not depend on loaded data are issued up front (two dependent round trips in all).
 #define MERGE_MAX_CH 512
 __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restrict__ qr, const float* __restrict__ part,
-                                               int nch, const __half* __restrict__ k_cur, const __half* __restrict__ v_cur,
-                                               const int* __restrict__ q_lim, int nq, float* __restrict__ out,
-                                               float* __restrict__ lse) {
+                                               int nch_all, int chunk_tokens, const __half* __restrict__ k_cur,
+                                               const __half* __restrict__ v_cur, const int* __restrict__ q_lim, int nq,
+                                               float* __restrict__ out, float* __restrict__ lse) {
   __shared__ float s_w[MERGE_MAX_CH];     // chunk maxima, then chunk weights
   __shared__ float s_l[MERGE_MAX_CH];
   __shared__ float s_part[2][64];         // per-wave partial sink scores
@@ -238,11 +240,14 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x, lane = c & 63, wave = c >> 6;
   const int kvh = h / (v.Hq / v.Hkv);
   const size_t qbase = ((size_t)b * v.Hq + h) * RKV_D;
-  const float* P = part + ((size_t)b * v.Hq + h) * nch * RKV_PART_STRIDE;
+  // partials are laid out for nch_all chunks (the longest sequence); this sequence wrote its first nch
+  const int len_b = rkv_len(v, b);
+  const int nch = min(nch_all, (len_b + chunk_tokens - 1) / chunk_tokens);
+  const float* P = part + ((size_t)b * v.Hq + h) * nch_all * RKV_PART_STRIDE;
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
   // with several query tokens (q_lim set) a query only sees tokens up to its own position
   const RkvVHead vh = rkv_virtual_head(v, h, nq);
-  const int lim = q_lim ? min(q_lim[b * nq + vh.qi], v.len - 1) : v.len - 1;
+  const int lim = q_lim ? min(q_lim[b * nq + vh.qi], len_b - 1) : len_b - 1;
 
   for (int k = c; k < nch; k += 128) {
     s_w[k] = P[(size_t)k * RKV_PART_STRIDE];
@@ -283,7 +288,7 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   if (k_cur) {
     const __half* kr = k_cur + ((size_t)b * v.Hkv + kvh) * RKV_D;
     double sn, cs;
-    sincos((double)v.len * pow((double)v.theta, -(double)j / 64.0), &sn, &cs);
+    sincos((double)len_b * pow((double)v.theta, -(double)j / 64.0), &sn, &cs);
     const float x = __half2float(kr[c]), p = __half2float(kr[partner]);
     float d = qc * (x * (float)cs + sgn * p * (float)sn);
     for (int o = 32; o > 0; o >>= 1) d += __shfl_xor(d, o);
@@ -348,13 +353,13 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   if (lse && c == 0) lse[orow] = M + logf(L);
 }
 
-void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, int share, int nq,
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int cur, float* qr, int share, int nq,
                        hipStream_t s) {
-  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, default_pos, qr, share, nq);
+  hipLaunchKernelGGL(k_prep_q, dim3(v.Hq, v.B), dim3(128), 0, s, v, q, q_pos, cur, qr, share, nq);
 }
-void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, const __half* k_cur, const __half* v_cur,
-                      const int* q_lim, int nq, float* out, float* lse, hipStream_t s) {
-  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, k_cur, v_cur, q_lim, nq, out, lse);
+void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, int chunk_tokens, const __half* k_cur,
+                      const __half* v_cur, const int* q_lim, int nq, float* out, float* lse, hipStream_t s) {
+  hipLaunchKernelGGL(k_merge, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, chunk_tokens, k_cur, v_cur, q_lim, nq, out, lse);
 }
 
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
@@ -370,7 +375,7 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   const size_t qbytes = rkv_query_scratch_bytes(v.B, v.Hq);
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
-  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, 1, 1, s);
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, 1, 1, s);
   const int rep = v.Hq / v.Hkv, nq = rep * v.g;
   const size_t lds = ((size_t)nq * RKV_D + (size_t)nq * GEN_CHUNK + 2 * (size_t)v.g * GEN_CHUNK + 2 * nq) * 4;
   dim3 grid(nch, v.NRG, v.B);
@@ -386,6 +391,6 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch > 0) hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, qr, part, nch);   // an empty cache has only the current token
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
-  rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, nullptr, 1, out, lse, s);
+  rkv_launch_merge(v, qr, part, nch, GEN_CHUNK, c->cur_k, c->cur_v, nullptr, 1, out, lse, s);
   return rkv_check_launch();
 }

@@ -169,7 +169,6 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
-  const int len = v.len;
   {
     uint4* a4 = reinterpret_cast<uint4*>(&s_A[0][0][0]);
     for (int i = tid; i < (int)(sizeof(s_A) / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
@@ -209,6 +208,8 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   const int rrg = blockIdx.x / nch8, chunk = blockIdx.x - rrg * nch8;
   const int rg = blockIdx.y, b = blockIdx.z;
   if (chunk >= nch) return;
+  const int len = rkv_len(v, b);
+  if (chunk * MF_CH >= len) return;              // the grid covers the longest sequence
   const int rep = v.Hq / v.Hkv;
   const int t0 = chunk * MF_CH;
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
@@ -633,7 +634,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   // workgroup measured slower: 158 against 151 us on the GQA configuration - the variant needs
   // more registers than three workgroups per compute unit leave)
   const int share = rep % 2 == 0 ? 2 : 1;
-  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? v.len : v.len - 1, qr, share, nq, s);
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   dim3 grid(((nch + 7) & ~7) * (rep / share), v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
@@ -641,6 +642,6 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   else if (multi) launch_kernel<true>(v, share, grid, qt, part, nch, q_pos, nq, s);
   else launch_kernel<false>(v, share, grid, qt, part, nch, nullptr, 1, s);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
-  rkv_launch_merge(v, qr, part, nch, c->cur_k, c->cur_v, multi ? q_pos : nullptr, nq, out, lse, s);
+  rkv_launch_merge(v, qr, part, nch, MF_CH, c->cur_k, c->cur_v, multi ? q_pos : nullptr, nq, out, lse, s);
   return rkv_check_launch();
 }

@@ -47,13 +47,22 @@ struct RkvView {
   float2* rope;
   uint32_t* hop;     // Hadamard B-operand image for the FP4 matrix instruction: [8 tiles][64 lanes][4 dwords]
   int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate, keys_rotated;
+  const int* lens;   // per-sequence lengths [B] once the sequences differ in length, else null (all have `len` tokens)
+  const int* nnew;   // during an append with per-sequence token counts: those counts [B], else null
   int meta8;         // 1: km / vm hold, per (token, rotation group), g FP8 E4M3 scales followed by g 8-bit zero-points (value + 128)
   float theta;
 };
 
+// length of sequence b
+__device__ inline int rkv_len(const RkvView& v, int b) { return v.lens ? v.lens[b] : v.len; }
+
 struct rkv_cache {
   rkv_config cfg;
-  RkvView v;
+  RkvView v;           // v.len: the length of the longest sequence
+  int32_t* hlens;      // host mirror of the per-sequence lengths [batch]
+  int* dev_lens;       // device copy (kept current once `ragged` is set) and staging for per-sequence token counts
+  int* dev_nnew;
+  int ragged;          // 1 once sequences differ in length
   size_t bytes;
   char* base;
   size_t off_tables;      // everything before this offset is cleared by reset
@@ -204,7 +213,9 @@ int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s);
 int rkv_launch_set_perm_tables(rkv_cache* c, hipStream_t s);
 int rkv_launch_append(rkv_cache* c, const __half* k, const __half* v, int n_new, const uint8_t* mask, hipStream_t s);
 bool rkv_append_mfma_supported(const rkv_cache* c);
-int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* v, int n_new, hipStream_t s);
+int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* v, int n_new, int max_slabs, hipStream_t s);
+int rkv_launch_sinks(rkv_cache* c, const __half* k, const __half* v, const uint8_t* mask, int n_new, hipStream_t s);
+int rkv_launch_lens(rkv_cache* c, int set_to, int add, hipStream_t s);
 int rkv_launch_dequant(rkv_cache* c, float* k_hat, float* v_hat, hipStream_t s);
 int rkv_launch_export(rkv_cache* c, uint8_t* kc, float* ks, float* kz, uint8_t* vc, float* vs, float* vz, hipStream_t s);
 int rkv_launch_import(rkv_cache* c, int T, const uint8_t* kc, const float* ks, const float* kz, const uint8_t* vc,
@@ -214,10 +225,10 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int nq, float* out, float* lse, void* scratch,
                            hipStream_t s);
 bool rkv_mfma_supported(const rkv_cache* c);
-void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int default_pos, float* qr, int share, int nq,
+void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int cur, float* qr, int share, int nq,
                        hipStream_t s);
-void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, const __half* k_cur, const __half* v_cur,
-                      const int* q_lim, int nq, float* out, float* lse, hipStream_t s);
+void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, int chunk_tokens, const __half* k_cur,
+                      const __half* v_cur, const int* q_lim, int nq, float* out, float* lse, hipStream_t s);
 int rkv_launch_calibrate(const rkv_config* cfg, const __half* k_cal, int n_tok, int* perm_out, void* scratch, hipStream_t s);
 int rkv_launch_fold_rotation(const rkv_config* cfg, const float* w, int rows, const int* perm, float* out, hipStream_t s);
 int rkv_launch_select_sinks(const __half* x, int batch, int n_tok, int width, int k, int32_t* idx_out, uint8_t* mask_out,

@@ -109,11 +109,13 @@ __global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restri
   __shared__ int s_tok[64];
   __shared__ int s_new;
   __shared__ float s_row[512];
+  // n_new: rows per sequence in k, vv and mask; sequence b uses the first n_b of them
   const int b = blockIdx.x, tid = threadIdx.x;
+  const int n_b = v.nnew ? v.nnew[b] : n_new;
   const int cnt0 = v.sink_cnt[b];
   const int room = v.max_sinks - cnt0;
-  const int per = (n_new + 255) / 256;
-  const int lo = tid * per, hi = min(lo + per, n_new);
+  const int per = (n_b + 255) / 256;
+  const int lo = min(tid * per, n_b), hi = min(lo + per, n_b);
   int mine = 0;
   for (int t = lo; t < hi; ++t) mine += mask[(size_t)b * n_new + t] != 0;
   s_count[tid] = mine;
@@ -165,7 +167,7 @@ __global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restri
         __syncthreads();
       }
     }
-    if (tid == 0) v.sink_pos[b * v.max_sinks + cnt0 + i] = v.len + t;
+    if (tid == 0) v.sink_pos[b * v.max_sinks + cnt0 + i] = rkv_len(v, b) + t;
   }
   if (tid == 0) v.sink_cnt[b] = cnt0 + nn;
 }
@@ -468,10 +470,31 @@ __global__ void __launch_bounds__(256) k_append_fast(RkvView v, const __half* __
   }
 }
 
+int rkv_launch_sinks(rkv_cache* c, const __half* k, const __half* vv, const uint8_t* mask, int n_new, hipStream_t s) {
+  const RkvView& v = c->v;
+  hipLaunchKernelGGL(k_sinks, dim3(v.B), dim3(256), 0, s, v, k, vv, mask, n_new);
+  return rkv_check_launch();
+}
+
+// Per-sequence lengths on the device: set_to >= 0 sets every length to it; otherwise each length
+// grows by `add` plus, while an append with per-sequence counts is in progress, by its count.
+__global__ void k_lens(RkvView v, int* lens, int set_to, int add) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= v.B) return;
+  if (set_to >= 0) lens[b] = set_to;
+  else lens[b] += add + (v.nnew ? v.nnew[b] : 0);
+}
+
+int rkv_launch_lens(rkv_cache* c, int set_to, int add, hipStream_t s) {
+  const RkvView& v = c->v;
+  hipLaunchKernelGGL(k_lens, dim3((v.B + 255) / 256), dim3(256), 0, s, v, c->dev_lens, set_to, add);
+  return rkv_check_launch();
+}
+
 int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new, const uint8_t* mask, hipStream_t s) {
   const RkvView& v = c->v;
   if (mask && v.max_sinks > 0) hipLaunchKernelGGL(k_sinks, dim3(v.B), dim3(256), 0, s, v, k, vv, mask, n_new);
-  if (rkv_append_mfma_supported(c)) return rkv_launch_append_mfma(c, k, vv, n_new, s);
+  if (rkv_append_mfma_supported(c)) return rkv_launch_append_mfma(c, k, vv, n_new, 0, s);
   if (c->blocks_aligned && (v.g == 2 || v.g == 4)) {
     const int slab0 = v.len >> 5, slab1 = (v.len + n_new - 1) >> 5;
     dim3 grid(slab1 - slab0 + 1, v.NRG, v.B);

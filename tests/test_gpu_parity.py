@@ -719,3 +719,90 @@ def test_shared_scratch_reused_across_caches():
         for i in range(2):
             out = caches[i].decode_attention(qs[i])
             assert torch.equal(out, refs[i]), f"repetition {rep}, cache {i}"
+
+
+def test_sequences_of_different_lengths():
+    """rkv_quantize_append_ragged: three sequences are prefilled with 300 / 37 / 513 tokens in one
+    call, extended by 5 / 0 / 40 in a second, then take three ordinary single-token steps.  Each
+    sequence is compared with an oracle cache of its own (batch 1): codes under the tie protocol,
+    sink rows, and - on the GPU's own codes - decode attention on both kernels with the default
+    query position (each sequence's own last token), the current-token variant and two causal
+    query tokens per step."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8)
+    B = 3
+    cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=600, max_sinks=4, rot_heads=4)
+    steps = [[300, 37, 513], [5, 0, 40], [1, 1, 1], [1, 1, 1], [1, 1, 1]]
+    total = [sum(st[b] for st in steps) for b in range(B)]
+    data = [S.make_kv(w, total[b] + 1, batch=1, layer=b) for b in range(B)]       # one spare token for the current-token call
+    cache = R.RkvCache(cfg)
+    ocs = [O.cache_new(P.oracle_cfg(dataclasses.replace(cfg, batch=1))) for _ in range(B)]
+    done = [0] * B
+    for st in steps:
+        n_max = max(st)
+        k = np.zeros((B, n_max, 8, 128), np.float16)
+        v = np.zeros_like(k)
+        m = np.zeros((B, n_max), np.uint8)
+        for b in range(B):
+            kb, vb, mb = data[b]
+            sl = slice(done[b], done[b] + st[b])
+            k[b, :st[b]], v[b, :st[b]], m[b, :st[b]] = kb[0, sl], vb[0, sl], mb[0, sl]
+            if st[b]:
+                O.quantize_append(ocs[b], kb[:, sl], vb[:, sl], mb[:, sl])
+            done[b] += st[b]
+        print(f"[case] ragged append {st}", flush=True)
+        if len(set(st)) == 1:
+            cache.quantize_append(P.gpu(k), P.gpu(v), P.gpu(m))
+        else:
+            cache.quantize_append_ragged(P.gpu(k), P.gpu(v), st, P.gpu(m))
+    torch.cuda.synchronize()
+    assert cache.lengths == total and cache.length == max(total)
+    g = P.export_numpy(cache)
+    sinks = {kk: vv.cpu().numpy() for kk, vv in cache.export_sinks().items()}
+    ocg = []
+    for b in range(B):
+        gb = {name: arr[b:b + 1, :total[b]] for name, arr in g.items()}
+        P.compare_codes(ocs[b].k_rot, ocs[b].k_codes, ocs[b].k_scale, ocs[b].k_zero, gb["k_codes"], gb["k_scale"], gb["k_zero"],
+                        f"ragged b={b} K", rot_span=512)
+        P.compare_codes(ocs[b].v_in, ocs[b].v_codes, ocs[b].v_scale, ocs[b].v_zero, gb["v_codes"], gb["v_scale"], gb["v_zero"],
+                        f"ragged b={b} V")
+        assert sinks["count"][b] == len(ocs[b].sink_pos[0])
+        for i, pos in enumerate(ocs[b].sink_pos[0]):
+            assert sinks["pos"][b, i] == pos
+            assert np.array_equal(sinks["k"][b, i], ocs[b].sink_k[0][i].reshape(-1))
+        ocg.append(oracle_from_export(ocs[b], gb))
+    q = S.make_q(w, batch=B)
+    for path in (2, 1):
+        cache.set_decode_path(path)
+        out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
+        torch.cuda.synchronize()
+        for b in range(B):
+            ref, lse_ref = O.decode_attention(ocg[b], q[b:b + 1])
+            e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
+            le = float(np.abs(lse[b:b + 1].cpu().numpy() - lse_ref).max())
+            print(f"[parity] ragged decode path={path} b={b} len={total[b]}: out err {e:.3e} lse err {le:.3e}", flush=True)
+            assert e <= ATT_TOL and le <= LSE_TOL
+        kc = np.concatenate([data[b][0][:, total[b]] for b in range(B)])
+        vc = np.concatenate([data[b][1][:, total[b]] for b in range(B)])
+        out = cache.decode_attention(P.gpu(q), k_cur=P.gpu(kc), v_cur=P.gpu(vc))
+        torch.cuda.synchronize()
+        for b in range(B):
+            ref, _ = O.decode_attention(ocg[b], q[b:b + 1], None, kc[b:b + 1], vc[b:b + 1])
+            e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
+            assert e <= ATT_TOL, f"current token, path {path}, b={b}: {e}"
+    cache.set_decode_path(0)
+    q2 = np.stack([S.make_q(w, batch=B, step=i) for i in range(2)], axis=1)
+    q_pos = np.array([[total[b] - 2, total[b] - 1] for b in range(B)], dtype=np.int32)
+    out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
+        e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
+        assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
+    # what the entry point refuses
+    with pytest.raises(R.RkvError) as ei:
+        cache.quantize_append_ragged(P.gpu(np.zeros((B, 50, 8, 128), np.float16)), P.gpu(np.zeros((B, 50, 8, 128), np.float16)), [1, 1, 50])
+    assert ei.value.code == -2 and cache.lengths == total          # sequence 2 would pass max_tokens; nothing appended
+    with pytest.raises(R.RkvError):
+        cache.quantize_append_ragged(P.gpu(np.zeros((B, 2, 8, 128), np.float16)), P.gpu(np.zeros((B, 2, 8, 128), np.float16)), [1, 3, 0])
+    cache.reset()
+    assert cache.lengths == [0, 0, 0]
