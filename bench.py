@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--queries", type=int, default=1,
                     help="query tokens per sequence and step (above 1: that many tokens are appended, then read the cache in one multi-query call)")
     ap.add_argument("--meta-format", type=int, default=0, help="0: fp16 scale and zero-point (2.25 bits); 1: FP8 scale, INT8 zero-point (2.125 bits)")
+    ap.add_argument("--ragged-min", type=float, default=1.0,
+                    help="below 1: sequence lengths spread evenly from this fraction of the context up to the full context")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -133,20 +135,28 @@ def main():
     caches, bulk_ms = [], []
     n_pre = T - (K + W) * NQ   # the last timed step decodes over exactly T tokens
     e0, e1 = hip.event(), hip.event()
+    pre_lens = None
+    if args.ragged_min < 1.0:      # sequence b ends the run with final_lens[b] tokens
+        final_lens = [int(round(T * (args.ragged_min + (1.0 - args.ragged_min) * b / max(B - 1, 1)))) for b in range(B)]
+        pre_lens = [max(fl - (K + W) * NQ, 1) for fl in final_lens]
     for l in range(L):
         c = R.RkvCache(cfg, device=dev, scratch=scratch)
         kcal, _, _ = S.make_kv_torch(w, 256, dev, batch=1, layer=l, stream=1)
         c.set_perm(R.calibrate_perm(cfg, kcal[0].contiguous()))
         k, v, mask = S.make_kv_torch(w, n_pre, dev, layer=l)
         c.set_profile_events(e0, e1)
-        c.quantize_append(k, v, mask)
+        if pre_lens is None:
+            c.quantize_append(k, v, mask)
+        else:
+            c.quantize_append_ragged(k, v, pre_lens, mask)
         torch.cuda.synchronize()
         bulk_ms.append(hip.elapsed_ms(e0, e1))
         c.set_profile_events(None, None)
         c.set_decode_path(args.path)
         caches.append(c)
         del k, v, mask
-    bulk_bytes = B * n_pre * (2 * E * 2 + 2 * E // 4 + 2 * (E // 128) * MB)
+    n_bulk = B * n_pre if pre_lens is None else sum(pre_lens)
+    bulk_bytes = n_bulk * (2 * E * 2 + 2 * E // 4 + 2 * (E // 128) * MB)
     bulk_best = min(bulk_ms)
     bulk_avg = sum(bulk_ms) / len(bulk_ms)
 
@@ -196,6 +206,7 @@ def main():
         one_step(s)
     torch.cuda.synchronize()
     assert caches[0].length == T - K * NQ
+    lens_now = caches[0].lengths
 
     # timed region: exactly K steps, whole-job wall clock; the decode kernel of every launch is
     # bracketed by its own pair of HIP events (recorded by the library on the launch stream)
@@ -205,7 +216,8 @@ def main():
     t0 = time.perf_counter()
     for s in range(K):
         decode_only_events(W + s, ev[s])
-        kv_tokens += B * caches[0].length * L
+        lens_now = [x + NQ for x in lens_now]
+        kv_tokens += sum(lens_now) * L
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kern_ms = [hip.elapsed_ms(a, b) for step in ev for (a, b) in step]
@@ -214,7 +226,7 @@ def main():
     med_ms = sorted(kern_ms)[len(kern_ms) // 2]
     ctx = T - (K - 1) * NQ / 2.0
     bytes_per_tok = 2 * E // 4 + 2 * (E // 128) * MB
-    launch_bytes = B * ctx * bytes_per_tok
+    launch_bytes = (sum(lens_now) - B * (K - 1) * NQ / 2.0) * bytes_per_tok      # mean over the timed steps
     achieved = launch_bytes / (avg_ms * 1e-3) / 1e9
 
     # measured HBM traffic of the decode kernel (rocprofv3 counters, calibrated; see profiles/)
@@ -241,6 +253,7 @@ def main():
         "config": {"workload": f"{w.name}: {SHAPES.get(w.name, 'custom')} decode, {L} layers x {w.n_q_heads} query / {w.n_kv_heads} KV heads x 128, "
                                f"batch {B}, context {T}, rotation over {w.rot_heads} heads, 2-bit group-128, {w.n_sinks} fp16 sinks",
                    "decode_path": args.path, "queries_per_step": NQ,
+                   "sequence_lengths": "all equal" if pre_lens is None else f"spread evenly from {lens_now[0]} to {lens_now[-1]} tokens",
                    "storage": "u2 codes + fp16 scale / fp16 zero per 128 (2.25 bits per element)" if MB == 4 else "u2 codes + FP8 E4M3 scale / INT8 zero per 128 (2.125 bits per element)",
                    "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -248,7 +261,7 @@ def main():
                      "algorithmic_bytes_per_launch": launch_bytes, "bytes_per_kv_token": bytes_per_tok},
         "append_bulk": {"GB/s_best": bulk_bytes / (bulk_best * 1e-3) / 1e9, "GB/s_avg": bulk_bytes / (bulk_avg * 1e-3) / 1e9,
                         "frac_of_hbm_peak_best": bulk_bytes / (bulk_best * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                        "kv_tokens_per_s_best": B * n_pre / (bulk_best * 1e-3), "tokens_per_call": B * n_pre,
+                        "kv_tokens_per_s_best": n_bulk / (bulk_best * 1e-3), "tokens_per_call": n_bulk,
                         "bytes_per_kv_token": 2 * E * 2 + bytes_per_tok},
     }
     if not args.no_cpu_baseline:

@@ -36,7 +36,7 @@ static int check_config(const rkv_config* c, bool need_capacity) {
 }
 
 struct Offsets {
-  size_t kc, km, vc, vm, sk, sv, spos, scnt, lens, nnew, tables, perm, pinv, gid, rope, hop, total;
+  size_t kc, km, vc, vm, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, total;
   int Tpad;
 };
 
@@ -57,6 +57,7 @@ static Offsets plan(const rkv_config* c) {
   o.scnt = p; p = align256(p + B * 4);
   o.lens = p; p = align256(p + B * 4);
   o.nnew = p; p = align256(p + B * 4);
+  o.cstart = p; p = align256(p + (B + 1) * 4);
   o.tables = p;
   o.perm = p; p = align256(p + E * 4);
   o.pinv = p; p = align256(p + E * 4);
@@ -104,6 +105,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   }
   c->dev_lens = (int*)(c->base + o.lens);
   c->dev_nnew = (int*)(c->base + o.nnew);
+  c->dev_cstart = (int*)(c->base + o.cstart);
   {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
@@ -144,6 +146,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.keys_rotated = cfg->keys_rotated;
   v.meta8 = cfg->meta_format == 1;
   v.lens = nullptr;
+  v.cstart = nullptr;
   v.nnew = nullptr;
   v.theta = cfg->rope_theta;
   rc = rkv_launch_init(c, true, (hipStream_t)stream);
@@ -164,6 +167,7 @@ RKV_EXPORT int rkv_cache_reset(rkv_cache* cache, void* stream) {
   if (!cache) return RKV_EINVAL;
   cache->v.len = 0;
   cache->v.lens = nullptr;
+  cache->v.cstart = nullptr;
   cache->ragged = 0;
   for (int b = 0; b < cache->v.B; ++b) cache->hlens[b] = 0;
   return rkv_launch_init(cache, false, (hipStream_t)stream);
@@ -287,6 +291,7 @@ RKV_EXPORT int rkv_quantize_append_ragged(rkv_cache* cache, const void* dev_k, c
     if (rc != RKV_OK) return rc;
     cache->ragged = 1;
     cache->v.lens = cache->dev_lens;
+    cache->v.cstart = cache->dev_cstart;
   }
   RKV_HIP_CHECK(hipMemcpyAsync(cache->dev_nnew, host_n_new, (size_t)B * 4, hipMemcpyHostToDevice, s));
   cache->v.nnew = cache->dev_nnew;

@@ -39,6 +39,7 @@ typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 #define MF_TILES 4         // 16-token tiles per wave
 #endif
 #define MF_CH (64 * MF_TILES)   // tokens per workgroup (4 waves)
+static_assert(MF_CH == 256, "the per-sequence chunk table (k_lens) counts chunks of 256 tokens");
 #ifndef MF_ACC
 #define MF_ACC 16         // score accumulators per lane and pass of the key phase
 #endif
@@ -204,13 +205,34 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   // chunk count rounded up to 8: if rep > REP the workgroups of the other query-head groups re-read
   // the same chunk, and with ids a multiple of 8 apart they land on the same XCD, whose L2 then
   // holds the chunk for the later ones
-  const int nch8 = (nch + 7) & ~7;
-  const int rrg = blockIdx.x / nch8, chunk = blockIdx.x - rrg * nch8;
-  const int rg = blockIdx.y, b = blockIdx.z;
-  if (chunk >= nch) return;
-  const int len = rkv_len(v, b);
-  if (chunk * MF_CH >= len) return;              // the grid covers the longest sequence
+  // With per-sequence lengths the grid has no sequence dimension: the chunks of all sequences are
+  // numbered consecutively (cstart[b] = chunks of the sequences before b), rounded up to 8 in all,
+  // so that no workgroup is launched for chunks a shorter sequence does not have.
   const int rep = v.Hq / v.Hkv;
+  const int rg = blockIdx.y;
+  int rrg, chunk, b;
+  if (v.lens) {
+    const int tot8 = gridDim.x / (rep / REP);
+    rrg = blockIdx.x / tot8;
+    const int w = blockIdx.x - rrg * tot8;
+    if (w >= v.cstart[v.B]) return;
+    int lo = 0, hi = v.B;                        // the last sequence whose first chunk is <= w and that has chunks
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (v.cstart[mid] <= w) lo = mid;
+      else hi = mid;
+    }
+    b = lo;
+    chunk = w - v.cstart[b];
+  } else {
+    const int nch8 = (nch + 7) & ~7;
+    rrg = blockIdx.x / nch8;
+    chunk = blockIdx.x - rrg * nch8;
+    b = blockIdx.z;
+    if (chunk >= nch) return;
+  }
+  const int len = rkv_len(v, b);
+  if (chunk * MF_CH >= len) return;
   const int t0 = chunk * MF_CH;
   const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
   // the sink list (complete after the barrier that precedes the key phase); every wave clears
@@ -637,6 +659,11 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   dim3 grid(((nch + 7) & ~7) * (rep / share), v.NRG, v.B);
+  if (c->ragged) {                                          // all sequences' chunks in one dimension
+    int total = 0;
+    for (int b = 0; b < v.B; ++b) total += (c->hlens[b] + MF_CH - 1) / MF_CH;
+    grid = dim3(((total + 7) & ~7) * (rep / share), v.NRG, 1);
+  }
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch == 0) {}                                          // an empty cache has only the current token
   else if (multi) launch_kernel<true>(v, share, grid, qt, part, nch, q_pos, nq, s);

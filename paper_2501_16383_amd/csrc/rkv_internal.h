@@ -48,6 +48,7 @@ struct RkvView {
   uint32_t* hop;     // Hadamard B-operand image for the FP4 matrix instruction: [8 tiles][64 lanes][4 dwords]
   int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate, keys_rotated;
   const int* lens;   // per-sequence lengths [B] once the sequences differ in length, else null (all have `len` tokens)
+  const int* cstart; // with `lens`: cstart[b] = 256-token chunks of the sequences before b, cstart[B] = all of them
   const int* nnew;   // during an append with per-sequence token counts: those counts [B], else null
   int meta8;         // 1: km / vm hold, per (token, rotation group), g FP8 E4M3 scales followed by g 8-bit zero-points (value + 128)
   float theta;
@@ -62,6 +63,7 @@ struct rkv_cache {
   int32_t* hlens;      // host mirror of the per-sequence lengths [batch]
   int* dev_lens;       // device copy (kept current once `ragged` is set) and staging for per-sequence token counts
   int* dev_nnew;
+  int* dev_cstart;     // [batch + 1], see RkvView::cstart
   int ragged;          // 1 once sequences differ in length
   size_t bytes;
   char* base;

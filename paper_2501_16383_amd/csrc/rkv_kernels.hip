@@ -478,16 +478,40 @@ int rkv_launch_sinks(rkv_cache* c, const __half* k, const __half* vv, const uint
 
 // Per-sequence lengths on the device: set_to >= 0 sets every length to it; otherwise each length
 // grows by `add` plus, while an append with per-sequence counts is in progress, by its count.
-__global__ void k_lens(RkvView v, int* lens, int set_to, int add) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= v.B) return;
-  if (set_to >= 0) lens[b] = set_to;
-  else lens[b] += add + (v.nnew ? v.nnew[b] : 0);
+// Also rebuilds cstart (running count of 256-token chunks, see RkvView) - one workgroup; thread i
+// owns a contiguous slice of the sequences.
+__global__ void __launch_bounds__(256) k_lens(RkvView v, int* lens, int* cstart, int set_to, int add) {
+  __shared__ int s_sum[256];
+  const int tid = threadIdx.x;
+  const int per = (v.B + 255) / 256, b0 = min(tid * per, v.B), b1 = min(b0 + per, v.B);
+  int chunks = 0;
+  for (int b = b0; b < b1; ++b) {
+    const int len = set_to >= 0 ? set_to : lens[b] + add + (v.nnew ? v.nnew[b] : 0);
+    lens[b] = len;
+    chunks += (len + 255) >> 8;
+  }
+  s_sum[tid] = chunks;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int i = 0; i < 256; ++i) {
+      const int c = s_sum[i];
+      s_sum[i] = run;
+      run += c;
+    }
+    cstart[v.B] = run;
+  }
+  __syncthreads();
+  int run = s_sum[tid];
+  for (int b = b0; b < b1; ++b) {
+    cstart[b] = run;
+    run += (lens[b] + 255) >> 8;
+  }
 }
 
 int rkv_launch_lens(rkv_cache* c, int set_to, int add, hipStream_t s) {
   const RkvView& v = c->v;
-  hipLaunchKernelGGL(k_lens, dim3((v.B + 255) / 256), dim3(256), 0, s, v, c->dev_lens, set_to, add);
+  hipLaunchKernelGGL(k_lens, dim3(1), dim3(256), 0, s, v, c->dev_lens, c->dev_cstart, set_to, add);
   return rkv_check_launch();
 }
 
