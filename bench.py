@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--meta-format", type=int, default=0, help="0: fp16 scale and zero-point (2.25 bits); 1: FP8 scale, INT8 zero-point (2.125 bits)")
     ap.add_argument("--ragged-min", type=float, default=1.0,
                     help="below 1: sequence lengths spread evenly from this fraction of the context up to the full context")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="make a step of rkv_quantize_append + rkv_decode_attention instead of the one-call rkv_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -180,14 +182,24 @@ def main():
         else:
             outs[l] = c.decode_attention_multi(step_q[l][s], step_pos[s])
 
+    one_call = NQ == 1 and not args.separate_calls     # rkv_decode_step: append + attend in one library call
+
     def one_step(s):
         for l in range(L):
-            caches[l].quantize_append(step_k[l][s], step_v[l][s])
-            decode(caches[l], l, s)
+            if one_call:
+                caches[l].decode_step(step_k[l][s], step_v[l][s], step_q[l][s], out=outs[l])
+            else:
+                caches[l].quantize_append(step_k[l][s], step_v[l][s])
+                decode(caches[l], l, s)
 
     def decode_only_events(s, events):
         for l in range(L):
             c = caches[l]
+            if one_call:                                   # the events bracket the cache-streaming kernel only
+                c.set_profile_events(*events[l])
+                c.decode_step(step_k[l][s], step_v[l][s], step_q[l][s], out=outs[l])
+                c.set_profile_events(None, None)
+                continue
             c.set_profile_events(None, None)
             c.quantize_append(step_k[l][s], step_v[l][s])
             c.set_profile_events(*events[l])
@@ -252,7 +264,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {SHAPES.get(w.name, 'custom')} decode, {L} layers x {w.n_q_heads} query / {w.n_kv_heads} KV heads x 128, "
                                f"batch {B}, context {T}, rotation over {w.rot_heads} heads, 2-bit group-128, {w.n_sinks} fp16 sinks",
-                   "decode_path": args.path, "queries_per_step": NQ,
+                   "decode_path": args.path, "queries_per_step": NQ, "calls_per_step_and_layer": 1 if one_call else 2,
                    "sequence_lengths": "all equal" if pre_lens is None else f"spread evenly from {lens_now[0]} to {lens_now[-1]} tokens",
                    "storage": "u2 codes + fp16 scale / fp16 zero per 128 (2.25 bits per element)" if MB == 4 else "u2 codes + FP8 E4M3 scale / INT8 zero per 128 (2.125 bits per element)",
                    "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"},

@@ -181,6 +181,15 @@ int rkv_decode_attention_with_current(rkv_cache* cache, const void* dev_q, const
                                       const void* dev_k_cur, const void* dev_v_cur, float* dev_out,
                                       float* dev_lse, void* dev_scratch, void* stream);
 
+/* One decode step in one call: rkv_quantize_append of one token per sequence (dev_k, dev_v
+ * [batch][1][n_kv_heads][head_dim] fp16, no sink mask) followed by rkv_decode_attention with the
+ * same remaining arguments - and the same results, bit for bit.  Where the matrix-core kernels
+ * cover the configuration the token's compression and the query's preparation share one kernel
+ * launch, which shortens the step by a few microseconds per layer; elsewhere the two calls are
+ * made one after the other.  Error codes as for the two calls. */
+int rkv_decode_step(rkv_cache* cache, const void* dev_k, const void* dev_v, const void* dev_q, const int32_t* dev_q_pos,
+                    float* dev_out, float* dev_lse, void* dev_scratch, void* stream);
+
 /* Several query tokens per sequence in one call (Eq. 5 with the causal mask): the tokens of a
  * multi-token step - verification of drafted tokens, a prefill continued in pieces - are appended
  * first and then read the cache together, so that the cache streams from memory once for all of

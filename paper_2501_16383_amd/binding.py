@@ -20,7 +20,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
     "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention", "rkv_decode_attention_with_current",
-    "rkv_decode_attention_multi", "rkv_quantize_append_ragged", "rkv_cache_lengths",
+    "rkv_decode_attention_multi", "rkv_decode_step", "rkv_quantize_append_ragged", "rkv_cache_lengths",
     "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
@@ -97,6 +97,7 @@ def load_library():
     lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.rkv_decode_attention_with_current.argtypes = [vp] * 9
     lib.rkv_decode_attention_multi.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp, vp]
+    lib.rkv_decode_step.argtypes = [vp] * 9
     lib.rkv_quantize_append_ragged.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp]
     lib.rkv_cache_lengths.argtypes = [vp, vp]
     lib.rkv_set_decode_path.argtypes = [vp, i32]
@@ -306,6 +307,26 @@ class RkvCache:
             return (out, lse) if want_lse else out
         _check(self.lib.rkv_decode_attention(self.handle, _ptr(q), _ptr(q_pos), _ptr(out), _ptr(lse),
                                              _ptr(self.scratch), _stream()), "rkv_decode_attention")
+        return (out, lse) if want_lse else out
+
+    def decode_step(self, k, v, q, q_pos=None, out=None, lse=None, want_lse=False):
+        """rkv_decode_step: append one token per sequence (k, v [batch, 1, n_kv_heads, 128]) and attend."""
+        import torch
+        k = _dev(k, torch.float16, "k")
+        v = _dev(v, torch.float16, "v")
+        q = _dev(q, torch.float16, "q")
+        q_pos = _dev(q_pos, torch.int32, "q_pos")
+        cfg = self.cfg
+        if k.shape != (cfg.batch, 1, cfg.n_kv_heads, cfg.head_dim) or v.shape != k.shape:
+            raise ValueError("k, v must be [batch, 1, n_kv_heads, head_dim]")
+        if q.shape != (cfg.batch, cfg.n_q_heads, cfg.head_dim):
+            raise ValueError("q must be [batch, n_q_heads, head_dim]")
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        if lse is None and want_lse:
+            lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+        _check(self.lib.rkv_decode_step(self.handle, _ptr(k), _ptr(v), _ptr(q), _ptr(q_pos), _ptr(out), _ptr(lse),
+                                        _ptr(self.scratch), _stream()), "rkv_decode_step")
         return (out, lse) if want_lse else out
 
     def decode_attention_multi(self, q, q_pos, want_lse=False):

@@ -329,8 +329,29 @@ RKV_EXPORT int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const i
   if (cache->decode_path == 2 && !fast) return RKV_EINVAL;
   if (cache->decode_path == 1) fast = false;
   if (fast)
-    return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, 0, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
+    return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, 0, dev_out, dev_lse, dev_scratch, false,
+                                  (hipStream_t)stream);
   return rkv_launch_decode_general(cache, (const __half*)dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
+}
+
+RKV_EXPORT int rkv_decode_step(rkv_cache* cache, const void* dev_k, const void* dev_v, const void* dev_q, const int32_t* dev_q_pos,
+                               float* dev_out, float* dev_lse, void* dev_scratch, void* stream) {
+  if (!cache || !dev_k || !dev_v || !dev_q || !dev_out || !dev_scratch) return RKV_EINVAL;
+  if ((int64_t)cache->v.len + 1 > cache->cfg.max_tokens) return RKV_ECAPACITY;
+  const bool fused = rkv_append_mfma_supported(cache) && rkv_mfma_supported(cache) && cache->decode_path != 1;
+  if (!fused) {   // the same two calls, one after the other
+    const int rc = rkv_quantize_append(cache, dev_k, dev_v, 1, nullptr, stream);
+    return rc != RKV_OK ? rc : rkv_decode_attention(cache, dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, stream);
+  }
+  hipStream_t s = (hipStream_t)stream;
+  const int share = rkv_mfma_share(cache->v.Hq / cache->v.Hkv);
+  int rc = rkv_launch_step_mfma(cache, (const __half*)dev_k, (const __half*)dev_v, (const __half*)dev_q, dev_q_pos,
+                                (float*)dev_scratch, share, s);
+  if (rc == RKV_OK && cache->ragged) rc = rkv_launch_lens(cache, -1, 1, s);
+  if (rc != RKV_OK) return rc;
+  cache->v.len += 1;
+  for (int b = 0; b < cache->v.B; ++b) cache->hlens[b] += 1;
+  return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, 0, dev_out, dev_lse, dev_scratch, true, s);
 }
 
 RKV_EXPORT int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, int32_t n_queries,
@@ -342,7 +363,7 @@ RKV_EXPORT int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, c
     for (int b = 0; b < cache->v.B; ++b)
       if (cache->hlens[b] < 1) return RKV_ESTATE;
   if (!rkv_mfma_supported(cache) || cache->decode_path == 1) return RKV_EINVAL;   // matrix-core path only
-  return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, n_queries, dev_out, dev_lse, dev_scratch,
+  return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, n_queries, dev_out, dev_lse, dev_scratch, false,
                                 (hipStream_t)stream);
 }
 

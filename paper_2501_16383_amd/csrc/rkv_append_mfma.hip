@@ -22,6 +22,7 @@
 //   values  wave w: tokens 8w..8w+7.
 #include "rkv_internal.h"
 #include "rkv_quant.h"
+#include "rkv_prep_q.h"
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -96,9 +97,10 @@ __device__ __forceinline__ void fused_round_consts(float zero, float& base, floa
   add = base + zero;
 }
 
+// bx, rg, b: the workgroup's place in the (3 x slabs, rotation groups, sequences) grid
 template <int G>
-__global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
-                                                     int n_new, int slab0) {
+__device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+                                                 int n_new, int slab0, int bx, int rg, int b) {
   constexpr int PL = 2 * G;                    // value channels per lane
   constexpr int LPB = 128 / PL;                // lanes per 128-block in the value role
   constexpr int n = 128 * G;
@@ -113,12 +115,11 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
   __shared__ float2 s_mm[2][2][16][G];         // [dword half][product pair][token][head] (min, max) of a quarter block
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: everything that depends only on it stays scalar
-  const int role = blockIdx.x % 3;             // 0, 1: the keys of K tile 0 / 1 of a slab; 2: the slab's values
+  const int role = bx % 3;                     // 0, 1: the keys of K tile 0 / 1 of a slab; 2: the slab's values
   // n_new: rows per sequence in kin and vin; sequence b holds len_b tokens and appends the first
   // n_b rows (all of them, at the common length, unless the view carries per-sequence arrays)
-  const int rg = blockIdx.y, b = blockIdx.z;
   const int len_b = rkv_len(v, b), n_b = v.nnew ? v.nnew[b] : n_new;
-  const int slab = (v.lens ? (len_b >> 5) : slab0) + blockIdx.x / 3;
+  const int slab = (v.lens ? (len_b >> 5) : slab0) + bx / 3;
   const int t_lo = len_b, t_hi = len_b + n_b;
   const int ts = slab * 32;
   if (ts >= t_hi || n_b <= 0) return;                 // the grid covers the longest append: nothing here for this sequence
@@ -380,6 +381,30 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
   }
 }
 
+template <int G>
+__global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+                                                     int n_new, int slab0) {
+  append_mfma_body<G>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// One decode step's write half and query preparation in one launch: the first 3 * n_slabs
+// workgroups of a (rotation group, sequence) append the step's token as k_append_mfma does, the
+// rest prepare that rotation group's query heads (two heads per workgroup) for the decode kernel,
+// which saves a launch of its own for a few microseconds of work.  The query's default position
+// is the appended token's: one past the last token the view knows of.
+template <int G>
+__global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+                                                   int slab0, int n_append_blocks, const __half* __restrict__ q,
+                                                   const int* __restrict__ q_pos, float* __restrict__ qr, int share) {
+  if ((int)blockIdx.x < n_append_blocks) {
+    append_mfma_body<G>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+    return;
+  }
+  const int rep = v.Hq / v.Hkv;
+  const int h = blockIdx.y * G * rep + 2 * ((int)blockIdx.x - n_append_blocks) + (threadIdx.x >> 7);
+  rkv_prep_q_one(v, q, q_pos, 1, qr, share, 1, h, blockIdx.z, threadIdx.x & 127);
+}
+
 bool rkv_append_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
   return c->blocks_aligned && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
@@ -404,5 +429,18 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   if (v.g == 4) hipLaunchKernelGGL(k_append_mfma<4>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   else hipLaunchKernelGGL(k_append_mfma<2>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
+  return rkv_check_launch();
+}
+
+// The fused launch of k_step_mfma: one token per sequence from k, vv [batch][1][...], queries q.
+int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const __half* q, const int* q_pos, float* qr, int share,
+                         hipStream_t s) {
+  const RkvView& v = c->v;
+  if (!rkv_append_mfma_supported(c)) return RKV_EINVAL;
+  int max_slabs = 1;                                        // one token touches one slab of its sequence
+  const int n_append = 3 * max_slabs, rep = v.Hq / v.Hkv;
+  dim3 grid(n_append + v.g * rep / 2, v.NRG, v.B);
+  if (v.g == 4) hipLaunchKernelGGL(k_step_mfma<4>, grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  else hipLaunchKernelGGL(k_step_mfma<2>, grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
   return rkv_check_launch();
 }

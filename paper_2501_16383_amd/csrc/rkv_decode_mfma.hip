@@ -639,8 +639,14 @@ static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* q
 // token's exact row).  nq >= 1: nq query tokens per sequence, token i at position q_pos[b][i] and
 // blind to cached tokens behind it; q, out and lse are then [batch][nq][heads][...] and the scratch
 // buffer holds nq times the single-query size.
+// query heads of a KV head served by one workgroup: two where the ratio is even (four per
+// workgroup measured slower: 158 against 151 us on the GQA configuration - the variant needs
+// more registers than three workgroups per compute unit leave)
+int rkv_mfma_share(int heads_per_kv_head) { return heads_per_kv_head % 2 == 0 ? 2 : 1; }
+
+// q_prepared: the queries are already in the scratch block (rkv_launch_step_mfma put them there)
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int nq, float* out, float* lse, void* scratch,
-                           hipStream_t s) {
+                           bool q_prepared, hipStream_t s) {
   if (!rkv_mfma_supported(c)) return RKV_EINVAL;
   const bool multi = nq > 0;
   if (multi && (c->cur_k || !q_pos)) return RKV_EINVAL;
@@ -652,11 +658,8 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
   const int rep = v.Hq / v.Hkv;
-  // query heads of a KV head served by one workgroup: two where the ratio is even (four per
-  // workgroup measured slower: 158 against 151 us on the GQA configuration - the variant needs
-  // more registers than three workgroups per compute unit leave)
-  const int share = rep % 2 == 0 ? 2 : 1;
-  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
+  const int share = rkv_mfma_share(rep);
+  if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   dim3 grid(((nch + 7) & ~7) * (rep / share), v.NRG, v.B);
   if (c->ragged) {                                          // all sequences' chunks in one dimension

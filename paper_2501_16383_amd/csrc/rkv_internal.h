@@ -225,7 +225,10 @@ int rkv_launch_import(rkv_cache* c, int T, const uint8_t* kc, const float* ks, c
 int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
                               hipStream_t s);
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int nq, float* out, float* lse, void* scratch,
-                           hipStream_t s);
+                           bool q_prepared, hipStream_t s);
+int rkv_mfma_share(int heads_per_kv_head);
+int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* v, const __half* q, const int* q_pos, float* qr, int share,
+                         hipStream_t s);
 bool rkv_mfma_supported(const rkv_cache* c);
 void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int cur, float* qr, int share, int nq,
                        hipStream_t s);

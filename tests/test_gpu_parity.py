@@ -806,3 +806,43 @@ def test_sequences_of_different_lengths():
         cache.quantize_append_ragged(P.gpu(np.zeros((B, 2, 8, 128), np.float16)), P.gpu(np.zeros((B, 2, 8, 128), np.float16)), [1, 3, 0])
     cache.reset()
     assert cache.lengths == [0, 0, 0]
+
+
+@pytest.mark.parametrize("hq,hkv,g,ragged", [(8, 8, 4, False), (16, 4, 4, False), (4, 4, 2, True), (8, 8, 8, False)])
+def test_one_call_decode_step_equals_the_two_calls(hq, hkv, g, ragged):
+    """rkv_decode_step (append + attention in one call; on the matrix-core configurations the
+    token's compression and the query's preparation share a launch) against rkv_quantize_append
+    followed by rkv_decode_attention on a second cache with the same contents: outputs, codes and
+    metadata bit for bit, over several steps that cross a tile and a slab boundary; also with
+    sequences of different lengths, explicit query positions, and on a configuration that falls
+    back to the two calls (rotation over 8 heads)."""
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
+    B, T0, steps = 2, 29, 6
+    cfg = R.RkvConfig(batch=B, n_q_heads=hq, n_kv_heads=hkv, max_tokens=128, max_sinks=4, rot_heads=g)
+    k, v, mask = S.make_kv(w, T0 + steps, batch=B)
+    a, b = R.RkvCache(cfg), R.RkvCache(cfg)
+    for c in (a, b):
+        if ragged:
+            c.quantize_append_ragged(P.gpu(k[:, :T0]), P.gpu(v[:, :T0]), [T0, T0 - 12], P.gpu(mask[:, :T0]))
+        else:
+            c.quantize_append(P.gpu(k[:, :T0]), P.gpu(v[:, :T0]), P.gpu(mask[:, :T0]))
+    for s_ in range(steps):
+        q = P.gpu(S.make_q(w, batch=B, step=s_))
+        kk, vv = P.gpu(k[:, T0 + s_:T0 + s_ + 1]), P.gpu(v[:, T0 + s_:T0 + s_ + 1])
+        q_pos = None if s_ % 2 == 0 else P.gpu(np.array([200 + s_, 7], dtype=np.int32))
+        print(f"[case] decode step {s_} Hq={hq} Hkv={hkv} g={g} ragged={ragged}", flush=True)
+        o1, l1 = a.decode_step(kk, vv, q, q_pos, want_lse=True)
+        b.quantize_append(kk, vv)
+        o2, l2 = b.decode_attention(q, q_pos, want_lse=True)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2) and torch.equal(l1, l2), f"step {s_}"
+    assert a.lengths == b.lengths
+    ea, eb = a.export_codes(), b.export_codes()
+    torch.cuda.synchronize()
+    for name in ea:
+        assert torch.equal(ea[name], eb[name]), name
+    with pytest.raises(R.RkvError) as ei:                     # a full cache refuses the step
+        full = R.RkvCache(dataclasses.replace(cfg, max_tokens=T0))
+        full.quantize_append(P.gpu(k[:, :T0]), P.gpu(v[:, :T0]))
+        full.decode_step(P.gpu(k[:, :1]), P.gpu(v[:, :1]), P.gpu(S.make_q(w, batch=B)))
+    assert ei.value.code == -2
