@@ -142,9 +142,33 @@ __global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restri
   for (int i = 0; i < nn; ++i) {
     const int t = s_tok[i];
     const size_t src = ((size_t)b * n_new + t) * v.E, dst = ((size_t)b * v.max_sinks + cnt0 + i) * v.E;
-    for (int e = tid; e < v.E; e += 256) {
-      if (!v.keys_rotated) v.sink_k[dst + e] = k[src + e];
-      v.sink_v[dst + e] = vv[src + e];
+    // whole rows, 16 bytes per lane, every load of a round issued before its stores (rows are
+    // 256-byte multiples and 16-byte aligned: E is a multiple of 128 halves)
+    {
+      const uint4* k4 = reinterpret_cast<const uint4*>(k + src);
+      const uint4* v4 = reinterpret_cast<const uint4*>(vv + src);
+      uint4* dk4 = reinterpret_cast<uint4*>(v.sink_k + dst);
+      uint4* dv4 = reinterpret_cast<uint4*>(v.sink_v + dst);
+      const int n16 = v.E / 8;
+      for (int e0 = 0; e0 < n16; e0 += 4 * 256) {
+        uint4 a[4], c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + u * 256 + tid;
+          if (e < n16) {
+            if (!v.keys_rotated) a[u] = k4[e];
+            c[u] = v4[e];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + u * 256 + tid;
+          if (e < n16) {
+            if (!v.keys_rotated) dk4[e] = a[u];
+            dv4[e] = c[u];
+          }
+        }
+      }
     }
     if (v.keys_rotated) {
       // the keys arrived rotated and reordered: undo the reorder, rotate again (H is its own
