@@ -73,16 +73,28 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
   const int hh = lane / lanes_per_head;                       // KV head inside the group
   const int idx0 = (PL * lane) & (RKV_D - 1);                 // first channel inside the head
   const float rs = rsqrtf((float)n);
+  // What does not depend on the token: a lane's PL consecutive rotated channels share one dword of
+  // a K tile (the layout keeps 16 aligned channels of a token together), at a fixed offset and with
+  // fixed shifts; each channel's quantization block, hence the place of its metadata in a token's row.
+  int sh[PL];
+  size_t mi0[PL];
+  int dw_off = 0;
+#pragma unroll
+  for (int i = 0; i < PL; ++i) {
+    const int c = PL * lane + i;
+    const int off = rkv_k_off(g, 0, c, sh[i]);
+    if (i == 0) dw_off = off;
+    mi0[i] = rkv_meta_index(v, b, 0, v.gid[rg * n + c]);
+  }
+  const int tok_stride = g == 1 ? 2 : 4;                       // dwords between consecutive tokens of a tile
   for (int t = t0 + wave; t < t1; t += 4) {
     float x[PL];
+    const uint32_t w = v.kc[rkv_k_tilebase(v, b, rg, t >> 4) + dw_off + (t & 15) * tok_stride];
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
-      const int c = PL * lane + i;
-      int sh;
-      const uint32_t w = v.kc[rkv_k_dword(v, b, rg, t, c, sh)];
       float sc, zero;
-      rkv_load_meta(v, v.km, rkv_meta_index(v, b, t, v.gid[rg * n + c]), sc, zero);
-      x[i] = sc * ((float)((w >> sh) & 3u) - zero);             // Eq. 7
+      rkv_load_meta(v, v.km, mi0[i] + (size_t)t * g, sc, zero);
+      x[i] = sc * ((float)((w >> sh[i]) & 3u) - zero);          // Eq. 7
     }
     fwht_lanes_d<PL>(x, lane, 6);                               // inverse rotation (H is its own inverse)
     float y[PL];
