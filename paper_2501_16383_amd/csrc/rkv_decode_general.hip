@@ -223,11 +223,15 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   float pv[PRE];
 #pragma unroll
   for (int k = 0; k < PRE; ++k) pv[k] = k < nch ? P[(size_t)k * RKV_PART_STRIDE + 4 + c] : 0.f;
-  for (int s0 = 0; s0 < cnt; s0 += 4) {                    // four sink rows at a time: their loads overlap
+  // Sink rows four at a time, so that their loads overlap.  Row indices are clamped to the store's
+  // capacity, not to the count of retained rows: the first group's loads then do not wait for that
+  // count to arrive (slots never written hold position 0 and zeros; their scores are not used).
+  const int smax = v.max_sinks > 0 ? v.max_sinks - 1 : 0;
+  auto sink_group = [&](int s0) {
     float d[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int s = min(s0 + i, cnt - 1);
+      const int s = min(s0 + i, smax);
       const int pos = v.sink_pos[b * v.max_sinks + s];
       const __half* kr = v.sink_k + ((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D;
       const float2 cs = v.rope[(size_t)pos * 64 + j];
@@ -239,7 +243,9 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
       for (int o = 32; o > 0; o >>= 1) d[i] += __shfl_xor(d[i], o);
       if (lane == 0 && s0 + i < cnt) s_part[wave][s0 + i] = v.sink_pos[b * v.max_sinks + s0 + i] <= lim ? d[i] : -INFINITY;
     }
-  }
+  };
+  if (v.max_sinks > 0) sink_group(0);
+  for (int s0 = 4; s0 < cnt; s0 += 4) sink_group(s0);
   // the token being decoded, if it is attended in full precision: an exact row at position len
   // (which may lie one past the angle table, so its angles are computed here)
   float cur_score = -INFINITY;
