@@ -201,15 +201,13 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
   const uint32_t sm23 = ((__popc(hrow & 2) & 1) ? 0x00008000u : 0u) | ((__popc(hrow & 3) & 1) ? 0x80000000u : 0u);
 
   // Of the `rep` query heads that share a KV head (GQA) one workgroup serves REP, so that unpacking,
-  // rotation and RoPE of the keys are done once for them.  blockIdx.x = rrg * nch8 + chunk, nch8 =
-  // chunk count rounded up to 8: if rep > REP the workgroups of the other query-head groups re-read
-  // the same chunk, and with ids a multiple of 8 apart they land on the same XCD, whose L2 then
-  // holds the chunk for the later ones
+  // rotation and RoPE of the keys are done once for them; if rep > REP the workgroups of the other
+  // query-head groups re-read the same chunk.
   // With per-sequence lengths the grid has no sequence dimension: the chunks of all sequences are
   // numbered consecutively (cstart[b] = chunks of the sequences before b), rounded up to 8 in all,
   // so that no workgroup is launched for chunks a shorter sequence does not have.
   const int rep = v.Hq / v.Hkv;
-  const int rg = blockIdx.y;
+  int rg = blockIdx.y;
   int rrg, chunk, b;
   if (v.lens) {
     const int tot8 = gridDim.x / (rep / REP);
@@ -225,11 +223,19 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
     b = lo;
     chunk = w - v.cstart[b];
   } else {
-    const int nch8 = (nch + 7) & ~7;
-    rrg = blockIdx.x / nch8;
-    chunk = blockIdx.x - rrg * nch8;
-    b = blockIdx.z;
-    if (chunk >= nch) return;
+    // One grid dimension.  Workgroups go to the chip's eight compute dies (each with an L2 of its
+    // own) in turn, so id % 8 names the die: a die takes every eighth (sequence, rotation group)
+    // and runs all of its chunks, and for each chunk the workgroups of all query-head groups one
+    // after the other.  What those workgroups share - the prepared queries, the sink list, and
+    // with GQA the chunk's codes themselves - is then fetched into one L2 once.
+    const int xcd = blockIdx.x & 7, t = blockIdx.x >> 3, ns = rep / REP;
+    const int br8 = t / (nch * ns), rem = t - br8 * (nch * ns);
+    chunk = rem / ns;
+    rrg = rem - chunk * ns;
+    const int br = br8 * 8 + xcd;
+    if (br >= v.B * v.NRG) return;
+    b = br / v.NRG;
+    rg = br - b * v.NRG;
   }
   const int len = rkv_len(v, b);
   if (chunk * MF_CH >= len) return;
@@ -661,7 +667,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   const int share = rkv_mfma_share(rep);
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
-  dim3 grid(((nch + 7) & ~7) * (rep / share), v.NRG, v.B);
+  dim3 grid(8 * ((v.B * v.NRG + 7) / 8) * nch * (rep / share), 1, 1);   // see the kernel for the mapping
   if (c->ragged) {                                          // all sequences' chunks in one dimension
     int total = 0;
     for (int b = 0; b < v.B; ++b) total += (c->hlens[b] + MF_CH - 1) / MF_CH;
