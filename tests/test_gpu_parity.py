@@ -846,3 +846,42 @@ def test_one_call_decode_step_equals_the_two_calls(hq, hkv, g, ragged):
         full.quantize_append(P.gpu(k[:, :T0]), P.gpu(v[:, :T0]))
         full.decode_step(P.gpu(k[:, :1]), P.gpu(v[:, :1]), P.gpu(S.make_q(w, batch=B)))
     assert ei.value.code == -2
+
+
+@pytest.mark.parametrize("hq,hkv,g,fmt", [(24, 8, 4, 0), (32, 4, 4, 1), (8, 4, 2, 0), (12, 4, 2, 1)])
+def test_gqa_ratios_and_metadata_formats(hq, hkv, g, fmt):
+    """Query heads per KV head of 3 (one per workgroup), 8 (four workgroups of two per KV head) and
+    2, with rotation over 4 and over 2 heads, in both metadata formats; both decode kernels."""
+    w = small("cfg4", n_q_heads=hq, n_kv_heads=hkv)
+    cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=hkv, max_tokens=600, max_sinks=4, rot_heads=g, meta_format=fmt,
+                      rope_theta=500000.0)
+    full_check(w, cfg, 531, paths=(1, 2))
+
+
+def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
+    """Features together: keys from a projection with the rotation folded in, FP8 / INT8 metadata,
+    no sink rows, prefill followed by one-call decode steps; codes against the oracle under the
+    tie protocol, attention on the GPU's own codes."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8, n_sinks=0)
+    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=0, rot_heads=4, keys_rotated=1, meta_format=1)
+    ocfg = P.oracle_cfg(cfg)
+    T0, steps = 70, 3
+    k, v, _ = S.make_kv(w, T0 + steps, batch=2, sink_positions=[])
+    # what the folded projection hands over: rotated, (identity-)reordered, rounded to fp16
+    kz = O.fold_rotation(k.astype(np.float64).reshape(-1, cfg.E), ocfg).astype(np.float16).reshape(k.shape)
+    cache = R.RkvCache(cfg)
+    oc = O.cache_new(ocfg)
+    cache.quantize_append(P.gpu(kz[:, :T0]), P.gpu(v[:, :T0]))
+    O.quantize_append(oc, kz[:, :T0], v[:, :T0], None, keys_rotated=True)
+    for s_ in range(steps):
+        q = S.make_q(w, batch=2, step=s_)
+        t = T0 + s_
+        print(f"[case] rotated keys + fp8 metadata, one-call step {s_}", flush=True)
+        out = cache.decode_step(P.gpu(kz[:, t:t + 1]), P.gpu(v[:, t:t + 1]), P.gpu(q))
+        O.quantize_append(oc, kz[:, t:t + 1], v[:, t:t + 1], None, keys_rotated=True)
+        torch.cuda.synchronize()
+        g, _, _ = P.check_cache_against_oracle(cache, oc, f"rotated keys + fp8, step {s_}")
+        ref, _ = O.decode_attention(oracle_from_export(oc, g), q)
+        e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
+        print(f"[parity] step {s_}: out err {e:.3e}", flush=True)
+        assert e <= ATT_TOL
