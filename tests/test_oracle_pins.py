@@ -638,3 +638,66 @@ def test_multi_query_decode_is_a_sequence_of_single_steps():
     for i in range(nq):
         assert np.allclose(out[:, i], ref[i][0], rtol=0, atol=1e-12)
         assert np.allclose(lse[:, i], ref[i][1], rtol=0, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- properties over random shapes
+
+from hypothesis import given, settings, strategies as st   # noqa: E402
+
+
+@settings(max_examples=40, deadline=None)
+@given(st.integers(0, 2 ** 31 - 1), st.sampled_from([1, 2, 4]), st.sampled_from([1, 2, 4, 8]), st.sampled_from([128, "n", "E"]))
+def test_write_then_read_views_are_consistent(seed, rot_heads, heads_mult, span_kind):
+    """For random head counts, rotation sizes and reorder spans: the reorder from calibration is a
+    permutation closed under its span; reorder and rotation invert exactly; every reconstructed
+    element of the rotated, reordered row lies within half a stored step of what was quantized;
+    and the dequantized cache is that reconstruction carried back (inverse reorder, rotation)."""
+    hkv = rot_heads * heads_mult
+    cfg = O.OracleConfig(batch=1, n_q_heads=hkv, n_kv_heads=hkv, rot_heads=rot_heads)
+    span = {128: 128, "n": cfg.n, "E": cfg.E}[span_kind]
+    cfg = O.OracleConfig(batch=1, n_q_heads=hkv, n_kv_heads=hkv, rot_heads=rot_heads, perm_span=span, max_sinks=0)
+    rng = np.random.default_rng(seed)
+    perm = O.calibrate_perm(rng.standard_normal((8, hkv, 128)) + rng.standard_normal((1, hkv, 128)), cfg)
+    assert sorted(perm.tolist()) == list(range(cfg.E))
+    assert np.array_equal(perm // span, np.arange(cfg.E) // span)
+    k = (rng.standard_normal((1, 5, hkv, 128)) * np.exp(rng.uniform(-2, 2))).astype(np.float16)
+    v = rng.standard_normal((1, 5, hkv, 128)).astype(np.float16)
+    c = O.cache_new(cfg, perm)
+    O.quantize_append(c, k, v)
+    z = c.k_rot
+    back = O.rotate_groups(O.reorder_inverse(z, perm), cfg.n).reshape(k.shape)
+    assert np.allclose(back, k.astype(np.float64), atol=1e-9 * max(1.0, float(np.abs(k).max())))
+    zq = O.dequantize(c.k_codes, c.k_scale, c.k_zero)
+    assert np.all(np.abs(zq - z) <= 0.5 * np.repeat(c.k_scale, 128, axis=-1) * (1 + 2.0 ** -8))
+    k_hat, v_hat = O.dequantize_cache(c)
+    assert np.allclose(k_hat, O.rotate_groups(O.reorder_inverse(zq, perm), cfg.n).reshape(k.shape), atol=1e-9 * max(1.0, float(np.abs(k).max())))
+    assert np.all(np.abs(v_hat.reshape(1, 5, -1) - v.astype(np.float64).reshape(1, 5, -1)) <= 0.5 * np.repeat(c.v_scale, 128, axis=-1) * (1 + 2.0 ** -8))
+
+
+@settings(max_examples=25, deadline=None)
+@given(st.integers(0, 2 ** 31 - 1), st.integers(1, 40), st.sampled_from([(4, 4), (8, 2), (6, 3)]), st.integers(0, 3))
+def test_attention_is_a_convex_combination_and_shift_invariant(seed, T, heads, n_sink):
+    """Eq. 5 for random lengths and GQA ratios: every output lies in the hull of the values the
+    read half sees; the log-sum-exp bounds the largest score; shifting the query position and all
+    key positions together is impossible to express through the interface, but a query far away
+    changes nothing when every key sits at position 0 (T = 1)."""
+    hq, hkv = heads
+    cfg = O.OracleConfig(batch=1, n_q_heads=hq, n_kv_heads=hkv, rot_heads=1, max_sinks=4)
+    rng = np.random.default_rng(seed)
+    k = rng.standard_normal((1, T, hkv, 128)).astype(np.float16)
+    v = rng.standard_normal((1, T, hkv, 128)).astype(np.float16)
+    q = rng.standard_normal((1, hq, 128)).astype(np.float16)
+    mask = np.zeros((1, T), np.uint8)
+    mask[0, :min(n_sink, T)] = 1
+    c = O.cache_new(cfg)
+    O.quantize_append(c, k, v, mask)
+    out, lse = O.decode_attention(c, q)
+    _, v_hat = O.dequantize_cache(c, substitute_sinks=True)
+    rep = hq // hkv
+    for h in range(hq):
+        vals = v_hat[0, :, h // rep, :]
+        assert np.all(out[0, h] <= vals.max(0) + 1e-9) and np.all(out[0, h] >= vals.min(0) - 1e-9)
+    assert np.isfinite(lse).all()
+    if T == 1:
+        out2, _ = O.decode_attention(c, q, np.array([12345]))
+        assert np.allclose(out, out2, atol=1e-12)       # softmax over one key: its value, wherever the query sits
