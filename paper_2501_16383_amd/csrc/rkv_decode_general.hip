@@ -227,6 +227,11 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
   // capacity, not to the count of retained rows: the first group's loads then do not wait for that
   // count to arrive (slots never written hold position 0 and zeros; their scores are not used).
   const int smax = v.max_sinks > 0 ? v.max_sinks - 1 : 0;
+  // the value rows of the first four sinks are requested here as well, long before they are used
+  float sv[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    sv[i] = __half2float(v.sink_v[((size_t)b * v.max_sinks + min(i, smax)) * v.E + (size_t)kvh * RKV_D + c]);
   auto sink_group = [&](int s0) {
     float d[4];
 #pragma unroll
@@ -302,7 +307,15 @@ __global__ void __launch_bounds__(128) k_merge(RkvView v, const float* __restric
     }
     acc = red[c] * 0.08838834764831845f;
   }
-  for (int s = 0; s < cnt; ++s) {
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    if (s < cnt) {
+      const float w = s_score[s] > -INFINITY ? __expf(s_score[s] - M) : 0.f;
+      L += w;
+      acc += w * sv[s];
+    }
+  }
+  for (int s = 4; s < cnt; ++s) {
     const float w = s_score[s] > -INFINITY ? __expf(s_score[s] - M) : 0.f;
     L += w;
     acc += w * __half2float(v.sink_v[((size_t)b * v.max_sinks + s) * v.E + (size_t)kvh * RKV_D + c]);
