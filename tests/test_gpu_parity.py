@@ -276,8 +276,8 @@ def export_host(cache):
 @pytest.mark.parametrize("meta_format", [0, 1])
 def test_full_size_config2_sampled(meta_format):
     """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
-    configuration bench.py times: bulk append of 4095 tokens, one single-token append, decode on
-    the matrix-core path.  The oracle recomputes sampled (sequence, rotation group) slices - a
+    configuration bench.py times: bulk append of 4095 tokens, then one rkv_decode_step (the last
+    token's append and the attention on the matrix-core path).  The oracle recomputes sampled (sequence, rotation group) slices - a
     rotation group's codes and attention outputs depend on nothing outside the slice.  Once with
     fp16 metadata, once with the FP8 scale / INT8 zero-point storage."""
     w = S.WORKLOADS["cfg2"]
@@ -305,11 +305,11 @@ def test_full_size_config2_sampled(meta_format):
     mask = torch.cat(m_parts).cuda()
     del k_parts, v_parts
     q = S.make_q(w)
-    print("[case] full-size config 2: bulk append 4095 + single append + decode", flush=True)
+    print("[case] full-size config 2: bulk append 4095 + one decode step (append 1 + attention, as bench.py does)", flush=True)
     cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous())
-    cache.quantize_append(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), mask[:, T - 1:].contiguous())
     cache.set_decode_path(2)
-    out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
+    assert not bool(mask[:, T - 1:].any())                  # the step's token is an ordinary one
+    out, lse = cache.decode_step(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), P.gpu(q), want_lse=True)
     exp = export_host(cache)
     assert cache.length == T
     out = out.cpu().numpy().astype(np.float64)
