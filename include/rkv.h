@@ -4,7 +4,8 @@
  * The library implements the write half and the read half of RotateKV (arXiv 2501.16383):
  *   write  (Sec. 4.1, 4.2, 4.4; Eq. 6-9): grouped-head Walsh-Hadamard rotation of pre-RoPE keys,
  *          calibrated channel reorder, per-token asymmetric 2-bit quantization in blocks of 128
- *          with an fp16 scale and an fp16 integer zero-point per block, attention-sink tokens
+ *          with a scale and an integer zero-point per block (fp16 + fp16, or FP8 + INT8 as in
+ *          the quantization settings of Sec. 5.1: rkv_config.meta_format), attention-sink tokens
  *          kept in fp16 (Sec. 4.3);
  *   read   (decoding phase, Eq. 4-5; Sec. 4.4 "inverse online reordering and rotation"):
  *          dequantize, undo reorder and rotation, RoPE, softmax(q.K^T/sqrt(d)).V.
@@ -17,7 +18,8 @@
  *     otherwise a call only enqueues work on that stream and returns without synchronising.
  *   - Every call returns RKV_OK (0) or a negative error code; nothing is thrown across the ABI.
  *     On RKV_EHIP the HIP error is left readable through hipGetLastError.
- *   - One cache object holds one layer.  All sequences of a cache have the same length.
+ *   - One cache object holds one layer.  All sequences of a cache have the same length unless
+ *     rkv_quantize_append_ragged has given them lengths of their own.
  *   - Tensors are dense, row-major, in the index order written next to each argument.
  *     A token's keys/values are [n_kv_heads][head_dim] (head-major), E = n_kv_heads*head_dim.
  *   - Keys are given and stored PRE-RoPE; RoPE is applied inside rkv_decode_attention to the
