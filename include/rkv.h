@@ -100,6 +100,15 @@ int rkv_cache_length(const rkv_cache* cache);
 /* The same per sequence: host_lengths [batch] int32 (host memory). */
 int rkv_cache_lengths(const rkv_cache* cache, int32_t* host_lengths);
 
+/* Shorten sequences: sequence b keeps its first host_new_lengths[b] tokens (0 <= new <= current
+ * length, else RKV_EINVAL and nothing changes); retained sink rows at or behind the new end are
+ * dropped.  This is the roll-back after a multi-token step whose later tokens were rejected
+ * (speculative decoding with rkv_decode_attention_multi); the slots are reused by later appends.
+ * If the new lengths differ the cache continues with per-sequence lengths, under the conditions
+ * of rkv_quantize_append_ragged.
+ *   host_new_lengths  [batch] int32 in host memory; read before the call returns */
+int rkv_cache_truncate(rkv_cache* cache, const int32_t* host_new_lengths, void* stream);
+
 /* Calibration for reordering indices (Alg. 1): rotate the calibration keys with the grouped-head
  * Hadamard, sum every channel over all tokens (signed, float64), and sort channel indices by that
  * sum - ascending, stable, inside each perm_span block.

@@ -20,7 +20,7 @@ RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
     "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention", "rkv_decode_attention_with_current",
-    "rkv_decode_attention_multi", "rkv_decode_step", "rkv_quantize_append_ragged", "rkv_cache_lengths",
+    "rkv_decode_attention_multi", "rkv_decode_step", "rkv_quantize_append_ragged", "rkv_cache_lengths", "rkv_cache_truncate",
     "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
@@ -100,6 +100,7 @@ def load_library():
     lib.rkv_decode_step.argtypes = [vp] * 9
     lib.rkv_quantize_append_ragged.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp]
     lib.rkv_cache_lengths.argtypes = [vp, vp]
+    lib.rkv_cache_truncate.argtypes = [vp, vp, vp]
     lib.rkv_set_decode_path.argtypes = [vp, i32]
     lib.rkv_set_profile_events.argtypes = [vp, vp, vp]
     lib.rkv_dequantize.argtypes = [vp, vp, vp, vp]
@@ -265,6 +266,15 @@ class RkvCache:
         arr = (C.c_int32 * self.cfg.batch)()
         _check(self.lib.rkv_cache_lengths(self.handle, arr), "rkv_cache_lengths")
         return list(arr)
+
+    def truncate(self, new_lengths):
+        """rkv_cache_truncate: an int (all sequences) or one int per sequence."""
+        B = self.cfg.batch
+        vals = [int(new_lengths)] * B if isinstance(new_lengths, int) else [int(x) for x in new_lengths]
+        if len(vals) != B:
+            raise ValueError("one length per sequence")
+        arr = (C.c_int32 * B)(*vals)
+        _check(self.lib.rkv_cache_truncate(self.handle, arr, _stream()), "rkv_cache_truncate")
 
     def quantize_append_ragged(self, k, v, n_new, sink_mask=None):
         """rkv_quantize_append_ragged: k, v [batch, n_new_max, n_kv_heads, 128] fp16; n_new: ints per sequence."""

@@ -181,6 +181,33 @@ RKV_EXPORT int rkv_cache_lengths(const rkv_cache* cache, int32_t* host_lengths) 
   return RKV_OK;
 }
 
+RKV_EXPORT int rkv_cache_truncate(rkv_cache* cache, const int32_t* host_new_lengths, void* stream) {
+  if (!cache || !host_new_lengths) return RKV_EINVAL;
+  const int B = cache->v.B;
+  int lo = host_new_lengths[0], hi = lo;
+  for (int b = 0; b < B; ++b) {
+    const int nl = host_new_lengths[b];
+    if (nl < 0 || nl > cache->hlens[b]) return RKV_EINVAL;
+    lo = nl < lo ? nl : lo;
+    hi = nl > hi ? nl : hi;
+  }
+  if (lo != hi && !cache->ragged && !rkv_append_mfma_supported(cache)) return RKV_EINVAL;   // would need per-sequence lengths
+  hipStream_t s = (hipStream_t)stream;
+  RKV_HIP_CHECK(hipMemcpyAsync(cache->dev_nnew, host_new_lengths, (size_t)B * 4, hipMemcpyHostToDevice, s));
+  cache->v.nnew = cache->dev_nnew;
+  const int rc = rkv_launch_lens(cache, -2, 0, s);
+  cache->v.nnew = nullptr;
+  if (rc != RKV_OK) return rc;
+  for (int b = 0; b < B; ++b) cache->hlens[b] = host_new_lengths[b];
+  cache->v.len = hi;
+  if (lo != hi && !cache->ragged) {
+    cache->ragged = 1;
+    cache->v.lens = cache->dev_lens;
+    cache->v.cstart = cache->dev_cstart;
+  }
+  return RKV_OK;
+}
+
 RKV_EXPORT int rkv_set_decode_path(rkv_cache* cache, int32_t path) {
   if (!cache || path < 0 || path > 2) return RKV_EINVAL;
   cache->decode_path = path;

@@ -500,8 +500,10 @@ int rkv_launch_sinks(rkv_cache* c, const __half* k, const __half* vv, const uint
   return rkv_check_launch();
 }
 
-// Per-sequence lengths on the device: set_to >= 0 sets every length to it; otherwise each length
-// grows by `add` plus, while an append with per-sequence counts is in progress, by its count.
+// Per-sequence lengths on the device: set_to >= 0 sets every length to it; set_to == -2 takes them
+// from the staged per-sequence array (a truncation: retained sink rows at or behind the new end
+// are dropped too - they were added in order of position); otherwise each length grows by `add`
+// plus, while an append with per-sequence counts is in progress, by its count.
 // Also rebuilds cstart (running count of 256-token chunks, see RkvView) - one workgroup; thread i
 // owns a contiguous slice of the sequences.
 __global__ void __launch_bounds__(256) k_lens(RkvView v, int* lens, int* cstart, int set_to, int add) {
@@ -510,8 +512,13 @@ __global__ void __launch_bounds__(256) k_lens(RkvView v, int* lens, int* cstart,
   const int per = (v.B + 255) / 256, b0 = min(tid * per, v.B), b1 = min(b0 + per, v.B);
   int chunks = 0;
   for (int b = b0; b < b1; ++b) {
-    const int len = set_to >= 0 ? set_to : lens[b] + add + (v.nnew ? v.nnew[b] : 0);
+    const int len = set_to >= 0 ? set_to : (set_to == -2 ? v.nnew[b] : lens[b] + add + (v.nnew ? v.nnew[b] : 0));
     lens[b] = len;
+    if (set_to == -2 && v.max_sinks > 0) {
+      int c = v.sink_cnt[b];
+      while (c > 0 && v.sink_pos[b * v.max_sinks + c - 1] >= len) --c;
+      v.sink_cnt[b] = c;
+    }
     chunks += (len + 255) >> 8;
   }
   s_sum[tid] = chunks;

@@ -885,3 +885,63 @@ def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
         e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
         print(f"[parity] step {s_}: out err {e:.3e}", flush=True)
         assert e <= ATT_TOL
+
+
+@pytest.mark.parametrize("uniform", [True, False])
+def test_truncate_rolls_back_a_multi_token_step(uniform):
+    """Speculative decoding's shape: four drafted tokens are appended and read the cache together
+    (rkv_decode_attention_multi); some are rejected, rkv_cache_truncate rolls the cache back, and
+    decoding goes on with other tokens.  The cache must then equal - codes, metadata, sink rows,
+    lengths, attention outputs, all bit for bit - a cache that only ever saw the accepted tokens.
+    One of the drafted tokens is a flagged sink behind the cut: it must be dropped."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8)
+    B, T0 = 2, 45
+    cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=4, rot_heads=4)
+    k, v, mask = S.make_kv(w, T0 + 4 + 3, batch=B, sink_positions=[0, 1])
+    mask = mask.copy()
+    mask[:, T0 + 3] = 1                                        # the last drafted token is flagged as a sink
+    accepted = [2, 2] if uniform else [3, 1]
+    a, b = R.RkvCache(cfg), R.RkvCache(cfg)
+    a.quantize_append(P.gpu(k[:, :T0 + 4]), P.gpu(v[:, :T0 + 4]), P.gpu(mask[:, :T0 + 4]))
+    q4 = np.stack([S.make_q(w, batch=B, step=i) for i in range(4)], axis=1)
+    pos = np.tile(np.arange(T0, T0 + 4, dtype=np.int32), (B, 1))
+    a.decode_attention_multi(P.gpu(q4), P.gpu(pos))            # the verification pass
+    assert int(a.export_sinks()["count"].max()) == 3
+    a.truncate([T0 + n for n in accepted])
+    assert a.lengths == [T0 + n for n in accepted]
+    # the reference cache: prefix + accepted drafts only
+    n_max = max(accepted)
+    kk = np.zeros((B, T0 + n_max, 8, 128), np.float16)
+    vv = np.zeros_like(kk)
+    mm = np.zeros((B, T0 + n_max), np.uint8)
+    for s_ in range(B):
+        n = T0 + accepted[s_]
+        kk[s_, :n], vv[s_, :n], mm[s_, :n] = k[s_, :n], v[s_, :n], mask[s_, :n]
+    if uniform:
+        b.quantize_append(P.gpu(kk), P.gpu(vv), P.gpu(mm))
+    else:
+        b.quantize_append_ragged(P.gpu(kk), P.gpu(vv), [T0 + n for n in accepted], P.gpu(mm))
+    # both go on decoding with three fresh tokens
+    for s_ in range(3):
+        t = T0 + 4 + s_
+        q = P.gpu(S.make_q(w, batch=B, step=10 + s_))
+        oa = a.decode_step(P.gpu(k[:, t:t + 1]), P.gpu(v[:, t:t + 1]), q)
+        ob = b.decode_step(P.gpu(k[:, t:t + 1]), P.gpu(v[:, t:t + 1]), q)
+        torch.cuda.synchronize()
+        assert torch.equal(oa, ob), f"step {s_}"
+    assert a.lengths == b.lengths
+    ea, eb = a.export_codes(), b.export_codes()
+    sa, sb = a.export_sinks(), b.export_sinks()
+    torch.cuda.synchronize()
+    assert torch.equal(sa["count"], sb["count"]) and int(sa["count"].max()) == 2
+    for s_ in range(B):
+        n = a.lengths[s_]
+        for name in ea:
+            assert torch.equal(ea[name][s_, :n], eb[name][s_, :n]), (name, s_)
+        c = int(sa["count"][s_])
+        for name in ("pos", "k", "v"):
+            assert torch.equal(sa[name][s_, :c], sb[name][s_, :c]), (name, s_)
+    with pytest.raises(R.RkvError):
+        a.truncate([a.lengths[0] + 1, 0])                      # cannot grow
+    a.truncate(0)
+    assert a.lengths == [0, 0]
