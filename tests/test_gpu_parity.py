@@ -673,11 +673,24 @@ def test_fp8_metadata_saturation_and_clamps():
     v[0, 4, 0] = np.float16(2.3)                                               # constant block
     v[0, 5, 1] = np.float16(0.0)
     k = rng.standard_normal((1, T, 4, 128)).astype(np.float16)
+    k[0, 6] = (k[0, 6].astype(np.float32) * 2.0 ** -11).astype(np.float16)      # a token whose key blocks get subnormal FP8 scales
+    k[0, 7] = (k[0, 7].astype(np.float32) * 300.0).astype(np.float16)          # ... and one whose scales saturate
     cache = R.RkvCache(cfg)
     oc = O.cache_new(P.oracle_cfg(cfg))
-    cache.quantize_append(P.gpu(k), P.gpu(v))
-    O.quantize_append(oc, k, v)
+    q = rng.standard_normal((1, 4, 128)).astype(np.float16)
+    # first without the saturated key token, whose huge scores would take all of the softmax's mass
+    cache.quantize_append(P.gpu(k[:, :7]), P.gpu(v[:, :7]))
+    O.quantize_append(oc, k[:, :7], v[:, :7])
+    oc7 = oracle_from_export(oc, P.export_numpy(cache))
+    for path in (1, 2):
+        cache.set_decode_path(path)
+        check_decode(cache, oc7, q, tag=f"special blocks, 7 tokens, path={path}")
+    cache.quantize_append(P.gpu(k[:, 7:]), P.gpu(v[:, 7:]))
+    O.quantize_append(oc, k[:, 7:], v[:, 7:])
     g = P.export_numpy(cache)
+    P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"], "special blocks K",
+                    rot_span=512, meta_format=1)
+    assert oc.k_scale[0, 6].max() < 2.0 ** -6 and oc.k_scale[0, 7].max() == 448.0
     assert np.array_equal(g["v_scale"], oc.v_scale)
     assert np.array_equal(g["v_zero"], oc.v_zero)
     P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], "special blocks V",
@@ -687,6 +700,11 @@ def test_fp8_metadata_saturation_and_clamps():
     assert np.all(gc[0, 4, 0] == 0) and np.all(gc[0, 5, 1] == 0)
     assert oc.v_scale[0, 0, 0] == 448.0 and oc.v_zero[0, 1, 1] == -128 and oc.v_zero[0, 2, 2] == 127
     assert oc.v_scale[0, 3, 3] == 2.0 ** -9
+    # the read half on these codes: subnormal and saturated scales, clamped zero-points, both kernels
+    oc_g = oracle_from_export(oc, g)
+    for path in (1, 2):
+        cache.set_decode_path(path)
+        check_decode(cache, oc_g, q, tag=f"special blocks path={path}")
 
 
 def test_shared_scratch_reused_across_caches():
