@@ -25,6 +25,12 @@ MUTANTS = [
      "q = np.floor(blocks / scale[..., None] + 0.5) + zero[..., None]"),
     ("Eq. 9 zero-point with the wrong sign", "zero = np.clip(-np.rint(mn / scale), zlo, zhi)", "zero = np.clip(np.rint(mn / scale), zlo, zhi)"),
     ("Eq. 8 divides the range by 2^bits", "qmax = float(2 ** bits - 1)", "qmax = float(2 ** bits)"),
+    ("Eq. 8 with the step count of 2-bit codes whatever the width", "qmax = float(2 ** bits - 1)", "qmax = 3.0"),
+    ("the cache quantizes with 2-bit codes whatever the configuration",
+     "kc, ks, kz = quantize(z, cfg.quant_group, cfg.bits, cfg.meta_format)", "kc, ks, kz = quantize(z, cfg.quant_group, 2, cfg.meta_format)"),
+    ("the read half dequantizes keys in blocks of 128 whatever the configuration",
+     "zq = dequantize(cache.k_codes, cache.k_scale, cache.k_zero, cfg.quant_group)", "zq = dequantize(cache.k_codes, cache.k_scale, cache.k_zero, 128)"),
+    ("average bits without the metadata's dependence on the group", "/ cfg.quant_group", "/ 128.0"),
     ("scale not rounded to the stored fp16 number", "scale = np.minimum(_to_f16((mx - mn) / qmax), F16_MAX)        # Eq. 8, stored in fp16",
      "scale = np.minimum((mx - mn) / qmax, F16_MAX)"),
     ("Eq. 7 without the scale on the zero-point", "x = np.asarray(scale)[..., None] * (blocks - np.asarray(zero)[..., None])",

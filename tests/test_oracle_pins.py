@@ -209,6 +209,108 @@ def test_average_bits_matches_paper():
     assert bits / c.size == float(val)
 
 
+# ----------------------------------------------------------------------------- 3- and 4-bit codes, groups of 64 and 32 (Sec. 5.1; Tables tab:ablation, tab:quantgrani)
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_wider_codes_nearest_level_bruteforce(bits):
+    """Every element takes a nearest of the 2^bits reconstruction levels; the block's minimum and
+    maximum take the first and the last code."""
+    rng = np.random.default_rng(70 + bits)
+    top = 2 ** bits - 1
+    for trial in range(200):
+        g = int(rng.choice([4, 8, 32]))
+        x = rng.standard_normal((1, g)) * rng.uniform(0.1, 30) + rng.uniform(-5, 5)
+        c, s, z = O.quantize(x, group=g, bits=bits)
+        levels = s[0, 0] * (np.arange(top + 1) - z[0, 0])
+        dist = np.abs(levels[None, :] - x[0][:, None])
+        assert np.all(dist[np.arange(g), c[0]] <= dist.min(axis=1) + 1e-12)
+        assert c[0, np.argmin(x[0])] == 0 and c[0, np.argmax(x[0])] == top
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_wider_codes_reproduce_grid_patterns(bits):
+    """Code patterns placed exactly on a grid with 2^bits levels come back unchanged, with the
+    grid's own step and zero-point as metadata."""
+    rng = np.random.default_rng(80 + bits)
+    top = 2 ** bits - 1
+    s, z = 0.375, 5.0
+    for trial in range(300):
+        pat = rng.integers(0, top + 1, size=8)
+        pat[rng.integers(0, 4)] = 0
+        pat[4 + rng.integers(0, 4)] = top
+        x = s * (pat.astype(np.float64)[None] - z)
+        c, sc, ze = O.quantize(x, group=8, bits=bits)
+        assert sc[0, 0] == s and ze[0, 0] == z
+        assert np.array_equal(c[0], pat)
+        assert np.array_equal(O.dequantize(c, sc, ze, group=8), x)
+
+
+@pytest.mark.parametrize("bits,group", [(2, 64), (2, 32), (3, 128), (3, 64), (4, 128), (4, 32)])
+def test_wider_codes_and_smaller_groups_error_law(bits, group):
+    """Half-step bound per element with the block's own stored step = fp16(range / (2^bits - 1));
+    on uniformly distributed data the rounding error is uniform over one step, so its mean square
+    is step^2 / 12."""
+    rng = np.random.default_rng(90 + bits + group)
+    top = 2 ** bits - 1
+    # a random offset per block, so that the grid (anchored at an integer zero-point) sits anywhere
+    # relative to the block's minimum
+    x = (rng.uniform(-1.0, 1.0, size=(256, 1024)) + np.repeat(rng.uniform(-3, 3, size=(256, 1024 // group)), group, axis=-1))
+    x = x * np.exp(rng.uniform(-2, 2, size=(256, 1)))
+    c, s, z = O.quantize(x, group=group, bits=bits)
+    assert s.shape == (256, 1024 // group) and z.shape == s.shape
+    assert c.max() == top and c.min() == 0
+    xh = O.dequantize(c, s, z, group=group)
+    step = np.repeat(s, group, axis=-1)
+    # the stored step is the exact one within 2^-11; over 2^bits - 1 steps that moves the top level
+    assert np.all(np.abs(x - xh) <= step * (0.5 + top * 2.0 ** -11 + 1e-12))
+    blocks = x.reshape(256, 1024 // group, group)
+    raw = (blocks.max(-1) - blocks.min(-1)) / top
+    assert np.all(np.abs(s - raw) <= raw * 2.0 ** -11)
+    ratio = np.mean(((x - xh) / step) ** 2) * 12.0
+    assert 0.96 <= ratio <= 1.04
+
+
+def test_average_bits_of_the_wider_settings():
+    """Codes plus 16 + 16 bits of metadata per block: 4.25 and 3.25 bits at group 128, 2.5 and 3
+    bits for 2-bit codes at groups 64 and 32 (half of it with 8 + 8 bits of metadata)."""
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=32)
+    want = {(4, 128, 0): 4.25, (3, 128, 0): 3.25, (2, 64, 0): 2.5, (2, 32, 0): 3.0, (4, 32, 0): 5.0,
+            (4, 128, 1): 4.125, (2, 64, 1): 2.25, (3, 32, 1): 3.5}
+    for (bits, group, mf), val in want.items():
+        cfg = O.OracleConfig(bits=bits, quant_group=group, meta_format=mf, **base)
+        assert O.average_bits(cfg) == val
+        c, s, z = O.quantize(np.random.default_rng(3).standard_normal((2, 4096)), group=group, bits=bits, meta_format=mf)
+        assert (c.size * bits + (s.size + z.size) * (8 if mf else 16)) / c.size == val
+
+
+@pytest.mark.parametrize("bits,group", [(4, 128), (3, 64), (2, 32)])
+def test_cache_with_wider_codes_and_smaller_groups(bits, group):
+    """The cache carries bits and group through the write and the read half: metadata shapes,
+    code range, half-step bound in the rotated and reordered basis, the read half equal to textbook
+    attention over the reconstructed cache, and reconstructions of keys and values closer to the
+    originals than the 2-bit, group-128 cache's."""
+    rng = np.random.default_rng(95)
+    k = rng.standard_normal((2, 48, 4, 128)).astype(np.float16)
+    k[..., 7] *= 12.0                                              # an outlier channel in every head
+    v = rng.standard_normal((2, 48, 4, 128)).astype(np.float16)
+    q = rng.standard_normal((2, 4, 128)).astype(np.float16)
+    outs = {}
+    for name, (b_, g_) in {"base": (2, 128), "this": (bits, group)}.items():
+        cfg = O.OracleConfig(batch=2, n_q_heads=4, n_kv_heads=4, rot_heads=2, max_sinks=0, bits=b_, quant_group=g_)
+        c = O.cache_new(cfg)
+        O.quantize_append(c, k, v)
+        assert c.k_scale.shape == (2, 48, 512 // g_) and c.v_zero.shape == (2, 48, 512 // g_)
+        assert c.k_codes.max() == 2 ** b_ - 1 and c.v_codes.max() == 2 ** b_ - 1
+        zq = O.dequantize(c.k_codes, c.k_scale, c.k_zero, g_)
+        assert np.all(np.abs(zq - c.k_rot) <= np.repeat(c.k_scale, g_, axis=-1) * (0.5 + (2 ** b_ - 1) * 2.0 ** -11 + 1e-12))
+        k_hat, v_hat = O.dequantize_cache(c)
+        out, _ = O.decode_attention(c, q)
+        ref = _textbook_attention(q.astype(np.float64), k_hat, v_hat, np.array([47, 47]), 10000.0, 1)
+        assert np.abs(out - ref).max() <= 1e-9
+        outs[name] = (np.mean((k_hat - k.astype(np.float64)) ** 2), np.mean((v_hat - v.astype(np.float64)) ** 2))
+    assert outs["this"][0] < 0.8 * outs["base"][0] and outs["this"][1] < 0.8 * outs["base"][1]
+
+
 # ----------------------------------------------------------------------------- FP8 scale + INT8 zero (Sec. 5.1, Table tab:ablation last row)
 
 def test_e4m3_table_matches_the_library_format():
