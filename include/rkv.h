@@ -52,8 +52,12 @@ typedef struct rkv_config {
   int32_t max_sinks;    /* fp16 sink rows kept per sequence (0..64)                              */
   int32_t rot_heads;    /* consecutive KV heads rotated together (Sec. 4.2): 1, 2, 4 or 8;       */
                         /* must divide n_kv_heads                                                */
-  int32_t quant_group;  /* 128 (Sec. 5.1 quantization settings)                                  */
-  int32_t bits;         /* 2                                                                     */
+  int32_t quant_group;  /* channels per quantization block: 128 (Sec. 5.1 quantization settings), */
+                        /* 64 or 32 (Table tab:quantgrani)                                       */
+  int32_t bits;         /* bits per code: 2 (the headline setting), 3 or 4 (Table tab:ablation). */
+                        /* Settings other than (128, 2) run on the general kernels only, need    */
+                        /* keys_rotated = 0, and have no rkv_quantize_append_ragged,             */
+                        /* rkv_decode_attention_multi or one-kernel rkv_decode_step              */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
                         /* printed sorts the whole row)                                           */
@@ -239,8 +243,10 @@ int rkv_dequantize(rkv_cache* cache, float* dev_k_hat, float* dev_v_hat, void* s
 
 /* The logical code array in canonical bytes, independent of the physical layout:
  *   dev_k_codes, dev_v_codes  [batch][length][E/4] uint8: byte j of a token holds reordered
- *                             channels 4j..4j+3, channel 4j+r in bits [2r, 2r+1]
- *   dev_k_scale, dev_k_zero, dev_v_scale, dev_v_zero   [batch][length][E/128] fp32
+ *                             channels 4j..4j+3, channel 4j+r in bits [2r, 2r+1]; with 3- or
+ *                             4-bit codes [batch][length][E/2]: byte j holds channel 2j in its
+ *                             low and channel 2j+1 in its high nibble
+ *   dev_k_scale, dev_k_zero, dev_v_scale, dev_v_zero   [batch][length][E/quant_group] fp32
  * Any pointer may be NULL. */
 int rkv_export_codes(rkv_cache* cache, uint8_t* dev_k_codes, float* dev_k_scale, float* dev_k_zero,
                      uint8_t* dev_v_codes, float* dev_v_scale, float* dev_v_zero, void* stream);
@@ -259,7 +265,7 @@ int rkv_export_sinks(rkv_cache* cache, int32_t* dev_count, int32_t* dev_pos, voi
 /* Where the physical layout keeps a code (host-only arithmetic, no device access): the index of
  * the 32-bit word inside the K-code (is_v = 0) or V-code (is_v = 1) region of a cache built from
  * cfg, and the bit position of the 2-bit code of sequence b, token t, ROTATED channel c (0..E-1,
- * i.e. before the reorder).  Also returns the number of words of the region in *n_words (may be
+ * i.e. before the reorder; of the low two bits of a wider code).  Also returns the number of words of the region in *n_words (may be
  * NULL).  Used to test that the layout is a bijection. */
 int rkv_layout_locate(const rkv_config* cfg, int32_t is_v, int32_t b, int32_t t, int32_t c,
                       size_t* word_index, int32_t* bit_shift, size_t* n_words);

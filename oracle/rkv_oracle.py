@@ -214,17 +214,24 @@ def dequantize(codes: np.ndarray, scale: np.ndarray, zero: np.ndarray, group: in
 
 def pack_canonical(codes: np.ndarray, bits: int = 2) -> np.ndarray:
     """Canonical byte image of a logical code array: byte k holds codes 4k..4k+3, code 4k+r in
-    bits [2r, 2r+1].  (The packing is not fixed by the paper; this is the reference image that a
-    physical layout must be a documented bijection of.)"""
-    if bits != 2:
-        raise ValueError("canonical packing is defined for 2-bit codes")
+    bits [2r, 2r+1]; 3- and 4-bit codes take a nibble each, byte k holding code 2k in its low and
+    code 2k+1 in its high nibble.  (The packing is not fixed by the paper; this is the reference
+    image that a physical layout must be a documented bijection of.)"""
     c = np.asarray(codes, dtype=np.uint8)
+    if bits in (3, 4):
+        c2 = c.reshape(c.shape[:-1] + (c.shape[-1] // 2, 2))
+        return (c2[..., 0] | (c2[..., 1] << 4)).astype(np.uint8)
+    if bits != 2:
+        raise ValueError("canonical packing is defined for 2-, 3- and 4-bit codes")
     c4 = c.reshape(c.shape[:-1] + (c.shape[-1] // 4, 4))
     return (c4[..., 0] | (c4[..., 1] << 2) | (c4[..., 2] << 4) | (c4[..., 3] << 6)).astype(np.uint8)
 
 
-def unpack_canonical(packed: np.ndarray) -> np.ndarray:
+def unpack_canonical(packed: np.ndarray, bits: int = 2) -> np.ndarray:
     p = np.asarray(packed, dtype=np.uint8)
+    if bits in (3, 4):
+        out = np.stack([p & 15, p >> 4], axis=-1)
+        return out.reshape(p.shape[:-1] + (p.shape[-1] * 2,)).astype(np.uint8)
     out = np.stack([(p >> (2 * r)) & 3 for r in range(4)], axis=-1)
     return out.reshape(p.shape[:-1] + (p.shape[-1] * 4,)).astype(np.uint8)
 

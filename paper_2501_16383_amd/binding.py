@@ -374,9 +374,9 @@ class RkvCache:
     def export_codes(self):
         import torch
         cfg, T, dev = self.cfg, self.length, self.device
-        kc = torch.empty((cfg.batch, T, cfg.E // 4), dtype=torch.uint8, device=dev)
+        kc = torch.empty((cfg.batch, T, cfg.E // (4 if cfg.bits == 2 else 2)), dtype=torch.uint8, device=dev)
         vc = torch.empty_like(kc)
-        meta = [torch.empty((cfg.batch, T, cfg.E // 128), dtype=torch.float32, device=dev) for _ in range(4)]
+        meta = [torch.empty((cfg.batch, T, cfg.E // cfg.quant_group), dtype=torch.float32, device=dev) for _ in range(4)]
         _check(self.lib.rkv_export_codes(self.handle, _ptr(kc), _ptr(meta[0]), _ptr(meta[1]), _ptr(vc), _ptr(meta[2]),
                                          _ptr(meta[3]), _stream()), "rkv_export_codes")
         return dict(k_codes=kc, k_scale=meta[0], k_zero=meta[1], v_codes=vc, v_scale=meta[2], v_zero=meta[3])

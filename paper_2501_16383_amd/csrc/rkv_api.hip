@@ -13,7 +13,10 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static int check_config(const rkv_config* c, bool need_capacity) {
   if (!c) return RKV_EINVAL;
-  if (c->head_dim != RKV_D || c->quant_group != 128 || c->bits != 2) return RKV_EINVAL;
+  if (c->head_dim != RKV_D) return RKV_EINVAL;
+  if (c->quant_group != 128 && c->quant_group != 64 && c->quant_group != 32) return RKV_EINVAL;
+  if (c->bits < 2 || c->bits > 4) return RKV_EINVAL;
+  if ((c->bits != 2 || c->quant_group != 128) && c->keys_rotated) return RKV_EINVAL;
   if (c->clip_ratio != 1.0f) return RKV_EINVAL;
   if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads != 0) return RKV_EINVAL;
   if (c->n_q_heads / c->n_kv_heads > 8) return RKV_EINVAL;
@@ -36,13 +39,13 @@ static int check_config(const rkv_config* c, bool need_capacity) {
 }
 
 struct Offsets {
-  size_t kc, km, vc, vm, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, total;
+  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, total;
   int Tpad;
 };
 
 static Offsets plan(const rkv_config* c) {
   Offsets o;
-  const size_t B = c->batch, E = (size_t)c->n_kv_heads * RKV_D, NG = E / 128;
+  const size_t B = c->batch, E = (size_t)c->n_kv_heads * RKV_D, NG = E / c->quant_group, HB = c->bits - 2;
   o.Tpad = (c->max_tokens + 255) & ~255;
   const size_t T = o.Tpad, S = c->max_sinks > 0 ? c->max_sinks : 1;
   const size_t MB = c->meta_format == 1 ? 2 : 4;           // bytes per (token, block) metadata entry
@@ -51,6 +54,8 @@ static Offsets plan(const rkv_config* c) {
   o.km = p; p = align256(p + B * T * NG * MB);
   o.vc = p; p = align256(p + B * T * E / 4);
   o.vm = p; p = align256(p + B * T * NG * MB);
+  o.kh = p; p = align256(p + B * T * E * HB / 8);
+  o.vh = p; p = align256(p + B * T * E * HB / 8);
   o.sk = p; p = align256(p + B * S * E * 2);
   o.sv = p; p = align256(p + B * S * E * 2);
   o.spos = p; p = align256(p + B * S * 4);
@@ -120,6 +125,12 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.km = (uint32_t*)(c->base + o.km);
   v.vc = (uint32_t*)(c->base + o.vc);
   v.vm = (uint32_t*)(c->base + o.vm);
+  v.hb = cfg->bits - 2;
+  v.kh = v.hb ? (uint32_t*)(c->base + o.kh) : nullptr;
+  v.vh = v.hb ? (uint32_t*)(c->base + o.vh) : nullptr;
+  v.qg = cfg->quant_group;
+  v.gm = cfg->rot_heads * (128 / cfg->quant_group);
+  c->wide = (cfg->bits != 2 || cfg->quant_group != 128) ? 1 : 0;
   v.sink_k = (__half*)(c->base + o.sk);
   v.sink_v = (__half*)(c->base + o.sv);
   v.sink_pos = (int*)(c->base + o.spos);
@@ -136,7 +147,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.n = cfg->rot_heads * RKV_D;
   v.E = cfg->n_kv_heads * RKV_D;
   v.NRG = cfg->n_kv_heads / cfg->rot_heads;
-  v.NG = v.E / 128;
+  v.NG = v.E / cfg->quant_group;
   v.Tpad = o.Tpad;
   v.max_sinks = cfg->max_sinks;
   v.len = 0;
@@ -237,8 +248,8 @@ RKV_EXPORT int rkv_set_perm(rkv_cache* cache, const int32_t* dev_perm, void* str
   }
   int aligned = 1;
   for (int c = 0; c < E; ++c) {
-    gid[c] = inv[c] / 128;
-    if (gid[c] != c / 128) aligned = 0;
+    gid[c] = inv[c] / cache->cfg.quant_group;
+    if (inv[c] / 128 != c / 128) aligned = 0;
   }
   RKV_HIP_CHECK(hipMemcpyAsync(cache->v.perm, p.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipMemcpyAsync(cache->v.pinv, inv.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));

@@ -407,7 +407,7 @@ __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* _
 
 bool rkv_append_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
+  return c->blocks_aligned && !c->wide && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 
 // max_slabs: most 32-token slabs any sequence's new tokens touch, or 0 to work it out for n_new

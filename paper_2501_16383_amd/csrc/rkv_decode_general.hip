@@ -53,9 +53,10 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
   const int nq = rep * g;                       // query heads served by this rotation group
   float* s_q = sm;                              // [nq][128]
   float* s_p = s_q + nq * RKV_D;                // [nq][GEN_CHUNK]
-  float* s_vs = s_p + nq * GEN_CHUNK;           // [g][GEN_CHUNK]
-  float* s_vz = s_vs + g * GEN_CHUNK;           // [g][GEN_CHUNK]
-  float* s_m = s_vz + g * GEN_CHUNK;            // [nq]
+  const int gm = v.gm;                          // quantization blocks of the group's n channels
+  float* s_vs = s_p + nq * GEN_CHUNK;           // [gm][GEN_CHUNK]
+  float* s_vz = s_vs + gm * GEN_CHUNK;          // [gm][GEN_CHUNK]
+  float* s_m = s_vz + gm * GEN_CHUNK;           // [nq]
   float* s_l = s_m + nq;                        // [nq]
   __shared__ int s_sink[64];
 
@@ -87,14 +88,19 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
     mi0[i] = rkv_meta_index(v, b, 0, v.gid[rg * n + c]);
   }
   const int tok_stride = g == 1 ? 2 : 4;                       // dwords between consecutive tokens of a tile
+  // bits above the low two (wider codes): those of a lane's PL channels are PL * hb consecutive
+  // bits of the token's row in the high-bit plane, inside one dword
+  const int hb = v.hb, hbit = (rg * n + PL * lane) * hb;
+  const uint32_t hmask = (1u << hb) - 1u;
   for (int t = t0 + wave; t < t1; t += 4) {
     float x[PL];
     const uint32_t w = v.kc[rkv_k_tilebase(v, b, rg, t >> 4) + dw_off + (t & 15) * tok_stride];
+    const uint32_t hw = hb ? v.kh[((size_t)b * v.Tpad + t) * (size_t)(v.E * hb / 32) + (hbit >> 5)] >> (hbit & 31) : 0u;
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
       float sc, zero;
-      rkv_load_meta(v, v.km, mi0[i] + (size_t)t * g, sc, zero);
-      x[i] = sc * ((float)((w >> sh[i]) & 3u) - zero);          // Eq. 7
+      rkv_load_meta(v, v.km, mi0[i] + (size_t)t * gm, sc, zero);
+      x[i] = sc * ((float)(((w >> sh[i]) & 3u) | (((hw >> (i * hb)) & hmask) << 2)) - zero);          // Eq. 7
     }
     fwht_lanes_d<PL>(x, lane, 6);                               // inverse rotation (H is its own inverse)
     float y[PL];
@@ -124,10 +130,10 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
       if ((lane & (lanes_per_head - 1)) == 0) s_p[(hh * rep + r) * GEN_CHUNK + (t - t0)] = sink ? -INFINITY : d;
     }
   }
-  for (int i = tid; i < g * GEN_CHUNK; i += 256) {
+  for (int i = tid; i < gm * GEN_CHUNK; i += 256) {
     const int h = i / GEN_CHUNK, tt = i - h * GEN_CHUNK;
     float sc = 0.f, zero = 0.f;
-    if (t0 + tt < t1) rkv_load_meta(v, v.vm, rkv_meta_index(v, b, t0 + tt, rg * g + h), sc, zero);
+    if (t0 + tt < t1) rkv_load_meta(v, v.vm, rkv_meta_index(v, b, t0 + tt, rg * gm + h), sc, zero);
     s_vs[i] = sc;
     s_vz[i] = zero;
   }
@@ -156,7 +162,7 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
 
   // ---- phase 3: acc[c] = sum_t p_t * s_t * (code - zero)   (Eq. 7 folded into the weights)
   for (int c = tid; c < n; c += 256) {
-    const int h = c >> 7;
+    const int h = c >> 7, blk = c / v.qg;
     float acc[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) acc[r] = 0.f;
@@ -164,7 +170,8 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
       int sh;
       const uint32_t w = v.vc[rkv_v_dword(v, b, rg, t0 + tt, c, sh)];
       for (int k = 0; k < 16 && tt + k < t1 - t0; ++k) {
-        const float val = s_vs[h * GEN_CHUNK + tt + k] * ((float)((w >> rkv_v_shift(k)) & 3u) - s_vz[h * GEN_CHUNK + tt + k]);
+        const uint32_t code = ((w >> rkv_v_shift(k)) & 3u) | rkv_hi_get(v, v.vh, b, t0 + tt + k, rg * n + c);
+        const float val = s_vs[blk * GEN_CHUNK + tt + k] * ((float)code - s_vz[blk * GEN_CHUNK + tt + k]);
 #pragma unroll
         for (int r = 0; r < 8; ++r)
           if (r < rep) acc[r] += s_p[(h * rep + r) * GEN_CHUNK + tt + k] * val;
@@ -354,7 +361,7 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
   rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, 1, 1, s);
   const int rep = v.Hq / v.Hkv, nq = rep * v.g;
-  const size_t lds = ((size_t)nq * RKV_D + (size_t)nq * GEN_CHUNK + 2 * (size_t)v.g * GEN_CHUNK + 2 * nq) * 4;
+  const size_t lds = ((size_t)nq * RKV_D + (size_t)nq * GEN_CHUNK + 2 * (size_t)v.gm * GEN_CHUNK + 2 * nq) * 4;
   dim3 grid(nch, v.NRG, v.B);
   void (*fn)(RkvView, const float*, float*, int) = nullptr;
   switch (v.n / 64) {

@@ -623,7 +623,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && (v.g == 2 || v.g == 4) && v.rope_style == 0;
+  return c->blocks_aligned && !c->wide && (v.g == 2 || v.g == 4) && v.rope_style == 0;
 }
 
 template <bool MULTI>

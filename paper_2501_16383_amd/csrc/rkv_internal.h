@@ -23,6 +23,15 @@
 //   sinks     fp16 rows [batch][max_sinks][E] for K and V, positions, counts.
 //   tables    perm, inverse perm, gid (int32 [E] each), RoPE angles float2 [Tpad][64], the
 //             Hadamard operand image of the matrix-core kernel.
+//
+// Codes wider than 2 bits and quantization groups smaller than 128 (Sec. 5.1, the settings of
+// Tables tab:ablation and tab:quantgrani) keep all of the above for the low two bits of every code
+// and add
+//   K high, V high   [batch][Tpad] rows of E * (bits - 2) / 32 dwords: the remaining 1 or 2 bits
+//             of rotated channel (K) or channel (V) c of the layer at bit (bits - 2) * c of the row;
+//   K meta, V meta   128 / quant_group entries in place of each one (gid then counts blocks of
+//             quant_group reordered positions).
+// Those settings run on the general kernels only.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -50,7 +59,12 @@ struct RkvView {
   const int* lens;   // per-sequence lengths [B] once the sequences differ in length, else null (all have `len` tokens)
   const int* cstart; // with `lens`: cstart[b] = 256-token chunks of the sequences before b, cstart[B] = all of them
   const int* nnew;   // during an append with per-sequence token counts: those counts [B], else null
-  int meta8;         // 1: km / vm hold, per (token, rotation group), g FP8 E4M3 scales followed by g 8-bit zero-points (value + 128)
+  int meta8;         // 1: km / vm hold, per (token, rotation group), gm FP8 E4M3 scales followed by gm 8-bit zero-points (value + 128)
+  uint32_t* kh;      // high bits of the codes (see the layout above), null with 2-bit codes
+  uint32_t* vh;
+  int qg;            // quantization group: 128, 64 or 32 channels
+  int gm;            // metadata entries per (token, rotation group): g * 128 / qg
+  int hb;            // bits per code above the low two: 0, 1 or 2
   float theta;
 };
 
@@ -68,7 +82,8 @@ struct rkv_cache {
   size_t bytes;
   char* base;
   size_t off_tables;      // everything before this offset is cleared by reset
-  int blocks_aligned;     // 1 if gid[c] == c/128 for every rotated channel
+  int blocks_aligned;     // 1 if the reorder keeps every rotated channel in its block of 128
+  int wide;               // 1 with codes wider than 2 bits or groups smaller than 128: general kernels only
   int decode_path;
   int n_cu;               // compute units of the device the cache lives on
   hipEvent_t ev_start, ev_stop;   // optional measurement hook around the main kernels
@@ -108,10 +123,21 @@ __host__ __device__ inline size_t rkv_v_dword(const RkvView& v, int b, int rg, i
   return rkv_v_slabbase(v, b, rg, t >> 5) + rkv_v_off(v.g, c, t & 31);
 }
 
-// meta entry of global quantization block G (0..E/128) of token t
+// meta entry of global quantization block G (0..E/qg) of token t
 __host__ __device__ inline size_t rkv_meta_index(const RkvView& v, int b, int t, int G) {
-  int rg = G / v.g, j = G - rg * v.g;
-  return ((size_t)(b * v.NRG + rg) * (size_t)v.Tpad + t) * v.g + j;
+  int rg = G / v.gm, j = G - rg * v.gm;
+  return ((size_t)(b * v.NRG + rg) * (size_t)v.Tpad + t) * v.gm + j;
+}
+// High bits of the code of channel ch (0..E) of token t: position in a high-bit plane
+__host__ __device__ inline size_t rkv_hi_dword(const RkvView& v, int b, int t, int ch, int& shift) {
+  shift = (ch * v.hb) & 31;
+  return ((size_t)b * v.Tpad + t) * (size_t)(v.E * v.hb / 32) + ((ch * v.hb) >> 5);
+}
+__device__ inline uint32_t rkv_hi_get(const RkvView& v, const uint32_t* plane, int b, int t, int ch) {
+  if (v.hb == 0) return 0u;
+  int sh;
+  const uint32_t w = plane[rkv_hi_dword(v, b, t, ch, sh)];
+  return ((w >> sh) & ((1u << v.hb) - 1u)) << 2;
 }
 
 __device__ inline uint32_t rkv_pack_meta(float scale, float zero) {
@@ -143,23 +169,23 @@ __device__ inline float rkv_e4m3_round_up(float x) {
   return __uint_as_float((__float_as_uint(x) + 0x000fffffu) & 0xfff00000u);   // three mantissa bits, carry into the exponent
 }
 // Entry idx (rkv_meta_index) of a metadata array in the cache's format.  The 8-bit format keeps,
-// for each (token, rotation group), the g scale bytes first and the g zero-point bytes after them
+// for each (token, rotation group), the gm scale bytes first and the gm zero-point bytes after them
 // (the matrix-core decode kernel converts either kind four at a time); a zero-point z in -128..127
 // is stored as the unsigned byte z + 128.
 __device__ inline void rkv_load_meta(const RkvView& v, const uint32_t* m, size_t idx, float& scale, float& zero) {
   if (v.meta8) {
-    const uint8_t* p = reinterpret_cast<const uint8_t*>(m) + 2 * (idx - idx % v.g) + idx % v.g;
+    const uint8_t* p = reinterpret_cast<const uint8_t*>(m) + 2 * (idx - idx % v.gm) + idx % v.gm;
     scale = rkv_e4m3_decode(p[0]);
-    zero = (float)p[v.g] - 128.0f;
+    zero = (float)p[v.gm] - 128.0f;
   } else {
     rkv_unpack_meta(m[idx], scale, zero);
   }
 }
 __device__ inline void rkv_store_meta(const RkvView& v, uint32_t* m, size_t idx, float scale, float zero) {
   if (v.meta8) {
-    uint8_t* p = reinterpret_cast<uint8_t*>(m) + 2 * (idx - idx % v.g) + idx % v.g;
+    uint8_t* p = reinterpret_cast<uint8_t*>(m) + 2 * (idx - idx % v.gm) + idx % v.gm;
     p[0] = (uint8_t)rkv_e4m3_encode(scale);
-    p[v.g] = (uint8_t)((int)zero + 128);
+    p[v.gm] = (uint8_t)((int)zero + 128);
   } else {
     m[idx] = rkv_pack_meta(scale, zero);
   }

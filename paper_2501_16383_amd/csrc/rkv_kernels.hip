@@ -53,7 +53,7 @@ __global__ void k_init_small(RkvView v, int tables) {
   if (tables && i < v.E) {
     v.perm[i] = i;
     v.pinv[i] = i;
-    v.gid[i] = i >> 7;
+    v.gid[i] = i / v.qg;
   }
 }
 
@@ -202,7 +202,9 @@ __global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restri
 //   closed under both the rotation and the reorder: max(perm_span, n) channels.  Each wave takes one
 //   token at a time: rotate in registers + lane exchanges (Sec. 4.2), scatter to reordered
 //   positions in LDS (Sec. 4.1), reduce min/max per block of 128, Eq. 6-9, and OR the codes into LDS
-//   images of the physical tile, which are then written with whole-dword stores.
+//   images of the physical tile, which are then written with whole-dword stores.  With codes wider
+//   than 2 bits the images take the low two bits and each wave collects the remaining bits of its
+//   token in an image of that token's piece of the high-bit rows, written after the token is done.
 // ---------------------------------------------------------------------------------------------
 
 template <int PL>
@@ -212,6 +214,11 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
   float* zbuf = reinterpret_cast<float*>(smem);            // [4][U]
   uint32_t* imgK = smem + 4 * U;                            // [U]  (16 tokens x U codes)
   uint32_t* imgV = imgK + U;                                // [U]  (one dword per channel)
+  const int hb = v.hb, hdw = U * hb / 32;                   // dwords of a token's high bits within the unit
+  uint32_t* imgKh = imgV + U;                               // [4 waves][hdw]
+  uint32_t* imgVh = imgKh + 4 * hdw;                        // [4 waves][hdw]
+  const float qmax = (float)((4 << hb) - 1);
+  const int blk_lanes = v.qg >> 3;                          // lanes (8 values each) of one quantization block
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tile = tile0 + blockIdx.x, unit = blockIdx.y, b = blockIdx.z;
   const int ubase = unit * U, n = v.n, g = v.g;
@@ -219,7 +226,7 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
   const int t_lo = v.len, t_hi = v.len + n_new;
   const float rs = rsqrtf((float)n);
 
-  for (int i = tid; i < 2 * U; i += 256) imgK[i] = 0;   // imgK and imgV are adjacent
+  for (int i = tid; i < 2 * U + 8 * hdw; i += 256) imgK[i] = 0;   // imgK, imgV and the high-bit images are adjacent
   __syncthreads();
 
   // old V dwords of a partly filled tile are fetched now and merged at the end
@@ -273,24 +280,24 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
             mx = fmaxf(mx, z[i]);
           }
         }
-#pragma unroll
-        for (int s = 1; s < 16; s <<= 1) {
+        for (int s = 1; s < blk_lanes; s <<= 1) {
           mn = fminf(mn, __shfl_xor(mn, s));
           mx = fmaxf(mx, __shfl_xor(mx, s));
         }
         if (on) {
           float sc, zero, inv;
-          quant_params(mn, mx, sc, zero, inv, v.meta8);
+          quant_params(mn, mx, sc, zero, inv, v.meta8, qmax);
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
-            const uint32_t code = quant_code(z[i], inv, zero);
+            const uint32_t code = quant_code(z[i], inv, zero, qmax);
             const int cr = v.perm[ubase + pos + i] - ubase;      // rotated channel, unit-local
             const int r = cr / n, c = cr - r * n;
             int sh;
             const int off = rkv_k_off(g, m, c, sh);
-            atomicOr(&imgK[r * 128 * g + off], code << sh);
+            atomicOr(&imgK[r * 128 * g + off], (code & 3u) << sh);
+            if (hb) atomicOr(&imgKh[wave * hdw + ((cr * hb) >> 5)], (code >> 2) << ((cr * hb) & 31));
           }
-          if ((lane & 15) == 0) rkv_store_meta(v, v.km, rkv_meta_index(v, b, t, (ubase + pos) >> 7), sc, zero);
+          if ((lane & (blk_lanes - 1)) == 0) rkv_store_meta(v, v.km, rkv_meta_index(v, b, t, (ubase + pos) / v.qg), sc, zero);
         }
         // ---- values: channels pos..pos+7 of the unit, block of 128 = one head
         float u[8];
@@ -310,22 +317,43 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
           mn = fminf(mn, u[i]);
           mx = fmaxf(mx, u[i]);
         }
-#pragma unroll
-        for (int s = 1; s < 16; s <<= 1) {
+        for (int s = 1; s < blk_lanes; s <<= 1) {
           mn = fminf(mn, __shfl_xor(mn, s));
           mx = fmaxf(mx, __shfl_xor(mx, s));
         }
         if (on) {
           float sc, zero, inv;
-          quant_params(mn, mx, sc, zero, inv, v.meta8);
+          quant_params(mn, mx, sc, zero, inv, v.meta8, qmax);
           const int sh = rkv_v_shift(t & 31);
+          uint32_t hi = 0;                                  // this lane's 8 channels: 8 * hb consecutive bits of the row
 #pragma unroll
-          for (int i = 0; i < 8; ++i) atomicOr(&imgV[pos + i], quant_code(u[i], inv, zero) << sh);
-          if ((lane & 15) == 0) rkv_store_meta(v, v.vm, rkv_meta_index(v, b, t, (ubase + pos) >> 7), sc, zero);
+          for (int i = 0; i < 8; ++i) {
+            const uint32_t code = quant_code(u[i], inv, zero, qmax);
+            atomicOr(&imgV[pos + i], (code & 3u) << sh);
+            hi |= (code >> 2) << (i * hb);
+          }
+          if (hb) atomicOr(&imgVh[wave * hdw + ((pos * hb) >> 5)], hi << ((pos * hb) & 31));
+          if ((lane & (blk_lanes - 1)) == 0) rkv_store_meta(v, v.vm, rkv_meta_index(v, b, t, (ubase + pos) / v.qg), sc, zero);
         }
       }
     }
     __syncthreads();
+    if (hb) {
+      // the token's high bits: whole dwords of its rows, then cleared for the wave's next token
+      // (the barrier in the middle of the next round orders that before the next use)
+      if (active) {
+        int sh;
+        const size_t hrow = rkv_hi_dword(v, b, t, ubase, sh);
+        for (int i = lane; i < hdw; i += 64) {
+          v.kh[hrow + i] = imgKh[wave * hdw + i];
+          v.vh[hrow + i] = imgVh[wave * hdw + i];
+        }
+      }
+      for (int i = lane; i < hdw; i += 64) {
+        imgKh[wave * hdw + i] = 0;
+        imgVh[wave * hdw + i] = 0;
+      }
+    }
   }
 
   // ---- write the images.  K: every 16-byte piece of a tile belongs to one token.
@@ -550,7 +578,7 @@ int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new
   const RkvView& v = c->v;
   if (mask && v.max_sinks > 0) hipLaunchKernelGGL(k_sinks, dim3(v.B), dim3(256), 0, s, v, k, vv, mask, n_new);
   if (rkv_append_mfma_supported(c)) return rkv_launch_append_mfma(c, k, vv, n_new, 0, s);
-  if (c->blocks_aligned && (v.g == 2 || v.g == 4)) {
+  if (c->blocks_aligned && !c->wide && (v.g == 2 || v.g == 4)) {
     const int slab0 = v.len >> 5, slab1 = (v.len + n_new - 1) >> 5;
     dim3 grid(slab1 - slab0 + 1, v.NRG, v.B);
     if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
@@ -562,7 +590,7 @@ int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new
   const int U = v.span > v.n ? v.span : v.n;
   const int tile0 = v.len >> 4, tile1 = (v.len + n_new - 1) >> 4;
   dim3 grid(tile1 - tile0 + 1, v.E / U, v.B);
-  const size_t lds = (size_t)6 * U * 4;
+  const size_t lds = (size_t)6 * U * 4 + (size_t)U * v.hb;   // the kernel's images, see there
   void (*fn)(RkvView, const __half*, const __half*, int, int, int) = nullptr;
   switch (v.n / 64) {
     case 2: fn = k_append<2>; break;
@@ -597,7 +625,7 @@ __global__ void __launch_bounds__(64) k_dequant(RkvView v, float* __restrict__ k
       const uint32_t w = v.kc[rkv_k_dword(v, b, rg, t, c, sh)];
       float sc, zero;
       rkv_load_meta(v, v.km, rkv_meta_index(v, b, t, v.gid[rg * n + c]), sc, zero);
-      x[i] = sc * ((float)((w >> sh) & 3u) - zero);
+      x[i] = sc * ((float)(((w >> sh) & 3u) | rkv_hi_get(v, v.kh, b, t, rg * n + c)) - zero);
     }
     fwht_lanes<PL>(x, lane, 6);
     const float rs = rsqrtf((float)n);
@@ -616,8 +644,8 @@ __global__ void __launch_bounds__(64) k_dequant(RkvView v, float* __restrict__ k
           int sh;
           const uint32_t w = v.vc[rkv_v_dword(v, b, rg, t, c0 + i, sh)];
           float sc, zero;
-          rkv_load_meta(v, v.vm, rkv_meta_index(v, b, t, (rg * n + c0) >> 7), sc, zero);
-          u[i] = sc * ((float)((w >> sh) & 3u) - zero);
+          rkv_load_meta(v, v.vm, rkv_meta_index(v, b, t, (rg * n + c0) / v.qg), sc, zero);
+          u[i] = sc * ((float)(((w >> sh) & 3u) | rkv_hi_get(v, v.vh, b, t, rg * n + c0 + i)) - zero);
         }
       }
       if (v.v_rotate) {
@@ -647,28 +675,30 @@ int rkv_launch_dequant(rkv_cache* c, float* k_hat, float* v_hat, hipStream_t s) 
 }
 
 // ---------------------------------------------------------------------------------------------
-// export / import of the logical code array in canonical bytes (test support)
+// export / import of the logical code array in canonical bytes (test support): four 2-bit codes
+// per byte, or two wider codes per byte (a nibble each), first code in the lowest bits
 // ---------------------------------------------------------------------------------------------
 
 __global__ void k_export(RkvView v, uint8_t* kc, float* ks, float* kz, uint8_t* vc, float* vs, float* vz) {
-  const size_t per_tok = v.E / 4;
+  const int cpb = v.hb ? 2 : 4, fw = 8 / cpb;                 // codes per byte, bits of a byte each takes
+  const size_t per_tok = v.E / cpb;
   const size_t total = (size_t)v.B * v.len * per_tok;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
     const int j = idx % per_tok;
     const size_t bt = idx / per_tok;
     const int t = bt % v.len, b = bt / v.len;
     uint32_t kb = 0, vb = 0;
-    for (int r = 0; r < 4; ++r) {
-      const int i = 4 * j + r;
+    for (int r = 0; r < cpb; ++r) {
+      const int i = cpb * j + r;
       int sh;
       if (kc) {
         const int cr = v.perm[i];
         const uint32_t w = v.kc[rkv_k_dword(v, b, cr / v.n, t, cr % v.n, sh)];
-        kb |= ((w >> sh) & 3u) << (2 * r);
+        kb |= (((w >> sh) & 3u) | rkv_hi_get(v, v.kh, b, t, cr)) << (fw * r);
       }
       if (vc) {
         const uint32_t w = v.vc[rkv_v_dword(v, b, i / v.n, t, i % v.n, sh)];
-        vb |= ((w >> sh) & 3u) << (2 * r);
+        vb |= (((w >> sh) & 3u) | rkv_hi_get(v, v.vh, b, t, i)) << (fw * r);
       }
     }
     if (kc) kc[idx] = (uint8_t)kb;
@@ -688,7 +718,7 @@ __global__ void k_export(RkvView v, uint8_t* kc, float* ks, float* kz, uint8_t* 
 
 int rkv_launch_export(rkv_cache* c, uint8_t* kc, float* ks, float* kz, uint8_t* vc, float* vs, float* vz, hipStream_t s) {
   const RkvView& v = c->v;
-  const size_t total = (size_t)v.B * v.len * (v.E / 4);
+  const size_t total = (size_t)v.B * v.len * (v.E / (v.hb ? 2 : 4));
   size_t blocks = (total + 255) / 256;
   if (blocks > 65535) blocks = 65535;
   hipLaunchKernelGGL(k_export, dim3((unsigned)blocks), dim3(256), 0, s, v, kc, ks, kz, vc, vs, vz);
@@ -697,21 +727,30 @@ int rkv_launch_export(rkv_cache* c, uint8_t* kc, float* ks, float* kz, uint8_t* 
 
 __global__ void k_import(RkvView v, int T, const uint8_t* kc, const float* ks, const float* kz, const uint8_t* vc,
                          const float* vs, const float* vz) {
-  const size_t per_tok = v.E / 4;
+  const int cpb = v.hb ? 2 : 4, fw = 8 / cpb;
+  const uint32_t fmask = (1u << fw) - 1u;
+  const size_t per_tok = v.E / cpb;
   const size_t total = (size_t)v.B * T * per_tok;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
     const int j = idx % per_tok;
     const size_t bt = idx / per_tok;
     const int t = bt % T, b = bt / T;
     const uint32_t kb = kc[idx], vb = vc[idx];
-    for (int r = 0; r < 4; ++r) {
-      const int i = 4 * j + r;
+    for (int r = 0; r < cpb; ++r) {
+      const int i = cpb * j + r;
       int sh;
       const int cr = v.perm[i];
+      const uint32_t kcode = (kb >> (fw * r)) & fmask, vcode = (vb >> (fw * r)) & fmask;
       size_t a = rkv_k_dword(v, b, cr / v.n, t, cr % v.n, sh);
-      atomicOr(&v.kc[a], ((kb >> (2 * r)) & 3u) << sh);
+      atomicOr(&v.kc[a], (kcode & 3u) << sh);
       a = rkv_v_dword(v, b, i / v.n, t, i % v.n, sh);
-      atomicOr(&v.vc[a], ((vb >> (2 * r)) & 3u) << sh);
+      atomicOr(&v.vc[a], (vcode & 3u) << sh);
+      if (v.hb) {
+        a = rkv_hi_dword(v, b, t, cr, sh);
+        atomicOr(&v.kh[a], (kcode >> 2) << sh);
+        a = rkv_hi_dword(v, b, t, i, sh);
+        atomicOr(&v.vh[a], (vcode >> 2) << sh);
+      }
     }
     if (j < v.NG) {
       const size_t mi = rkv_meta_index(v, b, t, j), o = bt * v.NG + j;
@@ -724,12 +763,12 @@ __global__ void k_import(RkvView v, int T, const uint8_t* kc, const float* ks, c
 int rkv_launch_import(rkv_cache* c, int T, const uint8_t* kc, const float* ks, const float* kz, const uint8_t* vc,
                       const float* vs, const float* vz, hipStream_t s) {
   const RkvView& v = c->v;
-  // clear the four code/meta regions (they are contiguous from the start of the block up to the sink store)
+  // clear the code and metadata regions (they are contiguous from the start of the block up to the sink store)
   const size_t n16 = ((char*)v.sink_k - c->base) / 16;
   size_t blocks = (n16 + 255) / 256;
   if (blocks > 16384) blocks = 16384;
   hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)c->base, n16);
-  const size_t total = (size_t)v.B * T * (v.E / 4);
+  const size_t total = (size_t)v.B * T * (v.E / (v.hb ? 2 : 4));
   blocks = (total + 255) / 256;
   if (blocks > 65535) blocks = 65535;
   hipLaunchKernelGGL(k_import, dim3((unsigned)blocks), dim3(256), 0, s, v, T, kc, ks, kz, vc, vs, vz);

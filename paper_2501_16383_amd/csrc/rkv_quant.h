@@ -28,13 +28,13 @@ __device__ inline void load_halves(const __half* p, float (&x)[PL]) {
   }
 }
 
-// Eq. 8-9 for one block of 128 given its min and max: fp16 scale actually stored, integer zero,
+// Eq. 8-9 for one block given its min and max and the largest code qmax = 2^bits - 1: fp16 scale actually stored, integer zero,
 // and the reciprocal of the scale (one IEEE division per block; elements multiply by it, which
 // differs from x / s only within ~1.5 ulp, far inside the rounding-tie window of the parity tests).
 // meta8: the scale is stored in FP8 E4M3 rounded up (a positive range then never rounds to 0) and
 // the zero-point in INT8.
-__device__ inline void quant_params(float mn, float mx, float& s, float& zero, float& inv_s, bool meta8 = false) {
-  float raw = (mx - mn) / 3.0f;
+__device__ inline void quant_params(float mn, float mx, float& s, float& zero, float& inv_s, bool meta8 = false, float qmax = 3.0f) {
+  float raw = (mx - mn) / qmax;
   if (meta8) {
     s = rkv_e4m3_round_up(raw);
     if (s == 0.0f) {
@@ -57,11 +57,11 @@ __device__ inline void quant_params(float mn, float mx, float& s, float& zero, f
   zero = fminf(fmaxf(zero, -2048.0f), 2048.0f);
 }
 // Eq. 6
-__device__ inline uint32_t quant_code(float x, float inv_s, float zero) {
+__device__ inline uint32_t quant_code(float x, float inv_s, float zero, float qmax = 3.0f) {
   // adding 1.5 * 2^23 rounds x * inv_s to an integer (ties to even, as rintf) in the same FMA and
   // leaves that integer in the low mantissa bits, which saves the float -> int conversion
   const float magic = 12582912.0f;
   float q = fmaf(x, inv_s, magic) + zero;
-  q = fminf(fmaxf(q, magic), magic + 3.0f);
-  return __float_as_uint(q) & 3u;
+  q = fminf(fmaxf(q, magic), magic + qmax);
+  return __float_as_uint(q) & 15u;
 }

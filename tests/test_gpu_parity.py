@@ -905,6 +905,43 @@ def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
         assert e <= ATT_TOL
 
 
+@pytest.mark.parametrize("bits,group,g,hq,fmt,span", [(4, 128, 4, 8, 0, 128), (3, 128, 4, 8, 0, 128), (2, 64, 4, 8, 0, 128),
+                                                      (2, 32, 2, 8, 0, 128), (4, 32, 1, 8, 1, 128), (3, 64, 8, 16, 1, 128),
+                                                      (4, 64, 4, 8, 0, 512), (3, 32, 2, 8, 0, 1024)])
+def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
+    """3- and 4-bit codes and quantization groups of 64 and 32 channels (Sec. 5.1; Tables
+    tab:ablation and tab:quantgrani) through the write half, the export and dequantize views and
+    the read half: every rotation size, both metadata formats, GQA, a reorder that crosses blocks;
+    appended in pieces with single-token steps.  The cache's size follows the setting."""
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
+    kw = dict(batch=2, n_q_heads=hq, n_kv_heads=8, max_tokens=256, max_sinks=4, rot_heads=g, meta_format=fmt)
+    cfg = R.RkvConfig(bits=bits, quant_group=group, perm_span=span, **kw)
+    mine, _ = R.query_sizes(cfg)
+    base, _ = R.query_sizes(R.RkvConfig(perm_span=span, **kw))
+    per_elem = (bits - 2) + (16 if fmt else 32) * (1.0 / group - 1.0 / 128)      # bits per cached element beyond 2-bit, group 128
+    assert mine - base == 2 * 2 * 256 * 1024 * per_elem / 8                       # K and V, batch 2, 256 token slots, 1024 channels
+    perm = None
+    if span != 128:
+        perm = calibrated_perm(w, R.RkvConfig(perm_span=span, **kw), offset_variant=True)
+        assert not np.array_equal(perm // group, np.arange(cfg.E) // group)
+    cache, oc, q = full_check(w, cfg, 213, perm=perm, chunks=[0, 100, 101, 102, 213], paths=(1, 0))
+    assert oc.k_codes.max() == 2 ** bits - 1 and oc.k_scale.shape[-1] == 1024 // group
+    # what the matrix-core kernels do not cover is refused, not mis-computed
+    with pytest.raises(R.RkvError):
+        cache.set_decode_path(2)
+        cache.decode_attention(P.gpu(q))
+    cache.set_decode_path(0)
+    # one more single-token step through rkv_decode_step (the two calls, on this setting)
+    k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
+    out = cache.decode_step(P.gpu(k1), P.gpu(v1), P.gpu(q))
+    torch.cuda.synchronize()
+    # the cache holds the oracle's codes from full_check; the same token goes to the oracle's cache
+    O.quantize_append(oc, k1, v1, None)
+    g_all = P.export_numpy(cache)
+    ref, _ = O.decode_attention(oracle_from_export(oc, g_all), q)
+    assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
+
+
 @pytest.mark.parametrize("uniform", [True, False])
 def test_truncate_rolls_back_a_multi_token_step(uniform):
     """Speculative decoding's shape: four drafted tokens are appended and read the cache together

@@ -44,7 +44,7 @@ def test_query_sizes_and_average_bits(lib):
 
 
 @pytest.mark.parametrize("field,value", [
-    ("head_dim", 64), ("quant_group", 64), ("bits", 4), ("rot_heads", 3), ("rot_heads", 16), ("perm_span", 256),
+    ("head_dim", 64), ("quant_group", 16), ("quant_group", 96), ("bits", 1), ("bits", 5), ("rot_heads", 3), ("rot_heads", 16), ("perm_span", 256),
     ("clip_ratio", 0.9), ("max_sinks", 65), ("max_tokens", 0), ("batch", 0), ("rope_style", 2), ("v_rotate", 2),
     ("n_q_heads", 41), ("rope_theta", 0.5),
 ])
@@ -54,6 +54,20 @@ def test_unsupported_configs_are_rejected(lib, field, value):
     with pytest.raises(R.RkvError) as ei:
         R.query_sizes(cfg)
     assert ei.value.code == binding.RKV_EINVAL
+
+
+@pytest.mark.parametrize("bits,group,fmt,avg", [(4, 128, 0, 4.25), (3, 128, 0, 3.25), (2, 64, 0, 2.5), (2, 32, 1, 2.5), (4, 32, 0, 5.0)])
+def test_sizes_of_wider_codes_and_smaller_groups(lib, bits, group, fmt, avg):
+    """The cache's payload is bits + (32 or 16) / group bits per element (codes, scale, zero-point)."""
+    cfg = R.RkvConfig(batch=16, n_q_heads=32, n_kv_heads=32, max_tokens=1024, max_sinks=0, bits=bits, quant_group=group,
+                      meta_format=fmt)
+    cache_bytes, _ = R.query_sizes(cfg)
+    payload = 2 * 16 * 1024 * 4096 * avg / 8
+    assert payload <= cache_bytes <= payload * 1.03
+    rot = R.RkvConfig(batch=4, n_q_heads=32, n_kv_heads=32, max_tokens=1024, bits=bits, quant_group=group, keys_rotated=1,
+                      rot_heads=4)
+    with pytest.raises(R.RkvError):
+        R.query_sizes(rot)                       # folded-in rotation is a matrix-core path: 2-bit, group 128 only
 
 
 def test_null_arguments(lib):

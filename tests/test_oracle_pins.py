@@ -196,6 +196,11 @@ def test_pack_roundtrip_all_bytes():
     assert codes.shape == (1, 1024) and codes.max() == 3
     assert np.array_equal(O.pack_canonical(codes)[0], allb)
     assert O.pack_canonical(np.array([[1, 0, 0, 0, 0, 2, 0, 0, 0, 0, 0, 3]], dtype=np.uint8))[0].tolist() == [1, 8, 192]
+    # wider codes: a nibble each, the even-numbered code in the low one
+    nib = O.unpack_canonical(allb[None], bits=4)
+    assert nib.shape == (1, 512) and nib.max() == 15 and nib[0, :6].tolist() == [0, 0, 1, 0, 2, 0]
+    assert np.array_equal(O.pack_canonical(nib, bits=4)[0], allb)
+    assert O.pack_canonical(np.array([[7, 1, 0, 5]], dtype=np.uint8), bits=3)[0].tolist() == [0x17, 0x50]
 
 
 def test_average_bits_matches_paper():
