@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--queries", type=int, default=1,
                     help="query tokens per sequence and step (above 1: that many tokens are appended, then read the cache in one multi-query call)")
     ap.add_argument("--meta-format", type=int, default=0, help="0: fp16 scale and zero-point (2.25 bits); 1: FP8 scale, INT8 zero-point (2.125 bits)")
+    ap.add_argument("--bits", type=int, default=2, help="bits per code: 2 (matrix-core kernels), 3 or 4 (general kernels)")
+    ap.add_argument("--quant-group", type=int, default=128, help="channels per quantization block: 128 (matrix-core kernels), 64 or 32 (general kernels)")
     ap.add_argument("--ragged-min", type=float, default=1.0,
                     help="below 1: sequence lengths spread evenly from this fraction of the context up to the full context")
     ap.add_argument("--separate-calls", action="store_true",
@@ -127,8 +129,10 @@ def main():
     hip = Hip()
 
     cfg = R.RkvConfig(batch=B, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=max(w.n_sinks, 1),
-                      rot_heads=w.rot_heads, perm_span=128, rope_theta=w.rope_theta, meta_format=args.meta_format)
-    MB = 2 if args.meta_format == 1 else 4       # bytes of metadata per (token, block of 128)
+                      rot_heads=w.rot_heads, perm_span=128, rope_theta=w.rope_theta, meta_format=args.meta_format,
+                      bits=args.bits, quant_group=args.quant_group)
+    QB, QG = args.bits, args.quant_group
+    MB = 2 if args.meta_format == 1 else 4       # bytes of metadata per (token, quantization block)
     E = cfg.E
     _, scratch_bytes = R.query_sizes(cfg)
     scratch = torch.empty(scratch_bytes * NQ, dtype=torch.uint8, device=dev)
@@ -158,7 +162,7 @@ def main():
         caches.append(c)
         del k, v, mask
     n_bulk = B * n_pre if pre_lens is None else sum(pre_lens)
-    bulk_bytes = n_bulk * (2 * E * 2 + 2 * E // 4 + 2 * (E // 128) * MB)
+    bulk_bytes = n_bulk * (2 * E * 2 + 2 * E * QB // 8 + 2 * (E // QG) * MB)
     bulk_best = min(bulk_ms)
     bulk_avg = sum(bulk_ms) / len(bulk_ms)
 
@@ -237,14 +241,15 @@ def main():
     min_ms = min(kern_ms)
     med_ms = sorted(kern_ms)[len(kern_ms) // 2]
     ctx = T - (K - 1) * NQ / 2.0
-    bytes_per_tok = 2 * E // 4 + 2 * (E // 128) * MB
+    bytes_per_tok = 2 * E * QB // 8 + 2 * (E // QG) * MB
     launch_bytes = (sum(lens_now) - B * (K - 1) * NQ / 2.0) * bytes_per_tok      # mean over the timed steps
     achieved = launch_bytes / (avg_ms * 1e-3) / 1e9
 
     # measured HBM traffic of the decode kernel (rocprofv3 counters, calibrated; see profiles/)
     traffic = None
     tfile = os.path.join(ROOT, "profiles", f"decode_{w.name}_hbm_traffic.md")
-    if os.path.exists(tfile) and L == w.layers:
+    default_run = (QB, QG, args.meta_format, NQ, args.path) == (2, 128, 0, 1, 0) and pre_lens is None   # what the counters were collected on
+    if os.path.exists(tfile) and L == w.layers and default_run:
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
@@ -253,8 +258,8 @@ def main():
     assert all(bool(torch.isfinite(o).all()) for o in outs)
 
     result = {
-        "metric": "2-bit decode-attention KV-tokens/s (one appended token per sequence plus decode attention over the full cache, per layer)"
-                  if NQ == 1 else f"2-bit decode-attention KV-tokens/s ({NQ} appended tokens per sequence, then {NQ} causal queries over the full cache in one call, per layer)",
+        "metric": f"{QB}-bit decode-attention KV-tokens/s (one appended token per sequence plus decode attention over the full cache, per layer)"
+                  if NQ == 1 else f"{QB}-bit decode-attention KV-tokens/s ({NQ} appended tokens per sequence, then {NQ} causal queries over the full cache in one call, per layer)",
         "value": kv_tokens / wall,
         "unit": "KV-tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W,
@@ -263,11 +268,13 @@ def main():
         "dtype": "f32",   # what the path accumulates in; storage is u2 codes + fp16 scale/zero, the rotations are exact fp4 / fp16 matrix products
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {SHAPES.get(w.name, 'custom')} decode, {L} layers x {w.n_q_heads} query / {w.n_kv_heads} KV heads x 128, "
-                               f"batch {B}, context {T}, rotation over {w.rot_heads} heads, 2-bit group-128, {w.n_sinks} fp16 sinks",
+                               f"batch {B}, context {T}, rotation over {w.rot_heads} heads, {QB}-bit group-{QG}, {w.n_sinks} fp16 sinks",
                    "decode_path": args.path, "queries_per_step": NQ, "calls_per_step_and_layer": 1 if one_call else 2,
                    "sequence_lengths": "all equal" if pre_lens is None else f"spread evenly from {lens_now[0]} to {lens_now[-1]} tokens",
-                   "storage": "u2 codes + fp16 scale / fp16 zero per 128 (2.25 bits per element)" if MB == 4 else "u2 codes + FP8 E4M3 scale / INT8 zero per 128 (2.125 bits per element)",
-                   "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"},
+                   "storage": f"u{QB} codes + " + ("fp16 scale / fp16 zero" if MB == 4 else "FP8 E4M3 scale / INT8 zero") +
+                              f" per {QG} ({QB + 8.0 * MB / QG:g} bits per element)",
+                   "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"
+                                 if (QB, QG) == (2, 128) and args.path != 1 else "fp32 vector arithmetic and accumulation (general kernels)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms, "launches_timed": len(kern_ms),
                      "algorithmic_bytes_per_launch": launch_bytes, "bytes_per_kv_token": bytes_per_tok},
