@@ -238,14 +238,15 @@ def test_error_codes():
     assert ei.value.code == -5
 
 
-def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag="", meta_format=0):
+def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag="", meta_format=0, rep=1, rope_theta=10000.0):
     """One (sequence, rotation group of 4 heads) slice of a full-size run against the oracle: a
     rotation group's codes and attention outputs depend on nothing outside the slice.  The codes
     must equal the oracle's outside the documented rounding ties; the attention output is then
     compared on the GPU's own codes, so that a tie cannot hide in (or leak into) the tolerance.
     exp: export_codes() tensors already on the host (numpy)."""
-    ocfg = O.OracleConfig(batch=1, n_q_heads=4, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=max_sinks,
-                          meta_format=meta_format)
+    ocfg = O.OracleConfig(batch=1, n_q_heads=4 * rep, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=max_sinks,
+                          meta_format=meta_format, rope_theta=rope_theta)
+    hq = slice(4 * rep * rg, 4 * rep * (rg + 1))               # the query heads of the group's four KV heads
     oc = O.cache_new(ocfg, None if perm is None else perm[512 * rg:512 * (rg + 1)] - 512 * rg)
     O.quantize_append(oc, ks, vs, ms)
     sl_c, sl_m = slice(128 * rg, 128 * (rg + 1)), slice(4 * rg, 4 * rg + 4)
@@ -260,9 +261,9 @@ def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag
                     f"{tag} b={b} rg={rg} V", meta_format=meta_format)
     for name, val in g.items():                                # attention on the GPU's own codes
         setattr(oc, name, val)
-    ref, lse_ref = O.decode_attention(oc, q[b:b + 1, 4 * rg:4 * rg + 4])
-    e = P.attention_error(out[b:b + 1, 4 * rg:4 * rg + 4], ref)
-    le = float(np.abs(lse[b:b + 1, 4 * rg:4 * rg + 4] - lse_ref).max())
+    ref, lse_ref = O.decode_attention(oc, q[b:b + 1, hq])
+    e = P.attention_error(out[b:b + 1, hq], ref)
+    le = float(np.abs(lse[b:b + 1, hq] - lse_ref).max())
     print(f"[parity] {tag} b={b} rg={rg}: out err {e:.3e} lse err {le:.3e}", flush=True)
     assert e <= ATT_TOL and le <= LSE_TOL
 
@@ -337,6 +338,50 @@ def test_full_size_long_context_sampled():
     lse = lse.cpu().numpy().astype(np.float64)
     rg = 5
     check_slice(exp, out, lse, 0, rg, k[:, :, 4 * rg:4 * rg + 4], v[:, :, 4 * rg:4 * rg + 4], mask, q, tag="long context")
+
+
+def test_full_size_config4_gqa_sampled():
+    """Configuration 4 at full size (batch 32, 32 query / 8 KV heads, context 8192, RoPE base
+    500000) in the launch configuration bench.py times: bulk append of 8191 tokens, then one
+    rkv_decode_step on the matrix-core path, where a workgroup serves two of the four query heads of
+    each KV head.  Two (sequence, rotation group) slices - four KV heads, sixteen query heads each -
+    are recomputed by the oracle."""
+    w = S.WORKLOADS["cfg4"]
+    T = w.context
+    cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=4,
+                      rot_heads=4, perm_span=128, rope_theta=w.rope_theta)
+    rep = w.n_q_heads // w.n_kv_heads
+    perm = calibrated_perm(w, cfg)
+    cache = R.RkvCache(cfg)
+    cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+    samples = [(0, 1), (31, 0)]
+    keep = {}
+    print("[case] full-size config 4: generating inputs per sequence", flush=True)
+    k = torch.empty((w.batch, T, w.n_kv_heads, 128), dtype=torch.float16, device="cuda")
+    v = torch.empty_like(k)
+    mask = torch.empty((w.batch, T), dtype=torch.uint8, device="cuda")
+    for b in range(w.batch):
+        kb, vb, mb = S.make_kv(dataclasses.replace(w, seed=w.seed + 100 * b), T, batch=1)
+        for (sb, rg) in samples:
+            if sb == b:
+                keep[(sb, rg)] = (kb[:, :, 4 * rg:4 * rg + 4].copy(), vb[:, :, 4 * rg:4 * rg + 4].copy(), mb.copy())
+        k[b:b + 1].copy_(torch.from_numpy(kb))
+        v[b:b + 1].copy_(torch.from_numpy(vb))
+        mask[b:b + 1].copy_(torch.from_numpy(mb))
+    q = S.make_q(w)
+    print("[case] full-size config 4: bulk append 8191 + one decode step", flush=True)
+    cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous())
+    cache.set_decode_path(2)
+    assert not bool(mask[:, T - 1:].any())
+    out, lse = cache.decode_step(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), P.gpu(q), want_lse=True)
+    exp = export_host(cache)
+    assert cache.length == T
+    out = out.cpu().numpy().astype(np.float64)
+    lse = lse.cpu().numpy().astype(np.float64)
+    assert np.isfinite(out).all()
+    for (b, rg) in samples:
+        ks, vs, ms = keep[(b, rg)]
+        check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag="full-size config 4", rep=rep, rope_theta=w.rope_theta)
 
 
 def test_full_size_config1_shape_without_sinks():
