@@ -27,8 +27,10 @@
 // Codes wider than 2 bits and quantization groups smaller than 128 (Sec. 5.1, the settings of
 // Tables tab:ablation and tab:quantgrani) keep all of the above for the low two bits of every code
 // and add
-//   K high, V high   [batch][Tpad] rows of E * (bits - 2) / 32 dwords: the remaining 1 or 2 bits
-//             of rotated channel (K) or channel (V) c of the layer at bit (bits - 2) * c of the row;
+//   K high, V high   4-bit codes: the upper two bits, in arrays laid out exactly as K codes and
+//             V codes (same dword, same bit position), so that the matrix-core kernels read them
+//             as a second plane; 3-bit codes: the third bit in [batch][Tpad] rows of E / 32 dwords,
+//             bit c of a row belonging to rotated channel (K) or channel (V) c of the layer;
 //   K meta, V meta   128 / quant_group entries in place of each one (gid then counts blocks of
 //             quant_group reordered positions).
 // Those settings run on the general kernels only.
@@ -128,16 +130,32 @@ __host__ __device__ inline size_t rkv_meta_index(const RkvView& v, int b, int t,
   int rg = G / v.gm, j = G - rg * v.gm;
   return ((size_t)(b * v.NRG + rg) * (size_t)v.Tpad + t) * v.gm + j;
 }
-// High bits of the code of channel ch (0..E) of token t: position in a high-bit plane
+// Third bit of a 3-bit code of channel ch (0..E) of token t: position in a high-bit plane (hb == 1)
 __host__ __device__ inline size_t rkv_hi_dword(const RkvView& v, int b, int t, int ch, int& shift) {
-  shift = (ch * v.hb) & 31;
-  return ((size_t)b * v.Tpad + t) * (size_t)(v.E * v.hb / 32) + ((ch * v.hb) >> 5);
+  shift = ch & 31;
+  return ((size_t)b * v.Tpad + t) * (size_t)(v.E / 32) + (ch >> 5);
 }
-__device__ inline uint32_t rkv_hi_get(const RkvView& v, const uint32_t* plane, int b, int t, int ch) {
+// The bits above the low two of the code of (rotated) channel c of rotation group rg, token t,
+// already shifted to their place in the code (0 with 2-bit codes)
+__device__ inline uint32_t rkv_khi_get(const RkvView& v, int b, int rg, int t, int c) {
   if (v.hb == 0) return 0u;
   int sh;
-  const uint32_t w = plane[rkv_hi_dword(v, b, t, ch, sh)];
-  return ((w >> sh) & ((1u << v.hb) - 1u)) << 2;
+  if (v.hb == 2) {
+    const uint32_t w = v.kh[rkv_k_dword(v, b, rg, t, c, sh)];
+    return ((w >> sh) & 3u) << 2;
+  }
+  const uint32_t w = v.kh[rkv_hi_dword(v, b, t, rg * v.n + c, sh)];
+  return ((w >> sh) & 1u) << 2;
+}
+__device__ inline uint32_t rkv_vhi_get(const RkvView& v, int b, int rg, int t, int c) {
+  if (v.hb == 0) return 0u;
+  int sh;
+  if (v.hb == 2) {
+    const uint32_t w = v.vh[rkv_v_dword(v, b, rg, t, c, sh)];
+    return ((w >> sh) & 3u) << 2;
+  }
+  const uint32_t w = v.vh[rkv_hi_dword(v, b, t, rg * v.n + c, sh)];
+  return ((w >> sh) & 1u) << 2;
 }
 
 __device__ inline uint32_t rkv_pack_meta(float scale, float zero) {

@@ -203,8 +203,10 @@ __global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restri
 //   token at a time: rotate in registers + lane exchanges (Sec. 4.2), scatter to reordered
 //   positions in LDS (Sec. 4.1), reduce min/max per block of 128, Eq. 6-9, and OR the codes into LDS
 //   images of the physical tile, which are then written with whole-dword stores.  With codes wider
-//   than 2 bits the images take the low two bits and each wave collects the remaining bits of its
-//   token in an image of that token's piece of the high-bit rows, written after the token is done.
+//   than 2 bits the images take the low two bits; the upper two bits of 4-bit codes go to a second
+//   pair of images (the planes have the same layout), and with 3-bit codes each wave collects the
+//   third bits of its token in an image of that token's piece of the high-bit rows, written after
+//   the token is done.
 // ---------------------------------------------------------------------------------------------
 
 template <int PL>
@@ -214,9 +216,10 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
   float* zbuf = reinterpret_cast<float*>(smem);            // [4][U]
   uint32_t* imgK = smem + 4 * U;                            // [U]  (16 tokens x U codes)
   uint32_t* imgV = imgK + U;                                // [U]  (one dword per channel)
-  const int hb = v.hb, hdw = U * hb / 32;                   // dwords of a token's high bits within the unit
-  uint32_t* imgKh = imgV + U;                               // [4 waves][hdw]
-  uint32_t* imgVh = imgKh + 4 * hdw;                        // [4 waves][hdw]
+  const int hb = v.hb, hdw = hb == 1 ? U / 32 : 0;          // 3-bit codes: dwords of a token's third bits within the unit
+  uint32_t* imgKh = imgV + U;                               // 3-bit: [4 waves][hdw]; 4-bit: [U], as imgK
+  uint32_t* imgVh = imgKh + (hb == 2 ? U : 4 * hdw);        // 3-bit: [4 waves][hdw]; 4-bit: [U], as imgV
+  const int himg = hb == 2 ? 2 * U : 8 * hdw;               // dwords of the two together
   const float qmax = (float)((4 << hb) - 1);
   const int blk_lanes = v.qg >> 3;                          // lanes (8 values each) of one quantization block
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -226,7 +229,7 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
   const int t_lo = v.len, t_hi = v.len + n_new;
   const float rs = rsqrtf((float)n);
 
-  for (int i = tid; i < 2 * U + 8 * hdw; i += 256) imgK[i] = 0;   // imgK, imgV and the high-bit images are adjacent
+  for (int i = tid; i < 2 * U + himg; i += 256) imgK[i] = 0;   // imgK, imgV and the high-bit images are adjacent
   __syncthreads();
 
   // old V dwords of a partly filled tile are fetched now and merged at the end
@@ -235,14 +238,16 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
     const int t = tile * 16 + m;
     if (!(t >= t_lo && t < t_hi)) keep |= 3u << rkv_v_shift(t & 31);
   }
-  uint32_t oldv[4] = {0, 0, 0, 0};
+  uint32_t oldv[4] = {0, 0, 0, 0}, oldv2[4] = {0, 0, 0, 0};
   if (keep && U <= 1024) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int idx = tid + 256 * k;
       if (idx < U) {
         const int r = idx / n, c = idx - r * n;
-        oldv[k] = v.vc[rkv_v_slabbase(v, b, rg0 + r, tile >> 1) + rkv_v_off(g, c, (tile & 1) * 16)];
+        const size_t a = rkv_v_slabbase(v, b, rg0 + r, tile >> 1) + rkv_v_off(g, c, (tile & 1) * 16);
+        oldv[k] = v.vc[a];
+        if (hb == 2) oldv2[k] = v.vh[a];
       }
     }
   }
@@ -295,7 +300,8 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
             int sh;
             const int off = rkv_k_off(g, m, c, sh);
             atomicOr(&imgK[r * 128 * g + off], (code & 3u) << sh);
-            if (hb) atomicOr(&imgKh[wave * hdw + ((cr * hb) >> 5)], (code >> 2) << ((cr * hb) & 31));
+            if (hb == 2) atomicOr(&imgKh[r * 128 * g + off], (code >> 2) << sh);
+            else if (hb == 1) atomicOr(&imgKh[wave * hdw + (cr >> 5)], (code >> 2) << (cr & 31));
           }
           if ((lane & (blk_lanes - 1)) == 0) rkv_store_meta(v, v.km, rkv_meta_index(v, b, t, (ubase + pos) / v.qg), sc, zero);
         }
@@ -325,21 +331,22 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
           float sc, zero, inv;
           quant_params(mn, mx, sc, zero, inv, v.meta8, qmax);
           const int sh = rkv_v_shift(t & 31);
-          uint32_t hi = 0;                                  // this lane's 8 channels: 8 * hb consecutive bits of the row
+          uint32_t hi = 0;                                  // 3-bit codes: this lane's 8 channels are 8 consecutive bits of the row
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             const uint32_t code = quant_code(u[i], inv, zero, qmax);
             atomicOr(&imgV[pos + i], (code & 3u) << sh);
-            hi |= (code >> 2) << (i * hb);
+            if (hb == 2) atomicOr(&imgVh[pos + i], (code >> 2) << sh);
+            hi |= (code >> 2) << i;
           }
-          if (hb) atomicOr(&imgVh[wave * hdw + ((pos * hb) >> 5)], hi << ((pos * hb) & 31));
+          if (hb == 1) atomicOr(&imgVh[wave * hdw + (pos >> 5)], hi << (pos & 31));
           if ((lane & (blk_lanes - 1)) == 0) rkv_store_meta(v, v.vm, rkv_meta_index(v, b, t, (ubase + pos) / v.qg), sc, zero);
         }
       }
     }
     __syncthreads();
-    if (hb) {
-      // the token's high bits: whole dwords of its rows, then cleared for the wave's next token
+    if (hb == 1) {
+      // the token's third bits: whole dwords of its rows, then cleared for the wave's next token
       // (the barrier in the middle of the next round orders that before the next use)
       if (active) {
         int sh;
@@ -361,7 +368,10 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
   for (int idx = tid; idx < U; idx += 256) {
     const int r = idx / tile_dw, off = idx - r * tile_dw;
     const int t = tile * 16 + rkv_k_tile_token(g, off);
-    if (t >= t_lo && t < t_hi) v.kc[rkv_k_tilebase(v, b, rg0 + r, tile) + off] = imgK[idx];
+    if (t >= t_lo && t < t_hi) {
+      v.kc[rkv_k_tilebase(v, b, rg0 + r, tile) + off] = imgK[idx];
+      if (hb == 2) v.kh[rkv_k_tilebase(v, b, rg0 + r, tile) + off] = imgKh[idx];
+    }
   }
   // V: a dword holds 16 token slots of one channel; keep the slots of tokens not in this call.
   for (int idx = tid, k = 0; idx < U; idx += 256, ++k) {
@@ -370,6 +380,11 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
     uint32_t w = imgV[idx];
     if (keep) w |= (U <= 1024 ? oldv[k & 3] : v.vc[a]) & keep;
     v.vc[a] = w;
+    if (hb == 2) {
+      w = imgVh[idx];
+      if (keep) w |= (U <= 1024 ? oldv2[k & 3] : v.vh[a]) & keep;
+      v.vh[a] = w;
+    }
   }
 }
 
@@ -590,7 +605,7 @@ int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new
   const int U = v.span > v.n ? v.span : v.n;
   const int tile0 = v.len >> 4, tile1 = (v.len + n_new - 1) >> 4;
   dim3 grid(tile1 - tile0 + 1, v.E / U, v.B);
-  const size_t lds = (size_t)6 * U * 4 + (size_t)U * v.hb;   // the kernel's images, see there
+  const size_t lds = (size_t)6 * U * 4 + (v.hb == 2 ? (size_t)8 * U : v.hb == 1 ? (size_t)U : 0);   // the kernel's images, see there
   void (*fn)(RkvView, const __half*, const __half*, int, int, int) = nullptr;
   switch (v.n / 64) {
     case 2: fn = k_append<2>; break;
@@ -625,7 +640,7 @@ __global__ void __launch_bounds__(64) k_dequant(RkvView v, float* __restrict__ k
       const uint32_t w = v.kc[rkv_k_dword(v, b, rg, t, c, sh)];
       float sc, zero;
       rkv_load_meta(v, v.km, rkv_meta_index(v, b, t, v.gid[rg * n + c]), sc, zero);
-      x[i] = sc * ((float)(((w >> sh) & 3u) | rkv_hi_get(v, v.kh, b, t, rg * n + c)) - zero);
+      x[i] = sc * ((float)(((w >> sh) & 3u) | rkv_khi_get(v, b, rg, t, c)) - zero);
     }
     fwht_lanes<PL>(x, lane, 6);
     const float rs = rsqrtf((float)n);
@@ -645,7 +660,7 @@ __global__ void __launch_bounds__(64) k_dequant(RkvView v, float* __restrict__ k
           const uint32_t w = v.vc[rkv_v_dword(v, b, rg, t, c0 + i, sh)];
           float sc, zero;
           rkv_load_meta(v, v.vm, rkv_meta_index(v, b, t, (rg * n + c0) / v.qg), sc, zero);
-          u[i] = sc * ((float)(((w >> sh) & 3u) | rkv_hi_get(v, v.vh, b, t, rg * n + c0 + i)) - zero);
+          u[i] = sc * ((float)(((w >> sh) & 3u) | rkv_vhi_get(v, b, rg, t, c0 + i)) - zero);
         }
       }
       if (v.v_rotate) {
@@ -694,11 +709,11 @@ __global__ void k_export(RkvView v, uint8_t* kc, float* ks, float* kz, uint8_t* 
       if (kc) {
         const int cr = v.perm[i];
         const uint32_t w = v.kc[rkv_k_dword(v, b, cr / v.n, t, cr % v.n, sh)];
-        kb |= (((w >> sh) & 3u) | rkv_hi_get(v, v.kh, b, t, cr)) << (fw * r);
+        kb |= (((w >> sh) & 3u) | rkv_khi_get(v, b, cr / v.n, t, cr % v.n)) << (fw * r);
       }
       if (vc) {
         const uint32_t w = v.vc[rkv_v_dword(v, b, i / v.n, t, i % v.n, sh)];
-        vb |= (((w >> sh) & 3u) | rkv_hi_get(v, v.vh, b, t, i)) << (fw * r);
+        vb |= (((w >> sh) & 3u) | rkv_vhi_get(v, b, i / v.n, t, i % v.n)) << (fw * r);
       }
     }
     if (kc) kc[idx] = (uint8_t)kb;
@@ -743,9 +758,11 @@ __global__ void k_import(RkvView v, int T, const uint8_t* kc, const float* ks, c
       const uint32_t kcode = (kb >> (fw * r)) & fmask, vcode = (vb >> (fw * r)) & fmask;
       size_t a = rkv_k_dword(v, b, cr / v.n, t, cr % v.n, sh);
       atomicOr(&v.kc[a], (kcode & 3u) << sh);
+      if (v.hb == 2) atomicOr(&v.kh[a], (kcode >> 2) << sh);
       a = rkv_v_dword(v, b, i / v.n, t, i % v.n, sh);
       atomicOr(&v.vc[a], (vcode & 3u) << sh);
-      if (v.hb) {
+      if (v.hb == 2) atomicOr(&v.vh[a], (vcode >> 2) << sh);
+      if (v.hb == 1) {
         a = rkv_hi_dword(v, b, t, cr, sh);
         atomicOr(&v.kh[a], (kcode >> 2) << sh);
         a = rkv_hi_dword(v, b, t, i, sh);
