@@ -43,6 +43,9 @@ static_assert(MF_CH == 256, "the per-sequence chunk table (k_lens) counts chunks
 #ifndef MF_ACC
 #define MF_ACC 16         // score accumulators per lane and pass of the key phase
 #endif
+#ifndef MF_OCC_HI
+#define MF_OCC_HI 2        // the same for the 4-bit variants, which hold a second plane of codes
+#endif
 #ifndef MF_OCC
 #define MF_OCC 3           // workgroups per compute unit the register budget is set for
 #endif
@@ -147,8 +150,13 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // rkv_virtual_head) and virtual head hv only attends tokens at positions <= q_lim[b][query token of hv].
 // META8: scales in FP8 E4M3 and zero-points in 8 bits (rkv_load_meta describes the layout); they
 // are widened to the fp16 operands of the small matrix products right after loading.
-template <int G, int REP, bool MULTI, bool META8>
-__global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
+// HI: 4-bit codes, c = c_lo + 4 c_hi.  The plane of the upper two bits has the layout of the lower
+// one.  Key phase: it goes through the same unpacking (nibble = c_hi / 2) and meets a copy of the
+// Hadamard operand with entries +-4 in place of +-1, accumulating onto the low plane's products,
+// so that the big products yield H_128 (c / 2) as before.  Value phase: it accumulates separately
+// and is folded in, times 4, once per chunk.  Sums stay exact: |H_128 (c / 2)| <= 960 < 1024.
+template <int G, int REP, bool MULTI, bool META8, bool HI>
+__global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq) {
   constexpr int NH = G * REP;                    // query heads served by this workgroup: REP per KV head
@@ -265,14 +273,19 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         cs_s[p] = cs.y;
       }
       const uint4* ktiles = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tw >> 4));
+      const uint4* khtiles = HI ? reinterpret_cast<const uint4*>(v.kh + rkv_k_tilebase(v, b, rg, tw >> 4)) : nullptr;
       const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * (META8 ? G / 2 : G);
 
-      uint4 cw[G / 2];
+      uint4 cw[G / 2], cwh[HI ? G / 2 : 1];
       constexpr int MW = META8 ? G / 2 : G;              // metadata dwords per token and rotation group
       uint32_t mw[4][MW];
       auto load_tile = [&](int ti) {
 #pragma unroll
         for (int pr = 0; pr < G / 2; ++pr) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
+        if constexpr (HI) {
+#pragma unroll
+          for (int pr = 0; pr < G / 2; ++pr) cwh[pr] = rkv_ld_stream(khtiles + (size_t)ti * (32 * G) + pr * 64 + lane);
+        }
         if constexpr (META8) {
           // the lane's four tokens are consecutive: 4 x 2G bytes in one piece
           const uint4* mp = reinterpret_cast<const uint4*>(kmeta + (size_t)(ti * 16 + 4 * q) * MW);
@@ -318,6 +331,14 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         for (int pr = 0; pr < G / 2; ++pr) {
           A[2 * pr] = unpack_fp4(cw[pr].x, cw[pr].y);
           A[2 * pr + 1] = unpack_fp4(cw[pr].z, cw[pr].w);
+        }
+        v8i Ah[HI ? G : 1];
+        if constexpr (HI) {
+#pragma unroll
+          for (int pr = 0; pr < G / 2; ++pr) {
+            Ah[2 * pr] = unpack_fp4(cwh[pr].x, cwh[pr].y);
+            Ah[2 * pr + 1] = unpack_fp4(cwh[pr].z, cwh[pr].w);
+          }
         }
         // scale rows of the 4x4 products: (+-s_0, +-s_1, +-s_2, +-s_3) of token 4q + r, signs of H_g row n & 3
         v4h sA[4];
@@ -388,6 +409,19 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
             for (int blk = 0; blk < G; ++blk) {
               lo[blk] = mfma_fp4(A[blk], Hlo, zero4);
               hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
+            }
+            if constexpr (HI) {
+              // FP4 1.0 (0x2) and -1.0 (0xA) with bit 2 set are 4.0 and -4.0
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                Hlo[i] |= 0x44444444;
+                Hhi[i] |= 0x44444444;
+              }
+#pragma unroll
+              for (int blk = 0; blk < G; ++blk) {
+                lo[blk] = mfma_fp4(Ah[blk], Hlo, lo[blk]);
+                hi[blk] = mfma_fp4(Ah[blk], Hhi, hi[blk]);
+              }
             }
           }
           float c = cs_c[p], s = cs_s[p];                      // angles of the pass's first token (REP == 1: of token 4q)
@@ -491,6 +525,7 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
     }
     const bool has_head = q < G;
     const uint4* vslab = reinterpret_cast<const uint4*>(v.vc + rkv_v_slabbase(v, b, rg, t0 >> 5));
+    const uint4* vhslab = HI ? reinterpret_cast<const uint4*>(v.vh + rkv_v_slabbase(v, b, rg, t0 >> 5)) : nullptr;
     const int lidx = wave * (16 * G) + (has_head ? lane : 0);
     const int nslab = min(MF_CH / 32, (len - t0 + 31) >> 5);
     // the softmax and value phases run once per query head of a KV head; the V codes are requested
@@ -498,11 +533,15 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 #pragma unroll 1
     for (int rri = 0; rri < REP; ++rri) {
     // all V codes of the chunk (one 16-byte load per lane and slab): in flight while the softmax phase runs
-    uint4 vcodes[MF_CH / 32];
+    uint4 vcodes[MF_CH / 32], vhcodes[HI ? MF_CH / 32 : 1];
 #pragma unroll
     for (int sl = 0; sl < MF_CH / 32; ++sl) {
       vcodes[sl] = make_uint4(0, 0, 0, 0);
       if (has_head && sl < nslab) vcodes[sl] = rkv_ld_stream(vslab + (size_t)sl * (64 * G) + lidx);
+      if constexpr (HI) {
+        vhcodes[sl] = make_uint4(0, 0, 0, 0);
+        if (has_head && sl < nslab) vhcodes[sl] = rkv_ld_stream(vhslab + (size_t)sl * (64 * G) + lidx);
+      }
     }
     __syncthreads();
 
@@ -579,9 +618,9 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
       const int adata = n * 32 + 16 * (q & 1);
       const int aoff0 = (ause && (arow >> 1) == 0) ? adata : SA_ZERO;
       const int aoff1 = (ause && (arow >> 1) == 1) ? adata : SA_ZERO;
-      v4f acc[2][2];                                        // [channel tile][digit set]
+      v4f acc[2][2], acch[2][2];                            // [channel tile][digit set]; acch: the plane of the upper bits
 #pragma unroll
-      for (int i = 0; i < 2; ++i) acc[i][0] = acc[i][1] = (v4f){0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < 2; ++i) acc[i][0] = acc[i][1] = acch[i][0] = acch[i][1] = (v4f){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int sl = 0; sl < MF_CH / 32; ++sl) {
         if (sl < nslab) {                                   // workgroup-uniform
@@ -599,6 +638,14 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
             acc[0][set] = mfma_fp8_fp4(A[set], B0, acc[0][set]);
             acc[1][set] = mfma_fp8_fp4(A[set], B1, acc[1][set]);
           }
+          if constexpr (HI) {
+            const v8i B0h = unpack_fp4(vhcodes[sl].x, vhcodes[sl].y), B1h = unpack_fp4(vhcodes[sl].z, vhcodes[sl].w);
+#pragma unroll
+            for (int set = 0; set < 2; ++set) {
+              acch[0][set] = mfma_fp8_fp4(A[set], B0h, acch[0][set]);
+              acch[1][set] = mfma_fp8_fp4(A[set], B1h, acch[1][set]);
+            }
+          }
         }
       }
       if (has_head) {
@@ -607,7 +654,11 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
         const float wsc = 2.0f * s_wsc[q];                  // FP4 nibble = code/2
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
-          const v4f hi = acc[ct][0], lo = acc[ct][1];
+          v4f hi = acc[ct][0], lo = acc[ct][1];
+          if constexpr (HI) {
+            hi += acch[ct][0] * 4.0f;
+            lo += acch[ct][1] * 4.0f;
+          }
           const float sum = ((((hi[0] * 16.0f + hi[1]) * 16.0f + hi[2]) * 16.0f + hi[3]) * 16.0f + lo[0]) * 16.0f + lo[1];
           dst[4 + 16 * (2 * wave + ct) + n] = sum * wsc - s_zs[q];
         }
@@ -623,7 +674,8 @@ __global__ void __launch_bounds__(256, MF_OCC) k_decode_mfma(RkvView v, const fl
 
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && !c->wide && (v.g == 2 || v.g == 4) && v.rope_style == 0;
+  // 2-bit codes, or 4-bit ones (a second plane), in groups of 128
+  return c->blocks_aligned && v.qg == 128 && v.hb != 1 && (v.g == 2 || v.g == 4) && v.rope_style == 0;
 }
 
 template <bool MULTI>
@@ -631,8 +683,15 @@ static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* q
                           int nq, hipStream_t s) {
 #define RKV_MF_LAUNCH(G_, R_)                                                                                              \
   do {                                                                                                                   \
-    if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-    else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);  \
+    if constexpr (!MULTI) {                                                                                                \
+      if (v.hb == 2) {                                                                                                     \
+        if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, true, true>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+        else hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, false, true>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+        break;                                                                                                             \
+      }                                                                                                                    \
+    }                                                                                                                      \
+    if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, false>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+    else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, false>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);  \
   } while (0)
   if (v.g == 4 && share == 1) RKV_MF_LAUNCH(4, 1);
   else if (v.g == 4) RKV_MF_LAUNCH(4, 2);
@@ -656,6 +715,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   if (!rkv_mfma_supported(c)) return RKV_EINVAL;
   const bool multi = nq > 0;
   if (multi && (c->cur_k || !q_pos)) return RKV_EINVAL;
+  if (multi && c->v.hb) return RKV_EINVAL;                   // several query tokens: 2-bit codes only
   if (!multi) nq = 1;
   RkvView v = c->v;
   v.Hq *= nq;                                               // virtual heads
