@@ -55,12 +55,14 @@ __device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
 }
 
 // Eq. 8-9 for one block given its min and max, as quant_params but without IEEE divisions: the
-// division by 3 is a multiplication (error below 1.5 ulp of fp32, which can change the fp16 scale
+// division by 3 (or 15) is a multiplication (error below 1.5 ulp of fp32, which can change the fp16 scale
 // only within 2^-23 of a rounding boundary) and the reciprocal of the scale is v_rcp_f32 refined by
 // one Newton step.
 // meta8: FP8 E4M3 scale rounded up, INT8 zero-point.
-__device__ __forceinline__ void quant_params_nodiv(float mn, float mx, float& s, float& zero, float& inv_s, bool meta8) {
-  const float raw = (mx - mn) * 0.33333334f;
+// inv_qmax: 1 / (2^bits - 1) rounded to fp32.
+__device__ __forceinline__ void quant_params_nodiv(float mn, float mx, float& s, float& zero, float& inv_s, bool meta8,
+                                                   float inv_qmax = 0.33333334f) {
+  const float raw = (mx - mn) * inv_qmax;
   if (meta8) {
     s = rkv_e4m3_round_up(raw);
     if (s == 0.0f) {
@@ -98,7 +100,9 @@ __device__ __forceinline__ void fused_round_consts(float zero, float& base, floa
 }
 
 // bx, rg, b: the workgroup's place in the (3 x slabs, rotation groups, sequences) grid
-template <int G>
+// HI: 4-bit codes.  The same arithmetic with 15 steps; the upper two bits of every code go to a
+// second plane with the layout of the first (a second image in LDS, written the same way).
+template <int G, bool HI>
 __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                  int n_new, int slab0, int bx, int rg, int b) {
   constexpr int PL = 2 * G;                    // value channels per lane
@@ -109,8 +113,12 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   // key roles: the fp16 keys of one K tile, [16 tokens][STRIDE16] pieces, later overwritten by the two
   // halves of the tile image (2 x 128 G dwords); value role: per wave the partial V dwords of its 8
   // tokens, [wave][i][lane]
+  // (with 4-bit codes: twice the images - 4 x 128 G and 8 x 64 PL dwords -, which still fit)
+  static_assert(16 * STRIDE16 * 4 >= 8 * 64 * PL && 16 * STRIDE16 * 4 >= 4 * 128 * G, "the images of both planes fit the key tile's space");
   __shared__ __attribute__((aligned(16))) uint32_t lds[16 * STRIDE16 * 4 > 4 * 64 * PL ? 16 * STRIDE16 * 4 : 4 * 64 * PL];
   uint32_t* img = lds;
+  uint32_t* imgh = lds + (PL == 8 ? 2048 : 1024);          // the upper plane's images: after 2 x 128 G (keys) or 4 x 64 PL (values) dwords
+  constexpr float QMAX = HI ? 15.0f : 3.0f, INV_QMAX = HI ? 0.06666667f : 0.33333334f;
   __shared__ uint32_t meta[32 * G];
   __shared__ float2 s_mm[2][2][16][G];         // [dword half][product pair][token][head] (min, max) of a quarter block
   const int tid = threadIdx.x, lane = tid & 63;
@@ -236,7 +244,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       const float2 m0 = s_mm[0][0][col][ah], m1 = s_mm[0][1][col][ah], m2 = s_mm[1][0][col][ah], m3 = s_mm[1][1][col][ah];
       float sc, zero_h, inv;
       quant_params_nodiv(fminf(fminf(m0.x, m1.x), fminf(m2.x, m3.x)) * rs, fmaxf(fmaxf(m0.y, m1.y), fmaxf(m2.y, m3.y)) * rs, sc,
-                         zero_h, inv, v.meta8);
+                         zero_h, inv, v.meta8, INV_QMAX);
       const float inv2_h = inv * rs;
       if (wave == 0 && q < G) meta[col * G + ah] = rkv_pack_meta(sc, zero_h);
       float base_h, add_h;
@@ -245,7 +253,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       for (int a = 0; a < G; ++a) {
         const int src4 = 4 * (col + 16 * a);
         const float inv2 = lane_read(inv2_h, src4), add = lane_read(add_h, src4), base = lane_read(base_h, src4);
-        const float top = base + 3.0f;
+        const float top = base + QMAX;
         uint32_t word = 0;
 #pragma unroll
         for (int ppl = 0; ppl < 2; ++ppl)
@@ -254,9 +262,17 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
             const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], inv2, add), base, top);
             word += __float_as_uint(c) << (16 * ppl + 4 * rr);
           }
-        // the 8 float bit patterns add up to bits(base) * 0x11111111 plus the packed codes, mod 2^32;
+        // the 8 float bit patterns add up to bits(base) * 0x11111111 plus the packed codes, mod 2^32
+        // (a code per nibble: 4-bit codes just fit);
         // this wave's codes sit 2 pph bits up in the dword it shares with the wave of the other pph
-        img[pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = (word - __float_as_uint(base) * 0x11111111u) << (2 * pph);
+        word -= __float_as_uint(base) * 0x11111111u;
+        const int io = pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d;
+        if constexpr (HI) {
+          img[io] = (word & 0x33333333u) << (2 * pph);
+          imgh[io] = ((word >> 2) & 0x33333333u) << (2 * pph);
+        } else {
+          img[io] = word << (2 * pph);
+        }
       }
     }
     __syncthreads();
@@ -266,7 +282,10 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       const int off = tid + 256 * k;
       if (off < 128 * G) {
         const int t = ts + ti * 16 + rkv_k_tile_token(G, off);
-        if (t >= t_lo && t < t_hi) rkv_st_stream(&v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], img[off] | img[128 * G + off]);
+        if (t >= t_lo && t < t_hi) {
+          rkv_st_stream(&v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], img[off] | img[128 * G + off]);
+          if constexpr (HI) rkv_st_stream(&v.kh[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], imgh[off] | imgh[128 * G + off]);
+        }
       }
     }
     for (int i = tid; i < 16 * G; i += 256) {
@@ -284,12 +303,20 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     if (!(t >= t_lo && t < t_hi)) keep[tau >> 4] |= 3u << rkv_v_shift(tau);
   }
   const size_t vbase = rkv_v_slabbase(v, b, rg, slab);
-  uint32_t oldv[G];
+  uint32_t oldv[G], oldvh[HI ? G : 1];
 #pragma unroll
   for (int k = 0; k < G; ++k) oldv[k] = 0;
+  if constexpr (HI) {
+#pragma unroll
+    for (int k = 0; k < G; ++k) oldvh[k] = 0;
+  }
   if (keep[0] | keep[1]) {
 #pragma unroll
     for (int k = 0; k < G; ++k) oldv[k] = v.vc[vbase + tid + 256 * k];
+    if constexpr (HI) {
+#pragma unroll
+      for (int k = 0; k < G; ++k) oldvh[k] = v.vh[vbase + tid + 256 * k];
+    }
   }
   uint32_t vraw[8][PL / 2];                                // rows of this wave's 8 tokens: lane = PL consecutive channels
 #pragma unroll
@@ -334,14 +361,18 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   float sc_v, zero_v, inv_v, base_v, add_v;
   {
     const h2 pr = as_h2(mine);
-    quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v, v.meta8);
+    quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v, v.meta8, INV_QMAX);
     fused_round_consts(zero_v, base_v, add_v);
     const int tau = 8 * wave + (lane & (LPB - 1));
     if ((lane & (LPB - 1)) < 8) meta[tau * G + blk] = rkv_pack_meta(sc_v, zero_v);
   }
-  uint32_t vword[PL];
+  uint32_t vword[PL], vwordh[HI ? PL : 1];
 #pragma unroll
   for (int i = 0; i < PL; ++i) vword[i] = 0;
+  if constexpr (HI) {
+#pragma unroll
+    for (int i = 0; i < PL; ++i) vwordh[i] = 0;
+  }
   uint32_t bias = 0;
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
@@ -349,18 +380,28 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     if (tau < tau_first || tau > tau_last) continue;       // wave-uniform
     const int src4 = 4 * ((lane & ~(LPB - 1)) | k);
     const float inv = lane_read(inv_v, src4), add = lane_read(add_v, src4), base = lane_read(base_v, src4);
-    const float top = base + 3.0f;
+    const float top = base + QMAX;
     const int sh = rkv_v_shift(tau);
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
       const h2 pr = as_h2(vraw[k][i >> 1]);
       const float c = __builtin_amdgcn_fmed3f(fmaf((float)pr[i & 1], inv, add), base, top);
-      vword[i] += __float_as_uint(c) << sh;
+      if constexpr (HI) {
+        const uint32_t code = __float_as_uint(c) - __float_as_uint(base);
+        vword[i] += (code & 3u) << sh;
+        vwordh[i] += (code >> 2) << sh;
+      } else {
+        vword[i] += __float_as_uint(c) << sh;
+      }
     }
-    bias += __float_as_uint(base) << sh;
+    if constexpr (!HI) bias += __float_as_uint(base) << sh;
   }
 #pragma unroll
   for (int i = 0; i < PL; ++i) img[(wave * PL + i) * 64 + lane] = vword[i] - bias;
+  if constexpr (HI) {
+#pragma unroll
+    for (int i = 0; i < PL; ++i) imgh[(wave * PL + i) * 64 + lane] = vwordh[i];
+  }
   __syncthreads();
   // V slab: dword idx = (((w*G + hh)*16 + nn)*2 + ct)*2 + d, channel c = 128hh + 32w + 16ct + nn;
   // waves 2d and 2d+1 hold the two halves of its 16 token slots
@@ -374,6 +415,11 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     uint32_t word = img[((2 * d) * PL + i) * 64 + ln] | img[((2 * d + 1) * PL + i) * 64 + ln];
     if (keep[d]) word |= oldv[k] & keep[d];
     if (keep[d] != 0xffffffffu) rkv_st_stream(&v.vc[vbase + idx], word);
+    if constexpr (HI) {
+      word = imgh[((2 * d) * PL + i) * 64 + ln] | imgh[((2 * d + 1) * PL + i) * 64 + ln];
+      if (keep[d]) word |= oldvh[k] & keep[d];
+      if (keep[d] != 0xffffffffu) rkv_st_stream(&v.vh[vbase + idx], word);
+    }
   }
   for (int i = tid; i < 32 * G; i += 256) {
     const int tau = i / G;
@@ -381,10 +427,10 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   }
 }
 
-template <int G>
-__global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
-                                                     int n_new, int slab0) {
-  append_mfma_body<G>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+template <int G, bool HI>
+__global__ void __launch_bounds__(256, HI ? 4 : 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+                                                              int n_new, int slab0) {
+  append_mfma_body<G, HI>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // One decode step's write half and query preparation in one launch: the first 3 * n_slabs
@@ -392,12 +438,12 @@ __global__ void __launch_bounds__(256, 6) k_append_mfma(RkvView v, const __half*
 // rest prepare that rotation group's query heads (two heads per workgroup) for the decode kernel,
 // which saves a launch of its own for a few microseconds of work.  The query's default position
 // is the appended token's: one past the last token the view knows of.
-template <int G>
+template <int G, bool HI>
 __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                    int slab0, int n_append_blocks, const __half* __restrict__ q,
                                                    const int* __restrict__ q_pos, float* __restrict__ qr, int share) {
   if ((int)blockIdx.x < n_append_blocks) {
-    append_mfma_body<G>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+    append_mfma_body<G, HI>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
     return;
   }
   const int rep = v.Hq / v.Hkv;
@@ -407,7 +453,8 @@ __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* _
 
 bool rkv_append_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && !c->wide && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
+  // 2-bit codes, or 4-bit ones (a second plane), in groups of 128
+  return c->blocks_aligned && v.qg == 128 && v.hb != 1 && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 
 // max_slabs: most 32-token slabs any sequence's new tokens touch, or 0 to work it out for n_new
@@ -426,8 +473,11 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   }
   dim3 grid(3 * max_slabs, v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  if (v.g == 4) hipLaunchKernelGGL(k_append_mfma<4>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  else hipLaunchKernelGGL(k_append_mfma<2>, grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  if (v.hb == 2) {
+    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    else hipLaunchKernelGGL((k_append_mfma<2, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  } else if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, false>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  else hipLaunchKernelGGL((k_append_mfma<2, false>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   return rkv_check_launch();
 }
@@ -440,7 +490,10 @@ int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const 
   int max_slabs = 1;                                        // one token touches one slab of its sequence
   const int n_append = 3 * max_slabs, rep = v.Hq / v.Hkv;
   dim3 grid(n_append + v.g * rep / 2, v.NRG, v.B);
-  if (v.g == 4) hipLaunchKernelGGL(k_step_mfma<4>, grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  else hipLaunchKernelGGL(k_step_mfma<2>, grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  if (v.hb == 2) {
+    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+    else hipLaunchKernelGGL((k_step_mfma<2, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  } else if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, false>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  else hipLaunchKernelGGL((k_step_mfma<2, false>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
   return rkv_check_launch();
 }
