@@ -238,27 +238,29 @@ def test_error_codes():
     assert ei.value.code == -5
 
 
-def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag="", meta_format=0, rep=1, rope_theta=10000.0):
+def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag="", meta_format=0, rep=1, rope_theta=10000.0,
+                bits=2):
     """One (sequence, rotation group of 4 heads) slice of a full-size run against the oracle: a
     rotation group's codes and attention outputs depend on nothing outside the slice.  The codes
     must equal the oracle's outside the documented rounding ties; the attention output is then
     compared on the GPU's own codes, so that a tie cannot hide in (or leak into) the tolerance.
     exp: export_codes() tensors already on the host (numpy)."""
     ocfg = O.OracleConfig(batch=1, n_q_heads=4 * rep, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=max_sinks,
-                          meta_format=meta_format, rope_theta=rope_theta)
+                          meta_format=meta_format, rope_theta=rope_theta, bits=bits)
     hq = slice(4 * rep * rg, 4 * rep * (rg + 1))               # the query heads of the group's four KV heads
     oc = O.cache_new(ocfg, None if perm is None else perm[512 * rg:512 * (rg + 1)] - 512 * rg)
     O.quantize_append(oc, ks, vs, ms)
-    sl_c, sl_m = slice(128 * rg, 128 * (rg + 1)), slice(4 * rg, 4 * rg + 4)
+    nb = 512 // (4 if bits == 2 else 2)                         # canonical bytes of the group's 512 codes
+    sl_c, sl_m = slice(nb * rg, nb * (rg + 1)), slice(4 * rg, 4 * rg + 4)
     g = {}
     for name in ("k", "v"):
-        g[name + "_codes"] = O.unpack_canonical(exp[name + "_codes"][b:b + 1, :, sl_c])
+        g[name + "_codes"] = O.unpack_canonical(exp[name + "_codes"][b:b + 1, :, sl_c], bits)
         g[name + "_scale"] = exp[name + "_scale"][b:b + 1, :, sl_m].astype(np.float64)
         g[name + "_zero"] = exp[name + "_zero"][b:b + 1, :, sl_m].astype(np.float64)
     P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"],
-                    f"{tag} b={b} rg={rg} K", rot_span=512, meta_format=meta_format)
+                    f"{tag} b={b} rg={rg} K", rot_span=512, meta_format=meta_format, bits=bits)
     P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"],
-                    f"{tag} b={b} rg={rg} V", meta_format=meta_format)
+                    f"{tag} b={b} rg={rg} V", meta_format=meta_format, bits=bits)
     for name, val in g.items():                                # attention on the GPU's own codes
         setattr(oc, name, val)
     ref, lse_ref = O.decode_attention(oc, q[b:b + 1, hq])
@@ -274,17 +276,17 @@ def export_host(cache):
     return {k: v.cpu().numpy() for k, v in exp.items()}
 
 
-@pytest.mark.parametrize("meta_format", [0, 1])
-def test_full_size_config2_sampled(meta_format):
+@pytest.mark.parametrize("meta_format,bits", [(0, 2), (1, 2), (0, 4)])
+def test_full_size_config2_sampled(meta_format, bits):
     """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, then one rkv_decode_step (the last
     token's append and the attention on the matrix-core path).  The oracle recomputes sampled (sequence, rotation group) slices - a
     rotation group's codes and attention outputs depend on nothing outside the slice.  Once with
-    fp16 metadata, once with the FP8 scale / INT8 zero-point storage."""
+    fp16 metadata, once with the FP8 scale / INT8 zero-point storage, once with 4-bit codes."""
     w = S.WORKLOADS["cfg2"]
     T = w.context
     cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=4,
-                      rot_heads=4, perm_span=128, meta_format=meta_format)
+                      rot_heads=4, perm_span=128, meta_format=meta_format, bits=bits)
     perm = calibrated_perm(w, cfg)
     cache = R.RkvCache(cfg)
     cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
@@ -318,7 +320,8 @@ def test_full_size_config2_sampled(meta_format):
     assert np.isfinite(out).all()
     for (b, rg) in samples:
         ks, vs, ms = keep[(b, rg)]
-        check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag=f"full-size meta_format={meta_format}", meta_format=meta_format)
+        check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag=f"full-size meta_format={meta_format} bits={bits}",
+                    meta_format=meta_format, bits=bits)
 
 
 def test_full_size_long_context_sampled():
@@ -784,8 +787,10 @@ def test_shared_scratch_reused_across_caches():
             assert torch.equal(out, refs[i]), f"repetition {rep}, cache {i}"
 
 
-def test_sequences_of_different_lengths():
-    """rkv_quantize_append_ragged: three sequences are prefilled with 300 / 37 / 513 tokens in one
+@pytest.mark.parametrize("bits", [2, 4])
+def test_sequences_of_different_lengths(bits):
+    """(With 2-bit codes and with 4-bit codes, which the matrix-core kernels read as two planes.)
+    rkv_quantize_append_ragged: three sequences are prefilled with 300 / 37 / 513 tokens in one
     call, extended by 5 / 0 / 40 in a second, then take three ordinary single-token steps.  Each
     sequence is compared with an oracle cache of its own (batch 1): codes under the tie protocol,
     sink rows, and - on the GPU's own codes - decode attention on both kernels with the default
@@ -793,7 +798,7 @@ def test_sequences_of_different_lengths():
     query tokens per step."""
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     B = 3
-    cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=600, max_sinks=4, rot_heads=4)
+    cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=600, max_sinks=4, rot_heads=4, bits=bits)
     steps = [[300, 37, 513], [5, 0, 40], [1, 1, 1], [1, 1, 1], [1, 1, 1]]
     total = [sum(st[b] for st in steps) for b in range(B)]
     data = [S.make_kv(w, total[b] + 1, batch=1, layer=b) for b in range(B)]       # one spare token for the current-token call
@@ -825,9 +830,9 @@ def test_sequences_of_different_lengths():
     for b in range(B):
         gb = {name: arr[b:b + 1, :total[b]] for name, arr in g.items()}
         P.compare_codes(ocs[b].k_rot, ocs[b].k_codes, ocs[b].k_scale, ocs[b].k_zero, gb["k_codes"], gb["k_scale"], gb["k_zero"],
-                        f"ragged b={b} K", rot_span=512)
+                        f"ragged b={b} K", rot_span=512, bits=bits)
         P.compare_codes(ocs[b].v_in, ocs[b].v_codes, ocs[b].v_scale, ocs[b].v_zero, gb["v_codes"], gb["v_scale"], gb["v_zero"],
-                        f"ragged b={b} V")
+                        f"ragged b={b} V", bits=bits)
         assert sinks["count"][b] == len(ocs[b].sink_pos[0])
         for i, pos in enumerate(ocs[b].sink_pos[0]):
             assert sinks["pos"][b, i] == pos
@@ -855,12 +860,16 @@ def test_sequences_of_different_lengths():
     cache.set_decode_path(0)
     q2 = np.stack([S.make_q(w, batch=B, step=i) for i in range(2)], axis=1)
     q_pos = np.array([[total[b] - 2, total[b] - 1] for b in range(B)], dtype=np.int32)
-    out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
-    torch.cuda.synchronize()
-    for b in range(B):
-        ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
-        e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
-        assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
+    if bits == 2:
+        out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
+        torch.cuda.synchronize()
+        for b in range(B):
+            ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
+            e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
+            assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
+    else:                                                      # several query tokens per step: 2-bit codes only
+        with pytest.raises(R.RkvError):
+            cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
     # what the entry point refuses
     with pytest.raises(R.RkvError) as ei:
         cache.quantize_append_ragged(P.gpu(np.zeros((B, 50, 8, 128), np.float16)), P.gpu(np.zeros((B, 50, 8, 128), np.float16)), [1, 1, 50])
@@ -871,17 +880,19 @@ def test_sequences_of_different_lengths():
     assert cache.lengths == [0, 0, 0]
 
 
-@pytest.mark.parametrize("hq,hkv,g,ragged", [(8, 8, 4, False), (16, 4, 4, False), (4, 4, 2, True), (8, 8, 8, False)])
-def test_one_call_decode_step_equals_the_two_calls(hq, hkv, g, ragged):
+@pytest.mark.parametrize("hq,hkv,g,ragged,bits", [(8, 8, 4, False, 2), (16, 4, 4, False, 2), (4, 4, 2, True, 2), (8, 8, 8, False, 2),
+                                                  (8, 8, 4, True, 4), (8, 4, 2, False, 4), (8, 8, 4, False, 3)])
+def test_one_call_decode_step_equals_the_two_calls(hq, hkv, g, ragged, bits):
     """rkv_decode_step (append + attention in one call; on the matrix-core configurations the
     token's compression and the query's preparation share a launch) against rkv_quantize_append
     followed by rkv_decode_attention on a second cache with the same contents: outputs, codes and
     metadata bit for bit, over several steps that cross a tile and a slab boundary; also with
     sequences of different lengths, explicit query positions, and on a configuration that falls
-    back to the two calls (rotation over 8 heads)."""
+    back to the two calls (rotation over 8 heads; 3-bit codes).  4-bit codes take the one-launch
+    path like 2-bit ones."""
     w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
     B, T0, steps = 2, 29, 6
-    cfg = R.RkvConfig(batch=B, n_q_heads=hq, n_kv_heads=hkv, max_tokens=128, max_sinks=4, rot_heads=g)
+    cfg = R.RkvConfig(batch=B, n_q_heads=hq, n_kv_heads=hkv, max_tokens=128, max_sinks=4, rot_heads=g, bits=bits)
     k, v, mask = S.make_kv(w, T0 + steps, batch=B)
     a, b = R.RkvCache(cfg), R.RkvCache(cfg)
     for c in (a, b):
