@@ -89,20 +89,26 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
   }
   const int tok_stride = g == 1 ? 2 : 4;                       // dwords between consecutive tokens of a tile
   // bits above the low two (wider codes).  4-bit codes: a second plane, same dword and shifts;
-  // 3-bit codes: the third bits of a lane's PL channels are PL consecutive bits of the token's row
-  // in the high-bit plane, inside one dword
-  const int hb = v.hb, hbit = rg * n + PL * lane;
+  // 3-bit codes: the third bits sit in the dword that belongs to the lane's dword and its
+  // neighbour, at places that follow from the shifts (rkv_h1_loc)
+  const int hb = v.hb;
+  int hsh[PL];
+#pragma unroll
+  for (int i = 0; i < PL; ++i) {
+    hsh[i] = sh[i];
+    if (hb == 1) rkv_h1_loc((size_t)dw_off, sh[i], hsh[i]);
+  }
   for (int t = t0 + wave; t < t1; t += 4) {
     float x[PL];
     const uint32_t w = v.kc[rkv_k_tilebase(v, b, rg, t >> 4) + dw_off + (t & 15) * tok_stride];
     uint32_t hw = 0u;
     if (hb == 2) hw = v.kh[rkv_k_tilebase(v, b, rg, t >> 4) + dw_off + (t & 15) * tok_stride];
-    else if (hb == 1) hw = v.kh[((size_t)b * v.Tpad + t) * (size_t)(v.E / 32) + (hbit >> 5)] >> (hbit & 31);
+    else if (hb == 1) hw = v.kh[(rkv_k_tilebase(v, b, rg, t >> 4) + dw_off + (t & 15) * tok_stride) >> 1];
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
       float sc, zero;
       rkv_load_meta(v, v.km, mi0[i] + (size_t)t * gm, sc, zero);
-      const uint32_t hi = hb == 2 ? ((hw >> sh[i]) & 3u) : ((hw >> i) & (uint32_t)hb);
+      const uint32_t hi = (hw >> hsh[i]) & (hb == 2 ? 3u : (uint32_t)hb);
       x[i] = sc * ((float)(((w >> sh[i]) & 3u) | (hi << 2)) - zero);          // Eq. 7
     }
     fwht_lanes_d<PL>(x, lane, 6);                               // inverse rotation (H is its own inverse)
@@ -172,10 +178,15 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
     for (int tt = 0; tt < t1 - t0; tt += 16) {
       int sh;
       const size_t wi = rkv_v_dword(v, b, rg, t0 + tt, c, sh);
-      const uint32_t w = v.vc[wi], w2 = v.hb == 2 ? v.vh[wi] : 0u;
+      const uint32_t w = v.vc[wi], w2 = v.hb == 2 ? v.vh[wi] : (v.hb == 1 ? v.vh[wi >> 1] : 0u);
       for (int k = 0; k < 16 && tt + k < t1 - t0; ++k) {
-        uint32_t code = ((w >> rkv_v_shift(k)) & 3u) | (((w2 >> rkv_v_shift(k)) & 3u) << 2);
-        if (v.hb == 1) code |= rkv_vhi_get(v, b, rg, t0 + tt + k, c);
+        uint32_t code = (w >> rkv_v_shift(k)) & 3u;
+        if (v.hb == 2) code |= ((w2 >> rkv_v_shift(k)) & 3u) << 2;
+        else if (v.hb == 1) {
+          int bit;
+          rkv_h1_loc(wi, rkv_v_shift(k), bit);
+          code |= ((w2 >> bit) & 1u) << 2;
+        }
         const float val = s_vs[blk * GEN_CHUNK + tt + k] * ((float)code - s_vz[blk * GEN_CHUNK + tt + k]);
 #pragma unroll
         for (int r = 0; r < 8; ++r)

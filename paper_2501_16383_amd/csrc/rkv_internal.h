@@ -29,8 +29,11 @@
 // and add
 //   K high, V high   4-bit codes: the upper two bits, in arrays laid out exactly as K codes and
 //             V codes (same dword, same bit position), so that the matrix-core kernels read them
-//             as a second plane; 3-bit codes: the third bit in [batch][Tpad] rows of E / 32 dwords,
-//             bit c of a row belonging to rotated channel (K) or channel (V) c of the layer;
+//             as a second plane; 3-bit codes: the third bit, one dword for each aligned pair of
+//             dwords (2p, 2p + 1) of K codes / V codes (the 32 codes of one matrix operand), the
+//             bit of the code at bit 2m of dword 2p + x sitting at bit 4 (m >> 1) + 2 x + (m & 1):
+//             shifting the dword right by k = 0..3 and masking every fourth bit yields the four
+//             operand dwords of FP4 nibbles, as the 2-bit unpacking does for the low bits;
 //   K meta, V meta   128 / quant_group entries in place of each one (gid then counts blocks of
 //             quant_group reordered positions).
 // Those settings run on the general kernels only.
@@ -130,10 +133,12 @@ __host__ __device__ inline size_t rkv_meta_index(const RkvView& v, int b, int t,
   int rg = G / v.gm, j = G - rg * v.gm;
   return ((size_t)(b * v.NRG + rg) * (size_t)v.Tpad + t) * v.gm + j;
 }
-// Third bit of a 3-bit code of channel ch (0..E) of token t: position in a high-bit plane (hb == 1)
-__host__ __device__ inline size_t rkv_hi_dword(const RkvView& v, int b, int t, int ch, int& shift) {
-  shift = ch & 31;
-  return ((size_t)b * v.Tpad + t) * (size_t)(v.E / 32) + (ch >> 5);
+// Third bit of a 3-bit code (hb == 1): from the place of its low two bits (dword index and shift
+// in K codes / V codes) to the dword index and bit in K high / V high
+__host__ __device__ inline size_t rkv_h1_loc(size_t lo_index, int lo_shift, int& bit) {
+  const int m = lo_shift >> 1;
+  bit = 4 * (m >> 1) + 2 * (int)(lo_index & 1) + (m & 1);
+  return lo_index >> 1;
 }
 // The bits above the low two of the code of (rotated) channel c of rotation group rg, token t,
 // already shifted to their place in the code (0 with 2-bit codes)
@@ -144,8 +149,9 @@ __device__ inline uint32_t rkv_khi_get(const RkvView& v, int b, int rg, int t, i
     const uint32_t w = v.kh[rkv_k_dword(v, b, rg, t, c, sh)];
     return ((w >> sh) & 3u) << 2;
   }
-  const uint32_t w = v.kh[rkv_hi_dword(v, b, t, rg * v.n + c, sh)];
-  return ((w >> sh) & 1u) << 2;
+  int bit;
+  const uint32_t w = v.kh[rkv_h1_loc(rkv_k_dword(v, b, rg, t, c, sh), sh, bit)];
+  return ((w >> bit) & 1u) << 2;
 }
 __device__ inline uint32_t rkv_vhi_get(const RkvView& v, int b, int rg, int t, int c) {
   if (v.hb == 0) return 0u;
@@ -154,8 +160,9 @@ __device__ inline uint32_t rkv_vhi_get(const RkvView& v, int b, int rg, int t, i
     const uint32_t w = v.vh[rkv_v_dword(v, b, rg, t, c, sh)];
     return ((w >> sh) & 3u) << 2;
   }
-  const uint32_t w = v.vh[rkv_hi_dword(v, b, t, rg * v.n + c, sh)];
-  return ((w >> sh) & 1u) << 2;
+  int bit;
+  const uint32_t w = v.vh[rkv_h1_loc(rkv_v_dword(v, b, rg, t, c, sh), sh, bit)];
+  return ((w >> bit) & 1u) << 2;
 }
 
 __device__ inline uint32_t rkv_pack_meta(float scale, float zero) {

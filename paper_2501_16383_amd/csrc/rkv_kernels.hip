@@ -204,9 +204,10 @@ __global__ void __launch_bounds__(256) k_sinks(RkvView v, const __half* __restri
 //   positions in LDS (Sec. 4.1), reduce min/max per block of 128, Eq. 6-9, and OR the codes into LDS
 //   images of the physical tile, which are then written with whole-dword stores.  With codes wider
 //   than 2 bits the images take the low two bits; the upper two bits of 4-bit codes go to a second
-//   pair of images (the planes have the same layout), and with 3-bit codes each wave collects the
-//   third bits of its token in an image of that token's piece of the high-bit rows, written after
-//   the token is done.
+//   pair of images (the planes have the same layout), the third bits of 3-bit codes to images of
+//   their plane (one dword per pair of dwords of the low plane; a V dword of that plane also holds
+//   the bits of the slab's other 16 tokens, which another workgroup may be writing: it is updated
+//   with atomic operations on this tile's bits only).
 // ---------------------------------------------------------------------------------------------
 
 template <int PL>
@@ -216,10 +217,10 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
   float* zbuf = reinterpret_cast<float*>(smem);            // [4][U]
   uint32_t* imgK = smem + 4 * U;                            // [U]  (16 tokens x U codes)
   uint32_t* imgV = imgK + U;                                // [U]  (one dword per channel)
-  const int hb = v.hb, hdw = hb == 1 ? U / 32 : 0;          // 3-bit codes: dwords of a token's third bits within the unit
-  uint32_t* imgKh = imgV + U;                               // 3-bit: [4 waves][hdw]; 4-bit: [U], as imgK
-  uint32_t* imgVh = imgKh + (hb == 2 ? U : 4 * hdw);        // 3-bit: [4 waves][hdw]; 4-bit: [U], as imgV
-  const int himg = hb == 2 ? 2 * U : 8 * hdw;               // dwords of the two together
+  const int hb = v.hb;
+  uint32_t* imgKh = imgV + U;                               // 4-bit: [U], as imgK; 3-bit: [U / 2]
+  uint32_t* imgVh = imgKh + (hb == 2 ? U : U / 2);          // 4-bit: [U], as imgV; 3-bit: [U], this tile's bits of the channel's dword
+  const int himg = hb == 2 ? 2 * U : (hb == 1 ? U + U / 2 : 0);   // dwords of the two together
   const float qmax = (float)((4 << hb) - 1);
   const int blk_lanes = v.qg >> 3;                          // lanes (8 values each) of one quantization block
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -301,7 +302,11 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
             const int off = rkv_k_off(g, m, c, sh);
             atomicOr(&imgK[r * 128 * g + off], (code & 3u) << sh);
             if (hb == 2) atomicOr(&imgKh[r * 128 * g + off], (code >> 2) << sh);
-            else if (hb == 1) atomicOr(&imgKh[wave * hdw + (cr >> 5)], (code >> 2) << (cr & 31));
+            else if (hb == 1) {
+              int bit;
+              const size_t hi_idx = rkv_h1_loc((size_t)(r * 128 * g + off), sh, bit);
+              atomicOr(&imgKh[hi_idx], (code >> 2) << bit);
+            }
           }
           if ((lane & (blk_lanes - 1)) == 0) rkv_store_meta(v, v.km, rkv_meta_index(v, b, t, (ubase + pos) / v.qg), sc, zero);
         }
@@ -331,36 +336,20 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
           float sc, zero, inv;
           quant_params(mn, mx, sc, zero, inv, v.meta8, qmax);
           const int sh = rkv_v_shift(t & 31);
-          uint32_t hi = 0;                                  // 3-bit codes: this lane's 8 channels are 8 consecutive bits of the row
+          int hbit = 0;                                     // 3-bit codes: the token's place in the third-bit dword of a channel
+          rkv_h1_loc((size_t)(tile & 1), sh, hbit);
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             const uint32_t code = quant_code(u[i], inv, zero, qmax);
             atomicOr(&imgV[pos + i], (code & 3u) << sh);
             if (hb == 2) atomicOr(&imgVh[pos + i], (code >> 2) << sh);
-            hi |= (code >> 2) << i;
+            else if (hb == 1) atomicOr(&imgVh[pos + i], (code >> 2) << hbit);
           }
-          if (hb == 1) atomicOr(&imgVh[wave * hdw + (pos >> 5)], hi << (pos & 31));
           if ((lane & (blk_lanes - 1)) == 0) rkv_store_meta(v, v.vm, rkv_meta_index(v, b, t, (ubase + pos) / v.qg), sc, zero);
         }
       }
     }
     __syncthreads();
-    if (hb == 1) {
-      // the token's third bits: whole dwords of its rows, then cleared for the wave's next token
-      // (the barrier in the middle of the next round orders that before the next use)
-      if (active) {
-        int sh;
-        const size_t hrow = rkv_hi_dword(v, b, t, ubase, sh);
-        for (int i = lane; i < hdw; i += 64) {
-          v.kh[hrow + i] = imgKh[wave * hdw + i];
-          v.vh[hrow + i] = imgVh[wave * hdw + i];
-        }
-      }
-      for (int i = lane; i < hdw; i += 64) {
-        imgKh[wave * hdw + i] = 0;
-        imgVh[wave * hdw + i] = 0;
-      }
-    }
   }
 
   // ---- write the images.  K: every 16-byte piece of a tile belongs to one token.
@@ -371,8 +360,18 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
     if (t >= t_lo && t < t_hi) {
       v.kc[rkv_k_tilebase(v, b, rg0 + r, tile) + off] = imgK[idx];
       if (hb == 2) v.kh[rkv_k_tilebase(v, b, rg0 + r, tile) + off] = imgKh[idx];
+      else if (hb == 1 && !(idx & 1)) v.kh[(rkv_k_tilebase(v, b, rg0 + r, tile) + off) >> 1] = imgKh[idx >> 1];
     }
   }
+  // third-bit places of this tile's tokens that this call writes (the same in every channel's dword)
+  uint32_t clr = 0;
+  if (hb == 1)
+    for (int m = 0; m < 16; ++m) {
+      const int t = tile * 16 + m;
+      int bit;
+      rkv_h1_loc((size_t)(tile & 1), rkv_v_shift(t & 31), bit);
+      if (t >= t_lo && t < t_hi) clr |= 1u << bit;
+    }
   // V: a dword holds 16 token slots of one channel; keep the slots of tokens not in this call.
   for (int idx = tid, k = 0; idx < U; idx += 256, ++k) {
     const int r = idx / n, c = idx - r * n;
@@ -384,6 +383,9 @@ __global__ void __launch_bounds__(256) k_append(RkvView v, const __half* __restr
       w = imgVh[idx];
       if (keep) w |= (U <= 1024 ? oldv2[k & 3] : v.vh[a]) & keep;
       v.vh[a] = w;
+    } else if (hb == 1) {
+      atomicAnd(&v.vh[a >> 1], ~clr);
+      atomicOr(&v.vh[a >> 1], imgVh[idx]);
     }
   }
 }
@@ -605,7 +607,7 @@ int rkv_launch_append(rkv_cache* c, const __half* k, const __half* vv, int n_new
   const int U = v.span > v.n ? v.span : v.n;
   const int tile0 = v.len >> 4, tile1 = (v.len + n_new - 1) >> 4;
   dim3 grid(tile1 - tile0 + 1, v.E / U, v.B);
-  const size_t lds = (size_t)6 * U * 4 + (v.hb == 2 ? (size_t)8 * U : v.hb == 1 ? (size_t)U : 0);   // the kernel's images, see there
+  const size_t lds = (size_t)6 * U * 4 + (v.hb == 2 ? (size_t)8 * U : v.hb == 1 ? (size_t)6 * U : 0);   // the kernel's images, see there
   void (*fn)(RkvView, const __half*, const __half*, int, int, int) = nullptr;
   switch (v.n / 64) {
     case 2: fn = k_append<2>; break;
@@ -763,10 +765,11 @@ __global__ void k_import(RkvView v, int T, const uint8_t* kc, const float* ks, c
       atomicOr(&v.vc[a], (vcode & 3u) << sh);
       if (v.hb == 2) atomicOr(&v.vh[a], (vcode >> 2) << sh);
       if (v.hb == 1) {
-        a = rkv_hi_dword(v, b, t, cr, sh);
-        atomicOr(&v.kh[a], (kcode >> 2) << sh);
-        a = rkv_hi_dword(v, b, t, i, sh);
-        atomicOr(&v.vh[a], (vcode >> 2) << sh);
+        int bit;
+        a = rkv_h1_loc(rkv_k_dword(v, b, cr / v.n, t, cr % v.n, sh), sh, bit);
+        atomicOr(&v.kh[a], (kcode >> 2) << bit);
+        a = rkv_h1_loc(rkv_v_dword(v, b, i / v.n, t, i % v.n, sh), sh, bit);
+        atomicOr(&v.vh[a], (vcode >> 2) << bit);
       }
     }
     if (j < v.NG) {
