@@ -83,6 +83,18 @@ __device__ __forceinline__ v8i unpack_fp4(uint32_t d0, uint32_t d1) {
   return r;
 }
 
+// one dword of third bits (3-bit codes; bit 4j + k belongs to nibble j of operand dword k) -> four
+// dwords of FP4 nibbles (value = bit / 2)
+__device__ __forceinline__ v8i unpack_fp4_bits(uint32_t h) {
+  v8i r;
+  r[0] = (int)(h & 0x11111111u);
+  r[1] = (int)((h >> 1) & 0x11111111u);
+  r[2] = (int)((h >> 2) & 0x11111111u);
+  r[3] = (int)((h >> 3) & 0x11111111u);
+  r[4] = r[5] = r[6] = r[7] = 0;
+  return r;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float x) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
@@ -150,15 +162,17 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // rkv_virtual_head) and virtual head hv only attends tokens at positions <= q_lim[b][query token of hv].
 // META8: scales in FP8 E4M3 and zero-points in 8 bits (rkv_load_meta describes the layout); they
 // are widened to the fp16 operands of the small matrix products right after loading.
-// HI: 4-bit codes, c = c_lo + 4 c_hi.  The plane of the upper two bits has the layout of the lower
-// one.  Key phase: it goes through the same unpacking (nibble = c_hi / 2) and meets a copy of the
+// HB = 2: 4-bit codes, c = c_lo + 4 c_hi.  The plane of the upper two bits has the layout of the lower
+// one.  HB = 1: 3-bit codes, the plane of third bits holds one dword per operand (half the size).
+// Key phase: it goes through the same unpacking (nibble = c_hi / 2) and meets a copy of the
 // Hadamard operand with entries +-4 in place of +-1, accumulating onto the low plane's products,
 // so that the big products yield H_128 (c / 2) as before.  Value phase: it accumulates separately
 // and is folded in, times 4, once per chunk.  Sums stay exact: |H_128 (c / 2)| <= 960 < 1024.
-template <int G, int REP, bool MULTI, bool META8, bool HI>
-__global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
+template <int G, int REP, bool MULTI, bool META8, int HB>
+__global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq) {
+  constexpr bool HI = HB != 0;
   constexpr int NH = G * REP;                    // query heads served by this workgroup: REP per KV head
   constexpr int RP = (MF_ACC / (G * REP) < 4) ? MF_ACC / (G * REP) : 4;   // tokens (of a lane's four) per pass of the key phase: MF_ACC score accumulators at most
   __shared__ float s_sc[NH][MF_CH];
@@ -273,7 +287,8 @@ __global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
         cs_s[p] = cs.y;
       }
       const uint4* ktiles = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tw >> 4));
-      const uint4* khtiles = HI ? reinterpret_cast<const uint4*>(v.kh + rkv_k_tilebase(v, b, rg, tw >> 4)) : nullptr;
+      // the plane above the low two bits: 16 bytes per lane and pair of blocks (HB = 2) or 8 (HB = 1)
+      const uint32_t* khtiles = HI ? v.kh + (rkv_k_tilebase(v, b, rg, tw >> 4) >> (HB == 1 ? 1 : 0)) : nullptr;
       const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * (META8 ? G / 2 : G);
 
       uint4 cw[G / 2], cwh[HI ? G / 2 : 1];
@@ -284,7 +299,15 @@ __global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
         for (int pr = 0; pr < G / 2; ++pr) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
         if constexpr (HI) {
 #pragma unroll
-          for (int pr = 0; pr < G / 2; ++pr) cwh[pr] = rkv_ld_stream(khtiles + (size_t)ti * (32 * G) + pr * 64 + lane);
+          for (int pr = 0; pr < G / 2; ++pr) {
+            const size_t li = (size_t)ti * (32 * G) + pr * 64 + lane;
+            if constexpr (HB == 2) {
+              cwh[pr] = rkv_ld_stream(reinterpret_cast<const uint4*>(khtiles) + li);
+            } else {
+              const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(khtiles) + li);
+              cwh[pr] = make_uint4(u.x, u.y, 0, 0);
+            }
+          }
         }
         if constexpr (META8) {
           // the lane's four tokens are consecutive: 4 x 2G bytes in one piece
@@ -336,8 +359,13 @@ __global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
         if constexpr (HI) {
 #pragma unroll
           for (int pr = 0; pr < G / 2; ++pr) {
-            Ah[2 * pr] = unpack_fp4(cwh[pr].x, cwh[pr].y);
-            Ah[2 * pr + 1] = unpack_fp4(cwh[pr].z, cwh[pr].w);
+            if constexpr (HB == 2) {
+              Ah[2 * pr] = unpack_fp4(cwh[pr].x, cwh[pr].y);
+              Ah[2 * pr + 1] = unpack_fp4(cwh[pr].z, cwh[pr].w);
+            } else {
+              Ah[2 * pr] = unpack_fp4_bits(cwh[pr].x);
+              Ah[2 * pr + 1] = unpack_fp4_bits(cwh[pr].y);
+            }
           }
         }
         // scale rows of the 4x4 products: (+-s_0, +-s_1, +-s_2, +-s_3) of token 4q + r, signs of H_g row n & 3
@@ -525,7 +553,7 @@ __global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
     }
     const bool has_head = q < G;
     const uint4* vslab = reinterpret_cast<const uint4*>(v.vc + rkv_v_slabbase(v, b, rg, t0 >> 5));
-    const uint4* vhslab = HI ? reinterpret_cast<const uint4*>(v.vh + rkv_v_slabbase(v, b, rg, t0 >> 5)) : nullptr;
+    const uint32_t* vhslab = HI ? v.vh + (rkv_v_slabbase(v, b, rg, t0 >> 5) >> (HB == 1 ? 1 : 0)) : nullptr;
     const int lidx = wave * (16 * G) + (has_head ? lane : 0);
     const int nslab = min(MF_CH / 32, (len - t0 + 31) >> 5);
     // the softmax and value phases run once per query head of a KV head; the V codes are requested
@@ -540,7 +568,14 @@ __global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
       if (has_head && sl < nslab) vcodes[sl] = rkv_ld_stream(vslab + (size_t)sl * (64 * G) + lidx);
       if constexpr (HI) {
         vhcodes[sl] = make_uint4(0, 0, 0, 0);
-        if (has_head && sl < nslab) vhcodes[sl] = rkv_ld_stream(vhslab + (size_t)sl * (64 * G) + lidx);
+        if (has_head && sl < nslab) {
+          if constexpr (HB == 2) {
+            vhcodes[sl] = rkv_ld_stream(reinterpret_cast<const uint4*>(vhslab) + (size_t)sl * (64 * G) + lidx);
+          } else {
+            const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(vhslab) + (size_t)sl * (64 * G) + lidx);
+            vhcodes[sl] = make_uint4(u.x, u.y, 0, 0);
+          }
+        }
       }
     }
     __syncthreads();
@@ -639,7 +674,8 @@ __global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
             acc[1][set] = mfma_fp8_fp4(A[set], B1, acc[1][set]);
           }
           if constexpr (HI) {
-            const v8i B0h = unpack_fp4(vhcodes[sl].x, vhcodes[sl].y), B1h = unpack_fp4(vhcodes[sl].z, vhcodes[sl].w);
+            const v8i B0h = HB == 2 ? unpack_fp4(vhcodes[sl].x, vhcodes[sl].y) : unpack_fp4_bits(vhcodes[sl].x);
+            const v8i B1h = HB == 2 ? unpack_fp4(vhcodes[sl].z, vhcodes[sl].w) : unpack_fp4_bits(vhcodes[sl].y);
 #pragma unroll
             for (int set = 0; set < 2; ++set) {
               acch[0][set] = mfma_fp8_fp4(A[set], B0h, acch[0][set]);
@@ -674,8 +710,8 @@ __global__ void __launch_bounds__(256, HI ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
 
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  // 2-bit codes, or 4-bit ones (a second plane), in groups of 128
-  return c->blocks_aligned && v.qg == 128 && v.hb != 1 && (v.g == 2 || v.g == 4) && v.rope_style == 0;
+  // 2-bit codes, or wider ones (a second plane), in groups of 128
+  return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4) && v.rope_style == 0;
 }
 
 template <bool MULTI>
@@ -685,13 +721,18 @@ static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* q
   do {                                                                                                                   \
     if constexpr (!MULTI) {                                                                                                \
       if (v.hb == 2) {                                                                                                     \
-        if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, true, true>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-        else hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, false, true>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+        if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+        else hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, false, 2>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+        break;                                                                                                             \
+      }                                                                                                                    \
+      if (v.hb == 1) {                                                                                                     \
+        if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, true, 1>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+        else hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, false, 1>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
         break;                                                                                                             \
       }                                                                                                                    \
     }                                                                                                                      \
-    if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, false>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-    else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, false>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);  \
+    if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+    else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);  \
   } while (0)
   if (v.g == 4 && share == 1) RKV_MF_LAUNCH(4, 1);
   else if (v.g == 4) RKV_MF_LAUNCH(4, 2);

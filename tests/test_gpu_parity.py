@@ -964,7 +964,7 @@ def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
 @pytest.mark.parametrize("bits,group,g,hq,fmt,span", [(4, 128, 4, 8, 0, 128), (3, 128, 4, 8, 0, 128), (2, 64, 4, 8, 0, 128),
                                                       (2, 32, 2, 8, 0, 128), (4, 32, 1, 8, 1, 128), (3, 64, 8, 16, 1, 128),
                                                       (4, 64, 4, 8, 0, 512), (3, 32, 2, 8, 0, 1024), (4, 128, 2, 16, 1, 128),
-                                                      (4, 128, 4, 32, 0, 128)])
+                                                      (4, 128, 4, 32, 0, 128), (3, 128, 2, 16, 1, 128), (3, 128, 4, 32, 0, 128)])
 def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     """3- and 4-bit codes and quantization groups of 64 and 32 channels (Sec. 5.1; Tables
     tab:ablation and tab:quantgrani) through the write half, the export and dequantize views and
@@ -981,8 +981,8 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     if span != 128:
         perm = calibrated_perm(w, R.RkvConfig(perm_span=span, **kw), offset_variant=True)
         assert not np.array_equal(perm // group, np.arange(cfg.E) // group)
-    # 4-bit codes in groups of 128 are read by the matrix-core decode kernel as two planes
-    on_matrix_cores = bits == 4 and group == 128 and g in (2, 4) and span == 128
+    # wider codes in groups of 128 are read by the matrix-core decode kernel as two planes
+    on_matrix_cores = bits in (3, 4) and group == 128 and g in (2, 4) and span == 128
     cache, oc, q = full_check(w, cfg, 213, perm=perm, chunks=[0, 100, 101, 102, 213], paths=(1, 2) if on_matrix_cores else (1, 0))
     assert oc.k_codes.max() == 2 ** bits - 1 and oc.k_scale.shape[-1] == 1024 // group
     if not on_matrix_cores:      # what those kernels do not cover is refused, not mis-computed
