@@ -55,7 +55,7 @@ __device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
 }
 
 // Eq. 8-9 for one block given its min and max, as quant_params but without IEEE divisions: the
-// division by 3 (or 15) is a multiplication (error below 1.5 ulp of fp32, which can change the fp16 scale
+// division by 3 (or 7, or 15) is a multiplication (error below 1.5 ulp of fp32, which can change the fp16 scale
 // only within 2^-23 of a rounding boundary) and the reciprocal of the scale is v_rcp_f32 refined by
 // one Newton step.
 // meta8: FP8 E4M3 scale rounded up, INT8 zero-point.
@@ -100,9 +100,12 @@ __device__ __forceinline__ void fused_round_consts(float zero, float& base, floa
 }
 
 // bx, rg, b: the workgroup's place in the (3 x slabs, rotation groups, sequences) grid
-// HI: 4-bit codes.  The same arithmetic with 15 steps; the upper two bits of every code go to a
+// HB = 1: 3-bit codes, 7 steps; the third bits go to their plane, whose dwords take the bits of
+// one matrix operand each (see the layout notes): the four key waves of a tile, and the four
+// value waves of a slab, each contribute one bit in four to a dword of it.
+// HB = 2: 4-bit codes.  The same arithmetic with 15 steps; the upper two bits of every code go to a
 // second plane with the layout of the first (a second image in LDS, written the same way).
-template <int G, bool HI>
+template <int G, int HB>
 __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                  int n_new, int slab0, int bx, int rg, int b) {
   constexpr int PL = 2 * G;                    // value channels per lane
@@ -118,7 +121,8 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   __shared__ __attribute__((aligned(16))) uint32_t lds[16 * STRIDE16 * 4 > 4 * 64 * PL ? 16 * STRIDE16 * 4 : 4 * 64 * PL];
   uint32_t* img = lds;
   uint32_t* imgh = lds + (PL == 8 ? 2048 : 1024);          // the upper plane's images: after 2 x 128 G (keys) or 4 x 64 PL (values) dwords
-  constexpr float QMAX = HI ? 15.0f : 3.0f, INV_QMAX = HI ? 0.06666667f : 0.33333334f;
+  constexpr bool HI = HB == 2, H1 = HB == 1;
+  constexpr float QMAX = HI ? 15.0f : (H1 ? 7.0f : 3.0f), INV_QMAX = HI ? 0.06666667f : (H1 ? 0.14285715f : 0.33333334f);
   __shared__ uint32_t meta[32 * G];
   __shared__ float2 s_mm[2][2][16][G];         // [dword half][product pair][token][head] (min, max) of a quarter block
   const int tid = threadIdx.x, lane = tid & 63;
@@ -270,6 +274,10 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         if constexpr (HI) {
           img[io] = (word & 0x33333333u) << (2 * pph);
           imgh[io] = ((word >> 2) & 0x33333333u) << (2 * pph);
+        } else if constexpr (H1) {
+          // code m = 2 j + pph of dword d of the pair: bit 4 j + 2 d + pph of the pair's dword of third bits
+          img[io] = (word & 0x33333333u) << (2 * pph);
+          imgh[(2 * pph + d) * (64 * G) + ((io - pph * (128 * G) - d) >> 1)] = ((word >> 2) & 0x11111111u) << (2 * d + pph);
         } else {
           img[io] = word << (2 * pph);
         }
@@ -285,6 +293,13 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         if (t >= t_lo && t < t_hi) {
           rkv_st_stream(&v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], img[off] | img[128 * G + off]);
           if constexpr (HI) rkv_st_stream(&v.kh[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], imgh[off] | imgh[128 * G + off]);
+          if constexpr (H1) {
+            if (!(off & 1)) {
+              const int o2 = off >> 1;
+              rkv_st_stream(&v.kh[(rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off) >> 1],
+                            imgh[o2] | imgh[64 * G + o2] | imgh[128 * G + o2] | imgh[192 * G + o2]);
+            }
+          }
         }
       }
     }
@@ -303,12 +318,20 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     if (!(t >= t_lo && t < t_hi)) keep[tau >> 4] |= 3u << rkv_v_shift(tau);
   }
   const size_t vbase = rkv_v_slabbase(v, b, rg, slab);
-  uint32_t oldv[G], oldvh[HI ? G : 1];
+  uint32_t oldv[G], oldvh[HB ? G : 1];
 #pragma unroll
   for (int k = 0; k < G; ++k) oldv[k] = 0;
-  if constexpr (HI) {
+  if constexpr (HB != 0) {
 #pragma unroll
     for (int k = 0; k < G; ++k) oldvh[k] = 0;
+  }
+  // third bits (HB = 1): token tau of the slab sits at bit 4 (tau & 7) + (tau >> 3) of a channel's dword
+  uint32_t keeph = 0;
+  if constexpr (H1) {
+    for (int tau = 0; tau < 32; ++tau) {
+      const int t = ts + tau;
+      if (!(t >= t_lo && t < t_hi)) keeph |= 1u << (4 * (tau & 7) + (tau >> 3));
+    }
   }
   if (keep[0] | keep[1]) {
 #pragma unroll
@@ -316,6 +339,10 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     if constexpr (HI) {
 #pragma unroll
       for (int k = 0; k < G; ++k) oldvh[k] = v.vh[vbase + tid + 256 * k];
+    }
+    if constexpr (H1) {
+#pragma unroll
+      for (int k = 0; k < G; ++k) oldvh[k] = v.vh[(vbase + tid + 256 * k) >> 1];
     }
   }
   uint32_t vraw[8][PL / 2];                                // rows of this wave's 8 tokens: lane = PL consecutive channels
@@ -366,10 +393,10 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     const int tau = 8 * wave + (lane & (LPB - 1));
     if ((lane & (LPB - 1)) < 8) meta[tau * G + blk] = rkv_pack_meta(sc_v, zero_v);
   }
-  uint32_t vword[PL], vwordh[HI ? PL : 1];
+  uint32_t vword[PL], vwordh[HB ? PL : 1];
 #pragma unroll
   for (int i = 0; i < PL; ++i) vword[i] = 0;
-  if constexpr (HI) {
+  if constexpr (HB != 0) {
 #pragma unroll
     for (int i = 0; i < PL; ++i) vwordh[i] = 0;
   }
@@ -390,15 +417,19 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         const uint32_t code = __float_as_uint(c) - __float_as_uint(base);
         vword[i] += (code & 3u) << sh;
         vwordh[i] += (code >> 2) << sh;
+      } else if constexpr (H1) {
+        const uint32_t code = __float_as_uint(c) - __float_as_uint(base);
+        vword[i] += (code & 3u) << sh;
+        vwordh[i] += (code >> 2) << (4 * k + wave);        // tau = 8 wave + k
       } else {
         vword[i] += __float_as_uint(c) << sh;
       }
     }
-    if constexpr (!HI) bias += __float_as_uint(base) << sh;
+    if constexpr (HB == 0) bias += __float_as_uint(base) << sh;
   }
 #pragma unroll
   for (int i = 0; i < PL; ++i) img[(wave * PL + i) * 64 + lane] = vword[i] - bias;
-  if constexpr (HI) {
+  if constexpr (HB != 0) {
 #pragma unroll
     for (int i = 0; i < PL; ++i) imgh[(wave * PL + i) * 64 + lane] = vwordh[i];
   }
@@ -420,6 +451,13 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       if (keep[d]) word |= oldvh[k] & keep[d];
       if (keep[d] != 0xffffffffu) rkv_st_stream(&v.vh[vbase + idx], word);
     }
+    if constexpr (H1) {
+      if (d == 0) {                                         // one dword of third bits per pair (d = 0, 1): all four waves' tokens
+        word = imgh[(0 * PL + i) * 64 + ln] | imgh[(1 * PL + i) * 64 + ln] | imgh[(2 * PL + i) * 64 + ln] | imgh[(3 * PL + i) * 64 + ln];
+        if (keeph) word |= oldvh[k] & keeph;
+        rkv_st_stream(&v.vh[(vbase + idx) >> 1], word);
+      }
+    }
   }
   for (int i = tid; i < 32 * G; i += 256) {
     const int tau = i / G;
@@ -427,10 +465,10 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   }
 }
 
-template <int G, bool HI>
-__global__ void __launch_bounds__(256, HI ? 4 : 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+template <int G, int HB>
+__global__ void __launch_bounds__(256, HB ? 4 : 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                               int n_new, int slab0) {
-  append_mfma_body<G, HI>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+  append_mfma_body<G, HB>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // One decode step's write half and query preparation in one launch: the first 3 * n_slabs
@@ -438,12 +476,12 @@ __global__ void __launch_bounds__(256, HI ? 4 : 6) k_append_mfma(RkvView v, cons
 // rest prepare that rotation group's query heads (two heads per workgroup) for the decode kernel,
 // which saves a launch of its own for a few microseconds of work.  The query's default position
 // is the appended token's: one past the last token the view knows of.
-template <int G, bool HI>
+template <int G, int HB>
 __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                    int slab0, int n_append_blocks, const __half* __restrict__ q,
                                                    const int* __restrict__ q_pos, float* __restrict__ qr, int share) {
   if ((int)blockIdx.x < n_append_blocks) {
-    append_mfma_body<G, HI>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+    append_mfma_body<G, HB>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
     return;
   }
   const int rep = v.Hq / v.Hkv;
@@ -453,8 +491,8 @@ __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* _
 
 bool rkv_append_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  // 2-bit codes, or 4-bit ones (a second plane), in groups of 128
-  return c->blocks_aligned && v.qg == 128 && v.hb != 1 && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
+  // 2-bit codes, or wider ones (a second plane), in groups of 128
+  return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 
 // max_slabs: most 32-token slabs any sequence's new tokens touch, or 0 to work it out for n_new
@@ -474,10 +512,13 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   dim3 grid(3 * max_slabs, v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (v.hb == 2) {
-    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-    else hipLaunchKernelGGL((k_append_mfma<2, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  } else if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, false>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  else hipLaunchKernelGGL((k_append_mfma<2, false>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    else hipLaunchKernelGGL((k_append_mfma<2, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  } else if (v.hb == 1) {
+    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 1>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    else hipLaunchKernelGGL((k_append_mfma<2, 1>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  } else if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  else hipLaunchKernelGGL((k_append_mfma<2, 0>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   return rkv_check_launch();
 }
@@ -491,9 +532,12 @@ int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const 
   const int n_append = 3 * max_slabs, rep = v.Hq / v.Hkv;
   dim3 grid(n_append + v.g * rep / 2, v.NRG, v.B);
   if (v.hb == 2) {
-    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-    else hipLaunchKernelGGL((k_step_mfma<2, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  } else if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, false>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  else hipLaunchKernelGGL((k_step_mfma<2, false>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+    else hipLaunchKernelGGL((k_step_mfma<2, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  } else if (v.hb == 1) {
+    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 1>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+    else hipLaunchKernelGGL((k_step_mfma<2, 1>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  } else if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  else hipLaunchKernelGGL((k_step_mfma<2, 0>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
   return rkv_check_launch();
 }

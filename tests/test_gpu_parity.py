@@ -276,13 +276,13 @@ def export_host(cache):
     return {k: v.cpu().numpy() for k, v in exp.items()}
 
 
-@pytest.mark.parametrize("meta_format,bits", [(0, 2), (1, 2), (0, 4)])
+@pytest.mark.parametrize("meta_format,bits", [(0, 2), (1, 2), (0, 4), (1, 3)])
 def test_full_size_config2_sampled(meta_format, bits):
     """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, then one rkv_decode_step (the last
     token's append and the attention on the matrix-core path).  The oracle recomputes sampled (sequence, rotation group) slices - a
     rotation group's codes and attention outputs depend on nothing outside the slice.  Once with
-    fp16 metadata, once with the FP8 scale / INT8 zero-point storage, once with 4-bit codes."""
+    fp16 metadata, once with the FP8 scale / INT8 zero-point storage, once with 4-bit codes, once with 3-bit codes and FP8 / INT8 metadata."""
     w = S.WORKLOADS["cfg2"]
     T = w.context
     cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=4,
@@ -787,9 +787,9 @@ def test_shared_scratch_reused_across_caches():
             assert torch.equal(out, refs[i]), f"repetition {rep}, cache {i}"
 
 
-@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_sequences_of_different_lengths(bits):
-    """(With 2-bit codes and with 4-bit codes, which the matrix-core kernels read as two planes.)
+    """(With 2-bit codes and with 3- and 4-bit codes, which the matrix-core kernels read as two planes.)
     rkv_quantize_append_ragged: three sequences are prefilled with 300 / 37 / 513 tokens in one
     call, extended by 5 / 0 / 40 in a second, then take three ordinary single-token steps.  Each
     sequence is compared with an oracle cache of its own (batch 1): codes under the tie protocol,
@@ -881,15 +881,15 @@ def test_sequences_of_different_lengths(bits):
 
 
 @pytest.mark.parametrize("hq,hkv,g,ragged,bits", [(8, 8, 4, False, 2), (16, 4, 4, False, 2), (4, 4, 2, True, 2), (8, 8, 8, False, 2),
-                                                  (8, 8, 4, True, 4), (8, 4, 2, False, 4), (8, 8, 4, False, 3)])
+                                                  (8, 8, 4, True, 4), (8, 4, 2, False, 4), (8, 8, 4, True, 3), (8, 4, 2, False, 3), (8, 8, 8, False, 3)])
 def test_one_call_decode_step_equals_the_two_calls(hq, hkv, g, ragged, bits):
     """rkv_decode_step (append + attention in one call; on the matrix-core configurations the
     token's compression and the query's preparation share a launch) against rkv_quantize_append
     followed by rkv_decode_attention on a second cache with the same contents: outputs, codes and
     metadata bit for bit, over several steps that cross a tile and a slab boundary; also with
     sequences of different lengths, explicit query positions, and on a configuration that falls
-    back to the two calls (rotation over 8 heads; 3-bit codes).  4-bit codes take the one-launch
-    path like 2-bit ones."""
+    back to the two calls (rotation over 8 heads).  3- and 4-bit codes take the one-launch path
+    like 2-bit ones."""
     w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
     B, T0, steps = 2, 29, 6
     cfg = R.RkvConfig(batch=B, n_q_heads=hq, n_kv_heads=hkv, max_tokens=128, max_sinks=4, rot_heads=g, bits=bits)
