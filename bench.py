@@ -97,7 +97,7 @@ def main():
     ap.add_argument("--queries", type=int, default=1,
                     help="query tokens per sequence and step (above 1: that many tokens are appended, then read the cache in one multi-query call)")
     ap.add_argument("--meta-format", type=int, default=0, help="0: fp16 scale and zero-point (2.25 bits); 1: FP8 scale, INT8 zero-point (2.125 bits)")
-    ap.add_argument("--bits", type=int, default=2, help="bits per code: 2 or 4 (matrix-core kernels), 3 (general kernels)")
+    ap.add_argument("--bits", type=int, default=2, help="bits per code: 2, 3 or 4")
     ap.add_argument("--quant-group", type=int, default=128, help="channels per quantization block: 128 (matrix-core kernels), 64 or 32 (general kernels)")
     ap.add_argument("--ragged-min", type=float, default=1.0,
                     help="below 1: sequence lengths spread evenly from this fraction of the context up to the full context")
@@ -274,7 +274,7 @@ def main():
                    "storage": f"u{QB} codes + " + ("fp16 scale / fp16 zero" if MB == 4 else "FP8 E4M3 scale / INT8 zero") +
                               f" per {QG} ({QB + 8.0 * MB / QG:g} bits per element)",
                    "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"
-                                 if QB in (2, 4) and QG == 128 and args.path != 1 else "fp32 vector arithmetic and accumulation (general kernels)"},
+                                 if QG == 128 and args.path != 1 else "fp32 vector arithmetic and accumulation (general kernels)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms, "launches_timed": len(kern_ms),
                      "algorithmic_bytes_per_launch": launch_bytes, "bytes_per_kv_token": bytes_per_tok},

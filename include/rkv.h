@@ -55,10 +55,10 @@ typedef struct rkv_config {
   int32_t quant_group;  /* channels per quantization block: 128 (Sec. 5.1 quantization settings), */
                         /* 64 or 32 (Table tab:quantgrani)                                       */
   int32_t bits;         /* bits per code: 2 (the headline setting), 3 or 4 (Table tab:ablation). */
-                        /* 4-bit codes in groups of 128 run on the matrix-core kernels like      */
-                        /* 2-bit ones (as two planes of 2 bits) but for keys_rotated and         */
-                        /* rkv_decode_attention_multi; 3-bit codes and groups of 64 / 32 run on  */
-                        /* the general kernels only, which also means no                         */
+                        /* 3- and 4-bit codes in groups of 128 run on the matrix-core kernels    */
+                        /* like 2-bit ones (the bits above the low two as a second plane) but    */
+                        /* for keys_rotated and rkv_decode_attention_multi; groups of 64 / 32    */
+                        /* run on the general kernels only, which also means no                  */
                         /* rkv_quantize_append_ragged and a two-kernel rkv_decode_step           */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
