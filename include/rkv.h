@@ -57,8 +57,8 @@ typedef struct rkv_config {
   int32_t bits;         /* bits per code: 2 (the headline setting), 3 or 4 (Table tab:ablation). */
                         /* 3- and 4-bit codes in groups of 128 run on the matrix-core kernels    */
                         /* like 2-bit ones (the bits above the low two as a second plane) but    */
-                        /* for keys_rotated and rkv_decode_attention_multi; groups of 64 / 32    */
-                        /* run on the general kernels only, which also means no                  */
+                        /* for rkv_decode_attention_multi; groups of 64 / 32 run on the general  */
+                        /* kernels only, which also means no keys_rotated, no                    */
                         /* rkv_quantize_append_ragged and a two-kernel rkv_decode_step           */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */

@@ -537,15 +537,15 @@ def test_fold_rotation_matches_oracle():
         assert err <= 2e-6 * np.abs(ref).max()
 
 
-@pytest.mark.parametrize("g", [4, 2])
-def test_rotated_keys_path(g):
+@pytest.mark.parametrize("g,bits", [(4, 2), (2, 2), (4, 4), (2, 3)])
+def test_rotated_keys_path(g, bits):
     """The deployment shape of Sec. 4.2: keys arrive already rotated and reordered (folded weights),
     the write half only quantizes and packs.  Codes under the tie protocol (the input is exact, so
     only exact ties of Eq. 6 remain), sink rows brought back to the original basis (fp32 on the
     GPU, float64 in the oracle: equal up to one fp16 ulp at rounding ties), decode on both paths."""
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     T = 150
-    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=T, max_sinks=4, rot_heads=g, keys_rotated=1)
+    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=T, max_sinks=4, rot_heads=g, keys_rotated=1, bits=bits)
     ocfg = P.oracle_cfg(cfg)
     rng = np.random.default_rng(32)
     perm = np.concatenate([128 * blk + rng.permutation(128) for blk in range(cfg.E // 128)]).astype(np.int32)
