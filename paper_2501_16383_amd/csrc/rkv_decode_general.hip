@@ -45,7 +45,8 @@ __device__ inline bool is_sink(const int* sp, int cnt, int t) {
   return s;
 }
 
-template <int PL>
+// WIDE: codes of 3 or 4 bits (a second plane of bits is read)
+template <int PL, bool WIDE>
 __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __restrict__ qr, float* __restrict__ part, int nch) {
   // LDS: q~ of this group's query heads, scores / probabilities, V meta, per-head stats
   extern __shared__ float sm[];
@@ -91,7 +92,7 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
   // bits above the low two (wider codes).  4-bit codes: a second plane, same dword and shifts;
   // 3-bit codes: the third bits sit in the dword that belongs to the lane's dword and its
   // neighbour, at places that follow from the shifts (rkv_h1_loc)
-  const int hb = v.hb;
+  const int hb = WIDE ? v.hb : 0;
   int hsh[PL];
 #pragma unroll
   for (int i = 0; i < PL; ++i) {
@@ -178,11 +179,11 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
     for (int tt = 0; tt < t1 - t0; tt += 16) {
       int sh;
       const size_t wi = rkv_v_dword(v, b, rg, t0 + tt, c, sh);
-      const uint32_t w = v.vc[wi], w2 = v.hb == 2 ? v.vh[wi] : (v.hb == 1 ? v.vh[wi >> 1] : 0u);
+      const uint32_t w = v.vc[wi], w2 = hb == 2 ? v.vh[wi] : (hb == 1 ? v.vh[wi >> 1] : 0u);
       for (int k = 0; k < 16 && tt + k < t1 - t0; ++k) {
         uint32_t code = (w >> rkv_v_shift(k)) & 3u;
-        if (v.hb == 2) code |= ((w2 >> rkv_v_shift(k)) & 3u) << 2;
-        else if (v.hb == 1) {
+        if (hb == 2) code |= ((w2 >> rkv_v_shift(k)) & 3u) << 2;
+        else if (hb == 1) {
           int bit;
           rkv_h1_loc(wi, rkv_v_shift(k), bit);
           code |= ((w2 >> bit) & 1u) << 2;
@@ -411,10 +412,10 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   dim3 grid(nch, v.NRG, v.B);
   void (*fn)(RkvView, const float*, float*, int) = nullptr;
   switch (v.n / 64) {
-    case 2: fn = k_decode_gen<2>; break;
-    case 4: fn = k_decode_gen<4>; break;
-    case 8: fn = k_decode_gen<8>; break;
-    case 16: fn = k_decode_gen<16>; break;
+    case 2: fn = v.hb ? k_decode_gen<2, true> : k_decode_gen<2, false>; break;
+    case 4: fn = v.hb ? k_decode_gen<4, true> : k_decode_gen<4, false>; break;
+    case 8: fn = v.hb ? k_decode_gen<8, true> : k_decode_gen<8, false>; break;
+    case 16: fn = v.hb ? k_decode_gen<16, true> : k_decode_gen<16, false>; break;
     default: return RKV_EINVAL;
   }
   if (lds > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
