@@ -387,7 +387,7 @@ void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int 
 }
 void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, int chunk_tokens, const __half* k_cur,
                       const __half* v_cur, const int* q_lim, int nq, float* out, float* lse, hipStream_t s) {
-  // long contexts: share the chunks among four groups of threads (128 chunks: 9.5 instead of 17 us;
+  // long contexts: share the chunks among four groups of threads (128 chunks: 9 instead of 17 us;
   // at 32 chunks the wider workgroups cost more than they save)
   if (nch > 32) hipLaunchKernelGGL(k_merge<4>, dim3(v.Hq, v.B), dim3(512), 0, s, v, qr, part, nch, chunk_tokens, k_cur, v_cur, q_lim, nq, out, lse);
   else hipLaunchKernelGGL(k_merge<1>, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, chunk_tokens, k_cur, v_cur, q_lim, nq, out, lse);
