@@ -56,10 +56,10 @@ typedef struct rkv_config {
                         /* 64 or 32 (Table tab:quantgrani)                                       */
   int32_t bits;         /* bits per code: 2 (the headline setting), 3 or 4 (Table tab:ablation). */
                         /* 3- and 4-bit codes in groups of 128 run on the matrix-core kernels    */
-                        /* like 2-bit ones (the bits above the low two as a second plane) but    */
-                        /* for rkv_decode_attention_multi; groups of 64 / 32 run on the general  */
-                        /* kernels only, which also means no keys_rotated, no                    */
-                        /* rkv_quantize_append_ragged and a two-kernel rkv_decode_step           */
+                        /* like 2-bit ones (the bits above the low two as a second plane);       */
+                        /* groups of 64 / 32 run on the general kernels only, which also means   */
+                        /* no keys_rotated, no rkv_quantize_append_ragged, no                    */
+                        /* rkv_decode_attention_multi and a two-kernel rkv_decode_step           */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
                         /* printed sorts the whole row)                                           */

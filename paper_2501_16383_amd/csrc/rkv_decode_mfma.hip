@@ -719,17 +719,15 @@ static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* q
                           int nq, hipStream_t s) {
 #define RKV_MF_LAUNCH(G_, R_)                                                                                              \
   do {                                                                                                                   \
-    if constexpr (!MULTI) {                                                                                                \
-      if (v.hb == 2) {                                                                                                     \
-        if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-        else hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, false, 2>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-        break;                                                                                                             \
-      }                                                                                                                    \
-      if (v.hb == 1) {                                                                                                     \
-        if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, true, 1>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-        else hipLaunchKernelGGL((k_decode_mfma<G_, R_, false, false, 1>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-        break;                                                                                                             \
-      }                                                                                                                    \
+    if (v.hb == 2) {                                                                                                       \
+      if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+      else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, 2>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+      break;                                                                                                               \
+    }                                                                                                                      \
+    if (v.hb == 1) {                                                                                                       \
+      if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, 1>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+      else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, 1>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
+      break;                                                                                                               \
     }                                                                                                                      \
     if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
     else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);  \
@@ -756,7 +754,6 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   if (!rkv_mfma_supported(c)) return RKV_EINVAL;
   const bool multi = nq > 0;
   if (multi && (c->cur_k || !q_pos)) return RKV_EINVAL;
-  if (multi && c->v.hb) return RKV_EINVAL;                   // several query tokens: 2-bit codes only
   if (!multi) nq = 1;
   RkvView v = c->v;
   v.Hq *= nq;                                               // virtual heads

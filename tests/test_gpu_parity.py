@@ -654,15 +654,16 @@ def test_maximum_context_length():
                     tag=f"65536 tokens path={path}")
 
 
-@pytest.mark.parametrize("hq,hkv,g,nq", [(8, 8, 4, 4), (8, 8, 4, 3), (16, 4, 4, 2), (4, 4, 2, 2), (8, 8, 4, 1)])
-def test_several_query_tokens_per_step(hq, hkv, g, nq):
+@pytest.mark.parametrize("hq,hkv,g,nq,bits", [(8, 8, 4, 4, 2), (8, 8, 4, 3, 2), (16, 4, 4, 2, 2), (4, 4, 2, 2, 2), (8, 8, 4, 1, 2),
+                                              (8, 8, 4, 4, 4), (16, 4, 4, 2, 3), (4, 4, 2, 3, 4)])
+def test_several_query_tokens_per_step(hq, hkv, g, nq, bits):
     """rkv_decode_attention_multi: the tokens of a multi-token step are appended, then all of them
     read the cache in one call, each blind to what lies behind its own position (one of the new
     tokens is a retained sink row, which the earlier ones must not see).  Checked against the
     oracle on the GPU's own codes; sequence 1 uses scattered positions, one past the cache."""
     w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
     T = 333
-    cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=hkv, max_tokens=400, max_sinks=4, rot_heads=g)
+    cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=hkv, max_tokens=400, max_sinks=4, rot_heads=g, bits=bits)
     sinks = [0, T - 2] if nq > 1 else [0]
     cache, oc, _ = build_pair(w, cfg, T, sink_positions=sinks, chunks=[0, T - nq, T])
     oc_g = oracle_from_export(oc, P.export_numpy(cache))
@@ -860,16 +861,12 @@ def test_sequences_of_different_lengths(bits):
     cache.set_decode_path(0)
     q2 = np.stack([S.make_q(w, batch=B, step=i) for i in range(2)], axis=1)
     q_pos = np.array([[total[b] - 2, total[b] - 1] for b in range(B)], dtype=np.int32)
-    if bits == 2:
-        out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
-        torch.cuda.synchronize()
-        for b in range(B):
-            ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
-            e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
-            assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
-    else:                                                      # several query tokens per step: 2-bit codes only
-        with pytest.raises(R.RkvError):
-            cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
+    out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
+        e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
+        assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
     # what the entry point refuses
     with pytest.raises(R.RkvError) as ei:
         cache.quantize_append_ragged(P.gpu(np.zeros((B, 50, 8, 128), np.float16)), P.gpu(np.zeros((B, 50, 8, 128), np.float16)), [1, 1, 50])
@@ -1001,8 +998,8 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
 
 
-@pytest.mark.parametrize("uniform", [True, False])
-def test_truncate_rolls_back_a_multi_token_step(uniform):
+@pytest.mark.parametrize("uniform,bits", [(True, 2), (False, 2), (False, 4), (True, 3)])
+def test_truncate_rolls_back_a_multi_token_step(uniform, bits):
     """Speculative decoding's shape: four drafted tokens are appended and read the cache together
     (rkv_decode_attention_multi); some are rejected, rkv_cache_truncate rolls the cache back, and
     decoding goes on with other tokens.  The cache must then equal - codes, metadata, sink rows,
@@ -1010,7 +1007,7 @@ def test_truncate_rolls_back_a_multi_token_step(uniform):
     One of the drafted tokens is a flagged sink behind the cut: it must be dropped."""
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     B, T0 = 2, 45
-    cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=4, rot_heads=4)
+    cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=4, rot_heads=4, bits=bits)
     k, v, mask = S.make_kv(w, T0 + 4 + 3, batch=B, sink_positions=[0, 1])
     mask = mask.copy()
     mask[:, T0 + 3] = 1                                        # the last drafted token is flagged as a sink
