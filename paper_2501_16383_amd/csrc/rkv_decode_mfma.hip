@@ -24,8 +24,9 @@
 //   phase S  wave a: softmax statistics of head a over the chunk, weights -> FP8 digits in LDS.
 //   phase V  wave w: channels 32w..32w+31 of every head; A = weight digits [16 x (4 heads x 32
 //            tokens)], block-diagonal over heads, B = codes [(4 heads x 32 tokens) x 16 channels].
-// Covers: reorder that keeps 128-blocks (gid[c] == c/128), rot_heads 2 or 4, half-split RoPE
-// pairs.  With GQA (or several query tokens per step) a workgroup serves two of the query heads
+// Covers: reorder that keeps 128-blocks, rot_heads 2 or 4, codes of 2 to 4 bits in groups of 128;
+// both RoPE pairings (the Hadamard operand tiles are built so that tiles p and p + 4 yield the two
+// channels of a pair).  With GQA (or several query tokens per step) a workgroup serves two of the query heads
 // that share a KV head: unpacking, rotation and RoPE of the keys are done once for them, the
 // softmax and value phases once per query head.  Everything else takes the general kernel.
 #include "rkv_internal.h"
@@ -425,7 +426,8 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
         for (int i = 0; i < RP * G * REP; ++i) pt[i] = 0.f;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-          // H_128 of the raw codes for channels 16p + n (lo) and 16p + n + 64 (hi): half-integers, exact
+          // H_128 of the raw codes for channels 16p + n (lo) and 16p + n + 64 (hi) - or the even and the odd
+          // channel of pair 16p + n -: half-integers, exact
           v4f lo[G], hi[G];
           {
             v8i Hlo, Hhi;
@@ -711,7 +713,7 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
   // 2-bit codes, or wider ones (a second plane), in groups of 128
-  return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4) && v.rope_style == 0;
+  return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4);
 }
 
 template <bool MULTI>

@@ -70,15 +70,17 @@ __global__ void k_init_rope(RkvView v) {
 
 // B operand of v_mfma_f32_16x16x128_f8f6f4 holding H_128 (entries +-1 as FP4 E2M1: 0x2 / 0xA).
 // Lane (n = lane & 15, q = lane >> 4) holds, in nibble e of dword v, input channel k = 32q + 8v + e
-// of output channel 16*tile + n.
-__global__ void k_init_hop(uint32_t* hop) {
+// of output channel 16*tile + n.  The decode kernel rotates the results of tiles p and p + 4 as a
+// RoPE pair: channels 16p + n and 16p + n + 64 - or, with interleaved pairs (rope_style 1),
+// tile p holds output channel 2 (16p + n) and tile p + 4 its odd neighbour.
+__global__ void k_init_hop(uint32_t* hop, int rope_style) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;   // (tile, lane, v)
   if (i >= 8 * 64 * 4) return;
   const int vreg = i & 3, lane = (i >> 2) & 63, tile = i >> 8;
   const int n = lane & 15, q = lane >> 4;
   uint32_t w = 0;
   for (int e = 0; e < 8; ++e) {
-    const int k = 32 * q + 8 * vreg + e, col = 16 * tile + n;
+    const int k = 32 * q + 8 * vreg + e, col = rope_style ? 2 * (16 * (tile & 3) + n) + (tile >> 2) : 16 * tile + n;
     w |= ((__popc(k & col) & 1) ? 0xAu : 0x2u) << (4 * e);
   }
   hop[i] = w;
@@ -94,7 +96,7 @@ int rkv_launch_init(rkv_cache* c, bool tables, hipStream_t s) {
   int m = v.B * S > v.E ? v.B * S : v.E;
   hipLaunchKernelGGL(k_init_small, dim3((m + 255) / 256), dim3(256), 0, s, v, tables ? 1 : 0);
   if (tables) hipLaunchKernelGGL(k_init_rope, dim3((v.Tpad * 64 + 255) / 256), dim3(256), 0, s, v);
-  if (tables) hipLaunchKernelGGL(k_init_hop, dim3(8), dim3(256), 0, s, v.hop);
+  if (tables) hipLaunchKernelGGL(k_init_hop, dim3(8), dim3(256), 0, s, v.hop, v.rope_style);
   if (tables) c->blocks_aligned = 1;
   return rkv_check_launch();
 }

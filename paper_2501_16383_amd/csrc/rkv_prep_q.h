@@ -32,12 +32,12 @@ __device__ __forceinline__ void rkv_prep_q_one(const RkvView& v, const __half* _
   //   [b][rot group][rr / share][r][p 0..3][f / 4][n 0..15][f % 4],  f = (KV head a * share + rr % share) * 2 + half
   // (rr = which of the query heads sharing KV head a; one workgroup serves `share` of them; the 16
   // channel lanes n read consecutive 16-byte pieces, which LDS serves without bank conflicts) with
-  // entry (n, p, half) = channel 16p + n + 64*half, pre-multiplied by 2/sqrt(rotation size)
+  // entry (n, p, half) = channel 16p + n + 64*half (interleaved pairs: 2 (16p + n) + half), pre-multiplied by 2/sqrt(rotation size)
   // (FP4 nibbles hold code/2; 1/sqrt(n) is the normalisation of Eq. 10).
   const int g = v.g, rep = v.Hq / v.Hkv;
   const int kvh = h / rep, rr = h - kvh * rep, rg = kvh / g, a = kvh - rg * g;
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;
-  const int nn = c & 15, pp = (c >> 4) & 3, half = c >> 6;
+  const int nn = v.rope_style ? (c >> 1) & 15 : c & 15, pp = v.rope_style ? (c >> 5) & 3 : (c >> 4) & 3, half = v.rope_style ? c & 1 : c >> 6;
   const int rrg = rr / share, rri = rr - rrg * share;
   const float lane_scale = 2.0f * rsqrtf((float)v.n);
 #pragma unroll

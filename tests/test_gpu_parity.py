@@ -171,13 +171,13 @@ def test_gqa_llama3_shape():
     full_check(w, cfg, 270, paths=(1, 2))
 
 
-@pytest.mark.parametrize("g,style,vrot", [(1, 0, 1), (2, 1, 0), (8, 0, 1), (4, 1, 1)])
+@pytest.mark.parametrize("g,style,vrot", [(1, 0, 1), (2, 1, 0), (8, 0, 1), (4, 1, 1), (4, 1, 0), (1, 1, 0)])
 def test_variants(g, style, vrot):
     """Other rotation sizes, interleaved RoPE pairing, library-side value rotation."""
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     cfg = R.RkvConfig(batch=1, n_q_heads=8, n_kv_heads=8, max_tokens=160, max_sinks=2, rot_heads=g, perm_span=128,
                       rope_style=style, v_rotate=vrot)
-    full_check(w, cfg, 150, sink_positions=[0, 3], paths=(1, 0))
+    full_check(w, cfg, 150, sink_positions=[0, 3], paths=(1, 2) if g in (2, 4) else (1, 0))
 
 
 def test_incremental_append_matches_bulk():
@@ -703,7 +703,7 @@ def test_fp8_scale_int8_zero_metadata(hq, hkv, g, style):
     b16, _ = R.query_sizes(R.RkvConfig(**kw))
     Tpad = 768
     assert b16 - b8 == 2 * 2 * Tpad * hkv * 2                     # K and V, 2 bytes less per (token, block)
-    paths = (1, 2) if (g in (2, 4) and style == 0) else (1, 0)
+    paths = (1, 2) if g in (2, 4) else (1, 0)
     full_check(w, cfg, 613, chunks=[0, 300, 301, 302, 613], paths=paths)
 
 
