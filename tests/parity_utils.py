@@ -105,6 +105,8 @@ def compare_codes(pre: np.ndarray, o_codes, o_scale, o_zero, g_codes, g_scale, g
     bounded = np.ones(g_scale.shape, dtype=bool)
     if meta_format == 1:      # a saturated scale or a clamped zero-point gives the bound up (on both sides alike)
         bounded = (raw <= O.E4M3_MAX) & (g_zero > -128) & (g_zero < 127)
+    else:
+        bounded = (np.abs(g_zero) < O.ZERO_LIMIT) & (raw <= 65504.0)
     # the stored step is the exact one within 2^-11 (fp16); over `top` steps that moves the last level
     ok = np.abs(blocks - recon) <= g_scale[..., None] * (0.5 + max(2.0 ** -9, top * 2.0 ** -11)) + slack
     assert np.all(ok | ~bounded[..., None]), f"{what}: half-step bound"
@@ -130,13 +132,14 @@ def export_numpy(cache: R.RkvCache):
     return out
 
 
-def check_cache_against_oracle(cache: R.RkvCache, oc: O.OracleCache, tag: str):
+def check_cache_against_oracle(cache: R.RkvCache, oc: O.OracleCache, tag: str, max_ambiguous: float = 0.02):
     g = export_numpy(cache)
     assert g["k_codes"].shape == oc.k_codes.shape
     sk = compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"], tag + " K",
-                       group=oc.cfg.quant_group, rot_span=oc.cfg.n, meta_format=oc.cfg.meta_format, bits=oc.cfg.bits)
+                       group=oc.cfg.quant_group, rot_span=oc.cfg.n, meta_format=oc.cfg.meta_format, bits=oc.cfg.bits,
+                       max_ambiguous=max_ambiguous)
     sv = compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], tag + " V",
-                       group=oc.cfg.quant_group, meta_format=oc.cfg.meta_format, bits=oc.cfg.bits)
+                       group=oc.cfg.quant_group, meta_format=oc.cfg.meta_format, bits=oc.cfg.bits, max_ambiguous=max_ambiguous)
     return g, sk, sv
 
 

@@ -75,13 +75,16 @@ def check_dequant(cache, oc_same_codes):
         print(f"[parity] dequantized {name}: max abs err {err.max():.3e}")
 
 
-def check_decode(cache, oc_same_codes, q, q_pos=None, tag=""):
+def check_decode(cache, oc_same_codes, q, q_pos=None, tag="", lse_relative=False):
     qp = None if q_pos is None else P.gpu(np.asarray(q_pos, dtype=np.int32))
     out, lse = cache.decode_attention(P.gpu(q), qp, want_lse=True)
     torch.cuda.synchronize()
     ref, lse_ref = O.decode_attention(oc_same_codes, q, q_pos)
     e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
-    le = float(np.abs(lse.cpu().numpy() - lse_ref).max())
+    le = np.abs(lse.cpu().numpy() - lse_ref)
+    if lse_relative:        # scores in the thousands (keys at the end of the fp16 range): fp32 carries them to ~1e-7 of their size
+        le = le / np.maximum(1.0, np.abs(lse_ref))
+    le = float(le.max())
     print(f"[parity] decode {tag}: out err {e:.3e}  lse err {le:.3e}", flush=True)
     assert e <= ATT_TOL and le <= LSE_TOL
     return e
@@ -437,6 +440,68 @@ def test_large_zero_points():
     for path in (1, 2):
         cache.set_decode_path(path)
         check_decode(cache, oc_g, q, tag=f"large zero-points path={path}")
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_degenerate_and_extreme_blocks(bits):
+    """Blocks the quantizer has special rules for, in keys and values alike (keys arrive rotated,
+    so both are quantized exactly as given): all zeros, constants, a range that rounds to a zero
+    scale, ranges of a few fp16 subnormals, values at the end of the fp16 range, and an offset so
+    far from zero that the zero-point is clamped.  Metadata and codes against the oracle (exact
+    outside ties), then the read half on those codes on both kernels."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8, n_sinks=0)
+    cfg = R.RkvConfig(batch=1, n_q_heads=8, n_kv_heads=8, max_tokens=64, max_sinks=0, rot_heads=4, keys_rotated=1, bits=bits)
+    T = 40
+    rng = np.random.default_rng(123 + bits)
+    x = rng.standard_normal((1, T, 8, 128)).astype(np.float16)
+    def special(a):
+        a = a.copy()
+        a[0, 0] = 0.0                                              # a token of zeros: every block degenerate, scale 1
+        a[0, 1, :, :] = np.float16(2.5)                            # constants
+        a[0, 2, :, :] = np.float16(-0.125)
+        a[0, 3, 0, :] = 0.0
+        a[0, 3, 0, 5] = np.float16(6e-8)                           # range of one fp16 subnormal: the scale rounds to 0 or to it
+        a[0, 4, 1, :] = np.float16(1e-7) * rng.integers(0, 4, size=128).astype(np.float16)   # a few subnormals
+        a[0, 5, 2, :] = np.where(rng.random(128) < 0.5, 65504.0, -65504.0).astype(np.float16)   # the ends of the fp16 range
+        a[0, 5, 2, :2] = [65504.0, -65504.0]
+        a[0, 6, 3, :] = (30000.0 + 16.0 * rng.integers(0, 2, size=128)).astype(np.float16)   # one fp16 step of range on a large
+        a[0, 6, 3, :2] = [30000.0, 30016.0]                                                   # offset: zero-point beyond its clamp
+        a[0, 7, 4, :] = (-30000.0 - 16.0 * rng.integers(0, 2, size=128)).astype(np.float16)
+        a[0, 7, 4, :2] = [-30000.0, -30016.0]
+        a[0, 8, 5, :] = 1000.0
+        a[0, 8, 5, 7] = 1000.5                                     # tiny range on a large offset
+        return a
+    k, v = special(x), special(rng.standard_normal((1, T, 8, 128)).astype(np.float16))
+    perm = np.concatenate([128 * blk + rng.permutation(128) for blk in range(8)]).astype(np.int32)
+    cache = R.RkvCache(cfg)
+    cache.set_perm(P.gpu(perm))
+    oc = O.cache_new(P.oracle_cfg(cfg), perm)
+    for a, b in ((0, 9), (9, 10), (10, T)):
+        cache.quantize_append(P.gpu(k[:, a:b]), P.gpu(v[:, a:b]))
+        with np.errstate(over="ignore"):        # the oracle also forms every token's fp16 sink row, which overflows here and is not used
+            O.quantize_append(oc, k[:, a:b], v[:, a:b], None, keys_rotated=True)
+    torch.cuda.synchronize()
+    # (the planted blocks with a range near zero count as ties in the comparison: their metadata
+    # and codes are checked one by one below instead)
+    g, sk, sv = P.check_cache_against_oracle(cache, oc, f"special blocks bits={bits}", max_ambiguous=0.3)
+    top = 2 ** bits - 1
+    for name in ("k", "v"):
+        sc, ze, co = g[name + "_scale"][0], g[name + "_zero"][0], g[name + "_codes"][0].reshape(T, 8, 128)
+        assert np.all(sc[0] == 1.0) and np.all(ze[0] == 0.0) and np.all(co[0] == 0)          # zeros: scale 1
+        assert np.all(sc[1] == 2.5) and np.all(ze[1] == -1.0) and np.all(co[1] == 0)         # constant c: scale |c|, zero -c/|c|
+        assert np.all(sc[2] == 0.125) and np.all(ze[2] == 1.0) and np.all(co[2] == 0)
+        assert np.abs(ze[6, 3]) == 2048 and np.abs(ze[7, 4]) == 2048                         # clamped
+        # the whole fp16 range in one block: -65504 / scale lies just above -(top / 2) - 1/2 (the fp16 scale is rounded up
+        # here), so the zero-point is (top - 1) / 2 and the codes are 0 and top - 1
+        oco = getattr(oc, name + "_codes")[0].reshape(T, 8, 128)
+        assert np.array_equal(co[5, 2], oco[5, 2]) and co[5, 2].min() == 0 and co[5, 2].max() == top - 1 and sc[5, 2] > 8000.0
+    assert np.array_equal(g["k_scale"], oc.k_scale) and np.array_equal(g["v_zero"], oc.v_zero)
+    oc_g = oracle_from_export(oc, g)
+    check_dequant(cache, oc_g)
+    q = S.make_q(w, batch=1)
+    for path in (1, 2):
+        cache.set_decode_path(path)
+        check_decode(cache, oc_g, q, tag=f"special blocks bits={bits} path={path}", lse_relative=True)
 
 
 def test_select_sinks_matches_oracle():
