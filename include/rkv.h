@@ -170,7 +170,7 @@ int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, 
  *   host_n_new      [batch] int32 in host memory, 0 <= host_n_new[b] <= n_new_max; read before the call returns
  *   dev_sink_mask   [batch][n_new_max] uint8 or NULL
  * Needs a configuration the matrix-core append kernel covers (reorder inside blocks of 128,
- * rot_heads 2 or 4, v_rotate 0), else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
+ * rot_heads 2 or 4, v_rotate 0, quant_group 128), else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
  * max_tokens (nothing is appended then).  rkv_import_codes returns RKV_ESTATE on such a cache;
  * the export and dequantize views cover rkv_cache_length tokens for every sequence, and what they
  * show past a sequence's own length is unspecified. */
@@ -227,7 +227,8 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
 
 /* Choose the decode kernel: 0 = automatic (default), 1 = force the general kernel (any supported
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
- * the configuration is outside what it covers). */
+ * the configuration is outside what it covers: a reorder across blocks of 128, rot_heads 1 or 8,
+ * quant_group 64 or 32). */
 int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 
 /* Measurement hook: ev_start / ev_stop are hipEvent_t handles (as void*) or NULL.  While set,
