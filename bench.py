@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--meta-format", type=int, default=0, help="0: fp16 scale and zero-point (2.25 bits); 1: FP8 scale, INT8 zero-point (2.125 bits)")
     ap.add_argument("--bits", type=int, default=2, help="bits per code: 2, 3 or 4")
     ap.add_argument("--quant-group", type=int, default=128, help="channels per quantization block: 128 (matrix-core kernels), 64 or 32 (general kernels)")
+    ap.add_argument("--perm-span", type=int, default=128,
+                    help="channels the reorder may move a channel within: 128 (a head), rot_heads*128 (a rotation group) or n_kv_heads*128 (the row, Alg. 1 as printed)")
     ap.add_argument("--ragged-min", type=float, default=1.0,
                     help="below 1: sequence lengths spread evenly from this fraction of the context up to the full context")
     ap.add_argument("--separate-calls", action="store_true",
@@ -129,7 +131,7 @@ def main():
     hip = Hip()
 
     cfg = R.RkvConfig(batch=B, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=max(w.n_sinks, 1),
-                      rot_heads=w.rot_heads, perm_span=128, rope_theta=w.rope_theta, meta_format=args.meta_format,
+                      rot_heads=w.rot_heads, perm_span=args.perm_span, rope_theta=w.rope_theta, meta_format=args.meta_format,
                       bits=args.bits, quant_group=args.quant_group)
     QB, QG = args.bits, args.quant_group
     MB = 2 if args.meta_format == 1 else 4       # bytes of metadata per (token, quantization block)
@@ -248,7 +250,7 @@ def main():
     # measured HBM traffic of the decode kernel (rocprofv3 counters, calibrated; see profiles/)
     traffic = None
     tfile = os.path.join(ROOT, "profiles", f"decode_{w.name}_hbm_traffic.md")
-    default_run = (QB, QG, args.meta_format, NQ, args.path) == (2, 128, 0, 1, 0) and pre_lens is None   # what the counters were collected on
+    default_run = (QB, QG, args.meta_format, NQ, args.path, args.perm_span) == (2, 128, 0, 1, 0, 128) and pre_lens is None   # what the counters were collected on
     if os.path.exists(tfile) and L == w.layers and default_run:
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -268,7 +270,7 @@ def main():
         "dtype": "f32",   # what the path accumulates in; storage is u2 codes + fp16 scale/zero, the rotations are exact fp4 / fp16 matrix products
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {SHAPES.get(w.name, 'custom')} decode, {L} layers x {w.n_q_heads} query / {w.n_kv_heads} KV heads x 128, "
-                               f"batch {B}, context {T}, rotation over {w.rot_heads} heads, {QB}-bit group-{QG}, {w.n_sinks} fp16 sinks",
+                               f"batch {B}, context {T}, rotation over {w.rot_heads} heads, reorder within {args.perm_span} channels, {QB}-bit group-{QG}, {w.n_sinks} fp16 sinks",
                    "decode_path": args.path, "queries_per_step": NQ, "calls_per_step_and_layer": 1 if one_call else 2,
                    "sequence_lengths": "all equal" if pre_lens is None else f"spread evenly from {lens_now[0]} to {lens_now[-1]} tokens",
                    "storage": f"u{QB} codes + " + ("fp16 scale / fp16 zero" if MB == 4 else "FP8 E4M3 scale / INT8 zero") +

@@ -39,7 +39,7 @@ static int check_config(const rkv_config* c, bool need_capacity) {
 }
 
 struct Offsets {
-  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, total;
+  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, xmask, xtt, total;
   int Tpad;
 };
 
@@ -69,6 +69,11 @@ static Offsets plan(const rkv_config* c) {
   o.gid = p; p = align256(p + E * 4);
   o.rope = p; p = align256(p + T * 64 * 8);
   o.hop = p; p = align256(p + 8 * 64 * 4 * 4);
+  {
+    const size_t g = c->rot_heads, nrg = c->n_kv_heads / c->rot_heads;
+    o.xmask = p; p = align256(p + nrg * g * g * 4 * 16);
+    o.xtt = p; p = align256(p + nrg * 128 * g * g * 4);
+  }
   o.total = p;
   return o;
 }
@@ -140,6 +145,9 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.gid = (int*)(c->base + o.gid);
   v.rope = (float2*)(c->base + o.rope);
   v.hop = (uint32_t*)(c->base + o.hop);
+  v.xmask = (uint32_t*)(c->base + o.xmask);
+  v.xtt = (float*)(c->base + o.xtt);
+  c->in_groups = 0;
   v.B = cfg->batch;
   v.Hq = cfg->n_q_heads;
   v.Hkv = cfg->n_kv_heads;
@@ -254,8 +262,33 @@ RKV_EXPORT int rkv_set_perm(rkv_cache* cache, const int32_t* dev_perm, void* str
   RKV_HIP_CHECK(hipMemcpyAsync(cache->v.perm, p.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipMemcpyAsync(cache->v.pinv, inv.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipMemcpyAsync(cache->v.gid, gid.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
+  // tables of the matrix-core decode path for reorders that cross 128-blocks inside a rotation group
+  const int g = cache->v.g, n = cache->v.n, nrg = cache->v.NRG;
+  int in_groups = (g == 2 || g == 4) ? 1 : 0;
+  for (int c = 0; c < E && in_groups; ++c)
+    if (inv[c] / n != c / n) in_groups = 0;
+  std::vector<uint32_t> xmask;
+  std::vector<float> xtt;
+  if (in_groups && !aligned) {
+    xmask.assign((size_t)nrg * g * g * 16, 0u);
+    xtt.assign((size_t)nrg * 128 * g * g, 0.f);
+    for (int rg = 0; rg < nrg; ++rg) {
+      for (int c = 0; c < n; ++c) {                          // rotated channel of the group
+        const int blk = c >> 7, kap = c & 127, q = kap >> 5, vreg = (kap >> 3) & 3, e = kap & 7;
+        const int gq = inv[rg * n + c] / 128 - rg * g;       // its quantization block within the group
+        xmask[((((size_t)rg * g + blk) * g + gq) * 4 + q) * 4 + vreg] |= 0xFu << (4 * e);
+        for (int i = 0; i < n; ++i) {                        // output channel i = 128 a + j of H_n (entries (-1)^popcount(i & c))
+          const float sgn = (__builtin_popcount((unsigned)(i & c)) & 1) ? -1.f : 1.f;
+          xtt[(((size_t)rg * 128 + (i & 127)) * g + gq) * g + (i >> 7)] += sgn;
+        }
+      }
+    }
+    RKV_HIP_CHECK(hipMemcpyAsync(cache->v.xmask, xmask.data(), xmask.size() * 4, hipMemcpyHostToDevice, s));
+    RKV_HIP_CHECK(hipMemcpyAsync(cache->v.xtt, xtt.data(), xtt.size() * 4, hipMemcpyHostToDevice, s));
+  }
   RKV_HIP_CHECK(hipStreamSynchronize(s));
   cache->blocks_aligned = aligned;
+  cache->in_groups = in_groups;
   return RKV_OK;
 }
 

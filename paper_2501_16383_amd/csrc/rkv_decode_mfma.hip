@@ -169,8 +169,15 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // Hadamard operand with entries +-4 in place of +-1, accumulating onto the low plane's products,
 // so that the big products yield H_128 (c / 2) as before.  Value phase: it accumulates separately
 // and is folded in, times 4, once per chunk.  Sums stay exact: |H_128 (c / 2)| <= 960 < 1024.
-template <int G, int REP, bool MULTI, bool META8, int HB>
-__global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
+// XB: the reorder crosses 128-blocks inside the rotation group: a rotated channel belongs to any
+// of the group's G quantization blocks.  The key phase then runs G passes per channel tile, one
+// per quantization block: the FP4 operands are ANDed with that block's mask (xmask), the big
+// products yield H_128 of its codes alone, and the small products - with that block's scale in all
+// four slots, signs of H_g as before - accumulate over the passes.  The zero-points no longer
+// collapse onto channel 0; their term, sum over the quantization blocks of s z / 2 times the
+// rotated indicator of the block's channels (xtt), starts the accumulators.
+template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false>
+__global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq) {
   constexpr bool HI = HB != 0;
@@ -190,6 +197,9 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
   __shared__ int s_lim[MULTI ? NH : 1];          // last position each served query head may attend
   constexpr int QV = REP == 1 ? 4 : 1;            // query versions held (positions pos - r); with REP > 1 only r = 0
   __shared__ uint4 s_q[QV][4][NH / 2][16];        // [r][p][f / 4][n] x 4 floats f % 4, f = (KV head * REP + query head of it) * 2 + (lo, hi)
+  __shared__ uint4 s_xmask[XB ? G * G * 4 : 1];   // [rotated block][quantization block][lane group q]
+  __shared__ float s_xtt[XB ? 128 * G * G : 1];   // [channel][quantization block][head]
+  static_assert(!XB || (REP == 1 && !MULTI && !META8 && HB == 0), "the cross-block variant exists for the plain configuration only");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -272,6 +282,10 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
   if constexpr (MULTI) {
     // served head a * REP + rri is virtual head rrg * REP + rri of its KV head: query token (that / heads per token)
     if (tid < NH) s_lim[tid] = min(q_lim[b * nq + (rrg * REP + tid % REP) / (rep / nq)], len - 1);
+  }
+  if constexpr (XB) {                              // this rotation group's masks and zero-point table
+    for (int i = tid; i < G * G * 4; i += 256) s_xmask[i] = reinterpret_cast<const uint4*>(v.xmask)[(size_t)rg * (G * G * 4) + i];
+    for (int i = tid; i < 128 * G * G; i += 256) s_xtt[i] = v.xtt[(size_t)rg * (128 * G * G) + i];
   }
   // queries of this rotation group, already RoPE'd, scaled and laid out as s_q by k_prep_q
   for (int i = tid; i < QV * 16 * 4 * 2 * NH / 4; i += 256)
@@ -412,6 +426,19 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
           }
           zB[r] = as_v4h(z01, z23);
         }
+        float xw[XB ? 4 : 1][XB ? G : 1];                  // cross-block variant: s z / 2 per (token, quantization block)
+        uint32_t xs2[XB ? 4 : 1][XB ? G : 1];              // and the block's fp16 scale in both halves of a dword
+        if constexpr (XB) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int gq = 0; gq < G; ++gq) {
+              float s_, z_;
+              rkv_unpack_meta(mw[r][gq], s_, z_);
+              xw[r][gq] = 0.5f * s_ * z_;
+              xs2[r][gq] = (mw[r][gq] & 0xffffu) * 0x10001u;
+            }
+        }
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
 
         // The key phase runs in passes over RP of the lane's four tokens, so that the score
@@ -435,10 +462,12 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
             Hlo[0] = (int)h0.x; Hlo[1] = (int)h0.y; Hlo[2] = (int)h0.z; Hlo[3] = (int)h0.w; Hlo[4] = Hlo[5] = Hlo[6] = Hlo[7] = 0;
             Hhi[0] = (int)h1.x; Hhi[1] = (int)h1.y; Hhi[2] = (int)h1.z; Hhi[3] = (int)h1.w; Hhi[4] = Hhi[5] = Hhi[6] = Hhi[7] = 0;
             const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (!XB) {
 #pragma unroll
-            for (int blk = 0; blk < G; ++blk) {
-              lo[blk] = mfma_fp4(A[blk], Hlo, zero4);
-              hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
+              for (int blk = 0; blk < G; ++blk) {
+                lo[blk] = mfma_fp4(A[blk], Hlo, zero4);
+                hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
+              }
             }
             if constexpr (HI) {
               // FP4 1.0 (0x2) and -1.0 (0xA) with bit 2 set are 4.0 and -4.0
@@ -454,6 +483,56 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
               }
             }
           }
+          v4f xk_lo[XB ? 4 : 1], xk_hi[XB ? 4 : 1];           // cross-block variant: the keys of the lane's four tokens
+          if constexpr (XB) {
+            // zero-points: - sum over the quantization blocks of (s z / 2) * (rotated indicator)[head][channel]
+            const int j_lo = v.rope_style ? 2 * (16 * p + n) : 16 * p + n, j_hi = v.rope_style ? j_lo + 1 : j_lo + 64;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+#pragma unroll
+              for (int a = 0; a < 4; ++a) {
+                float zl = 0.f, zh = 0.f;
+                if (a < G) {
+#pragma unroll
+                  for (int gq = 0; gq < G; ++gq) {
+                    zl = fmaf(xw[r][gq], s_xtt[(j_lo * G + gq) * G + a], zl);
+                    zh = fmaf(xw[r][gq], s_xtt[(j_hi * G + gq) * G + a], zh);
+                  }
+                }
+                xk_lo[r][a] = -zl;
+                xk_hi[r][a] = -zh;
+              }
+            }
+#pragma unroll
+            for (int gq = 0; gq < G; ++gq) {
+              const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+              v8i Hlo, Hhi;
+              const uint4 h0 = s_H[p][lane], h1 = s_H[p + 4][lane];
+              Hlo[0] = (int)h0.x; Hlo[1] = (int)h0.y; Hlo[2] = (int)h0.z; Hlo[3] = (int)h0.w; Hlo[4] = Hlo[5] = Hlo[6] = Hlo[7] = 0;
+              Hhi[0] = (int)h1.x; Hhi[1] = (int)h1.y; Hhi[2] = (int)h1.z; Hhi[3] = (int)h1.w; Hhi[4] = Hhi[5] = Hhi[6] = Hhi[7] = 0;
+#pragma unroll
+              for (int blk = 0; blk < G; ++blk) {
+                const uint4 m = s_xmask[(blk * G + gq) * 4 + q];
+                v8i Am = A[blk];
+                Am[0] &= (int)m.x; Am[1] &= (int)m.y; Am[2] &= (int)m.z; Am[3] &= (int)m.w;
+                lo[blk] = mfma_fp4(Am, Hlo, zero4);
+                hi[blk] = mfma_fp4(Am, Hhi, zero4);
+              }
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                // the block's scale in all four slots (contraction over the rotated blocks), signs of H_g
+                const uint32_t s2 = xs2[r][gq];
+                const v4h sx = as_v4h((s2 ^ sm01) & keep_row, G == 4 ? (s2 ^ sm23) & keep_row : 0u);
+                if constexpr (G == 4) {
+                  xk_lo[r] = mfma_4x4x4(sx, as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), xk_lo[r]);
+                  xk_hi[r] = mfma_4x4x4(sx, as_v4h(pk_f16(hi[0][r], hi[1][r]), pk_f16(hi[2][r], hi[3][r])), xk_hi[r]);
+                } else {
+                  xk_lo[r] = mfma_4x4x4(sx, as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), xk_lo[r]);
+                  xk_hi[r] = mfma_4x4x4(sx, as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), xk_hi[r]);
+                }
+              }
+            }
+          }
           float c = cs_c[p], s = cs_s[p];                      // angles of the pass's first token (REP == 1: of token 4q)
 #pragma unroll
           for (int rr = 0; rr < RP; ++rr) {
@@ -465,6 +544,10 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
             const v4f z4 = {0.f, 0.f, 0.f, 0.f};
             v4f klo, khi;
             v4f zc = z4;
+            if constexpr (XB) {
+              klo = xk_lo[r];
+              khi = xk_hi[r];
+            } else {
             if (p == 0) zc = mfma_4x4x4(sA[r], zB[r], z4) * -64.0f;
             if constexpr (G == 4) {
               klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), zc);
@@ -472,6 +555,7 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
             } else {
               klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), zc);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), z4);
+            }
             }
             // the query: with REP == 1 the copy rotated back by r positions, else the plain one
             // (floats 2 * REP * a .. of the row belong to KV head a: [query head of it][lo, hi])
@@ -710,8 +794,15 @@ __global__ void __launch_bounds__(256, HB ? MF_OCC_HI : MF_OCC) k_decode_mfma(Rk
   }
 }
 
+// the cross-block variant of the kernel: a reorder inside the rotation groups, plain configuration
+static bool mfma_cross_block(const rkv_cache* c) {
+  const RkvView& v = c->v;
+  return !c->blocks_aligned && c->in_groups && v.qg == 128 && v.hb == 0 && !v.meta8 && (v.g == 2 || v.g == 4);
+}
+
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
+  if (mfma_cross_block(c)) return true;
   // 2-bit codes, or wider ones (a second plane), in groups of 128
   return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4);
 }
@@ -764,7 +855,9 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
   const int rep = v.Hq / v.Hkv;
-  const int share = rkv_mfma_share(rep);
+  const bool xb = mfma_cross_block(c);
+  if (xb && multi) return RKV_EINVAL;                       // the cross-block variant takes one query token per step
+  const int share = xb ? 1 : rkv_mfma_share(rep);           // and one query head per workgroup
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   dim3 grid(8 * ((v.B * v.NRG + 7) / 8) * nch * (rep / share), 1, 1);   // see the kernel for the mapping
@@ -775,6 +868,10 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   }
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch == 0) {}                                          // an empty cache has only the current token
+  else if (xb) {
+    if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+    else hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+  }
   else if (multi) launch_kernel<true>(v, share, grid, qt, part, nch, q_pos, nq, s);
   else launch_kernel<false>(v, share, grid, qt, part, nch, nullptr, 1, s);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));

@@ -60,6 +60,11 @@ struct RkvView {
   int* gid;
   float2* rope;
   uint32_t* hop;     // Hadamard B-operand image for the FP4 matrix instruction: [8 tiles][64 lanes][4 dwords]
+  // For a reorder that crosses 128-blocks but stays inside the rotation groups (written by rkv_set_perm):
+  uint32_t* xmask;   // [rot group][rotated block][quantization block of the group][lane group q][4 dwords]: FP4-operand
+                     // nibbles (0xF) of the rotated block's channels that belong to that quantization block
+  float* xtt;        // [rot group][channel j 0..127][quantization block][head a]: (H_n m)[128 a + j], m = the
+                     // indicator of the quantization block's rotated channels, H_n with entries +-1
   int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate, keys_rotated;
   const int* lens;   // per-sequence lengths [B] once the sequences differ in length, else null (all have `len` tokens)
   const int* cstart; // with `lens`: cstart[b] = 256-token chunks of the sequences before b, cstart[B] = all of them
@@ -89,6 +94,7 @@ struct rkv_cache {
   size_t off_tables;      // everything before this offset is cleared by reset
   int blocks_aligned;     // 1 if the reorder keeps every rotated channel in its block of 128
   int wide;               // 1 with codes wider than 2 bits or groups smaller than 128: general kernels only
+  int in_groups;          // 1 if the reorder keeps every rotated channel inside its rotation group (and rot_heads is 2 or 4)
   int decode_path;
   int n_cu;               // compute units of the device the cache lives on
   hipEvent_t ev_start, ev_stop;   // optional measurement hook around the main kernels
