@@ -167,6 +167,34 @@ def test_reorder_across_blocks(span_kind):
     full_check(w, cfg, 100, perm=perm, paths=(1, 2) if span_kind == "group" else (1,))
 
 
+@pytest.mark.parametrize("g,hq,style", [(4, 8, 0), (2, 8, 0), (4, 32, 0), (2, 16, 1), (4, 8, 1)])
+def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style):
+    """perm_span = the rotation size: the quantization blocks mix channels of all the group's heads.
+    The matrix-core decode kernel's cross-block variant (masked operands, one pass per quantization
+    block) against the oracle and against the general kernel: rotation over 4 and 2 heads, GQA,
+    both RoPE pairings, several chunks and a ragged tail, sinks, single-token steps, the current
+    token as an exact row."""
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
+    cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=g, perm_span=128 * g,
+                      rope_style=style)
+    perm = calibrated_perm(w, cfg, offset_variant=True)
+    assert not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
+    cache, oc, q = full_check(w, cfg, 613, perm=perm, chunks=[0, 300, 301, 302, 613], paths=(1, 2))
+    cache.set_decode_path(2)
+    k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
+    out = cache.decode_attention(P.gpu(q), k_cur=P.gpu(k1[:, 0]), v_cur=P.gpu(v1[:, 0]))      # the cache holds the oracle's codes here
+    torch.cuda.synchronize()
+    ref, _ = O.decode_attention(oc, q, None, k1[:, 0], v1[:, 0])
+    assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
+    out = cache.decode_step(P.gpu(k1), P.gpu(v1), P.gpu(q))
+    torch.cuda.synchronize()
+    O.quantize_append(oc, k1, v1, None)
+    ref, _ = O.decode_attention(oracle_from_export(oc, P.export_numpy(cache)), q)
+    assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
+    with pytest.raises(R.RkvError):                              # several query tokens: not in this variant
+        cache.decode_attention_multi(P.gpu(np.stack([q, q], axis=1)), P.gpu(np.array([[600, 601], [600, 601]], dtype=np.int32)))
+
+
 def test_gqa_llama3_shape():
     """Config 4's geometry on a slice: 4 query heads per KV head, rope base 500000."""
     w = small("cfg4", n_q_heads=16, n_kv_heads=4)
