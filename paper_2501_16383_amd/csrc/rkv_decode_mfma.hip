@@ -309,7 +309,9 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
       uint4 cw[G / 2], cwh[HI ? G / 2 : 1];
       constexpr int MW = META8 ? G / 2 : G;              // metadata dwords per token and rotation group
       uint32_t mw[4][MW];
+      uint32_t xmeta = 0;                                  // cross-block variant: (scale, zero) of token n of the tile, quantization block q
       auto load_tile = [&](int ti) {
+        if constexpr (XB) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
 #pragma unroll
         for (int pr = 0; pr < G / 2; ++pr) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
         if constexpr (HI) {
@@ -426,18 +428,18 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
           }
           zB[r] = as_v4h(z01, z23);
         }
-        float xw[XB ? 4 : 1][XB ? G : 1];                  // cross-block variant: s z / 2 per (token, quantization block)
-        uint32_t xs2[XB ? 4 : 1][XB ? G : 1];              // and the block's fp16 scale in both halves of a dword
+        // cross-block variant: the block's fp16 scale in both halves of a dword, and - (s z / 2) of
+        // (token n, quantization block q), the A operand of the zero-point product
+        uint32_t xs2[XB ? 4 : 1][XB ? G : 1];
+        float xwa = 0.f;
         if constexpr (XB) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int gq = 0; gq < G; ++gq) {
-              float s_, z_;
-              rkv_unpack_meta(mw[r][gq], s_, z_);
-              xw[r][gq] = 0.5f * s_ * z_;
-              xs2[r][gq] = (mw[r][gq] & 0xffffu) * 0x10001u;
-            }
+            for (int gq = 0; gq < G; ++gq) xs2[r][gq] = (mw[r][gq] & 0xffffu) * 0x10001u;
+          float s_, z_;
+          rkv_unpack_meta(xmeta, s_, z_);
+          xwa = -0.5f * s_ * z_;
         }
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
 
@@ -485,22 +487,23 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
           }
           v4f xk_lo[XB ? 4 : 1], xk_hi[XB ? 4 : 1];           // cross-block variant: the keys of the lane's four tokens
           if constexpr (XB) {
-            // zero-points: - sum over the quantization blocks of (s z / 2) * (rotated indicator)[head][channel]
+            // zero-points: - sum over the quantization blocks of (s z / 2) * (rotated indicator)[head][channel],
+            // a [16 tokens x G] x [G x 16 channels] product in fp32 (s z is not an fp16 number) per head
+            // and channel tile; the result has the layout of the other accumulators
             const int j_lo = v.rope_style ? 2 * (16 * p + n) : 16 * p + n, j_hi = v.rope_style ? j_lo + 1 : j_lo + 64;
+            const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            for (int a = 0; a < 4; ++a) {
+              v4f zl = zero4, zh = zero4;
+              if (a < G) {
+                const float bl = q < G ? s_xtt[(j_lo * G + q) * G + a] : 0.f, bh = q < G ? s_xtt[(j_hi * G + q) * G + a] : 0.f;
+                zl = __builtin_amdgcn_mfma_f32_16x16x4f32(xwa, bl, zero4, 0, 0, 0);
+                zh = __builtin_amdgcn_mfma_f32_16x16x4f32(xwa, bh, zero4, 0, 0, 0);
+              }
 #pragma unroll
-              for (int a = 0; a < 4; ++a) {
-                float zl = 0.f, zh = 0.f;
-                if (a < G) {
-#pragma unroll
-                  for (int gq = 0; gq < G; ++gq) {
-                    zl = fmaf(xw[r][gq], s_xtt[(j_lo * G + gq) * G + a], zl);
-                    zh = fmaf(xw[r][gq], s_xtt[(j_hi * G + gq) * G + a], zh);
-                  }
-                }
-                xk_lo[r][a] = -zl;
-                xk_hi[r][a] = -zh;
+              for (int r = 0; r < 4; ++r) {
+                xk_lo[r][a] = zl[r];
+                xk_hi[r][a] = zh[r];
               }
             }
 #pragma unroll
