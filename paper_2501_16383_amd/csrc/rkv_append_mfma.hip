@@ -105,7 +105,11 @@ __device__ __forceinline__ void fused_round_consts(float zero, float& base, floa
 // value waves of a slab, each contribute one bit in four to a dword of it.
 // HB = 2: 4-bit codes.  The same arithmetic with 15 steps; the upper two bits of every code go to a
 // second plane with the layout of the first (a second image in LDS, written the same way).
-template <int G, int HB>
+// XW: the reorder crosses 128-blocks inside the rotation group (2-bit codes): a rotated channel's
+// quantization block is looked up (gid), the minima and maxima are kept per quantization block,
+// and every element takes the parameters of its own block.  Codes stay where they are - by
+// rotated channel - so only the key role differs.
+template <int G, int HB, bool XW = false>
 __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                  int n_new, int slab0, int bx, int rg, int b) {
   constexpr int PL = 2 * G;                    // value channels per lane
@@ -222,7 +226,38 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
           }
         }
     }
-    {
+    // cross-block variant: quantization block (within the group) of each of the lane's channels, 2 bits each
+    uint32_t gsel[G];
+    if constexpr (XW) {
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        gsel[h] = 0;
+#pragma unroll
+        for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const int chan = 128 * h + 32 * q + 8 * (2 * d + pph) + 4 * ppl + rr;
+            gsel[h] |= (uint32_t)(v.gid[rg * n + chan] - rg * G) << (2 * (4 * ppl + rr));
+          }
+      }
+#pragma unroll
+      for (int gq = 0; gq < G; ++gq) {
+        float mn = 3.0e38f, mx = -3.0e38f;
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+          for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+              const bool mine = ((gsel[h] >> (2 * (4 * ppl + rr))) & 3u) == (uint32_t)gq;
+              mn = mine ? fminf(mn, acc[h][ppl][rr]) : mn;
+              mx = mine ? fmaxf(mx, acc[h][ppl][rr]) : mx;
+            }
+        mn = fminf(mn, __shfl_xor(mn, 16)); mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mn = fminf(mn, __shfl_xor(mn, 32)); mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (q == 0) s_mm[d][pph][col][gq] = make_float2(mn, mx);
+      }
+    } else {
       // min / max of this wave's quarter of every block: 8 values in the lane, then the four q groups
 #pragma unroll
       for (int a = 0; a < G; ++a) {
@@ -253,6 +288,37 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       if (wave == 0 && q < G) meta[col * G + ah] = rkv_pack_meta(sc, zero_h);
       float base_h, add_h;
       fused_round_consts(zero_h, base_h, add_h);
+      if constexpr (XW) {
+        // the parameters of all G quantization blocks of this token, then each element takes its own
+        float inv2s[G], adds[G], bases[G];
+#pragma unroll
+        for (int gq = 0; gq < G; ++gq) {
+          const int src4 = 4 * (col + 16 * gq);
+          inv2s[gq] = lane_read(inv2_h, src4);
+          adds[gq] = lane_read(add_h, src4);
+          bases[gq] = lane_read(base_h, src4);
+        }
+#pragma unroll
+        for (int a = 0; a < G; ++a) {
+          uint32_t word = 0;
+#pragma unroll
+          for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+              const uint32_t gq = (gsel[a] >> (2 * (4 * ppl + rr))) & 3u;
+              float inv2 = inv2s[0], add = adds[0], base = bases[0];
+#pragma unroll
+              for (int k = 1; k < G; ++k) {
+                inv2 = gq == (uint32_t)k ? inv2s[k] : inv2;
+                add = gq == (uint32_t)k ? adds[k] : add;
+                base = gq == (uint32_t)k ? bases[k] : base;
+              }
+              const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], inv2, add), base, base + 3.0f);
+              word += (__float_as_uint(c) - __float_as_uint(base)) << (16 * ppl + 4 * rr);
+            }
+          img[pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = word << (2 * pph);
+        }
+      } else {
 #pragma unroll
       for (int a = 0; a < G; ++a) {
         const int src4 = 4 * (col + 16 * a);
@@ -281,6 +347,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         } else {
           img[io] = word << (2 * pph);
         }
+      }
       }
     }
     __syncthreads();
@@ -465,10 +532,10 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   }
 }
 
-template <int G, int HB>
-__global__ void __launch_bounds__(256, HB ? 4 : 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
-                                                              int n_new, int slab0) {
-  append_mfma_body<G, HB>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+template <int G, int HB, bool XW = false>
+__global__ void __launch_bounds__(256, (HB || XW) ? 4 : 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+                                                                      int n_new, int slab0) {
+  append_mfma_body<G, HB, XW>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // One decode step's write half and query preparation in one launch: the first 3 * n_slabs
@@ -476,12 +543,12 @@ __global__ void __launch_bounds__(256, HB ? 4 : 6) k_append_mfma(RkvView v, cons
 // rest prepare that rotation group's query heads (two heads per workgroup) for the decode kernel,
 // which saves a launch of its own for a few microseconds of work.  The query's default position
 // is the appended token's: one past the last token the view knows of.
-template <int G, int HB>
+template <int G, int HB, bool XW = false>
 __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                    int slab0, int n_append_blocks, const __half* __restrict__ q,
                                                    const int* __restrict__ q_pos, float* __restrict__ qr, int share) {
   if ((int)blockIdx.x < n_append_blocks) {
-    append_mfma_body<G, HB>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+    append_mfma_body<G, HB, XW>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
     return;
   }
   const int rep = v.Hq / v.Hkv;
@@ -491,8 +558,10 @@ __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* _
 
 bool rkv_append_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  // 2-bit codes, or wider ones (a second plane), in groups of 128
-  return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
+  // 2-bit codes, or wider ones (a second plane), in groups of 128; a reorder across 128-blocks
+  // inside the rotation groups with 2-bit codes
+  if (!c->blocks_aligned && !(c->in_groups && v.hb == 0 && !c->cfg.keys_rotated)) return false;
+  return v.qg == 128 && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 
 // max_slabs: most 32-token slabs any sequence's new tokens touch, or 0 to work it out for n_new
@@ -511,7 +580,10 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   }
   dim3 grid(3 * max_slabs, v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  if (v.hb == 2) {
+  if (!c->blocks_aligned) {
+    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    else hipLaunchKernelGGL((k_append_mfma<2, 0, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  } else if (v.hb == 2) {
     if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
     else hipLaunchKernelGGL((k_append_mfma<2, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   } else if (v.hb == 1) {
@@ -531,7 +603,10 @@ int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const 
   int max_slabs = 1;                                        // one token touches one slab of its sequence
   const int n_append = 3 * max_slabs, rep = v.Hq / v.Hkv;
   dim3 grid(n_append + v.g * rep / 2, v.NRG, v.B);
-  if (v.hb == 2) {
+  if (!c->blocks_aligned) {
+    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+    else hipLaunchKernelGGL((k_step_mfma<2, 0, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  } else if (v.hb == 2) {
     if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
     else hipLaunchKernelGGL((k_step_mfma<2, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
   } else if (v.hb == 1) {

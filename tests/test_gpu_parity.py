@@ -193,6 +193,31 @@ def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style):
     assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
     with pytest.raises(R.RkvError):                              # several query tokens: not in this variant
         cache.decode_attention_multi(P.gpu(np.stack([q, q], axis=1)), P.gpu(np.array([[600, 601], [600, 601]], dtype=np.int32)))
+    # sequences of different lengths, and the one-call step against the two calls, bit for bit
+    k, v, mask = S.make_kv(w, 40, batch=2)
+    a, b = R.RkvCache(cfg), R.RkvCache(cfg)
+    for c in (a, b):
+        c.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+        c.quantize_append_ragged(P.gpu(k[:, :33]), P.gpu(v[:, :33]), [33, 21], P.gpu(mask[:, :33]))
+    for s_ in range(4):
+        qq = P.gpu(S.make_q(w, batch=2, step=s_))
+        kk, vv = P.gpu(k[:, 33 + s_:34 + s_]), P.gpu(v[:, 33 + s_:34 + s_])
+        o1 = a.decode_step(kk, vv, qq)
+        b.quantize_append(kk, vv)
+        o2 = b.decode_attention(qq)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2), f"step {s_}"
+    ea, eb = a.export_codes(), b.export_codes()
+    torch.cuda.synchronize()
+    assert a.lengths == [37, 25] and all(torch.equal(ea[name], eb[name]) for name in ea)
+    oc1 = O.cache_new(P.oracle_cfg(dataclasses.replace(cfg, batch=1)), perm)                 # sequence 1 alone in the oracle
+    O.quantize_append(oc1, np.concatenate([k[1:2, :21], k[1:2, 33:37]], axis=1), np.concatenate([v[1:2, :21], v[1:2, 33:37]], axis=1),
+                      np.concatenate([mask[1:2, :21], np.zeros((1, 4), np.uint8)], axis=1))
+    g1 = {name: arr[1:2, :25].cpu().numpy() for name, arr in ea.items()}
+    for name in ("k_codes", "v_codes"):
+        g1[name] = O.unpack_canonical(g1[name])
+    P.compare_codes(oc1.k_rot, oc1.k_codes, oc1.k_scale, oc1.k_zero, g1["k_codes"], g1["k_scale"].astype(np.float64),
+                    g1["k_zero"].astype(np.float64), "cross-block ragged K", rot_span=128 * g)
 
 
 def test_gqa_llama3_shape():
