@@ -169,8 +169,9 @@ int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, 
  *   dev_k, dev_v    [batch][n_new_max][n_kv_heads][head_dim] fp16; rows beyond host_n_new[b] are not read
  *   host_n_new      [batch] int32 in host memory, 0 <= host_n_new[b] <= n_new_max; read before the call returns
  *   dev_sink_mask   [batch][n_new_max] uint8 or NULL
- * Needs a configuration the matrix-core append kernel covers (reorder inside blocks of 128,
- * rot_heads 2 or 4, v_rotate 0, quant_group 128), else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
+ * Needs a configuration the matrix-core append kernel covers (reorder inside blocks of 128 - or,
+ * with 2-bit codes, inside the rotation groups -, rot_heads 2 or 4, v_rotate 0, quant_group 128),
+ * else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
  * max_tokens (nothing is appended then).  rkv_import_codes returns RKV_ESTATE on such a cache;
  * the export and dequantize views cover rkv_cache_length tokens for every sequence, and what they
  * show past a sequence's own length is unspecified. */

@@ -39,7 +39,7 @@ static int check_config(const rkv_config* c, bool need_capacity) {
 }
 
 struct Offsets {
-  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, xmask, xtt, total;
+  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, xmask, xtt, xgsel, total;
   int Tpad;
 };
 
@@ -73,6 +73,7 @@ static Offsets plan(const rkv_config* c) {
     const size_t g = c->rot_heads, nrg = c->n_kv_heads / c->rot_heads;
     o.xmask = p; p = align256(p + nrg * g * g * 4 * 16);
     o.xtt = p; p = align256(p + nrg * 128 * g * g * 4);
+    o.xgsel = p; p = align256(p + nrg * 16 * g * 4);
   }
   o.total = p;
   return o;
@@ -147,6 +148,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.hop = (uint32_t*)(c->base + o.hop);
   v.xmask = (uint32_t*)(c->base + o.xmask);
   v.xtt = (float*)(c->base + o.xtt);
+  v.xgsel = (uint32_t*)(c->base + o.xgsel);
   c->in_groups = 0;
   v.B = cfg->batch;
   v.Hq = cfg->n_q_heads;
@@ -267,16 +269,21 @@ RKV_EXPORT int rkv_set_perm(rkv_cache* cache, const int32_t* dev_perm, void* str
   int in_groups = (g == 2 || g == 4) ? 1 : 0;
   for (int c = 0; c < E && in_groups; ++c)
     if (inv[c] / n != c / n) in_groups = 0;
-  std::vector<uint32_t> xmask;
+  std::vector<uint32_t> xmask, xgsel;
   std::vector<float> xtt;
   if (in_groups && !aligned) {
     xmask.assign((size_t)nrg * g * g * 16, 0u);
     xtt.assign((size_t)nrg * 128 * g * g, 0.f);
+    xgsel.assign((size_t)nrg * 16 * g, 0u);
     for (int rg = 0; rg < nrg; ++rg) {
       for (int c = 0; c < n; ++c) {                          // rotated channel of the group
         const int blk = c >> 7, kap = c & 127, q = kap >> 5, vreg = (kap >> 3) & 3, e = kap & 7;
         const int gq = inv[rg * n + c] / 128 - rg * g;       // its quantization block within the group
         xmask[((((size_t)rg * g + blk) * g + gq) * 4 + q) * 4 + vreg] |= 0xFu << (4 * e);
+        {
+          const int w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);   // 2 (wave & 1) + (wave >> 1) = w8
+          xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)gq << (2 * (kap & 7));
+        }
         for (int i = 0; i < n; ++i) {                        // output channel i = 128 a + j of H_n (entries (-1)^popcount(i & c))
           const float sgn = (__builtin_popcount((unsigned)(i & c)) & 1) ? -1.f : 1.f;
           xtt[(((size_t)rg * 128 + (i & 127)) * g + gq) * g + (i >> 7)] += sgn;
@@ -285,6 +292,7 @@ RKV_EXPORT int rkv_set_perm(rkv_cache* cache, const int32_t* dev_perm, void* str
     }
     RKV_HIP_CHECK(hipMemcpyAsync(cache->v.xmask, xmask.data(), xmask.size() * 4, hipMemcpyHostToDevice, s));
     RKV_HIP_CHECK(hipMemcpyAsync(cache->v.xtt, xtt.data(), xtt.size() * 4, hipMemcpyHostToDevice, s));
+    RKV_HIP_CHECK(hipMemcpyAsync(cache->v.xgsel, xgsel.data(), xgsel.size() * 4, hipMemcpyHostToDevice, s));
   }
   RKV_HIP_CHECK(hipStreamSynchronize(s));
   cache->blocks_aligned = aligned;

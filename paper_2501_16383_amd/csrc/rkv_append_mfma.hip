@@ -230,16 +230,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     uint32_t gsel[G];
     if constexpr (XW) {
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        gsel[h] = 0;
-#pragma unroll
-        for (int ppl = 0; ppl < 2; ++ppl)
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            const int chan = 128 * h + 32 * q + 8 * (2 * d + pph) + 4 * ppl + rr;
-            gsel[h] |= (uint32_t)(v.gid[rg * n + chan] - rg * G) << (2 * (4 * ppl + rr));
-          }
-      }
+      for (int h = 0; h < G; ++h) gsel[h] = v.xgsel[(((size_t)rg * 4 + wave) * 4 + q) * G + h];   // written by rkv_set_perm
 #pragma unroll
       for (int gq = 0; gq < G; ++gq) {
         float mn = 3.0e38f, mx = -3.0e38f;

@@ -65,6 +65,9 @@ struct RkvView {
                      // nibbles (0xF) of the rotated block's channels that belong to that quantization block
   float* xtt;        // [rot group][channel j 0..127][quantization block][head a]: (H_n m)[128 a + j], m = the
                      // indicator of the quantization block's rotated channels, H_n with entries +-1
+  uint32_t* xgsel;   // [rot group][wave 0..3][lane group q][head h]: the quantization blocks (2 bits each, element
+                     // 4 ppl + rr) of the eight channels 128 h + 32 q + 8 (2 (wave & 1) + (wave >> 1)) + 4 ppl + rr
+                     // that a lane of the append kernel's key role holds
   int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate, keys_rotated;
   const int* lens;   // per-sequence lengths [B] once the sequences differ in length, else null (all have `len` tokens)
   const int* cstart; // with `lens`: cstart[b] = 256-token chunks of the sequences before b, cstart[B] = all of them
