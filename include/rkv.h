@@ -230,7 +230,7 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
  * the configuration is outside what it covers: a reorder across rotation groups, rot_heads 1 or
  * 8, quant_group 64 or 32; a reorder across blocks of 128 inside the rotation groups only with
- * 2-bit codes, fp16 metadata and rkv_decode_attention). */
+ * 2-bit codes and one query token per step). */
 int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 
 /* Measurement hook: ev_start / ev_stop are hipEvent_t handles (as void*) or NULL.  While set,

@@ -199,7 +199,7 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
   __shared__ uint4 s_q[QV][4][NH / 2][16];        // [r][p][f / 4][n] x 4 floats f % 4, f = (KV head * REP + query head of it) * 2 + (lo, hi)
   __shared__ uint4 s_xmask[XB ? G * G * 4 : 1];   // [rotated block][quantization block][lane group q]
   __shared__ float s_xtt[XB ? 128 * G * G : 1];   // [channel][quantization block][head]
-  static_assert(!XB || (REP == 1 && !MULTI && !META8 && HB == 0), "the cross-block variant exists for the plain configuration only");
+  static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -309,9 +309,13 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
       uint4 cw[G / 2], cwh[HI ? G / 2 : 1];
       constexpr int MW = META8 ? G / 2 : G;              // metadata dwords per token and rotation group
       uint32_t mw[4][MW];
-      uint32_t xmeta = 0;                                  // cross-block variant: (scale, zero) of token n of the tile, quantization block q
+      uint32_t xmeta = 0, xmeta2 = 0;                      // cross-block variant: (scale, zero) of token n of the tile, quantization block q
       auto load_tile = [&](int ti) {
-        if constexpr (XB) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
+        if constexpr (XB && !META8) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
+        if constexpr (XB && META8) {                       // the token's scale bytes and zero-point bytes
+          xmeta = kmeta[(size_t)(ti * 16 + n) * MW];
+          if constexpr (G == 4) xmeta2 = kmeta[(size_t)(ti * 16 + n) * MW + 1];
+        }
 #pragma unroll
         for (int pr = 0; pr < G / 2; ++pr) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
         if constexpr (HI) {
@@ -436,9 +440,26 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
 #pragma unroll
           for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int gq = 0; gq < G; ++gq) xs2[r][gq] = (mw[r][gq] & 0xffffu) * 0x10001u;
-          float s_, z_;
-          rkv_unpack_meta(xmeta, s_, z_);
+            for (int gq = 0; gq < G; ++gq) {
+              if constexpr (META8) {                       // scale byte gq of the token's first dword: FP8 -> fp32 -> fp16, exact
+                const float f = gq == 0 ? __builtin_amdgcn_cvt_f32_fp8((int)mw[r][0], 0)
+                              : gq == 1 ? __builtin_amdgcn_cvt_f32_fp8((int)mw[r][0], 1)
+                              : gq == 2 ? __builtin_amdgcn_cvt_f32_fp8((int)mw[r][0], 2)
+                                        : __builtin_amdgcn_cvt_f32_fp8((int)mw[r][0], 3);
+                xs2[r][gq] = pk_f16(f, f);
+              } else {
+                xs2[r][gq] = (mw[r][gq] & 0xffffu) * 0x10001u;
+              }
+            }
+          float s_ = 0.f, z_ = 0.f;
+          if constexpr (META8) {
+            if (q < G) {
+              s_ = __builtin_amdgcn_cvt_f32_fp8((int)(xmeta >> (8 * q)), 0);
+              z_ = (float)(((G == 4 ? xmeta2 : xmeta >> 16) >> (8 * q)) & 0xffu) - 128.0f;
+            }
+          } else {
+            rkv_unpack_meta(xmeta, s_, z_);
+          }
           xwa = -0.5f * s_ * z_;
         }
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
@@ -800,7 +821,7 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
 // the cross-block variant of the kernel: a reorder inside the rotation groups, plain configuration
 static bool mfma_cross_block(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return !c->blocks_aligned && c->in_groups && v.qg == 128 && v.hb == 0 && !v.meta8 && (v.g == 2 || v.g == 4);
+  return !c->blocks_aligned && c->in_groups && v.qg == 128 && v.hb == 0 && (v.g == 2 || v.g == 4);
 }
 
 bool rkv_mfma_supported(const rkv_cache* c) {
@@ -872,7 +893,9 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch == 0) {}                                          // an empty cache has only the current token
   else if (xb) {
-    if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+    if (v.g == 4 && v.meta8) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, true, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+    else if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+    else if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<2, 1, false, true, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
     else hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
   }
   else if (multi) launch_kernel<true>(v, share, grid, qt, part, nch, q_pos, nq, s);

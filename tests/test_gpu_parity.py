@@ -167,16 +167,16 @@ def test_reorder_across_blocks(span_kind):
     full_check(w, cfg, 100, perm=perm, paths=(1, 2) if span_kind == "group" else (1,))
 
 
-@pytest.mark.parametrize("g,hq,style", [(4, 8, 0), (2, 8, 0), (4, 32, 0), (2, 16, 1), (4, 8, 1)])
-def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style):
+@pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
+def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style, fmt):
     """perm_span = the rotation size: the quantization blocks mix channels of all the group's heads.
     The matrix-core decode kernel's cross-block variant (masked operands, one pass per quantization
     block) against the oracle and against the general kernel: rotation over 4 and 2 heads, GQA,
-    both RoPE pairings, several chunks and a ragged tail, sinks, single-token steps, the current
-    token as an exact row."""
+    both RoPE pairings, both metadata formats, several chunks and a ragged tail, sinks, single-token
+    steps, the current token as an exact row."""
     w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
     cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=g, perm_span=128 * g,
-                      rope_style=style)
+                      rope_style=style, meta_format=fmt)
     perm = calibrated_perm(w, cfg, offset_variant=True)
     assert not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
     cache, oc, q = full_check(w, cfg, 613, perm=perm, chunks=[0, 300, 301, 302, 613], paths=(1, 2))
@@ -217,7 +217,7 @@ def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style):
     for name in ("k_codes", "v_codes"):
         g1[name] = O.unpack_canonical(g1[name])
     P.compare_codes(oc1.k_rot, oc1.k_codes, oc1.k_scale, oc1.k_zero, g1["k_codes"], g1["k_scale"].astype(np.float64),
-                    g1["k_zero"].astype(np.float64), "cross-block ragged K", rot_span=128 * g)
+                    g1["k_zero"].astype(np.float64), "cross-block ragged K", rot_span=128 * g, meta_format=fmt)
 
 
 def test_gqa_llama3_shape():
