@@ -70,13 +70,57 @@ static Offsets plan(const rkv_config* c) {
   o.rope = p; p = align256(p + T * 64 * 8);
   o.hop = p; p = align256(p + 8 * 64 * 4 * 4);
   {
-    const size_t g = c->rot_heads, nrg = c->n_kv_heads / c->rot_heads;
-    o.xmask = p; p = align256(p + nrg * g * g * 4 * 16);
-    o.xtt = p; p = align256(p + nrg * 128 * g * g * 4);
+    // passes of the matrix-core decode variants and quantization blocks per rotation group (see build_xtables)
+    const size_t g = c->rot_heads, nrg = c->n_kv_heads / c->rot_heads, sub = 128 / c->quant_group;
+    const size_t np = sub > 1 ? sub : g, xk = sub > 1 ? g * sub : g;
+    o.xmask = p; p = align256(p + nrg * g * np * 4 * 16);
+    o.xtt = p; p = align256(p + nrg * 128 * xk * g * 4);
     o.xgsel = p; p = align256(p + nrg * 16 * g * 4);
   }
   o.total = p;
   return o;
+}
+
+// Tables of the matrix-core kernels' variants (RkvView::xmask, xtt, xgsel), from the inverse
+// permutation (inv[c] = reordered position of rotated channel c).  Two cases need them:
+//   * a reorder that crosses 128-blocks but stays inside the rotation groups, groups of 128: the
+//     quantization block of a rotated channel is inv[c] / 128, one pass per block of the group;
+//   * quantization groups of 64 / 32 with a reorder inside the heads: block k = head * SUB + sub,
+//     sub = (inv[c] % 128) / quant_group, one pass per sub.
+static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int aligned, int* in_groups_out, hipStream_t s) {
+  const RkvView& v = cache->v;
+  const int E = v.E, g = v.g, n = v.n, nrg = v.NRG, qg = v.qg, sub_n = 128 / qg;
+  int in_groups = (g == 2 || g == 4) ? 1 : 0;
+  for (int c = 0; c < E && in_groups; ++c)
+    if (inv[c] / n != c / n) in_groups = 0;
+  *in_groups_out = in_groups;
+  const bool cross = in_groups && !aligned && qg == 128, subs = aligned && qg < 128 && (g == 2 || g == 4);
+  if (!cross && !subs) return RKV_OK;
+  const int np = subs ? sub_n : g, xk = subs ? g * sub_n : g;
+  std::vector<uint32_t> xmask((size_t)nrg * g * np * 16, 0u), xgsel((size_t)nrg * 16 * g, 0u);
+  std::vector<float> xtt((size_t)nrg * 128 * xk * g, 0.f);
+  for (int rg = 0; rg < nrg; ++rg) {
+    for (int c = 0; c < n; ++c) {                            // rotated channel of the group
+      const int blk = c >> 7, kap = c & 127, q = kap >> 5, vreg = (kap >> 3) & 3, e = kap & 7;
+      const int pos = inv[rg * n + c] - rg * n;              // reordered position within the group
+      const int pass = subs ? (pos & 127) / qg : pos >> 7;
+      const int k = subs ? blk * sub_n + pass : pass;        // quantization block within the group
+      xmask[((((size_t)rg * g + blk) * np + pass) * 4 + q) * 4 + vreg] |= 0xFu << (4 * e);
+      if (cross) {
+        const int w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);   // 2 (wave & 1) + (wave >> 1) = w8
+        xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)k << (2 * (kap & 7));
+      }
+      for (int i = 0; i < n; ++i) {                          // output channel i = 128 a + j of H_n (entries (-1)^popcount(i & c))
+        const float sgn = (__builtin_popcount((unsigned)(i & c)) & 1) ? -1.f : 1.f;
+        xtt[(((size_t)rg * 128 + (i & 127)) * xk + k) * g + (i >> 7)] += sgn;
+      }
+    }
+  }
+  RKV_HIP_CHECK(hipMemcpyAsync(v.xmask, xmask.data(), xmask.size() * 4, hipMemcpyHostToDevice, s));
+  RKV_HIP_CHECK(hipMemcpyAsync(v.xtt, xtt.data(), xtt.size() * 4, hipMemcpyHostToDevice, s));
+  if (cross) RKV_HIP_CHECK(hipMemcpyAsync(v.xgsel, xgsel.data(), xgsel.size() * 4, hipMemcpyHostToDevice, s));
+  RKV_HIP_CHECK(hipStreamSynchronize(s));                    // the vectors go out of scope
+  return RKV_OK;
 }
 
 RKV_EXPORT int rkv_query_sizes(const rkv_config* cfg, size_t* cache_bytes, size_t* scratch_bytes) {
@@ -171,7 +215,13 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.nnew = nullptr;
   v.theta = cfg->rope_theta;
   rc = rkv_launch_init(c, true, (hipStream_t)stream);
+  if (rc == RKV_OK && cfg->quant_group < 128) {            // the identity reorder's tables for groups of 64 / 32
+    std::vector<int32_t> ident(v.E);
+    for (int i = 0; i < v.E; ++i) ident[i] = i;
+    rc = build_xtables(c, ident, 1, &c->in_groups, (hipStream_t)stream);
+  }
   if (rc != RKV_OK) {
+    delete[] c->hlens;
     delete c;
     return rc;
   }
@@ -264,35 +314,10 @@ RKV_EXPORT int rkv_set_perm(rkv_cache* cache, const int32_t* dev_perm, void* str
   RKV_HIP_CHECK(hipMemcpyAsync(cache->v.perm, p.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipMemcpyAsync(cache->v.pinv, inv.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipMemcpyAsync(cache->v.gid, gid.data(), (size_t)E * 4, hipMemcpyHostToDevice, s));
-  // tables of the matrix-core decode path for reorders that cross 128-blocks inside a rotation group
-  const int g = cache->v.g, n = cache->v.n, nrg = cache->v.NRG;
-  int in_groups = (g == 2 || g == 4) ? 1 : 0;
-  for (int c = 0; c < E && in_groups; ++c)
-    if (inv[c] / n != c / n) in_groups = 0;
-  std::vector<uint32_t> xmask, xgsel;
-  std::vector<float> xtt;
-  if (in_groups && !aligned) {
-    xmask.assign((size_t)nrg * g * g * 16, 0u);
-    xtt.assign((size_t)nrg * 128 * g * g, 0.f);
-    xgsel.assign((size_t)nrg * 16 * g, 0u);
-    for (int rg = 0; rg < nrg; ++rg) {
-      for (int c = 0; c < n; ++c) {                          // rotated channel of the group
-        const int blk = c >> 7, kap = c & 127, q = kap >> 5, vreg = (kap >> 3) & 3, e = kap & 7;
-        const int gq = inv[rg * n + c] / 128 - rg * g;       // its quantization block within the group
-        xmask[((((size_t)rg * g + blk) * g + gq) * 4 + q) * 4 + vreg] |= 0xFu << (4 * e);
-        {
-          const int w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);   // 2 (wave & 1) + (wave >> 1) = w8
-          xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)gq << (2 * (kap & 7));
-        }
-        for (int i = 0; i < n; ++i) {                        // output channel i = 128 a + j of H_n (entries (-1)^popcount(i & c))
-          const float sgn = (__builtin_popcount((unsigned)(i & c)) & 1) ? -1.f : 1.f;
-          xtt[(((size_t)rg * 128 + (i & 127)) * g + gq) * g + (i >> 7)] += sgn;
-        }
-      }
-    }
-    RKV_HIP_CHECK(hipMemcpyAsync(cache->v.xmask, xmask.data(), xmask.size() * 4, hipMemcpyHostToDevice, s));
-    RKV_HIP_CHECK(hipMemcpyAsync(cache->v.xtt, xtt.data(), xtt.size() * 4, hipMemcpyHostToDevice, s));
-    RKV_HIP_CHECK(hipMemcpyAsync(cache->v.xgsel, xgsel.data(), xgsel.size() * 4, hipMemcpyHostToDevice, s));
+  int in_groups = 0;
+  {
+    const int rc = build_xtables(cache, inv, aligned, &in_groups, s);
+    if (rc != RKV_OK) return rc;
   }
   RKV_HIP_CHECK(hipStreamSynchronize(s));
   cache->blocks_aligned = aligned;

@@ -176,7 +176,11 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // four slots, signs of H_g as before - accumulate over the passes.  The zero-points no longer
 // collapse onto channel 0; their term, sum over the quantization blocks of s z / 2 times the
 // rotated indicator of the block's channels (xtt), starts the accumulators.
-template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false>
+// SUB = 2 or 4 (with XB): quantization groups of 64 or 32 channels, reorder inside the heads.  A
+// rotated 128-block then holds SUB quantization blocks; pass `sub` takes sub-block `sub` of every
+// head at once (masked operands; the small products with those sub-blocks' scales, one per head,
+// signs of H_g), and the zero-point product contracts over all G * SUB blocks of the group.
+template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false, int SUB = 0>
 __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq) {
@@ -189,22 +193,26 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
   // bytes of each row are kept, [slab][digit set][row][token], followed by one 16-byte piece of
   // zeros that the lanes holding the operand's empty parts read instead.
   constexpr int SA_ZERO = 16 * 32, SA_SET = SA_ZERO + 16;
-  __shared__ __attribute__((aligned(16))) uint8_t s_A[MF_CH / 32][2][SA_SET];
-  __shared__ float s_m[4], s_l[4], s_zs[4], s_wsc[4];
+  constexpr int NS = SUB ? SUB : 1;              // sub-blocks of a value head (groups of 64 / 32): weights per sub-block
+  __shared__ __attribute__((aligned(16))) uint8_t s_A[NS][MF_CH / 32][2][SA_SET];
+  __shared__ float s_m[4], s_l[4], s_zs[NS][4], s_wsc[NS][4];
   __shared__ int s_sink[64];
   __shared__ uint4 s_H[8][64];                   // Hadamard operand tiles
   __shared__ float2 s_step[64];                  // RoPE rotation by 16 positions, per channel pair
   __shared__ int s_lim[MULTI ? NH : 1];          // last position each served query head may attend
   constexpr int QV = REP == 1 ? 4 : 1;            // query versions held (positions pos - r); with REP > 1 only r = 0
   __shared__ uint4 s_q[QV][4][NH / 2][16];        // [r][p][f / 4][n] x 4 floats f % 4, f = (KV head * REP + query head of it) * 2 + (lo, hi)
-  __shared__ uint4 s_xmask[XB ? G * G * 4 : 1];   // [rotated block][quantization block][lane group q]
-  __shared__ float s_xtt[XB ? 128 * G * G : 1];   // [channel][quantization block][head]
+  constexpr int XK = XB ? (SUB ? G * SUB : G) : 1;   // quantization blocks of the rotation group
+  constexpr int NP = SUB ? SUB : G;                  // passes of the key phase
+  __shared__ uint4 s_xmask[XB ? G * NP * 4 : 1];  // [rotated block][pass][lane group q]
+  __shared__ float s_xtt[XB ? 128 * XK * G : 1];  // [channel][quantization block][head]
   static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
+  static_assert(SUB == 0 || (XB && !META8), "groups of 64 / 32 run as a variant of the cross-block kernel, fp16 metadata");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
   {
-    uint4* a4 = reinterpret_cast<uint4*>(&s_A[0][0][0]);
+    uint4* a4 = reinterpret_cast<uint4*>(&s_A[0][0][0][0]);
     for (int i = tid; i < (int)(sizeof(s_A) / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
   }
 
@@ -284,8 +292,8 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
     if (tid < NH) s_lim[tid] = min(q_lim[b * nq + (rrg * REP + tid % REP) / (rep / nq)], len - 1);
   }
   if constexpr (XB) {                              // this rotation group's masks and zero-point table
-    for (int i = tid; i < G * G * 4; i += 256) s_xmask[i] = reinterpret_cast<const uint4*>(v.xmask)[(size_t)rg * (G * G * 4) + i];
-    for (int i = tid; i < 128 * G * G; i += 256) s_xtt[i] = v.xtt[(size_t)rg * (128 * G * G) + i];
+    for (int i = tid; i < G * NP * 4; i += 256) s_xmask[i] = reinterpret_cast<const uint4*>(v.xmask)[(size_t)rg * (G * NP * 4) + i];
+    for (int i = tid; i < 128 * XK * G; i += 256) s_xtt[i] = v.xtt[(size_t)rg * (128 * XK * G) + i];
   }
   // queries of this rotation group, already RoPE'd, scaled and laid out as s_q by k_prep_q
   for (int i = tid; i < QV * 16 * 4 * 2 * NH / 4; i += 256)
@@ -304,14 +312,14 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
       const uint4* ktiles = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tw >> 4));
       // the plane above the low two bits: 16 bytes per lane and pair of blocks (HB = 2) or 8 (HB = 1)
       const uint32_t* khtiles = HI ? v.kh + (rkv_k_tilebase(v, b, rg, tw >> 4) >> (HB == 1 ? 1 : 0)) : nullptr;
-      const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * (META8 ? G / 2 : G);
+      const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * (SUB ? G * SUB : (META8 ? G / 2 : G));
 
       uint4 cw[G / 2], cwh[HI ? G / 2 : 1];
       constexpr int MW = META8 ? G / 2 : G;              // metadata dwords per token and rotation group
       uint32_t mw[4][MW];
       uint32_t xmeta = 0, xmeta2 = 0;                      // cross-block variant: (scale, zero) of token n of the tile, quantization block q
       auto load_tile = [&](int ti) {
-        if constexpr (XB && !META8) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
+        if constexpr (XB && !META8 && SUB == 0) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
         if constexpr (XB && META8) {                       // the token's scale bytes and zero-point bytes
           xmeta = kmeta[(size_t)(ti * 16 + n) * MW];
           if constexpr (G == 4) xmeta2 = kmeta[(size_t)(ti * 16 + n) * MW + 1];
@@ -330,7 +338,9 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
             }
           }
         }
-        if constexpr (META8) {
+        if constexpr (SUB != 0) {
+          // (groups of 64 / 32: the tile's metadata are fetched where they are used, G * SUB entries per token)
+        } else if constexpr (META8) {
           // the lane's four tokens are consecutive: 4 x 2G bytes in one piece
           const uint4* mp = reinterpret_cast<const uint4*>(kmeta + (size_t)(ti * 16 + 4 * q) * MW);
           const uint4 u0 = rkv_ld_stream(mp);
@@ -436,7 +446,38 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
         // (token n, quantization block q), the A operand of the zero-point product
         uint32_t xs2[XB ? 4 : 1][XB ? G : 1];
         float xwa = 0.f;
-        if constexpr (XB) {
+        // groups of 64 / 32: the scale rows of the small products per (pass, token), and the A operands
+        // of the zero-point product, one per four quantization blocks
+        constexpr int XSTEPS = (XK + 3) / 4;
+        v4h sAs[SUB ? SUB : 1][SUB ? 4 : 1];
+        float xwas[SUB ? XSTEPS : 1];
+        if constexpr (SUB != 0) {
+          constexpr int MWS = G * SUB;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            uint32_t e[MWS];                               // entry blk * SUB + sub of token 4q + r
+            const uint4* mp = reinterpret_cast<const uint4*>(kmeta + (size_t)(ti * 16 + 4 * q + r) * MWS);
+#pragma unroll
+            for (int i = 0; i < MWS / 4; ++i) {
+              const uint4 u = mp[i];
+              e[4 * i] = u.x; e[4 * i + 1] = u.y; e[4 * i + 2] = u.z; e[4 * i + 3] = u.w;
+            }
+#pragma unroll
+            for (int sub = 0; sub < SUB; ++sub) {
+              const uint32_t a01 = (__builtin_amdgcn_perm(e[SUB + sub], e[sub], 0x05040100u) ^ sm01) & keep_row;
+              uint32_t a23 = 0;
+              if constexpr (G == 4) a23 = (__builtin_amdgcn_perm(e[3 * SUB + sub], e[2 * SUB + sub], 0x05040100u) ^ sm23) & keep_row;
+              sAs[sub][r] = as_v4h(a01, a23);
+            }
+          }
+#pragma unroll
+          for (int st = 0; st < XSTEPS; ++st) {
+            float s_ = 0.f, z_ = 0.f;
+            if (4 * st + q < XK) rkv_unpack_meta(kmeta[(size_t)(ti * 16 + n) * MWS + 4 * st + q], s_, z_);
+            xwas[st] = -0.5f * s_ * z_;
+          }
+        }
+        if constexpr (XB && SUB == 0) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -517,9 +558,14 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
             for (int a = 0; a < 4; ++a) {
               v4f zl = zero4, zh = zero4;
               if (a < G) {
-                const float bl = q < G ? s_xtt[(j_lo * G + q) * G + a] : 0.f, bh = q < G ? s_xtt[(j_hi * G + q) * G + a] : 0.f;
-                zl = __builtin_amdgcn_mfma_f32_16x16x4f32(xwa, bl, zero4, 0, 0, 0);
-                zh = __builtin_amdgcn_mfma_f32_16x16x4f32(xwa, bh, zero4, 0, 0, 0);
+#pragma unroll
+                for (int st = 0; st < XSTEPS; ++st) {
+                  const int k = 4 * st + q;                   // this lane's quantization block of the step
+                  const float bl = k < XK ? s_xtt[(j_lo * XK + k) * G + a] : 0.f, bh = k < XK ? s_xtt[(j_hi * XK + k) * G + a] : 0.f;
+                  const float wa = SUB ? xwas[SUB ? st : 0] : xwa;
+                  zl = __builtin_amdgcn_mfma_f32_16x16x4f32(wa, bl, zl, 0, 0, 0);
+                  zh = __builtin_amdgcn_mfma_f32_16x16x4f32(wa, bh, zh, 0, 0, 0);
+                }
               }
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
@@ -528,7 +574,7 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
               }
             }
 #pragma unroll
-            for (int gq = 0; gq < G; ++gq) {
+            for (int gq = 0; gq < NP; ++gq) {                 // pass: a quantization block of the group, or a sub-block of every head
               const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
               v8i Hlo, Hhi;
               const uint4 h0 = s_H[p][lane], h1 = s_H[p + 4][lane];
@@ -536,7 +582,7 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
               Hhi[0] = (int)h1.x; Hhi[1] = (int)h1.y; Hhi[2] = (int)h1.z; Hhi[3] = (int)h1.w; Hhi[4] = Hhi[5] = Hhi[6] = Hhi[7] = 0;
 #pragma unroll
               for (int blk = 0; blk < G; ++blk) {
-                const uint4 m = s_xmask[(blk * G + gq) * 4 + q];
+                const uint4 m = s_xmask[(blk * NP + gq) * 4 + q];
                 v8i Am = A[blk];
                 Am[0] &= (int)m.x; Am[1] &= (int)m.y; Am[2] &= (int)m.z; Am[3] &= (int)m.w;
                 lo[blk] = mfma_fp4(Am, Hlo, zero4);
@@ -545,8 +591,13 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
                 // the block's scale in all four slots (contraction over the rotated blocks), signs of H_g
-                const uint32_t s2 = xs2[r][gq];
-                const v4h sx = as_v4h((s2 ^ sm01) & keep_row, G == 4 ? (s2 ^ sm23) & keep_row : 0u);
+                v4h sx;
+                if constexpr (SUB != 0) {
+                  sx = sAs[SUB ? gq : 0][SUB ? r : 0];        // the sub-blocks' own scales, one per head
+                } else {
+                  const uint32_t s2 = xs2[r][gq];
+                  sx = as_v4h((s2 ^ sm01) & keep_row, G == 4 ? (s2 ^ sm23) & keep_row : 0u);
+                }
                 if constexpr (G == 4) {
                   xk_lo[r] = mfma_4x4x4(sx, as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), xk_lo[r]);
                   xk_hi[r] = mfma_4x4x4(sx, as_v4h(pk_f16(hi[0][r], hi[1][r]), pk_f16(hi[2][r], hi[3][r])), xk_hi[r]);
@@ -650,15 +701,18 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
     // V metadata of the four tokens this lane turns into weights in phase S (head = wave); requested
     // here and not before the key phase, where four more live registers would mean spills - and
     // with them a scratch allocation, which keeps some shader engines from holding three workgroups
-    uint32_t vmeta[MF_CH / 64];
+    uint32_t vmeta[NS][MF_CH / 64];
 #pragma unroll
     for (int i = 0; i < MF_CH / 64; ++i) {
-      const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * G;
-      if constexpr (META8) {
+      const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * (G * NS);
+      if constexpr (SUB != 0) {
+#pragma unroll
+        for (int sb = 0; sb < NS; ++sb) vmeta[sb][i] = wave < G ? v.vm[mi + wave * NS + sb] : 0u;
+      } else if constexpr (META8) {
         const uint8_t* vm8 = reinterpret_cast<const uint8_t*>(v.vm) + 2 * mi;
-        vmeta[i] = wave < G ? ((uint32_t)vm8[wave] | ((uint32_t)vm8[G + wave] << 8)) : 0x8000u;
+        vmeta[0][i] = wave < G ? ((uint32_t)vm8[wave] | ((uint32_t)vm8[G + wave] << 8)) : 0x8000u;
       } else {
-        vmeta[i] = wave < G ? v.vm[mi + wave] : 0u;
+        vmeta[0][i] = wave < G ? v.vm[mi + wave] : 0u;
       }
     }
     const bool has_head = q < G;
@@ -701,24 +755,29 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
         m = fmaxf(m, sv[i]);
       }
       m = wave_allreduce<true>(m);
-      float l = 0.f, wmax = 0.f;
+      float pe[MF_CH / 64], l = 0.f;
 #pragma unroll
       for (int i = 0; i < MF_CH / 64; ++i) {
-        float p = 0.f;
-        if (sv[i] > -INFINITY) p = __expf(sv[i] - m);
-        float s_, z_;
-        if constexpr (META8) {
-          s_ = __builtin_amdgcn_cvt_f32_fp8((int)vmeta[i], 0);
-          z_ = (float)((vmeta[i] >> 8) & 0xffu) - 128.0f;
-        } else {
-          rkv_unpack_meta(vmeta[i], s_, z_);
-        }
-        w[i] = p * s_;
-        zv[i] = z_;
-        l += p;
-        wmax = fmaxf(wmax, w[i]);
+        pe[i] = sv[i] > -INFINITY ? __expf(sv[i] - m) : 0.f;
+        l += pe[i];
       }
       l = wave_allreduce<false>(l);
+#pragma unroll
+      for (int sb = 0; sb < NS; ++sb) {                     // once, or once per sub-block of the head (its own scales and zero-points)
+      float wmax = 0.f;
+#pragma unroll
+      for (int i = 0; i < MF_CH / 64; ++i) {
+        float s_, z_;
+        if constexpr (META8) {
+          s_ = __builtin_amdgcn_cvt_f32_fp8((int)vmeta[sb][i], 0);
+          z_ = (float)((vmeta[sb][i] >> 8) & 0xffu) - 128.0f;
+        } else {
+          rkv_unpack_meta(vmeta[sb][i], s_, z_);
+        }
+        w[i] = pe[i] * s_;
+        zv[i] = z_;
+        wmax = fmaxf(wmax, w[i]);
+      }
       wmax = wave_allreduce<true>(wmax);
       // 24-bit fixed point: largest weight lands in [2^23, 2^24); six base-16 digits, exact in E4M3
       int ex = 0;
@@ -730,7 +789,7 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
         const int tl = lane + 64 * i, slab = tl >> 5, tau = tl & 31;
         const uint32_t W = (uint32_t)rintf(w[i] * up);
         zs += (float)W * zv[i];
-        uint8_t* dst = &s_A[slab][0][(4 * a) * 32 + tau];
+        uint8_t* dst = &s_A[sb][slab][0][(4 * a) * 32 + tau];
 #pragma unroll
         for (int k = 0; k < 6; k += 2) {
           // digits 5-k and 4-k (most significant first): rows 0..3 of set 0, rows 0..1 of set 1
@@ -746,8 +805,9 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
       if (lane == 0) {
         s_m[a] = m;
         s_l[a] = l;
-        s_zs[a] = zs * down;
-        s_wsc[a] = down;
+        s_zs[sb][a] = zs * down;
+        s_wsc[sb][a] = down;
+      }
       }
     }
     __syncthreads();
@@ -758,6 +818,7 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
       // which the V codes' layout assigns to head 2 * (second half of the 32) + (q >> 1), tokens
       // 16 * (q & 1) .. + 15 of the slab: its first or second 16 bytes are that head's row, the
       // rest of the operand is zero
+      const int vsub = SUB ? (wave * SUB) / 4 : 0;          // this wave's channels 32 wave .. + 31 lie in one sub-block of their head
       const int arow = n >> 2;
       const bool ause = (q >> 1) == (arow & 1);
       const int adata = n * 32 + 16 * (q & 1);
@@ -772,8 +833,8 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
           v8i A[2];
 #pragma unroll
           for (int set = 0; set < 2; ++set) {
-            const uint4 a0 = *reinterpret_cast<const uint4*>(&s_A[sl][set][aoff0]);
-            const uint4 a1 = *reinterpret_cast<const uint4*>(&s_A[sl][set][aoff1]);
+            const uint4 a0 = *reinterpret_cast<const uint4*>(&s_A[vsub][sl][set][aoff0]);
+            const uint4 a1 = *reinterpret_cast<const uint4*>(&s_A[vsub][sl][set][aoff1]);
             A[set][0] = (int)a0.x; A[set][1] = (int)a0.y; A[set][2] = (int)a0.z; A[set][3] = (int)a0.w;
             A[set][4] = (int)a1.x; A[set][5] = (int)a1.y; A[set][6] = (int)a1.z; A[set][7] = (int)a1.w;
           }
@@ -797,7 +858,7 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
       if (has_head) {
         const int qh = (rg * G + q) * rep + rrg * REP + rri;   // query head served for KV head rg*G + q
         float* dst = part + (((size_t)b * v.Hq + qh) * nch + chunk) * RKV_PART_STRIDE;
-        const float wsc = 2.0f * s_wsc[q];                  // FP4 nibble = code/2
+        const float wsc = 2.0f * s_wsc[vsub][q];            // FP4 nibble = code/2
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
           v4f hi = acc[ct][0], lo = acc[ct][1];
@@ -806,7 +867,7 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
             lo += acch[ct][1] * 4.0f;
           }
           const float sum = ((((hi[0] * 16.0f + hi[1]) * 16.0f + hi[2]) * 16.0f + hi[3]) * 16.0f + lo[0]) * 16.0f + lo[1];
-          dst[4 + 16 * (2 * wave + ct) + n] = sum * wsc - s_zs[q];
+          dst[4 + 16 * (2 * wave + ct) + n] = sum * wsc - s_zs[vsub][q];
         }
         if (wave == 0 && n == 0) {
           dst[0] = s_m[q];
@@ -824,9 +885,15 @@ static bool mfma_cross_block(const rkv_cache* c) {
   return !c->blocks_aligned && c->in_groups && v.qg == 128 && v.hb == 0 && (v.g == 2 || v.g == 4);
 }
 
+// groups of 64 / 32 with the reorder inside the heads: the sub-group variant of the same kernel
+static bool mfma_sub_groups(const rkv_cache* c) {
+  const RkvView& v = c->v;
+  return c->blocks_aligned && v.qg < 128 && v.hb == 0 && !v.meta8 && (v.g == 2 || v.g == 4);
+}
+
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  if (mfma_cross_block(c)) return true;
+  if (mfma_cross_block(c) || mfma_sub_groups(c)) return true;
   // 2-bit codes, or wider ones (a second plane), in groups of 128
   return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4);
 }
@@ -879,8 +946,9 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + MF_CH - 1) / MF_CH;
   const int rep = v.Hq / v.Hkv;
-  const bool xb = mfma_cross_block(c);
-  if (xb && multi) return RKV_EINVAL;                       // the cross-block variant takes one query token per step
+  const bool sg = mfma_sub_groups(c);
+  const bool xb = mfma_cross_block(c) || sg;
+  if (xb && multi) return RKV_EINVAL;                       // the cross-block variants take one query token per step
   const int share = xb ? 1 : rkv_mfma_share(rep);           // and one query head per workgroup
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
@@ -892,6 +960,13 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   }
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch == 0) {}                                          // an empty cache has only the current token
+  else if (sg) {
+    const int sub = 128 / v.qg;
+    if (v.g == 4 && sub == 2) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+    else if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true, 4>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+    else if (sub == 2) hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+    else hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, true, 4>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+  }
   else if (xb) {
     if (v.g == 4 && v.meta8) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, true, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
     else if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);

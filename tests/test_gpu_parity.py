@@ -164,7 +164,7 @@ def test_reorder_across_blocks(span_kind):
     perm = calibrated_perm(w, cfg, offset_variant=True)
     assert not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
     # a reorder inside the rotation group has a matrix-core variant of the decode kernel; across groups only the general one
-    full_check(w, cfg, 100, perm=perm, paths=(1, 2) if span_kind == "group" else (1,))
+    full_check(w, cfg, 100, perm=perm, paths=(1, 2) if span_kind == "group" else (1,), sink_positions=[])
 
 
 @pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
@@ -179,7 +179,9 @@ def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style, fmt):
                       rope_style=style, meta_format=fmt)
     perm = calibrated_perm(w, cfg, offset_variant=True)
     assert not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
-    cache, oc, q = full_check(w, cfg, 613, perm=perm, chunks=[0, 300, 301, 302, 613], paths=(1, 2))
+    # all but the first case without retained fp16 rows, so that the compressed stream alone decides the outputs
+    cache, oc, q = full_check(w, cfg, 613, perm=perm, chunks=[0, 300, 301, 302, 613], paths=(1, 2),
+                              sink_positions=None if (g, hq, style, fmt) == (4, 8, 0, 0) else [])
     cache.set_decode_path(2)
     k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
     out = cache.decode_attention(P.gpu(q), k_cur=P.gpu(k1[:, 0]), v_cur=P.gpu(v1[:, 0]))      # the cache holds the oracle's codes here
@@ -1080,7 +1082,8 @@ def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
 @pytest.mark.parametrize("bits,group,g,hq,fmt,span", [(4, 128, 4, 8, 0, 128), (3, 128, 4, 8, 0, 128), (2, 64, 4, 8, 0, 128),
                                                       (2, 32, 2, 8, 0, 128), (4, 32, 1, 8, 1, 128), (3, 64, 8, 16, 1, 128),
                                                       (4, 64, 4, 8, 0, 512), (3, 32, 2, 8, 0, 1024), (4, 128, 2, 16, 1, 128),
-                                                      (4, 128, 4, 32, 0, 128), (3, 128, 2, 16, 1, 128), (3, 128, 4, 32, 0, 128)])
+                                                      (4, 128, 4, 32, 0, 128), (3, 128, 2, 16, 1, 128), (3, 128, 4, 32, 0, 128),
+                                                      (2, 32, 4, 16, 0, 128), (2, 64, 2, 8, 0, 128)])
 def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     """3- and 4-bit codes and quantization groups of 64 and 32 channels (Sec. 5.1; Tables
     tab:ablation and tab:quantgrani) through the write half, the export and dequantize views and
@@ -1092,14 +1095,18 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     mine, _ = R.query_sizes(cfg)
     base, _ = R.query_sizes(R.RkvConfig(perm_span=span, **kw))
     per_elem = (bits - 2) + (16 if fmt else 32) * (1.0 / group - 1.0 / 128)      # bits per cached element beyond 2-bit, group 128
-    assert mine - base == 2 * 2 * 256 * 1024 * per_elem / 8                       # K and V, batch 2, 256 token slots, 1024 channels
+    # K and V, batch 2, 256 token slots, 1024 channels; smaller groups also enlarge the per-cache tables of the decode kernel
+    assert 0 <= (mine - base) - 2 * 2 * 256 * 1024 * per_elem / 8 <= (0 if group == 128 else 256 * 1024)
     perm = None
     if span != 128:
         perm = calibrated_perm(w, R.RkvConfig(perm_span=span, **kw), offset_variant=True)
         assert not np.array_equal(perm // group, np.arange(cfg.E) // group)
-    # wider codes in groups of 128 are read by the matrix-core decode kernel as two planes
-    on_matrix_cores = bits in (3, 4) and group == 128 and g in (2, 4) and span == 128
-    cache, oc, q = full_check(w, cfg, 213, perm=perm, chunks=[0, 100, 101, 102, 213], paths=(1, 2) if on_matrix_cores else (1, 0))
+    # wider codes in groups of 128 are read by the matrix-core decode kernel as two planes, 2-bit codes in
+    # smaller groups by its sub-group variant
+    on_matrix_cores = g in (2, 4) and span == 128 and ((bits in (3, 4) and group == 128) or (bits == 2 and fmt == 0))
+    # half of the cases without any retained fp16 row, so that the compressed stream alone decides the outputs
+    cache, oc, q = full_check(w, cfg, 213, perm=perm, chunks=[0, 100, 101, 102, 213], paths=(1, 2) if on_matrix_cores else (1, 0),
+                              sink_positions=[] if (hq + group + bits) % 3 != 0 else None)
     assert oc.k_codes.max() == 2 ** bits - 1 and oc.k_scale.shape[-1] == 1024 // group
     if not on_matrix_cores:      # what those kernels do not cover is refused, not mis-computed
         with pytest.raises(R.RkvError):
