@@ -446,12 +446,14 @@ def test_full_size_config4_gqa_sampled():
         check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag="full-size config 4", rep=rep, rope_theta=w.rope_theta)
 
 
-def test_full_size_config1_shape_without_sinks():
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_full_size_config1_shape_without_sinks(bits):
     """Configuration 1's full shape (batch 8, 32 heads, context 4096) with no sink tokens, so that
-    nothing hides the 2-bit stream's contribution; sampled slices against the oracle."""
+    nothing hides the compressed stream's contribution; sampled slices against the oracle.  With
+    2-, 3- and 4-bit codes."""
     w = small("cfg1", n_sinks=0)
     T = w.context
-    cfg = R.RkvConfig(batch=w.batch, n_q_heads=32, n_kv_heads=32, max_tokens=T, max_sinks=0, rot_heads=4, perm_span=128)
+    cfg = R.RkvConfig(batch=w.batch, n_q_heads=32, n_kv_heads=32, max_tokens=T, max_sinks=0, rot_heads=4, perm_span=128, bits=bits)
     cache = R.RkvCache(cfg)
     k, v, _ = S.make_kv(w, T, sink_positions=[])
     q = S.make_q(w)
@@ -464,7 +466,7 @@ def test_full_size_config1_shape_without_sinks():
     lse = lse.cpu().numpy().astype(np.float64)
     for (b, rg) in [(0, 0), (3, 5), (7, 7)]:
         check_slice(exp, out, lse, b, rg, k[b:b + 1, :, 4 * rg:4 * rg + 4], v[b:b + 1, :, 4 * rg:4 * rg + 4], None, q,
-                    max_sinks=0, tag="config 1 shape")
+                    max_sinks=0, tag=f"config 1 shape bits={bits}", bits=bits)
 
 
 def test_large_zero_points():
