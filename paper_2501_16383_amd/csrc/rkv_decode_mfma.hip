@@ -194,7 +194,13 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
   // zeros that the lanes holding the operand's empty parts read instead.
   constexpr int SA_ZERO = 16 * 32, SA_SET = SA_ZERO + 16;
   constexpr int NS = SUB ? SUB : 1;              // sub-blocks of a value head (groups of 64 / 32): weights per sub-block
-  __shared__ __attribute__((aligned(16))) uint8_t s_A[NS][MF_CH / 32][2][SA_SET];
+  // With groups of 32 the zero-point table of the key phase (32 KB) and these digits (33 KB) take
+  // turns in one piece of LDS, so that two workgroups still fit a compute unit: the table is dead
+  // once every wave has left the key phase.
+  constexpr bool ALIAS = SUB == 4;
+  constexpr size_t SA_BYTES = (size_t)NS * (MF_CH / 32) * 2 * SA_SET, XTT_BYTES = XB ? (size_t)128 * (SUB ? G * SUB : G) * G * 4 : 4;
+  __shared__ __attribute__((aligned(16))) uint8_t s_A_raw[ALIAS ? (SA_BYTES > XTT_BYTES ? SA_BYTES : XTT_BYTES) : SA_BYTES];
+  uint8_t (*const s_A)[MF_CH / 32][2][SA_SET] = reinterpret_cast<uint8_t (*)[MF_CH / 32][2][SA_SET]>(s_A_raw);
   __shared__ float s_m[4], s_l[4], s_zs[NS][4], s_wsc[NS][4];
   __shared__ int s_sink[64];
   __shared__ uint4 s_H[8][64];                   // Hadamard operand tiles
@@ -205,15 +211,16 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
   constexpr int XK = XB ? (SUB ? G * SUB : G) : 1;   // quantization blocks of the rotation group
   constexpr int NP = SUB ? SUB : G;                  // passes of the key phase
   __shared__ uint4 s_xmask[XB ? G * NP * 4 : 1];  // [rotated block][pass][lane group q]
-  __shared__ float s_xtt[XB ? 128 * XK * G : 1];  // [channel][quantization block][head]
+  __shared__ float s_xtt_own[(XB && !ALIAS) ? 128 * XK * G : 1];
+  float* const s_xtt = ALIAS ? reinterpret_cast<float*>(s_A_raw) : s_xtt_own;   // [channel][quantization block][head]
   static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
   static_assert(SUB == 0 || (XB && !META8), "groups of 64 / 32 run as a variant of the cross-block kernel, fp16 metadata");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
-  {
-    uint4* a4 = reinterpret_cast<uint4*>(&s_A[0][0][0][0]);
-    for (int i = tid; i < (int)(sizeof(s_A) / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
+  if constexpr (!ALIAS) {
+    uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
+    for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
   }
 
   // Hadamard operand tiles go to LDS once per workgroup; the key phase reads two of them per step
@@ -697,6 +704,11 @@ __global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode
         }
         }
       }
+    }
+    if constexpr (ALIAS) {                                   // the table's space becomes the digits' (see s_A_raw)
+      __syncthreads();
+      uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
+      for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
     }
     // V metadata of the four tokens this lane turns into weights in phase S (head = wave); requested
     // here and not before the key phase, where four more live registers would mean spills - and
