@@ -57,8 +57,9 @@ typedef struct rkv_config {
   int32_t bits;         /* bits per code: 2 (the headline setting), 3 or 4 (Table tab:ablation). */
                         /* 3- and 4-bit codes in groups of 128 run on the matrix-core kernels    */
                         /* like 2-bit ones (the bits above the low two as a second plane);       */
-                        /* groups of 64 / 32 run on the general kernels only, which also means   */
-                        /* no keys_rotated, no rkv_quantize_append_ragged, no                    */
+                        /* groups of 64 / 32 are written by the general append kernel (and read  */
+                        /* by a matrix-core variant with 2-bit codes and fp16 metadata), which   */
+                        /* means no keys_rotated, no rkv_quantize_append_ragged, no              */
                         /* rkv_decode_attention_multi and a two-kernel rkv_decode_step           */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
@@ -229,8 +230,9 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
 /* Choose the decode kernel: 0 = automatic (default), 1 = force the general kernel (any supported
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
  * the configuration is outside what it covers: a reorder across rotation groups, rot_heads 1 or
- * 8, quant_group 64 or 32; a reorder across blocks of 128 inside the rotation groups only with
- * 2-bit codes and one query token per step). */
+ * 8; a reorder across blocks of 128 inside the rotation groups only with 2-bit codes and one
+ * query token per step; quant_group 64 or 32 only with 2-bit codes, fp16 metadata, a reorder
+ * inside the heads and one query token per step). */
 int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 
 /* Measurement hook: ev_start / ev_stop are hipEvent_t handles (as void*) or NULL.  While set,
