@@ -228,6 +228,7 @@ def test_gqa_llama3_shape():
     cfg = R.RkvConfig(batch=2, n_q_heads=16, n_kv_heads=4, max_tokens=300, max_sinks=4, rot_heads=4, perm_span=128,
                       rope_theta=500000.0)
     full_check(w, cfg, 270, paths=(1, 2))
+    full_check(w, cfg, 270, paths=(1, 2), sink_positions=[])       # and with nothing but the compressed stream
 
 
 @pytest.mark.parametrize("g,style,vrot", [(1, 0, 1), (2, 1, 0), (8, 0, 1), (4, 1, 1), (4, 1, 0), (1, 1, 0)])
@@ -402,15 +403,17 @@ def test_full_size_long_context_sampled():
     check_slice(exp, out, lse, 0, rg, k[:, :, 4 * rg:4 * rg + 4], v[:, :, 4 * rg:4 * rg + 4], mask, q, tag="long context")
 
 
-def test_full_size_config4_gqa_sampled():
-    """Configuration 4 at full size (batch 32, 32 query / 8 KV heads, context 8192, RoPE base
+@pytest.mark.parametrize("with_sinks", [True, False])
+def test_full_size_config4_gqa_sampled(with_sinks):
+    """(With the workload's four fp16 sink rows, as bench.py runs it, and without any, so that the
+    compressed stream alone decides the outputs.)  Configuration 4 at full size (batch 32, 32 query / 8 KV heads, context 8192, RoPE base
     500000) in the launch configuration bench.py times: bulk append of 8191 tokens, then one
     rkv_decode_step on the matrix-core path, where a workgroup serves two of the four query heads of
     each KV head.  Two (sequence, rotation group) slices - four KV heads, sixteen query heads each -
     are recomputed by the oracle."""
     w = S.WORKLOADS["cfg4"]
     T = w.context
-    cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=4,
+    cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=4 if with_sinks else 0,
                       rot_heads=4, perm_span=128, rope_theta=w.rope_theta)
     rep = w.n_q_heads // w.n_kv_heads
     perm = calibrated_perm(w, cfg)
@@ -423,7 +426,7 @@ def test_full_size_config4_gqa_sampled():
     v = torch.empty_like(k)
     mask = torch.empty((w.batch, T), dtype=torch.uint8, device="cuda")
     for b in range(w.batch):
-        kb, vb, mb = S.make_kv(dataclasses.replace(w, seed=w.seed + 100 * b), T, batch=1)
+        kb, vb, mb = S.make_kv(dataclasses.replace(w, seed=w.seed + 100 * b), T, batch=1, sink_positions=None if with_sinks else [])
         for (sb, rg) in samples:
             if sb == b:
                 keep[(sb, rg)] = (kb[:, :, 4 * rg:4 * rg + 4].copy(), vb[:, :, 4 * rg:4 * rg + 4].copy(), mb.copy())
@@ -432,7 +435,7 @@ def test_full_size_config4_gqa_sampled():
         mask[b:b + 1].copy_(torch.from_numpy(mb))
     q = S.make_q(w)
     print("[case] full-size config 4: bulk append 8191 + one decode step", flush=True)
-    cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous())
+    cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous() if with_sinks else None)
     cache.set_decode_path(2)
     assert not bool(mask[:, T - 1:].any())
     out, lse = cache.decode_step(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), P.gpu(q), want_lse=True)
@@ -443,7 +446,8 @@ def test_full_size_config4_gqa_sampled():
     assert np.isfinite(out).all()
     for (b, rg) in samples:
         ks, vs, ms = keep[(b, rg)]
-        check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag="full-size config 4", rep=rep, rope_theta=w.rope_theta)
+        check_slice(exp, out, lse, b, rg, ks, vs, ms if with_sinks else None, q, perm=perm, max_sinks=4 if with_sinks else 0,
+                    tag=f"full-size config 4 sinks={with_sinks}", rep=rep, rope_theta=w.rope_theta)
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
@@ -721,7 +725,7 @@ def test_current_token_attended_in_full_precision(T):
     sees it quantized."""
     w = small("cfg1", n_q_heads=16, n_kv_heads=8)
     cfg = R.RkvConfig(batch=2, n_q_heads=16, n_kv_heads=8, max_tokens=128, max_sinks=2, rot_heads=4)
-    k, v, mask, q = P.make_case(w, cfg, T + 1, sink_positions=[0] if T > 0 else [])
+    k, v, mask, q = P.make_case(w, cfg, T + 1, sink_positions=[0] if T == 1 else [])
     cache = R.RkvCache(cfg)
     oc = O.cache_new(P.oracle_cfg(cfg))
     if T > 0:
@@ -788,6 +792,8 @@ def test_several_query_tokens_per_step(hq, hkv, g, nq, bits):
     T = 333
     cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=hkv, max_tokens=400, max_sinks=4, rot_heads=g, bits=bits)
     sinks = [0, T - 2] if nq > 1 else [0]
+    if (hq, nq, bits) in ((8, 3, 2), (16, 2, 2), (8, 4, 4), (16, 2, 3)):
+        sinks = []                                             # nothing but the compressed stream behind every query
     cache, oc, _ = build_pair(w, cfg, T, sink_positions=sinks, chunks=[0, T - nq, T])
     oc_g = oracle_from_export(oc, P.export_numpy(cache))
     q = np.stack([S.make_q(w, batch=2, step=i) for i in range(nq)], axis=1)          # [B, nq, Hq, d]
@@ -827,7 +833,8 @@ def test_fp8_scale_int8_zero_metadata(hq, hkv, g, style):
     Tpad = 768
     assert b16 - b8 == 2 * 2 * Tpad * hkv * 2                     # K and V, 2 bytes less per (token, block)
     paths = (1, 2) if g in (2, 4) else (1, 0)
-    full_check(w, cfg, 613, chunks=[0, 300, 301, 302, 613], paths=paths)
+    # (the cases with half-split RoPE pairs without retained fp16 rows: the compressed stream alone decides the outputs)
+    full_check(w, cfg, 613, chunks=[0, 300, 301, 302, 613], paths=paths, sink_positions=[] if style == 0 else None)
 
 
 def test_fp8_metadata_saturation_and_clamps():
@@ -925,7 +932,8 @@ def test_sequences_of_different_lengths(bits):
     cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=600, max_sinks=4, rot_heads=4, bits=bits)
     steps = [[300, 37, 513], [5, 0, 40], [1, 1, 1], [1, 1, 1], [1, 1, 1]]
     total = [sum(st[b] for st in steps) for b in range(B)]
-    data = [S.make_kv(w, total[b] + 1, batch=1, layer=b) for b in range(B)]       # one spare token for the current-token call
+    # (with 2-bit codes the sequences keep their fp16 sink rows; the wider codes run on the compressed stream alone)
+    data = [S.make_kv(w, total[b] + 1, batch=1, layer=b, sink_positions=None if bits == 2 else []) for b in range(B)]   # one spare token for the current-token call
     cache = R.RkvCache(cfg)
     ocs = [O.cache_new(P.oracle_cfg(dataclasses.replace(cfg, batch=1))) for _ in range(B)]
     done = [0] * B
@@ -1049,7 +1057,8 @@ def test_gqa_ratios_and_metadata_formats(hq, hkv, g, fmt):
     w = small("cfg4", n_q_heads=hq, n_kv_heads=hkv)
     cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=hkv, max_tokens=600, max_sinks=4, rot_heads=g, meta_format=fmt,
                       rope_theta=500000.0)
-    full_check(w, cfg, 531, paths=(1, 2))
+    # three of the four without retained fp16 rows: the compressed stream alone decides the outputs
+    full_check(w, cfg, 531, paths=(1, 2), sink_positions=None if hq == 8 else [])
 
 
 def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
