@@ -25,9 +25,7 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = False) -> str:
-    extra = os.environ.get("RKV_EXTRA_HIPCC_FLAGS", "").split()     # tuning experiments only
-    cmd = [hipcc(), *FLAGS, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -37,6 +35,23 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stderr)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+
+
+def build_library(verbose: bool = False) -> str:
+    """One object per source file, compiled side by side (the decode kernel's many variants take most
+    of the time), then linked into the shared library."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    extra = os.environ.get("RKV_EXTRA_HIPCC_FLAGS", "").split()     # tuning experiments only
+    cflags = [f for f in FLAGS if f != "-shared"]
+    os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)        # objects live here for the duration of the build only
+    with tempfile.TemporaryDirectory(prefix="obj_", dir=os.path.join(HERE, "_build")) as tmp:
+        objs = [os.path.join(tmp, os.path.splitext(src)[0] + ".o") for src in SOURCES]
+        jobs = [[hipcc(), *cflags, *extra, "-c", os.path.join(CSRC, src), "-o", obj] for src, obj in zip(SOURCES, objs)]
+        with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 6)) as ex:
+            list(ex.map(lambda c: _run(c, verbose), jobs))
+        _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", *objs, "-o", LIB + ".tmp"], verbose)
+    os.replace(LIB + ".tmp", LIB)
     return LIB
 
 
