@@ -46,7 +46,7 @@ WORKLOADS = {
     "cfg2": Workload("cfg2", 16, 40, 40, 128, 4096, 40, 4, 4, 10000.0, (4, 8), (10.0, 50.0), seed=1002),
     "cfg3": Workload("cfg3", 1, 32, 32, 128, 32768, 1, 4, 4, 10000.0, (4, 8), (10.0, 50.0), seed=1003),
     "cfg4": Workload("cfg4", 32, 32, 8, 128, 8192, 32, 4, 4, 500000.0, (4, 8), (10.0, 50.0), seed=1004),
-    # not a BASELINE configuration: one sequence of config 1's model, the latency-bound end of decoding
+    # not one of the benchmark configurations: one sequence of config 1's model, the latency-bound end of decoding
     "single": Workload("single", 1, 32, 32, 128, 4096, 32, 4, 4, 10000.0, (4, 8), (10.0, 50.0), seed=1005),
 }
 
