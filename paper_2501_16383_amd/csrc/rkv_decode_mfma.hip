@@ -45,7 +45,7 @@ static_assert(MF_CH == 256, "the per-sequence chunk table (k_lens) counts chunks
 #define MF_ACC 16         // score accumulators per lane and pass of the key phase
 #endif
 #ifndef MF_OCC_HI
-#define MF_OCC_HI 2        // the same for the 4-bit variants, which hold a second plane of codes
+#define MF_OCC_HI 2        // the same for the variants that hold a second plane of codes of four heads (three would spill)
 #endif
 #ifndef MF_OCC
 #define MF_OCC 3           // workgroups per compute unit the register budget is set for
@@ -181,7 +181,7 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // head at once (masked operands; the small products with those sub-blocks' scales, one per head,
 // signs of H_g), and the zero-point product contracts over all G * SUB blocks of the group.
 template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false, int SUB = 0>
-__global__ void __launch_bounds__(256, (HB || XB) ? MF_OCC_HI : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
+__global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF_OCC)) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq) {
   constexpr bool HI = HB != 0;
