@@ -7,7 +7,7 @@
  *          with a scale and an integer zero-point per block (fp16 + fp16, or FP8 + INT8 as in
  *          the quantization settings of Sec. 5.1: rkv_config.meta_format), attention-sink tokens
  *          kept in fp16 (Sec. 4.3);
- *   read   (decoding phase, Eq. 4-5; Sec. 4.4 "inverse online reordering and rotation"):
+ *   read   (decoding phase, Eq. 4-5; the online steps of Sec. 4.4 undone):
  *          dequantize, undo reorder and rotation, RoPE, softmax(q.K^T/sqrt(d)).V.
  *
  * General rules

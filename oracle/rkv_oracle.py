@@ -16,9 +16,8 @@ Conventions shared by all functions
     (the reshape of Alg. 1 step 2);
   * a rotation group is `rot_heads` consecutive KV heads, n = rot_heads * head_dim channels
     (Sec. 4.2, grouped-head rotation);
-  * `perm` P is an index vector over the E rotated channels, z[i] = y[P[i]] (Sec. 4.1,
-    "reordering the channels of each token using the indices sorted by the values after
-    rotation");
+  * `perm` P is an index vector over the E rotated channels, z[i] = y[P[i]]: position i of the
+    reordered row takes rotated channel P[i] (Sec. 4.1);
   * quantization is per token, in blocks of `quant_group` consecutive reordered channels
     (Sec. 5.1, quantization settings), Eq. 6-9 with round-half-to-even and no clipping;
   * scale is stored in fp16 and the stored value is the one used to quantize, so that the write
@@ -123,7 +122,7 @@ def calibrate_perm(k_cal: np.ndarray, cfg: OracleConfig) -> np.ndarray:
     """
     E = cfg.E
     rows = np.asarray(k_cal, dtype=np.float64).reshape(-1, E)
-    rotated = rotate_groups(rows, cfg.n)            # "Key states after rotation"
+    rotated = rotate_groups(rows, cfg.n)            # the algorithm's input: keys already rotated
     channel_sum = rotated.sum(axis=0)               # step 3
     perm = np.empty(E, dtype=np.int32)
     span = cfg.perm_span
@@ -237,7 +236,7 @@ def unpack_canonical(packed: np.ndarray, bits: int = 2) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------------------------
-# RoPE (Sec. 4.2: "applied to pairs of channels"; the cache holds pre-RoPE keys)
+# RoPE (Sec. 4.2: it acts on channel pairs; the cache holds pre-RoPE keys)
 # --------------------------------------------------------------------------------------------
 
 def rope(x: np.ndarray, pos: np.ndarray, theta: float, style: int = 0) -> np.ndarray:
@@ -388,8 +387,8 @@ def dequantize_cache(cache: OracleCache, substitute_sinks: bool = False):
     """Reconstructed keys and values in the original basis, keys pre-RoPE: [B, T, Hkv, d].
 
     Keys: Eq. 7, inverse reorder, then the same grouped rotation again (H is symmetric and
-    orthogonal, so it is its own inverse) - the "inverse online reordering and rotation" of
-    Sec. 4.4.  Values: Eq. 7, and the per-head rotation undone when v_rotate is set.
+    orthogonal, so it is its own inverse) - the two online steps that Sec. 4.4 undoes before
+    attention.  Values: Eq. 7, and the per-head rotation undone when v_rotate is set.
     """
     cfg = cache.cfg
     B, T, E = cache.k_codes.shape

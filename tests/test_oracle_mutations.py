@@ -13,7 +13,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 ORACLE = os.path.join(ROOT, "oracle", "rkv_oracle.py")
 
-# (what is planted, text in the oracle, replacement) - the text must occur exactly once
+# (what is planted, text in the oracle, replacement) - the text must occur exactly once; a tuple
+# of texts and a tuple of replacements plant one mistake in several places
 MUTANTS = [
     ("Hadamard recursion without the minus sign", "np.block([[H, H], [H, -H]])", "np.block([[H, H], [H, H]])"),
     ("rotation without its normalisation", "x[..., r * n:(r + 1) * n] @ H.T", "x[..., r * n:(r + 1) * n] @ H.T * np.sqrt(n)"),
@@ -51,6 +52,14 @@ MUTANTS = [
     ("several query tokens: a sink behind the query is still seen", "keep = [s for s, pos in enumerate(cache.sink_pos[b]) if pos < T]",
      "keep = [s for s, pos in enumerate(cache.sink_pos[b])]"),
     ("current token put in front of the cache instead of behind it", "k_hat = np.concatenate([k_hat, kc], axis=1)", "k_hat = np.concatenate([kc, k_hat], axis=1)"),
+    ("log-sum-exp without the maximum that was taken out of the exponentials", "lse[b, h] = m + np.log(l)", "lse[b, h] = np.log(l)"),
+    ("fp16 zero-point not clamped to the integers fp16 holds", "        zlo, zhi = -ZERO_LIMIT, ZERO_LIMIT\n", "        zlo, zhi = -1e9, 1e9\n"),
+    ("fp16 scale not clamped to the largest fp16 number", "scale = np.minimum(_to_f16((mx - mn) / qmax), F16_MAX)", "scale = _to_f16((mx - mn) / qmax)"),
+    ("value rotation over the keys' rotation group instead of each head (write side)", "u = rotate_groups(u, cfg.head_dim)", "u = rotate_groups(u, cfg.n)"),
+    ("value rotation over the keys' rotation group instead of each head (read side)", "v_hat = rotate_groups(v_hat, cfg.head_dim)", "v_hat = rotate_groups(v_hat, cfg.n)"),
+    ("value rotation over the keys' rotation group instead of each head (both sides)",
+     ("u = rotate_groups(u, cfg.head_dim)", "v_hat = rotate_groups(v_hat, cfg.head_dim)"),
+     ("u = rotate_groups(u, cfg.n)", "v_hat = rotate_groups(v_hat, cfg.n)")),
 ]
 
 
@@ -60,16 +69,20 @@ def _find(src, needle):
 
 def _run_mutant(i):
     what, old, new = MUTANTS[i]
+    olds, news = (old, new) if isinstance(old, tuple) else ((old,), (new,))
     code = (
         "import sys, types\n"
         f"sys.path.insert(0, {ROOT!r}); sys.path.insert(0, {os.path.join(ROOT, 'tests')!r})\n"
         f"src = open({ORACLE!r}).read()\n"
-        f"old, new = {old!r}, {new!r}\n"
-        "assert src.count(old) == 1, 'mutation site not found exactly once'\n"
+        f"olds, news = {olds!r}, {news!r}\n"
+        "for old in olds:\n"
+        "    assert src.count(old) == 1, 'mutation site not found exactly once'\n"
+        "for old, new in zip(olds, news):\n"
+        "    src = src.replace(old, new)\n"
         "import oracle\n"
         "mod = types.ModuleType('oracle.rkv_oracle'); mod.__file__ = 'mutant'\n"
         "sys.modules['oracle.rkv_oracle'] = mod\n"
-        f"exec(compile(src.replace(old, new), {ORACLE!r}, 'exec'), mod.__dict__)\n"
+        f"exec(compile(src, {ORACLE!r}, 'exec'), mod.__dict__)\n"
         "oracle.rkv_oracle = mod\n"
         "import pytest\n"
         f"sys.exit(pytest.main(['-x', '-q', '-p', 'no:cacheprovider', {os.path.join(ROOT, 'tests', 'test_oracle_pins.py')!r}]))\n"

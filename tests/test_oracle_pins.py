@@ -190,6 +190,40 @@ def test_quantizer_degenerate_blocks():
         assert np.isfinite(s).all() and s[0, 0] > 0
 
 
+def test_fp16_metadata_clamps_written_out_by_hand():
+    """The stored zero-point is an integer in an fp16 field: beyond +-2048 fp16 no longer holds
+    every integer, so Eq. 9's value is clamped there; the stored scale cannot exceed the largest
+    fp16 number 65504.  Expected metadata and codes below are Eq. 6, 8, 9 worked by hand."""
+    # range 0.3 at offset 1000: Eq. 8 gives 0.1 -> fp16 0.0999755859375; Eq. 9 gives
+    # -rint(1000 / 0.09998) = -10002, stored as -2048; Eq. 6: rint(x / s) - 2048 > 3 for every x -> 3
+    x = np.array([[1000.0, 1000.1, 1000.2, 1000.3]])
+    c, s, z = O.quantize(x, group=4)
+    assert s[0, 0] == float(np.float16(0.1)) == 0.0999755859375
+    assert z[0, 0] == -2048.0
+    assert c[0].tolist() == [3, 3, 3, 3]
+    # the mirror image: Eq. 9 gives +10005 (-1000.3 / s = -10005.4), stored as +2048; codes clamp to 0
+    c, s, z = O.quantize(-x, group=4)
+    assert s[0, 0] == 0.0999755859375 and z[0, 0] == 2048.0
+    assert c[0].tolist() == [0, 0, 0, 0]
+    # just inside the limit nothing is clamped: min -204.6, range 0.3 -> zero = rint(204.6 / s) = 2046
+    y = np.array([[-204.6, -204.5, -204.4, -204.3]])
+    c, s, z = O.quantize(y, group=4)
+    assert z[0, 0] == 2046.0 == np.rint(204.6 / 0.0999755859375)
+    assert c[0].tolist() == [0, 1, 2, 3]
+    # range 300000: Eq. 8 gives 100000, beyond fp16 -> stored 65504; Eq. 9: -rint(-150000 / 65504) = 2;
+    # Eq. 6: rint(x / 65504) + 2 = 0, 2, 3, 4 -> 0, 2, 3, 3
+    w = np.array([[-150000.0, 0.0, 60000.0, 150000.0]])
+    c, s, z = O.quantize(w, group=4)
+    assert s[0, 0] == 65504.0 and z[0, 0] == 2.0
+    assert c[0].tolist() == [0, 2, 3, 3]
+    assert np.all(np.isfinite(O.dequantize(c, s, z, group=4)))
+    # the largest range that needs no clamp: 3 * 65504
+    # (x / s = -1.5, -0.61, 0.61, 1.5; halves go to the even neighbour: -2, -1, 1, 2; plus zero = 2)
+    w = np.array([[-98256.0, -40000.0, 40000.0, 98256.0]])
+    c, s, z = O.quantize(w, group=4)
+    assert s[0, 0] == 65504.0 and z[0, 0] == 2.0 and c[0].tolist() == [0, 1, 3, 3]
+
+
 def test_pack_roundtrip_all_bytes():
     allb = np.arange(256, dtype=np.uint8)
     codes = O.unpack_canonical(allb[None])
@@ -528,6 +562,50 @@ def test_all_sink_cache_is_textbook_attention(hq, hkv):
     out, lse = O.decode_attention(cache, q, q_pos)
     ref = _textbook_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), q_pos, 10000.0, hq // hkv)
     assert np.allclose(out, ref, atol=1e-10)
+    assert np.allclose(lse, _library_lse(q, k.astype(np.float64), q_pos, 10000.0, hq // hkv), rtol=0, atol=1e-10)
+
+
+def _library_lse(q, k_hat, q_pos, theta, rep):
+    """Eq. 5's normaliser by a library log-sum-exp: log sum_t exp(q~ . k~_t / sqrt(d)) for keys
+    k_hat [B, T, Hkv, d] (pre-RoPE), RoPE written as a complex rotation."""
+    from scipy.special import logsumexp
+    B, T, Hkv, d = k_hat.shape
+    w = theta ** (-np.arange(d // 2) / (d / 2))
+    kz = (k_hat[..., :d // 2] + 1j * k_hat[..., d // 2:]) * np.exp(1j * np.arange(T)[None, :, None, None] * w)
+    qf = np.asarray(q, dtype=np.float64)
+    qz = (qf[..., :d // 2] + 1j * qf[..., d // 2:]) * np.exp(1j * np.asarray(q_pos)[:, None, None] * w)
+    out = np.empty(qf.shape[:2])
+    for b in range(B):
+        for h in range(qf.shape[1]):
+            scores = (kz[b, :, h // rep] * np.conj(qz[b, h])).real.sum(-1) / np.sqrt(d)
+            out[b, h] = logsumexp(scores)
+    return out
+
+
+def test_lse_of_a_quantized_cache_is_the_log_sum_exp_of_its_scores():
+    """The second result of the read half is Eq. 5's normaliser, max included: against a library
+    log-sum-exp over the scores of the reconstructed keys (retained rows substituted).  The keys
+    are scaled so that the largest score is far from 0 - a normaliser without its max term, or
+    with the sum taken before the shift, is then off by tens."""
+    cfg = _cfg(n_q_heads=8, n_kv_heads=4, rot_heads=2, max_sinks=2)
+    rng = np.random.default_rng(31)
+    T = 48
+    k = (rng.standard_normal((2, T, 4, 128)) * 6.0).astype(np.float16)
+    v = rng.standard_normal((2, T, 4, 128)).astype(np.float16)
+    q = rng.standard_normal((2, 8, 128)).astype(np.float16)
+    mask = np.zeros((2, T), np.uint8)
+    mask[:, 3] = 1
+    cache = O.cache_new(cfg)
+    O.quantize_append(cache, k, v, mask)
+    q_pos = np.array([T - 1, T + 2])
+    out, lse = O.decode_attention(cache, q, q_pos)
+    k_hat, v_hat = O.dequantize_cache(cache, substitute_sinks=True)
+    ref = _library_lse(q, k_hat, q_pos, 10000.0, 2)
+    assert np.abs(ref).min() > 3.0                      # the max term matters in every head
+    assert np.allclose(lse, ref, rtol=0, atol=1e-9)
+    # and the first result is the softmax-weighted mean that goes with that normaliser
+    ref_out = _textbook_attention(q.astype(np.float64), k_hat, v_hat, q_pos, 10000.0, 2)
+    assert np.allclose(out, ref_out, rtol=0, atol=1e-10)
 
 
 def test_no_quantization_error_on_grid_data():
@@ -599,6 +677,36 @@ def test_v_rotate_roundtrip():
     err = np.sqrt(((v_hat - v.astype(np.float64)) ** 2).sum(-1))
     assert np.all(err <= np.sqrt(((0.5 * step * (1 + 2.0 ** -8)) ** 2).sum(-1)) + 1e-9)
     assert not np.array_equal(c1.v_codes, O.quantize(v.astype(np.float64).reshape(2, 8, 512))[0])
+
+
+def test_v_rotate_is_a_rotation_of_each_head_on_its_own():
+    """The value rotation of Sec. 4.4 is a Hadamard of the head dimension, head by head (the
+    grouped rotation is the keys').  A value row that is non-zero in one head only must leave
+    every other head's block constant (all codes 0), and a head that holds one constant c becomes
+    c sqrt(128) e_0 - codes (3, 0, 0, ...), scale fp16(c sqrt(128) / 3), zero 0 - and reads back
+    as the constant."""
+    cfg = _cfg(batch=1, v_rotate=1, rot_heads=4)
+    k = np.zeros((1, 2, 4, 128), np.float16)
+    v = np.zeros((1, 2, 4, 128), np.float16)
+    v[0, 0, 1, :] = 0.75                       # token 0: head 1 constant
+    rng = np.random.default_rng(33)
+    v[0, 1, 2, :] = rng.standard_normal(128).astype(np.float16)   # token 1: head 2 only
+    cache = O.cache_new(cfg)
+    O.quantize_append(cache, k, v)
+    codes = cache.v_codes.reshape(1, 2, 4, 128)
+    for t, live in ((0, 1), (1, 2)):
+        for h in range(4):
+            if h != live:
+                assert not codes[0, t, h].any(), (t, h)
+    assert codes[0, 0, 1].tolist() == [3] + [0] * 127
+    assert cache.v_scale[0, 0, 1] == float(np.float16(0.75 * np.sqrt(128.0) / 3.0)) and cache.v_zero[0, 0, 1] == 0.0
+    _, v_hat = O.dequantize_cache(cache)
+    assert np.allclose(v_hat[0, 0, 1], 3.0 * cache.v_scale[0, 0, 1] / np.sqrt(128.0), atol=1e-12)
+    assert np.abs(v_hat[0, 0, 1] - 0.75).max() < 1e-3
+    assert not v_hat[0, 0, [0, 2, 3]].any() and not v_hat[0, 1, [0, 1, 3]].any()
+    # token 1, head 2: codes are those of H_128 applied to that head alone
+    u = O.rotate_groups(v[0, 1, 2].astype(np.float64)[None], 128)
+    assert np.array_equal(codes[0, 1, 2], O.quantize(u, 128)[0][0])
 
 
 def test_reorder_lowers_error_on_offset_outliers():
