@@ -63,7 +63,12 @@ typedef struct rkv_config {
                         /* rkv_decode_attention_multi and a two-kernel rkv_decode_step           */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
-                        /* printed sorts the whole row)                                           */
+                        /* printed sorts the whole row).  The append kernel for a reorder across */
+                        /* rotation groups holds U = max(perm_span, rot_heads*head_dim) channels */
+                        /* of 16 tokens in LDS: 24 U bytes (30 U with 3-bit, 32 U with 4-bit     */
+                        /* codes) must not exceed 160 KB, else RKV_EINVAL from rkv_query_sizes   */
+                        /* and rkv_cache_create (whole-row reorder: at most 53 KV heads, 40 with */
+                        /* 4-bit codes)                                                           */
   int32_t rope_style;   /* 0: channel j pairs with j+64; 1: channel 2j pairs with 2j+1          */
   int32_t v_rotate;     /* 0: values are quantized as given (the caller has folded the value    */
                         /* rotation of Sec. 4.4 into its weights); 1: the library applies a      */
@@ -234,6 +239,21 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
  * query token per step; quant_group 64 or 32 only with 2-bit codes, fp16 metadata, a reorder
  * inside the heads and one query token per step). */
 int rkv_set_decode_path(rkv_cache* cache, int32_t path);
+
+/* Which kernel the cache's configuration and installed reorder take (no device work): the decode
+ * kernel of rkv_decode_attention / rkv_decode_step (n_queries = 0) or of
+ * rkv_decode_attention_multi (n_queries >= 1), the append kernel of rkv_quantize_append.  A
+ * caller - or a test - that counts on the matrix-core kernels can assert it instead of finding
+ * out from the timing.  Returns one of the RKV_KERNEL_* values, or RKV_EINVAL where the call
+ * itself would (rkv_set_decode_path(2) outside the matrix-core kernels' coverage, several query
+ * tokens outside the plain matrix-core kernel's). */
+#define RKV_KERNEL_GENERAL    1  /* vector-ALU kernels: any supported configuration                  */
+#define RKV_KERNEL_SHUFFLE    2  /* append only: FWHT in registers (v_rotate = 1, reorder in blocks)  */
+#define RKV_KERNEL_MFMA       3  /* matrix-core kernels: reorder inside blocks of 128, rot_heads 2, 4 */
+#define RKV_KERNEL_MFMA_CROSS 4  /* their variant for a reorder across blocks inside rotation groups  */
+#define RKV_KERNEL_MFMA_SUB   5  /* decode only: their variant for quant_group 64 / 32                */
+int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries);
+int rkv_append_kernel_of(const rkv_cache* cache);
 
 /* Measurement hook: ev_start / ev_stop are hipEvent_t handles (as void*) or NULL.  While set,
  * every rkv_decode_attention on this cache records ev_start immediately before and ev_stop

@@ -16,12 +16,13 @@ _LIB_PATH = os.path.join(_HERE, "librkv.so")
 _lib = None
 
 RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, -3, -4, -5
+KERNEL_GENERAL, KERNEL_SHUFFLE, KERNEL_MFMA, KERNEL_MFMA_CROSS, KERNEL_MFMA_SUB = 1, 2, 3, 4, 5
 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
     "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention", "rkv_decode_attention_with_current",
     "rkv_decode_attention_multi", "rkv_decode_step", "rkv_quantize_append_ragged", "rkv_cache_lengths", "rkv_cache_truncate",
-    "rkv_set_decode_path", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
+    "rkv_set_decode_path", "rkv_decode_kernel_of", "rkv_append_kernel_of", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
 ]
 
@@ -102,6 +103,8 @@ def load_library():
     lib.rkv_cache_lengths.argtypes = [vp, vp]
     lib.rkv_cache_truncate.argtypes = [vp, vp, vp]
     lib.rkv_set_decode_path.argtypes = [vp, i32]
+    lib.rkv_decode_kernel_of.argtypes = [vp, i32]
+    lib.rkv_append_kernel_of.argtypes = [vp]
     lib.rkv_set_profile_events.argtypes = [vp, vp, vp]
     lib.rkv_dequantize.argtypes = [vp, vp, vp, vp]
     lib.rkv_export_codes.argtypes = [vp] * 8
@@ -242,6 +245,20 @@ class RkvCache:
 
     def set_decode_path(self, path: int):
         _check(self.lib.rkv_set_decode_path(self.handle, path), "rkv_set_decode_path")
+
+    def decode_kernel(self, n_queries: int = 0) -> int:
+        """rkv_decode_kernel_of: the KERNEL_* value of the decode kernel this cache takes."""
+        rc = self.lib.rkv_decode_kernel_of(self.handle, n_queries)
+        if rc < 0:
+            raise RkvError(rc, "rkv_decode_kernel_of")
+        return rc
+
+    def append_kernel(self) -> int:
+        """rkv_append_kernel_of: the KERNEL_* value of the append kernel this cache takes."""
+        rc = self.lib.rkv_append_kernel_of(self.handle)
+        if rc < 0:
+            raise RkvError(rc, "rkv_append_kernel_of")
+        return rc
 
     def set_profile_events(self, ev_start, ev_stop):
         """hipEvent_t handles (ints) recorded around the main kernel of the next calls, or None, None."""

@@ -37,23 +37,53 @@ def _run(cmd, verbose):
         print(err, file=sys.stderr)
 
 
-def build_library(verbose: bool = False) -> str:
+def _stamp(src: str, cflags) -> str:
+    """What an object depends on: its source, every header of the library, the flags."""
+    import hashlib
+    h = hashlib.sha256(" ".join(cflags).encode())
+    deps = [os.path.join(CSRC, src)] + sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h"))
+    deps.append(os.path.join(HERE, "..", "include", "rkv.h"))
+    for d in deps:
+        with open(d, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def build_library(verbose: bool = False, incremental: bool = False) -> str:
     """One object per source file, compiled side by side (the decode kernel's many variants take most
-    of the time), then linked into the shared library."""
+    of the time), then linked into the shared library.  incremental: keep the objects under _build/
+    and recompile only the sources whose text, headers or flags changed (a developer's shortcut; the
+    default compiles everything)."""
     import tempfile
     from concurrent.futures import ThreadPoolExecutor
     extra = os.environ.get("RKV_EXTRA_HIPCC_FLAGS", "").split()     # tuning experiments only
-    cflags = [f for f in FLAGS if f != "-shared"]
-    os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)        # objects live here for the duration of the build only
-    with tempfile.TemporaryDirectory(prefix="obj_", dir=os.path.join(HERE, "_build")) as tmp:
-        objs = [os.path.join(tmp, os.path.splitext(src)[0] + ".o") for src in SOURCES]
-        jobs = [[hipcc(), *cflags, *extra, "-c", os.path.join(CSRC, src), "-o", obj] for src, obj in zip(SOURCES, objs)]
-        with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 6)) as ex:
-            list(ex.map(lambda c: _run(c, verbose), jobs))
+    cflags = [f for f in FLAGS if f != "-shared"] + extra
+    bdir = os.path.join(HERE, "_build")
+    os.makedirs(bdir, exist_ok=True)
+    with tempfile.TemporaryDirectory(prefix="obj_", dir=bdir) as tmp:
+        odir = os.path.join(bdir, "inc") if incremental else tmp
+        os.makedirs(odir, exist_ok=True)
+        objs = [os.path.join(odir, os.path.splitext(src)[0] + ".o") for src in SOURCES]
+        jobs = []
+        for src, obj in zip(SOURCES, objs):
+            stamp = _stamp(src, cflags) if incremental else ""
+            if incremental and os.path.exists(obj) and os.path.exists(obj + ".stamp") and open(obj + ".stamp").read() == stamp:
+                continue
+            jobs.append(([hipcc(), *cflags, "-c", os.path.join(CSRC, src), "-o", obj], obj, stamp))
+
+        def one(job):
+            cmd, obj, stamp = job
+            _run(cmd, verbose)
+            if incremental:
+                with open(obj + ".stamp", "w") as f:
+                    f.write(stamp)
+        if jobs:
+            with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 6)) as ex:
+                list(ex.map(one, jobs))
         _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", *objs, "-o", LIB + ".tmp"], verbose)
     os.replace(LIB + ".tmp", LIB)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=True, incremental="--incremental" in sys.argv[1:]))

@@ -10,6 +10,7 @@
 #define RKV_EXPORT extern "C" __attribute__((visibility("default")))
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static void free_host_side(rkv_cache* c);
 
 static int check_config(const rkv_config* c, bool need_capacity) {
   if (!c) return RKV_EINVAL;
@@ -31,6 +32,13 @@ static int check_config(const rkv_config* c, bool need_capacity) {
   if (c->meta_format != 0 && c->meta_format != 1) return RKV_EINVAL;
   if (c->keys_rotated && ((c->rot_heads != 2 && c->rot_heads != 4) || c->perm_span != RKV_D || c->v_rotate)) return RKV_EINVAL;
   if (!(c->rope_theta > 1.0f)) return RKV_EINVAL;
+  {
+    // the general append kernel, the only one for a reorder across rotation groups, keeps the images
+    // of max(perm_span, n) channels of a tile in LDS (rkv_launch_append): that must fit a compute unit
+    const size_t U = c->perm_span > n ? c->perm_span : n;
+    const size_t lds = 24 * U + (c->bits == 4 ? 8 * U : c->bits == 3 ? 6 * U : 0);
+    if (lds > RKV_LDS_BYTES) return RKV_EINVAL;
+  }
   if (need_capacity) {
     if (c->batch < 1 || c->max_tokens < 1 || c->max_sinks < 0 || c->max_sinks > 64) return RKV_EINVAL;
     if ((int64_t)c->max_tokens > 65536 || (int64_t)c->batch > 65535) return RKV_EINVAL;
@@ -154,10 +162,27 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   c->cur_k = c->cur_v = nullptr;
   c->ragged = 0;
   c->hlens = new (std::nothrow) int32_t[cfg->batch]();
+  c->stage = nullptr;
+  c->stage_next = 0;
+  for (int i = 0; i < RKV_STAGE_SLOTS; ++i) {
+    c->stage_ev[i] = nullptr;
+    c->stage_used[i] = 0;
+  }
   if (!c->hlens) {
-    delete c;
+    free_host_side(c);
     return RKV_EINVAL;
   }
+  if (hipHostMalloc((void**)&c->stage, (size_t)RKV_STAGE_SLOTS * cfg->batch * 4, hipHostMallocDefault) != hipSuccess) {
+    c->stage = nullptr;
+    free_host_side(c);
+    return RKV_EHIP;
+  }
+  for (int i = 0; i < RKV_STAGE_SLOTS; ++i)
+    if (hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming) != hipSuccess) {
+      c->stage_ev[i] = nullptr;
+      free_host_side(c);
+      return RKV_EHIP;
+    }
   c->dev_lens = (int*)(c->base + o.lens);
   c->dev_nnew = (int*)(c->base + o.nnew);
   c->dev_cstart = (int*)(c->base + o.cstart);
@@ -165,7 +190,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
         cus < 1) {
-      delete c;
+      free_host_side(c);
       return RKV_EHIP;
     }
     c->n_cu = cus;
@@ -221,18 +246,39 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
     rc = build_xtables(c, ident, 1, &c->in_groups, (hipStream_t)stream);
   }
   if (rc != RKV_OK) {
-    delete[] c->hlens;
-    delete c;
+    free_host_side(c);
     return rc;
   }
   *out = c;
   return RKV_OK;
 }
 
-RKV_EXPORT void rkv_cache_destroy(rkv_cache* cache) {
-  if (cache) delete[] cache->hlens;
-  delete cache;
+// Per-sequence counts that a call takes from host memory go to the device through a slot of the
+// cache's own pinned ring, so that the caller's array is done with when the call returns whatever
+// the runtime does with pageable memory.  A slot is reused only after the copy that last read it
+// has completed (its event).
+static int stage_counts(rkv_cache* c, const int32_t* host_vals, hipStream_t s) {
+  const int slot = c->stage_next;
+  c->stage_next = (slot + 1) % RKV_STAGE_SLOTS;
+  if (c->stage_used[slot]) RKV_HIP_CHECK(hipEventSynchronize(c->stage_ev[slot]));
+  int32_t* dst = c->stage + (size_t)slot * c->v.B;
+  memcpy(dst, host_vals, (size_t)c->v.B * 4);
+  RKV_HIP_CHECK(hipMemcpyAsync(c->dev_nnew, dst, (size_t)c->v.B * 4, hipMemcpyHostToDevice, s));
+  RKV_HIP_CHECK(hipEventRecord(c->stage_ev[slot], s));
+  c->stage_used[slot] = 1;
+  return RKV_OK;
 }
+
+static void free_host_side(rkv_cache* c) {
+  if (!c) return;
+  delete[] c->hlens;
+  if (c->stage) (void)hipHostFree(c->stage);
+  for (int i = 0; i < RKV_STAGE_SLOTS; ++i)
+    if (c->stage_ev[i]) (void)hipEventDestroy(c->stage_ev[i]);
+  delete c;
+}
+
+RKV_EXPORT void rkv_cache_destroy(rkv_cache* cache) { free_host_side(cache); }
 
 RKV_EXPORT int rkv_cache_reset(rkv_cache* cache, void* stream) {
   if (!cache) return RKV_EINVAL;
@@ -264,7 +310,10 @@ RKV_EXPORT int rkv_cache_truncate(rkv_cache* cache, const int32_t* host_new_leng
   }
   if (lo != hi && !cache->ragged && !rkv_append_mfma_supported(cache)) return RKV_EINVAL;   // would need per-sequence lengths
   hipStream_t s = (hipStream_t)stream;
-  RKV_HIP_CHECK(hipMemcpyAsync(cache->dev_nnew, host_new_lengths, (size_t)B * 4, hipMemcpyHostToDevice, s));
+  {
+    const int rc = stage_counts(cache, host_new_lengths, s);
+    if (rc != RKV_OK) return rc;
+  }
   cache->v.nnew = cache->dev_nnew;
   const int rc = rkv_launch_lens(cache, -2, 0, s);
   cache->v.nnew = nullptr;
@@ -283,6 +332,23 @@ RKV_EXPORT int rkv_set_decode_path(rkv_cache* cache, int32_t path) {
   if (!cache || path < 0 || path > 2) return RKV_EINVAL;
   cache->decode_path = path;
   return RKV_OK;
+}
+
+RKV_EXPORT int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries) {
+  if (!cache || n_queries < 0 || n_queries > RKV_MAX_QUERIES) return RKV_EINVAL;
+  const int kind = rkv_mfma_supported(cache) ? rkv_mfma_variant(cache) : RKV_KERNEL_GENERAL;
+  if (n_queries > 0) return kind == RKV_KERNEL_MFMA && cache->decode_path != 1 ? kind : RKV_EINVAL;   // multi-query: plain matrix-core kernel only
+  if (cache->decode_path == 1) return RKV_KERNEL_GENERAL;
+  if (cache->decode_path == 2 && kind == RKV_KERNEL_GENERAL) return RKV_EINVAL;
+  return kind;
+}
+
+RKV_EXPORT int rkv_append_kernel_of(const rkv_cache* cache) {
+  if (!cache) return RKV_EINVAL;
+  const RkvView& v = cache->v;
+  if (rkv_append_mfma_supported(cache)) return cache->blocks_aligned ? RKV_KERNEL_MFMA : RKV_KERNEL_MFMA_CROSS;
+  if (cache->blocks_aligned && !cache->wide && (v.g == 2 || v.g == 4)) return RKV_KERNEL_SHUFFLE;
+  return RKV_KERNEL_GENERAL;
 }
 
 RKV_EXPORT int rkv_set_profile_events(rkv_cache* cache, void* ev_start, void* ev_stop) {
@@ -397,7 +463,8 @@ RKV_EXPORT int rkv_quantize_append_ragged(rkv_cache* cache, const void* dev_k, c
     cache->v.lens = cache->dev_lens;
     cache->v.cstart = cache->dev_cstart;
   }
-  RKV_HIP_CHECK(hipMemcpyAsync(cache->dev_nnew, host_n_new, (size_t)B * 4, hipMemcpyHostToDevice, s));
+  rc = stage_counts(cache, host_n_new, s);
+  if (rc != RKV_OK) return rc;
   cache->v.nnew = cache->dev_nnew;
   if (dev_sink_mask && cache->v.max_sinks > 0)
     rc = rkv_launch_sinks(cache, (const __half*)dev_k, (const __half*)dev_v, dev_sink_mask, n_new_max, s);

@@ -903,6 +903,10 @@ static bool mfma_sub_groups(const rkv_cache* c) {
   return c->blocks_aligned && v.qg < 128 && v.hb == 0 && !v.meta8 && (v.g == 2 || v.g == 4);
 }
 
+int rkv_mfma_variant(const rkv_cache* c) {
+  return mfma_cross_block(c) ? RKV_KERNEL_MFMA_CROSS : mfma_sub_groups(c) ? RKV_KERNEL_MFMA_SUB : RKV_KERNEL_MFMA;
+}
+
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
   if (mfma_cross_block(c) || mfma_sub_groups(c)) return true;

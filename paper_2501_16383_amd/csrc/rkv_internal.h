@@ -36,7 +36,10 @@
 //             operand dwords of FP4 nibbles, as the 2-bit unpacking does for the low bits;
 //   K meta, V meta   128 / quant_group entries in place of each one (gid then counts blocks of
 //             quant_group reordered positions).
-// Those settings run on the general kernels only.
+// 3- and 4-bit codes in groups of 128 run on the matrix-core kernels (k_append_mfma<.., HB>,
+// k_decode_mfma<.., HB>: the planes above the low two bits go through the same products); groups
+// of 64 / 32 are read by the sub-group variant of the matrix-core decode kernel (2-bit codes, fp16
+// metadata) and by the general kernel otherwise.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -44,6 +47,8 @@
 #include "../../include/rkv.h"
 
 #define RKV_D 128
+#define RKV_LDS_BYTES (160 * 1024)   // LDS of a compute unit
+#define RKV_STAGE_SLOTS 4             // pinned host slots for per-sequence counts on their way to the device
 #define RKV_PART_STRIDE 132   // floats per split-K partial: m, l, 2 pad, acc[128]
 
 struct RkvView {
@@ -88,6 +93,9 @@ struct rkv_cache {
   rkv_config cfg;
   RkvView v;           // v.len: the length of the longest sequence
   int32_t* hlens;      // host mirror of the per-sequence lengths [batch]
+  int32_t* stage;      // pinned host ring [RKV_STAGE_SLOTS][batch]: per-sequence counts on their way to dev_nnew
+  hipEvent_t stage_ev[RKV_STAGE_SLOTS];   // recorded after the copy that reads a slot
+  int stage_used[RKV_STAGE_SLOTS], stage_next;
   int* dev_lens;       // device copy (kept current once `ragged` is set) and staging for per-sequence token counts
   int* dev_nnew;
   int* dev_cstart;     // [batch + 1], see RkvView::cstart
@@ -290,6 +298,7 @@ int rkv_mfma_share(int heads_per_kv_head);
 int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* v, const __half* q, const int* q_pos, float* qr, int share,
                          hipStream_t s);
 bool rkv_mfma_supported(const rkv_cache* c);
+int rkv_mfma_variant(const rkv_cache* c);   // RKV_KERNEL_MFMA, _MFMA_CROSS or _MFMA_SUB (if rkv_mfma_supported)
 void rkv_launch_prep_q(const RkvView& v, const __half* q, const int* q_pos, int cur, float* qr, int share, int nq,
                        hipStream_t s);
 void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int nch, int chunk_tokens, const __half* k_cur,

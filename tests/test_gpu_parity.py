@@ -13,6 +13,7 @@ from oracle import rkv_oracle as O
 import paper_2501_16383_amd as R
 import rkv_synth as S
 import parity_utils as P
+from paper_2501_16383_amd import binding as RB
 
 pytestmark = pytest.mark.gpu
 
@@ -164,7 +165,10 @@ def test_reorder_across_blocks(span_kind):
     perm = calibrated_perm(w, cfg, offset_variant=True)
     assert not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
     # a reorder inside the rotation group has a matrix-core variant of the decode kernel; across groups only the general one
-    full_check(w, cfg, 100, perm=perm, paths=(1, 2) if span_kind == "group" else (1,), sink_positions=[])
+    cache, _, _ = full_check(w, cfg, 100, perm=perm, paths=(1, 2) if span_kind == "group" else (1,), sink_positions=[])
+    cache.set_decode_path(0)
+    want = RB.KERNEL_MFMA_CROSS if span_kind == "group" else RB.KERNEL_GENERAL
+    assert cache.decode_kernel() == want and cache.append_kernel() == want
 
 
 @pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
@@ -183,6 +187,7 @@ def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style, fmt):
     cache, oc, q = full_check(w, cfg, 613, perm=perm, chunks=[0, 300, 301, 302, 613], paths=(1, 2),
                               sink_positions=None if (g, hq, style, fmt) == (4, 8, 0, 0) else [])
     cache.set_decode_path(2)
+    assert cache.decode_kernel() == RB.KERNEL_MFMA_CROSS and cache.append_kernel() == RB.KERNEL_MFMA_CROSS
     k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
     out = cache.decode_attention(P.gpu(q), k_cur=P.gpu(k1[:, 0]), v_cur=P.gpu(v1[:, 0]))      # the cache holds the oracle's codes here
     torch.cuda.synchronize()
@@ -237,7 +242,10 @@ def test_variants(g, style, vrot):
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     cfg = R.RkvConfig(batch=1, n_q_heads=8, n_kv_heads=8, max_tokens=160, max_sinks=2, rot_heads=g, perm_span=128,
                       rope_style=style, v_rotate=vrot)
-    full_check(w, cfg, 150, sink_positions=[0, 3], paths=(1, 2) if g in (2, 4) else (1, 0))
+    cache, _, _ = full_check(w, cfg, 150, sink_positions=[0, 3], paths=(1, 2) if g in (2, 4) else (1, 0))
+    cache.set_decode_path(0)
+    assert cache.decode_kernel() == (RB.KERNEL_MFMA if g in (2, 4) else RB.KERNEL_GENERAL)
+    assert cache.append_kernel() == (RB.KERNEL_GENERAL if g in (1, 8) else RB.KERNEL_SHUFFLE if vrot else RB.KERNEL_MFMA)
 
 
 def test_incremental_append_matches_bulk():
@@ -336,16 +344,20 @@ def export_host(cache):
     return {k: v.cpu().numpy() for k, v in exp.items()}
 
 
-@pytest.mark.parametrize("meta_format,bits", [(0, 2), (1, 2), (0, 4), (1, 3)])
-def test_full_size_config2_sampled(meta_format, bits):
+@pytest.mark.parametrize("meta_format,bits,with_sinks", [(0, 2, True), (0, 2, False), (1, 2, True), (0, 4, True), (1, 3, False)])
+def test_full_size_config2_sampled(meta_format, bits, with_sinks):
     """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, then one rkv_decode_step (the last
     token's append and the attention on the matrix-core path).  The oracle recomputes sampled (sequence, rotation group) slices - a
     rotation group's codes and attention outputs depend on nothing outside the slice.  Once with
-    fp16 metadata, once with the FP8 scale / INT8 zero-point storage, once with 4-bit codes, once with 3-bit codes and FP8 / INT8 metadata."""
+    fp16 metadata, once with the FP8 scale / INT8 zero-point storage, once with 4-bit codes, once with 3-bit codes and FP8 / INT8 metadata.
+    With the workload's four fp16 sink rows, as bench.py runs it, and with no retained rows at
+    all: the sink keys are a hundred times the rest and take nearly all the softmax weight, so only
+    the run without them lets the compressed stream decide the outputs."""
     w = S.WORKLOADS["cfg2"]
     T = w.context
-    cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=4,
+    n_keep = 4 if with_sinks else 0
+    cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=n_keep,
                       rot_heads=4, perm_span=128, meta_format=meta_format, bits=bits)
     perm = calibrated_perm(w, cfg)
     cache = R.RkvCache(cfg)
@@ -356,7 +368,7 @@ def test_full_size_config2_sampled(meta_format, bits):
     k_parts, v_parts, m_parts = [], [], []
     rng_w = dataclasses.replace(w)
     for b in range(w.batch):
-        kb, vb, mb = S.make_kv(dataclasses.replace(rng_w, seed=w.seed + 100 * b), T, batch=1)
+        kb, vb, mb = S.make_kv(dataclasses.replace(rng_w, seed=w.seed + 100 * b), T, batch=1, sink_positions=None if with_sinks else [])
         for (sb, rg) in samples:
             if sb == b:
                 keep[(sb, rg)] = (kb[:, :, 4 * rg:4 * rg + 4].copy(), vb[:, :, 4 * rg:4 * rg + 4].copy(), mb.copy())
@@ -369,8 +381,10 @@ def test_full_size_config2_sampled(meta_format, bits):
     del k_parts, v_parts
     q = S.make_q(w)
     print("[case] full-size config 2: bulk append 4095 + one decode step (append 1 + attention, as bench.py does)", flush=True)
-    cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous())
+    cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous() if with_sinks else None)
     cache.set_decode_path(2)
+    # the kernels bench.py times, not a fall-back to the general ones
+    assert cache.decode_kernel() == RB.KERNEL_MFMA and cache.append_kernel() == RB.KERNEL_MFMA
     assert not bool(mask[:, T - 1:].any())                  # the step's token is an ordinary one
     out, lse = cache.decode_step(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), P.gpu(q), want_lse=True)
     exp = export_host(cache)
@@ -380,8 +394,8 @@ def test_full_size_config2_sampled(meta_format, bits):
     assert np.isfinite(out).all()
     for (b, rg) in samples:
         ks, vs, ms = keep[(b, rg)]
-        check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=perm, tag=f"full-size meta_format={meta_format} bits={bits}",
-                    meta_format=meta_format, bits=bits)
+        check_slice(exp, out, lse, b, rg, ks, vs, ms if with_sinks else None, q, perm=perm, max_sinks=n_keep,
+                    tag=f"full-size meta_format={meta_format} bits={bits} sinks={with_sinks}", meta_format=meta_format, bits=bits)
 
 
 def test_full_size_long_context_sampled():
@@ -395,6 +409,7 @@ def test_full_size_long_context_sampled():
     q = S.make_q(w)
     print("[case] long context: bulk append 32768 + decode", flush=True)
     cache.quantize_append(P.gpu(k), P.gpu(v), P.gpu(mask))
+    assert cache.decode_kernel() == RB.KERNEL_MFMA and cache.append_kernel() == RB.KERNEL_MFMA
     out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
     exp = export_host(cache)
     out = out.cpu().numpy().astype(np.float64)
@@ -437,6 +452,7 @@ def test_full_size_config4_gqa_sampled(with_sinks):
     print("[case] full-size config 4: bulk append 8191 + one decode step", flush=True)
     cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous() if with_sinks else None)
     cache.set_decode_path(2)
+    assert cache.decode_kernel() == RB.KERNEL_MFMA and cache.append_kernel() == RB.KERNEL_MFMA
     assert not bool(mask[:, T - 1:].any())
     out, lse = cache.decode_step(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), P.gpu(q), want_lse=True)
     exp = export_host(cache)
