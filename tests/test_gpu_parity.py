@@ -508,9 +508,9 @@ def test_large_zero_points():
     cache.quantize_append(P.gpu(k), P.gpu(v))
     O.quantize_append(oc, k, v)
     g = P.export_numpy(cache)
-    # values of magnitude 300 against block ranges of ~6: many more blocks sit inside the (wider) tie windows
+    # values of magnitude 300 against block ranges of ~6: more blocks sit inside the (wider) tie windows - 11 % observed
     P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"], "large zero-points K",
-                    rot_span=512, max_ambiguous=0.5)
+                    rot_span=512, max_ambiguous=0.2)
     P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], "large zero-points V")
     assert np.abs(g["k_zero"]).max() > 100
     oc_g = oracle_from_export(oc, g)
@@ -560,8 +560,8 @@ def test_degenerate_and_extreme_blocks(bits):
             O.quantize_append(oc, k[:, a:b], v[:, a:b], None, keys_rotated=True)
     torch.cuda.synchronize()
     # (the planted blocks with a range near zero count as ties in the comparison: their metadata
-    # and codes are checked one by one below instead)
-    g, sk, sv = P.check_cache_against_oracle(cache, oc, f"special blocks bits={bits}", max_ambiguous=0.3)
+    # and codes are checked one by one below instead: 13 % of the blocks here)
+    g, sk, sv = P.check_cache_against_oracle(cache, oc, f"special blocks bits={bits}", max_ambiguous=0.25)
     top = 2 ** bits - 1
     for name in ("k", "v"):
         sc, ze, co = g[name + "_scale"][0], g[name + "_zero"][0], g[name + "_codes"][0].reshape(T, 8, 128)
