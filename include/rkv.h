@@ -41,6 +41,7 @@ extern "C" {
 #define RKV_EPERM     (-3)  /* reorder indices are not a permutation or leave their perm_span    */
 #define RKV_EHIP      (-4)  /* a HIP call or kernel launch failed                                */
 #define RKV_ESTATE    (-5)  /* call not valid in the cache's current state (e.g. empty cache)    */
+#define RKV_ESCRATCH  (-6)  /* rkv_decode_attention_static: built-in work space too small        */
 
 typedef struct rkv_config {
   int32_t batch;        /* sequences per cache, >= 1                                             */
@@ -194,6 +195,22 @@ int rkv_quantize_append_ragged(rkv_cache* cache, const void* dev_k, const void* 
  * RKV_ESTATE on an empty cache. */
 int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos,
                          float* dev_out, float* dev_lse, void* dev_scratch, void* stream);
+
+/* rkv_decode_attention for callers that cannot allocate or hand over a work space: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The prepared queries and
+ * the split-K partials go to a work space built into the library (a device array of
+ * RKV_STATIC_SCRATCH_BYTES, one copy per GPU, held until the process ends) instead of dev_scratch;
+ * the call allocates and frees nothing.  Same arguments otherwise, same kernels, same results bit
+ * for bit.  RKV_ESCRATCH - and nothing enqueued - if this call needs more than the built-in space:
+ * 2560 bytes per (sequence, query head) plus 528 bytes per (sequence, query head, chunk of 256
+ * cached tokens; of 128 on the general kernel), e.g. 7 MB for batch 16 x 40 heads x 4096 tokens.
+ * All calls on one GPU share that GPU's array and it keeps the last call's contents (nothing in
+ * it needs clearing: every partial a call reads it has written first): calls that overlap on one
+ * GPU - different streams, different caches - race; order them on one stream.  The device that
+ * was current at rkv_cache_create must be current. */
+#define RKV_STATIC_SCRATCH_BYTES (24u << 20)
+int rkv_decode_attention_static(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos,
+                                float* dev_out, float* dev_lse, void* stream);
 
 /* The same, with the token being decoded attended in full precision (the decoding procedure that
  * concatenates the new key and value to the dequantized cache before they are quantized): the

@@ -15,12 +15,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librkv.so")
 _lib = None
 
-RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE = 0, -1, -2, -3, -4, -5
+RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE, RKV_ESCRATCH = 0, -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 24 << 20
 KERNEL_GENERAL, KERNEL_SHUFFLE, KERNEL_MFMA, KERNEL_MFMA_CROSS, KERNEL_MFMA_SUB = 1, 2, 3, 4, 5
 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",
-    "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention", "rkv_decode_attention_with_current",
+    "rkv_calibrate_perm", "rkv_fold_rotation", "rkv_set_perm", "rkv_select_sinks", "rkv_quantize_append", "rkv_decode_attention", "rkv_decode_attention_static", "rkv_decode_attention_with_current",
     "rkv_decode_attention_multi", "rkv_decode_step", "rkv_quantize_append_ragged", "rkv_cache_lengths", "rkv_cache_truncate",
     "rkv_set_decode_path", "rkv_decode_kernel_of", "rkv_append_kernel_of", "rkv_set_profile_events", "rkv_dequantize", "rkv_export_codes", "rkv_import_codes", "rkv_export_sinks", "rkv_layout_locate",
     "rkv_strerror",
@@ -96,6 +97,7 @@ def load_library():
     lib.rkv_select_sinks.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.rkv_quantize_append.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rkv_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.rkv_decode_attention_static.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.rkv_decode_attention_with_current.argtypes = [vp] * 9
     lib.rkv_decode_attention_multi.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp, vp]
     lib.rkv_decode_step.argtypes = [vp] * 9
@@ -335,6 +337,24 @@ class RkvCache:
         _check(self.lib.rkv_decode_attention(self.handle, _ptr(q), _ptr(q_pos), _ptr(out), _ptr(lse),
                                              _ptr(self.scratch), _stream()), "rkv_decode_attention")
         return (out, lse) if want_lse else out
+
+    def decode_attention_static(self, q, out, q_pos=None, lse=None):
+        """rkv_decode_attention_static: the library's built-in work space instead of a scratch
+        tensor; the caller brings every buffer (out [batch, n_q_heads, 128] fp32, lse optional), so
+        that neither this wrapper nor the library allocates."""
+        import torch
+        q = _dev(q, torch.float16, "q")
+        q_pos = _dev(q_pos, torch.int32, "q_pos")
+        out = _dev(out, torch.float32, "out")
+        lse = _dev(lse, torch.float32, "lse")
+        cfg = self.cfg
+        if q.shape != (cfg.batch, cfg.n_q_heads, cfg.head_dim) or out.shape != q.shape:
+            raise ValueError("q, out must be [batch, n_q_heads, head_dim]")
+        if lse is not None and lse.shape != q.shape[:2]:
+            raise ValueError("lse must be [batch, n_q_heads]")
+        _check(self.lib.rkv_decode_attention_static(self.handle, _ptr(q), _ptr(q_pos), _ptr(out), _ptr(lse), _stream()),
+               "rkv_decode_attention_static")
+        return out
 
     def decode_step(self, k, v, q, q_pos=None, out=None, lse=None, want_lse=False):
         """rkv_decode_step: append one token per sequence (k, v [batch, 1, n_kv_heads, 128]) and attend."""

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -11,6 +12,29 @@
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static void free_host_side(rkv_cache* c);
+
+// Work space of rkv_decode_attention_static: prepared queries and split-K partials, as in the
+// caller's dev_scratch of rkv_decode_attention.  Every GPU the library runs on holds its own copy
+// of the array, at its own address, until the process ends.  In host code `scratch` is only a
+// handle for hipGetSymbolAddress: the kernels get the address looked up below.
+static __device__ __align__(256) unsigned char scratch[RKV_STATIC_SCRATCH_BYTES];
+#define RKV_MAX_DEVICES 64
+static void* g_static_scratch[RKV_MAX_DEVICES];   // per device, filled on the first look-up with that device current
+static std::mutex g_static_scratch_lock;
+
+static int static_scratch_of_current_device(void** out) {
+  int dev = -1;
+  RKV_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= RKV_MAX_DEVICES) return RKV_EINVAL;
+  std::lock_guard<std::mutex> hold(g_static_scratch_lock);
+  if (!g_static_scratch[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RKV_EHIP;
+    g_static_scratch[dev] = p;
+  }
+  *out = g_static_scratch[dev];
+  return RKV_OK;
+}
 
 static int check_config(const rkv_config* c, bool need_capacity) {
   if (!c) return RKV_EINVAL;
@@ -239,6 +263,14 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.cstart = nullptr;
   v.nnew = nullptr;
   v.theta = cfg->rope_theta;
+  {
+    void* unused = nullptr;                                  // set-up: this device's address of the static work space
+    rc = static_scratch_of_current_device(&unused);
+    if (rc != RKV_OK) {
+      free_host_side(c);
+      return rc;
+    }
+  }
   rc = rkv_launch_init(c, true, (hipStream_t)stream);
   if (rc == RKV_OK && cfg->quant_group < 128) {            // the identity reorder's tables for groups of 64 / 32
     std::vector<int32_t> ident(v.E);
@@ -505,6 +537,23 @@ RKV_EXPORT int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const i
   return rkv_launch_decode_general(cache, (const __half*)dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
 }
 
+RKV_EXPORT int rkv_decode_attention_static(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, float* dev_out,
+                                           float* dev_lse, void* stream) {
+  if (!cache) return RKV_EINVAL;
+  // what this call's kernels write: the prepared queries, then one partial per (sequence, query
+  // head, chunk of the cache's current length) - chunks of the kernel that will run
+  const bool fast = rkv_mfma_supported(cache) && cache->decode_path != 1;
+  const size_t chunk = fast ? RKV_MFMA_CHUNK : RKV_GEN_CHUNK;
+  const size_t nch = ((size_t)cache->v.len + chunk - 1) / chunk;
+  const size_t need = rkv_query_scratch_bytes(cache->v.B, cache->v.Hq) +
+                      (size_t)cache->v.B * cache->v.Hq * nch * RKV_PART_STRIDE * 4 + 256;
+  if (need > RKV_STATIC_SCRATCH_BYTES) return RKV_ESCRATCH;
+  void* ptr = nullptr;
+  const int rc = static_scratch_of_current_device(&ptr);
+  if (rc != RKV_OK) return rc;
+  return rkv_decode_attention(cache, dev_q, dev_q_pos, dev_out, dev_lse, ptr, stream);
+}
+
 RKV_EXPORT int rkv_decode_step(rkv_cache* cache, const void* dev_k, const void* dev_v, const void* dev_q, const int32_t* dev_q_pos,
                                float* dev_out, float* dev_lse, void* dev_scratch, void* stream) {
   if (!cache || !dev_k || !dev_v || !dev_q || !dev_out || !dev_scratch) return RKV_EINVAL;
@@ -612,6 +661,7 @@ RKV_EXPORT const char* rkv_strerror(int code) {
     case RKV_EPERM: return "reorder indices are not a permutation closed under perm_span";
     case RKV_EHIP: return "HIP runtime error";
     case RKV_ESTATE: return "call not valid in the cache's current state";
+    case RKV_ESCRATCH: return "the library's built-in work space is too small for this cache (pass a work space of your own: rkv_decode_attention)";
     default: return "unknown error";
   }
 }

@@ -7,7 +7,7 @@
 #include "rkv_internal.h"
 #include "rkv_prep_q.h"
 
-#define GEN_CHUNK 128
+#define GEN_CHUNK RKV_GEN_CHUNK
 
 template <int PL, typename T>
 __device__ inline void fwht_lanes_d(T (&x)[PL], int lane, int xstages) {

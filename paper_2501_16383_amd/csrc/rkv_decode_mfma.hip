@@ -41,6 +41,7 @@ typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 #endif
 #define MF_CH (64 * MF_TILES)   // tokens per workgroup (4 waves)
 static_assert(MF_CH == 256, "the per-sequence chunk table (k_lens) counts chunks of 256 tokens");
+static_assert(MF_CH == RKV_MFMA_CHUNK, "the work-space size of a call is worked out from RKV_MFMA_CHUNK");
 #ifndef MF_ACC
 #define MF_ACC 16         // score accumulators per lane and pass of the key phase
 #endif

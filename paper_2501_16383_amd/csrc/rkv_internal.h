@@ -50,6 +50,8 @@
 #define RKV_LDS_BYTES (160 * 1024)   // LDS of a compute unit
 #define RKV_STAGE_SLOTS 4             // pinned host slots for per-sequence counts on their way to the device
 #define RKV_PART_STRIDE 132   // floats per split-K partial: m, l, 2 pad, acc[128]
+#define RKV_GEN_CHUNK 128     // tokens per split-K chunk of the general decode kernel
+#define RKV_MFMA_CHUNK 256    // ... of the matrix-core decode kernel
 
 struct RkvView {
   uint32_t* kc;
