@@ -254,7 +254,12 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
  * the configuration is outside what it covers: a reorder across rotation groups, rot_heads 1 or
  * 8; a reorder across blocks of 128 inside the rotation groups only with 2-bit codes and one
  * query token per step; quant_group 64 or 32 only with 2-bit codes, fp16 metadata, a reorder
- * inside the heads and one query token per step). */
+ * inside the heads and one query token per step).
+ * 3 = measurement only: the matrix-core kernel with the cache stream (codes and metadata of keys
+ * and values) replaced by values made up in registers, i.e. the time its arithmetic takes when no
+ * byte of the cache has to arrive - the ceiling the vector and matrix units set.  Outputs are
+ * meaningless.  Plain configurations only (2-bit codes, fp16 metadata, reorder inside blocks of
+ * 128, one query head per KV head), else RKV_EINVAL at the next decode. */
 int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 
 /* Which kernel the cache's configuration and installed reorder take (no device work): the decode

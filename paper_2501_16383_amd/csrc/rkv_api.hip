@@ -361,7 +361,7 @@ RKV_EXPORT int rkv_cache_truncate(rkv_cache* cache, const int32_t* host_new_leng
 }
 
 RKV_EXPORT int rkv_set_decode_path(rkv_cache* cache, int32_t path) {
-  if (!cache || path < 0 || path > 2) return RKV_EINVAL;
+  if (!cache || path < 0 || path > 3) return RKV_EINVAL;
   cache->decode_path = path;
   return RKV_OK;
 }
@@ -371,7 +371,7 @@ RKV_EXPORT int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries) {
   const int kind = rkv_mfma_supported(cache) ? rkv_mfma_variant(cache) : RKV_KERNEL_GENERAL;
   if (n_queries > 0) return kind == RKV_KERNEL_MFMA && cache->decode_path != 1 ? kind : RKV_EINVAL;   // multi-query: plain matrix-core kernel only
   if (cache->decode_path == 1) return RKV_KERNEL_GENERAL;
-  if (cache->decode_path == 2 && kind == RKV_KERNEL_GENERAL) return RKV_EINVAL;
+  if (cache->decode_path >= 2 && kind == RKV_KERNEL_GENERAL) return RKV_EINVAL;
   return kind;
 }
 
@@ -529,7 +529,7 @@ RKV_EXPORT int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const i
     for (int b = 0; b < cache->v.B; ++b)
       if (cache->hlens[b] < 1) return RKV_ESTATE;           // a sequence with nothing to attend
   bool fast = rkv_mfma_supported(cache);
-  if (cache->decode_path == 2 && !fast) return RKV_EINVAL;
+  if (cache->decode_path >= 2 && !fast) return RKV_EINVAL;
   if (cache->decode_path == 1) fast = false;
   if (fast)
     return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, 0, dev_out, dev_lse, dev_scratch, false,

@@ -30,6 +30,7 @@
 // that share a KV head: unpacking, rotation and RoPE of the keys are done once for them, the
 // softmax and value phases once per query head.  Everything else takes the general kernel.
 #include "rkv_internal.h"
+#include <cstdlib>
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -181,7 +182,11 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // rotated 128-block then holds SUB quantization blocks; pass `sub` takes sub-block `sub` of every
 // head at once (masked operands; the small products with those sub-blocks' scales, one per head,
 // signs of H_g), and the zero-point product contracts over all G * SUB blocks of the group.
-template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false, int SUB = 0>
+// ALU: measurement only.  The same kernel with the cache stream - K codes, K metadata, V codes,
+// V metadata - replaced by values made up in registers (from the lane number and a kernel
+// argument, so that nothing folds at compile time): what the arithmetic alone costs when no byte
+// of the cache has to arrive.  The results mean nothing.
+template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false, int SUB = 0, bool ALU = false>
 __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF_OCC)) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq) {
@@ -209,6 +214,12 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   __shared__ int s_lim[MULTI ? NH : 1];          // last position each served query head may attend
   constexpr int QV = REP == 1 ? 4 : 1;            // query versions held (positions pos - r); with REP > 1 only r = 0
   __shared__ uint4 s_q[QV][4][NH / 2][16];        // [r][p][f / 4][n] x 4 floats f % 4, f = (KV head * REP + query head of it) * 2 + (lo, hi)
+  // Metadata of the chunk's keys and values (plain variants): fetched once, at the start, token by
+  // token, and kept in LDS - a tile's worth held in registers a whole tile ahead of its use costs
+  // 16 registers, which is the difference between three and four workgroups per compute unit
+  constexpr bool LM = !XB;
+  constexpr int MWL = META8 ? G / 2 : G;             // metadata dwords per token and rotation group
+  __shared__ __attribute__((aligned(16))) uint32_t s_km[LM ? MF_CH * MWL : 1], s_vm[LM ? MF_CH * MWL : 1];
   constexpr int XK = XB ? (SUB ? G * SUB : G) : 1;   // quantization blocks of the rotation group
   constexpr int NP = SUB ? SUB : G;                  // passes of the key phase
   __shared__ uint4 s_xmask[XB ? G * NP * 4 : 1];  // [rotated block][pass][lane group q]
@@ -216,6 +227,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   float* const s_xtt = ALIAS ? reinterpret_cast<float*>(s_A_raw) : s_xtt_own;   // [channel][quantization block][head]
   static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
   static_assert(SUB == 0 || (XB && !META8), "groups of 64 / 32 run as a variant of the cross-block kernel, fp16 metadata");
+  static_assert(!ALU || (!XB && !META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -306,6 +318,29 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   // queries of this rotation group, already RoPE'd, scaled and laid out as s_q by k_prep_q
   for (int i = tid; i < QV * 16 * 4 * 2 * NH / 4; i += 256)
     (&s_q[0][0][0][0])[i] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (4 * 16 * 4 * 2 * NH))[i];
+  if constexpr (LM) {                              // thread = token of the chunk (inside the padded allocation)
+    const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * MWL;
+    if constexpr (ALU) {                                 // scale 1, zero-point 0
+#pragma unroll
+      for (int i = 0; i < MWL; ++i) s_km[tid * MWL + i] = 0x00003C00u + (uint32_t)(nq - 1);
+    } else if constexpr (MWL == 4) {
+      *reinterpret_cast<uint4*>(&s_km[tid * 4]) = rkv_ld_stream(reinterpret_cast<const uint4*>(v.km + mi));
+    } else if constexpr (MWL == 2) {
+      *reinterpret_cast<uint2*>(&s_km[tid * 2]) = rkv_ld_stream(reinterpret_cast<const uint2*>(v.km + mi));
+    } else {
+      s_km[tid] = v.km[mi];
+    }
+    if constexpr (ALU) {
+#pragma unroll
+      for (int i = 0; i < MWL; ++i) s_vm[tid * MWL + i] = 0x00003C00u + (uint32_t)(nq - 1);
+    } else if constexpr (MWL == 4) {
+      *reinterpret_cast<uint4*>(&s_vm[tid * 4]) = rkv_ld_stream(reinterpret_cast<const uint4*>(v.vm + mi));
+    } else if constexpr (MWL == 2) {
+      *reinterpret_cast<uint2*>(&s_vm[tid * 2]) = rkv_ld_stream(reinterpret_cast<const uint2*>(v.vm + mi));
+    } else {
+      s_vm[tid] = v.vm[mi];
+    }
+  }
   {
     // ------------------------------------------------------------------ phase K
     {
@@ -327,13 +362,18 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       uint32_t mw[4][MW];
       uint32_t xmeta = 0, xmeta2 = 0;                      // cross-block variant: (scale, zero) of token n of the tile, quantization block q
       auto load_tile = [&](int ti) {
+        if constexpr (ALU) {                                 // made-up codes
+          const uint32_t x = (uint32_t)lane * 2654435761u ^ (uint32_t)(nq + ti);
+#pragma unroll
+          for (int pr = 0; pr < G / 2; ++pr) cw[pr] = make_uint4(x, x * 3u, x * 5u, x * 7u + pr);
+        }
         if constexpr (XB && !META8 && SUB == 0) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
         if constexpr (XB && META8) {                       // the token's scale bytes and zero-point bytes
           xmeta = kmeta[(size_t)(ti * 16 + n) * MW];
           if constexpr (G == 4) xmeta2 = kmeta[(size_t)(ti * 16 + n) * MW + 1];
         }
 #pragma unroll
-        for (int pr = 0; pr < G / 2; ++pr) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
+        for (int pr = 0; pr < G / 2; ++pr) if constexpr (!ALU) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
         if constexpr (HI) {
 #pragma unroll
           for (int pr = 0; pr < G / 2; ++pr) {
@@ -346,7 +386,9 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
             }
           }
         }
-        if constexpr (SUB != 0) {
+        if constexpr (LM) {
+          // (plain variants: the chunk's metadata are in LDS)
+        } else if constexpr (SUB != 0) {
           // (groups of 64 / 32: the tile's metadata are fetched where they are used, G * SUB entries per token)
         } else if constexpr (META8) {
           // the lane's four tokens are consecutive: 4 x 2G bytes in one piece
@@ -388,6 +430,25 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       for (int ti = 0; ti < MF_TILES; ++ti) {
         const int tt = tw + ti * 16;
         if (tt >= len) break;                              // wave-uniform
+        if constexpr (LM) {                                // the metadata of the lane's four tokens: consecutive in LDS
+          const uint32_t* mp = &s_km[(wave * (16 * MF_TILES) + ti * 16 + 4 * q) * MW];
+          if constexpr (MW == 4) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const uint4 u = *reinterpret_cast<const uint4*>(mp + 4 * r);
+              mw[r][0] = u.x; mw[r][1] = u.y; mw[r][2] = u.z; mw[r][3] = u.w;
+            }
+          } else if constexpr (MW == 2) {
+#pragma unroll
+            for (int r = 0; r < 4; r += 2) {
+              const uint4 u = *reinterpret_cast<const uint4*>(mp + 2 * r);
+              mw[r][0] = u.x; mw[r][1] = u.y; mw[r + 1][0] = u.z; mw[r + 1][1] = u.w;
+            }
+          } else {
+            const uint4 u = *reinterpret_cast<const uint4*>(mp);
+            mw[0][0] = u.x; mw[1][0] = u.y; mw[2][0] = u.z; mw[3][0] = u.w;
+          }
+        }
         v8i A[G];
 #pragma unroll
         for (int pr = 0; pr < G / 2; ++pr) {
@@ -718,7 +779,9 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 #pragma unroll
     for (int i = 0; i < MF_CH / 64; ++i) {
       const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * (G * NS);
-      if constexpr (SUB != 0) {
+      if constexpr (LM) {
+        // (read from LDS in the softmax phase)
+      } else if constexpr (SUB != 0) {
 #pragma unroll
         for (int sb = 0; sb < NS; ++sb) vmeta[sb][i] = wave < G ? v.vm[mi + wave * NS + sb] : 0u;
       } else if constexpr (META8) {
@@ -742,7 +805,10 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 #pragma unroll
     for (int sl = 0; sl < MF_CH / 32; ++sl) {
       vcodes[sl] = make_uint4(0, 0, 0, 0);
-      if (has_head && sl < nslab) vcodes[sl] = rkv_ld_stream(vslab + (size_t)sl * (64 * G) + lidx);
+      if constexpr (ALU) {
+        const uint32_t x = (uint32_t)lidx * 2654435761u ^ (uint32_t)(nq + sl);
+        if (has_head && sl < nslab) vcodes[sl] = make_uint4(x, x * 3u, x * 5u, x * 7u);
+      } else if (has_head && sl < nslab) vcodes[sl] = rkv_ld_stream(vslab + (size_t)sl * (64 * G) + lidx);
       if constexpr (HI) {
         vhcodes[sl] = make_uint4(0, 0, 0, 0);
         if (has_head && sl < nslab) {
@@ -781,7 +847,16 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 #pragma unroll
       for (int i = 0; i < MF_CH / 64; ++i) {
         float s_, z_;
-        if constexpr (META8) {
+        if constexpr (LM) {                                 // token lane + 64 i, head a
+          const uint32_t* mp = &s_vm[(lane + 64 * i) * MWL];
+          if constexpr (META8) {                            // G scale bytes, then G zero-point bytes
+            const uint32_t sw = mp[0], zw = G == 4 ? mp[1] : mp[0] >> 16;
+            s_ = rkv_e4m3_decode((sw >> (8 * a)) & 0xffu);
+            z_ = (float)((zw >> (8 * a)) & 0xffu) - 128.0f;
+          } else {
+            rkv_unpack_meta(mp[a], s_, z_);
+          }
+        } else if constexpr (META8) {
           s_ = __builtin_amdgcn_cvt_f32_fp8((int)vmeta[sb][i], 0);
           z_ = (float)((vmeta[sb][i] >> 8) & 0xffu) - 128.0f;
         } else {
@@ -892,6 +967,8 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   }
 }
 
+
+
 // the cross-block variant of the kernel: a reorder inside the rotation groups, plain configuration
 static bool mfma_cross_block(const rkv_cache* c) {
   const RkvView& v = c->v;
@@ -915,6 +992,16 @@ bool rkv_mfma_supported(const rkv_cache* c) {
   return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4);
 }
 
+#ifdef RKV_DEV_FEW_VARIANTS
+// developer builds: only the plain 2-bit variants of four-head rotation groups (quick to compile)
+template <bool MULTI>
+static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* qt, float* part, int nch, const int* q_lim,
+                          int nq, hipStream_t s) {
+  if (MULTI || v.g != 4 || v.hb || v.meta8) abort();
+  if (share == 1) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);
+  else hipLaunchKernelGGL((k_decode_mfma<4, 2, false, false, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);
+}
+#else
 template <bool MULTI>
 static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* qt, float* part, int nch, const int* q_lim,
                           int nq, hipStream_t s) {
@@ -939,6 +1026,8 @@ static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* q
   else RKV_MF_LAUNCH(2, 2);
 #undef RKV_MF_LAUNCH
 }
+
+#endif
 
 // nq == 0: the usual step, one query token that attends the whole cache (and, if set, the current
 // token's exact row).  nq >= 1: nq query tokens per sequence, token i at position q_pos[b][i] and
@@ -977,6 +1066,9 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   }
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (nch == 0) {}                                          // an empty cache has only the current token
+#ifdef RKV_DEV_FEW_VARIANTS
+  else if (sg || xb) abort();
+#else
   else if (sg) {
     const int sub = 128 / v.qg;
     if (v.g == 4 && sub == 2) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
@@ -989,6 +1081,12 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
     else if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
     else if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<2, 1, false, true, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
     else hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+  }
+#endif
+  else if (c->decode_path == 3) {                           // arithmetic-only measurement
+    if (multi || v.hb || v.meta8 || share != 1) return RKV_EINVAL;
+    if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
+    else hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
   }
   else if (multi) launch_kernel<true>(v, share, grid, qt, part, nch, q_pos, nq, s);
   else launch_kernel<false>(v, share, grid, qt, part, nch, nullptr, 1, s);
