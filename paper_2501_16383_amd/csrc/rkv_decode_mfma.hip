@@ -217,9 +217,20 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   // Metadata of the chunk's keys and values (plain variants): fetched once, at the start, token by
   // token, and kept in LDS - a tile's worth held in registers a whole tile ahead of its use costs
   // 16 registers, which is the difference between three and four workgroups per compute unit
+  // They are stored there in the form their users take: per token the scales of the group's blocks
+  // as packed fp16 pairs (s_ks: the A operand of the small matrix products, up to signs), for the
+  // values (scale, zero-point) per head (s_vm) - whatever the storage format was.  The keys'
+  // zero-points never reach the key phase: H_128 of a constant block is 128 z e_0, so they only
+  // touch channel 0 of every head, k^[a][0] -= (2 / sqrt(n)) * 64 * Z_a(t) with
+  // Z_a(t) = sum_blk H_g[a][blk] * scale_blk * zero_blk, and channel 0 is one half of RoPE pair 0,
+  // whose angle at token t is t itself.  Their share of the score of (token t, query head h),
+  //     - 64 * Z_a(t) * (cos(t) * q~[h][pair 0, first half] + sin(t) * q~[h][pair 0, second half]),
+  // is worked out once per token when the metadata are staged and put where the key phase adds
+  // its sum (s_sc).
   constexpr bool LM = !XB;
-  constexpr int MWL = META8 ? G / 2 : G;             // metadata dwords per token and rotation group
-  __shared__ __attribute__((aligned(16))) uint32_t s_km[LM ? MF_CH * MWL : 1], s_vm[LM ? MF_CH * MWL : 1];
+  constexpr int MWL = META8 ? G / 2 : G;             // metadata dwords per token and rotation group as stored
+  constexpr int GP = G / 2;                          // packed pairs per token
+  __shared__ __attribute__((aligned(16))) uint32_t s_ks[LM ? MF_CH * GP : 1], s_vm[LM ? MF_CH * G : 1];
   constexpr int XK = XB ? (SUB ? G * SUB : G) : 1;   // quantization blocks of the rotation group
   constexpr int NP = SUB ? SUB : G;                  // passes of the key phase
   __shared__ uint4 s_xmask[XB ? G * NP * 4 : 1];  // [rotated block][pass][lane group q]
@@ -257,7 +268,6 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   // rows >= G are zero
   const int hrow = n & 3;
   const uint32_t keep_row = hrow < G ? 0xffffffffu : 0u;
-  const uint32_t lane0_mask = (n == 0) ? 0xffffffffu : 0u;
   const uint32_t sm01 = ((__popc(hrow & 1) & 1) ? 0x80000000u : 0u);
   const uint32_t sm23 = ((__popc(hrow & 2) & 1) ? 0x00008000u : 0u) | ((__popc(hrow & 3) & 1) ? 0x80000000u : 0u);
 
@@ -305,8 +315,10 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   // the sink list (complete after the barrier that precedes the key phase); every wave clears
   // its own 64 score slots
   if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
+  if constexpr (!LM) {
 #pragma unroll
-  for (int a = 0; a < NH; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
+    for (int a = 0; a < NH; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
+  }
   if constexpr (MULTI) {
     // served head a * REP + rri is virtual head rrg * REP + rri of its KV head: query token (that / heads per token)
     if (tid < NH) s_lim[tid] = min(q_lim[b * nq + (rrg * REP + tid % REP) / (rep / nq)], len - 1);
@@ -320,25 +332,89 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
     (&s_q[0][0][0][0])[i] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (4 * 16 * 4 * 2 * NH))[i];
   if constexpr (LM) {                              // thread = token of the chunk (inside the padded allocation)
     const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * MWL;
-    if constexpr (ALU) {                                 // scale 1, zero-point 0
+    // a token's metadata as stored -> packed fp16 pairs (s01, s23) and (z01, z23)
+    auto pairs = [&](const uint32_t* src, uint32_t (&sp)[2], uint32_t (&zp)[2]) {
+      sp[1] = zp[1] = 0;
+      if constexpr (ALU) {                               // scale 1, zero-point 0
+        sp[0] = sp[1] = 0x3C003C00u + (uint32_t)(nq - 1);
+        zp[0] = zp[1] = 0;
+      } else if constexpr (META8) {
+        // G scale bytes, then G zero-point bytes.  FP8 -> fp32 -> fp16 is exact; a zero-point byte
+        // u = z + 128 under the high byte 0x64 is the fp16 number 1024 + u
+        const uint32_t d0 = src[0], dz = G == 4 ? src[1] : src[0] >> 16;
+        const v2h off = {(_Float16)1152.0f, (_Float16)1152.0f};
+        const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8((int)d0, false);
+        sp[0] = pk_f16(f01[0], f01[1]);
+        zp[0] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, __builtin_amdgcn_perm(0x64646464u, dz, 0x04010400u)) - off);
+        if constexpr (G == 4) {
+          const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8((int)d0, true);
+          sp[1] = pk_f16(f23[0], f23[1]);
+          zp[1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, __builtin_amdgcn_perm(0x64646464u, dz, 0x04030402u)) - off);
+        }
+      } else {                                           // (scale, zero-point) fp16 pairs per block
+        sp[0] = __builtin_amdgcn_perm(src[1], src[0], 0x05040100u);
+        zp[0] = __builtin_amdgcn_perm(src[1], src[0], 0x07060302u);
+        if constexpr (G == 4) {
+          sp[1] = __builtin_amdgcn_perm(src[3], src[2], 0x05040100u);
+          zp[1] = __builtin_amdgcn_perm(src[3], src[2], 0x07060302u);
+        }
+      }
+    };
+    auto fetch = [&](const uint32_t* g, uint32_t (&d)[4]) {
+      d[0] = d[1] = d[2] = d[3] = 0;
+      if constexpr (ALU) return;
+      if constexpr (MWL == 4) {
+        const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(g));
+        d[0] = u.x; d[1] = u.y; d[2] = u.z; d[3] = u.w;
+      } else if constexpr (MWL == 2) {
+        const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(g));
+        d[0] = u.x; d[1] = u.y;
+      } else {
+        d[0] = *g;
+      }
+    };
+    uint32_t dk[4], dv[4], sp[2], zp[2];
+    fetch(v.km + mi, dk);
+    fetch(v.vm + mi, dv);
+    pairs(dk, sp, zp);
 #pragma unroll
-      for (int i = 0; i < MWL; ++i) s_km[tid * MWL + i] = 0x00003C00u + (uint32_t)(nq - 1);
-    } else if constexpr (MWL == 4) {
-      *reinterpret_cast<uint4*>(&s_km[tid * 4]) = rkv_ld_stream(reinterpret_cast<const uint4*>(v.km + mi));
-    } else if constexpr (MWL == 2) {
-      *reinterpret_cast<uint2*>(&s_km[tid * 2]) = rkv_ld_stream(reinterpret_cast<const uint2*>(v.km + mi));
-    } else {
-      s_km[tid] = v.km[mi];
+    for (int i = 0; i < GP; ++i) s_ks[tid * GP + i] = sp[i];
+    {
+      // the zero-points' share of this token's scores (see above); -infinity past the sequence's end,
+      // which is what a slot the key phase never writes must hold
+      float sf[4], zf[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t sw = sp[i >> 1], zw = zp[i >> 1];
+        sf[i] = i < G ? (float)__builtin_bit_cast(_Float16, (uint16_t)(i & 1 ? sw >> 16 : sw & 0xffffu)) : 0.f;
+        zf[i] = i < G ? (float)__builtin_bit_cast(_Float16, (uint16_t)(i & 1 ? zw >> 16 : zw & 0xffffu)) : 0.f;
+      }
+      const float2 cs0 = v.rope[(size_t)(t0 + tid) * 64];
+      const float* q0 = qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (4 * 16 * 4 * 2 * NH);
+#pragma unroll
+      for (int a = 0; a < G; ++a) {
+        float Z = 0.f;
+#pragma unroll
+        for (int i = 0; i < G; ++i) Z = fmaf((__popc(a & i) & 1) ? -sf[i] : sf[i], zf[i], Z);
+#pragma unroll
+        for (int rri = 0; rri < REP; ++rri) {
+          const int f = (a * REP + rri) * 2;                 // entry (r = 0, p = 0, n = 0) of the prepared query: floats f, f + 1
+          const float ql = q0[(f >> 2) * 64 + (f & 3)], qh = q0[(f >> 2) * 64 + (f & 3) + 1];
+          s_sc[a * REP + rri][tid] = t0 + tid < len ? -64.0f * Z * fmaf(cs0.x, ql, cs0.y * qh) : -INFINITY;
+        }
+      }
     }
-    if constexpr (ALU) {
-#pragma unroll
-      for (int i = 0; i < MWL; ++i) s_vm[tid * MWL + i] = 0x00003C00u + (uint32_t)(nq - 1);
-    } else if constexpr (MWL == 4) {
-      *reinterpret_cast<uint4*>(&s_vm[tid * 4]) = rkv_ld_stream(reinterpret_cast<const uint4*>(v.vm + mi));
-    } else if constexpr (MWL == 2) {
-      *reinterpret_cast<uint2*>(&s_vm[tid * 2]) = rkv_ld_stream(reinterpret_cast<const uint2*>(v.vm + mi));
+    if constexpr (META8 || ALU) {                      // values: (scale, zero-point) per head
+      pairs(dv, sp, zp);
+      s_vm[tid * G] = __builtin_amdgcn_perm(zp[0], sp[0], 0x05040100u);
+      s_vm[tid * G + 1] = __builtin_amdgcn_perm(zp[0], sp[0], 0x07060302u);
+      if constexpr (G == 4) {
+        s_vm[tid * G + 2] = __builtin_amdgcn_perm(zp[1], sp[1], 0x05040100u);
+        s_vm[tid * G + 3] = __builtin_amdgcn_perm(zp[1], sp[1], 0x07060302u);
+      }
     } else {
-      s_vm[tid] = v.vm[mi];
+#pragma unroll
+      for (int i = 0; i < G; ++i) s_vm[tid * G + i] = dv[i];
     }
   }
   {
@@ -430,25 +506,6 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       for (int ti = 0; ti < MF_TILES; ++ti) {
         const int tt = tw + ti * 16;
         if (tt >= len) break;                              // wave-uniform
-        if constexpr (LM) {                                // the metadata of the lane's four tokens: consecutive in LDS
-          const uint32_t* mp = &s_km[(wave * (16 * MF_TILES) + ti * 16 + 4 * q) * MW];
-          if constexpr (MW == 4) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const uint4 u = *reinterpret_cast<const uint4*>(mp + 4 * r);
-              mw[r][0] = u.x; mw[r][1] = u.y; mw[r][2] = u.z; mw[r][3] = u.w;
-            }
-          } else if constexpr (MW == 2) {
-#pragma unroll
-            for (int r = 0; r < 4; r += 2) {
-              const uint4 u = *reinterpret_cast<const uint4*>(mp + 2 * r);
-              mw[r][0] = u.x; mw[r][1] = u.y; mw[r + 1][0] = u.z; mw[r + 1][1] = u.w;
-            }
-          } else {
-            const uint4 u = *reinterpret_cast<const uint4*>(mp);
-            mw[0][0] = u.x; mw[1][0] = u.y; mw[2][0] = u.z; mw[3][0] = u.w;
-          }
-        }
         v8i A[G];
 #pragma unroll
         for (int pr = 0; pr < G / 2; ++pr) {
@@ -470,46 +527,22 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
         }
         // scale rows of the 4x4 products: (+-s_0, +-s_1, +-s_2, +-s_3) of token 4q + r, signs of H_g row n & 3
         v4h sA[4];
+        if constexpr (LM) {
+          const uint32_t* sp = &s_ks[(wave * (16 * MF_TILES) + ti * 16 + 4 * q) * GP];
+          uint32_t sw[4][2];
+          if constexpr (G == 4) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          uint32_t a01, a23 = 0;
-          if constexpr (META8) {
-            // scale bytes 0..G-1 of the token's first dword: FP8 -> fp32 -> fp16, all exact
-            const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8((int)mw[r][0], false);
-            a01 = (pk_f16(f01[0], f01[1]) ^ sm01) & keep_row;
-            if constexpr (G == 4) {
-              const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8((int)mw[r][0], true);
-              a23 = (pk_f16(f23[0], f23[1]) ^ sm23) & keep_row;
+            for (int r = 0; r < 4; r += 2) {
+              const uint4 a = *reinterpret_cast<const uint4*>(sp + 2 * r);
+              sw[r][0] = a.x; sw[r][1] = a.y; sw[r + 1][0] = a.z; sw[r + 1][1] = a.w;
             }
           } else {
-            a01 = (__builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x05040100u) ^ sm01) & keep_row;
-            if constexpr (G == 4) a23 = (__builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x05040100u) ^ sm23) & keep_row;
+            const uint4 a = *reinterpret_cast<const uint4*>(sp);
+            sw[0][0] = a.x; sw[1][0] = a.y; sw[2][0] = a.z; sw[3][0] = a.w;
+            sw[0][1] = sw[1][1] = sw[2][1] = sw[3][1] = 0;
           }
-          sA[r] = as_v4h(a01, a23);
-        }
-        // zero-points: H_128 of a constant block is 128 z e_0, so they only touch channel 0 (lanes
-        // with n == 0).  sum_blk H_g[a][blk] * scale_blk * z_blk is one more 4x4x4 product (zero-points
-        // are integers up to 2048: exact in fp16); times -64 it becomes the accumulator of the
-        // channel-0 product below.
-        v4h zB[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          uint32_t z01, z23 = 0;
-          if constexpr (META8) {
-            // a zero-point byte u = z + 128 under the high byte 0x64 is the fp16 number 1024 + u
-            const uint32_t dz = mw[r][MW - 1];
-            const v2h off = {(_Float16)1152.0f, (_Float16)1152.0f};
-            const uint32_t w01 = __builtin_amdgcn_perm(0x64646464u, dz, G == 4 ? 0x04010400u : 0x04030402u);
-            z01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, w01) - off) & lane0_mask;
-            if constexpr (G == 4) {
-              const uint32_t w23 = __builtin_amdgcn_perm(0x64646464u, dz, 0x04030402u);
-              z23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, w23) - off) & lane0_mask;
-            }
-          } else {
-            z01 = __builtin_amdgcn_perm(mw[r][1], mw[r][0], 0x07060302u) & lane0_mask;
-            if constexpr (G == 4) z23 = __builtin_amdgcn_perm(mw[r][3], mw[r][2], 0x07060302u) & lane0_mask;
-          }
-          zB[r] = as_v4h(z01, z23);
+          for (int r = 0; r < 4; ++r) sA[r] = as_v4h((sw[r][0] ^ sm01) & keep_row, G == 4 ? (sw[r][1] ^ sm23) & keep_row : 0u);
         }
         // cross-block variant: the block's fp16 scale in both halves of a dword, and - (s z / 2) of
         // (token n, quantization block q), the A operand of the zero-point product
@@ -687,17 +720,15 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
             // below 1024: exact in fp16), fp32 accumulate
             const v4f z4 = {0.f, 0.f, 0.f, 0.f};
             v4f klo, khi;
-            v4f zc = z4;
             if constexpr (XB) {
               klo = xk_lo[r];
               khi = xk_hi[r];
             } else {
-            if (p == 0) zc = mfma_4x4x4(sA[r], zB[r], z4) * -64.0f;
             if constexpr (G == 4) {
-              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), zc);
+              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), z4);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), pk_f16(hi[2][r], hi[3][r])), z4);
             } else {
-              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), zc);
+              klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), z4);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), z4);
             }
             }
@@ -762,7 +793,11 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
           if constexpr (MULTI) masked = tok > s_lim[hq];
           if (sink_tiles & (1u << ti))
             for (int i = 0; i < cnt; ++i) masked |= (s_sink[i] == tok);
-          if (n < NR && !masked) s_sc[hq][tok - t0] = tot;
+          if constexpr (LM) {                              // onto the zero-points' share, put there when the metadata were staged
+            if (n < NR) s_sc[hq][tok - t0] = masked ? -INFINITY : tot + s_sc[hq][tok - t0];
+          } else {
+            if (n < NR && !masked) s_sc[hq][tok - t0] = tot;
+          }
         }
         }
       }
@@ -848,14 +883,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       for (int i = 0; i < MF_CH / 64; ++i) {
         float s_, z_;
         if constexpr (LM) {                                 // token lane + 64 i, head a
-          const uint32_t* mp = &s_vm[(lane + 64 * i) * MWL];
-          if constexpr (META8) {                            // G scale bytes, then G zero-point bytes
-            const uint32_t sw = mp[0], zw = G == 4 ? mp[1] : mp[0] >> 16;
-            s_ = rkv_e4m3_decode((sw >> (8 * a)) & 0xffu);
-            z_ = (float)((zw >> (8 * a)) & 0xffu) - 128.0f;
-          } else {
-            rkv_unpack_meta(mp[a], s_, z_);
-          }
+          rkv_unpack_meta(s_vm[(lane + 64 * i) * G + a], s_, z_);
         } else if constexpr (META8) {
           s_ = __builtin_amdgcn_cvt_f32_fp8((int)vmeta[sb][i], 0);
           z_ = (float)((vmeta[sb][i] >> 8) & 0xffu) - 128.0f;
@@ -992,42 +1020,47 @@ bool rkv_mfma_supported(const rkv_cache* c) {
   return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4);
 }
 
-#ifdef RKV_DEV_FEW_VARIANTS
-// developer builds: only the plain 2-bit variants of four-head rotation groups (quick to compile)
-template <bool MULTI>
-static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* qt, float* part, int nch, const int* q_lim,
-                          int nq, hipStream_t s) {
-  if (MULTI || v.g != 4 || v.hb || v.meta8) abort();
-  if (share == 1) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);
-  else hipLaunchKernelGGL((k_decode_mfma<4, 2, false, false, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);
-}
-#else
-template <bool MULTI>
-static void launch_kernel(const RkvView& v, int share, dim3 grid, const float* qt, float* part, int nch, const int* q_lim,
-                          int nq, hipStream_t s) {
-#define RKV_MF_LAUNCH(G_, R_)                                                                                              \
-  do {                                                                                                                   \
-    if (v.hb == 2) {                                                                                                       \
-      if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-      else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, 2>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-      break;                                                                                                               \
-    }                                                                                                                      \
-    if (v.hb == 1) {                                                                                                       \
-      if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, 1>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-      else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, 1>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-      break;                                                                                                               \
-    }                                                                                                                      \
-    if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, true, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq); \
-    else hipLaunchKernelGGL((k_decode_mfma<G_, R_, MULTI, false, 0>), grid, dim3(256), 0, s, v, qt, part, nch, q_lim, nq);  \
-  } while (0)
-  if (v.g == 4 && share == 1) RKV_MF_LAUNCH(4, 1);
-  else if (v.g == 4) RKV_MF_LAUNCH(4, 2);
-  else if (share == 1) RKV_MF_LAUNCH(2, 1);
-  else RKV_MF_LAUNCH(2, 2);
-#undef RKV_MF_LAUNCH
-}
+typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int);
 
+// The variant of the kernel a cache takes.  multi: several query tokens per sequence; share: query
+// heads of a KV head per workgroup (1 or 2); alu: the arithmetic-only measurement.
+static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool alu) {
+  const RkvView& v = c->v;
+#ifdef RKV_DEV_FEW_VARIANTS
+  // developer builds: only the plain 2-bit variants of four-head rotation groups (quick to compile)
+  if (multi || v.g != 4 || v.hb || v.meta8 || !c->blocks_aligned || v.qg != 128) abort();
+  if (alu) return k_decode_mfma<4, 1, false, false, 0, false, 0, true>;
+  return share == 1 ? k_decode_mfma<4, 1, false, false, 0> : k_decode_mfma<4, 2, false, false, 0>;
+#else
+  if (mfma_sub_groups(c)) {
+    const int sub = 128 / v.qg;
+    if (v.g == 4) return sub == 2 ? k_decode_mfma<4, 1, false, false, 0, true, 2> : k_decode_mfma<4, 1, false, false, 0, true, 4>;
+    return sub == 2 ? k_decode_mfma<2, 1, false, false, 0, true, 2> : k_decode_mfma<2, 1, false, false, 0, true, 4>;
+  }
+  if (mfma_cross_block(c)) {
+    if (v.g == 4) return v.meta8 ? k_decode_mfma<4, 1, false, true, 0, true> : k_decode_mfma<4, 1, false, false, 0, true>;
+    return v.meta8 ? k_decode_mfma<2, 1, false, true, 0, true> : k_decode_mfma<2, 1, false, false, 0, true>;
+  }
+  if (alu) return v.g == 4 ? k_decode_mfma<4, 1, false, false, 0, false, 0, true> : k_decode_mfma<2, 1, false, false, 0, false, 0, true>;
+#define RKV_MF_PICK(G_, R_, M_)                                                                            \
+  do {                                                                                                     \
+    if (v.hb == 2) return v.meta8 ? k_decode_mfma<G_, R_, M_, true, 2> : k_decode_mfma<G_, R_, M_, false, 2>; \
+    if (v.hb == 1) return v.meta8 ? k_decode_mfma<G_, R_, M_, true, 1> : k_decode_mfma<G_, R_, M_, false, 1>; \
+    return v.meta8 ? k_decode_mfma<G_, R_, M_, true, 0> : k_decode_mfma<G_, R_, M_, false, 0>;               \
+  } while (0)
+  if (multi) {
+    if (v.g == 4 && share == 1) RKV_MF_PICK(4, 1, true);
+    else if (v.g == 4) RKV_MF_PICK(4, 2, true);
+    else if (share == 1) RKV_MF_PICK(2, 1, true);
+    else RKV_MF_PICK(2, 2, true);
+  }
+  if (v.g == 4 && share == 1) RKV_MF_PICK(4, 1, false);
+  else if (v.g == 4) RKV_MF_PICK(4, 2, false);
+  else if (share == 1) RKV_MF_PICK(2, 1, false);
+  else RKV_MF_PICK(2, 2, false);
+#undef RKV_MF_PICK
 #endif
+}
 
 // nq == 0: the usual step, one query token that attends the whole cache (and, if set, the current
 // token's exact row).  nq >= 1: nq query tokens per sequence, token i at position q_pos[b][i] and
@@ -1050,7 +1083,6 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   float* qr = (float*)scratch;
   const size_t qbytes = rkv_query_scratch_bytes(v.B, v.Hq);
   float* part = (float*)((char*)scratch + qbytes);
-  const int nch = (v.len + MF_CH - 1) / MF_CH;
   const int rep = v.Hq / v.Hkv;
   const bool sg = mfma_sub_groups(c);
   const bool xb = mfma_cross_block(c) || sg;
@@ -1058,6 +1090,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   const int share = xb ? 1 : rkv_mfma_share(rep);           // and one query head per workgroup
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
+  const int nch = (v.len + MF_CH - 1) / MF_CH;
   dim3 grid(8 * ((v.B * v.NRG + 7) / 8) * nch * (rep / share), 1, 1);   // see the kernel for the mapping
   if (c->ragged) {                                          // all sequences' chunks in one dimension
     int total = 0;
@@ -1065,31 +1098,10 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
     grid = dim3(((total + 7) & ~7) * (rep / share), v.NRG, 1);
   }
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  if (nch == 0) {}                                          // an empty cache has only the current token
-#ifdef RKV_DEV_FEW_VARIANTS
-  else if (sg || xb) abort();
-#else
-  else if (sg) {
-    const int sub = 128 / v.qg;
-    if (v.g == 4 && sub == 2) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-    else if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true, 4>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-    else if (sub == 2) hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, true, 2>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-    else hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, true, 4>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-  }
-  else if (xb) {
-    if (v.g == 4 && v.meta8) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, true, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-    else if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-    else if (v.meta8) hipLaunchKernelGGL((k_decode_mfma<2, 1, false, true, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-    else hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-  }
-#endif
-  else if (c->decode_path == 3) {                           // arithmetic-only measurement
-    if (multi || v.hb || v.meta8 || share != 1) return RKV_EINVAL;
-    if (v.g == 4) hipLaunchKernelGGL((k_decode_mfma<4, 1, false, false, 0, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-    else hipLaunchKernelGGL((k_decode_mfma<2, 1, false, false, 0, false, 0, true>), grid, dim3(256), 0, s, v, qt, part, nch, nullptr, 1);
-  }
-  else if (multi) launch_kernel<true>(v, share, grid, qt, part, nch, q_pos, nq, s);
-  else launch_kernel<false>(v, share, grid, qt, part, nch, nullptr, 1, s);
+  if (c->decode_path == 3 && (multi || xb || v.hb || v.meta8 || share != 1)) return RKV_EINVAL;   // arithmetic-only measurement: plain variants
+  if (nch > 0)                                              // (an empty cache has only the current token)
+    hipLaunchKernelGGL(pick_kernel(c, multi, share, c->decode_path == 3), grid, dim3(256), 0, s, v, qt, part, nch,
+                       multi ? q_pos : nullptr, nq);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   rkv_launch_merge(v, qr, part, nch, MF_CH, c->cur_k, c->cur_v, multi ? q_pos : nullptr, nq, out, lse, s);
   return rkv_check_launch();
