@@ -189,7 +189,7 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false, int SUB = 0, bool ALU = false>
 __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF_OCC)) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
-                                                                       const int* __restrict__ q_lim, int nq) {
+                                                                       const int* __restrict__ q_lim, int nq, int ns, uint32_t inv_ns, uint32_t inv_nrg) {
   constexpr bool HI = HB != 0;
   constexpr int NH = G * REP;                    // query heads served by this workgroup: REP per KV head
   constexpr int RP = (MF_ACC / (G * REP) < 4) ? MF_ACC / (G * REP) : 4;   // tokens (of a lane's four) per pass of the key phase: MF_ACC score accumulators at most
@@ -242,28 +242,15 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
-  if constexpr (!ALIAS) {
-    uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
-    for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
-  }
-
-  // Hadamard operand tiles go to LDS once per workgroup; the key phase reads two of them per step
-  for (int i = tid; i < 8 * 64; i += 256) (&s_H[0][0])[i] = reinterpret_cast<const uint4*>(v.hop)[i];
-  // RoPE angles are kept for the first of a lane's four tokens only.  With one query head per KV
-  // head they rotate all four keys and the query comes rotated back by 0..3 positions to make up
-  // for it (k_prep_q); with several (REP > 1: the extra query copies would not fit the register
-  // budget) the other three tokens follow by rotating one position at a time (table row 1).  The
-  // next tile follows by rotating 16 positions (table row 16; used once per tile, read from LDS)
-  if (tid < 64) s_step[tid] = v.rope[(REP == 1 ? 16 : 12) * 64 + tid];
-  float s1_c[4], s1_s[4];
-  if constexpr (REP > 1) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const float2 s1 = v.rope[64 + 16 * p + n];
-      s1_c[p] = s1.x;
-      s1_s[p] = s1.y;
-    }
-  }
+  // Wave priority: the few instructions before the first barrier, and the short softmax and
+  // value phases at the end, go ahead of the key phases of the compute unit's other workgroups
+  // (which are dense vector work and fill every gap): a young wave otherwise waits behind them for
+  // each of its instructions, and its workgroup's place on the compute unit idles meanwhile.
+  __builtin_amdgcn_s_setprio(3);
+  // The arguments the first microsecond needs, asked for in one go (left to itself the compiler
+  // fetches each where it is first used, one scalar round trip after the other)
+  asm volatile("" ::"s"(v.kc), "s"(v.km), "s"(v.vc), "s"(v.vm), "s"(v.rope), "s"(v.hop), "s"(v.sink_pos), "s"(v.sink_cnt), "s"(v.lens),
+               "s"(qt), "s"(v.Tpad), "s"(v.NRG), "s"(v.B), "s"(v.len), "s"(v.max_sinks), "s"(nch), "s"(ns), "s"(inv_ns), "s"(inv_nrg));
   // row (n & 3) of H_g as fp16 sign masks for the packed scale pairs (blocks 0,1) and (2,3);
   // rows >= G are zero
   const int hrow = n & 3;
@@ -277,11 +264,15 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   // With per-sequence lengths the grid has no sequence dimension: the chunks of all sequences are
   // numbered consecutively (cstart[b] = chunks of the sequences before b), rounded up to 8 in all,
   // so that no workgroup is launched for chunks a shorter sequence does not have.
-  const int rep = v.Hq / v.Hkv;
+  // (ns = query-head groups of a KV head = rep / REP; the quotients below are taken with the
+  // reciprocals the host passes - inv = ceil(2^32 / d), 0 for d = 1 -: a scalar integer division
+  // is some thirty dependent instructions, several of them on the vector pipe that the compute
+  // unit's other workgroups keep busy, and there were five of them before the first request)
+  const int rep = ns * REP;
   int rg = blockIdx.y;
   int rrg, chunk, b;
   if (v.lens) {
-    const int tot8 = gridDim.x / (rep / REP);
+    const int tot8 = gridDim.x / ns;
     rrg = blockIdx.x / tot8;
     const int w = blockIdx.x - rrg * tot8;
     if (w >= v.cstart[v.B]) return;
@@ -299,69 +290,58 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
     // and runs all of its chunks, and for each chunk the workgroups of all query-head groups one
     // after the other.  What those workgroups share - the prepared queries, the sink list, and
     // with GQA the chunk's codes themselves - is then fetched into one L2 once.
-    const int xcd = blockIdx.x & 7, t = blockIdx.x >> 3, ns = rep / REP;
-    const int br8 = t / (nch * ns), rem = t - br8 * (nch * ns);
-    chunk = rem / ns;
+    // (grid: x = 8 * nch * ns, y = eighths of the (sequence, rotation group) pairs; x runs fastest)
+    const int xcd = blockIdx.x & 7, rem = blockIdx.x >> 3;
+    chunk = inv_ns ? (int)__umulhi((uint32_t)rem, inv_ns) : rem;
     rrg = rem - chunk * ns;
-    const int br = br8 * 8 + xcd;
+    const int br = blockIdx.y * 8 + xcd;
     if (br >= v.B * v.NRG) return;
-    b = br / v.NRG;
+    b = inv_nrg ? (int)__umulhi((uint32_t)br, inv_nrg) : br;
     rg = br - b * v.NRG;
   }
   const int len = rkv_len(v, b);
   if (chunk * MF_CH >= len) return;
   const int t0 = chunk * MF_CH;
-  const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
-  // the sink list (complete after the barrier that precedes the key phase); every wave clears
-  // its own 64 score slots
-  if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
-  if constexpr (!LM) {
+
+  // Everything the workgroup needs before its first tile is requested here, back to back, and put
+  // in LDS further down, once - a request that is waited for before the next one goes out costs a
+  // round trip to L2 or memory each, and the workgroup's place on the compute unit idles meanwhile
+  // (six such round trips were a quarter of a workgroup's life).
+  //  - Hadamard operand tiles (the key phase reads two of them per step)
+  const uint4 ld_h0 = reinterpret_cast<const uint4*>(v.hop)[tid], ld_h1 = reinterpret_cast<const uint4*>(v.hop)[tid + 256];
+  //  - queries of this rotation group, already RoPE'd, scaled and laid out as s_q by k_prep_q
+  constexpr int Q16 = QV * 16 * 4 * 2 * NH / 4;          // 16-byte pieces in all
+  constexpr int QN = (Q16 + 255) / 256;                  // per thread
+  const uint4* q_src = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * ns + rrg) * (4 * 16 * 4 * 2 * NH));
+  uint4 ld_q[QN];
 #pragma unroll
-    for (int a = 0; a < NH; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
+  for (int i = 0; i < QN; ++i) ld_q[i] = tid + 256 * i < Q16 ? q_src[tid + 256 * i] : make_uint4(0, 0, 0, 0);
+  //  - RoPE angles are kept for the first of a lane's four tokens only.  With one query head per KV
+  //    head they rotate all four keys and the query comes rotated back by 0..3 positions to make up
+  //    for it (k_prep_q); with several (REP > 1: the extra query copies would not fit the register
+  //    budget) the other three tokens follow by rotating one position at a time (table row 1).  The
+  //    next tile follows by rotating 16 positions (table row 16; used once per tile, read from LDS)
+  const float2 ld_step = v.rope[(REP == 1 ? 16 : 12) * 64 + (tid & 63)];
+  float s1_c[4], s1_s[4];
+  if constexpr (REP > 1) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const float2 s1 = v.rope[64 + 16 * p + n];
+      s1_c[p] = s1.x;
+      s1_s[p] = s1.y;
+    }
   }
-  if constexpr (MULTI) {
-    // served head a * REP + rri is virtual head rrg * REP + rri of its KV head: query token (that / heads per token)
-    if (tid < NH) s_lim[tid] = min(q_lim[b * nq + (rrg * REP + tid % REP) / (rep / nq)], len - 1);
-  }
-  if constexpr (XB) {                              // this rotation group's masks and zero-point table
-    for (int i = tid; i < G * NP * 4; i += 256) s_xmask[i] = reinterpret_cast<const uint4*>(v.xmask)[(size_t)rg * (G * NP * 4) + i];
-    for (int i = tid; i < 128 * XK * G; i += 256) s_xtt[i] = v.xtt[(size_t)rg * (128 * XK * G) + i];
-  }
-  // queries of this rotation group, already RoPE'd, scaled and laid out as s_q by k_prep_q
-  for (int i = tid; i < QV * 16 * 4 * 2 * NH / 4; i += 256)
-    (&s_q[0][0][0][0])[i] = reinterpret_cast<const uint4*>(qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (4 * 16 * 4 * 2 * NH))[i];
-  if constexpr (LM) {                              // thread = token of the chunk (inside the padded allocation)
+  //  - the sink list: positions unconditionally (the store holds max_sinks of them, unused ones -1), masked by the count below
+  const int ld_cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
+  const int ld_spos = (v.max_sinks > 0 && (tid & 63) < v.max_sinks) ? v.sink_pos[b * v.max_sinks + (tid & 63)] : -1;
+  //  - (plain variants) the metadata of token t0 + tid of keys and values, its RoPE angle for channel
+  //    pair 0 and the queries' entries for that pair: staged below
+  uint32_t ld_mk[4] = {0, 0, 0, 0}, ld_mv[4] = {0, 0, 0, 0};
+  float2 ld_cs0 = make_float2(0.f, 0.f);
+  float4 ld_q0[LM ? NH / 2 : 1];
+  if constexpr (LM) {
     const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * MWL;
-    // a token's metadata as stored -> packed fp16 pairs (s01, s23) and (z01, z23)
-    auto pairs = [&](const uint32_t* src, uint32_t (&sp)[2], uint32_t (&zp)[2]) {
-      sp[1] = zp[1] = 0;
-      if constexpr (ALU) {                               // scale 1, zero-point 0
-        sp[0] = sp[1] = 0x3C003C00u + (uint32_t)(nq - 1);
-        zp[0] = zp[1] = 0;
-      } else if constexpr (META8) {
-        // G scale bytes, then G zero-point bytes.  FP8 -> fp32 -> fp16 is exact; a zero-point byte
-        // u = z + 128 under the high byte 0x64 is the fp16 number 1024 + u
-        const uint32_t d0 = src[0], dz = G == 4 ? src[1] : src[0] >> 16;
-        const v2h off = {(_Float16)1152.0f, (_Float16)1152.0f};
-        const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8((int)d0, false);
-        sp[0] = pk_f16(f01[0], f01[1]);
-        zp[0] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, __builtin_amdgcn_perm(0x64646464u, dz, 0x04010400u)) - off);
-        if constexpr (G == 4) {
-          const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8((int)d0, true);
-          sp[1] = pk_f16(f23[0], f23[1]);
-          zp[1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, __builtin_amdgcn_perm(0x64646464u, dz, 0x04030402u)) - off);
-        }
-      } else {                                           // (scale, zero-point) fp16 pairs per block
-        sp[0] = __builtin_amdgcn_perm(src[1], src[0], 0x05040100u);
-        zp[0] = __builtin_amdgcn_perm(src[1], src[0], 0x07060302u);
-        if constexpr (G == 4) {
-          sp[1] = __builtin_amdgcn_perm(src[3], src[2], 0x05040100u);
-          zp[1] = __builtin_amdgcn_perm(src[3], src[2], 0x07060302u);
-        }
-      }
-    };
     auto fetch = [&](const uint32_t* g, uint32_t (&d)[4]) {
-      d[0] = d[1] = d[2] = d[3] = 0;
       if constexpr (ALU) return;
       if constexpr (MWL == 4) {
         const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(g));
@@ -373,50 +353,21 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
         d[0] = *g;
       }
     };
-    uint32_t dk[4], dv[4], sp[2], zp[2];
-    fetch(v.km + mi, dk);
-    fetch(v.vm + mi, dv);
-    pairs(dk, sp, zp);
+    fetch(v.km + mi, ld_mk);
+    fetch(v.vm + mi, ld_mv);
+    ld_cs0 = v.rope[(size_t)(t0 + tid) * 64];
+    // entry (r = 0, p = 0, n = 0) of the prepared queries: floats f % 4 of piece f / 4, f = 2 * head + half
 #pragma unroll
-    for (int i = 0; i < GP; ++i) s_ks[tid * GP + i] = sp[i];
-    {
-      // the zero-points' share of this token's scores (see above); -infinity past the sequence's end,
-      // which is what a slot the key phase never writes must hold
-      float sf[4], zf[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t sw = sp[i >> 1], zw = zp[i >> 1];
-        sf[i] = i < G ? (float)__builtin_bit_cast(_Float16, (uint16_t)(i & 1 ? sw >> 16 : sw & 0xffffu)) : 0.f;
-        zf[i] = i < G ? (float)__builtin_bit_cast(_Float16, (uint16_t)(i & 1 ? zw >> 16 : zw & 0xffffu)) : 0.f;
-      }
-      const float2 cs0 = v.rope[(size_t)(t0 + tid) * 64];
-      const float* q0 = qt + (((size_t)b * v.NRG + rg) * (rep / REP) + rrg) * (4 * 16 * 4 * 2 * NH);
-#pragma unroll
-      for (int a = 0; a < G; ++a) {
-        float Z = 0.f;
-#pragma unroll
-        for (int i = 0; i < G; ++i) Z = fmaf((__popc(a & i) & 1) ? -sf[i] : sf[i], zf[i], Z);
-#pragma unroll
-        for (int rri = 0; rri < REP; ++rri) {
-          const int f = (a * REP + rri) * 2;                 // entry (r = 0, p = 0, n = 0) of the prepared query: floats f, f + 1
-          const float ql = q0[(f >> 2) * 64 + (f & 3)], qh = q0[(f >> 2) * 64 + (f & 3) + 1];
-          s_sc[a * REP + rri][tid] = t0 + tid < len ? -64.0f * Z * fmaf(cs0.x, ql, cs0.y * qh) : -INFINITY;
-        }
-      }
-    }
-    if constexpr (META8 || ALU) {                      // values: (scale, zero-point) per head
-      pairs(dv, sp, zp);
-      s_vm[tid * G] = __builtin_amdgcn_perm(zp[0], sp[0], 0x05040100u);
-      s_vm[tid * G + 1] = __builtin_amdgcn_perm(zp[0], sp[0], 0x07060302u);
-      if constexpr (G == 4) {
-        s_vm[tid * G + 2] = __builtin_amdgcn_perm(zp[1], sp[1], 0x05040100u);
-        s_vm[tid * G + 3] = __builtin_amdgcn_perm(zp[1], sp[1], 0x07060302u);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < G; ++i) s_vm[tid * G + i] = dv[i];
-    }
+    for (int i = 0; i < NH / 2; ++i) ld_q0[i] = reinterpret_cast<const float4*>(q_src)[i * 16];
   }
+  //  - the RoPE angles of this lane's first token and the first key tile: in the key phase below
+  int ld_lim = 0;
+  if constexpr (MULTI) {
+    // served head a * REP + rri is virtual head rrg * REP + rri of its KV head: query token (that / heads per token)
+    ld_lim = q_lim[b * nq + (rrg * REP + (tid < NH ? tid : 0) % REP) / (rep / nq)];
+  }
+
+  const int cnt = ld_cnt;
   {
     // ------------------------------------------------------------------ phase K
     {
@@ -492,7 +443,105 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
         }
       };
       load_tile(0);
+      // (the requests are all out: what came back goes to LDS)
+      if constexpr (!ALIAS) {
+        uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
+        for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
+      }
+      (&s_H[0][0])[tid] = ld_h0;
+      (&s_H[0][0])[tid + 256] = ld_h1;
+    #pragma unroll
+      for (int i = 0; i < QN; ++i)
+      if (tid + 256 * i < Q16) (&s_q[0][0][0][0])[tid + 256 * i] = ld_q[i];
+      if (tid < 64) {
+        s_step[tid] = ld_step;
+        s_sink[tid] = tid < cnt ? ld_spos : -1;              // complete after the barrier that precedes the key phase
+      }
+      if constexpr (!LM) {                                   // every wave clears its own 64 score slots
+    #pragma unroll
+        for (int a = 0; a < NH; ++a) s_sc[a][wave * 64 + lane] = -INFINITY;
+      }
+      if constexpr (MULTI) {
+        if (tid < NH) s_lim[tid] = min(ld_lim, len - 1);
+      }
+      if constexpr (XB) {                              // this rotation group's masks and zero-point table
+        for (int i = tid; i < G * NP * 4; i += 256) s_xmask[i] = reinterpret_cast<const uint4*>(v.xmask)[(size_t)rg * (G * NP * 4) + i];
+        for (int i = tid; i < 128 * XK * G; i += 256) s_xtt[i] = v.xtt[(size_t)rg * (128 * XK * G) + i];
+      }
+      if constexpr (LM) {                              // thread = token of the chunk (inside the padded allocation)
+        // a token's metadata as stored -> packed fp16 pairs (s01, s23) and (z01, z23)
+        auto pairs = [&](const uint32_t* src, uint32_t (&sp)[2], uint32_t (&zp)[2]) {
+          sp[1] = zp[1] = 0;
+          if constexpr (ALU) {                               // scale 1, zero-point 0
+            sp[0] = sp[1] = 0x3C003C00u + (uint32_t)(nq - 1);
+            zp[0] = zp[1] = 0;
+          } else if constexpr (META8) {
+            // G scale bytes, then G zero-point bytes.  FP8 -> fp32 -> fp16 is exact; a zero-point byte
+            // u = z + 128 under the high byte 0x64 is the fp16 number 1024 + u
+            const uint32_t d0 = src[0], dz = G == 4 ? src[1] : src[0] >> 16;
+            const v2h off = {(_Float16)1152.0f, (_Float16)1152.0f};
+            const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8((int)d0, false);
+            sp[0] = pk_f16(f01[0], f01[1]);
+            zp[0] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, __builtin_amdgcn_perm(0x64646464u, dz, 0x04010400u)) - off);
+            if constexpr (G == 4) {
+              const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8((int)d0, true);
+              sp[1] = pk_f16(f23[0], f23[1]);
+              zp[1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2h, __builtin_amdgcn_perm(0x64646464u, dz, 0x04030402u)) - off);
+            }
+          } else {                                           // (scale, zero-point) fp16 pairs per block
+            sp[0] = __builtin_amdgcn_perm(src[1], src[0], 0x05040100u);
+            zp[0] = __builtin_amdgcn_perm(src[1], src[0], 0x07060302u);
+            if constexpr (G == 4) {
+              sp[1] = __builtin_amdgcn_perm(src[3], src[2], 0x05040100u);
+              zp[1] = __builtin_amdgcn_perm(src[3], src[2], 0x07060302u);
+            }
+          }
+        };
+        uint32_t sp[2], zp[2];
+        uint32_t (&dk)[4] = ld_mk, (&dv)[4] = ld_mv;
+        pairs(dk, sp, zp);
+    #pragma unroll
+        for (int i = 0; i < GP; ++i) s_ks[tid * GP + i] = sp[i];
+        {
+          // the zero-points' share of this token's scores (see above); -infinity past the sequence's end,
+          // which is what a slot the key phase never writes must hold
+          float sf[4], zf[4];
+    #pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uint32_t sw = sp[i >> 1], zw = zp[i >> 1];
+            sf[i] = i < G ? (float)__builtin_bit_cast(_Float16, (uint16_t)(i & 1 ? sw >> 16 : sw & 0xffffu)) : 0.f;
+            zf[i] = i < G ? (float)__builtin_bit_cast(_Float16, (uint16_t)(i & 1 ? zw >> 16 : zw & 0xffffu)) : 0.f;
+          }
+          const float2 cs0 = ld_cs0;
+    #pragma unroll
+          for (int a = 0; a < G; ++a) {
+            float Z = 0.f;
+    #pragma unroll
+            for (int i = 0; i < G; ++i) Z = fmaf((__popc(a & i) & 1) ? -sf[i] : sf[i], zf[i], Z);
+    #pragma unroll
+            for (int rri = 0; rri < REP; ++rri) {
+              const int f = (a * REP + rri) * 2;                 // entry (r = 0, p = 0, n = 0) of the prepared query: floats f, f + 1
+              const float4 q4 = ld_q0[f >> 2];
+              const float ql = (f & 3) ? q4.z : q4.x, qh = (f & 3) ? q4.w : q4.y;
+              s_sc[a * REP + rri][tid] = t0 + tid < len ? -64.0f * Z * fmaf(cs0.x, ql, cs0.y * qh) : -INFINITY;
+            }
+          }
+        }
+        if constexpr (META8 || ALU) {                      // values: (scale, zero-point) per head
+          pairs(dv, sp, zp);
+          s_vm[tid * G] = __builtin_amdgcn_perm(zp[0], sp[0], 0x05040100u);
+          s_vm[tid * G + 1] = __builtin_amdgcn_perm(zp[0], sp[0], 0x07060302u);
+          if constexpr (G == 4) {
+            s_vm[tid * G + 2] = __builtin_amdgcn_perm(zp[1], sp[1], 0x05040100u);
+            s_vm[tid * G + 3] = __builtin_amdgcn_perm(zp[1], sp[1], 0x07060302u);
+          }
+        } else {
+    #pragma unroll
+          for (int i = 0; i < G; ++i) s_vm[tid * G + i] = dv[i];
+        }
+      }
       __syncthreads();        // LDS copies of the Hadamard operand and the query are complete; first tile already in flight
+      __builtin_amdgcn_s_setprio(0);
       // which of the wave's tiles hold a retained sink token (a wave-uniform bit mask): the others
       // skip the comparison with the sink list
       uint32_t sink_tiles = 0;
@@ -802,6 +851,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
         }
       }
     }
+    __builtin_amdgcn_s_setprio(3);
     if constexpr (ALIAS) {                                   // the table's space becomes the digits' (see s_A_raw)
       __syncthreads();
       uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
@@ -1020,7 +1070,7 @@ bool rkv_mfma_supported(const rkv_cache* c) {
   return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4);
 }
 
-typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int);
+typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int, int, uint32_t, uint32_t);
 
 // The variant of the kernel a cache takes.  multi: several query tokens per sequence; share: query
 // heads of a KV head per workgroup (1 or 2); alu: the arithmetic-only measurement.
@@ -1091,17 +1141,21 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   const int nch = (v.len + MF_CH - 1) / MF_CH;
-  dim3 grid(8 * ((v.B * v.NRG + 7) / 8) * nch * (rep / share), 1, 1);   // see the kernel for the mapping
+  const int ns = rep / share;
+  // reciprocals for the kernel's index arithmetic: ceil(2^32 / d) gives exact quotients n / d for n * d < 2^32
+  auto recip = [](int d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };
+  dim3 grid(8 * nch * ns, (v.B * v.NRG + 7) / 8, 1);        // see the kernel for the mapping
   if (c->ragged) {                                          // all sequences' chunks in one dimension
     int total = 0;
     for (int b = 0; b < v.B; ++b) total += (c->hlens[b] + MF_CH - 1) / MF_CH;
-    grid = dim3(((total + 7) & ~7) * (rep / share), v.NRG, 1);
+    grid = dim3(((total + 7) & ~7) * ns, v.NRG, 1);
   }
+  if (grid.y > 65535) return RKV_EINVAL;
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (c->decode_path == 3 && (multi || xb || v.hb || v.meta8 || share != 1)) return RKV_EINVAL;   // arithmetic-only measurement: plain variants
   if (nch > 0)                                              // (an empty cache has only the current token)
     hipLaunchKernelGGL(pick_kernel(c, multi, share, c->decode_path == 3), grid, dim3(256), 0, s, v, qt, part, nch,
-                       multi ? q_pos : nullptr, nq);
+                       multi ? q_pos : nullptr, nq, ns, recip(ns), recip(v.NRG));
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   rkv_launch_merge(v, qr, part, nch, MF_CH, c->cur_k, c->cur_v, multi ? q_pos : nullptr, nq, out, lse, s);
   return rkv_check_launch();
