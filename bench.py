@@ -248,13 +248,25 @@ def main():
     achieved = launch_bytes / (avg_ms * 1e-3) / 1e9
 
     # measured HBM traffic of the decode kernel (rocprofv3 counters, calibrated; see profiles/)
+    # The counters are not read in this run: the figure is quoted from the tracked profile, and only if
+    # that profile was taken on the kernel sources that are in the tree now (their hash is in the file).
     traffic = None
+    traffic_source = None
     tfile = os.path.join(ROOT, "profiles", f"decode_{w.name}_hbm_traffic.md")
     default_run = (QB, QG, args.meta_format, NQ, args.path, args.perm_span) == (2, 128, 0, 1, 0, 128) and pre_lens is None   # what the counters were collected on
     if os.path.exists(tfile) and L == w.layers and default_run:
+        from paper_2501_16383_amd.build import source_hash
+        quoted, taken_at = None, None
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch:"):
-                traffic = float(line.split(":")[1])
+                quoted = float(line.split(":")[1])
+            if line.startswith("csrc_sha256:"):
+                taken_at = line.split(":")[1].strip()
+        now = source_hash()
+        traffic_source = {"file": os.path.relpath(tfile, ROOT), "csrc_sha256_of_profile": taken_at, "csrc_sha256_now": now,
+                          "match": taken_at == now}
+        if quoted is not None and taken_at == now:
+            traffic = quoted
 
     # sanity: finite outputs
     assert args.path == 3 or all(bool(torch.isfinite(o).all()) for o in outs)
@@ -262,7 +274,7 @@ def main():
     # the arithmetic-only ceiling of the decode kernel: the same launches with the cache stream replaced
     # by register values (rkv_set_decode_path 3), timed with the same events; plain configurations only
     alu_only_ms = None
-    if default_run and args.path == 0:
+    if default_run and args.path == 0 and w.n_q_heads == w.n_kv_heads:      # (one query head per KV head: the variant the measurement exists for)
         tmp = torch.empty_like(outs[0])
         reps = 3
         ev_a = [[(hip.event(), hip.event()) for _ in range(L)] for _ in range(reps)]
@@ -299,7 +311,7 @@ def main():
                    "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"
                                  if QG == 128 and args.path != 1 else "fp32 vector arithmetic and accumulation (general kernels)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms, "launches_timed": len(kern_ms),
+                     "traffic": traffic, "traffic_source": traffic_source, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms, "launches_timed": len(kern_ms),
                      "algorithmic_bytes_per_launch": launch_bytes, "bytes_per_kv_token": bytes_per_tok,
                      "alu_only_ms": alu_only_ms},
         "append_bulk": {"GB/s_best": bulk_bytes / (bulk_best * 1e-3) / 1e9, "GB/s_avg": bulk_bytes / (bulk_avg * 1e-3) / 1e9,

@@ -49,6 +49,19 @@ def _stamp(src: str, cflags) -> str:
     return h.hexdigest()
 
 
+def source_hash() -> str:
+    """SHA-256 over the kernel sources and headers (names and contents, in name order): what a
+    counter profile was taken on, so that a figure quoted from it can be tied to the code that runs."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(f for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+    for name in files + ["../../include/rkv.h"]:
+        h.update(os.path.basename(name).encode() + b"\0")
+        with open(os.path.join(CSRC, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def build_library(verbose: bool = False, incremental: bool = False) -> str:
     """One object per source file, compiled side by side (the decode kernel's many variants take most
     of the time), then linked into the shared library.  incremental: keep the objects under _build/
@@ -86,4 +99,7 @@ def build_library(verbose: bool = False, incremental: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True, incremental="--incremental" in sys.argv[1:]))
+    if "--source-hash" in sys.argv[1:]:
+        print(source_hash())
+    else:
+        print(build_library(verbose=True, incremental="--incremental" in sys.argv[1:]))

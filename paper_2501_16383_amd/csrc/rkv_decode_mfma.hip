@@ -31,6 +31,7 @@
 // softmax and value phases once per query head.  Everything else takes the general kernel.
 #include "rkv_internal.h"
 #include <cstdlib>
+#include <hip/hip_ext.h>
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -109,8 +110,54 @@ __device__ __forceinline__ float dpp_f(float x) {
 
 // Sum NV values over the 16 lanes of a row; lane n ends with the total of value n (NV = 16) or of
 // value n & 7 (NV = 8).
+// The first two steps of the sixteen-value case, written out: a step's lanes of the upper half keep
+// the upper values and those of the lower half the lower ones, which a DPP addition does in one
+// instruction per half when it is told to write only that half's banks of four lanes (the other
+// lanes keep what the destination holds) - two instructions per result where a select of what to
+// keep, a select of what to send and the addition take three.  The compiler does not look into
+// the text for the two idle cycles a DPP operand needs after a vector write of it, and it does not
+// know of them for the results either: hence the waits at both ends, and the order inside (every
+// register is read two or more instructions after it was written).
+__device__ __forceinline__ void row_transpose_reduce_16_to_4(const float (&v)[16], float (&k4)[4]) {
+  float a0, a1, a2, a3, a4, a5, a6, a7;
+  asm("s_nop 1\n\t"
+      "v_add_f32_dpp %4, %12, %12 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %5, %13, %13 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %6, %14, %14 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %7, %15, %15 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %8, %16, %16 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %9, %17, %17 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %10, %18, %18 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %11, %19, %19 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %4, %20, %20 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "v_add_f32_dpp %5, %21, %21 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "v_add_f32_dpp %6, %22, %22 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "v_add_f32_dpp %7, %23, %23 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "v_add_f32_dpp %8, %24, %24 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "v_add_f32_dpp %9, %25, %25 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "v_add_f32_dpp %10, %26, %26 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "v_add_f32_dpp %11, %27, %27 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "v_add_f32_dpp %0, %4, %4 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+      "v_add_f32_dpp %1, %5, %5 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+      "v_add_f32_dpp %2, %6, %6 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+      "v_add_f32_dpp %3, %7, %7 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+      "v_add_f32_dpp %0, %8, %8 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+      "v_add_f32_dpp %1, %9, %9 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+      "v_add_f32_dpp %2, %10, %10 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+      "v_add_f32_dpp %3, %11, %11 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+      "s_nop 1"
+      : "=&v"(k4[0]), "=&v"(k4[1]), "=&v"(k4[2]), "=&v"(k4[3]), "=&v"(a0), "=&v"(a1), "=&v"(a2), "=&v"(a3), "=&v"(a4), "=&v"(a5),
+        "=&v"(a6), "=&v"(a7)
+      : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]), "v"(v[8]), "v"(v[9]), "v"(v[10]),
+        "v"(v[11]), "v"(v[12]), "v"(v[13]), "v"(v[14]), "v"(v[15]));
+}
+
 template <int NV>
 __device__ __forceinline__ float row_transpose_reduce(float (&v)[NV], int n) {
+  float k4[4];
+  if constexpr (NV == 16) {
+    row_transpose_reduce_16_to_4(v, k4);
+  } else {
   float k8[8];
   if constexpr (NV == 16) {
     const bool hi = (n & 8) != 0;
@@ -123,7 +170,6 @@ __device__ __forceinline__ float row_transpose_reduce(float (&v)[NV], int n) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) k8[i] = v[i] + dpp_f<DPP_ROW_MIRROR>(v[i]);
   }
-  float k4[4];
   {
     const bool hi = (n & 4) != 0;
 #pragma unroll
@@ -131,6 +177,7 @@ __device__ __forceinline__ float row_transpose_reduce(float (&v)[NV], int n) {
       const float keep = hi ? k8[i + 4] : k8[i], send = hi ? k8[i] : k8[i + 4];
       k4[i] = keep + dpp_f<DPP_ROW_HALF_MIRROR>(send);
     }
+  }
   }
   float k2[2];
   {
@@ -889,7 +936,8 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
     uint4 vcodes[MF_CH / 32], vhcodes[HI ? MF_CH / 32 : 1];
 #pragma unroll
     for (int sl = 0; sl < MF_CH / 32; ++sl) {
-      vcodes[sl] = make_uint4(0, 0, 0, 0);
+      // (lanes without a head feed zeros to the products; slabs beyond the chunk's end are never used)
+      if constexpr (G < 4) vcodes[sl] = make_uint4(0, 0, 0, 0);
       if constexpr (ALU) {
         const uint32_t x = (uint32_t)lidx * 2654435761u ^ (uint32_t)(nq + sl);
         if (has_head && sl < nslab) vcodes[sl] = make_uint4(x, x * 3u, x * 5u, x * 7u);
@@ -1151,12 +1199,22 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
     grid = dim3(((total + 7) & ~7) * ns, v.NRG, 1);
   }
   if (grid.y > 65535) return RKV_EINVAL;
-  if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (c->decode_path == 3 && (multi || xb || v.hb || v.meta8 || share != 1)) return RKV_EINVAL;   // arithmetic-only measurement: plain variants
-  if (nch > 0)                                              // (an empty cache has only the current token)
-    hipLaunchKernelGGL(pick_kernel(c, multi, share, c->decode_path == 3), grid, dim3(256), 0, s, v, qt, part, nch,
-                       multi ? q_pos : nullptr, nq, ns, recip(ns), recip(v.NRG));
-  if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
+  // The measurement events, if set, are tied to the kernel's own dispatch (its begin and end time
+  // stamps): events recorded as separate commands before and after it also count the gaps between
+  // commands on the stream, some 4 us per launch.
+  const bool timed = c->ev_start && c->ev_stop;
+  if (nch > 0) {                                            // (an empty cache has only the current token)
+    if (timed)
+      hipExtLaunchKernelGGL(pick_kernel(c, multi, share, c->decode_path == 3), grid, dim3(256), 0, s, c->ev_start, c->ev_stop, 0, v,
+                            qt, part, nch, multi ? q_pos : nullptr, nq, ns, recip(ns), recip(v.NRG));
+    else
+      hipLaunchKernelGGL(pick_kernel(c, multi, share, c->decode_path == 3), grid, dim3(256), 0, s, v, qt, part, nch,
+                         multi ? q_pos : nullptr, nq, ns, recip(ns), recip(v.NRG));
+  } else if (timed) {
+    RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
+    RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
+  }
   rkv_launch_merge(v, qr, part, nch, MF_CH, c->cur_k, c->cur_v, multi ? q_pos : nullptr, nq, out, lse, s);
   return rkv_check_launch();
 }
