@@ -98,7 +98,7 @@ def main():
                     help="query tokens per sequence and step (above 1: that many tokens are appended, then read the cache in one multi-query call)")
     ap.add_argument("--meta-format", type=int, default=0, help="0: fp16 scale and zero-point (2.25 bits); 1: FP8 scale, INT8 zero-point (2.125 bits)")
     ap.add_argument("--bits", type=int, default=2, help="bits per code: 2, 3 or 4")
-    ap.add_argument("--quant-group", type=int, default=128, help="channels per quantization block: 128 (matrix-core kernels), 64 or 32 (general kernels)")
+    ap.add_argument("--quant-group", type=int, default=128, help="channels per quantization block: 128, or 64 / 32 (Table tab:quantgrani; sub-group variants of the matrix-core kernels with 2-bit codes and fp16 metadata, the general kernels otherwise)")
     ap.add_argument("--perm-span", type=int, default=128,
                     help="channels the reorder may move a channel within: 128 (a head), rot_heads*128 (a rotation group) or n_kv_heads*128 (the row, Alg. 1 as printed)")
     ap.add_argument("--ragged-min", type=float, default=1.0,
@@ -223,6 +223,9 @@ def main():
     for s in range(W):
         one_step(s)
     torch.cuda.synchronize()
+    # which kernels this configuration takes (RKV_KERNEL_* of the library)
+    KIND_NAMES = {1: "general", 2: "shuffle", 3: "matrix-core", 4: "matrix-core, cross-block variant", 5: "matrix-core, sub-group variant"}
+    kinds = (caches[0].decode_kernel(NQ if NQ > 1 else 0), caches[0].append_kernel())
     assert caches[0].length == T - K * NQ
     lens_now = caches[0].lengths
 
@@ -309,7 +312,8 @@ def main():
                    "storage": f"u{QB} codes + " + ("fp16 scale / fp16 zero" if MB == 4 else "FP8 E4M3 scale / INT8 zero") +
                               f" per {QG} ({QB + 8.0 * MB / QG:g} bits per element)",
                    "arithmetic": "fp4 and fp16 matrix products (exact), fp32 vector arithmetic and accumulation"
-                                 if QG == 128 and args.path != 1 else "fp32 vector arithmetic and accumulation (general kernels)"},
+                                 if kinds[0] != 1 else "fp32 vector arithmetic and accumulation (general kernel)",
+                   "decode_kernel": KIND_NAMES.get(kinds[0], str(kinds[0])), "append_kernel": KIND_NAMES.get(kinds[1], str(kinds[1]))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_source, "kernel": "decode (cache-streaming) kernel", "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms, "launches_timed": len(kern_ms),
                      "algorithmic_bytes_per_launch": launch_bytes, "bytes_per_kv_token": bytes_per_tok,

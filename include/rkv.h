@@ -58,10 +58,11 @@ typedef struct rkv_config {
   int32_t bits;         /* bits per code: 2 (the headline setting), 3 or 4 (Table tab:ablation). */
                         /* 3- and 4-bit codes in groups of 128 run on the matrix-core kernels    */
                         /* like 2-bit ones (the bits above the low two as a second plane);       */
-                        /* groups of 64 / 32 are written by the general append kernel (and read  */
-                        /* by a matrix-core variant with 2-bit codes and fp16 metadata), which   */
-                        /* means no keys_rotated, no rkv_quantize_append_ragged, no              */
-                        /* rkv_decode_attention_multi and a two-kernel rkv_decode_step           */
+                        /* groups of 64 / 32 have variants of the matrix-core kernels for 2-bit  */
+                        /* codes with fp16 metadata and a reorder inside the heads (other        */
+                        /* settings of those groups take the general kernels, which means no     */
+                        /* keys_rotated, no rkv_quantize_append_ragged and a two-kernel          */
+                        /* rkv_decode_step); rkv_decode_attention_multi needs groups of 128      */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
                         /* printed sorts the whole row).  The append kernel for a reorder across */
@@ -177,7 +178,8 @@ int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, 
  *   host_n_new      [batch] int32 in host memory, 0 <= host_n_new[b] <= n_new_max; read before the call returns
  *   dev_sink_mask   [batch][n_new_max] uint8 or NULL
  * Needs a configuration the matrix-core append kernel covers (reorder inside blocks of 128 - or,
- * with 2-bit codes, inside the rotation groups -, rot_heads 2 or 4, v_rotate 0, quant_group 128),
+ * with 2-bit codes, inside the rotation groups -, rot_heads 2 or 4, v_rotate 0; quant_group 64 or
+ * 32 only with 2-bit codes, fp16 metadata and a reorder inside blocks of 128),
  * else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
  * max_tokens (nothing is appended then).  rkv_import_codes returns RKV_ESTATE on such a cache;
  * the export and dequantize views cover rkv_cache_length tokens for every sequence, and what they
@@ -273,7 +275,7 @@ int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 #define RKV_KERNEL_SHUFFLE    2  /* append only: FWHT in registers (v_rotate = 1, reorder in blocks)  */
 #define RKV_KERNEL_MFMA       3  /* matrix-core kernels: reorder inside blocks of 128, rot_heads 2, 4 */
 #define RKV_KERNEL_MFMA_CROSS 4  /* their variant for a reorder across blocks inside rotation groups  */
-#define RKV_KERNEL_MFMA_SUB   5  /* decode only: their variant for quant_group 64 / 32                */
+#define RKV_KERNEL_MFMA_SUB   5  /* their variant for quant_group 64 / 32                             */
 int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries);
 int rkv_append_kernel_of(const rkv_cache* cache);
 

@@ -41,7 +41,8 @@ static int check_config(const rkv_config* c, bool need_capacity) {
   if (c->head_dim != RKV_D) return RKV_EINVAL;
   if (c->quant_group != 128 && c->quant_group != 64 && c->quant_group != 32) return RKV_EINVAL;
   if (c->bits < 2 || c->bits > 4) return RKV_EINVAL;
-  if (c->quant_group != 128 && c->keys_rotated) return RKV_EINVAL;   // a path of the matrix-core append kernel
+  // (keys_rotated is a path of the matrix-core append kernel, which takes groups of 64 / 32 with 2-bit codes and fp16 metadata)
+  if (c->quant_group != 128 && c->keys_rotated && (c->bits != 2 || c->meta_format != 0)) return RKV_EINVAL;
   if (c->clip_ratio != 1.0f) return RKV_EINVAL;
   if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads != 0) return RKV_EINVAL;
   if (c->n_q_heads / c->n_kv_heads > 8) return RKV_EINVAL;
@@ -138,9 +139,11 @@ static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int 
       const int pass = subs ? (pos & 127) / qg : pos >> 7;
       const int k = subs ? blk * sub_n + pass : pass;        // quantization block within the group
       xmask[((((size_t)rg * g + blk) * np + pass) * 4 + q) * 4 + vreg] |= 0xFu << (4 * e);
-      if (cross) {
+      {
+        // the append kernel's table: per (wave, lane group, rotated block) 2 bits for each of a lane's 8
+        // channels - the quantization block within the group, or the sub-block within the head
         const int w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);   // 2 (wave & 1) + (wave >> 1) = w8
-        xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)k << (2 * (kap & 7));
+        xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)pass << (2 * (kap & 7));
       }
       for (int i = 0; i < n; ++i) {                          // output channel i = 128 a + j of H_n (entries (-1)^popcount(i & c))
         const float sgn = (__builtin_popcount((unsigned)(i & c)) & 1) ? -1.f : 1.f;
@@ -150,7 +153,7 @@ static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int 
   }
   RKV_HIP_CHECK(hipMemcpyAsync(v.xmask, xmask.data(), xmask.size() * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipMemcpyAsync(v.xtt, xtt.data(), xtt.size() * 4, hipMemcpyHostToDevice, s));
-  if (cross) RKV_HIP_CHECK(hipMemcpyAsync(v.xgsel, xgsel.data(), xgsel.size() * 4, hipMemcpyHostToDevice, s));
+  RKV_HIP_CHECK(hipMemcpyAsync(v.xgsel, xgsel.data(), xgsel.size() * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipStreamSynchronize(s));                    // the vectors go out of scope
   return RKV_OK;
 }
@@ -378,7 +381,7 @@ RKV_EXPORT int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries) {
 RKV_EXPORT int rkv_append_kernel_of(const rkv_cache* cache) {
   if (!cache) return RKV_EINVAL;
   const RkvView& v = cache->v;
-  if (rkv_append_mfma_supported(cache)) return cache->blocks_aligned ? RKV_KERNEL_MFMA : RKV_KERNEL_MFMA_CROSS;
+  if (rkv_append_mfma_supported(cache)) return v.qg != 128 ? RKV_KERNEL_MFMA_SUB : cache->blocks_aligned ? RKV_KERNEL_MFMA : RKV_KERNEL_MFMA_CROSS;
   if (cache->blocks_aligned && !cache->wide && (v.g == 2 || v.g == 4)) return RKV_KERNEL_SHUFFLE;
   return RKV_KERNEL_GENERAL;
 }
@@ -564,8 +567,8 @@ RKV_EXPORT int rkv_decode_step(rkv_cache* cache, const void* dev_k, const void* 
     return rc != RKV_OK ? rc : rkv_decode_attention(cache, dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, stream);
   }
   hipStream_t s = (hipStream_t)stream;
-  // (the cross-block variant of the decode kernel takes one query head per workgroup)
-  const int share = cache->blocks_aligned ? rkv_mfma_share(cache->v.Hq / cache->v.Hkv) : 1;
+  // (the cross-block and sub-group variants of the decode kernel take one query head per workgroup)
+  const int share = rkv_mfma_variant(cache) == RKV_KERNEL_MFMA ? rkv_mfma_share(cache->v.Hq / cache->v.Hkv) : 1;
   int rc = rkv_launch_step_mfma(cache, (const __half*)dev_k, (const __half*)dev_v, (const __half*)dev_q, dev_q_pos,
                                 (float*)dev_scratch, share, s);
   if (rc == RKV_OK && cache->ragged) rc = rkv_launch_lens(cache, -1, 1, s);

@@ -49,6 +49,10 @@ __device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {
   asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
   return r;
 }
+// float minimum / maximum into LDS (ds_min_f32, ds_max_f32; nothing is returned)
+typedef __attribute__((address_space(3))) float lds_float;
+__device__ __forceinline__ void lds_fmin(float* p, float x) { __builtin_amdgcn_ds_fminf((lds_float*)p, x, 0, 0, false); }
+__device__ __forceinline__ void lds_fmax(float* p, float x) { __builtin_amdgcn_ds_fmaxf((lds_float*)p, x, 0, 0, false); }
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, true);
@@ -109,7 +113,15 @@ __device__ __forceinline__ void fused_round_consts(float zero, float& base, floa
 // quantization block is looked up (gid), the minima and maxima are kept per quantization block,
 // and every element takes the parameters of its own block.  Codes stay where they are - by
 // rotated channel - so only the key role differs.
-template <int G, int HB, bool XW = false>
+// SUB = 2 or 4: quantization groups of 64 or 32 channels (2-bit codes, fp16 metadata, reorder
+// inside the heads): a rotated 128-block holds SUB quantization blocks, block head * SUB + sub of
+// the rotation group, and a rotated channel's sub-block follows from its reordered position (the
+// same per-cache table, 2 bits per channel).  Keys: the minima and maxima of a token's G * SUB
+// blocks are gathered with LDS float atomics (every element goes to its own block's pair), one
+// thread per (token, block) then works out the parameters and leaves them in LDS, where every
+// element fetches its block's.  Values are not reordered: a sub-block is 128 / SUB consecutive
+// channels of a head, so the lane-exchange reduction simply stops earlier.
+template <int G, int HB, bool XW = false, int SUB = 0>
 __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                  int n_new, int slab0, int bx, int rg, int b) {
   constexpr int PL = 2 * G;                    // value channels per lane
@@ -127,8 +139,17 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   uint32_t* imgh = lds + (PL == 8 ? 2048 : 1024);          // the upper plane's images: after 2 x 128 G (keys) or 4 x 64 PL (values) dwords
   constexpr bool HI = HB == 2, H1 = HB == 1;
   constexpr float QMAX = HI ? 15.0f : (H1 ? 7.0f : 3.0f), INV_QMAX = HI ? 0.06666667f : (H1 ? 0.14285715f : 0.33333334f);
-  __shared__ uint32_t meta[32 * G];
-  __shared__ float2 s_mm[2][2][16][G];         // [dword half][product pair][token][head] (min, max) of a quarter block
+  constexpr int NSB = SUB ? SUB : 1, GM = G * NSB;      // quantization blocks per 128-block, per rotation group
+  static_assert(SUB == 0 || (HB == 0 && !XW), "groups of 64 / 32: 2-bit codes, reorder inside the heads");
+  __shared__ uint32_t meta[32 * GM];
+  __shared__ float2 s_mm[SUB ? 1 : 2][SUB ? 1 : 2][SUB ? 1 : 16][SUB ? 1 : G];   // [dword half][product pair][token][head] (min, max) of a quarter block
+  // groups of 64 / 32: extrema of the tile [lane group q][token][block] (a copy per lane group, so
+  // that the four lanes of a token never meet on one word; rows padded to an odd length, so that the
+  // 64 lanes of an instruction spread over the banks) and [token][block] (reciprocal scale, constant
+  // added, base) of Eq. 6
+  constexpr int GMP = GM + 1;
+  __shared__ float s_mn[SUB ? 64 * GMP : 1], s_mx[SUB ? 64 * GMP : 1];
+  __shared__ float4 s_par[SUB ? 16 * GMP : 1];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: everything that depends only on it stays scalar
   const int role = bx % 3;                     // 0, 1: the keys of K tile 0 / 1 of a slab; 2: the slab's values
@@ -140,7 +161,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   const int ts = slab * 32;
   if (ts >= t_hi || n_b <= 0) return;                 // the grid covers the longest append: nothing here for this sequence
   const int tau_first = max(0, t_lo - ts), tau_last = min(31, t_hi - 1 - ts);
-  const size_t mrow = ((size_t)(b * v.NRG + rg) * v.Tpad + ts) * G;     // metadata row of the slab's first token
+  const size_t mrow = ((size_t)(b * v.NRG + rg) * v.Tpad + ts) * GM;    // metadata row of the slab's first token
 
   if (role < 2) {
     // ================================================================== keys of one tile
@@ -164,6 +185,13 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       for (int k = 0; k < 4 / TPI; ++k) {
         const int m = 4 * wave + TPI * k + lane / ROW16;
         reinterpret_cast<uint4*>(lds)[m * STRIDE16 + lane % ROW16] = st[k];
+      }
+    }
+    if constexpr (SUB != 0) {
+      static_assert(16 * GM <= 256, "one thread per (token, block) of a tile");
+      for (int i = tid; i < 64 * GMP; i += 256) {
+        s_mn[i] = 3.0e38f;
+        s_mx[i] = -3.0e38f;
       }
     }
     __syncthreads();
@@ -228,7 +256,20 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     }
     // cross-block variant: quantization block (within the group) of each of the lane's channels, 2 bits each
     uint32_t gsel[G];
-    if constexpr (XW) {
+    if constexpr (SUB != 0) {
+#pragma unroll
+      for (int h = 0; h < G; ++h) gsel[h] = v.xgsel[(((size_t)rg * 4 + wave) * 4 + q) * G + h];   // sub-block of each channel
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const int blk = (q * 16 + col) * GMP + h * SUB + (int)((gsel[h] >> (2 * (4 * ppl + rr))) & 3u);
+            lds_fmin(&s_mn[blk], acc[h][ppl][rr]);
+            lds_fmax(&s_mx[blk], acc[h][ppl][rr]);
+          }
+    } else if constexpr (XW) {
 #pragma unroll
       for (int h = 0; h < G; ++h) gsel[h] = v.xgsel[(((size_t)rg * 4 + wave) * 4 + q) * G + h];   // written by rkv_set_perm
 #pragma unroll
@@ -266,7 +307,37 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       }
     }
     __syncthreads();
-    {
+    if constexpr (SUB != 0) {
+      // Eq. 8-9 per (token, block), one thread each; Eq. 6 with each element's own block's parameters
+      if (tid < 16 * GM) {
+        const int tk = tid / GM, bk = tid - tk * GM;
+        float mn = s_mn[tk * GMP + bk], mx = s_mx[tk * GMP + bk];
+#pragma unroll
+        for (int qq = 1; qq < 4; ++qq) {
+          mn = fminf(mn, s_mn[(qq * 16 + tk) * GMP + bk]);
+          mx = fmaxf(mx, s_mx[(qq * 16 + tk) * GMP + bk]);
+        }
+        float sc, zero_b, inv, base_b, add_b;
+        quant_params_nodiv(mn * rs, mx * rs, sc, zero_b, inv, false, INV_QMAX);
+        fused_round_consts(zero_b, base_b, add_b);
+        s_par[tk * GMP + bk] = make_float4(inv * rs, add_b, base_b, 0.f);
+        meta[tid] = rkv_pack_meta(sc, zero_b);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int a = 0; a < G; ++a) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const float4 pr = s_par[col * GMP + a * SUB + (int)((gsel[a] >> (2 * (4 * ppl + rr))) & 3u)];
+            const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + 3.0f);
+            word += (__float_as_uint(c) - __float_as_uint(pr.z)) << (16 * ppl + 4 * rr);
+          }
+        img[pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = word << (2 * pph);
+      }
+    } else {
       // Eq. 6-9 on y = (raw rotation) / sqrt(n): min and max scale exactly (rounding is monotone),
       // the elements take the factor inside the reciprocal scale.  Lane group q works out the
       // parameters of head q & (G-1) for its token; the others fetch them with lane exchanges.
@@ -361,9 +432,9 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         }
       }
     }
-    for (int i = tid; i < 16 * G; i += 256) {
-      const int tau = 16 * ti + i / G;
-      if (tau >= tau_first && tau <= tau_last) rkv_store_meta_word(v, v.km, mrow + 16 * ti * G + i, meta[i]);
+    for (int i = tid; i < 16 * GM; i += 256) {
+      const int tau = 16 * ti + i / GM;
+      if (tau >= tau_first && tau <= tau_last) rkv_store_meta_word(v, v.km, mrow + 16 * ti * GM + i, meta[i]);
     }
     return;
   }
@@ -419,7 +490,9 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   }
   // min and max of a block travel together as one packed pair (min, -max), so that one packed
   // fp16 minimum per step reduces both (fp16 min/max of fp16 inputs is exact)
-  const int blk = lane / LPB;                              // 128-block (= KV head) of this lane's channels
+  constexpr int LPS = LPB / NSB;                           // lanes per quantization block
+  static_assert(LPS >= 4, "a quantization block spans at least four lanes");
+  const int blk = lane / LPS;                              // quantization block (KV head, or a sub-block of it) of this lane's channels
   uint32_t mm[8];
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
@@ -434,22 +507,26 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     uint32_t p = __builtin_amdgcn_perm(hi, lo, 0x05040100u) ^ 0x80000000u;   // (min, -max)
     p = pk_min(p, dpp_u<0xB1>(p));                                        // quad_perm [1,0,3,2]
     p = pk_min(p, dpp_u<0x4E>(p));                                        // quad_perm [2,3,0,1]
-    p = pk_min(p, dpp_u<0x141>(p));                                       // row_half_mirror
-    p = pk_min(p, dpp_u<0x140>(p));                                       // row_mirror
-    if constexpr (LPB == 32) p = pk_min(p, (uint32_t)__shfl_xor((int)p, 16));
+    if constexpr (LPS >= 8) p = pk_min(p, dpp_u<0x141>(p));               // row_half_mirror
+    if constexpr (LPS >= 16) p = pk_min(p, dpp_u<0x140>(p));              // row_mirror
+    if constexpr (LPS == 32) p = pk_min(p, (uint32_t)__shfl_xor((int)p, 16));
     mm[k] = p;
   }
-  // lane k of every block works out the parameters of token 8 wave + k; the others fetch them
-  uint32_t mine = mm[0];
+  // lane j of every block works out the parameters of token 8 wave + j (blocks of four lanes: of
+  // tokens j and j + 4, in two rounds); the others fetch them
+  constexpr int NRND = LPS >= 8 ? 1 : 8 / LPS, TPR = 8 / NRND;   // rounds, tokens per round
+  float inv_v[NRND], base_v[NRND], add_v[NRND];
 #pragma unroll
-  for (int k = 1; k < 8; ++k) mine = ((lane & (LPB - 1)) == k) ? mm[k] : mine;
-  float sc_v, zero_v, inv_v, base_v, add_v;
-  {
+  for (int r = 0; r < NRND; ++r) {
+    uint32_t mine = mm[TPR * r];
+#pragma unroll
+    for (int k = 1; k < TPR; ++k) mine = ((lane & (LPS - 1)) == k) ? mm[TPR * r + k] : mine;
+    float sc_v, zero_v;
     const h2 pr = as_h2(mine);
-    quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v, v.meta8, INV_QMAX);
-    fused_round_consts(zero_v, base_v, add_v);
-    const int tau = 8 * wave + (lane & (LPB - 1));
-    if ((lane & (LPB - 1)) < 8) meta[tau * G + blk] = rkv_pack_meta(sc_v, zero_v);
+    quant_params_nodiv((float)pr[0], -(float)pr[1], sc_v, zero_v, inv_v[r], v.meta8, INV_QMAX);
+    fused_round_consts(zero_v, base_v[r], add_v[r]);
+    const int tau = 8 * wave + TPR * r + (lane & (LPS - 1));
+    if ((lane & (LPS - 1)) < TPR) meta[tau * GM + blk] = rkv_pack_meta(sc_v, zero_v);
   }
   uint32_t vword[PL], vwordh[HB ? PL : 1];
 #pragma unroll
@@ -463,8 +540,8 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   for (int k = 0; k < 8; ++k) {
     const int tau = 8 * wave + k;
     if (tau < tau_first || tau > tau_last) continue;       // wave-uniform
-    const int src4 = 4 * ((lane & ~(LPB - 1)) | k);
-    const float inv = lane_read(inv_v, src4), add = lane_read(add_v, src4), base = lane_read(base_v, src4);
+    const int src4 = 4 * ((lane & ~(LPS - 1)) | (k % TPR));
+    const float inv = lane_read(inv_v[k / TPR], src4), add = lane_read(add_v[k / TPR], src4), base = lane_read(base_v[k / TPR], src4);
     const float top = base + QMAX;
     const int sh = rkv_v_shift(tau);
 #pragma unroll
@@ -517,16 +594,16 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       }
     }
   }
-  for (int i = tid; i < 32 * G; i += 256) {
-    const int tau = i / G;
+  for (int i = tid; i < 32 * GM; i += 256) {
+    const int tau = i / GM;
     if (tau >= tau_first && tau <= tau_last) rkv_store_meta_word(v, v.vm, mrow + i, meta[i]);
   }
 }
 
-template <int G, int HB, bool XW = false>
-__global__ void __launch_bounds__(256, (HB || XW) ? 4 : 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
+template <int G, int HB, bool XW = false, int SUB = 0>
+__global__ void __launch_bounds__(256, (HB || XW || SUB) ? 4 : 6) k_append_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                                       int n_new, int slab0) {
-  append_mfma_body<G, HB, XW>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+  append_mfma_body<G, HB, XW, SUB>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // One decode step's write half and query preparation in one launch: the first 3 * n_slabs
@@ -534,12 +611,12 @@ __global__ void __launch_bounds__(256, (HB || XW) ? 4 : 6) k_append_mfma(RkvView
 // rest prepare that rotation group's query heads (two heads per workgroup) for the decode kernel,
 // which saves a launch of its own for a few microseconds of work.  The query's default position
 // is the appended token's: one past the last token the view knows of.
-template <int G, int HB, bool XW = false>
+template <int G, int HB, bool XW = false, int SUB = 0>
 __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* __restrict__ kin, const __half* __restrict__ vin,
                                                    int slab0, int n_append_blocks, const __half* __restrict__ q,
                                                    const int* __restrict__ q_pos, float* __restrict__ qr, int share) {
   if ((int)blockIdx.x < n_append_blocks) {
-    append_mfma_body<G, HB, XW>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
+    append_mfma_body<G, HB, XW, SUB>(v, kin, vin, 1, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
     return;
   }
   const int rep = v.Hq / v.Hkv;
@@ -552,7 +629,9 @@ bool rkv_append_mfma_supported(const rkv_cache* c) {
   // 2-bit codes, or wider ones (a second plane), in groups of 128; a reorder across 128-blocks
   // inside the rotation groups with 2-bit codes
   if (!c->blocks_aligned && !(c->in_groups && v.hb == 0 && !c->cfg.keys_rotated)) return false;
-  return v.qg == 128 && (v.g == 2 || v.g == 4) && v.v_rotate == 0;
+  // groups of 64 / 32: 2-bit codes, fp16 metadata, a reorder inside the heads
+  if (v.qg != 128 && !(c->blocks_aligned && v.hb == 0 && !v.meta8)) return false;
+  return (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 
 // max_slabs: most 32-token slabs any sequence's new tokens touch, or 0 to work it out for n_new
@@ -571,7 +650,13 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   }
   dim3 grid(3 * max_slabs, v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  if (!c->blocks_aligned) {
+  if (v.qg == 64) {
+    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    else hipLaunchKernelGGL((k_append_mfma<2, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  } else if (v.qg == 32) {
+    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0, false, 4>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+    else hipLaunchKernelGGL((k_append_mfma<2, 0, false, 4>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  } else if (!c->blocks_aligned) {
     if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
     else hipLaunchKernelGGL((k_append_mfma<2, 0, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   } else if (v.hb == 2) {
@@ -594,7 +679,13 @@ int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const 
   int max_slabs = 1;                                        // one token touches one slab of its sequence
   const int n_append = 3 * max_slabs, rep = v.Hq / v.Hkv;
   dim3 grid(n_append + v.g * rep / 2, v.NRG, v.B);
-  if (!c->blocks_aligned) {
+  if (v.qg == 64) {
+    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+    else hipLaunchKernelGGL((k_step_mfma<2, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  } else if (v.qg == 32) {
+    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0, false, 4>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+    else hipLaunchKernelGGL((k_step_mfma<2, 0, false, 4>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+  } else if (!c->blocks_aligned) {
     if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
     else hipLaunchKernelGGL((k_step_mfma<2, 0, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
   } else if (v.hb == 2) {

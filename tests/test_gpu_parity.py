@@ -680,15 +680,16 @@ def test_fold_rotation_matches_oracle():
         assert err <= 2e-6 * np.abs(ref).max()
 
 
-@pytest.mark.parametrize("g,bits", [(4, 2), (2, 2), (4, 4), (2, 3)])
-def test_rotated_keys_path(g, bits):
+@pytest.mark.parametrize("g,bits,group", [(4, 2, 128), (2, 2, 128), (4, 4, 128), (2, 3, 128), (4, 2, 64), (2, 2, 32), (4, 2, 32)])
+def test_rotated_keys_path(g, bits, group):
     """The deployment shape of Sec. 4.2: keys arrive already rotated and reordered (folded weights),
     the write half only quantizes and packs.  Codes under the tie protocol (the input is exact, so
     only exact ties of Eq. 6 remain), sink rows brought back to the original basis (fp32 on the
     GPU, float64 in the oracle: equal up to one fp16 ulp at rounding ties), decode on both paths."""
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     T = 150
-    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=T, max_sinks=4, rot_heads=g, keys_rotated=1, bits=bits)
+    cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=T, max_sinks=4, rot_heads=g, keys_rotated=1, bits=bits,
+                      quant_group=group)
     ocfg = P.oracle_cfg(cfg)
     rng = np.random.default_rng(32)
     perm = np.concatenate([128 * blk + rng.permutation(128) for blk in range(cfg.E // 128)]).astype(np.int32)
@@ -698,6 +699,7 @@ def test_rotated_keys_path(g, bits):
     k_rot = k_rot.reshape(k.shape)
     cache = R.RkvCache(cfg)
     cache.set_perm(P.gpu(perm))
+    assert cache.append_kernel() == (RB.KERNEL_MFMA if group == 128 else RB.KERNEL_MFMA_SUB)
     oc = O.cache_new(ocfg, perm)
     for a, b in ((0, 70), (70, 71), (71, T)):
         print(f"[case] rotated keys g={g}: append {a}:{b}", flush=True)
@@ -705,7 +707,10 @@ def test_rotated_keys_path(g, bits):
         O.quantize_append(oc, k_rot[:, a:b], v[:, a:b], mask[:, a:b], keys_rotated=True)
     torch.cuda.synchronize()
     gexp, sk, sv = P.check_cache_against_oracle(cache, oc, f"rotated keys g={g}")
-    assert sk["mismatched_scales"] == 0
+    # (Eq. 8's division by 3 is a multiplication by the rounded reciprocal on the GPU: within 2^-23 of an
+    # fp16 rounding boundary the stored scale may differ by one ulp, which the protocol allows in the
+    # blocks it marks ambiguous; with four times the blocks, groups of 32 meet a couple of those)
+    assert sk["mismatched_scales"] <= (0 if group == 128 else min(4, sk["ambiguous_groups"]))
     s = {kk: vv.cpu().numpy() for kk, vv in cache.export_sinks().items()}
     for b in range(2):
         assert s["count"][b] == len(oc.sink_pos[b])
@@ -934,9 +939,10 @@ def test_shared_scratch_reused_across_caches():
             assert torch.equal(out, refs[i]), f"repetition {rep}, cache {i}"
 
 
-@pytest.mark.parametrize("bits", [2, 3, 4])
-def test_sequences_of_different_lengths(bits):
-    """(With 2-bit codes and with 3- and 4-bit codes, which the matrix-core kernels read as two planes.)
+@pytest.mark.parametrize("bits,group", [(2, 128), (3, 128), (4, 128), (2, 64), (2, 32)])
+def test_sequences_of_different_lengths(bits, group):
+    """(With 2-bit codes and with 3- and 4-bit codes, which the matrix-core kernels read as two planes;
+    with 2-bit codes in groups of 64 and 32, which take their sub-group variants.)
     rkv_quantize_append_ragged: three sequences are prefilled with 300 / 37 / 513 tokens in one
     call, extended by 5 / 0 / 40 in a second, then take three ordinary single-token steps.  Each
     sequence is compared with an oracle cache of its own (batch 1): codes under the tie protocol,
@@ -945,7 +951,7 @@ def test_sequences_of_different_lengths(bits):
     query tokens per step."""
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     B = 3
-    cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=600, max_sinks=4, rot_heads=4, bits=bits)
+    cfg = R.RkvConfig(batch=B, n_q_heads=8, n_kv_heads=8, max_tokens=600, max_sinks=4, rot_heads=4, bits=bits, quant_group=group)
     steps = [[300, 37, 513], [5, 0, 40], [1, 1, 1], [1, 1, 1], [1, 1, 1]]
     total = [sum(st[b] for st in steps) for b in range(B)]
     # (with 2-bit codes the sequences keep their fp16 sink rows; the wider codes run on the compressed stream alone)
@@ -978,9 +984,9 @@ def test_sequences_of_different_lengths(bits):
     for b in range(B):
         gb = {name: arr[b:b + 1, :total[b]] for name, arr in g.items()}
         P.compare_codes(ocs[b].k_rot, ocs[b].k_codes, ocs[b].k_scale, ocs[b].k_zero, gb["k_codes"], gb["k_scale"], gb["k_zero"],
-                        f"ragged b={b} K", rot_span=512, bits=bits)
+                        f"ragged b={b} K", rot_span=512, bits=bits, group=group)
         P.compare_codes(ocs[b].v_in, ocs[b].v_codes, ocs[b].v_scale, ocs[b].v_zero, gb["v_codes"], gb["v_scale"], gb["v_zero"],
-                        f"ragged b={b} V", bits=bits)
+                        f"ragged b={b} V", bits=bits, group=group)
         assert sinks["count"][b] == len(ocs[b].sink_pos[0])
         for i, pos in enumerate(ocs[b].sink_pos[0]):
             assert sinks["pos"][b, i] == pos
@@ -1006,14 +1012,19 @@ def test_sequences_of_different_lengths(bits):
             e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
             assert e <= ATT_TOL, f"current token, path {path}, b={b}: {e}"
     cache.set_decode_path(0)
+    assert cache.append_kernel() == (RB.KERNEL_MFMA if group == 128 else RB.KERNEL_MFMA_SUB)
     q2 = np.stack([S.make_q(w, batch=B, step=i) for i in range(2)], axis=1)
     q_pos = np.array([[total[b] - 2, total[b] - 1] for b in range(B)], dtype=np.int32)
-    out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
-    torch.cuda.synchronize()
-    for b in range(B):
-        ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
-        e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
-        assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
+    if group == 128:
+        out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
+        torch.cuda.synchronize()
+        for b in range(B):
+            ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
+            e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
+            assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
+    else:                       # the sub-group variant of the decode kernel takes one query token per step
+        with pytest.raises(R.RkvError):
+            cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
     # what the entry point refuses
     with pytest.raises(R.RkvError) as ei:
         cache.quantize_append_ragged(P.gpu(np.zeros((B, 50, 8, 128), np.float16)), P.gpu(np.zeros((B, 50, 8, 128), np.float16)), [1, 1, 50])
@@ -1140,6 +1151,9 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
             cache.set_decode_path(2)
             cache.decode_attention(P.gpu(q))
     cache.set_decode_path(0)
+    if on_matrix_cores:
+        assert cache.append_kernel() == (RB.KERNEL_MFMA if group == 128 else RB.KERNEL_MFMA_SUB)
+        assert cache.decode_kernel() == (RB.KERNEL_MFMA if group == 128 else RB.KERNEL_MFMA_SUB)
     # one more single-token step through rkv_decode_step (the two calls, on this setting)
     k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
     out = cache.decode_step(P.gpu(k1), P.gpu(v1), P.gpu(q))
