@@ -276,6 +276,8 @@ int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 #define RKV_KERNEL_MFMA       3  /* matrix-core kernels: reorder inside blocks of 128, rot_heads 2, 4 */
 #define RKV_KERNEL_MFMA_CROSS 4  /* their variant for a reorder across blocks inside rotation groups  */
 #define RKV_KERNEL_MFMA_SUB   5  /* their variant for quant_group 64 / 32                             */
+#define RKV_KERNEL_MFMA_ROW   6  /* decode only: a reorder over the whole row - scores by a kernel of  */
+                                 /* their own (fp16 matrix products), the rest by the matrix-core one  */
 int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries);
 int rkv_append_kernel_of(const rkv_cache* cache);
 

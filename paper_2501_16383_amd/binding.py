@@ -17,7 +17,7 @@ _lib = None
 
 RKV_OK, RKV_EINVAL, RKV_ECAPACITY, RKV_EPERM, RKV_EHIP, RKV_ESTATE, RKV_ESCRATCH = 0, -1, -2, -3, -4, -5, -6
 STATIC_SCRATCH_BYTES = 24 << 20
-KERNEL_GENERAL, KERNEL_SHUFFLE, KERNEL_MFMA, KERNEL_MFMA_CROSS, KERNEL_MFMA_SUB = 1, 2, 3, 4, 5
+KERNEL_GENERAL, KERNEL_SHUFFLE, KERNEL_MFMA, KERNEL_MFMA_CROSS, KERNEL_MFMA_SUB, KERNEL_MFMA_ROW = 1, 2, 3, 4, 5, 6
 
 EXPORTS = [
     "rkv_query_sizes", "rkv_cache_create", "rkv_cache_destroy", "rkv_cache_reset", "rkv_cache_length",

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librkv.so")
-SOURCES = ["rkv_api.hip", "rkv_kernels.hip", "rkv_append_mfma.hip", "rkv_select.hip", "rkv_decode_general.hip", "rkv_decode_mfma.hip"]
+SOURCES = ["rkv_api.hip", "rkv_kernels.hip", "rkv_append_mfma.hip", "rkv_select.hip", "rkv_decode_general.hip", "rkv_decode_mfma.hip", "rkv_decode_row.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
     # packed-FP32 instructions are kept out of the generated code on purpose

@@ -393,10 +393,17 @@ void rkv_launch_merge(const RkvView& v, const float* qr, const float* part, int 
   else hipLaunchKernelGGL(k_merge<1>, dim3(v.Hq, v.B), dim3(128), 0, s, v, qr, part, nch, chunk_tokens, k_cur, v_cur, q_lim, nq, out, lse);
 }
 
+// the split-K partial results of a launch over Tpad token slots (chunks of 128 tokens at the finest)
+size_t rkv_partial_bytes(int batch, int n_q_heads, int Tpad) {
+  return ((size_t)batch * n_q_heads * (Tpad / 128) * RKV_PART_STRIDE * 4 + 255) & ~(size_t)255;
+}
+
 size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
   const size_t Tpad = (cfg->max_tokens + 255) & ~255;
-  const size_t nch = Tpad / 128;
-  return rkv_query_scratch_bytes(cfg->batch, cfg->n_q_heads) + (size_t)cfg->batch * cfg->n_q_heads * nch * RKV_PART_STRIDE * 4 + 256;
+  size_t bytes = rkv_query_scratch_bytes(cfg->batch, cfg->n_q_heads) + rkv_partial_bytes(cfg->batch, cfg->n_q_heads, (int)Tpad) + 256;
+  // a reorder over the whole row: the scores of the compressed stream pass through a buffer (k_scores_row)
+  if (cfg->perm_span > cfg->rot_heads * RKV_D) bytes += rkv_row_scores_bytes(cfg->batch, cfg->n_q_heads, cfg->max_tokens);
+  return bytes;
 }
 
 int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,

@@ -233,7 +233,11 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // V metadata - replaced by values made up in registers (from the lane number and a kernel
 // argument, so that nothing folds at compile time): what the arithmetic alone costs when no byte
 // of the cache has to arrive.  The results mean nothing.
-template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false, int SUB = 0, bool ALU = false>
+// PRE: the scores of the compressed stream come from a buffer [sequence][query head][token slot]
+// (-infinity at retained sink tokens) in place of the key phase - a reorder over the whole token
+// row, whose scores k_scores_row computes; qt then points to that buffer.  Softmax, values and
+// partial results as in the plain kernel.
+template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false, int SUB = 0, bool ALU = false, bool PRE = false>
 __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF_OCC)) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq, int ns, uint32_t inv_ns, uint32_t inv_nrg) {
@@ -286,6 +290,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
   static_assert(SUB == 0 || (XB && !META8), "groups of 64 / 32 run as a variant of the cross-block kernel, fp16 metadata");
   static_assert(!ALU || (!XB && !META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
+  static_assert(!PRE || (!XB && !META8 && HB == 0 && !MULTI && !ALU), "precomputed scores: plain 2-bit layout, fp16 metadata, one query token");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -416,6 +421,34 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 
   const int cnt = ld_cnt;
   {
+    if constexpr (PRE) {
+      // thread = token of the chunk: its scores from the buffer, its value metadata to LDS
+      const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * G;
+      uint32_t dv[G];
+      if constexpr (G == 4) {
+        const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(v.vm + mi));
+        dv[0] = u.x; dv[1] = u.y; dv[2] = u.z; dv[3] = u.w;
+      } else {
+        const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(v.vm + mi));
+        dv[0] = u.x; dv[1] = u.y;
+      }
+      float pre[NH];
+#pragma unroll
+      for (int a = 0; a < G; ++a)
+#pragma unroll
+        for (int rri = 0; rri < REP; ++rri) {
+          const int qh = (rg * G + a) * rep + rrg * REP + rri;
+          pre[a * REP + rri] = t0 + tid < len ? qt[((size_t)b * v.Hq + qh) * v.Tpad + t0 + tid] : -INFINITY;
+        }
+      uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
+      for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
+      if (tid < 64) s_sink[tid] = tid < cnt ? ld_spos : -1;
+#pragma unroll
+      for (int i = 0; i < G; ++i) s_vm[tid * G + i] = dv[i];
+#pragma unroll
+      for (int a = 0; a < NH; ++a) s_sc[a][tid] = pre[a];
+      __syncthreads();
+    } else {
     // ------------------------------------------------------------------ phase K
     {
       const int tw = t0 + wave * (16 * MF_TILES);
@@ -898,6 +931,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
         }
       }
     }
+    }
     __builtin_amdgcn_s_setprio(3);
     if constexpr (ALIAS) {                                   // the table's space becomes the digits' (see s_A_raw)
       __syncthreads();
@@ -1108,12 +1142,12 @@ static bool mfma_sub_groups(const rkv_cache* c) {
 }
 
 int rkv_mfma_variant(const rkv_cache* c) {
-  return mfma_cross_block(c) ? RKV_KERNEL_MFMA_CROSS : mfma_sub_groups(c) ? RKV_KERNEL_MFMA_SUB : RKV_KERNEL_MFMA;
+  return rkv_row_supported(c) ? RKV_KERNEL_MFMA_ROW : mfma_cross_block(c) ? RKV_KERNEL_MFMA_CROSS : mfma_sub_groups(c) ? RKV_KERNEL_MFMA_SUB : RKV_KERNEL_MFMA;
 }
 
 bool rkv_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  if (mfma_cross_block(c) || mfma_sub_groups(c)) return true;
+  if (mfma_cross_block(c) || mfma_sub_groups(c) || rkv_row_supported(c)) return true;
   // 2-bit codes, or wider ones (a second plane), in groups of 128
   return c->blocks_aligned && v.qg == 128 && (v.g == 2 || v.g == 4);
 }
@@ -1124,6 +1158,10 @@ typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int,
 // heads of a KV head per workgroup (1 or 2); alu: the arithmetic-only measurement.
 static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool alu) {
   const RkvView& v = c->v;
+  if (rkv_row_supported(c)) {                               // scores from k_scores_row
+    if (v.g == 4) return share == 1 ? k_decode_mfma<4, 1, false, false, 0, false, 0, false, true> : k_decode_mfma<4, 2, false, false, 0, false, 0, false, true>;
+    return share == 1 ? k_decode_mfma<2, 1, false, false, 0, false, 0, false, true> : k_decode_mfma<2, 2, false, false, 0, false, 0, false, true>;
+  }
 #ifdef RKV_DEV_FEW_VARIANTS
   // developer builds: only the plain 2-bit variants of four-head rotation groups (quick to compile)
   if (multi || v.g != 4 || v.hb || v.meta8 || !c->blocks_aligned || v.qg != 128) abort();
@@ -1184,8 +1222,9 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   const int rep = v.Hq / v.Hkv;
   const bool sg = mfma_sub_groups(c);
   const bool xb = mfma_cross_block(c) || sg;
-  if (xb && multi) return RKV_EINVAL;                       // the cross-block variants take one query token per step
-  const int share = xb ? 1 : rkv_mfma_share(rep);           // and one query head per workgroup
+  const bool row = rkv_row_supported(c);
+  if ((xb || row) && multi) return RKV_EINVAL;              // the cross-block and whole-row variants take one query token per step
+  const int share = xb ? 1 : rkv_mfma_share(rep);           // and (cross-block) one query head per workgroup
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   const int nch = (v.len + MF_CH - 1) / MF_CH;
@@ -1204,6 +1243,21 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   // stamps): events recorded as separate commands before and after it also count the gaps between
   // commands on the stream, some 4 us per launch.
   const bool timed = c->ev_start && c->ev_stop;
+  if (row) {
+    // a reorder over the whole row: the scores come from a kernel of their own, into a buffer behind
+    // the partial results (rkv_decode_scratch_bytes reserves it); the events span both kernels
+    if (c->decode_path == 3) return RKV_EINVAL;
+    float* sc = (float*)((char*)part + rkv_partial_bytes(v.B, v.Hq, (int)v.Tpad));
+    if (timed) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
+    const int rc = rkv_launch_scores_row(c, qr, sc, s);
+    if (rc != RKV_OK) return rc;
+    if (nch > 0)
+      hipLaunchKernelGGL(pick_kernel(c, false, share, false), grid, dim3(256), 0, s, v, (const float*)sc, part, nch, (const int*)nullptr, nq,
+                         ns, recip(ns), recip(v.NRG));
+    if (timed) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
+    rkv_launch_merge(v, qr, part, nch, MF_CH, c->cur_k, c->cur_v, nullptr, nq, out, lse, s);
+    return rkv_check_launch();
+  }
   if (nch > 0) {                                            // (an empty cache has only the current token)
     if (timed)
       hipExtLaunchKernelGGL(pick_kernel(c, multi, share, c->decode_path == 3), grid, dim3(256), 0, s, c->ev_start, c->ev_stop, 0, v,

@@ -52,6 +52,7 @@
 #define RKV_PART_STRIDE 132   // floats per split-K partial: m, l, 2 pad, acc[128]
 #define RKV_GEN_CHUNK 128     // tokens per split-K chunk of the general decode kernel
 #define RKV_MFMA_CHUNK 256    // ... of the matrix-core decode kernel
+#define RKV_ROW_CHUNK 64      // tokens per workgroup of the scores kernel for a reorder over the whole row
 
 struct RkvView {
   uint32_t* kc;
@@ -297,6 +298,11 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int nq, float* out, float* lse, void* scratch,
                            bool q_prepared, hipStream_t s);
 int rkv_mfma_share(int heads_per_kv_head);
+// a reorder over the whole token row (rkv_decode_row.hip): its scores kernel and the buffer it fills
+bool rkv_row_supported(const rkv_cache* c);
+size_t rkv_row_scores_bytes(int batch, int n_q_heads, int max_tokens);
+int rkv_launch_scores_row(const rkv_cache* c, const float* qr, float* sc, hipStream_t s);
+size_t rkv_partial_bytes(int batch, int n_q_heads, int Tpad);
 int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* v, const __half* q, const int* q_pos, float* qr, int share,
                          hipStream_t s);
 bool rkv_mfma_supported(const rkv_cache* c);

@@ -164,11 +164,56 @@ def test_reorder_across_blocks(span_kind):
     cfg = R.RkvConfig(batch=1, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=span)
     perm = calibrated_perm(w, cfg, offset_variant=True)
     assert not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
-    # a reorder inside the rotation group has a matrix-core variant of the decode kernel; across groups only the general one
-    cache, _, _ = full_check(w, cfg, 100, perm=perm, paths=(1, 2) if span_kind == "group" else (1,), sink_positions=[])
+    # a reorder inside the rotation group has a variant of both matrix-core kernels; across groups the read
+    # half has one (the scores from a kernel of their own), the write half takes the general kernel
+    cache, _, _ = full_check(w, cfg, 100, perm=perm, paths=(1, 2), sink_positions=[])
     cache.set_decode_path(0)
-    want = RB.KERNEL_MFMA_CROSS if span_kind == "group" else RB.KERNEL_GENERAL
-    assert cache.decode_kernel() == want and cache.append_kernel() == want
+    if span_kind == "group":
+        assert cache.decode_kernel() == RB.KERNEL_MFMA_CROSS and cache.append_kernel() == RB.KERNEL_MFMA_CROSS
+    else:
+        assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_GENERAL
+
+
+@pytest.mark.parametrize("g,hq,style", [(4, 8, 0), (2, 8, 0), (4, 32, 0), (2, 16, 1), (4, 8, 1), (4, 64, 0)])
+def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
+    """perm_span = the whole token row (Alg. 1 as printed): a rotated channel belongs to any of the
+    row's quantization blocks.  The read half's path for it - scores from k_scores_row (elements
+    dequantized, split into two fp16 parts, rotated on the matrix cores), softmax and values from
+    the matrix-core decode kernel - against the oracle and the general kernel: rotation over 4 and 2
+    heads, GQA up to 8 query heads per KV head, both RoPE pairings, several chunks and a ragged
+    tail, with and without retained sink rows, the current token as an exact row, single-token
+    steps, sequences of different lengths."""
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
+    cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=g, perm_span=1024, rope_style=style)
+    perm = calibrated_perm(w, cfg, offset_variant=True)
+    assert not np.array_equal(perm // (128 * g), np.arange(cfg.E) // (128 * g))       # channels leave their rotation groups
+    cache, oc, q = full_check(w, cfg, 613, perm=perm, chunks=[0, 300, 301, 613], paths=(1, 2),
+                              sink_positions=None if (g, hq, style) in ((4, 8, 0), (2, 16, 1)) else [])
+    cache.set_decode_path(2)
+    assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_GENERAL
+    k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
+    out = cache.decode_attention(P.gpu(q), k_cur=P.gpu(k1[:, 0]), v_cur=P.gpu(v1[:, 0]))      # the cache holds the oracle's codes here
+    torch.cuda.synchronize()
+    ref, _ = O.decode_attention(oc, q, None, k1[:, 0], v1[:, 0])
+    assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
+    out = cache.decode_step(P.gpu(k1), P.gpu(v1), P.gpu(q))
+    torch.cuda.synchronize()
+    O.quantize_append(oc, k1, v1, None)
+    ref, _ = O.decode_attention(oracle_from_export(oc, P.export_numpy(cache)), q)
+    assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
+    with pytest.raises(R.RkvError):                              # several query tokens: not on this path
+        cache.decode_attention_multi(P.gpu(np.stack([q, q], axis=1)), P.gpu(np.array([[600, 601], [600, 601]], dtype=np.int32)))
+    # against the general kernel on the same cache, and on the work space built into the library
+    cache.set_decode_path(1)
+    o_gen, l_gen = cache.decode_attention(P.gpu(q), want_lse=True)
+    cache.set_decode_path(0)
+    o_row, l_row = cache.decode_attention(P.gpu(q), want_lse=True)
+    o_st = torch.empty_like(o_row)
+    cache.decode_attention_static(P.gpu(q), o_st)
+    torch.cuda.synchronize()
+    assert P.attention_error(o_row.cpu().numpy().astype(np.float64), o_gen.cpu().numpy().astype(np.float64)) <= 1e-4
+    assert float((l_row - l_gen).abs().max()) <= 1e-4
+    assert torch.equal(o_st, o_row)
 
 
 @pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
