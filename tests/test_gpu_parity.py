@@ -352,28 +352,29 @@ def test_error_codes():
 
 
 def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag="", meta_format=0, rep=1, rope_theta=10000.0,
-                bits=2):
+                bits=2, group=128):
     """One (sequence, rotation group of 4 heads) slice of a full-size run against the oracle: a
     rotation group's codes and attention outputs depend on nothing outside the slice.  The codes
     must equal the oracle's outside the documented rounding ties; the attention output is then
     compared on the GPU's own codes, so that a tie cannot hide in (or leak into) the tolerance.
     exp: export_codes() tensors already on the host (numpy)."""
     ocfg = O.OracleConfig(batch=1, n_q_heads=4 * rep, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=max_sinks,
-                          meta_format=meta_format, rope_theta=rope_theta, bits=bits)
+                          meta_format=meta_format, rope_theta=rope_theta, bits=bits, quant_group=group)
     hq = slice(4 * rep * rg, 4 * rep * (rg + 1))               # the query heads of the group's four KV heads
     oc = O.cache_new(ocfg, None if perm is None else perm[512 * rg:512 * (rg + 1)] - 512 * rg)
     O.quantize_append(oc, ks, vs, ms)
     nb = 512 // (4 if bits == 2 else 2)                         # canonical bytes of the group's 512 codes
-    sl_c, sl_m = slice(nb * rg, nb * (rg + 1)), slice(4 * rg, 4 * rg + 4)
+    nm = 512 // group                                           # metadata entries of the group
+    sl_c, sl_m = slice(nb * rg, nb * (rg + 1)), slice(nm * rg, nm * (rg + 1))
     g = {}
     for name in ("k", "v"):
         g[name + "_codes"] = O.unpack_canonical(exp[name + "_codes"][b:b + 1, :, sl_c], bits)
         g[name + "_scale"] = exp[name + "_scale"][b:b + 1, :, sl_m].astype(np.float64)
         g[name + "_zero"] = exp[name + "_zero"][b:b + 1, :, sl_m].astype(np.float64)
     P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"],
-                    f"{tag} b={b} rg={rg} K", rot_span=512, meta_format=meta_format, bits=bits)
+                    f"{tag} b={b} rg={rg} K", rot_span=512, meta_format=meta_format, bits=bits, group=group)
     P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"],
-                    f"{tag} b={b} rg={rg} V", meta_format=meta_format, bits=bits)
+                    f"{tag} b={b} rg={rg} V", meta_format=meta_format, bits=bits, group=group)
     for name, val in g.items():                                # attention on the GPU's own codes
         setattr(oc, name, val)
     ref, lse_ref = O.decode_attention(oc, q[b:b + 1, hq])
@@ -389,13 +390,15 @@ def export_host(cache):
     return {k: v.cpu().numpy() for k, v in exp.items()}
 
 
-@pytest.mark.parametrize("meta_format,bits,with_sinks", [(0, 2, True), (0, 2, False), (1, 2, True), (0, 4, True), (1, 3, False)])
-def test_full_size_config2_sampled(meta_format, bits, with_sinks):
+@pytest.mark.parametrize("meta_format,bits,with_sinks,group", [(0, 2, True, 128), (0, 2, False, 128), (1, 2, True, 128), (0, 4, True, 128),
+                                                              (1, 3, False, 128), (0, 2, False, 64), (0, 2, True, 32)])
+def test_full_size_config2_sampled(meta_format, bits, with_sinks, group):
     """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, then one rkv_decode_step (the last
     token's append and the attention on the matrix-core path).  The oracle recomputes sampled (sequence, rotation group) slices - a
     rotation group's codes and attention outputs depend on nothing outside the slice.  Once with
-    fp16 metadata, once with the FP8 scale / INT8 zero-point storage, once with 4-bit codes, once with 3-bit codes and FP8 / INT8 metadata.
+    fp16 metadata, once with the FP8 scale / INT8 zero-point storage, once with 4-bit codes, once with 3-bit codes and FP8 / INT8 metadata,
+    and with quantization groups of 64 and 32 (Table tab:quantgrani: the sub-group variants of both matrix-core kernels).
     With the workload's four fp16 sink rows, as bench.py runs it, and with no retained rows at
     all: the sink keys are a hundred times the rest and take nearly all the softmax weight, so only
     the run without them lets the compressed stream decide the outputs."""
@@ -403,7 +406,7 @@ def test_full_size_config2_sampled(meta_format, bits, with_sinks):
     T = w.context
     n_keep = 4 if with_sinks else 0
     cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=n_keep,
-                      rot_heads=4, perm_span=128, meta_format=meta_format, bits=bits)
+                      rot_heads=4, perm_span=128, meta_format=meta_format, bits=bits, quant_group=group)
     perm = calibrated_perm(w, cfg)
     cache = R.RkvCache(cfg)
     cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
@@ -429,7 +432,8 @@ def test_full_size_config2_sampled(meta_format, bits, with_sinks):
     cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous() if with_sinks else None)
     cache.set_decode_path(2)
     # the kernels bench.py times, not a fall-back to the general ones
-    assert cache.decode_kernel() == RB.KERNEL_MFMA and cache.append_kernel() == RB.KERNEL_MFMA
+    want_kind = RB.KERNEL_MFMA if group == 128 else RB.KERNEL_MFMA_SUB
+    assert cache.decode_kernel() == want_kind and cache.append_kernel() == want_kind
     assert not bool(mask[:, T - 1:].any())                  # the step's token is an ordinary one
     out, lse = cache.decode_step(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), P.gpu(q), want_lse=True)
     exp = export_host(cache)
@@ -440,7 +444,68 @@ def test_full_size_config2_sampled(meta_format, bits, with_sinks):
     for (b, rg) in samples:
         ks, vs, ms = keep[(b, rg)]
         check_slice(exp, out, lse, b, rg, ks, vs, ms if with_sinks else None, q, perm=perm, max_sinks=n_keep,
-                    tag=f"full-size meta_format={meta_format} bits={bits} sinks={with_sinks}", meta_format=meta_format, bits=bits)
+                    tag=f"full-size meta_format={meta_format} bits={bits} sinks={with_sinks} group={group}", meta_format=meta_format, bits=bits,
+                    group=group)
+
+
+@pytest.mark.parametrize("with_sinks", [False, True])
+def test_full_size_config2_whole_row_reorder_sampled(with_sinks):
+    """Configuration 2's geometry with the reorder over the whole token row (perm_span = 5120:
+    Alg. 1 as printed), at full size: bulk append, then decode attention on the path bench.py
+    times for this setting (scores kernel + matrix-core decode kernel).  With such a reorder a
+    quantization block mixes channels of every rotation group, so the oracle recomputes whole
+    sequences (two of the sixteen, all 40 heads): codes under the tie protocol, then attention on
+    the GPU's own codes."""
+    w = S.WORKLOADS["cfg2"]
+    T = w.context
+    n_keep = 4 if with_sinks else 0
+    cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=n_keep,
+                      rot_heads=4, perm_span=w.n_kv_heads * 128)
+    perm = calibrated_perm(w, cfg, offset_variant=True)
+    assert not np.array_equal(perm // 512, np.arange(cfg.E) // 512)
+    cache = R.RkvCache(cfg)
+    cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+    assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW
+    sampled = (3, 15)
+    keep, k_parts, v_parts, m_parts = {}, [], [], []
+    print("[case] full-size config 2, whole-row reorder: generating inputs per sequence", flush=True)
+    for b in range(w.batch):
+        kb, vb, mb = S.make_kv(dataclasses.replace(w, seed=w.seed + 100 * b), T, batch=1, sink_positions=None if with_sinks else [])
+        if b in sampled:
+            keep[b] = (kb.copy(), vb.copy(), mb.copy())
+        k_parts.append(torch.from_numpy(kb))
+        v_parts.append(torch.from_numpy(vb))
+        m_parts.append(torch.from_numpy(mb))
+    k, v, mask = torch.cat(k_parts).cuda(), torch.cat(v_parts).cuda(), torch.cat(m_parts).cuda()
+    del k_parts, v_parts
+    q = S.make_q(w)
+    print("[case] full-size config 2, whole-row reorder: bulk append 4096 + decode attention", flush=True)
+    cache.quantize_append(k, v, mask if with_sinks else None)
+    out, lse = cache.decode_attention(P.gpu(q), want_lse=True)
+    exp = export_host(cache)
+    out = out.cpu().numpy().astype(np.float64)
+    lse = lse.cpu().numpy().astype(np.float64)
+    assert np.isfinite(out).all() and cache.length == T
+    ocfg = P.oracle_cfg(dataclasses.replace(cfg, batch=1))
+    for b in sampled:
+        kb, vb, mb = keep[b]
+        oc = O.cache_new(ocfg, perm)
+        O.quantize_append(oc, kb, vb, mb if with_sinks else None)
+        g = {}
+        for name in ("k", "v"):
+            g[name + "_codes"] = O.unpack_canonical(exp[name + "_codes"][b:b + 1], 2)
+            g[name + "_scale"] = exp[name + "_scale"][b:b + 1].astype(np.float64)
+            g[name + "_zero"] = exp[name + "_zero"][b:b + 1].astype(np.float64)
+        P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"],
+                        f"whole-row full size b={b} K", rot_span=cfg.E)    # (a block's members come from any rotation group)
+        P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], f"whole-row full size b={b} V")
+        for name, val in g.items():                            # attention on the GPU's own codes
+            setattr(oc, name, val)
+        ref, lse_ref = O.decode_attention(oc, q[b:b + 1])
+        e = P.attention_error(out[b:b + 1], ref)
+        le = float(np.abs(lse[b:b + 1] - lse_ref).max())
+        print(f"[parity] whole-row full size sinks={with_sinks} b={b}: out err {e:.3e} lse err {le:.3e}", flush=True)
+        assert e <= ATT_TOL and le <= LSE_TOL
 
 
 def test_full_size_long_context_sampled():
