@@ -182,7 +182,7 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
     the matrix-core decode kernel - against the oracle and the general kernel: rotation over 4 and 2
     heads, GQA up to 8 query heads per KV head, both RoPE pairings, several chunks and a ragged
     tail, with and without retained sink rows, the current token as an exact row, single-token
-    steps, sequences of different lengths."""
+    steps, a cache cut back by rkv_cache_truncate, the work space built into the library."""
     w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
     cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=g, perm_span=1024, rope_style=style)
     perm = calibrated_perm(w, cfg, offset_variant=True)
@@ -214,6 +214,17 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
     assert P.attention_error(o_row.cpu().numpy().astype(np.float64), o_gen.cpu().numpy().astype(np.float64)) <= 1e-4
     assert float((l_row - l_gen).abs().max()) <= 1e-4
     assert torch.equal(o_st, o_row)
+    # per-sequence lengths are a path of the matrix-core append kernel, which this setting does not take: refused,
+    # while cutting all sequences back to one length works and the read half follows
+    with pytest.raises(R.RkvError):
+        cache.truncate([500, 133])
+    cache.truncate([133, 133])
+    o_row = cache.decode_attention(P.gpu(q))
+    cache.set_decode_path(1)
+    o_gen = cache.decode_attention(P.gpu(q))
+    torch.cuda.synchronize()
+    assert cache.lengths == [133, 133]
+    assert P.attention_error(o_row.cpu().numpy().astype(np.float64), o_gen.cpu().numpy().astype(np.float64)) <= 1e-4
 
 
 @pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
