@@ -178,7 +178,7 @@ int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, 
  *   host_n_new      [batch] int32 in host memory, 0 <= host_n_new[b] <= n_new_max; read before the call returns
  *   dev_sink_mask   [batch][n_new_max] uint8 or NULL
  * Needs a configuration the matrix-core append kernel covers (reorder inside blocks of 128 - or,
- * with 2-bit codes, inside the rotation groups -, rot_heads 2 or 4, v_rotate 0; quant_group 64 or
+ * with 2-bit codes and groups of 128, anywhere in the row -, rot_heads 2 or 4, v_rotate 0; quant_group 64 or
  * 32 only with 2-bit codes, fp16 metadata and a reorder inside blocks of 128),
  * else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
  * max_tokens (nothing is appended then).  rkv_import_codes returns RKV_ESTATE on such a cache;
@@ -276,8 +276,10 @@ int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 #define RKV_KERNEL_MFMA       3  /* matrix-core kernels: reorder inside blocks of 128, rot_heads 2, 4 */
 #define RKV_KERNEL_MFMA_CROSS 4  /* their variant for a reorder across blocks inside rotation groups  */
 #define RKV_KERNEL_MFMA_SUB   5  /* their variant for quant_group 64 / 32                             */
-#define RKV_KERNEL_MFMA_ROW   6  /* decode only: a reorder over the whole row - scores by a kernel of  */
-                                 /* their own (fp16 matrix products), the rest by the matrix-core one  */
+#define RKV_KERNEL_MFMA_ROW   6  /* a reorder over the whole row.  Decode: scores by a kernel of their */
+                                 /* own (fp16 matrix products), the rest by the matrix-core one; append: */
+                                 /* keys by a kernel that sees whole token rows (2-bit codes, groups of  */
+                                 /* 128, rot_heads 2 or 4)                                               */
 int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries);
 int rkv_append_kernel_of(const rkv_cache* cache);
 

@@ -72,7 +72,7 @@ static int check_config(const rkv_config* c, bool need_capacity) {
 }
 
 struct Offsets {
-  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, xmask, xtt, xgsel, total;
+  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, xmask, xtt, xgsel, xgid8, total;
   int Tpad;
 };
 
@@ -109,6 +109,7 @@ static Offsets plan(const rkv_config* c) {
     o.xmask = p; p = align256(p + nrg * g * np * 4 * 16);
     o.xtt = p; p = align256(p + nrg * 128 * xk * g * 4);
     o.xgsel = p; p = align256(p + nrg * 16 * g * 4);
+    o.xgid8 = p; p = align256(p + nrg * 16 * g * 8);
   }
   o.total = p;
   return o;
@@ -128,6 +129,19 @@ static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int 
     if (inv[c] / n != c / n) in_groups = 0;
   *in_groups_out = in_groups;
   const bool cross = in_groups && !aligned && qg == 128, subs = aligned && qg < 128 && (g == 2 || g == 4);
+  if (!in_groups && !aligned && qg == 128 && (g == 2 || g == 4)) {
+    // a reorder over the whole row: the row's quantization block of every rotated channel, as bytes in the
+    // order the append kernel's lanes hold them
+    std::vector<uint8_t> x8((size_t)nrg * 16 * g * 8, 0);
+    for (int rg = 0; rg < nrg; ++rg)
+      for (int c = 0; c < n; ++c) {
+        const int blk = c >> 7, kap = c & 127, q = kap >> 5, w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);
+        x8[((((size_t)rg * 4 + wave) * 4 + q) * g + blk) * 8 + (kap & 7)] = (uint8_t)(inv[rg * n + c] >> 7);
+      }
+    RKV_HIP_CHECK(hipMemcpyAsync((void*)v.xgid8, x8.data(), x8.size(), hipMemcpyHostToDevice, s));
+    RKV_HIP_CHECK(hipStreamSynchronize(s));
+    return RKV_OK;
+  }
   if (!cross && !subs) return RKV_OK;
   const int np = subs ? sub_n : g, xk = subs ? g * sub_n : g;
   std::vector<uint32_t> xmask((size_t)nrg * g * np * 16, 0u), xgsel((size_t)nrg * 16 * g, 0u);
@@ -245,6 +259,7 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.xmask = (uint32_t*)(c->base + o.xmask);
   v.xtt = (float*)(c->base + o.xtt);
   v.xgsel = (uint32_t*)(c->base + o.xgsel);
+  v.xgid8 = (const uint2*)(c->base + o.xgid8);
   c->in_groups = 0;
   v.B = cfg->batch;
   v.Hq = cfg->n_q_heads;
@@ -381,7 +396,7 @@ RKV_EXPORT int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries) {
 RKV_EXPORT int rkv_append_kernel_of(const rkv_cache* cache) {
   if (!cache) return RKV_EINVAL;
   const RkvView& v = cache->v;
-  if (rkv_append_mfma_supported(cache)) return v.qg != 128 ? RKV_KERNEL_MFMA_SUB : cache->blocks_aligned ? RKV_KERNEL_MFMA : RKV_KERNEL_MFMA_CROSS;
+  if (rkv_append_mfma_supported(cache)) return rkv_append_mfma_variant(cache);
   if (cache->blocks_aligned && !cache->wide && (v.g == 2 || v.g == 4)) return RKV_KERNEL_SHUFFLE;
   return RKV_KERNEL_GENERAL;
 }
@@ -565,7 +580,8 @@ RKV_EXPORT int rkv_decode_step(rkv_cache* cache, const void* dev_k, const void* 
                                float* dev_out, float* dev_lse, void* dev_scratch, void* stream) {
   if (!cache || !dev_k || !dev_v || !dev_q || !dev_out || !dev_scratch) return RKV_EINVAL;
   if ((int64_t)cache->v.len + 1 > cache->cfg.max_tokens) return RKV_ECAPACITY;
-  const bool fused = rkv_append_mfma_supported(cache) && rkv_mfma_supported(cache) && cache->decode_path != 1;
+  const bool fused = rkv_append_mfma_supported(cache) && rkv_append_mfma_variant(cache) != RKV_KERNEL_MFMA_ROW &&
+                     rkv_mfma_supported(cache) && cache->decode_path != 1;
   if (!fused) {   // the same two calls, one after the other
     const int rc = rkv_quantize_append(cache, dev_k, dev_v, 1, nullptr, stream);
     return rc != RKV_OK ? rc : rkv_decode_attention(cache, dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, stream);

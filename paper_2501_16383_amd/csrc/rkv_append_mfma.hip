@@ -606,6 +606,197 @@ __global__ void __launch_bounds__(256, (HB || XW || SUB) ? 4 : 6) k_append_mfma(
   append_mfma_body<G, HB, XW, SUB>(v, kin, vin, n_new, slab0, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
+// the value role alone (grid x = slabs): the keys of a reorder over the whole row have a kernel of their own
+template <int G>
+__global__ void __launch_bounds__(256, 6) k_append_values(RkvView v, const __half* __restrict__ vin, int n_new, int slab0) {
+  append_mfma_body<G, 0, false, 0>(v, nullptr, vin, n_new, slab0, 3 * blockIdx.x + 2, blockIdx.y, blockIdx.z);
+}
+
+// Keys under a reorder over the whole token row (perm_span = n_kv_heads * 128, Alg. 1 as printed;
+// 2-bit codes in groups of 128).  A rotated channel then belongs to any of the row's E / 128
+// quantization blocks, so a block's minimum and maximum (Eq. 8-9) need the rotated values of all
+// rotation groups of the token.  One workgroup = (sequence, tile of 16 tokens) takes the groups one
+// after the other, twice: the first pass rotates (H_128 on fp16 matrix products, H_g in the lane,
+// as k_append_mfma) and gathers the extrema of the tile's 16 x E/128 blocks with LDS float atomics;
+// one thread per (token, block) then works out the parameters, stores the metadata and leaves
+// (reciprocal scale, constant added, base) in LDS; the second pass rotates again - the tile's keys
+// come back from the last-level cache - and quantizes every element with its own block's
+// parameters.  Codes stay where they are, by rotated channel.  The quantization block of each of a
+// lane's channels comes from a per-cache table of bytes (xgid8, written by rkv_set_perm).
+// dynamic LDS: [16][NG | 1] float minima, the same of maxima, [16][NG | 1] float4 parameters.
+template <int G>
+__global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __half* __restrict__ kin, int n_new, int slab0) {
+  constexpr int n = 128 * G;
+  constexpr int ROW16 = 16 * G, STRIDE16 = ROW16 + 1;
+  __shared__ __attribute__((aligned(16))) uint32_t lds[16 * STRIDE16 * 4];
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_row[];
+  const int NG = v.E >> 7, NGP = NG | 1;       // (rows of odd length: the tile's 16 tokens start in different banks)
+  float* s_mn = reinterpret_cast<float*>(dyn_row);
+  float* s_mx = s_mn + 16 * NGP;
+  float4* s_par = reinterpret_cast<float4*>(dyn_row + (size_t)2 * 16 * NGP * 4);      // (128 NGP bytes in: 16-byte aligned)
+  __shared__ uint32_t img[2 * 128 * G];        // the tile image of one rotation group, in two halves (see k_append_mfma)
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int b = blockIdx.y, ti = blockIdx.x & 1;
+  const int len_b = rkv_len(v, b), n_b = v.nnew ? v.nnew[b] : n_new;
+  const int slab = (v.lens ? (len_b >> 5) : slab0) + (blockIdx.x >> 1);
+  const int t_lo = len_b, t_hi = len_b + n_b;
+  const int ts = slab * 32;
+  if (ts >= t_hi || n_b <= 0) return;
+  if (!((ts + 16 * ti < t_hi) && (ts + 16 * ti + 16 > t_lo))) return;   // no token of this call in the tile
+  const int tau_first = max(0, t_lo - ts), tau_last = min(31, t_hi - 1 - ts);
+  const int d = wave & 1, pph = wave >> 1;                 // this wave: products pp = 2 pph + {0, 1} of dword half d
+  const int col = lane & 15, q = lane >> 4;                // result: token `col` of the tile, rows 4q..4q+3
+  const float rs = rsqrtf((float)n);
+  // A operands (see k_append_mfma): lane (row m, k-group kg) holds H_128[channel][32 ks + 8 kg + i]
+  const int m = lane & 15, kg = lane >> 4, r = m & 3, qa = m >> 2;
+  uint32_t base[2][4];
+#pragma unroll
+  for (int eb = 0; eb < 2; ++eb)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int e = 4 * eb + r;
+      base[eb][j] = (0x3C003C00u ^ parity_mask(e & (2 * j), 0x00008000u)) ^ parity_mask(e & (2 * j + 1), 0x80000000u);
+    }
+  const uint32_t maskv = parity_mask((2 * d + pph) & kg, 0x80008000u);
+
+  constexpr int TPI = 64 / ROW16;                        // token rows per wave-wide 16-byte load
+  // the tile's rows of one rotation group (wave w: tokens 4w..4w+3), requested one group ahead and
+  // held in registers meanwhile (named registers: as an array they were given a place in memory)
+  uint4 st0 = make_uint4(0, 0, 0, 0), st1 = st0, st2 = st0, st3 = st0;
+  auto row_ptr = [&](int rg, int k) __attribute__((always_inline)) {
+    // rows of tokens outside this call are replaced by a row inside it (their codes are never stored)
+    const int tau = min(max(16 * ti + 4 * wave + TPI * k + lane / ROW16, tau_first), tau_last);
+    return reinterpret_cast<const uint4*>(kin + ((size_t)b * n_new + (ts + tau - t_lo)) * v.E + (size_t)rg * n) + lane % ROW16;
+  };
+#define RKV_ROW_REQUEST(rg_)                    \
+  do {                                          \
+    st0 = *row_ptr(rg_, 0);                     \
+    st1 = *row_ptr(rg_, 1);                     \
+    if constexpr (TPI == 1) {                   \
+      st2 = *row_ptr(rg_, 2);                   \
+      st3 = *row_ptr(rg_, 3);                   \
+    }                                           \
+  } while (0)
+#define RKV_ROW_DEPOSIT()                                                                             \
+  do {                                                                                                \
+    uint4* rows_ = reinterpret_cast<uint4*>(lds);                                                     \
+    rows_[(4 * wave + TPI * 0 + lane / ROW16) * STRIDE16 + lane % ROW16] = st0;                       \
+    rows_[(4 * wave + TPI * 1 + lane / ROW16) * STRIDE16 + lane % ROW16] = st1;                       \
+    if constexpr (TPI == 1) {                                                                         \
+      rows_[(4 * wave + 2 + lane / ROW16) * STRIDE16 + lane % ROW16] = st2;                           \
+      rows_[(4 * wave + 3 + lane / ROW16) * STRIDE16 + lane % ROW16] = st3;                           \
+    }                                                                                                 \
+  } while (0)
+  auto rotate = [&](v4f (&acc)[G][2]) __attribute__((always_inline)) {
+    const uint4* xrow = reinterpret_cast<const uint4*>(lds) + col * STRIDE16 + q;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const uint32_t mk = maskv ^ parity_mask(qa & ks, 0x80008000u);
+#pragma unroll
+      for (int ppl = 0; ppl < 2; ++ppl) {
+        const v8h a = as_v8h(base[ppl][0] ^ mk, base[ppl][1] ^ mk, base[ppl][2] ^ mk, base[ppl][3] ^ mk);
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          const uint4 xb = xrow[16 * h + 4 * ks];
+          const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+          acc[h][ppl] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, as_v8h(xb.x, xb.y, xb.z, xb.w), ks == 0 ? zero4 : acc[h][ppl], 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        if constexpr (G == 4) {
+          const float x0 = acc[0][ppl][rr], x1 = acc[1][ppl][rr], x2 = acc[2][ppl][rr], x3 = acc[3][ppl][rr];
+          const float a0 = x0 + x1, a1 = x0 - x1, a2 = x2 + x3, a3 = x2 - x3;
+          acc[0][ppl][rr] = a0 + a2; acc[1][ppl][rr] = a1 + a3; acc[2][ppl][rr] = a0 - a2; acc[3][ppl][rr] = a1 - a3;
+        } else {
+          const float x0 = acc[0][ppl][rr], x1 = acc[1][ppl][rr];
+          acc[0][ppl][rr] = x0 + x1; acc[1][ppl][rr] = x0 - x1;
+        }
+      }
+  };
+  // quantization blocks (of the row) of the lane's eight channels of head h, one byte each (element 4 ppl + rr)
+  auto blocks_of = [&](int rg, int h) __attribute__((always_inline)) { return v.xgid8[(((size_t)rg * 4 + wave) * 4 + q) * G + h]; };
+
+  for (int i = tid; i < 16 * NGP; i += 256) {
+    s_mn[i] = 3.0e38f;
+    s_mx[i] = -3.0e38f;
+  }
+  // ---- first pass: extrema
+  RKV_ROW_REQUEST(0);
+  for (int rg = 0; rg < v.NRG; ++rg) {
+    RKV_ROW_DEPOSIT();
+    __syncthreads();
+    if (rg + 1 < v.NRG) RKV_ROW_REQUEST(rg + 1);
+    v4f acc[G][2];
+    rotate(acc);
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const uint2 gb = blocks_of(rg, h);
+#pragma unroll
+      for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int blk = col * NGP + (int)(((ppl ? gb.y : gb.x) >> (8 * rr)) & 0xffu);
+          lds_fmin(&s_mn[blk], acc[h][ppl][rr]);
+          lds_fmax(&s_mx[blk], acc[h][ppl][rr]);
+        }
+    }
+    __syncthreads();                                       // the rows are read: the next group's may come
+  }
+  // ---- Eq. 8-9 per (token, block)
+  RKV_ROW_REQUEST(0);
+  for (int e = tid; e < 16 * NG; e += 256) {
+    const int tk = e / NG, bk = e - tk * NG;
+    float sc, zero_b, inv, base_b, add_b;
+    quant_params_nodiv(s_mn[tk * NGP + bk] * rs, s_mx[tk * NGP + bk] * rs, sc, zero_b, inv, v.meta8);
+    fused_round_consts(zero_b, base_b, add_b);
+    s_par[tk * NGP + bk] = make_float4(inv * rs, add_b, base_b, 0.f);
+    const int tau = 16 * ti + tk;
+    if (tau >= tau_first && tau <= tau_last) rkv_store_meta(v, v.km, rkv_meta_index(v, b, ts + tau, bk), sc, zero_b);
+  }
+  // ---- second pass: Eq. 6 with each element's own block's parameters
+  for (int rg = 0; rg < v.NRG; ++rg) {
+    RKV_ROW_DEPOSIT();
+    __syncthreads();                                       // (also: the parameters are complete)
+    if (rg + 1 < v.NRG) RKV_ROW_REQUEST(rg + 1);
+    v4f acc[G][2];
+    rotate(acc);
+    uint32_t words[G];
+#pragma unroll
+    for (int a = 0; a < G; ++a) {
+      const uint2 gb = blocks_of(rg, a);
+      uint32_t word = 0;
+#pragma unroll
+      for (int ppl = 0; ppl < 2; ++ppl)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const float4 pr = s_par[col * NGP + (int)(((ppl ? gb.y : gb.x) >> (8 * rr)) & 0xffu)];
+          const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + 3.0f);
+          word += (__float_as_uint(c) - __float_as_uint(pr.z)) << (16 * ppl + 4 * rr);
+        }
+      words[a] = word << (2 * pph);
+    }
+    // (the previous group's image was stored before this group's first barrier)
+#pragma unroll
+    for (int a = 0; a < G; ++a) img[pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = words[a];
+    __syncthreads();                                       // the image is complete; the rows are read: the next group's may come
+#pragma unroll
+    for (int k = 0; k < (128 * G + 255) / 256; ++k) {
+      const int off = tid + 256 * k;
+      if (off < 128 * G) {
+        const int t = ts + ti * 16 + rkv_k_tile_token(G, off);
+        if (t >= t_lo && t < t_hi) rkv_st_stream(&v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], img[off] | img[128 * G + off]);
+      }
+    }
+  }
+#undef RKV_ROW_REQUEST
+#undef RKV_ROW_DEPOSIT
+}
+
 // One decode step's write half and query preparation in one launch: the first 3 * n_slabs
 // workgroups of a (rotation group, sequence) append the step's token as k_append_mfma does, the
 // rest prepare that rotation group's query heads (two heads per workgroup) for the decode kernel,
@@ -624,8 +815,19 @@ __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* _
   rkv_prep_q_one(v, q, q_pos, 1, qr, share, 1, h, blockIdx.z, threadIdx.x & 127);
 }
 
+// a reorder over the whole row: k_append_row_keys + k_append_values
+static bool append_row(const rkv_cache* c) {
+  const RkvView& v = c->v;
+  return !c->blocks_aligned && !c->in_groups && v.qg == 128 && v.hb == 0 && (v.g == 2 || v.g == 4) && v.v_rotate == 0 &&
+         !c->cfg.keys_rotated && (size_t)384 * ((v.E >> 7) | 1) <= 48 * 1024;
+}
+int rkv_append_mfma_variant(const rkv_cache* c) {
+  return append_row(c) ? RKV_KERNEL_MFMA_ROW : c->v.qg != 128 ? RKV_KERNEL_MFMA_SUB : c->blocks_aligned ? RKV_KERNEL_MFMA : RKV_KERNEL_MFMA_CROSS;
+}
+
 bool rkv_append_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
+  if (append_row(c)) return true;
   // 2-bit codes, or wider ones (a second plane), in groups of 128; a reorder across 128-blocks
   // inside the rotation groups with 2-bit codes
   if (!c->blocks_aligned && !(c->in_groups && v.hb == 0 && !c->cfg.keys_rotated)) return false;
@@ -650,7 +852,16 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   }
   dim3 grid(3 * max_slabs, v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  if (v.qg == 64) {
+  if (append_row(c)) {
+    const size_t dyn = (size_t)384 * ((v.E >> 7) | 1);
+    if (v.g == 4) {
+      hipLaunchKernelGGL(k_append_row_keys<4>, dim3(2 * max_slabs, v.B), dim3(256), dyn, s, v, k, n_new, slab0);
+      hipLaunchKernelGGL(k_append_values<4>, dim3(max_slabs, v.NRG, v.B), dim3(256), 0, s, v, vv, n_new, slab0);
+    } else {
+      hipLaunchKernelGGL(k_append_row_keys<2>, dim3(2 * max_slabs, v.B), dim3(256), dyn, s, v, k, n_new, slab0);
+      hipLaunchKernelGGL(k_append_values<2>, dim3(max_slabs, v.NRG, v.B), dim3(256), 0, s, v, vv, n_new, slab0);
+    }
+  } else if (v.qg == 64) {
     if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
     else hipLaunchKernelGGL((k_append_mfma<2, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
   } else if (v.qg == 32) {
@@ -675,7 +886,7 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
 int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const __half* q, const int* q_pos, float* qr, int share,
                          hipStream_t s) {
   const RkvView& v = c->v;
-  if (!rkv_append_mfma_supported(c)) return RKV_EINVAL;
+  if (!rkv_append_mfma_supported(c) || append_row(c)) return RKV_EINVAL;
   int max_slabs = 1;                                        // one token touches one slab of its sequence
   const int n_append = 3 * max_slabs, rep = v.Hq / v.Hkv;
   dim3 grid(n_append + v.g * rep / 2, v.NRG, v.B);

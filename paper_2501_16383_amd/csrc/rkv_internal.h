@@ -76,6 +76,8 @@ struct RkvView {
   uint32_t* xgsel;   // [rot group][wave 0..3][lane group q][head h]: the quantization blocks (2 bits each, element
                      // 4 ppl + rr) of the eight channels 128 h + 32 q + 8 (2 (wave & 1) + (wave >> 1)) + 4 ppl + rr
                      // that a lane of the append kernel's key role holds
+  const uint2* xgid8; // [rot group][wave 0..3][lane group q][head h]: the same eight channels' quantization blocks of the
+                     // whole row, one byte each (a reorder over the whole row: k_append_row_keys)
   int B, Hq, Hkv, g, n, E, NRG, NG, Tpad, max_sinks, len, span, rope_style, v_rotate, keys_rotated;
   const int* lens;   // per-sequence lengths [B] once the sequences differ in length, else null (all have `len` tokens)
   const int* cstart; // with `lens`: cstart[b] = 256-token chunks of the sequences before b, cstart[B] = all of them
@@ -300,6 +302,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
 int rkv_mfma_share(int heads_per_kv_head);
 // a reorder over the whole token row (rkv_decode_row.hip): its scores kernel and the buffer it fills
 bool rkv_row_supported(const rkv_cache* c);
+int rkv_append_mfma_variant(const rkv_cache* c);   // RKV_KERNEL_* of the matrix-core append kernel a cache takes
 size_t rkv_row_scores_bytes(int batch, int n_q_heads, int max_tokens);
 int rkv_launch_scores_row(const rkv_cache* c, const float* qr, float* sc, hipStream_t s);
 size_t rkv_partial_bytes(int batch, int n_q_heads, int Tpad);

@@ -164,14 +164,14 @@ def test_reorder_across_blocks(span_kind):
     cfg = R.RkvConfig(batch=1, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=span)
     perm = calibrated_perm(w, cfg, offset_variant=True)
     assert not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
-    # a reorder inside the rotation group has a variant of both matrix-core kernels; across groups the read
-    # half has one (the scores from a kernel of their own), the write half takes the general kernel
+    # a reorder inside the rotation group has a variant of both matrix-core kernels, and so has one across groups
+    # (read half: the scores from a kernel of their own; write half: the keys from one that sees whole token rows)
     cache, _, _ = full_check(w, cfg, 100, perm=perm, paths=(1, 2), sink_positions=[])
     cache.set_decode_path(0)
     if span_kind == "group":
         assert cache.decode_kernel() == RB.KERNEL_MFMA_CROSS and cache.append_kernel() == RB.KERNEL_MFMA_CROSS
     else:
-        assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_GENERAL
+        assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_MFMA_ROW
 
 
 @pytest.mark.parametrize("g,hq,style", [(4, 8, 0), (2, 8, 0), (4, 32, 0), (2, 16, 1), (4, 8, 1), (4, 64, 0)])
@@ -182,7 +182,8 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
     the matrix-core decode kernel - against the oracle and the general kernel: rotation over 4 and 2
     heads, GQA up to 8 query heads per KV head, both RoPE pairings, several chunks and a ragged
     tail, with and without retained sink rows, the current token as an exact row, single-token
-    steps, a cache cut back by rkv_cache_truncate, the work space built into the library."""
+    steps, sequences of different lengths, the work space built into the library.  The write half
+    of this setting: k_append_row_keys (the quantization blocks span all rotation groups of a token)."""
     w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
     cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=g, perm_span=1024, rope_style=style)
     perm = calibrated_perm(w, cfg, offset_variant=True)
@@ -190,7 +191,7 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
     cache, oc, q = full_check(w, cfg, 613, perm=perm, chunks=[0, 300, 301, 613], paths=(1, 2),
                               sink_positions=None if (g, hq, style) in ((4, 8, 0), (2, 16, 1)) else [])
     cache.set_decode_path(2)
-    assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_GENERAL
+    assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_MFMA_ROW
     k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
     out = cache.decode_attention(P.gpu(q), k_cur=P.gpu(k1[:, 0]), v_cur=P.gpu(v1[:, 0]))      # the cache holds the oracle's codes here
     torch.cuda.synchronize()
@@ -214,17 +215,34 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
     assert P.attention_error(o_row.cpu().numpy().astype(np.float64), o_gen.cpu().numpy().astype(np.float64)) <= 1e-4
     assert float((l_row - l_gen).abs().max()) <= 1e-4
     assert torch.equal(o_st, o_row)
-    # per-sequence lengths are a path of the matrix-core append kernel, which this setting does not take: refused,
-    # while cutting all sequences back to one length works and the read half follows
-    with pytest.raises(R.RkvError):
-        cache.truncate([500, 133])
-    cache.truncate([133, 133])
+    # sequences of different lengths: a cache cut back, then one filled by rkv_quantize_append_ragged
+    cache.truncate([500, 133])
+    assert cache.lengths == [500, 133]
     o_row = cache.decode_attention(P.gpu(q))
     cache.set_decode_path(1)
     o_gen = cache.decode_attention(P.gpu(q))
     torch.cuda.synchronize()
-    assert cache.lengths == [133, 133]
     assert P.attention_error(o_row.cpu().numpy().astype(np.float64), o_gen.cpu().numpy().astype(np.float64)) <= 1e-4
+    k, v, mask = S.make_kv(w, 60, batch=2)
+    rag = R.RkvCache(cfg)
+    rag.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+    rag.quantize_append_ragged(P.gpu(k[:, :50]), P.gpu(v[:, :50]), [50, 21], P.gpu(mask[:, :50]))
+    rag.quantize_append_ragged(P.gpu(k[:, 50:60]), P.gpu(v[:, 50:60]), [3, 10], None)
+    assert rag.lengths == [53, 31]
+    o_rag = rag.decode_attention(P.gpu(q))
+    g_rag = P.export_numpy(rag)
+    torch.cuda.synchronize()
+    for bb, parts in enumerate([[(0, 50), (50, 53)], [(0, 21), (50, 60)]]):     # each sequence alone in the oracle
+        oc1 = O.cache_new(P.oracle_cfg(dataclasses.replace(cfg, batch=1)), perm)
+        for a_, b_ in parts:
+            O.quantize_append(oc1, k[bb:bb + 1, a_:b_], v[bb:bb + 1, a_:b_], mask[bb:bb + 1, a_:b_] if a_ == 0 else None)
+        n_b = oc1.length
+        gb = {name: arr[bb:bb + 1, :n_b] for name, arr in g_rag.items()}
+        P.compare_codes(oc1.k_rot, oc1.k_codes, oc1.k_scale, oc1.k_zero, gb["k_codes"], gb["k_scale"], gb["k_zero"],
+                        f"whole-row ragged b={bb} K", rot_span=cfg.E)
+        P.compare_codes(oc1.v_in, oc1.v_codes, oc1.v_scale, oc1.v_zero, gb["v_codes"], gb["v_scale"], gb["v_zero"], f"whole-row ragged b={bb} V")
+        ref, _ = O.decode_attention(oracle_from_export(oc1, gb), q[bb:bb + 1])
+        assert P.attention_error(o_rag[bb:bb + 1].cpu().numpy().astype(np.float64), ref) <= ATT_TOL
 
 
 @pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
@@ -476,7 +494,7 @@ def test_full_size_config2_whole_row_reorder_sampled(with_sinks):
     assert not np.array_equal(perm // 512, np.arange(cfg.E) // 512)
     cache = R.RkvCache(cfg)
     cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
-    assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW
+    assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_MFMA_ROW
     sampled = (3, 15)
     keep, k_parts, v_parts, m_parts = {}, [], [], []
     print("[case] full-size config 2, whole-row reorder: generating inputs per sequence", flush=True)
