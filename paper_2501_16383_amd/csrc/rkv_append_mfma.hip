@@ -141,15 +141,17 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   constexpr float QMAX = HI ? 15.0f : (H1 ? 7.0f : 3.0f), INV_QMAX = HI ? 0.06666667f : (H1 ? 0.14285715f : 0.33333334f);
   constexpr int NSB = SUB ? SUB : 1, GM = G * NSB;      // quantization blocks per 128-block, per rotation group
   static_assert(SUB == 0 || (HB == 0 && !XW), "groups of 64 / 32: 2-bit codes, reorder inside the heads");
+  static_assert(!XW || HB == 0, "a reorder across blocks: 2-bit codes");
+  constexpr bool OWN = SUB != 0 || XW;          // every element looks up its own quantization block (keys)
   __shared__ uint32_t meta[32 * GM];
-  __shared__ float2 s_mm[SUB ? 1 : 2][SUB ? 1 : 2][SUB ? 1 : 16][SUB ? 1 : G];   // [dword half][product pair][token][head] (min, max) of a quarter block
+  __shared__ float2 s_mm[OWN ? 1 : 2][OWN ? 1 : 2][OWN ? 1 : 16][OWN ? 1 : G];   // [dword half][product pair][token][head] (min, max) of a quarter block
   // groups of 64 / 32: extrema of the tile [lane group q][token][block] (a copy per lane group, so
   // that the four lanes of a token never meet on one word; rows padded to an odd length, so that the
   // 64 lanes of an instruction spread over the banks) and [token][block] (reciprocal scale, constant
   // added, base) of Eq. 6
   constexpr int GMP = GM + 1;
-  __shared__ float s_mn[SUB ? 64 * GMP : 1], s_mx[SUB ? 64 * GMP : 1];
-  __shared__ float4 s_par[SUB ? 16 * GMP : 1];
+  __shared__ float s_mn[OWN ? 64 * GMP : 1], s_mx[OWN ? 64 * GMP : 1];
+  __shared__ float4 s_par[OWN ? 16 * GMP : 1];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: everything that depends only on it stays scalar
   const int role = bx % 3;                     // 0, 1: the keys of K tile 0 / 1 of a slab; 2: the slab's values
@@ -187,7 +189,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         reinterpret_cast<uint4*>(lds)[m * STRIDE16 + lane % ROW16] = st[k];
       }
     }
-    if constexpr (SUB != 0) {
+    if constexpr (OWN) {
       static_assert(16 * GM <= 256, "one thread per (token, block) of a tile");
       for (int i = tid; i < 64 * GMP; i += 256) {
         s_mn[i] = 3.0e38f;
@@ -256,39 +258,22 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
     }
     // cross-block variant: quantization block (within the group) of each of the lane's channels, 2 bits each
     uint32_t gsel[G];
-    if constexpr (SUB != 0) {
+    if constexpr (OWN) {
+      // the block of each of the lane's channels, 2 bits each (a per-cache table written by rkv_set_perm):
+      // the sub-block inside the head (groups of 64 / 32), or the quantization block of the rotation group
+      // (a reorder across blocks: any head's channel may belong to it)
 #pragma unroll
-      for (int h = 0; h < G; ++h) gsel[h] = v.xgsel[(((size_t)rg * 4 + wave) * 4 + q) * G + h];   // sub-block of each channel
+      for (int h = 0; h < G; ++h) gsel[h] = v.xgsel[(((size_t)rg * 4 + wave) * 4 + q) * G + h];
 #pragma unroll
       for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
-            const int blk = (q * 16 + col) * GMP + h * SUB + (int)((gsel[h] >> (2 * (4 * ppl + rr))) & 3u);
+            const int blk = (q * 16 + col) * GMP + (SUB ? h * SUB : 0) + (int)((gsel[h] >> (2 * (4 * ppl + rr))) & 3u);
             lds_fmin(&s_mn[blk], acc[h][ppl][rr]);
             lds_fmax(&s_mx[blk], acc[h][ppl][rr]);
           }
-    } else if constexpr (XW) {
-#pragma unroll
-      for (int h = 0; h < G; ++h) gsel[h] = v.xgsel[(((size_t)rg * 4 + wave) * 4 + q) * G + h];   // written by rkv_set_perm
-#pragma unroll
-      for (int gq = 0; gq < G; ++gq) {
-        float mn = 3.0e38f, mx = -3.0e38f;
-#pragma unroll
-        for (int h = 0; h < G; ++h)
-#pragma unroll
-          for (int ppl = 0; ppl < 2; ++ppl)
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-              const bool mine = ((gsel[h] >> (2 * (4 * ppl + rr))) & 3u) == (uint32_t)gq;
-              mn = mine ? fminf(mn, acc[h][ppl][rr]) : mn;
-              mx = mine ? fmaxf(mx, acc[h][ppl][rr]) : mx;
-            }
-        mn = fminf(mn, __shfl_xor(mn, 16)); mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mn = fminf(mn, __shfl_xor(mn, 32)); mx = fmaxf(mx, __shfl_xor(mx, 32));
-        if (q == 0) s_mm[d][pph][col][gq] = make_float2(mn, mx);
-      }
     } else {
       // min / max of this wave's quarter of every block: 8 values in the lane, then the four q groups
 #pragma unroll
@@ -307,7 +292,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       }
     }
     __syncthreads();
-    if constexpr (SUB != 0) {
+    if constexpr (OWN) {
       // Eq. 8-9 per (token, block), one thread each; Eq. 6 with each element's own block's parameters
       if (tid < 16 * GM) {
         const int tk = tid / GM, bk = tid - tk * GM;
@@ -318,7 +303,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
           mx = fmaxf(mx, s_mx[(qq * 16 + tk) * GMP + bk]);
         }
         float sc, zero_b, inv, base_b, add_b;
-        quant_params_nodiv(mn * rs, mx * rs, sc, zero_b, inv, false, INV_QMAX);
+        quant_params_nodiv(mn * rs, mx * rs, sc, zero_b, inv, v.meta8, INV_QMAX);
         fused_round_consts(zero_b, base_b, add_b);
         s_par[tk * GMP + bk] = make_float4(inv * rs, add_b, base_b, 0.f);
         meta[tid] = rkv_pack_meta(sc, zero_b);
@@ -331,7 +316,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
-            const float4 pr = s_par[col * GMP + a * SUB + (int)((gsel[a] >> (2 * (4 * ppl + rr))) & 3u)];
+            const float4 pr = s_par[col * GMP + (SUB ? a * SUB : 0) + (int)((gsel[a] >> (2 * (4 * ppl + rr))) & 3u)];
             const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + 3.0f);
             word += (__float_as_uint(c) - __float_as_uint(pr.z)) << (16 * ppl + 4 * rr);
           }
@@ -350,37 +335,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
       if (wave == 0 && q < G) meta[col * G + ah] = rkv_pack_meta(sc, zero_h);
       float base_h, add_h;
       fused_round_consts(zero_h, base_h, add_h);
-      if constexpr (XW) {
-        // the parameters of all G quantization blocks of this token, then each element takes its own
-        float inv2s[G], adds[G], bases[G];
-#pragma unroll
-        for (int gq = 0; gq < G; ++gq) {
-          const int src4 = 4 * (col + 16 * gq);
-          inv2s[gq] = lane_read(inv2_h, src4);
-          adds[gq] = lane_read(add_h, src4);
-          bases[gq] = lane_read(base_h, src4);
-        }
-#pragma unroll
-        for (int a = 0; a < G; ++a) {
-          uint32_t word = 0;
-#pragma unroll
-          for (int ppl = 0; ppl < 2; ++ppl)
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-              const uint32_t gq = (gsel[a] >> (2 * (4 * ppl + rr))) & 3u;
-              float inv2 = inv2s[0], add = adds[0], base = bases[0];
-#pragma unroll
-              for (int k = 1; k < G; ++k) {
-                inv2 = gq == (uint32_t)k ? inv2s[k] : inv2;
-                add = gq == (uint32_t)k ? adds[k] : add;
-                base = gq == (uint32_t)k ? bases[k] : base;
-              }
-              const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], inv2, add), base, base + 3.0f);
-              word += (__float_as_uint(c) - __float_as_uint(base)) << (16 * ppl + 4 * rr);
-            }
-          img[pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = word << (2 * pph);
-        }
-      } else {
+      {
 #pragma unroll
       for (int a = 0; a < G; ++a) {
         const int src4 = 4 * (col + 16 * a);
