@@ -262,6 +262,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   __shared__ int s_sink[64];
   __shared__ uint4 s_H[8][64];                   // Hadamard operand tiles
   __shared__ float2 s_step[64];                  // RoPE rotation by 16 positions, per channel pair
+  __shared__ float2 s_step1[REP > 1 ? 64 : 1];   // ... by one position (several query heads per KV head)
   __shared__ int s_lim[MULTI ? NH : 1];          // last position each served query head may attend
   constexpr int QV = REP == 1 ? 4 : 1;            // query versions held (positions pos - r); with REP > 1 only r = 0
   __shared__ uint4 s_q[QV][4][NH / 2][16];        // [r][p][f / 4][n] x 4 floats f % 4, f = (KV head * REP + query head of it) * 2 + (lo, hi)
@@ -374,15 +375,9 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   //    budget) the other three tokens follow by rotating one position at a time (table row 1).  The
   //    next tile follows by rotating 16 positions (table row 16; used once per tile, read from LDS)
   const float2 ld_step = v.rope[(REP == 1 ? 16 : 12) * 64 + (tid & 63)];
-  float s1_c[4], s1_s[4];
-  if constexpr (REP > 1) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const float2 s1 = v.rope[64 + 16 * p + n];
-      s1_c[p] = s1.x;
-      s1_s[p] = s1.y;
-    }
-  }
+  //    (the one-position rotation: table row 1, kept in LDS as well - eight registers less where they are scarce)
+  float2 ld_step1 = make_float2(0.f, 0.f);
+  if constexpr (REP > 1) ld_step1 = v.rope[64 + (tid & 63)];
   //  - the sink list: positions unconditionally (the store holds max_sinks of them, unused ones -1), masked by the count below
   const int ld_cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
   const int ld_spos = (v.max_sinks > 0 && (tid & 63) < v.max_sinks) ? v.sink_pos[b * v.max_sinks + (tid & 63)] : -1;
@@ -535,6 +530,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       if (tid + 256 * i < Q16) (&s_q[0][0][0][0])[tid + 256 * i] = ld_q[i];
       if (tid < 64) {
         s_step[tid] = ld_step;
+        if constexpr (REP > 1) s_step1[tid] = ld_step1;
         s_sink[tid] = tid < cnt ? ld_spos : -1;              // complete after the barrier that precedes the key phase
       }
       if constexpr (!LM) {                                   // every wave clears its own 64 score slots
@@ -885,8 +881,9 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
               }
             }
             if constexpr (REP > 1) {                           // next token: one position further
-              const float c1 = c * s1_c[p] - s * s1_s[p];
-              s = s * s1_c[p] + c * s1_s[p];
+              const float2 s1 = s_step1[16 * p + n];
+              const float c1 = c * s1.x - s * s1.y;
+              s = s * s1.x + c * s1.y;
               c = c1;
             }
           }
