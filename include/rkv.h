@@ -62,7 +62,7 @@ typedef struct rkv_config {
                         /* codes with fp16 metadata and a reorder inside the heads (other        */
                         /* settings of those groups take the general kernels, which means no     */
                         /* keys_rotated, no rkv_quantize_append_ragged and a two-kernel          */
-                        /* rkv_decode_step); rkv_decode_attention_multi needs groups of 128      */
+                        /* rkv_decode_step)                                                      */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
                         /* printed sorts the whole row).  The append kernel for a reorder across */
@@ -245,8 +245,11 @@ int rkv_decode_step(rkv_cache* cache, const void* dev_k, const void* dev_v, cons
  *   dev_out    [batch][n_queries][n_q_heads][head_dim] fp32
  *   dev_lse    [batch][n_queries][n_q_heads] fp32, or NULL
  *   dev_scratch >= n_queries * scratch_bytes of rkv_query_sizes
- * Matrix-core decode path only: RKV_EINVAL for a configuration it does not cover (see
- * rkv_set_decode_path) or when the general kernel is forced; RKV_ESTATE on an empty cache. */
+ * Runs on the plain matrix-core decode kernel where the configuration has it (reorder inside
+ * blocks of 128, rot_heads 2 or 4, groups of 128); any other configuration takes the general
+ * kernel, which serves at most 8 (query token, query head) pairs per KV head: RKV_EINVAL beyond
+ * that, or when rkv_set_decode_path(2) forces a matrix-core kernel the configuration does not
+ * have for several query tokens; RKV_ESTATE on an empty cache. */
 #define RKV_MAX_QUERIES 64
 int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, int32_t n_queries,
                                float* dev_out, float* dev_lse, void* dev_scratch, void* stream);
@@ -270,7 +273,7 @@ int rkv_set_decode_path(rkv_cache* cache, int32_t path);
  * caller - or a test - that counts on the matrix-core kernels can assert it instead of finding
  * out from the timing.  Returns one of the RKV_KERNEL_* values, or RKV_EINVAL where the call
  * itself would (rkv_set_decode_path(2) outside the matrix-core kernels' coverage, several query
- * tokens outside the plain matrix-core kernel's). */
+ * tokens beyond what the general kernel serves). */
 #define RKV_KERNEL_GENERAL    1  /* vector-ALU kernels: any supported configuration                  */
 #define RKV_KERNEL_SHUFFLE    2  /* append only: FWHT in registers (v_rotate = 1, reorder in blocks)  */
 #define RKV_KERNEL_MFMA       3  /* matrix-core kernels: reorder inside blocks of 128, rot_heads 2, 4 */

@@ -387,7 +387,13 @@ RKV_EXPORT int rkv_set_decode_path(rkv_cache* cache, int32_t path) {
 RKV_EXPORT int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries) {
   if (!cache || n_queries < 0 || n_queries > RKV_MAX_QUERIES) return RKV_EINVAL;
   const int kind = rkv_mfma_supported(cache) ? rkv_mfma_variant(cache) : RKV_KERNEL_GENERAL;
-  if (n_queries > 0) return kind == RKV_KERNEL_MFMA && cache->decode_path != 1 ? kind : RKV_EINVAL;   // multi-query: plain matrix-core kernel only
+  if (n_queries > 0) {
+    // several query tokens per step: the plain matrix-core kernel, else the general one, which serves up to
+    // 8 (query token, query head) pairs per KV head
+    if (kind == RKV_KERNEL_MFMA && cache->decode_path != 1) return kind;
+    if (cache->decode_path >= 2) return RKV_EINVAL;
+    return (cache->v.Hq / cache->v.Hkv) * n_queries <= 8 ? RKV_KERNEL_GENERAL : RKV_EINVAL;
+  }
   if (cache->decode_path == 1) return RKV_KERNEL_GENERAL;
   if (cache->decode_path >= 2 && kind == RKV_KERNEL_GENERAL) return RKV_EINVAL;
   return kind;
@@ -552,7 +558,7 @@ RKV_EXPORT int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const i
   if (fast)
     return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, 0, dev_out, dev_lse, dev_scratch, false,
                                   (hipStream_t)stream);
-  return rkv_launch_decode_general(cache, (const __half*)dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
+  return rkv_launch_decode_general(cache, (const __half*)dev_q, dev_q_pos, 0, dev_out, dev_lse, dev_scratch, (hipStream_t)stream);
 }
 
 RKV_EXPORT int rkv_decode_attention_static(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, float* dev_out,
@@ -606,7 +612,11 @@ RKV_EXPORT int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, c
   if (cache->ragged)
     for (int b = 0; b < cache->v.B; ++b)
       if (cache->hlens[b] < 1) return RKV_ESTATE;
-  if (!rkv_mfma_supported(cache) || cache->decode_path == 1) return RKV_EINVAL;   // matrix-core path only
+  const int kind = rkv_decode_kernel_of(cache, n_queries);
+  if (kind < 0) return kind;
+  if (kind == RKV_KERNEL_GENERAL)
+    return rkv_launch_decode_general(cache, (const __half*)dev_q, dev_q_pos, n_queries, dev_out, dev_lse, dev_scratch,
+                                     (hipStream_t)stream);
   return rkv_launch_decode_mfma(cache, (const __half*)dev_q, dev_q_pos, n_queries, dev_out, dev_lse, dev_scratch, false,
                                 (hipStream_t)stream);
 }

@@ -46,8 +46,11 @@ __device__ inline bool is_sink(const int* sp, int cnt, int t) {
 }
 
 // WIDE: codes of 3 or 4 bits (a second plane of bits is read)
+// q_lim, nqt: several query tokens per sequence (else null, 1): v.Hq then counts virtual heads (nqt per
+// real head, see rkv_virtual_head) and a virtual head only attends tokens at positions <= q_lim[b][its token]
 template <int PL, bool WIDE>
-__global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __restrict__ qr, float* __restrict__ part, int nch) {
+__global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __restrict__ qr, float* __restrict__ part, int nch,
+                                                    const int* __restrict__ q_lim, int nqt) {
   // LDS: q~ of this group's query heads, scores / probabilities, V meta, per-head stats
   extern __shared__ float sm[];
   const int rep = v.Hq / v.Hkv, g = v.g, n = v.n;
@@ -137,7 +140,9 @@ __global__ void __launch_bounds__(256) k_decode_gen(RkvView v, const float* __re
 #pragma unroll
       for (int i = 0; i < PL; ++i) d += y[i] * qh[i];
       for (int s = 1; s < lanes_per_head; s <<= 1) d += __shfl_xor(d, s);
-      if ((lane & (lanes_per_head - 1)) == 0) s_p[(hh * rep + r) * GEN_CHUNK + (t - t0)] = sink ? -INFINITY : d;
+      // (virtual head r of a KV head belongs to query token r / (real heads per KV head))
+      const bool hidden = sink || (q_lim && t > q_lim[b * nqt + r / (rep / nqt)]);
+      if ((lane & (lanes_per_head - 1)) == 0) s_p[(hh * rep + r) * GEN_CHUNK + (t - t0)] = hidden ? -INFINITY : d;
     }
   }
   for (int i = tid; i < gm * GEN_CHUNK; i += 256) {
@@ -406,18 +411,26 @@ size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
   return bytes;
 }
 
-int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
+// n_queries == 0: the usual step.  n_queries >= 1: that many query tokens per sequence, token i at
+// position q_pos[b][i] and blind to cached tokens behind it (q, out, lse [batch][n_queries][heads][...];
+// the scratch buffer holds n_queries times the single-query size); at most 8 virtual heads per KV head.
+int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, int n_queries, float* out, float* lse, void* scratch,
                               hipStream_t s) {
-  const RkvView& v = c->v;
+  const bool multi = n_queries > 0;
+  if (multi && (c->cur_k || !q_pos)) return RKV_EINVAL;
+  const int nqt = multi ? n_queries : 1;
+  RkvView v = c->v;
+  v.Hq *= nqt;                                              // virtual heads
+  if (v.Hq / v.Hkv > 8) return RKV_EINVAL;
   float* qr = (float*)scratch;
   const size_t qbytes = rkv_query_scratch_bytes(v.B, v.Hq);
   float* part = (float*)((char*)scratch + qbytes);
   const int nch = (v.len + GEN_CHUNK - 1) / GEN_CHUNK;
-  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, 1, 1, s);
+  rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, 1, nqt, s);
   const int rep = v.Hq / v.Hkv, nq = rep * v.g;
   const size_t lds = ((size_t)nq * RKV_D + (size_t)nq * GEN_CHUNK + 2 * (size_t)v.gm * GEN_CHUNK + 2 * nq) * 4;
   dim3 grid(nch, v.NRG, v.B);
-  void (*fn)(RkvView, const float*, float*, int) = nullptr;
+  void (*fn)(RkvView, const float*, float*, int, const int*, int) = nullptr;
   switch (v.n / 64) {
     case 2: fn = v.hb ? k_decode_gen<2, true> : k_decode_gen<2, false>; break;
     case 4: fn = v.hb ? k_decode_gen<4, true> : k_decode_gen<4, false>; break;
@@ -427,8 +440,9 @@ int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, f
   }
   if (lds > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-  if (nch > 0) hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, qr, part, nch);   // an empty cache has only the current token
+  if (nch > 0)                                              // (an empty cache has only the current token)
+    hipLaunchKernelGGL(fn, grid, dim3(256), lds, s, v, qr, part, nch, multi ? q_pos : (const int*)nullptr, nqt);
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
-  rkv_launch_merge(v, qr, part, nch, GEN_CHUNK, c->cur_k, c->cur_v, nullptr, 1, out, lse, s);
+  rkv_launch_merge(v, qr, part, nch, GEN_CHUNK, c->cur_k, c->cur_v, multi ? q_pos : nullptr, nqt, out, lse, s);
   return rkv_check_launch();
 }

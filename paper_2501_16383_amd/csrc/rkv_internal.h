@@ -295,7 +295,7 @@ int rkv_launch_dequant(rkv_cache* c, float* k_hat, float* v_hat, hipStream_t s);
 int rkv_launch_export(rkv_cache* c, uint8_t* kc, float* ks, float* kz, uint8_t* vc, float* vs, float* vz, hipStream_t s);
 int rkv_launch_import(rkv_cache* c, int T, const uint8_t* kc, const float* ks, const float* kz, const uint8_t* vc,
                       const float* vs, const float* vz, hipStream_t s);
-int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, float* out, float* lse, void* scratch,
+int rkv_launch_decode_general(rkv_cache* c, const __half* q, const int* q_pos, int n_queries, float* out, float* lse, void* scratch,
                               hipStream_t s);
 int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int nq, float* out, float* lse, void* scratch,
                            bool q_prepared, hipStream_t s);

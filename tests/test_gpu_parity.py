@@ -174,6 +174,26 @@ def test_reorder_across_blocks(span_kind):
         assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_MFMA_ROW
 
 
+def check_multi_on_general_kernel(cache, oc, q, hq, hkv, tag):
+    """Two causal query tokens per sequence on a configuration without the plain matrix-core kernel:
+    rkv_decode_attention_multi takes the general kernel (at most 8 (query token, query head) pairs
+    per KV head; refused beyond).  Against the oracle on the GPU's own codes."""
+    q2 = np.stack([q, q[::-1].copy()], axis=1)
+    q_pos = np.array([[600, 601], [300, 612]], dtype=np.int32)
+    if (hq // hkv) * 2 > 8:
+        with pytest.raises(R.RkvError):
+            cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
+        return
+    assert cache.decode_kernel(2) == RB.KERNEL_GENERAL
+    out, lse = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos), want_lse=True)
+    torch.cuda.synchronize()
+    ref, lse_ref = O.decode_attention_multi(oracle_from_export(oc, P.export_numpy(cache)), q2, q_pos)
+    e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
+    le = float(np.abs(lse.cpu().numpy() - lse_ref).max())
+    print(f"[parity] {tag}: two query tokens on the general kernel: out err {e:.3e} lse err {le:.3e}", flush=True)
+    assert e <= ATT_TOL and le <= LSE_TOL
+
+
 @pytest.mark.parametrize("g,hq,style", [(4, 8, 0), (2, 8, 0), (4, 32, 0), (2, 16, 1), (4, 8, 1), (4, 64, 0)])
 def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
     """perm_span = the whole token row (Alg. 1 as printed): a rotated channel belongs to any of the
@@ -202,8 +222,8 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
     O.quantize_append(oc, k1, v1, None)
     ref, _ = O.decode_attention(oracle_from_export(oc, P.export_numpy(cache)), q)
     assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
-    with pytest.raises(R.RkvError):                              # several query tokens: not on this path
-        cache.decode_attention_multi(P.gpu(np.stack([q, q], axis=1)), P.gpu(np.array([[600, 601], [600, 601]], dtype=np.int32)))
+    cache.set_decode_path(0)
+    check_multi_on_general_kernel(cache, oc, q, hq, 8, f"whole-row reorder g={g} hq={hq}")
     # against the general kernel on the same cache, and on the work space built into the library
     cache.set_decode_path(1)
     o_gen, l_gen = cache.decode_attention(P.gpu(q), want_lse=True)
@@ -272,7 +292,10 @@ def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style, fmt):
     O.quantize_append(oc, k1, v1, None)
     ref, _ = O.decode_attention(oracle_from_export(oc, P.export_numpy(cache)), q)
     assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
-    with pytest.raises(R.RkvError):                              # several query tokens: not in this variant
+    cache.set_decode_path(0)
+    check_multi_on_general_kernel(cache, oc, q, hq, 8, f"cross-block reorder g={g} hq={hq} fmt={fmt}")
+    cache.set_decode_path(2)
+    with pytest.raises(R.RkvError):                              # (no matrix-core variant for several query tokens here)
         cache.decode_attention_multi(P.gpu(np.stack([q, q], axis=1)), P.gpu(np.array([[600, 601], [600, 601]], dtype=np.int32)))
     # sequences of different lengths, and the one-call step against the two calls, bit for bit
     k, v, mask = S.make_kv(w, 40, batch=2)
@@ -973,10 +996,17 @@ def test_several_query_tokens_per_step(hq, hkv, g, nq, bits):
         out1 = cache.decode_attention(P.gpu(q[:, 0]))
         torch.cuda.synchronize()
         assert float((out1 - out[:, 0]).abs().max()) <= 1e-6 * float(out1.abs().max())
-    # what the entry point refuses
+    # the general kernel serves the same call (up to 8 (query token, query head) pairs per KV head)
     cache.set_decode_path(1)
+    assert (hq // hkv) * nq <= 8 and cache.decode_kernel(nq) == RB.KERNEL_GENERAL
+    out_g, lse_g = cache.decode_attention_multi(P.gpu(q), P.gpu(q_pos), want_lse=True)
+    torch.cuda.synchronize()
+    assert P.attention_error(out_g.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
+    assert float(np.abs(lse_g.cpu().numpy() - lse_ref).max()) <= LSE_TOL
+    # what the entry point refuses there: more pairs than that
+    q9 = np.repeat(q[:, :1], 9, axis=1)
     with pytest.raises(R.RkvError):
-        cache.decode_attention_multi(P.gpu(q), P.gpu(q_pos))
+        cache.decode_attention_multi(P.gpu(q9), P.gpu(np.repeat(q_pos[:, :1], 9, axis=1)))
 
 
 @pytest.mark.parametrize("hq,hkv,g,style", [(8, 8, 4, 0), (4, 4, 2, 0), (16, 4, 4, 0), (8, 8, 1, 0), (8, 8, 4, 1), (8, 8, 8, 0)])
@@ -1161,9 +1191,14 @@ def test_sequences_of_different_lengths(bits, group):
             ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
             e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
             assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
-    else:                       # the sub-group variant of the decode kernel takes one query token per step
-        with pytest.raises(R.RkvError):
-            cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
+    else:                       # the sub-group variant of the decode kernel takes one query token per step: the general kernel serves
+        assert cache.decode_kernel(2) == RB.KERNEL_GENERAL
+        out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
+        torch.cuda.synchronize()
+        for b in range(B):
+            ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
+            e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
+            assert e <= ATT_TOL, f"two query tokens on the general kernel, b={b}: {e}"
     # what the entry point refuses
     with pytest.raises(R.RkvError) as ei:
         cache.quantize_append_ragged(P.gpu(np.zeros((B, 50, 8, 128), np.float16)), P.gpu(np.zeros((B, 50, 8, 128), np.float16)), [1, 1, 50])
