@@ -70,7 +70,9 @@ typedef struct rkv_config {
                         /* of 16 tokens in LDS: 24 U bytes (30 U with 3-bit, 32 U with 4-bit     */
                         /* codes) must not exceed 160 KB, else RKV_EINVAL from rkv_query_sizes   */
                         /* and rkv_cache_create (whole-row reorder: at most 53 KV heads, 40 with */
-                        /* 4-bit codes)                                                           */
+                        /* 4-bit codes).  Not so where every reorder has a matrix-core append    */
+                        /* kernel (2-bit codes, quant_group 128, rot_heads 2 or 4, v_rotate 0,   */
+                        /* keys_rotated 0): up to 127 KV heads                                    */
   int32_t rope_style;   /* 0: channel j pairs with j+64; 1: channel 2j pairs with 2j+1          */
   int32_t v_rotate;     /* 0: values are quantized as given (the caller has folded the value    */
                         /* rotation of Sec. 4.4 into its weights); 1: the library applies a      */

@@ -265,6 +265,18 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
         assert P.attention_error(o_rag[bb:bb + 1].cpu().numpy().astype(np.float64), ref) <= ATT_TOL
 
 
+def test_whole_row_reorder_with_many_heads():
+    """A row of 64 KV heads (8192 channels, 64 quantization blocks) under a reorder over the whole
+    row: beyond what the general append kernel's LDS holds (53 heads), within what the matrix-core
+    kernels for this reorder serve; both read paths against the oracle."""
+    w = small("cfg1", n_q_heads=64, n_kv_heads=64)
+    cfg = R.RkvConfig(batch=1, n_q_heads=64, n_kv_heads=64, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=64 * 128)
+    perm = calibrated_perm(w, cfg, offset_variant=True)
+    cache, _, _ = full_check(w, cfg, 90, perm=perm, chunks=[0, 40, 41, 90], paths=(1, 2), sink_positions=[])
+    cache.set_decode_path(0)
+    assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_MFMA_ROW
+
+
 @pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
 def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style, fmt):
     """perm_span = the rotation size: the quantization blocks mix channels of all the group's heads.

@@ -114,10 +114,12 @@ def test_physical_layout_is_a_bijection(lib, g, heads, tokens):
             assert all(len(v) == 1 for v in words.values()) and len(words) == g * 128     # token-minor: one word per channel
 
 
-@pytest.mark.parametrize("heads,bits,ok", [(52, 2, True), (56, 2, False), (40, 4, True), (44, 4, False), (52, 3, False), (40, 3, True)])
+@pytest.mark.parametrize("heads,bits,ok", [(52, 2, True), (56, 2, True), (124, 2, True), (128, 2, False), (40, 4, True), (44, 4, False),
+                                           (52, 3, False), (40, 3, True)])
 def test_whole_row_reorder_is_bounded_by_the_append_kernels_lds(lib, heads, bits, ok):
-    """A reorder over the whole row runs on the append kernel that stages the row in LDS: shapes
-    beyond a compute unit's 160 KB fail at rkv_query_sizes, not at the first append."""
+    """A reorder over the whole row with wider codes runs on the append kernel that stages the row
+    in LDS: shapes beyond a compute unit's 160 KB fail at rkv_query_sizes, not at the first append.
+    With 2-bit codes the matrix-core append kernel for such a reorder serves up to 127 KV heads."""
     cfg = R.RkvConfig(batch=1, n_q_heads=heads, n_kv_heads=heads, max_tokens=128, perm_span=heads * 128, bits=bits)
     if ok:
         R.query_sizes(cfg)
