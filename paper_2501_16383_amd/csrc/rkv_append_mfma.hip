@@ -578,14 +578,15 @@ __global__ void __launch_bounds__(256, 6) k_append_values(RkvView v, const __hal
 // come back from the last-level cache - and quantizes every element with its own block's
 // parameters.  Codes stay where they are, by rotated channel.  The quantization block of each of a
 // lane's channels comes from a per-cache table of bytes (xgid8, written by rkv_set_perm).
-// dynamic LDS: [16][NG | 1] float minima, the same of maxima, [16][NG | 1] float4 parameters.
+// dynamic LDS: [NG][16 tokens] float minima, the same of maxima, [NG][16] float4 parameters (block-major: the 16
+// tokens of a row of lanes, which share their channels and hence their blocks, touch 16 different LDS banks).
 template <int G>
 __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __half* __restrict__ kin, int n_new, int slab0) {
   constexpr int n = 128 * G;
   constexpr int ROW16 = 16 * G, STRIDE16 = ROW16 + 1;
   __shared__ __attribute__((aligned(16))) uint32_t lds[16 * STRIDE16 * 4];
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_row[];
-  const int NG = v.E >> 7, NGP = NG | 1;       // (rows of odd length: the tile's 16 tokens start in different banks)
+  const int NG = v.E >> 7, NGP = NG | 1;       // (the allocation counts NGP blocks)
   float* s_mn = reinterpret_cast<float*>(dyn_row);
   float* s_mx = s_mn + 16 * NGP;
   float4* s_par = reinterpret_cast<float4*>(dyn_row + (size_t)2 * 16 * NGP * 4);      // (128 NGP bytes in: 16-byte aligned)
@@ -695,7 +696,7 @@ __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __h
       for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-          const int blk = col * NGP + (int)(((ppl ? gb.y : gb.x) >> (8 * rr)) & 0xffu);
+          const int blk = (int)(((ppl ? gb.y : gb.x) >> (8 * rr)) & 0xffu) * 16 + col;
           lds_fmin(&s_mn[blk], acc[h][ppl][rr]);
           lds_fmax(&s_mx[blk], acc[h][ppl][rr]);
         }
@@ -705,11 +706,11 @@ __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __h
   // ---- Eq. 8-9 per (token, block)
   RKV_ROW_REQUEST(0);
   for (int e = tid; e < 16 * NG; e += 256) {
-    const int tk = e / NG, bk = e - tk * NG;
+    const int tk = e & 15, bk = e >> 4;
     float sc, zero_b, inv, base_b, add_b;
-    quant_params_nodiv(s_mn[tk * NGP + bk] * rs, s_mx[tk * NGP + bk] * rs, sc, zero_b, inv, v.meta8);
+    quant_params_nodiv(s_mn[e] * rs, s_mx[e] * rs, sc, zero_b, inv, v.meta8);
     fused_round_consts(zero_b, base_b, add_b);
-    s_par[tk * NGP + bk] = make_float4(inv * rs, add_b, base_b, 0.f);
+    s_par[e] = make_float4(inv * rs, add_b, base_b, 0.f);
     const int tau = 16 * ti + tk;
     if (tau >= tau_first && tau <= tau_last) rkv_store_meta(v, v.km, rkv_meta_index(v, b, ts + tau, bk), sc, zero_b);
   }
@@ -729,7 +730,7 @@ __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __h
       for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-          const float4 pr = s_par[col * NGP + (int)(((ppl ? gb.y : gb.x) >> (8 * rr)) & 0xffu)];
+          const float4 pr = s_par[(int)(((ppl ? gb.y : gb.x) >> (8 * rr)) & 0xffu) * 16 + col];
           const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + 3.0f);
           word += (__float_as_uint(c) - __float_as_uint(pr.z)) << (16 * ppl + 4 * rr);
         }

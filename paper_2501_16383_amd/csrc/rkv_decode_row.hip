@@ -298,6 +298,392 @@ __global__ void __launch_bounds__(256, 3) k_scores_row(RkvView v, const float* _
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same scores with one wave per tile of 16 tokens and no traffic of dequantized rows through
+// LDS (rows of at most 63 quantization blocks; the kernel above serves longer rows).
+//
+// A lane of the K tile's 16-byte load, (token, quarter q), holds exactly the codes the matrix
+// instruction wants from it as the B operand [k][token]: four channels per product, each as its
+// (hi, lo) pair of fp16 numbers in two neighbouring k slots (the A operand repeats its +-1 for
+// both, so the instruction adds the two parts by itself).  The pairs come ready-made from a table
+// in LDS, one dword (hi | lo << 16) per (token, quantization block, code), laid out [entry][token]
+// so that the 16 tokens of a row of lanes read 16 different banks whatever their codes are; the
+// byte address of a channel's entry is (block << 8 | code << 6 | token << 2): the block is a
+// per-layer constant that sits in a small table, four channels to a dword, the low byte is made
+// for four code fields of the stream at once, and one byte permute per channel joins the two.
+//
+// H_128 = H_8 (x) H_16: a product contracts the channel bits {1, 2} (the four channels of a lane's
+// dword) and {5, 6} (the quarter) against the same bits of the output channel (rows of A), and
+// the bits {0, 3, 4} by accumulation - the eight products of a head's eight steps s onto output
+// tile mt carry the sign (-1)^popc(mt & s), the same for every lane, i.e. A or -A.  A lane
+// (token, g4) of the result holds, per head, tiles mt = 0..7 x rows r = 0..3: output channel bits
+// 6 = r & 1, 5 = g4 >> 1, 4 3 0 = mt, 2 = g4 & 1, 1 = r >> 1 - both channels of a RoPE pair of either
+// pairing.  H_g over the heads is split: P0 = X0 + X1, P1 = X0 - X1 of a pair of heads go through
+// RoPE and are multiplied with the queries of the output heads that take them (a of the same
+// parity; the second pair of heads enters with the sign of H_g's second stage), so that only two
+// heads' results are in registers at a time.  The query values of a lane's 32 channels are spread
+// over the four lanes of its quad (the four lanes hold the same channels for different tokens) and
+// reach the multiply-adds through the quad-broadcast operand modifier.
+// Everything a wave touches between two tiles is its own (table, partial sums), so the tile loop
+// has no workgroup barrier.
+#ifndef RS2_TILES
+#define RS2_TILES 1                     // tiles of 16 tokens per wave (measured on config 2's geometry: 1: 157 us, 2: 171, 4: 175, 8: 180 -
+#endif                                  // short-lived waves drift apart, so one wave's matrix products run beside another's vector work)
+#define RS2_CHUNK (64 * RS2_TILES)      // tokens per workgroup
+#define RS2_MPRE 3                      // rounds of metadata (4 rotation groups x 16 tokens each) requested a tile ahead
+#ifndef RS2_OCC
+#define RS2_OCC 3                       // workgroups per compute unit the register budget is set for
+#endif
+#ifndef RS2_EARLY
+#define RS2_EARLY 0
+#endif
+#ifndef RS2_LOOK
+#define RS2_LOOK 4                      // steps looked up at a time (4 registers each)
+#endif
+#define RS2_MAX_NG 63                   // longest row in quantization blocks (a wave's table takes 256 bytes per block)
+
+// d += (q of lane U of the quad) * k.  The operand modifier reads q from another lane; the hardware wants two
+// instructions between a vector write of q and this read: q is loaded from LDS and pinned by rs2_settle below.
+typedef __attribute__((address_space(3))) unsigned char rs2_lds_u8;
+typedef __attribute__((address_space(3))) uint32_t rs2_lds_u32;
+
+template <int U>
+__device__ __forceinline__ void fmac_quad(float& d, float q, float k) {
+  if constexpr (U == 0) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf" : "+v"(d) : "v"(q), "v"(k));
+  if constexpr (U == 1) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf" : "+v"(d) : "v"(q), "v"(k));
+  if constexpr (U == 2) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf" : "+v"(d) : "v"(q), "v"(k));
+  if constexpr (U == 3) asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf" : "+v"(d) : "v"(q), "v"(k));
+}
+template <int U>
+__device__ __forceinline__ float fmul_quad(float q, float k) {       // (q of lane U of the quad) * k
+  float d;
+  if constexpr (U == 0) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf" : "=v"(d) : "v"(q), "v"(k));
+  if constexpr (U == 1) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf" : "=v"(d) : "v"(q), "v"(k));
+  if constexpr (U == 2) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf" : "=v"(d) : "v"(q), "v"(k));
+  if constexpr (U == 3) asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf" : "=v"(d) : "v"(q), "v"(k));
+  return d;
+}
+__device__ __forceinline__ void rs2_settle(float (&q)[2][4]) {
+  asm volatile("s_nop 1" : "+v"(q[0][0]), "+v"(q[0][1]), "+v"(q[0][2]), "+v"(q[0][3]), "+v"(q[1][0]), "+v"(q[1][1]), "+v"(q[1][2]), "+v"(q[1][3]));
+}
+
+#ifdef RS2_TS
+__device__ unsigned long long rs2_ts[8];
+extern "C" __attribute__((visibility("default"))) int rkv_dbg_ts(unsigned long long* out, int clear) {
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(rs2_ts), 64) != hipSuccess) return -1;
+  if (clear) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(rs2_ts), z, 64) != hipSuccess) return -1; }
+  return 0;
+}
+#define RS2_STAMP(i)                                                         \
+  do {                                                                       \
+    const unsigned long long now_ = __builtin_readcyclecounter();            \
+    ts_acc[i] += now_ - ts_last;                                             \
+    ts_last = now_;                                                          \
+  } while (0)
+#else
+#define RS2_STAMP(i)
+#endif
+// dynamic LDS: [4 waves][NG * 4 entries][16 tokens] dwords, [4 waves][G * rep][16] float partial sums, [G * rep][128] float
+// queries, [4 waves][4 * G * 8] dwords of block bytes, 64 sink positions
+template <int G, int STYLE>
+__global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const float* __restrict__ qr, float* __restrict__ sc, int rep) {
+  constexpr int n = 128 * G;
+  // (no static LDS in this kernel: the tables start where the workgroup's LDS starts, so that a table's byte
+  // address >> 8 plus a block index stays below 256 for rows of up to RS2_MAX_NG blocks)
+  extern __shared__ __attribute__((aligned(256))) unsigned char dyn2[];
+  const int NG = v.E >> 7, nqh = G * rep;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  uint32_t* s_tab = reinterpret_cast<uint32_t*>(dyn2) + (size_t)wave * NG * 64;
+  float* s_pd = reinterpret_cast<float*>(dyn2 + (size_t)4 * NG * 256) + wave * nqh * 16;
+  const float* s_qp = reinterpret_cast<const float*>(dyn2 + (size_t)4 * NG * 256 + (size_t)4 * nqh * 64);
+  // [wave][q][head][dword dw][shift ksh]: four channels' quantization blocks, a byte each, plus (the wave's table >> 8)
+  uint32_t* s_g4 = reinterpret_cast<uint32_t*>(dyn2 + (size_t)4 * NG * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4);
+  int* s_sink = reinterpret_cast<int*>(s_g4 + 4 * 4 * G * 8);
+#ifdef RS2_TS
+  unsigned long long ts_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ts_last = __builtin_readcyclecounter();
+#endif
+  const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
+  const int len = rkv_len(v, b);
+  const int t0 = chunk * RS2_CHUNK;
+  if (t0 >= len) return;                               // (the grid covers the longest sequence)
+  const int tok = lane & 15, kq = lane >> 4;           // B operand and result: (token, quarter / row group g4)
+  const uint32_t tokrep = 4u * tok * 0x01010101u;      // token << 2 in every byte
+  // A operand: lane (row m, k-group kg) holds +-1 for k = (channel j of the step, part): the sign is the parity of
+  // m0 & in6 ^ m3 & in5 ^ m1 & in1 ^ m2 & in2, in6 in5 = kg, in2 in1 = j
+  uint32_t a_pos[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int m = lane & 15, kg = lane >> 4;
+    const int sg = ((m & 1) & (kg >> 1)) ^ ((m >> 3) & (kg & 1)) ^ (((m >> 1) & 1) & (j & 1)) ^ (((m >> 2) & 1) & (j >> 1));
+    a_pos[j] = 0x3C003C00u ^ (sg ? 0x80008000u : 0u);
+  }
+  const v8h A_pos = row_v8h(a_pos[0], a_pos[1], a_pos[2], a_pos[3]);
+  const v8h A_neg = row_v8h(a_pos[0] ^ 0x80008000u, a_pos[1] ^ 0x80008000u, a_pos[2] ^ 0x80008000u, a_pos[3] ^ 0x80008000u);
+  const float out_scale = 64.0f * rsqrtf((float)n);        // the table's 1/64 and the normalisation of Eq. 10
+  const int g4hi = kq >> 1, g4lo = kq & 1, qu = lane & 3;
+  const int rounds = (v.NRG + 3) >> 2;
+
+  uint4 cw[G / 2];
+  uint32_t mw[RS2_MPRE][G];
+  const uint32_t roff = (uint32_t)(tok * 64 + (STYLE == 0 ? 32 * g4hi + 4 * g4lo : 16 * g4hi + 2 * g4lo));   // the lane's place in a tile's RoPE rows
+  const uint32_t moff = (uint32_t)(kq * v.Tpad + tok);   // metadata entry of (rotation group kq of a round, token), in units of G dwords
+  auto request = [&](int tt) {
+    const uint4* kt = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tt >> 4));
+#pragma unroll
+    for (int bp = 0; bp < G / 2; ++bp) cw[bp] = rkv_ld_stream(kt + 64 * bp + lane);
+#pragma unroll
+    for (int k = 0; k < RS2_MPRE; ++k) {
+      const int g2 = kq + 4 * k;
+      if (g2 < v.NRG) {
+        // (a base that is the same for all lanes plus a 32-bit lane offset: one register per lane, not an address pair)
+        const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt) * G;
+        if constexpr (G == 4) {
+          const uint4 u = reinterpret_cast<const uint4*>(mrow)[moff];
+          mw[k][0] = u.x; mw[k][1] = u.y; mw[k][2] = u.z; mw[k][3] = u.w;
+        } else {
+          const uint2 u = reinterpret_cast<const uint2*>(mrow)[moff];
+          mw[k][0] = u.x; mw[k][1] = u.y;
+        }
+      }
+    }
+  };
+  request(t0 + 16 * RS2_TILES * wave);                             // (in flight during the set-up)
+  const int cnt = v.max_sinks > 0 ? v.sink_cnt[b] : 0;
+  if (tid < 64) s_sink[tid] = tid < cnt ? v.sink_pos[b * v.max_sinks + tid] : -1;
+  if (tid < 4 * G * 8) {
+    const int q = tid / (8 * G), h = (tid >> 3) % G, dw = (tid >> 2) & 1, ksh = tid & 3;
+    const int c0 = 128 * h + 32 * q + 16 * dw + 8 * (ksh & 1) + (ksh >> 1);
+    uint32_t w = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w |= (uint32_t)v.gid[rg * n + c0 + 2 * j] << (8 * j);
+    const uint32_t tab0 = (uint32_t)(uintptr_t)(rs2_lds_u8*)dyn2;     // LDS byte address of the first table (a multiple of 256)
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) s_g4[ww * (4 * G * 8) + tid] = w + (((tab0 >> 8) + (uint32_t)(ww * NG)) * 0x01010101u);
+  }
+  {
+    float* qp = const_cast<float*>(s_qp);
+    for (int i = tid; i < nqh * RKV_D; i += 256) qp[i] = qr[((size_t)b * v.Hq + (size_t)rg * nqh) * RKV_D + i];
+  }
+  __syncthreads();
+
+  // the four table entries of one quantization block of the lane's token
+  auto put_block = [&](int blk, uint32_t word) {
+    float s_, z_;
+    rkv_unpack_meta(word, s_, z_);
+    s_ *= 0.015625f;
+    const float u0 = s_ * (0.f - z_), u1 = s_ * (1.f - z_), u2 = s_ * (2.f - z_), u3 = s_ * (3.f - z_);
+    const uint32_t h01 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(u0, u1));
+    const uint32_t h23 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(u2, u3));
+    float l0, l1, l2, l3;                                   // what the fp16 number misses (exact)
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(l0) : "v"(h01), "v"(u0));
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(l1) : "v"(h01), "v"(u1));
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(l2) : "v"(h23), "v"(u2));
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(l3) : "v"(h23), "v"(u3));
+    const uint32_t l01 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l0, l1));
+    const uint32_t l23 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l2, l3));
+    uint32_t* e = s_tab + (blk * 4) * 16 + tok;
+    e[0] = __builtin_amdgcn_perm(l01, h01, 0x05040100u);
+    e[16] = __builtin_amdgcn_perm(l01, h01, 0x07060302u);
+    e[32] = __builtin_amdgcn_perm(l23, h23, 0x05040100u);
+    e[48] = __builtin_amdgcn_perm(l23, h23, 0x07060302u);
+  };
+
+  RS2_STAMP(0);
+  for (int it = 0; it < RS2_TILES; ++it) {
+    const int tt = t0 + 16 * RS2_TILES * wave + 16 * it;
+    if (tt >= len) break;                                  // wave-uniform
+    // ---- the tile's table (the lanes of a wave write and read it in program order)
+#pragma unroll
+    for (int k = 0; k < RS2_MPRE; ++k) {
+      const int g2 = kq + 4 * k;
+      if (g2 < v.NRG) {
+#pragma unroll
+        for (int j = 0; j < G; ++j) put_block(g2 * G + j, mw[k][j]);
+      }
+    }
+    for (int k = RS2_MPRE; k < rounds; ++k) {
+      const int g2 = kq + 4 * k;
+      if (g2 < v.NRG) {
+        const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt) * G;
+#pragma unroll
+        for (int j = 0; j < G; ++j) put_block(g2 * G + j, mrow[moff * G + j]);
+      }
+    }
+    RS2_STAMP(1);
+    // RoPE angles of the lane's token at its 16 pairs (eight 16-byte pieces of the table row)
+    float4 ang[4][2];
+    {
+      const float2* rrow = v.rope + (size_t)tt * 64;
+#pragma unroll
+      for (int mq = 0; mq < 4; ++mq)
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          const int j = STYLE == 0 ? 8 * mq + 2 * x : 32 * x + 4 * mq;
+          ang[mq][x] = *reinterpret_cast<const float4*>(rrow + (roff + j));
+        }
+    }
+    const uint4 cw0 = cw[0];
+    uint4 cw1 = cw0;
+    if constexpr (G == 4) cw1 = cw[1];
+    asm volatile("" ::: "memory");                        // (the LDS unit takes a wave's accesses in program order)
+    __builtin_amdgcn_wave_barrier();
+#if RS2_EARLY
+    if (it + 1 < RS2_TILES && tt + 16 < len) request(tt + 16);   // (in flight during the products)
+#endif
+
+#pragma unroll
+    for (int ph = 0; ph < G / 2; ++ph) {
+      // ---- H_128 of heads 2 ph and 2 ph + 1
+      v4f acc[2][8];
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int h = 2 * ph + hh;
+        const uint4 cwp = ph == 0 ? cw0 : cw1;
+        const uint32_t wd[2] = {hh ? cwp.z : cwp.x, hh ? cwp.w : cwp.y};
+        const uint4* gp = reinterpret_cast<const uint4*>(s_g4 + wave * (4 * G * 8) + (kq * G + h) * 8);
+        const uint4 gA = gp[0], gB = gp[1];
+        const uint32_t g4w[8] = {gA.x, gA.y, gA.z, gA.w, gB.x, gB.y, gB.z, gB.w};
+#pragma unroll
+        for (int sh = 0; sh < 8; sh += RS2_LOOK) {         // look-ups of RS2_LOOK steps, then their products
+          uint32_t bv[RS2_LOOK][4];
+#pragma unroll
+          for (int sl = 0; sl < RS2_LOOK; ++sl) {
+            const int s = sh + sl, dw = s >> 2, ksh = s & 3;
+            // LDS byte address of (block, code, token) = (table >> 8 + block) << 8 | code << 6 | token << 2: the low bytes of four
+            // channels at once, then one byte permute per channel puts the block above
+            const uint32_t low4 = ((wd[dw] << (6 - 2 * ksh)) & 0xC0C0C0C0u) | tokrep;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const uint32_t addr = __builtin_amdgcn_perm(g4w[s], low4, 0x0c0c0000u | ((4u + j) << 8) | j);
+              bv[sl][j] = *reinterpret_cast<const rs2_lds_u32*>((uintptr_t)addr);
+            }
+          }
+#pragma unroll
+          for (int sl = 0; sl < RS2_LOOK; ++sl) {
+            const int s = sh + sl, dw = s >> 2, ksh = s & 3;
+            const v8h B = row_v8h(bv[sl][0], bv[sl][1], bv[sl][2], bv[sl][3]);
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+              // input bits 4, 3, 0 = dw, ksh & 1, ksh >> 1 against the tile's bits 4, 3, 0 = mt >> 2, (mt >> 1) & 1, mt & 1
+              const int neg = (((mt >> 2) & dw) ^ (((mt >> 1) & 1) & (ksh & 1)) ^ ((mt & 1) & (ksh >> 1))) & 1;
+              const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+              acc[hh][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg ? A_neg : A_pos, B, s == 0 ? zero4 : acc[hh][mt], 0, 0, 0);
+            }
+          }
+        }
+      }
+      RS2_STAMP(2 + 2 * ph);
+      // ---- first stage of H_g, RoPE at the token's position
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float x0 = acc[0][mt][r], x1 = acc[1][mt][r];
+          acc[0][mt][r] = x0 + x1;
+          acc[1][mt][r] = x0 - x1;
+        }
+#pragma unroll
+      for (int pi = 0; pi < 2; ++pi) {
+        if constexpr (STYLE == 0) {
+          // pairs (j, j + 64): rows 2 r1 and 2 r1 + 1 of a tile; angle piece r1 of the tile's group mq, entry mt & 1
+#pragma unroll
+          for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+            for (int r1 = 0; r1 < 2; ++r1) {
+              const float4 a4 = ang[mt >> 1][r1];
+              const float c = (mt & 1) ? a4.z : a4.x, s = (mt & 1) ? a4.w : a4.y;
+              const float x = acc[pi][mt][2 * r1], y = acc[pi][mt][2 * r1 + 1];
+              acc[pi][mt][2 * r1] = x * c - y * s;
+              acc[pi][mt][2 * r1 + 1] = x * s + y * c;
+            }
+        } else {
+          // pairs (2 j, 2 j + 1): tiles mt and mt + 1 (mt even); angle piece r & 1, entry r >> 1
+#pragma unroll
+          for (int mt = 0; mt < 8; mt += 2)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float4 a4 = ang[mt >> 1][r & 1];
+              const float c = (r >> 1) ? a4.z : a4.x, s = (r >> 1) ? a4.w : a4.y;
+              const float x = acc[pi][mt][r], y = acc[pi][mt + 1][r];
+              acc[pi][mt][r] = x * c - y * s;
+              acc[pi][mt + 1][r] = x * s + y * c;
+            }
+        }
+      }
+      // ---- dots with the queries of the output heads a = pi, pi + 2 (second stage of H_g: sign -1 for a >= 2 in the second phase)
+      for (int rq = 0; rq < rep; ++rq) {
+#pragma unroll
+        for (int pi = 0; pi < 2; ++pi)
+#pragma unroll
+          for (int ah = 0; ah < G / 2; ++ah) {
+            const int a = 2 * ah + pi;
+            // this lane's share of the query row: channels of tiles mt = 2 qu, 2 qu + 1
+            const float* qrow = s_qp + (a * rep + rq) * RKV_D + 32 * g4hi + 16 * (qu >> 1) + 8 * (qu & 1) + 4 * g4lo;
+            float qv[2][4];
+#pragma unroll
+            for (int b0 = 0; b0 < 2; ++b0)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) qv[b0][r] = qrow[64 * (r & 1) + 2 * (r >> 1) + b0];
+            rs2_settle(qv);
+            float dd[4];                                   // four chains: no multiply-add reads the result of the one before it
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dd[r] = fmul_quad<0>(qv[0][r], acc[pi][0][r]);
+#pragma unroll
+            for (int mt = 1; mt < 8; ++mt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                if ((mt >> 1) == 0) fmac_quad<0>(dd[r], qv[mt & 1][r], acc[pi][mt][r]);
+                if ((mt >> 1) == 1) fmac_quad<1>(dd[r], qv[mt & 1][r], acc[pi][mt][r]);
+                if ((mt >> 1) == 2) fmac_quad<2>(dd[r], qv[mt & 1][r], acc[pi][mt][r]);
+                if ((mt >> 1) == 3) fmac_quad<3>(dd[r], qv[mt & 1][r], acc[pi][mt][r]);
+              }
+            float d = (dd[0] + dd[1]) + (dd[2] + dd[3]);
+            d += __shfl_xor(d, 16);
+            d += __shfl_xor(d, 32);
+            if (kq == 0) {
+              float* slot = s_pd + (a * rep + rq) * 16 + tok;
+              if (ph == 0) *slot = d;
+              else *slot = (ah & ph) ? *slot - d : *slot + d;
+            }
+          }
+      }
+      RS2_STAMP(3 + 2 * ph);
+    }
+#if !RS2_EARLY
+    if (it + 1 < RS2_TILES && tt + 16 < len) request(tt + 16);
+#endif
+    asm volatile("" ::: "memory");                        // (the LDS unit takes a wave's accesses in program order)
+    __builtin_amdgcn_wave_barrier();
+    // ---- the tile's scores; retained sink tokens are masked out of the stream
+    for (int i = lane; i < nqh * 16; i += 64) {
+      const int hr = i >> 4, tk = tt + (i & 15);
+      if (tk < len) {
+        bool sink = false;
+        for (int k = 0; k < cnt; ++k) sink |= (s_sink[k] == tk);
+        float* srow = sc + ((size_t)b * v.Hq + (size_t)rg * nqh) * v.Tpad + tt;
+        srow[(uint32_t)(hr * v.Tpad + (i & 15))] = sink ? -INFINITY : s_pd[i] * out_scale;
+      }
+    }
+    RS2_STAMP(6);
+#ifdef RS2_TS
+    ts_acc[7] += 1;
+#endif
+  }
+#ifdef RS2_TS
+  if (lane == 0)
+    for (int i = 0; i < 8; ++i) atomicAdd(&rs2_ts[i], ts_acc[i]);
+#endif
+}
+
+static size_t row2_dynamic_lds(const RkvView& v) {
+  const int nqh = v.g * (v.Hq / v.Hkv), NG = v.E >> 7;
+  return (size_t)4 * NG * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4 + (size_t)4 * 4 * v.g * 8 * 4 + 256;
+}
+static bool row2_applies(const RkvView& v) {
+  return (v.E >> 7) <= RS2_MAX_NG && row2_dynamic_lds(v) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
+}
+
 // Whether a cache takes this path: a reorder that leaves the rotation groups (else the plain or the
 // cross-block kernel serves it), 2-bit codes in groups of 128 with fp16 metadata, rot_heads 2 or 4.
 static size_t row_dynamic_lds(const RkvView& v) {
@@ -323,9 +709,18 @@ int rkv_launch_scores_row(const rkv_cache* c, const float* qr, float* sc, hipStr
   const RkvView& v = c->v;
   if (!rkv_row_supported(c)) return RKV_EINVAL;
   const int rep = v.Hq / v.Hkv;
+  if (v.len == 0) return RKV_OK;
+  if (row2_applies(v)) {
+    const size_t dyn = row2_dynamic_lds(v);
+    dim3 grid((v.len + RS2_CHUNK - 1) / RS2_CHUNK, v.NRG, v.B);
+    void (*fn)(RkvView, const float*, float*, int) =
+        v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0> : k_scores_row2<4, 1>) : (v.rope_style == 0 ? k_scores_row2<2, 0> : k_scores_row2<2, 1>);
+    if (dyn > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
+    hipLaunchKernelGGL(fn, grid, dim3(256), dyn, s, v, qr, sc, rep);
+    return rkv_check_launch();
+  }
   const size_t dyn = row_dynamic_lds(v);
   const int nch = (v.len + RKV_ROW_CHUNK - 1) / RKV_ROW_CHUNK;
-  if (nch == 0) return RKV_OK;
   dim3 grid(nch, v.NRG, v.B);
   if (v.g == 4) {
     if (v.rope_style == 0) hipLaunchKernelGGL((k_scores_row<4, 0>), grid, dim3(256), dyn, s, v, qr, sc, rep);
