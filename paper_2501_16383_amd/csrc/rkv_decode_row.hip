@@ -367,22 +367,6 @@ __device__ __forceinline__ void rs2_settle(float (&q)[2][4]) {
   asm volatile("s_nop 1" : "+v"(q[0][0]), "+v"(q[0][1]), "+v"(q[0][2]), "+v"(q[0][3]), "+v"(q[1][0]), "+v"(q[1][1]), "+v"(q[1][2]), "+v"(q[1][3]));
 }
 
-#ifdef RS2_TS
-__device__ unsigned long long rs2_ts[8];
-extern "C" __attribute__((visibility("default"))) int rkv_dbg_ts(unsigned long long* out, int clear) {
-  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(rs2_ts), 64) != hipSuccess) return -1;
-  if (clear) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(rs2_ts), z, 64) != hipSuccess) return -1; }
-  return 0;
-}
-#define RS2_STAMP(i)                                                         \
-  do {                                                                       \
-    const unsigned long long now_ = __builtin_readcyclecounter();            \
-    ts_acc[i] += now_ - ts_last;                                             \
-    ts_last = now_;                                                          \
-  } while (0)
-#else
-#define RS2_STAMP(i)
-#endif
 // dynamic LDS: [4 waves][NG * 4 entries][16 tokens] dwords, [4 waves][G * rep][16] float partial sums, [G * rep][128] float
 // queries, [4 waves][4 * G * 8] dwords of block bytes, 64 sink positions
 template <int G, int STYLE>
@@ -400,9 +384,6 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
   // [wave][q][head][dword dw][shift ksh]: four channels' quantization blocks, a byte each, plus (the wave's table >> 8)
   uint32_t* s_g4 = reinterpret_cast<uint32_t*>(dyn2 + (size_t)4 * NG * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4);
   int* s_sink = reinterpret_cast<int*>(s_g4 + 4 * 4 * G * 8);
-#ifdef RS2_TS
-  unsigned long long ts_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ts_last = __builtin_readcyclecounter();
-#endif
   const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
   const int len = rkv_len(v, b);
   const int t0 = chunk * RS2_CHUNK;
@@ -489,7 +470,6 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     e[48] = __builtin_amdgcn_perm(l23, h23, 0x07060302u);
   };
 
-  RS2_STAMP(0);
   for (int it = 0; it < RS2_TILES; ++it) {
     const int tt = t0 + 16 * RS2_TILES * wave + 16 * it;
     if (tt >= len) break;                                  // wave-uniform
@@ -510,7 +490,6 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
         for (int j = 0; j < G; ++j) put_block(g2 * G + j, mrow[moff * G + j]);
       }
     }
-    RS2_STAMP(1);
     // RoPE angles of the lane's token at its 16 pairs (eight 16-byte pieces of the table row)
     float4 ang[4][2];
     {
@@ -573,7 +552,6 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
           }
         }
       }
-      RS2_STAMP(2 + 2 * ph);
       // ---- first stage of H_g, RoPE at the token's position
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt)
@@ -648,7 +626,6 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
             }
           }
       }
-      RS2_STAMP(3 + 2 * ph);
     }
 #if !RS2_EARLY
     if (it + 1 < RS2_TILES && tt + 16 < len) request(tt + 16);
@@ -665,15 +642,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
         srow[(uint32_t)(hr * v.Tpad + (i & 15))] = sink ? -INFINITY : s_pd[i] * out_scale;
       }
     }
-    RS2_STAMP(6);
-#ifdef RS2_TS
-    ts_acc[7] += 1;
-#endif
   }
-#ifdef RS2_TS
-  if (lane == 0)
-    for (int i = 0; i < 8; ++i) atomicAdd(&rs2_ts[i], ts_acc[i]);
-#endif
 }
 
 static size_t row2_dynamic_lds(const RkvView& v) {
