@@ -167,6 +167,7 @@ def main():
     bulk_bytes = n_bulk * (2 * E * 2 + 2 * E * QB // 8 + 2 * (E // QG) * MB)
     bulk_best = min(bulk_ms)
     bulk_avg = sum(bulk_ms) / len(bulk_ms)
+    bulk_med = sorted(bulk_ms)[len(bulk_ms) // 2]
 
     # ---- per-step inputs, resident before the timed region
     n_total = K + W
@@ -319,6 +320,7 @@ def main():
                      "algorithmic_bytes_per_launch": launch_bytes, "bytes_per_kv_token": bytes_per_tok,
                      "alu_only_ms": alu_only_ms},
         "append_bulk": {"GB/s_best": bulk_bytes / (bulk_best * 1e-3) / 1e9, "GB/s_avg": bulk_bytes / (bulk_avg * 1e-3) / 1e9,
+                        "GB/s_median": bulk_bytes / (bulk_med * 1e-3) / 1e9, "calls": len(bulk_ms),
                         "frac_of_hbm_peak_best": bulk_bytes / (bulk_best * 1e-3) / 1e9 / HBM_PEAK_GBS,
                         "kv_tokens_per_s_best": n_bulk / (bulk_best * 1e-3), "tokens_per_call": n_bulk,
                         "bytes_per_kv_token": 2 * E * 2 + bytes_per_tok},

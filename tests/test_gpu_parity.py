@@ -265,12 +265,15 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
         assert P.attention_error(o_rag[bb:bb + 1].cpu().numpy().astype(np.float64), ref) <= ATT_TOL
 
 
-def test_whole_row_reorder_with_many_heads():
+@pytest.mark.parametrize("heads", [64, 60])
+def test_whole_row_reorder_with_many_heads(heads):
     """A row of 64 KV heads (8192 channels, 64 quantization blocks) under a reorder over the whole
     row: beyond what the general append kernel's LDS holds (53 heads), within what the matrix-core
-    kernels for this reorder serve; both read paths against the oracle."""
-    w = small("cfg1", n_q_heads=64, n_kv_heads=64)
-    cfg = R.RkvConfig(batch=1, n_q_heads=64, n_kv_heads=64, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=64 * 128)
+    kernels for this reorder serve; both read paths against the oracle.  64 blocks take the scores
+    kernel that stages rows in LDS, 60 the one with a table per wave (61 KB of tables: more dynamic
+    LDS than a launch gets without asking)."""
+    w = small("cfg1", n_q_heads=heads, n_kv_heads=heads)
+    cfg = R.RkvConfig(batch=1, n_q_heads=heads, n_kv_heads=heads, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=heads * 128)
     perm = calibrated_perm(w, cfg, offset_variant=True)
     cache, _, _ = full_check(w, cfg, 90, perm=perm, chunks=[0, 40, 41, 90], paths=(1, 2), sink_positions=[])
     cache.set_decode_path(0)
