@@ -315,7 +315,10 @@ __global__ void __launch_bounds__(256, 3) k_scores_row(RkvView v, const float* _
 // H_128 = H_8 (x) H_16: a product contracts the channel bits {1, 2} (the four channels of a lane's
 // dword) and {5, 6} (the quarter) against the same bits of the output channel (rows of A), and
 // the bits {0, 3, 4} by accumulation - the eight products of a head's eight steps s onto output
-// tile mt carry the sign (-1)^popc(mt & s), the same for every lane, i.e. A or -A.  A lane
+// tile mt carry the sign (-1)^popc(mt & s), the same for every lane, i.e. A or -A (equal partial
+// sums are shared, and the stage of bit 4 is a pair of additions in the lane: 22 products and 32
+// additions per head; a matrix product keeps the vector pipe from issuing for most of its 16
+// cycles, so trading 21 of them for 32 additions pays).  A lane
 // (token, g4) of the result holds, per head, tiles mt = 0..7 x rows r = 0..3: output channel bits
 // 6 = r & 1, 5 = g4 >> 1, 4 3 0 = mt, 2 = g4 & 1, 1 = r >> 1 - both channels of a RoPE pair of either
 // pairing.  H_g over the heads is split: P0 = X0 + X1, P1 = X0 - X1 of a pair of heads go through
@@ -336,6 +339,9 @@ __global__ void __launch_bounds__(256, 3) k_scores_row(RkvView v, const float* _
 #endif
 #ifndef RS2_EARLY
 #define RS2_EARLY 0
+#endif
+#ifndef RS2_HALVES
+#define RS2_HALVES 1                    // 1: the last stage of H_8 as additions in the lane (22 products and 32 additions per head instead of 43 products)
 #endif
 #ifndef RS2_LOOK
 #define RS2_LOOK 4                      // steps looked up at a time (4 registers each)
@@ -523,6 +529,9 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
         const uint4* gp = reinterpret_cast<const uint4*>(s_g4 + wave * (4 * G * 8) + (kq * G + h) * 8);
         const uint4 gA = gp[0], gB = gp[1];
         const uint32_t g4w[8] = {gA.x, gA.y, gA.z, gA.w, gB.x, gB.y, gB.z, gB.w};
+#if RS2_HALVES
+        v4f wpart[2][4];
+#endif
 #pragma unroll
         for (int sh = 0; sh < 8; sh += RS2_LOOK) {         // look-ups of RS2_LOOK steps, then their products
           uint32_t bv[RS2_LOOK][4];
@@ -542,6 +551,15 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
           for (int sl = 0; sl < RS2_LOOK; ++sl) {
             const int s = sh + sl, dw = s >> 2, ksh = s & 3;
             const v8h B = row_v8h(bv[sl][0], bv[sl][1], bv[sl][2], bv[sl][3]);
+#if RS2_HALVES
+            // the steps of either dword onto four partial tiles (bits 3, 0 of the tile against ksh & 1, ksh >> 1)
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb) {
+              const int neg = (((bb >> 1) & (ksh & 1)) ^ ((bb & 1) & (ksh >> 1))) & 1;
+              const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+              wpart[dw][bb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg ? A_neg : A_pos, B, ksh == 0 ? zero4 : wpart[dw][bb], 0, 0, 0);
+            }
+#else
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
               // input bits 4, 3, 0 = dw, ksh & 1, ksh >> 1 against the tile's bits 4, 3, 0 = mt >> 2, (mt >> 1) & 1, mt & 1
@@ -549,8 +567,17 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
               const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
               acc[hh][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg ? A_neg : A_pos, B, s == 0 ? zero4 : acc[hh][mt], 0, 0, 0);
             }
+#endif
           }
         }
+#if RS2_HALVES
+        // bit 4 of the tile against the dword: the last stage of the transform in the lane
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            acc[hh][mt][r] = (mt >> 2) ? wpart[0][mt & 3][r] - wpart[1][mt & 3][r] : wpart[0][mt & 3][r] + wpart[1][mt & 3][r];
+#endif
       }
       // ---- first stage of H_g, RoPE at the token's position
 #pragma unroll
