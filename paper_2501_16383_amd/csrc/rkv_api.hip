@@ -576,7 +576,7 @@ RKV_EXPORT int rkv_decode_attention_static(rkv_cache* cache, const void* dev_q, 
   size_t need = rkv_query_scratch_bytes(cache->v.B, cache->v.Hq) +
                 (size_t)cache->v.B * cache->v.Hq * nch * RKV_PART_STRIDE * 4 + 256;
   // (a reorder over the whole row: the scores buffer sits behind the partial results of the cache's capacity)
-  if (fast && rkv_row_supported(cache))
+  if (fast && rkv_scores_path(cache))
     need = rkv_query_scratch_bytes(cache->v.B, cache->v.Hq) + rkv_partial_bytes(cache->v.B, cache->v.Hq, cache->v.Tpad) +
            rkv_row_scores_bytes(cache->v.B, cache->v.Hq, cache->cfg.max_tokens) + 256;
   if (need > RKV_STATIC_SCRATCH_BYTES) return RKV_ESCRATCH;

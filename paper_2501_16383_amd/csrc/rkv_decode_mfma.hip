@@ -254,7 +254,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   // With groups of 32 the zero-point table of the key phase (32 KB) and these digits (33 KB) take
   // turns in one piece of LDS, so that two workgroups still fit a compute unit: the table is dead
   // once every wave has left the key phase.
-  constexpr bool ALIAS = SUB == 4;
+  constexpr bool ALIAS = SUB == 4 && XB;
   constexpr size_t SA_BYTES = (size_t)NS * (MF_CH / 32) * 2 * SA_SET, XTT_BYTES = XB ? (size_t)128 * (SUB ? G * SUB : G) * G * 4 : 4;
   __shared__ __attribute__((aligned(16))) uint8_t s_A_raw[ALIAS ? (SA_BYTES > XTT_BYTES ? SA_BYTES : XTT_BYTES) : SA_BYTES];
   uint8_t (*const s_A)[MF_CH / 32][2][SA_SET] = reinterpret_cast<uint8_t (*)[MF_CH / 32][2][SA_SET]>(s_A_raw);
@@ -279,7 +279,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   //     - 64 * Z_a(t) * (cos(t) * q~[h][pair 0, first half] + sin(t) * q~[h][pair 0, second half]),
   // is worked out once per token when the metadata are staged and put where the key phase adds
   // its sum (s_sc).
-  constexpr bool LM = !XB;
+  constexpr bool LM = !XB && SUB == 0;
   constexpr int MWL = META8 ? G / 2 : G;             // metadata dwords per token and rotation group as stored
   constexpr int GP = G / 2;                          // packed pairs per token
   __shared__ __attribute__((aligned(16))) uint32_t s_ks[LM ? MF_CH * GP : 1], s_vm[LM ? MF_CH * G : 1];
@@ -289,7 +289,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   __shared__ float s_xtt_own[(XB && !ALIAS) ? 128 * XK * G : 1];
   float* const s_xtt = ALIAS ? reinterpret_cast<float*>(s_A_raw) : s_xtt_own;   // [channel][quantization block][head]
   static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
-  static_assert(SUB == 0 || (XB && !META8), "groups of 64 / 32 run as a variant of the cross-block kernel, fp16 metadata");
+  static_assert(SUB == 0 || ((XB || PRE) && !META8), "groups of 64 / 32 run as a variant of the cross-block kernel (or on precomputed scores), fp16 metadata");
   static_assert(!ALU || (!XB && !META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
   static_assert(!PRE || (!XB && !META8 && HB == 0 && !MULTI && !ALU), "precomputed scores: plain 2-bit layout, fp16 metadata, one query token");
 
@@ -417,15 +417,18 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   const int cnt = ld_cnt;
   {
     if constexpr (PRE) {
-      // thread = token of the chunk: its scores from the buffer, its value metadata to LDS
-      const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * G;
+      // thread = token of the chunk: its scores from the buffer, its value metadata to LDS (with
+      // groups of 64 / 32 the softmax phase fetches the sub-blocks' metadata itself)
       uint32_t dv[G];
-      if constexpr (G == 4) {
-        const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(v.vm + mi));
-        dv[0] = u.x; dv[1] = u.y; dv[2] = u.z; dv[3] = u.w;
-      } else {
-        const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(v.vm + mi));
-        dv[0] = u.x; dv[1] = u.y;
+      if constexpr (LM) {
+        const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * G;
+        if constexpr (G == 4) {
+          const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(v.vm + mi));
+          dv[0] = u.x; dv[1] = u.y; dv[2] = u.z; dv[3] = u.w;
+        } else {
+          const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(v.vm + mi));
+          dv[0] = u.x; dv[1] = u.y;
+        }
       }
       float pre[NH];
 #pragma unroll
@@ -438,8 +441,10 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
       for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
       if (tid < 64) s_sink[tid] = tid < cnt ? ld_spos : -1;
+      if constexpr (LM) {
 #pragma unroll
-      for (int i = 0; i < G; ++i) s_vm[tid * G + i] = dv[i];
+        for (int i = 0; i < G; ++i) s_vm[tid * G + i] = dv[i];
+      }
 #pragma unroll
       for (int a = 0; a < NH; ++a) s_sc[a][tid] = pre[a];
       __syncthreads();
@@ -1155,6 +1160,11 @@ typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int,
 // heads of a KV head per workgroup (1 or 2); alu: the arithmetic-only measurement.
 static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool alu) {
   const RkvView& v = c->v;
+  if (rkv_scores_local(c)) {                                // groups of 32: scores from k_scores_row2, sub-blocks in the value phase
+    const int sub = 128 / v.qg;
+    if (v.g == 4) return sub == 4 ? k_decode_mfma<4, 1, false, false, 0, false, 4, false, true> : k_decode_mfma<4, 1, false, false, 0, false, 2, false, true>;
+    return sub == 4 ? k_decode_mfma<2, 1, false, false, 0, false, 4, false, true> : k_decode_mfma<2, 1, false, false, 0, false, 2, false, true>;
+  }
   if (rkv_row_supported(c)) {                               // scores from k_scores_row
     if (v.g == 4) return share == 1 ? k_decode_mfma<4, 1, false, false, 0, false, 0, false, true> : k_decode_mfma<4, 2, false, false, 0, false, 0, false, true>;
     return share == 1 ? k_decode_mfma<2, 1, false, false, 0, false, 0, false, true> : k_decode_mfma<2, 2, false, false, 0, false, 0, false, true>;
@@ -1219,9 +1229,9 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   const int rep = v.Hq / v.Hkv;
   const bool sg = mfma_sub_groups(c);
   const bool xb = mfma_cross_block(c) || sg;
-  const bool row = rkv_row_supported(c);
+  const bool row = rkv_scores_path(c);
   if ((xb || row) && multi) return RKV_EINVAL;              // the cross-block and whole-row variants take one query token per step
-  const int share = xb ? 1 : rkv_mfma_share(rep);           // and (cross-block) one query head per workgroup
+  const int share = xb ? 1 : rkv_mfma_share(rep);           // and (cross-block, sub-groups) one query head per workgroup
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   const int nch = (v.len + MF_CH - 1) / MF_CH;

@@ -375,13 +375,14 @@ __device__ __forceinline__ void rs2_settle(float (&q)[2][4]) {
 
 // dynamic LDS: [4 waves][NG * 4 entries][16 tokens] dwords, [4 waves][G * rep][16] float partial sums, [G * rep][128] float
 // queries, [4 waves][4 * G * 8] dwords of block bytes, 64 sink positions
-template <int G, int STYLE>
+// LOCAL: groups of 64 / 32 with the reorder inside the heads - the table holds the rotation group's own v.gm blocks
+template <int G, int STYLE, bool LOCAL>
 __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const float* __restrict__ qr, float* __restrict__ sc, int rep) {
   constexpr int n = 128 * G;
   // (no static LDS in this kernel: the tables start where the workgroup's LDS starts, so that a table's byte
   // address >> 8 plus a block index stays below 256 for rows of up to RS2_MAX_NG blocks)
   extern __shared__ __attribute__((aligned(256))) unsigned char dyn2[];
-  const int NG = v.E >> 7, nqh = G * rep;
+  const int NG = LOCAL ? v.gm : v.E >> 7, nqh = G * rep;   // blocks in a wave's table
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   uint32_t* s_tab = reinterpret_cast<uint32_t*>(dyn2) + (size_t)wave * NG * 64;
@@ -413,12 +414,23 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
 
   uint4 cw[G / 2];
   uint32_t mw[RS2_MPRE][G];
+  uint32_t ml[4] = {0, 0, 0, 0};
+  const int bpl = LOCAL ? v.gm >> 2 : 0;                                  // blocks per lane group (1, 2 or 4)
+  const uint32_t loff = LOCAL ? (uint32_t)(tok * v.gm + kq * bpl) : 0u;
   const uint32_t roff = (uint32_t)(tok * 64 + (STYLE == 0 ? 32 * g4hi + 4 * g4lo : 16 * g4hi + 2 * g4lo));   // the lane's place in a tile's RoPE rows
   const uint32_t moff = (uint32_t)(kq * v.Tpad + tok);   // metadata entry of (rotation group kq of a round, token), in units of G dwords
   auto request = [&](int tt) {
     const uint4* kt = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tt >> 4));
 #pragma unroll
     for (int bp = 0; bp < G / 2; ++bp) cw[bp] = rkv_ld_stream(kt + 64 * bp + lane);
+    if constexpr (LOCAL) {
+      // the token's v.gm entries of this rotation group: a quarter of them per lane group
+      const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tt) * v.gm;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (i < bpl) ml[i] = mrow[loff + i];
+      return;
+    }
 #pragma unroll
     for (int k = 0; k < RS2_MPRE; ++k) {
       const int g2 = kq + 4 * k;
@@ -443,7 +455,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     const int c0 = 128 * h + 32 * q + 16 * dw + 8 * (ksh & 1) + (ksh >> 1);
     uint32_t w = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w |= (uint32_t)v.gid[rg * n + c0 + 2 * j] << (8 * j);
+    for (int j = 0; j < 4; ++j) w |= (uint32_t)(v.gid[rg * n + c0 + 2 * j] - (LOCAL ? rg * v.gm : 0)) << (8 * j);
     const uint32_t tab0 = (uint32_t)(uintptr_t)(rs2_lds_u8*)dyn2;     // LDS byte address of the first table (a multiple of 256)
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) s_g4[ww * (4 * G * 8) + tid] = w + (((tab0 >> 8) + (uint32_t)(ww * NG)) * 0x01010101u);
@@ -480,15 +492,20 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     const int tt = t0 + 16 * RS2_TILES * wave + 16 * it;
     if (tt >= len) break;                                  // wave-uniform
     // ---- the tile's table (the lanes of a wave write and read it in program order)
+    if constexpr (LOCAL) {
 #pragma unroll
-    for (int k = 0; k < RS2_MPRE; ++k) {
+      for (int i = 0; i < 4; ++i)
+        if (i < bpl) put_block(kq * bpl + i, ml[i]);
+    }
+#pragma unroll
+    for (int k = 0; k < (LOCAL ? 0 : RS2_MPRE); ++k) {
       const int g2 = kq + 4 * k;
       if (g2 < v.NRG) {
 #pragma unroll
         for (int j = 0; j < G; ++j) put_block(g2 * G + j, mw[k][j]);
       }
     }
-    for (int k = RS2_MPRE; k < rounds; ++k) {
+    for (int k = RS2_MPRE; k < (LOCAL ? 0 : rounds); ++k) {
       const int g2 = kq + 4 * k;
       if (g2 < v.NRG) {
         const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt) * G;
@@ -672,12 +689,12 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
   }
 }
 
-static size_t row2_dynamic_lds(const RkvView& v) {
-  const int nqh = v.g * (v.Hq / v.Hkv), NG = v.E >> 7;
+static size_t row2_dynamic_lds(const RkvView& v, bool local) {
+  const int nqh = v.g * (v.Hq / v.Hkv), NG = local ? v.gm : v.E >> 7;
   return (size_t)4 * NG * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4 + (size_t)4 * 4 * v.g * 8 * 4 + 256;
 }
 static bool row2_applies(const RkvView& v) {
-  return (v.E >> 7) <= RS2_MAX_NG && row2_dynamic_lds(v) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
+  return (v.E >> 7) <= RS2_MAX_NG && row2_dynamic_lds(v, false) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
 }
 
 // Whether a cache takes this path: a reorder that leaves the rotation groups (else the plain or the
@@ -695,6 +712,20 @@ bool rkv_row_supported(const rkv_cache* c) {
   return row_dynamic_lds(v) + fixed <= 80 * 1024 && v.NRG <= 32;
 }
 
+// Groups of 64 / 32 with the reorder inside the heads take the same route (scores from
+// k_scores_row2 with the rotation group's own blocks in the table, then the softmax and value
+// phases of the matrix-core kernel): a key phase of two or four masked passes over the sub-blocks
+// costs more (measured on config 2's geometry: 177 and 292 us against 162 and 175).
+#ifndef RKV_SCORES_LOCAL_MAX_QG
+#define RKV_SCORES_LOCAL_MAX_QG 64
+#endif
+bool rkv_scores_local(const rkv_cache* c) {
+  const RkvView& v = c->v;
+  return c->blocks_aligned && v.qg <= RKV_SCORES_LOCAL_MAX_QG && v.qg < 128 && v.hb == 0 && !v.meta8 && (v.g == 2 || v.g == 4) &&
+         row2_dynamic_lds(v, true) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
+}
+bool rkv_scores_path(const rkv_cache* c) { return rkv_row_supported(c) || rkv_scores_local(c); }
+
 size_t rkv_row_scores_bytes(int batch, int n_q_heads, int max_tokens) {
   const size_t Tpad = ((size_t)max_tokens + 255) & ~(size_t)255;
   return (size_t)batch * n_q_heads * Tpad * 4;
@@ -703,14 +734,20 @@ size_t rkv_row_scores_bytes(int batch, int n_q_heads, int max_tokens) {
 // scores of every cached token for every query head of `v` (one query token per sequence, prepared queries qr)
 int rkv_launch_scores_row(const rkv_cache* c, const float* qr, float* sc, hipStream_t s) {
   const RkvView& v = c->v;
-  if (!rkv_row_supported(c)) return RKV_EINVAL;
+  if (!rkv_scores_path(c)) return RKV_EINVAL;
   const int rep = v.Hq / v.Hkv;
   if (v.len == 0) return RKV_OK;
-  if (row2_applies(v)) {
-    const size_t dyn = row2_dynamic_lds(v);
+  const bool local = rkv_scores_local(c);
+  if (local || row2_applies(v)) {
+    const size_t dyn = row2_dynamic_lds(v, local);
     dim3 grid((v.len + RS2_CHUNK - 1) / RS2_CHUNK, v.NRG, v.B);
-    void (*fn)(RkvView, const float*, float*, int) =
-        v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0> : k_scores_row2<4, 1>) : (v.rope_style == 0 ? k_scores_row2<2, 0> : k_scores_row2<2, 1>);
+    void (*fn)(RkvView, const float*, float*, int);
+    if (local)
+      fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, true> : k_scores_row2<4, 1, true>)
+                    : (v.rope_style == 0 ? k_scores_row2<2, 0, true> : k_scores_row2<2, 1, true>);
+    else
+      fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, false> : k_scores_row2<4, 1, false>)
+                    : (v.rope_style == 0 ? k_scores_row2<2, 0, false> : k_scores_row2<2, 1, false>);
     if (dyn > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
     hipLaunchKernelGGL(fn, grid, dim3(256), dyn, s, v, qr, sc, rep);
     return rkv_check_launch();

@@ -302,6 +302,8 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
 int rkv_mfma_share(int heads_per_kv_head);
 // a reorder over the whole token row (rkv_decode_row.hip): its scores kernel and the buffer it fills
 bool rkv_row_supported(const rkv_cache* c);
+bool rkv_scores_local(const rkv_cache* c);   // groups of 32 inside the heads: scores from the same kernel
+bool rkv_scores_path(const rkv_cache* c);    // either of the two
 int rkv_append_mfma_variant(const rkv_cache* c);   // RKV_KERNEL_* of the matrix-core append kernel a cache takes
 size_t rkv_row_scores_bytes(int batch, int n_q_heads, int max_tokens);
 int rkv_launch_scores_row(const rkv_cache* c, const float* qr, float* sc, hipStream_t s);
