@@ -124,7 +124,8 @@ static Offsets plan(const rkv_config* c) {
 //   * a reorder that crosses 128-blocks but stays inside the rotation groups, groups of 128: the
 //     quantization block of a rotated channel is inv[c] / 128, one pass per block of the group;
 //   * quantization groups of 64 / 32 with a reorder inside the heads: block k = head * SUB + sub,
-//     sub = (inv[c] % 128) / quant_group, one pass per sub.
+//     sub = (inv[c] % 128) / quant_group (the append kernel's sub-group variant reads xgsel; the read
+//     half of this setting takes gid and needs none of these tables).
 static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int aligned, int* in_groups_out, hipStream_t s) {
   const RkvView& v = cache->v;
   const int E = v.E, g = v.g, n = v.n, nrg = v.NRG, qg = v.qg, sub_n = 128 / qg;

@@ -225,10 +225,11 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // four slots, signs of H_g as before - accumulate over the passes.  The zero-points no longer
 // collapse onto channel 0; their term, sum over the quantization blocks of s z / 2 times the
 // rotated indicator of the block's channels (xtt), starts the accumulators.
-// SUB = 2 or 4 (with XB): quantization groups of 64 or 32 channels, reorder inside the heads.  A
-// rotated 128-block then holds SUB quantization blocks; pass `sub` takes sub-block `sub` of every
-// head at once (masked operands; the small products with those sub-blocks' scales, one per head,
-// signs of H_g), and the zero-point product contracts over all G * SUB blocks of the group.
+// SUB = 2 or 4 (with PRE): quantization groups of 64 or 32 channels, reorder inside the heads.  The
+// scores come from k_scores_row2 (a key phase of SUB masked passes over the sub-blocks was the
+// first design and measured slower); here every value head has SUB (scale, zero-point) pairs per
+// token, so the softmax phase makes SUB sets of weight digits and a wave of the value phase takes
+// the set of the sub-block its 32 channels lie in.
 // ALU: measurement only.  The same kernel with the cache stream - K codes, K metadata, V codes,
 // V metadata - replaced by values made up in registers (from the lane number and a kernel
 // argument, so that nothing folds at compile time): what the arithmetic alone costs when no byte
@@ -251,12 +252,8 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   // zeros that the lanes holding the operand's empty parts read instead.
   constexpr int SA_ZERO = 16 * 32, SA_SET = SA_ZERO + 16;
   constexpr int NS = SUB ? SUB : 1;              // sub-blocks of a value head (groups of 64 / 32): weights per sub-block
-  // With groups of 32 the zero-point table of the key phase (32 KB) and these digits (33 KB) take
-  // turns in one piece of LDS, so that two workgroups still fit a compute unit: the table is dead
-  // once every wave has left the key phase.
-  constexpr bool ALIAS = SUB == 4 && XB;
-  constexpr size_t SA_BYTES = (size_t)NS * (MF_CH / 32) * 2 * SA_SET, XTT_BYTES = XB ? (size_t)128 * (SUB ? G * SUB : G) * G * 4 : 4;
-  __shared__ __attribute__((aligned(16))) uint8_t s_A_raw[ALIAS ? (SA_BYTES > XTT_BYTES ? SA_BYTES : XTT_BYTES) : SA_BYTES];
+  constexpr size_t SA_BYTES = (size_t)NS * (MF_CH / 32) * 2 * SA_SET;
+  __shared__ __attribute__((aligned(16))) uint8_t s_A_raw[SA_BYTES];
   uint8_t (*const s_A)[MF_CH / 32][2][SA_SET] = reinterpret_cast<uint8_t (*)[MF_CH / 32][2][SA_SET]>(s_A_raw);
   __shared__ float s_m[4], s_l[4], s_zs[NS][4], s_wsc[NS][4];
   __shared__ int s_sink[64];
@@ -283,13 +280,12 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   constexpr int MWL = META8 ? G / 2 : G;             // metadata dwords per token and rotation group as stored
   constexpr int GP = G / 2;                          // packed pairs per token
   __shared__ __attribute__((aligned(16))) uint32_t s_ks[LM ? MF_CH * GP : 1], s_vm[LM ? MF_CH * G : 1];
-  constexpr int XK = XB ? (SUB ? G * SUB : G) : 1;   // quantization blocks of the rotation group
-  constexpr int NP = SUB ? SUB : G;                  // passes of the key phase
+  constexpr int XK = XB ? G : 1;                     // quantization blocks of the rotation group
+  constexpr int NP = G;                              // passes of the key phase (cross-block variant)
   __shared__ uint4 s_xmask[XB ? G * NP * 4 : 1];  // [rotated block][pass][lane group q]
-  __shared__ float s_xtt_own[(XB && !ALIAS) ? 128 * XK * G : 1];
-  float* const s_xtt = ALIAS ? reinterpret_cast<float*>(s_A_raw) : s_xtt_own;   // [channel][quantization block][head]
+  __shared__ float s_xtt[XB ? 128 * XK * G : 1];  // [channel][quantization block][head]
   static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
-  static_assert(SUB == 0 || ((XB || PRE) && !META8), "groups of 64 / 32 run as a variant of the cross-block kernel (or on precomputed scores), fp16 metadata");
+  static_assert(SUB == 0 || (PRE && !META8), "groups of 64 / 32 run on precomputed scores, fp16 metadata");
   static_assert(!ALU || (!XB && !META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
   static_assert(!PRE || (!XB && !META8 && HB == 0 && !MULTI && !ALU), "precomputed scores: plain 2-bit layout, fp16 metadata, one query token");
 
@@ -462,7 +458,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       const uint4* ktiles = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tw >> 4));
       // the plane above the low two bits: 16 bytes per lane and pair of blocks (HB = 2) or 8 (HB = 1)
       const uint32_t* khtiles = HI ? v.kh + (rkv_k_tilebase(v, b, rg, tw >> 4) >> (HB == 1 ? 1 : 0)) : nullptr;
-      const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * (SUB ? G * SUB : (META8 ? G / 2 : G));
+      const uint32_t* kmeta = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tw) * (META8 ? G / 2 : G);
 
       uint4 cw[G / 2], cwh[HI ? G / 2 : 1];
       constexpr int MW = META8 ? G / 2 : G;              // metadata dwords per token and rotation group
@@ -474,7 +470,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 #pragma unroll
           for (int pr = 0; pr < G / 2; ++pr) cw[pr] = make_uint4(x, x * 3u, x * 5u, x * 7u + pr);
         }
-        if constexpr (XB && !META8 && SUB == 0) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
+        if constexpr (XB && !META8) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
         if constexpr (XB && META8) {                       // the token's scale bytes and zero-point bytes
           xmeta = kmeta[(size_t)(ti * 16 + n) * MW];
           if constexpr (G == 4) xmeta2 = kmeta[(size_t)(ti * 16 + n) * MW + 1];
@@ -495,8 +491,6 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
         }
         if constexpr (LM) {
           // (plain variants: the chunk's metadata are in LDS)
-        } else if constexpr (SUB != 0) {
-          // (groups of 64 / 32: the tile's metadata are fetched where they are used, G * SUB entries per token)
         } else if constexpr (META8) {
           // the lane's four tokens are consecutive: 4 x 2G bytes in one piece
           const uint4* mp = reinterpret_cast<const uint4*>(kmeta + (size_t)(ti * 16 + 4 * q) * MW);
@@ -524,7 +518,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       };
       load_tile(0);
       // (the requests are all out: what came back goes to LDS)
-      if constexpr (!ALIAS) {
+      {
         uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
         for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
       }
@@ -678,38 +672,8 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
         // (token n, quantization block q), the A operand of the zero-point product
         uint32_t xs2[XB ? 4 : 1][XB ? G : 1];
         float xwa = 0.f;
-        // groups of 64 / 32: the scale rows of the small products per (pass, token), and the A operands
-        // of the zero-point product, one per four quantization blocks
         constexpr int XSTEPS = (XK + 3) / 4;
-        v4h sAs[SUB ? SUB : 1][SUB ? 4 : 1];
-        float xwas[SUB ? XSTEPS : 1];
-        if constexpr (SUB != 0) {
-          constexpr int MWS = G * SUB;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            uint32_t e[MWS];                               // entry blk * SUB + sub of token 4q + r
-            const uint4* mp = reinterpret_cast<const uint4*>(kmeta + (size_t)(ti * 16 + 4 * q + r) * MWS);
-#pragma unroll
-            for (int i = 0; i < MWS / 4; ++i) {
-              const uint4 u = mp[i];
-              e[4 * i] = u.x; e[4 * i + 1] = u.y; e[4 * i + 2] = u.z; e[4 * i + 3] = u.w;
-            }
-#pragma unroll
-            for (int sub = 0; sub < SUB; ++sub) {
-              const uint32_t a01 = (__builtin_amdgcn_perm(e[SUB + sub], e[sub], 0x05040100u) ^ sm01) & keep_row;
-              uint32_t a23 = 0;
-              if constexpr (G == 4) a23 = (__builtin_amdgcn_perm(e[3 * SUB + sub], e[2 * SUB + sub], 0x05040100u) ^ sm23) & keep_row;
-              sAs[sub][r] = as_v4h(a01, a23);
-            }
-          }
-#pragma unroll
-          for (int st = 0; st < XSTEPS; ++st) {
-            float s_ = 0.f, z_ = 0.f;
-            if (4 * st + q < XK) rkv_unpack_meta(kmeta[(size_t)(ti * 16 + n) * MWS + 4 * st + q], s_, z_);
-            xwas[st] = -0.5f * s_ * z_;
-          }
-        }
-        if constexpr (XB && SUB == 0) {
+        if constexpr (XB) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -794,7 +758,7 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
                 for (int st = 0; st < XSTEPS; ++st) {
                   const int k = 4 * st + q;                   // this lane's quantization block of the step
                   const float bl = k < XK ? s_xtt[(j_lo * XK + k) * G + a] : 0.f, bh = k < XK ? s_xtt[(j_hi * XK + k) * G + a] : 0.f;
-                  const float wa = SUB ? xwas[SUB ? st : 0] : xwa;
+                  const float wa = xwa;
                   zl = __builtin_amdgcn_mfma_f32_16x16x4f32(wa, bl, zl, 0, 0, 0);
                   zh = __builtin_amdgcn_mfma_f32_16x16x4f32(wa, bh, zh, 0, 0, 0);
                 }
@@ -823,13 +787,8 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
                 // the block's scale in all four slots (contraction over the rotated blocks), signs of H_g
-                v4h sx;
-                if constexpr (SUB != 0) {
-                  sx = sAs[SUB ? gq : 0][SUB ? r : 0];        // the sub-blocks' own scales, one per head
-                } else {
-                  const uint32_t s2 = xs2[r][gq];
-                  sx = as_v4h((s2 ^ sm01) & keep_row, G == 4 ? (s2 ^ sm23) & keep_row : 0u);
-                }
+                const uint32_t s2 = xs2[r][gq];
+                const v4h sx = as_v4h((s2 ^ sm01) & keep_row, G == 4 ? (s2 ^ sm23) & keep_row : 0u);
                 if constexpr (G == 4) {
                   xk_lo[r] = mfma_4x4x4(sx, as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), xk_lo[r]);
                   xk_hi[r] = mfma_4x4x4(sx, as_v4h(pk_f16(hi[0][r], hi[1][r]), pk_f16(hi[2][r], hi[3][r])), xk_hi[r]);
@@ -935,11 +894,6 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
     }
     }
     __builtin_amdgcn_s_setprio(3);
-    if constexpr (ALIAS) {                                   // the table's space becomes the digits' (see s_A_raw)
-      __syncthreads();
-      uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
-      for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
-    }
     // V metadata of the four tokens this lane turns into weights in phase S (head = wave); requested
     // here and not before the key phase, where four more live registers would mean spills - and
     // with them a scratch allocation, which keeps some shader engines from holding three workgroups
@@ -1175,11 +1129,6 @@ static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool a
   if (alu) return k_decode_mfma<4, 1, false, false, 0, false, 0, true>;
   return share == 1 ? k_decode_mfma<4, 1, false, false, 0> : k_decode_mfma<4, 2, false, false, 0>;
 #else
-  if (mfma_sub_groups(c)) {
-    const int sub = 128 / v.qg;
-    if (v.g == 4) return sub == 2 ? k_decode_mfma<4, 1, false, false, 0, true, 2> : k_decode_mfma<4, 1, false, false, 0, true, 4>;
-    return sub == 2 ? k_decode_mfma<2, 1, false, false, 0, true, 2> : k_decode_mfma<2, 1, false, false, 0, true, 4>;
-  }
   if (mfma_cross_block(c)) {
     if (v.g == 4) return v.meta8 ? k_decode_mfma<4, 1, false, true, 0, true> : k_decode_mfma<4, 1, false, false, 0, true>;
     return v.meta8 ? k_decode_mfma<2, 1, false, true, 0, true> : k_decode_mfma<2, 1, false, false, 0, true>;
