@@ -1354,6 +1354,18 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
 
 
+@pytest.mark.parametrize("group,g,hq", [(32, 4, 16), (64, 2, 8)])
+def test_smaller_groups_with_interleaved_rope_pairs(group, g, hq):
+    """Groups of 64 / 32 with the interleaved RoPE pairing (and GQA): the scores kernel's table of the
+    rotation group's own sub-blocks together with its other pairing of a lane's channels; no
+    retained rows, several chunks and a ragged tail."""
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
+    cfg = R.RkvConfig(batch=2, n_q_heads=hq, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=g, quant_group=group, rope_style=1)
+    cache, _, _ = full_check(w, cfg, 613, chunks=[0, 300, 301, 613], paths=(1, 2), sink_positions=[])
+    cache.set_decode_path(0)
+    assert cache.decode_kernel() == RB.KERNEL_MFMA_SUB and cache.append_kernel() == RB.KERNEL_MFMA_SUB
+
+
 @pytest.mark.parametrize("uniform,bits", [(True, 2), (False, 2), (False, 4), (True, 3)])
 def test_truncate_rolls_back_a_multi_token_step(uniform, bits):
     """Speculative decoding's shape: four drafted tokens are appended and read the cache together
