@@ -1366,6 +1366,26 @@ def test_smaller_groups_with_interleaved_rope_pairs(group, g, hq):
     assert cache.decode_kernel() == RB.KERNEL_MFMA_SUB and cache.append_kernel() == RB.KERNEL_MFMA_SUB
 
 
+@pytest.mark.parametrize("T", [1, 15, 16, 17, 64, 65])
+@pytest.mark.parametrize("setting", ["groups of 32", "whole row"])
+def test_scores_kernel_at_tile_and_chunk_edges(setting, T):
+    """The read half that takes its scores from the scores kernel (groups of 64 / 32, a reorder over
+    the whole row) with a handful of tokens: one token, one short of a 16-token tile, exactly one
+    tile, one over, exactly the 64 tokens of a workgroup, one over; a sink row among them where there
+    is room."""
+    w = small("cfg1", n_q_heads=8, n_kv_heads=8)
+    if setting == "whole row":
+        cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=2, rot_heads=4, perm_span=1024)
+        perm = calibrated_perm(w, cfg, offset_variant=True)
+        kind = RB.KERNEL_MFMA_ROW
+    else:
+        cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=128, max_sinks=2, rot_heads=4, quant_group=32)
+        perm, kind = None, RB.KERNEL_MFMA_SUB
+    cache, _, _ = full_check(w, cfg, T, perm=perm, paths=(1, 2), sink_positions=[0] if T > 1 else [])
+    cache.set_decode_path(0)
+    assert cache.decode_kernel() == kind
+
+
 @pytest.mark.parametrize("uniform,bits", [(True, 2), (False, 2), (False, 4), (True, 3)])
 def test_truncate_rolls_back_a_multi_token_step(uniform, bits):
     """Speculative decoding's shape: four drafted tokens are appended and read the cache together
