@@ -59,7 +59,7 @@ typedef struct rkv_config {
                         /* 3- and 4-bit codes in groups of 128 run on the matrix-core kernels    */
                         /* like 2-bit ones (the bits above the low two as a second plane);       */
                         /* groups of 64 / 32 have variants of the matrix-core kernels for 2-bit  */
-                        /* codes with fp16 metadata and a reorder inside the heads (other        */
+                        /* codes (either metadata format) and a reorder inside the heads (other  */
                         /* settings of those groups take the general kernels, which means no     */
                         /* keys_rotated, no rkv_quantize_append_ragged and a two-kernel          */
                         /* rkv_decode_step)                                                      */
@@ -181,7 +181,7 @@ int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, 
  *   dev_sink_mask   [batch][n_new_max] uint8 or NULL
  * Needs a configuration the matrix-core append kernel covers (reorder inside blocks of 128 - or,
  * with 2-bit codes and groups of 128, anywhere in the row -, rot_heads 2 or 4, v_rotate 0; quant_group 64 or
- * 32 only with 2-bit codes, fp16 metadata and a reorder inside blocks of 128),
+ * 32 only with 2-bit codes and a reorder inside blocks of 128),
  * else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
  * max_tokens (nothing is appended then).  rkv_import_codes returns RKV_ESTATE on such a cache;
  * the export and dequantize views cover rkv_cache_length tokens for every sequence, and what they
@@ -263,7 +263,7 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
  * the configuration is outside what it covers: a reorder across rotation groups, rot_heads 1 or
  * 8; a reorder across blocks of 128 inside the rotation groups only with 2-bit codes and one
- * query token per step; quant_group 64 or 32 only with 2-bit codes, fp16 metadata, a reorder
+ * query token per step; quant_group 64 or 32 only with 2-bit codes, a reorder
  * inside the heads and one query token per step).
  * 3 = measurement only: the matrix-core kernel with the cache stream (codes and metadata of keys
  * and values) replaced by values made up in registers, i.e. the time its arithmetic takes when no

@@ -113,7 +113,7 @@ __device__ __forceinline__ void fused_round_consts(float zero, float& base, floa
 // quantization block is looked up (gid), the minima and maxima are kept per quantization block,
 // and every element takes the parameters of its own block.  Codes stay where they are - by
 // rotated channel - so only the key role differs.
-// SUB = 2 or 4: quantization groups of 64 or 32 channels (2-bit codes, fp16 metadata, reorder
+// SUB = 2 or 4: quantization groups of 64 or 32 channels (2-bit codes, either metadata format, reorder
 // inside the heads): a rotated 128-block holds SUB quantization blocks, block head * SUB + sub of
 // the rotation group, and a rotated channel's sub-block follows from its reordered position (the
 // same per-cache table, 2 bits per channel).  Keys: the minima and maxima of a token's G * SUB
@@ -787,8 +787,8 @@ bool rkv_append_mfma_supported(const rkv_cache* c) {
   // 2-bit codes, or wider ones (a second plane), in groups of 128; a reorder across 128-blocks
   // inside the rotation groups with 2-bit codes
   if (!c->blocks_aligned && !(c->in_groups && v.hb == 0 && !c->cfg.keys_rotated)) return false;
-  // groups of 64 / 32: 2-bit codes, fp16 metadata, a reorder inside the heads
-  if (v.qg != 128 && !(c->blocks_aligned && v.hb == 0 && !v.meta8)) return false;
+  // groups of 64 / 32: 2-bit codes, a reorder inside the heads
+  if (v.qg != 128 && !(c->blocks_aligned && v.hb == 0)) return false;
   return (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 

@@ -285,9 +285,9 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   __shared__ uint4 s_xmask[XB ? G * NP * 4 : 1];  // [rotated block][pass][lane group q]
   __shared__ float s_xtt[XB ? 128 * XK * G : 1];  // [channel][quantization block][head]
   static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
-  static_assert(SUB == 0 || (PRE && !META8), "groups of 64 / 32 run on precomputed scores, fp16 metadata");
+  static_assert(SUB == 0 || PRE, "groups of 64 / 32 run on precomputed scores");
   static_assert(!ALU || (!XB && !META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
-  static_assert(!PRE || (!XB && !META8 && HB == 0 && !MULTI && !ALU), "precomputed scores: plain 2-bit layout, fp16 metadata, one query token");
+  static_assert(!PRE || (!XB && HB == 0 && !MULTI && !ALU), "precomputed scores: plain 2-bit layout, one query token");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -416,7 +416,12 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       // thread = token of the chunk: its scores from the buffer, its value metadata to LDS (with
       // groups of 64 / 32 the softmax phase fetches the sub-blocks' metadata itself)
       uint32_t dv[G];
-      if constexpr (LM) {
+      if constexpr (LM && META8) {
+        // G scale bytes, then G zero-point bytes -> (scale, zero-point) fp16 pairs, the form the softmax phase takes
+        const uint8_t* vm8 = reinterpret_cast<const uint8_t*>(v.vm) + ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * (2 * G);
+#pragma unroll
+        for (int i = 0; i < G; ++i) dv[i] = rkv_pack_meta(rkv_e4m3_decode(vm8[i]), (float)vm8[G + i] - 128.0f);
+      } else if constexpr (LM) {
         const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * G;
         if constexpr (G == 4) {
           const uint4 u = rkv_ld_stream(reinterpret_cast<const uint4*>(v.vm + mi));
@@ -903,6 +908,11 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + lane + 64 * i) * (G * NS);
       if constexpr (LM) {
         // (read from LDS in the softmax phase)
+      } else if constexpr (SUB != 0 && META8) {
+        const uint8_t* vm8 = reinterpret_cast<const uint8_t*>(v.vm) + 2 * mi;
+#pragma unroll
+        for (int sb = 0; sb < NS; ++sb)
+          vmeta[sb][i] = wave < G ? ((uint32_t)vm8[wave * NS + sb] | ((uint32_t)vm8[G * NS + wave * NS + sb] << 8)) : 0x8000u;
       } else if constexpr (SUB != 0) {
 #pragma unroll
         for (int sb = 0; sb < NS; ++sb) vmeta[sb][i] = wave < G ? v.vm[mi + wave * NS + sb] : 0u;
@@ -1094,7 +1104,7 @@ static bool mfma_cross_block(const rkv_cache* c) {
 // groups of 64 / 32 with the reorder inside the heads: the sub-group variant of the same kernel
 static bool mfma_sub_groups(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && v.qg < 128 && v.hb == 0 && !v.meta8 && (v.g == 2 || v.g == 4);
+  return c->blocks_aligned && v.qg < 128 && v.hb == 0 && (v.g == 2 || v.g == 4);
 }
 
 int rkv_mfma_variant(const rkv_cache* c) {
@@ -1114,15 +1124,18 @@ typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int,
 // heads of a KV head per workgroup (1 or 2); alu: the arithmetic-only measurement.
 static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool alu) {
   const RkvView& v = c->v;
-  if (rkv_scores_local(c)) {                                // groups of 32: scores from k_scores_row2, sub-blocks in the value phase
+  // precomputed scores (groups of 64 / 32; a reorder over the whole row): softmax and value phases only
+#define RKV_MF_PRE(G_, R_, S_) (v.meta8 ? k_decode_mfma<G_, R_, false, true, 0, false, S_, false, true> : k_decode_mfma<G_, R_, false, false, 0, false, S_, false, true>)
+  if (rkv_scores_local(c)) {
     const int sub = 128 / v.qg;
-    if (v.g == 4) return sub == 4 ? k_decode_mfma<4, 1, false, false, 0, false, 4, false, true> : k_decode_mfma<4, 1, false, false, 0, false, 2, false, true>;
-    return sub == 4 ? k_decode_mfma<2, 1, false, false, 0, false, 4, false, true> : k_decode_mfma<2, 1, false, false, 0, false, 2, false, true>;
+    if (v.g == 4) return sub == 4 ? RKV_MF_PRE(4, 1, 4) : RKV_MF_PRE(4, 1, 2);
+    return sub == 4 ? RKV_MF_PRE(2, 1, 4) : RKV_MF_PRE(2, 1, 2);
   }
-  if (rkv_row_supported(c)) {                               // scores from k_scores_row
-    if (v.g == 4) return share == 1 ? k_decode_mfma<4, 1, false, false, 0, false, 0, false, true> : k_decode_mfma<4, 2, false, false, 0, false, 0, false, true>;
-    return share == 1 ? k_decode_mfma<2, 1, false, false, 0, false, 0, false, true> : k_decode_mfma<2, 2, false, false, 0, false, 0, false, true>;
+  if (rkv_row_supported(c)) {
+    if (v.g == 4) return share == 1 ? RKV_MF_PRE(4, 1, 0) : RKV_MF_PRE(4, 2, 0);
+    return share == 1 ? RKV_MF_PRE(2, 1, 0) : RKV_MF_PRE(2, 2, 0);
   }
+#undef RKV_MF_PRE
 #ifdef RKV_DEV_FEW_VARIANTS
   // developer builds: only the plain 2-bit variants of four-head rotation groups (quick to compile)
   if (multi || v.g != 4 || v.hb || v.meta8 || !c->blocks_aligned || v.qg != 128) abort();

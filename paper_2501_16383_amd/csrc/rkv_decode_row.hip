@@ -425,6 +425,13 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     for (int bp = 0; bp < G / 2; ++bp) cw[bp] = rkv_ld_stream(kt + 64 * bp + lane);
     if constexpr (LOCAL) {
       // the token's v.gm entries of this rotation group: a quarter of them per lane group
+      if (v.meta8) {                                       // v.gm scale bytes, then v.gm zero-point bytes: (scale | zero << 8)
+        const uint8_t* m8 = reinterpret_cast<const uint8_t*>(v.km) + ((size_t)(b * v.NRG + rg) * v.Tpad + tt + tok) * (2 * v.gm) + kq * bpl;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (i < bpl) ml[i] = (uint32_t)m8[i] | ((uint32_t)m8[v.gm + i] << 8);
+        return;
+      }
       const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tt) * v.gm;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -436,6 +443,12 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
       const int g2 = kq + 4 * k;
       if (g2 < v.NRG) {
         // (a base that is the same for all lanes plus a 32-bit lane offset: one register per lane, not an address pair)
+        if (v.meta8) {                                     // G scale bytes, then G zero-point bytes per (token, rotation group)
+          const uint8_t* m8 = reinterpret_cast<const uint8_t*>(v.km) + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt + moff) * (2 * G);
+#pragma unroll
+          for (int j = 0; j < G; ++j) mw[k][j] = (uint32_t)m8[j] | ((uint32_t)m8[G + j] << 8);
+          continue;
+        }
         const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt) * G;
         if constexpr (G == 4) {
           const uint4 u = reinterpret_cast<const uint4*>(mrow)[moff];
@@ -469,7 +482,12 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
   // the four table entries of one quantization block of the lane's token
   auto put_block = [&](int blk, uint32_t word) {
     float s_, z_;
-    rkv_unpack_meta(word, s_, z_);
+    if (v.meta8) {                                         // (scale byte | zero-point byte << 8)
+      s_ = rkv_e4m3_decode(word & 0xffu);
+      z_ = (float)((word >> 8) & 0xffu) - 128.0f;
+    } else {
+      rkv_unpack_meta(word, s_, z_);
+    }
     s_ *= 0.015625f;
     const float u0 = s_ * (0.f - z_), u1 = s_ * (1.f - z_), u2 = s_ * (2.f - z_), u3 = s_ * (3.f - z_);
     const uint32_t h01 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(u0, u1));
@@ -508,9 +526,15 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     for (int k = RS2_MPRE; k < (LOCAL ? 0 : rounds); ++k) {
       const int g2 = kq + 4 * k;
       if (g2 < v.NRG) {
-        const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt) * G;
+        if (v.meta8) {
+          const uint8_t* m8 = reinterpret_cast<const uint8_t*>(v.km) + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt + moff) * (2 * G);
 #pragma unroll
-        for (int j = 0; j < G; ++j) put_block(g2 * G + j, mrow[moff * G + j]);
+          for (int j = 0; j < G; ++j) put_block(g2 * G + j, (uint32_t)m8[j] | ((uint32_t)m8[G + j] << 8));
+        } else {
+          const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt) * G;
+#pragma unroll
+          for (int j = 0; j < G; ++j) put_block(g2 * G + j, mrow[moff * G + j]);
+        }
       }
     }
     // RoPE angles of the lane's token at its 16 pairs (eight 16-byte pieces of the table row)
@@ -698,7 +722,8 @@ static bool row2_applies(const RkvView& v) {
 }
 
 // Whether a cache takes this path: a reorder that leaves the rotation groups (else the plain or the
-// cross-block kernel serves it), 2-bit codes in groups of 128 with fp16 metadata, rot_heads 2 or 4.
+// cross-block kernel serves it), 2-bit codes in groups of 128, rot_heads 2 or 4 (8-bit metadata where the
+// table-per-wave kernel applies).
 static size_t row_dynamic_lds(const RkvView& v) {
   const int nqh = v.g * (v.Hq / v.Hkv), NG = v.E >> 7;
   return (size_t)16 * (NG | 1) * 16 + (size_t)nqh * RKV_D * 4 + (size_t)4 * nqh * 16 * 4;
@@ -706,7 +731,8 @@ static size_t row_dynamic_lds(const RkvView& v) {
 
 bool rkv_row_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  if (c->blocks_aligned || c->in_groups || v.qg != 128 || v.hb != 0 || v.meta8 || !(v.g == 2 || v.g == 4)) return false;
+  if (c->blocks_aligned || c->in_groups || v.qg != 128 || v.hb != 0 || !(v.g == 2 || v.g == 4)) return false;
+  if (v.meta8 && !row2_applies(v)) return false;           // (8-bit metadata: the table-per-wave kernel only)
   // two workgroups per compute unit must fit its LDS; a tile's metadata: at most 32 rotation groups
   const size_t fixed = (size_t)2 * 16 * (16 * v.g + 1) * 16 + (size_t)144 * v.g * 4 + 256;
   return row_dynamic_lds(v) + fixed <= 80 * 1024 && v.NRG <= 32;
@@ -721,7 +747,7 @@ bool rkv_row_supported(const rkv_cache* c) {
 #endif
 bool rkv_scores_local(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && v.qg <= RKV_SCORES_LOCAL_MAX_QG && v.qg < 128 && v.hb == 0 && !v.meta8 && (v.g == 2 || v.g == 4) &&
+  return c->blocks_aligned && v.qg <= RKV_SCORES_LOCAL_MAX_QG && v.qg < 128 && v.hb == 0 && (v.g == 2 || v.g == 4) &&
          row2_dynamic_lds(v, true) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
 }
 bool rkv_scores_path(const rkv_cache* c) { return rkv_row_supported(c) || rkv_scores_local(c); }

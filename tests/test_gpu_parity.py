@@ -857,8 +857,9 @@ def test_fold_rotation_matches_oracle():
         assert err <= 2e-6 * np.abs(ref).max()
 
 
-@pytest.mark.parametrize("g,bits,group", [(4, 2, 128), (2, 2, 128), (4, 4, 128), (2, 3, 128), (4, 2, 64), (2, 2, 32), (4, 2, 32)])
-def test_rotated_keys_path(g, bits, group):
+@pytest.mark.parametrize("g,bits,group,fmt", [(4, 2, 128, 0), (2, 2, 128, 0), (4, 4, 128, 0), (2, 3, 128, 0), (4, 2, 64, 0), (2, 2, 32, 0),
+                                              (4, 2, 32, 0), (4, 2, 64, 1), (2, 2, 32, 1)])
+def test_rotated_keys_path(g, bits, group, fmt):
     """The deployment shape of Sec. 4.2: keys arrive already rotated and reordered (folded weights),
     the write half only quantizes and packs.  Codes under the tie protocol (the input is exact, so
     only exact ties of Eq. 6 remain), sink rows brought back to the original basis (fp32 on the
@@ -866,7 +867,7 @@ def test_rotated_keys_path(g, bits, group):
     w = small("cfg1", n_q_heads=8, n_kv_heads=8)
     T = 150
     cfg = R.RkvConfig(batch=2, n_q_heads=8, n_kv_heads=8, max_tokens=T, max_sinks=4, rot_heads=g, keys_rotated=1, bits=bits,
-                      quant_group=group)
+                      quant_group=group, meta_format=fmt)
     ocfg = P.oracle_cfg(cfg)
     rng = np.random.default_rng(32)
     perm = np.concatenate([128 * blk + rng.permutation(128) for blk in range(cfg.E // 128)]).astype(np.int32)
@@ -1330,7 +1331,7 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
         assert not np.array_equal(perm // group, np.arange(cfg.E) // group)
     # wider codes in groups of 128 are read by the matrix-core decode kernel as two planes, 2-bit codes in
     # smaller groups by its sub-group variant
-    on_matrix_cores = g in (2, 4) and span == 128 and ((bits in (3, 4) and group == 128) or (bits == 2 and fmt == 0))
+    on_matrix_cores = g in (2, 4) and span == 128 and ((bits in (3, 4) and group == 128) or bits == 2)
     # half of the cases without any retained fp16 row, so that the compressed stream alone decides the outputs
     cache, oc, q = full_check(w, cfg, 213, perm=perm, chunks=[0, 100, 101, 102, 213], paths=(1, 2) if on_matrix_cores else (1, 0),
                               sink_positions=[] if (hq + group + bits) % 3 != 0 else None)
@@ -1364,6 +1365,33 @@ def test_smaller_groups_with_interleaved_rope_pairs(group, g, hq):
     cache, _, _ = full_check(w, cfg, 613, chunks=[0, 300, 301, 613], paths=(1, 2), sink_positions=[])
     cache.set_decode_path(0)
     assert cache.decode_kernel() == RB.KERNEL_MFMA_SUB and cache.append_kernel() == RB.KERNEL_MFMA_SUB
+
+
+@pytest.mark.parametrize("setting,g,hq", [("whole row", 4, 8), ("whole row", 2, 16), ("groups of 64", 4, 8), ("groups of 32", 2, 16),
+                                          ("groups of 32", 4, 8)])
+def test_fp8_metadata_on_the_scores_kernel_paths(setting, g, hq):
+    """FP8 scales and INT8 zero-points (Sec. 5.1) together with a reorder over the whole row (Alg. 1
+    as printed) or with groups of 64 / 32 (Table tab:quantgrani): the matrix-core write half of
+    each setting and the read half that takes its scores from the scores kernel, against the oracle
+    and the general kernel; GQA, several chunks, a ragged tail, with and without retained rows,
+    one more token through rkv_decode_step."""
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
+    kw = dict(batch=2, n_q_heads=hq, n_kv_heads=8, max_tokens=700, max_sinks=4, rot_heads=g, meta_format=1)
+    perm = None
+    if setting == "whole row":
+        cfg, kind = R.RkvConfig(perm_span=1024, **kw), RB.KERNEL_MFMA_ROW
+        perm = calibrated_perm(w, cfg, offset_variant=True)
+    else:
+        cfg, kind = R.RkvConfig(quant_group=int(setting.split()[-1]), **kw), RB.KERNEL_MFMA_SUB
+    cache, oc, q = full_check(w, cfg, 613, perm=perm, chunks=[0, 300, 301, 613], paths=(1, 2), sink_positions=None if g == 4 and hq == 8 else [])
+    cache.set_decode_path(0)
+    assert cache.decode_kernel() == kind and cache.append_kernel() == kind
+    k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
+    out = cache.decode_step(P.gpu(k1), P.gpu(v1), P.gpu(q))
+    torch.cuda.synchronize()
+    O.quantize_append(oc, k1, v1, None)                    # (the cache holds the oracle's codes from full_check)
+    ref, _ = O.decode_attention(oracle_from_export(oc, P.export_numpy(cache)), q)
+    assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
 
 
 @pytest.mark.parametrize("T", [1, 15, 16, 17, 64, 65])
