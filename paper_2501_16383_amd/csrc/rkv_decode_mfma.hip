@@ -419,8 +419,20 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       if constexpr (LM && META8) {
         // G scale bytes, then G zero-point bytes -> (scale, zero-point) fp16 pairs, the form the softmax phase takes
         const uint8_t* vm8 = reinterpret_cast<const uint8_t*>(v.vm) + ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * (2 * G);
-#pragma unroll
-        for (int i = 0; i < G; ++i) dv[i] = rkv_pack_meta(rkv_e4m3_decode(vm8[i]), (float)vm8[G + i] - 128.0f);
+        uint32_t sw, zw;
+        if constexpr (G == 4) {
+          const uint2 u = rkv_ld_stream(reinterpret_cast<const uint2*>(vm8));
+          sw = u.x; zw = u.y;
+        } else {
+          sw = *reinterpret_cast<const uint32_t*>(vm8);
+          zw = sw >> 16;
+        }
+        dv[0] = rkv_pack_meta(__builtin_amdgcn_cvt_f32_fp8((int)sw, 0), (float)(zw & 0xffu) - 128.0f);
+        dv[1] = rkv_pack_meta(__builtin_amdgcn_cvt_f32_fp8((int)sw, 1), (float)((zw >> 8) & 0xffu) - 128.0f);
+        if constexpr (G == 4) {
+          dv[2] = rkv_pack_meta(__builtin_amdgcn_cvt_f32_fp8((int)sw, 2), (float)((zw >> 16) & 0xffu) - 128.0f);
+          dv[3] = rkv_pack_meta(__builtin_amdgcn_cvt_f32_fp8((int)sw, 3), (float)(zw >> 24) - 128.0f);
+        }
       } else if constexpr (LM) {
         const size_t mi = ((size_t)(b * v.NRG + rg) * v.Tpad + t0 + tid) * G;
         if constexpr (G == 4) {
@@ -909,10 +921,19 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       if constexpr (LM) {
         // (read from LDS in the softmax phase)
       } else if constexpr (SUB != 0 && META8) {
-        const uint8_t* vm8 = reinterpret_cast<const uint8_t*>(v.vm) + 2 * mi;
+        // the head's NS scale bytes and NS zero-point bytes, one load each
+        const uint8_t* vm8 = reinterpret_cast<const uint8_t*>(v.vm) + 2 * mi + (wave < G ? wave : 0) * NS;
+        uint32_t sw, zw;
+        if constexpr (NS == 4) {
+          sw = *reinterpret_cast<const uint32_t*>(vm8);
+          zw = *reinterpret_cast<const uint32_t*>(vm8 + G * NS);
+        } else {
+          sw = *reinterpret_cast<const uint16_t*>(vm8);
+          zw = *reinterpret_cast<const uint16_t*>(vm8 + G * NS);
+        }
 #pragma unroll
         for (int sb = 0; sb < NS; ++sb)
-          vmeta[sb][i] = wave < G ? ((uint32_t)vm8[wave * NS + sb] | ((uint32_t)vm8[G * NS + wave * NS + sb] << 8)) : 0x8000u;
+          vmeta[sb][i] = wave < G ? __builtin_amdgcn_perm(zw, sw, 0x0c0c0000u | ((4u + sb) << 8) | sb) : 0x8000u;
       } else if constexpr (SUB != 0) {
 #pragma unroll
         for (int sb = 0; sb < NS; ++sb) vmeta[sb][i] = wave < G ? v.vm[mi + wave * NS + sb] : 0u;

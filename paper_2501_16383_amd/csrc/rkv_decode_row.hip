@@ -350,6 +350,14 @@ __global__ void __launch_bounds__(256, 3) k_scores_row(RkvView v, const float* _
 
 // d += (q of lane U of the quad) * k.  The operand modifier reads q from another lane; the hardware wants two
 // instructions between a vector write of q and this read: q is loaded from LDS and pinned by rs2_settle below.
+// (scale byte j of sw as FP8 E4M3, zero-point byte j of zw as value + 128) -> the fp16 (scale, zero-point) pair of
+// the other format (both numbers are exact in fp16), so that the table is made by one piece of code
+__device__ __forceinline__ uint32_t rs2_meta8_pair(uint32_t sw, uint32_t zw, int j) {
+  const float s_ = j == 0 ? __builtin_amdgcn_cvt_f32_fp8((int)sw, 0) : j == 1 ? __builtin_amdgcn_cvt_f32_fp8((int)sw, 1)
+                 : j == 2 ? __builtin_amdgcn_cvt_f32_fp8((int)sw, 2) : __builtin_amdgcn_cvt_f32_fp8((int)sw, 3);
+  return rkv_pack_meta(s_, (float)((zw >> (8 * j)) & 0xffu) - 128.0f);
+}
+
 typedef __attribute__((address_space(3))) unsigned char rs2_lds_u8;
 typedef __attribute__((address_space(3))) uint32_t rs2_lds_u32;
 
@@ -425,11 +433,21 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     for (int bp = 0; bp < G / 2; ++bp) cw[bp] = rkv_ld_stream(kt + 64 * bp + lane);
     if constexpr (LOCAL) {
       // the token's v.gm entries of this rotation group: a quarter of them per lane group
-      if (v.meta8) {                                       // v.gm scale bytes, then v.gm zero-point bytes: (scale | zero << 8)
+      if (v.meta8) {                                       // v.gm scale bytes, then v.gm zero-point bytes
         const uint8_t* m8 = reinterpret_cast<const uint8_t*>(v.km) + ((size_t)(b * v.NRG + rg) * v.Tpad + tt + tok) * (2 * v.gm) + kq * bpl;
+        uint32_t sw, zw;                                     // the lane's bpl scale bytes and zero-point bytes, one load each
+        if (bpl == 4) {
+          sw = *reinterpret_cast<const uint32_t*>(m8);
+          zw = *reinterpret_cast<const uint32_t*>(m8 + v.gm);
+        } else if (bpl == 2) {
+          sw = *reinterpret_cast<const uint16_t*>(m8);
+          zw = *reinterpret_cast<const uint16_t*>(m8 + v.gm);
+        } else {
+          sw = m8[0];
+          zw = m8[v.gm];
+        }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (i < bpl) ml[i] = (uint32_t)m8[i] | ((uint32_t)m8[v.gm + i] << 8);
+        for (int i = 0; i < 4; ++i) ml[i] = rs2_meta8_pair(sw, zw, i);
         return;
       }
       const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tt) * v.gm;
@@ -445,8 +463,16 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
         // (a base that is the same for all lanes plus a 32-bit lane offset: one register per lane, not an address pair)
         if (v.meta8) {                                     // G scale bytes, then G zero-point bytes per (token, rotation group)
           const uint8_t* m8 = reinterpret_cast<const uint8_t*>(v.km) + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt + moff) * (2 * G);
+          uint32_t sw, zw;
+          if constexpr (G == 4) {
+            const uint2 u = *reinterpret_cast<const uint2*>(m8);
+            sw = u.x; zw = u.y;
+          } else {
+            sw = *reinterpret_cast<const uint32_t*>(m8);
+            zw = sw >> 16;
+          }
 #pragma unroll
-          for (int j = 0; j < G; ++j) mw[k][j] = (uint32_t)m8[j] | ((uint32_t)m8[G + j] << 8);
+          for (int j = 0; j < G; ++j) mw[k][j] = rs2_meta8_pair(sw, zw, j);
           continue;
         }
         const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt) * G;
@@ -482,12 +508,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
   // the four table entries of one quantization block of the lane's token
   auto put_block = [&](int blk, uint32_t word) {
     float s_, z_;
-    if (v.meta8) {                                         // (scale byte | zero-point byte << 8)
-      s_ = rkv_e4m3_decode(word & 0xffu);
-      z_ = (float)((word >> 8) & 0xffu) - 128.0f;
-    } else {
-      rkv_unpack_meta(word, s_, z_);
-    }
+    rkv_unpack_meta(word, s_, z_);                         // (8-bit metadata were turned into this form when they were fetched)
     s_ *= 0.015625f;
     const float u0 = s_ * (0.f - z_), u1 = s_ * (1.f - z_), u2 = s_ * (2.f - z_), u3 = s_ * (3.f - z_);
     const uint32_t h01 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(u0, u1));
@@ -529,7 +550,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
         if (v.meta8) {
           const uint8_t* m8 = reinterpret_cast<const uint8_t*>(v.km) + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt + moff) * (2 * G);
 #pragma unroll
-          for (int j = 0; j < G; ++j) put_block(g2 * G + j, (uint32_t)m8[j] | ((uint32_t)m8[G + j] << 8));
+          for (int j = 0; j < G; ++j) put_block(g2 * G + j, rs2_meta8_pair(m8[j], m8[G + j], 0));
         } else {
           const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + 4 * k) * v.Tpad + tt) * G;
 #pragma unroll
