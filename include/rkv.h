@@ -283,6 +283,7 @@ int rkv_set_decode_path(rkv_cache* cache, int32_t path);
 #define RKV_KERNEL_SHUFFLE    2  /* append only: FWHT in registers (v_rotate = 1, reorder in blocks)  */
 #define RKV_KERNEL_MFMA       3  /* matrix-core kernels: reorder inside blocks of 128, rot_heads 2, 4 */
 #define RKV_KERNEL_MFMA_CROSS 4  /* their variant for a reorder across blocks inside rotation groups  */
+                                 /* (decode: scores by the scores kernel, the rest by the matrix-core one) */
 #define RKV_KERNEL_MFMA_SUB   5  /* their variant for quant_group 64 / 32 (decode: scores by the      */
                                  /* scores kernel of the whole-row path, the rest by the matrix-core one) */
 #define RKV_KERNEL_MFMA_ROW   6  /* a reorder over the whole row.  Decode: scores by a kernel of their */

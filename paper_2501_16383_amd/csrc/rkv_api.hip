@@ -76,7 +76,7 @@ static int check_config(const rkv_config* c, bool need_capacity) {
 }
 
 struct Offsets {
-  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, xmask, xtt, xgsel, xgid8, total;
+  size_t kc, km, vc, vm, kh, vh, sk, sv, spos, scnt, lens, nnew, cstart, tables, perm, pinv, gid, rope, hop, xgsel, xgid8, total;
   int Tpad;
 };
 
@@ -107,11 +107,8 @@ static Offsets plan(const rkv_config* c) {
   o.rope = p; p = align256(p + T * 64 * 8);
   o.hop = p; p = align256(p + 8 * 64 * 4 * 4);
   {
-    // passes of the matrix-core decode variants and quantization blocks per rotation group (see build_xtables)
-    const size_t g = c->rot_heads, nrg = c->n_kv_heads / c->rot_heads, sub = 128 / c->quant_group;
-    const size_t np = sub > 1 ? sub : g, xk = sub > 1 ? g * sub : g;
-    o.xmask = p; p = align256(p + nrg * g * np * 4 * 16);
-    o.xtt = p; p = align256(p + nrg * 128 * xk * g * 4);
+    // tables of the matrix-core append kernel's variants (see build_xtables)
+    const size_t g = c->rot_heads, nrg = c->n_kv_heads / c->rot_heads;
     o.xgsel = p; p = align256(p + nrg * 16 * g * 4);
     o.xgid8 = p; p = align256(p + nrg * 16 * g * 8);
   }
@@ -119,16 +116,17 @@ static Offsets plan(const rkv_config* c) {
   return o;
 }
 
-// Tables of the matrix-core kernels' variants (RkvView::xmask, xtt, xgsel), from the inverse
-// permutation (inv[c] = reordered position of rotated channel c).  Two cases need them:
+// Tables of the matrix-core append kernel's variants (RkvView::xgsel, xgid8), from the inverse
+// permutation (inv[c] = reordered position of rotated channel c):
 //   * a reorder that crosses 128-blocks but stays inside the rotation groups, groups of 128: the
-//     quantization block of a rotated channel is inv[c] / 128, one pass per block of the group;
-//   * quantization groups of 64 / 32 with a reorder inside the heads: block k = head * SUB + sub,
-//     sub = (inv[c] % 128) / quant_group (the append kernel's sub-group variant reads xgsel; the read
-//     half of this setting takes gid and needs none of these tables).
+//     quantization block of a rotated channel within its group is (inv[c] % n) / 128;
+//   * quantization groups of 64 / 32 with a reorder inside the heads: the sub-block of its head is
+//     (inv[c] % 128) / quant_group;
+//   * a reorder over the whole row: the row's block inv[c] / 128, a byte each.
+// (The read half of these settings takes gid.)
 static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int aligned, int* in_groups_out, hipStream_t s) {
   const RkvView& v = cache->v;
-  const int E = v.E, g = v.g, n = v.n, nrg = v.NRG, qg = v.qg, sub_n = 128 / qg;
+  const int E = v.E, g = v.g, n = v.n, nrg = v.NRG, qg = v.qg;
   int in_groups = (g == 2 || g == 4) ? 1 : 0;
   for (int c = 0; c < E && in_groups; ++c)
     if (inv[c] / n != c / n) in_groups = 0;
@@ -148,30 +146,18 @@ static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int 
     return RKV_OK;
   }
   if (!cross && !subs) return RKV_OK;
-  const int np = subs ? sub_n : g, xk = subs ? g * sub_n : g;
-  std::vector<uint32_t> xmask((size_t)nrg * g * np * 16, 0u), xgsel((size_t)nrg * 16 * g, 0u);
-  std::vector<float> xtt((size_t)nrg * 128 * xk * g, 0.f);
+  std::vector<uint32_t> xgsel((size_t)nrg * 16 * g, 0u);
   for (int rg = 0; rg < nrg; ++rg) {
     for (int c = 0; c < n; ++c) {                            // rotated channel of the group
-      const int blk = c >> 7, kap = c & 127, q = kap >> 5, vreg = (kap >> 3) & 3, e = kap & 7;
+      const int blk = c >> 7, kap = c & 127, q = kap >> 5;
       const int pos = inv[rg * n + c] - rg * n;              // reordered position within the group
       const int pass = subs ? (pos & 127) / qg : pos >> 7;
-      const int k = subs ? blk * sub_n + pass : pass;        // quantization block within the group
-      xmask[((((size_t)rg * g + blk) * np + pass) * 4 + q) * 4 + vreg] |= 0xFu << (4 * e);
-      {
-        // the append kernel's table: per (wave, lane group, rotated block) 2 bits for each of a lane's 8
-        // channels - the quantization block within the group, or the sub-block within the head
-        const int w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);   // 2 (wave & 1) + (wave >> 1) = w8
-        xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)pass << (2 * (kap & 7));
-      }
-      for (int i = 0; i < n; ++i) {                          // output channel i = 128 a + j of H_n (entries (-1)^popcount(i & c))
-        const float sgn = (__builtin_popcount((unsigned)(i & c)) & 1) ? -1.f : 1.f;
-        xtt[(((size_t)rg * 128 + (i & 127)) * xk + k) * g + (i >> 7)] += sgn;
-      }
+      // per (wave, lane group, rotated block) 2 bits for each of a lane's 8 channels: the quantization
+      // block within the group, or the sub-block within the head
+      const int w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);     // 2 (wave & 1) + (wave >> 1) = w8
+      xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)pass << (2 * (kap & 7));
     }
   }
-  RKV_HIP_CHECK(hipMemcpyAsync(v.xmask, xmask.data(), xmask.size() * 4, hipMemcpyHostToDevice, s));
-  RKV_HIP_CHECK(hipMemcpyAsync(v.xtt, xtt.data(), xtt.size() * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipMemcpyAsync(v.xgsel, xgsel.data(), xgsel.size() * 4, hipMemcpyHostToDevice, s));
   RKV_HIP_CHECK(hipStreamSynchronize(s));                    // the vectors go out of scope
   return RKV_OK;
@@ -261,8 +247,6 @@ RKV_EXPORT int rkv_cache_create(const rkv_config* cfg, void* dev_mem, size_t byt
   v.gid = (int*)(c->base + o.gid);
   v.rope = (float2*)(c->base + o.rope);
   v.hop = (uint32_t*)(c->base + o.hop);
-  v.xmask = (uint32_t*)(c->base + o.xmask);
-  v.xtt = (float*)(c->base + o.xtt);
   v.xgsel = (uint32_t*)(c->base + o.xgsel);
   v.xgid8 = (const uint2*)(c->base + o.xgid8);
   c->in_groups = 0;

@@ -408,7 +408,7 @@ size_t rkv_decode_scratch_bytes(const rkv_config* cfg) {
   size_t bytes = rkv_query_scratch_bytes(cfg->batch, cfg->n_q_heads) + rkv_partial_bytes(cfg->batch, cfg->n_q_heads, (int)Tpad) + 256;
   // a reorder over the whole row: the scores of the compressed stream pass through a buffer (k_scores_row)
   // (and groups of 64 / 32 where they take the same route)
-  if (cfg->perm_span > cfg->rot_heads * RKV_D || cfg->quant_group < 128) bytes += rkv_row_scores_bytes(cfg->batch, cfg->n_q_heads, cfg->max_tokens);
+  if (cfg->perm_span > RKV_D || cfg->quant_group < 128) bytes += rkv_row_scores_bytes(cfg->batch, cfg->n_q_heads, cfg->max_tokens);
   return bytes;
 }
 

@@ -218,13 +218,6 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // Hadamard operand with entries +-4 in place of +-1, accumulating onto the low plane's products,
 // so that the big products yield H_128 (c / 2) as before.  Value phase: it accumulates separately
 // and is folded in, times 4, once per chunk.  Sums stay exact: |H_128 (c / 2)| <= 960 < 1024.
-// XB: the reorder crosses 128-blocks inside the rotation group: a rotated channel belongs to any
-// of the group's G quantization blocks.  The key phase then runs G passes per channel tile, one
-// per quantization block: the FP4 operands are ANDed with that block's mask (xmask), the big
-// products yield H_128 of its codes alone, and the small products - with that block's scale in all
-// four slots, signs of H_g as before - accumulate over the passes.  The zero-points no longer
-// collapse onto channel 0; their term, sum over the quantization blocks of s z / 2 times the
-// rotated indicator of the block's channels (xtt), starts the accumulators.
 // SUB = 2 or 4 (with PRE): quantization groups of 64 or 32 channels, reorder inside the heads.  The
 // scores come from k_scores_row2 (a key phase of SUB masked passes over the sub-blocks was the
 // first design and measured slower); here every value head has SUB (scale, zero-point) pairs per
@@ -238,8 +231,8 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // (-infinity at retained sink tokens) in place of the key phase - a reorder over the whole token
 // row, whose scores k_scores_row computes; qt then points to that buffer.  Softmax, values and
 // partial results as in the plain kernel.
-template <int G, int REP, bool MULTI, bool META8, int HB, bool XB = false, int SUB = 0, bool ALU = false, bool PRE = false>
-__global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF_OCC)) k_decode_mfma(RkvView v, const float* __restrict__ qt,
+template <int G, int REP, bool MULTI, bool META8, int HB, int SUB = 0, bool ALU = false, bool PRE = false>
+__global__ void __launch_bounds__(256, (HB && G == 4) ? MF_OCC_HI : MF_OCC) k_decode_mfma(RkvView v, const float* __restrict__ qt,
                                                                        float* __restrict__ part, int nch,
                                                                        const int* __restrict__ q_lim, int nq, int ns, uint32_t inv_ns, uint32_t inv_nrg) {
   constexpr bool HI = HB != 0;
@@ -276,18 +269,13 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
   //     - 64 * Z_a(t) * (cos(t) * q~[h][pair 0, first half] + sin(t) * q~[h][pair 0, second half]),
   // is worked out once per token when the metadata are staged and put where the key phase adds
   // its sum (s_sc).
-  constexpr bool LM = !XB && SUB == 0;
+  constexpr bool LM = SUB == 0;
   constexpr int MWL = META8 ? G / 2 : G;             // metadata dwords per token and rotation group as stored
   constexpr int GP = G / 2;                          // packed pairs per token
   __shared__ __attribute__((aligned(16))) uint32_t s_ks[LM ? MF_CH * GP : 1], s_vm[LM ? MF_CH * G : 1];
-  constexpr int XK = XB ? G : 1;                     // quantization blocks of the rotation group
-  constexpr int NP = G;                              // passes of the key phase (cross-block variant)
-  __shared__ uint4 s_xmask[XB ? G * NP * 4 : 1];  // [rotated block][pass][lane group q]
-  __shared__ float s_xtt[XB ? 128 * XK * G : 1];  // [channel][quantization block][head]
-  static_assert(!XB || (REP == 1 && !MULTI && HB == 0), "the cross-block variant exists for one query head per workgroup, one query token, 2-bit codes");
   static_assert(SUB == 0 || PRE, "groups of 64 / 32 run on precomputed scores");
-  static_assert(!ALU || (!XB && !META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
-  static_assert(!PRE || (!XB && HB == 0 && !MULTI && !ALU), "precomputed scores: plain 2-bit layout, one query token");
+  static_assert(!ALU || (!META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
+  static_assert(!PRE || (HB == 0 && !MULTI && !ALU), "precomputed scores: plain 2-bit layout, one query token");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -480,17 +468,11 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       uint4 cw[G / 2], cwh[HI ? G / 2 : 1];
       constexpr int MW = META8 ? G / 2 : G;              // metadata dwords per token and rotation group
       uint32_t mw[4][MW];
-      uint32_t xmeta = 0, xmeta2 = 0;                      // cross-block variant: (scale, zero) of token n of the tile, quantization block q
       auto load_tile = [&](int ti) {
         if constexpr (ALU) {                                 // made-up codes
           const uint32_t x = (uint32_t)lane * 2654435761u ^ (uint32_t)(nq + ti);
 #pragma unroll
           for (int pr = 0; pr < G / 2; ++pr) cw[pr] = make_uint4(x, x * 3u, x * 5u, x * 7u + pr);
-        }
-        if constexpr (XB && !META8) xmeta = q < G ? kmeta[(size_t)(ti * 16 + n) * MW + q] : 0u;
-        if constexpr (XB && META8) {                       // the token's scale bytes and zero-point bytes
-          xmeta = kmeta[(size_t)(ti * 16 + n) * MW];
-          if constexpr (G == 4) xmeta2 = kmeta[(size_t)(ti * 16 + n) * MW + 1];
         }
 #pragma unroll
         for (int pr = 0; pr < G / 2; ++pr) if constexpr (!ALU) cw[pr] = rkv_ld_stream(ktiles + (size_t)ti * (32 * G) + pr * 64 + lane);
@@ -555,10 +537,6 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
       }
       if constexpr (MULTI) {
         if (tid < NH) s_lim[tid] = min(ld_lim, len - 1);
-      }
-      if constexpr (XB) {                              // this rotation group's masks and zero-point table
-        for (int i = tid; i < G * NP * 4; i += 256) s_xmask[i] = reinterpret_cast<const uint4*>(v.xmask)[(size_t)rg * (G * NP * 4) + i];
-        for (int i = tid; i < 128 * XK * G; i += 256) s_xtt[i] = v.xtt[(size_t)rg * (128 * XK * G) + i];
       }
       if constexpr (LM) {                              // thread = token of the chunk (inside the padded allocation)
         // a token's metadata as stored -> packed fp16 pairs (s01, s23) and (z01, z23)
@@ -685,37 +663,6 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 #pragma unroll
           for (int r = 0; r < 4; ++r) sA[r] = as_v4h((sw[r][0] ^ sm01) & keep_row, G == 4 ? (sw[r][1] ^ sm23) & keep_row : 0u);
         }
-        // cross-block variant: the block's fp16 scale in both halves of a dword, and - (s z / 2) of
-        // (token n, quantization block q), the A operand of the zero-point product
-        uint32_t xs2[XB ? 4 : 1][XB ? G : 1];
-        float xwa = 0.f;
-        constexpr int XSTEPS = (XK + 3) / 4;
-        if constexpr (XB) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int gq = 0; gq < G; ++gq) {
-              if constexpr (META8) {                       // scale byte gq of the token's first dword: FP8 -> fp32 -> fp16, exact
-                const float f = gq == 0 ? __builtin_amdgcn_cvt_f32_fp8((int)mw[r][0], 0)
-                              : gq == 1 ? __builtin_amdgcn_cvt_f32_fp8((int)mw[r][0], 1)
-                              : gq == 2 ? __builtin_amdgcn_cvt_f32_fp8((int)mw[r][0], 2)
-                                        : __builtin_amdgcn_cvt_f32_fp8((int)mw[r][0], 3);
-                xs2[r][gq] = pk_f16(f, f);
-              } else {
-                xs2[r][gq] = (mw[r][gq] & 0xffffu) * 0x10001u;
-              }
-            }
-          float s_ = 0.f, z_ = 0.f;
-          if constexpr (META8) {
-            if (q < G) {
-              s_ = __builtin_amdgcn_cvt_f32_fp8((int)(xmeta >> (8 * q)), 0);
-              z_ = (float)(((G == 4 ? xmeta2 : xmeta >> 16) >> (8 * q)) & 0xffu) - 128.0f;
-            }
-          } else {
-            rkv_unpack_meta(xmeta, s_, z_);
-          }
-          xwa = -0.5f * s_ * z_;
-        }
         if (ti + 1 < MF_TILES) load_tile(ti + 1);          // prefetch (inside the padded allocation)
 
         // The key phase runs in passes over RP of the lane's four tokens, so that the score
@@ -739,12 +686,10 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
             Hlo[0] = (int)h0.x; Hlo[1] = (int)h0.y; Hlo[2] = (int)h0.z; Hlo[3] = (int)h0.w; Hlo[4] = Hlo[5] = Hlo[6] = Hlo[7] = 0;
             Hhi[0] = (int)h1.x; Hhi[1] = (int)h1.y; Hhi[2] = (int)h1.z; Hhi[3] = (int)h1.w; Hhi[4] = Hhi[5] = Hhi[6] = Hhi[7] = 0;
             const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-            if constexpr (!XB) {
 #pragma unroll
-              for (int blk = 0; blk < G; ++blk) {
-                lo[blk] = mfma_fp4(A[blk], Hlo, zero4);
-                hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
-              }
+            for (int blk = 0; blk < G; ++blk) {
+              lo[blk] = mfma_fp4(A[blk], Hlo, zero4);
+              hi[blk] = mfma_fp4(A[blk], Hhi, zero4);
             }
             if constexpr (HI) {
               // FP4 1.0 (0x2) and -1.0 (0xA) with bit 2 set are 4.0 and -4.0
@@ -760,62 +705,6 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
               }
             }
           }
-          v4f xk_lo[XB ? 4 : 1], xk_hi[XB ? 4 : 1];           // cross-block variant: the keys of the lane's four tokens
-          if constexpr (XB) {
-            // zero-points: - sum over the quantization blocks of (s z / 2) * (rotated indicator)[head][channel],
-            // a [16 tokens x G] x [G x 16 channels] product in fp32 (s z is not an fp16 number) per head
-            // and channel tile; the result has the layout of the other accumulators
-            const int j_lo = v.rope_style ? 2 * (16 * p + n) : 16 * p + n, j_hi = v.rope_style ? j_lo + 1 : j_lo + 64;
-            const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-              v4f zl = zero4, zh = zero4;
-              if (a < G) {
-#pragma unroll
-                for (int st = 0; st < XSTEPS; ++st) {
-                  const int k = 4 * st + q;                   // this lane's quantization block of the step
-                  const float bl = k < XK ? s_xtt[(j_lo * XK + k) * G + a] : 0.f, bh = k < XK ? s_xtt[(j_hi * XK + k) * G + a] : 0.f;
-                  const float wa = xwa;
-                  zl = __builtin_amdgcn_mfma_f32_16x16x4f32(wa, bl, zl, 0, 0, 0);
-                  zh = __builtin_amdgcn_mfma_f32_16x16x4f32(wa, bh, zh, 0, 0, 0);
-                }
-              }
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                xk_lo[r][a] = zl[r];
-                xk_hi[r][a] = zh[r];
-              }
-            }
-#pragma unroll
-            for (int gq = 0; gq < NP; ++gq) {                 // pass: a quantization block of the group, or a sub-block of every head
-              const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-              v8i Hlo, Hhi;
-              const uint4 h0 = s_H[p][lane], h1 = s_H[p + 4][lane];
-              Hlo[0] = (int)h0.x; Hlo[1] = (int)h0.y; Hlo[2] = (int)h0.z; Hlo[3] = (int)h0.w; Hlo[4] = Hlo[5] = Hlo[6] = Hlo[7] = 0;
-              Hhi[0] = (int)h1.x; Hhi[1] = (int)h1.y; Hhi[2] = (int)h1.z; Hhi[3] = (int)h1.w; Hhi[4] = Hhi[5] = Hhi[6] = Hhi[7] = 0;
-#pragma unroll
-              for (int blk = 0; blk < G; ++blk) {
-                const uint4 m = s_xmask[(blk * NP + gq) * 4 + q];
-                v8i Am = A[blk];
-                Am[0] &= (int)m.x; Am[1] &= (int)m.y; Am[2] &= (int)m.z; Am[3] &= (int)m.w;
-                lo[blk] = mfma_fp4(Am, Hlo, zero4);
-                hi[blk] = mfma_fp4(Am, Hhi, zero4);
-              }
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                // the block's scale in all four slots (contraction over the rotated blocks), signs of H_g
-                const uint32_t s2 = xs2[r][gq];
-                const v4h sx = as_v4h((s2 ^ sm01) & keep_row, G == 4 ? (s2 ^ sm23) & keep_row : 0u);
-                if constexpr (G == 4) {
-                  xk_lo[r] = mfma_4x4x4(sx, as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), xk_lo[r]);
-                  xk_hi[r] = mfma_4x4x4(sx, as_v4h(pk_f16(hi[0][r], hi[1][r]), pk_f16(hi[2][r], hi[3][r])), xk_hi[r]);
-                } else {
-                  xk_lo[r] = mfma_4x4x4(sx, as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), xk_lo[r]);
-                  xk_hi[r] = mfma_4x4x4(sx, as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), xk_hi[r]);
-                }
-              }
-            }
-          }
           float c = cs_c[p], s = cs_s[p];                      // angles of the pass's first token (REP == 1: of token 4q)
 #pragma unroll
           for (int rr = 0; rr < RP; ++rr) {
@@ -826,17 +715,12 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
             // below 1024: exact in fp16), fp32 accumulate
             const v4f z4 = {0.f, 0.f, 0.f, 0.f};
             v4f klo, khi;
-            if constexpr (XB) {
-              klo = xk_lo[r];
-              khi = xk_hi[r];
-            } else {
             if constexpr (G == 4) {
               klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), pk_f16(lo[2][r], lo[3][r])), z4);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), pk_f16(hi[2][r], hi[3][r])), z4);
             } else {
               klo = mfma_4x4x4(sA[r], as_v4h(pk_f16(lo[0][r], lo[1][r]), 0u), z4);
               khi = mfma_4x4x4(sA[r], as_v4h(pk_f16(hi[0][r], hi[1][r]), 0u), z4);
-            }
             }
             // the query: with REP == 1 the copy rotated back by r positions, else the plain one
             // (floats 2 * REP * a .. of the row belong to KV head a: [query head of it][lo, hi])
@@ -1116,16 +1000,17 @@ __global__ void __launch_bounds__(256, XB ? 2 : ((HB && G == 4) ? MF_OCC_HI : MF
 
 
 
-// the cross-block variant of the kernel: a reorder inside the rotation groups, plain configuration
+// a reorder across 128-blocks inside the rotation groups, groups of 128: scores from the scores kernel
+// (the rotation group's own blocks in its table), softmax and values from this file's kernel
 static bool mfma_cross_block(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return !c->blocks_aligned && c->in_groups && v.qg == 128 && v.hb == 0 && (v.g == 2 || v.g == 4);
+  return !c->blocks_aligned && c->in_groups && v.qg == 128 && rkv_scores_local(c);
 }
 
-// groups of 64 / 32 with the reorder inside the heads: the sub-group variant of the same kernel
+// groups of 64 / 32 with the reorder inside the heads: the same route
 static bool mfma_sub_groups(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && v.qg < 128 && v.hb == 0 && (v.g == 2 || v.g == 4);
+  return c->blocks_aligned && v.qg < 128 && rkv_scores_local(c);
 }
 
 int rkv_mfma_variant(const rkv_cache* c) {
@@ -1146,13 +1031,13 @@ typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int,
 static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool alu) {
   const RkvView& v = c->v;
   // precomputed scores (groups of 64 / 32; a reorder over the whole row): softmax and value phases only
-#define RKV_MF_PRE(G_, R_, S_) (v.meta8 ? k_decode_mfma<G_, R_, false, true, 0, false, S_, false, true> : k_decode_mfma<G_, R_, false, false, 0, false, S_, false, true>)
-  if (rkv_scores_local(c)) {
+#define RKV_MF_PRE(G_, R_, S_) (v.meta8 ? k_decode_mfma<G_, R_, false, true, 0, S_, false, true> : k_decode_mfma<G_, R_, false, false, 0, S_, false, true>)
+  if (rkv_scores_local(c) && v.qg < 128) {
     const int sub = 128 / v.qg;
     if (v.g == 4) return sub == 4 ? RKV_MF_PRE(4, 1, 4) : RKV_MF_PRE(4, 1, 2);
     return sub == 4 ? RKV_MF_PRE(2, 1, 4) : RKV_MF_PRE(2, 1, 2);
   }
-  if (rkv_row_supported(c)) {
+  if (rkv_scores_path(c)) {                                 // (a reorder over the whole row, or across blocks inside the rotation groups)
     if (v.g == 4) return share == 1 ? RKV_MF_PRE(4, 1, 0) : RKV_MF_PRE(4, 2, 0);
     return share == 1 ? RKV_MF_PRE(2, 1, 0) : RKV_MF_PRE(2, 2, 0);
   }
@@ -1160,14 +1045,10 @@ static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool a
 #ifdef RKV_DEV_FEW_VARIANTS
   // developer builds: only the plain 2-bit variants of four-head rotation groups (quick to compile)
   if (multi || v.g != 4 || v.hb || v.meta8 || !c->blocks_aligned || v.qg != 128) abort();
-  if (alu) return k_decode_mfma<4, 1, false, false, 0, false, 0, true>;
+  if (alu) return k_decode_mfma<4, 1, false, false, 0, 0, true>;
   return share == 1 ? k_decode_mfma<4, 1, false, false, 0> : k_decode_mfma<4, 2, false, false, 0>;
 #else
-  if (mfma_cross_block(c)) {
-    if (v.g == 4) return v.meta8 ? k_decode_mfma<4, 1, false, true, 0, true> : k_decode_mfma<4, 1, false, false, 0, true>;
-    return v.meta8 ? k_decode_mfma<2, 1, false, true, 0, true> : k_decode_mfma<2, 1, false, false, 0, true>;
-  }
-  if (alu) return v.g == 4 ? k_decode_mfma<4, 1, false, false, 0, false, 0, true> : k_decode_mfma<2, 1, false, false, 0, false, 0, true>;
+  if (alu) return v.g == 4 ? k_decode_mfma<4, 1, false, false, 0, 0, true> : k_decode_mfma<2, 1, false, false, 0, 0, true>;
 #define RKV_MF_PICK(G_, R_, M_)                                                                            \
   do {                                                                                                     \
     if (v.hb == 2) return v.meta8 ? k_decode_mfma<G_, R_, M_, true, 2> : k_decode_mfma<G_, R_, M_, false, 2>; \
@@ -1213,8 +1094,8 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   const bool sg = mfma_sub_groups(c);
   const bool xb = mfma_cross_block(c) || sg;
   const bool row = rkv_scores_path(c);
-  if ((xb || row) && multi) return RKV_EINVAL;              // the cross-block and whole-row variants take one query token per step
-  const int share = xb ? 1 : rkv_mfma_share(rep);           // and (cross-block, sub-groups) one query head per workgroup
+  if ((xb || row) && multi) return RKV_EINVAL;              // the scores kernel serves one query token per step
+  const int share = xb ? 1 : rkv_mfma_share(rep);           // (cross-block, sub-groups: one query head per workgroup)
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   const int nch = (v.len + MF_CH - 1) / MF_CH;

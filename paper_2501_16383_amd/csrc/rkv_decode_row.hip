@@ -423,7 +423,8 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
   uint4 cw[G / 2];
   uint32_t mw[RS2_MPRE][G];
   uint32_t ml[4] = {0, 0, 0, 0};
-  const int bpl = LOCAL ? v.gm >> 2 : 0;                                  // blocks per lane group (1, 2 or 4)
+  const int bpl = LOCAL ? (v.gm >= 4 ? v.gm >> 2 : 1) : 0;                // blocks per lane group (1, 2 or 4; with two blocks, lane groups 0 and 1 take one each)
+  const bool lact = LOCAL && kq * bpl < v.gm;
   const uint32_t loff = LOCAL ? (uint32_t)(tok * v.gm + kq * bpl) : 0u;
   const uint32_t roff = (uint32_t)(tok * 64 + (STYLE == 0 ? 32 * g4hi + 4 * g4lo : 16 * g4hi + 2 * g4lo));   // the lane's place in a tile's RoPE rows
   const uint32_t moff = (uint32_t)(kq * v.Tpad + tok);   // metadata entry of (rotation group kq of a round, token), in units of G dwords
@@ -443,8 +444,8 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
           sw = *reinterpret_cast<const uint16_t*>(m8);
           zw = *reinterpret_cast<const uint16_t*>(m8 + v.gm);
         } else {
-          sw = m8[0];
-          zw = m8[v.gm];
+          sw = lact ? m8[0] : 0u;
+          zw = lact ? m8[v.gm] : 0u;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) ml[i] = rs2_meta8_pair(sw, zw, i);
@@ -453,7 +454,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
       const uint32_t* mrow = v.km + ((size_t)(b * v.NRG + rg) * v.Tpad + tt) * v.gm;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        if (i < bpl) ml[i] = mrow[loff + i];
+        if (i < bpl && lact) ml[i] = mrow[loff + i];
       return;
     }
 #pragma unroll
@@ -534,7 +535,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     if constexpr (LOCAL) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        if (i < bpl) put_block(kq * bpl + i, ml[i]);
+        if (i < bpl && lact) put_block(kq * bpl + i, ml[i]);
     }
 #pragma unroll
     for (int k = 0; k < (LOCAL ? 0 : RS2_MPRE); ++k) {
@@ -742,8 +743,8 @@ static bool row2_applies(const RkvView& v) {
   return (v.E >> 7) <= RS2_MAX_NG && row2_dynamic_lds(v, false) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
 }
 
-// Whether a cache takes this path: a reorder that leaves the rotation groups (else the plain or the
-// cross-block kernel serves it), 2-bit codes in groups of 128, rot_heads 2 or 4 (8-bit metadata where the
+// Whether a cache takes this path: a reorder that leaves the rotation groups (else the plain kernel or
+// rkv_scores_local's route serves it), 2-bit codes in groups of 128, rot_heads 2 or 4 (8-bit metadata where the
 // table-per-wave kernel applies).
 static size_t row_dynamic_lds(const RkvView& v) {
   const int nqh = v.g * (v.Hq / v.Hkv), NG = v.E >> 7;
@@ -759,17 +760,16 @@ bool rkv_row_supported(const rkv_cache* c) {
   return row_dynamic_lds(v) + fixed <= 80 * 1024 && v.NRG <= 32;
 }
 
-// Groups of 64 / 32 with the reorder inside the heads take the same route (scores from
-// k_scores_row2 with the rotation group's own blocks in the table, then the softmax and value
-// phases of the matrix-core kernel): a key phase of two or four masked passes over the sub-blocks
-// costs more (measured on config 2's geometry: 177 and 292 us against 162 and 175).
-#ifndef RKV_SCORES_LOCAL_MAX_QG
-#define RKV_SCORES_LOCAL_MAX_QG 64
-#endif
+// Groups of 64 / 32 with the reorder inside the heads, and a reorder across 128-blocks inside the
+// rotation groups, take the same route (scores from k_scores_row2 with the rotation group's own
+// blocks in the table, then the softmax and value phases of the matrix-core kernel): key phases of
+// masked passes over the blocks, the first design, cost more (measured on config 2's geometry:
+// 177, 292 and 160 us against 162, 175 and 153).
 bool rkv_scores_local(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && v.qg <= RKV_SCORES_LOCAL_MAX_QG && v.qg < 128 && v.hb == 0 && (v.g == 2 || v.g == 4) &&
-         row2_dynamic_lds(v, true) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
+  const bool sub = c->blocks_aligned && v.qg < 128;
+  const bool cross = !c->blocks_aligned && c->in_groups && v.qg == 128;
+  return (sub || cross) && v.hb == 0 && (v.g == 2 || v.g == 4) && row2_dynamic_lds(v, true) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
 }
 bool rkv_scores_path(const rkv_cache* c) { return rkv_row_supported(c) || rkv_scores_local(c); }
 

@@ -68,11 +68,7 @@ struct RkvView {
   int* gid;
   float2* rope;
   uint32_t* hop;     // Hadamard B-operand image for the FP4 matrix instruction: [8 tiles][64 lanes][4 dwords]
-  // For a reorder that crosses 128-blocks but stays inside the rotation groups (written by rkv_set_perm):
-  uint32_t* xmask;   // [rot group][rotated block][quantization block of the group][lane group q][4 dwords]: FP4-operand
-                     // nibbles (0xF) of the rotated block's channels that belong to that quantization block
-  float* xtt;        // [rot group][channel j 0..127][quantization block][head a]: (H_n m)[128 a + j], m = the
-                     // indicator of the quantization block's rotated channels, H_n with entries +-1
+  // Tables of the append kernel's variants (written by rkv_set_perm):
   uint32_t* xgsel;   // [rot group][wave 0..3][lane group q][head h]: the quantization blocks (2 bits each, element
                      // 4 ppl + rr) of the eight channels 128 h + 32 q + 8 (2 (wave & 1) + (wave >> 1)) + 4 ppl + rr
                      // that a lane of the append kernel's key role holds

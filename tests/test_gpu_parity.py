@@ -283,8 +283,8 @@ def test_whole_row_reorder_with_many_heads(heads):
 @pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
 def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style, fmt):
     """perm_span = the rotation size: the quantization blocks mix channels of all the group's heads.
-    The matrix-core decode kernel's cross-block variant (masked operands, one pass per quantization
-    block) against the oracle and against the general kernel: rotation over 4 and 2 heads, GQA,
+    The decode path for this setting (scores kernel with the rotation group's blocks in its table,
+    then the matrix-core kernel's softmax and value phases) against the oracle and against the general kernel: rotation over 4 and 2 heads, GQA,
     both RoPE pairings, both metadata formats, several chunks and a ragged tail, sinks, single-token
     steps, the current token as an exact row."""
     w = small("cfg1", n_q_heads=hq, n_kv_heads=8)
