@@ -76,7 +76,7 @@ def check_dequant(cache, oc_same_codes):
         print(f"[parity] dequantized {name}: max abs err {err.max():.3e}")
 
 
-def check_decode(cache, oc_same_codes, q, q_pos=None, tag="", lse_relative=False):
+def check_decode(cache, oc_same_codes, q, q_pos=None, tag="", lse_relative=False, lse_bar=None):
     qp = None if q_pos is None else P.gpu(np.asarray(q_pos, dtype=np.int32))
     out, lse = cache.decode_attention(P.gpu(q), qp, want_lse=True)
     torch.cuda.synchronize()
@@ -87,11 +87,11 @@ def check_decode(cache, oc_same_codes, q, q_pos=None, tag="", lse_relative=False
         le = le / np.maximum(1.0, np.abs(lse_ref))
     le = float(le.max())
     print(f"[parity] decode {tag}: out err {e:.3e}  lse err {le:.3e}", flush=True)
-    assert e <= ATT_TOL and le <= LSE_TOL
+    assert e <= ATT_TOL and le <= (LSE_TOL if lse_bar is None else lse_bar(lse_ref))
     return e
 
 
-def full_check(w, cfg, T, perm=None, sink_positions=None, chunks=None, q_pos=None, paths=(1,)):
+def full_check(w, cfg, T, perm=None, sink_positions=None, chunks=None, q_pos=None, paths=(1,), lse_bar=None):
     cache, oc, q = build_pair(w, cfg, T, perm, sink_positions, chunks)
     g, _, _ = P.check_cache_against_oracle(cache, oc, f"{w.name} T={T}")
     check_sinks(cache, oc)
@@ -99,12 +99,12 @@ def full_check(w, cfg, T, perm=None, sink_positions=None, chunks=None, q_pos=Non
     check_dequant(cache, oc_g)
     for path in paths:
         cache.set_decode_path(path)
-        check_decode(cache, oc_g, q, q_pos, tag=f"own codes path={path}")
+        check_decode(cache, oc_g, q, q_pos, tag=f"own codes path={path}", lse_bar=lse_bar)
     # the oracle's codes through the GPU read half
     P.import_oracle_codes(cache, oc)
     for path in paths:
         cache.set_decode_path(path)
-        check_decode(cache, oc, q, q_pos, tag=f"oracle codes path={path}")
+        check_decode(cache, oc, q, q_pos, tag=f"oracle codes path={path}", lse_bar=lse_bar)
     return cache, oc, q
 
 
@@ -1472,3 +1472,192 @@ def test_truncate_rolls_back_a_multi_token_step(uniform, bits):
         a.truncate([a.lengths[0] + 1, 0])                      # cannot grow
     a.truncate(0)
     assert a.lengths == [0, 0]
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_randomly_drawn_configurations(seed):
+    """Forty configurations per seed, drawn over everything a configuration may combine: rotation
+    size, GQA ratio, code width, group size, metadata format, RoPE pairing, reorder span, batch,
+    length (tile and chunk edges among them), retained rows, appends in pieces - most of them
+    settings with a matrix-core variant.  Each goes through full_check (write half bit for bit,
+    sinks, dequantize view, both decode paths on the GPU's and on the oracle's codes).
+    The synthetic keys carry massive activations, so the scores here run into the thousands; a
+    score is an fp32 sum over the rotation group's 128 g channels, in which the energy of the
+    group's other heads cancels only up to rounding, so its error scales with the group's largest
+    score and not with the head's own: the log-sum-exp bar is 1e-3, or 2e-6 (sqrt(512) 2^-24 is
+    1.3e-6) of the largest log-sum-exp of the case where that is more."""
+    import random
+    rnd = random.Random(seed)
+    lse_bar = lambda ref: max(LSE_TOL, 2e-6 * float(np.abs(ref).max()))
+    seen = set()
+    for i in range(40):
+        g = rnd.choice([2, 4, 4, 2, 4, 2, 4, 2, 1, 8])
+        hkv = rnd.choice([8, 16]) if g == 8 else rnd.choice([4, 8, 12, 16])
+        if hkv % g:
+            hkv = 8
+        hq = hkv * rnd.choice([1, 1, 2, 3, 4])
+        bits, group = rnd.choice([2, 2, 2, 3, 4]), rnd.choice([128, 128, 64, 32])
+        fmt, style = rnd.choice([0, 1]), rnd.choice([0, 1])
+        span = rnd.choice([128, 128, 128 * g, 128 * hkv])
+        if rnd.random() < 0.85:                                # a setting with a matrix-core variant (if g is 2 or 4)
+            kind = rnd.choice(["plain", "plain", "groups", "across blocks", "whole row"])
+            if kind == "plain":
+                group, span = 128, 128
+            elif kind == "groups":
+                bits, group, span = 2, rnd.choice([64, 32]), 128
+            elif kind == "across blocks":
+                bits, group, span = 2, 128, 128 * g
+            else:
+                bits, group, span = 2, 128, 128 * hkv
+        B = rnd.choice([1, 2, 3])
+        T = rnd.choice([1, 15, 16, 17, 63, 64, 65, 100, 255, 256, 257, rnd.randint(1, 600), rnd.randint(200, 900)])
+        sinks = rnd.choice([0, 4, 2])
+        w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
+        kw = dict(batch=B, n_q_heads=hq, n_kv_heads=hkv, max_tokens=T + rnd.choice([0, 1, 37]), max_sinks=sinks, rot_heads=g,
+                  meta_format=fmt, rope_style=style)
+        cfg = R.RkvConfig(bits=bits, quant_group=group, perm_span=span, **kw)
+        print(f"[case {i}] seed={seed} g={g} hq={hq} hkv={hkv} bits={bits} group={group} fmt={fmt} style={style} span={span} "
+              f"B={B} T={T} sinks={sinks}", flush=True)
+        perm = None
+        if span != 128 or rnd.random() < 0.8:
+            perm = calibrated_perm(w, R.RkvConfig(perm_span=span, **kw), offset_variant=span != 128)
+        cuts = sorted(set([0, T] + [rnd.randint(0, T) for _ in range(rnd.choice([0, 1, 3]))]))
+        probe = R.RkvCache(cfg)
+        if perm is not None:
+            probe.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+        kernel = probe.decode_kernel()
+        del probe
+        seen.add(kernel)
+        full_check(w, cfg, T, perm=perm, chunks=cuts, paths=(1, 0) if kernel == RB.KERNEL_GENERAL else (1, 2),
+                   sink_positions=[] if sinks == 0 or rnd.random() < 0.5 else None, lse_bar=lse_bar)
+    assert seen == {RB.KERNEL_GENERAL, RB.KERNEL_MFMA, RB.KERNEL_MFMA_CROSS, RB.KERNEL_MFMA_SUB, RB.KERNEL_MFMA_ROW}
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_randomly_drawn_steps_lengths_and_query_counts(seed):
+    """Forty configurations per seed, drawn as in test_randomly_drawn_configurations, through the
+    other entry points: a prefill with per-sequence lengths (empty sequences among them) where the
+    append kernel serves them, then one-call decode steps against the two calls on a second cache
+    (outputs, log-sum-exp, codes and metadata bit for bit; explicit query positions on every other
+    step), then - each sequence against an oracle cache of its own, on the GPU's codes - decode
+    attention on both kernels, its current-token variant, and two to four causal query tokens
+    (within the general kernel's limit of 8 rows per KV head where that kernel serves them)."""
+    import random
+    rnd = random.Random(seed)
+    for i in range(40):
+        g = rnd.choice([2, 4, 4, 2, 4, 2, 4, 2, 1, 8])
+        hkv = rnd.choice([8, 16]) if g == 8 else rnd.choice([4, 8, 12, 16])
+        if hkv % g:
+            hkv = 8
+        rep = rnd.choice([1, 1, 2, 3, 4])
+        hq = hkv * rep
+        bits, group = rnd.choice([2, 2, 2, 3, 4]), rnd.choice([128, 128, 64, 32])
+        fmt, style = rnd.choice([0, 1]), rnd.choice([0, 1])
+        span = rnd.choice([128, 128, 128 * g, 128 * hkv])
+        if rnd.random() < 0.85:
+            kind = rnd.choice(["plain", "plain", "groups", "across blocks", "whole row"])
+            if kind == "plain":
+                group, span = 128, 128
+            elif kind == "groups":
+                bits, group, span = 2, rnd.choice([64, 32]), 128
+            elif kind == "across blocks":
+                bits, group, span = 2, 128, 128 * g
+            else:
+                bits, group, span = 2, 128, 128 * hkv
+        B, sinks = rnd.choice([1, 2, 3, 4]), rnd.choice([0, 4, 2])
+        t_max = rnd.choice([1, 16, 17, 64, 65, 255, 256, 257, rnd.randint(1, 500), rnd.randint(100, 700)])
+        lens = [t_max] * B
+        if rnd.random() < 0.6:
+            lens = [rnd.choice([t_max, rnd.randint(0, t_max), rnd.randint(0, t_max), 0]) for _ in range(B)]
+            if max(lens) == 0:
+                lens[0] = t_max
+        n_steps = rnd.choice([1, 3, 5])
+        w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
+        kw = dict(batch=B, n_q_heads=hq, n_kv_heads=hkv, max_tokens=max(lens) + n_steps + rnd.choice([0, 1, 40]), max_sinks=sinks,
+                  rot_heads=g, meta_format=fmt, rope_style=style)
+        cfg = R.RkvConfig(bits=bits, quant_group=group, perm_span=span, **kw)
+        perm = None
+        if span != 128 or rnd.random() < 0.8:
+            perm = calibrated_perm(w, R.RkvConfig(perm_span=span, **kw), offset_variant=span != 128)
+        a, b2 = R.RkvCache(cfg), R.RkvCache(cfg)
+        if perm is not None:
+            for c in (a, b2):
+                c.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+        vector_append = a.append_kernel() in (RB.KERNEL_GENERAL, RB.KERNEL_SHUFFLE)
+        if vector_append:                                      # per-sequence lengths need the matrix-core append kernel
+            lens = [max(lens)] * B
+        total = [n + n_steps for n in lens]
+        print(f"[case {i}] seed={seed} g={g} hq={hq} hkv={hkv} bits={bits} group={group} fmt={fmt} style={style} span={span} "
+              f"lens={lens} steps={n_steps} sinks={sinks} kernels: decode {a.decode_kernel()} append {a.append_kernel()}", flush=True)
+        sp = [] if sinks == 0 or rnd.random() < 0.5 else None
+        data = [S.make_kv(w, total[s_] + 1, batch=1, layer=s_, sink_positions=sp) for s_ in range(B)]
+        ocs = [O.cache_new(P.oracle_cfg(dataclasses.replace(cfg, batch=1)), perm) for _ in range(B)]
+        n_max = max(lens)
+        k = np.zeros((B, n_max, hkv, 128), np.float16)
+        v = np.zeros_like(k)
+        m = np.zeros((B, n_max), np.uint8)
+        for s_ in range(B):
+            kb, vb, mb = data[s_]
+            n = lens[s_]
+            k[s_, :n], v[s_, :n], m[s_, :n] = kb[0, :n], vb[0, :n], mb[0, :n]
+            if n:
+                O.quantize_append(ocs[s_], kb[:, :n], vb[:, :n], mb[:, :n] if sinks else None)
+        for c in (a, b2):
+            if len(set(lens)) == 1:
+                c.quantize_append(P.gpu(k), P.gpu(v), P.gpu(m) if sinks else None)
+            else:
+                c.quantize_append_ragged(P.gpu(k), P.gpu(v), lens, P.gpu(m) if sinks else None)
+        for st in range(n_steps):
+            q = P.gpu(S.make_q(w, batch=B, step=st))
+            kk = np.stack([data[s_][0][0, lens[s_] + st] for s_ in range(B)])[:, None]
+            vv = np.stack([data[s_][1][0, lens[s_] + st] for s_ in range(B)])[:, None]
+            for s_ in range(B):
+                O.quantize_append(ocs[s_], kk[s_:s_ + 1], vv[s_:s_ + 1], None)
+            q_pos = None if st % 2 == 0 else P.gpu(np.array([lens[s_] + st + rnd.choice([0, 5, 300]) for s_ in range(B)], dtype=np.int32))
+            o1, l1 = a.decode_step(P.gpu(kk), P.gpu(vv), q, q_pos, want_lse=True)
+            b2.quantize_append(P.gpu(kk), P.gpu(vv))
+            o2, l2 = b2.decode_attention(q, q_pos, want_lse=True)
+            torch.cuda.synchronize()
+            assert torch.equal(o1, o2) and torch.equal(l1, l2), f"step {st}: one call against two"
+        assert a.lengths == total and b2.lengths == total
+        ea, eb = a.export_codes(), b2.export_codes()
+        torch.cuda.synchronize()
+        for s_ in range(B):
+            for name in ea:
+                assert torch.equal(ea[name][s_, :total[s_]], eb[name][s_, :total[s_]]), (name, s_)
+        gexp = P.export_numpy(a)
+        ocg = [oracle_from_export(ocs[s_], {name: arr[s_:s_ + 1, :total[s_]] for name, arr in gexp.items()}) for s_ in range(B)]
+        q = S.make_q(w, batch=B, step=77)
+        kc = np.concatenate([data[s_][0][:, total[s_]] for s_ in range(B)])
+        vc = np.concatenate([data[s_][1][:, total[s_]] for s_ in range(B)])
+        for path in ((1, 0) if a.decode_kernel() == RB.KERNEL_GENERAL else (1, 2)):
+            a.set_decode_path(path)
+            out, lse = a.decode_attention(P.gpu(q), want_lse=True)
+            out_cur = a.decode_attention(P.gpu(q), k_cur=P.gpu(kc), v_cur=P.gpu(vc))
+            torch.cuda.synchronize()
+            for s_ in range(B):
+                ref, lse_ref = O.decode_attention(ocg[s_], q[s_:s_ + 1])
+                e = P.attention_error(out[s_:s_ + 1].cpu().numpy().astype(np.float64), ref)
+                le = float(np.abs(lse[s_:s_ + 1].cpu().numpy() - lse_ref).max())
+                # (the log-sum-exp bar: see test_randomly_drawn_configurations)
+                assert e <= ATT_TOL and le <= max(LSE_TOL, 2e-6 * float(np.abs(lse_ref).max())), f"path {path} sequence {s_}: {e} {le}"
+                ref, _ = O.decode_attention(ocg[s_], q[s_:s_ + 1], None, kc[s_:s_ + 1], vc[s_:s_ + 1])
+                e = P.attention_error(out_cur[s_:s_ + 1].cpu().numpy().astype(np.float64), ref)
+                assert e <= ATT_TOL, f"current token, path {path}, sequence {s_}: {e}"
+        a.set_decode_path(0)
+        nq = rnd.choice([2, 3, 4])
+        try:
+            a.decode_kernel(nq)
+        except R.RkvError:                                     # beyond the general kernel's 8 rows per KV head: refused, not mis-computed
+            with pytest.raises(R.RkvError):
+                a.decode_attention_multi(P.gpu(np.zeros((B, nq, hq, 128), np.float16)), P.gpu(np.zeros((B, nq), np.int32)))
+            nq = max(1, 8 // rep)
+        if min(total) >= nq:
+            qn = np.stack([S.make_q(w, batch=B, step=20 + j) for j in range(nq)], axis=1)
+            q_pos = np.array([[total[s_] - nq + j for j in range(nq)] for s_ in range(B)], dtype=np.int32)
+            out = a.decode_attention_multi(P.gpu(qn), P.gpu(q_pos))
+            torch.cuda.synchronize()
+            for s_ in range(B):
+                ref, _ = O.decode_attention_multi(ocg[s_], qn[s_:s_ + 1], q_pos[s_:s_ + 1])
+                e = P.attention_error(out[s_:s_ + 1].cpu().numpy().astype(np.float64), ref)
+                assert e <= ATT_TOL, f"{nq} query tokens, sequence {s_}: {e}"
