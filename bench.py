@@ -225,7 +225,8 @@ def main():
         one_step(s)
     torch.cuda.synchronize()
     # which kernels this configuration takes (RKV_KERNEL_* of the library)
-    KIND_NAMES = {1: "general", 2: "shuffle", 3: "matrix-core", 4: "matrix-core, cross-block variant", 5: "matrix-core, sub-group variant"}
+    KIND_NAMES = {1: "general", 2: "shuffle", 3: "matrix-core", 4: "matrix-core, cross-block variant", 5: "matrix-core, sub-group variant",
+                  6: "matrix-core, whole-row variant"}
     kinds = (caches[0].decode_kernel(NQ if NQ > 1 else 0), caches[0].append_kernel())
     assert caches[0].length == T - K * NQ
     lens_now = caches[0].lengths
