@@ -419,13 +419,13 @@ def test_error_codes():
 
 
 def check_slice(exp, out, lse, b, rg, ks, vs, ms, q, perm=None, max_sinks=4, tag="", meta_format=0, rep=1, rope_theta=10000.0,
-                bits=2, group=128):
+                bits=2, group=128, span=128):
     """One (sequence, rotation group of 4 heads) slice of a full-size run against the oracle: a
     rotation group's codes and attention outputs depend on nothing outside the slice.  The codes
     must equal the oracle's outside the documented rounding ties; the attention output is then
     compared on the GPU's own codes, so that a tie cannot hide in (or leak into) the tolerance.
     exp: export_codes() tensors already on the host (numpy)."""
-    ocfg = O.OracleConfig(batch=1, n_q_heads=4 * rep, n_kv_heads=4, rot_heads=4, perm_span=128, max_sinks=max_sinks,
+    ocfg = O.OracleConfig(batch=1, n_q_heads=4 * rep, n_kv_heads=4, rot_heads=4, perm_span=span, max_sinks=max_sinks,
                           meta_format=meta_format, rope_theta=rope_theta, bits=bits, quant_group=group)
     hq = slice(4 * rep * rg, 4 * rep * (rg + 1))               # the query heads of the group's four KV heads
     oc = O.cache_new(ocfg, None if perm is None else perm[512 * rg:512 * (rg + 1)] - 512 * rg)
@@ -457,15 +457,17 @@ def export_host(cache):
     return {k: v.cpu().numpy() for k, v in exp.items()}
 
 
-@pytest.mark.parametrize("meta_format,bits,with_sinks,group", [(0, 2, True, 128), (0, 2, False, 128), (1, 2, True, 128), (0, 4, True, 128),
-                                                              (1, 3, False, 128), (0, 2, False, 64), (0, 2, True, 32)])
-def test_full_size_config2_sampled(meta_format, bits, with_sinks, group):
+@pytest.mark.parametrize("meta_format,bits,with_sinks,group,span", [(0, 2, True, 128, 128), (0, 2, False, 128, 128), (1, 2, True, 128, 128),
+                                                                   (0, 4, True, 128, 128), (1, 3, False, 128, 128), (0, 2, False, 64, 128),
+                                                                   (0, 2, True, 32, 128), (0, 2, False, 128, 512)])
+def test_full_size_config2_sampled(meta_format, bits, with_sinks, group, span):
     """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, then one rkv_decode_step (the last
     token's append and the attention on the matrix-core path).  The oracle recomputes sampled (sequence, rotation group) slices - a
     rotation group's codes and attention outputs depend on nothing outside the slice.  Once with
     fp16 metadata, once with the FP8 scale / INT8 zero-point storage, once with 4-bit codes, once with 3-bit codes and FP8 / INT8 metadata,
-    and with quantization groups of 64 and 32 (Table tab:quantgrani: the sub-group variants of both matrix-core kernels).
+    with quantization groups of 64 and 32 (Table tab:quantgrani: the sub-group variants of both matrix-core kernels),
+    and with the reorder over the rotation group (span 512: quantization blocks mix the group's four heads).
     With the workload's four fp16 sink rows, as bench.py runs it, and with no retained rows at
     all: the sink keys are a hundred times the rest and take nearly all the softmax weight, so only
     the run without them lets the compressed stream decide the outputs."""
@@ -473,8 +475,9 @@ def test_full_size_config2_sampled(meta_format, bits, with_sinks, group):
     T = w.context
     n_keep = 4 if with_sinks else 0
     cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=n_keep,
-                      rot_heads=4, perm_span=128, meta_format=meta_format, bits=bits, quant_group=group)
-    perm = calibrated_perm(w, cfg)
+                      rot_heads=4, perm_span=span, meta_format=meta_format, bits=bits, quant_group=group)
+    perm = calibrated_perm(w, cfg, offset_variant=span != 128)
+    assert span == 128 or not np.array_equal(perm // 128, np.arange(cfg.E) // 128)
     cache = R.RkvCache(cfg)
     cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
     samples = [(0, 0), (7, 3), (15, 9)]
@@ -499,7 +502,7 @@ def test_full_size_config2_sampled(meta_format, bits, with_sinks, group):
     cache.quantize_append(k[:, :T - 1].contiguous(), v[:, :T - 1].contiguous(), mask[:, :T - 1].contiguous() if with_sinks else None)
     cache.set_decode_path(2)
     # the kernels bench.py times, not a fall-back to the general ones
-    want_kind = RB.KERNEL_MFMA if group == 128 else RB.KERNEL_MFMA_SUB
+    want_kind = RB.KERNEL_MFMA_CROSS if span != 128 else RB.KERNEL_MFMA if group == 128 else RB.KERNEL_MFMA_SUB
     assert cache.decode_kernel() == want_kind and cache.append_kernel() == want_kind
     assert not bool(mask[:, T - 1:].any())                  # the step's token is an ordinary one
     out, lse = cache.decode_step(k[:, T - 1:].contiguous(), v[:, T - 1:].contiguous(), P.gpu(q), want_lse=True)
@@ -511,8 +514,8 @@ def test_full_size_config2_sampled(meta_format, bits, with_sinks, group):
     for (b, rg) in samples:
         ks, vs, ms = keep[(b, rg)]
         check_slice(exp, out, lse, b, rg, ks, vs, ms if with_sinks else None, q, perm=perm, max_sinks=n_keep,
-                    tag=f"full-size meta_format={meta_format} bits={bits} sinks={with_sinks} group={group}", meta_format=meta_format, bits=bits,
-                    group=group)
+                    tag=f"full-size meta_format={meta_format} bits={bits} sinks={with_sinks} group={group} span={span}",
+                    meta_format=meta_format, bits=bits, group=group, span=span)
 
 
 @pytest.mark.parametrize("with_sinks", [False, True])
