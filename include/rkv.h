@@ -208,8 +208,8 @@ int rkv_decode_attention(rkv_cache* cache, const void* dev_q, const int32_t* dev
  * for bit.  RKV_ESCRATCH - and nothing enqueued - if this call needs more than the built-in space:
  * 2560 bytes per (sequence, query head) plus 528 bytes per (sequence, query head, chunk of 256
  * cached tokens; of 128 on the general kernel), e.g. 7 MB for batch 16 x 40 heads x 4096 tokens.
- * With a reorder over the whole row, or groups of 64 / 32, on the matrix-core path the scores pass
- * through the work space as well: the partials then count the chunks of max_tokens, and 4 bytes
+ * With a reorder that crosses blocks of 128 (inside the rotation groups or over the whole row), or
+ * groups of 64 / 32, on the matrix-core path the scores pass through the work space as well: the partials then count the chunks of max_tokens, and 4 bytes
  * per (sequence, query head, token slot of max_tokens rounded up to 256) come on top.
  * All calls on one GPU share that GPU's array and it keeps the last call's contents (nothing in
  * it needs clearing: every partial a call reads it has written first): calls that overlap on one

@@ -63,6 +63,41 @@ def test_static_work_space_gives_the_same_results_twice_in_a_row(path):
     assert P.attention_error(out_b.cpu().numpy().astype(np.float64), ref) <= 2e-3
 
 
+@pytest.mark.parametrize("setting", ["whole row", "across blocks", "groups of 32"])
+def test_static_work_space_on_the_scores_kernel_paths(setting):
+    """Settings whose scores pass through the work space (a kernel of their own computes them, the
+    matrix-core kernel takes them from there): the static entry point against the ordinary one,
+    bit for bit, a larger cache first and a smaller one after it on the same built-in space."""
+    import dataclasses
+    from test_gpu_parity import calibrated_perm
+    w = dataclasses.replace(S.WORKLOADS["cfg1"], n_q_heads=16, n_kv_heads=8, n_sinks=0)
+    kw = dict(n_q_heads=16, n_kv_heads=8, max_sinks=0, rot_heads=4,
+              perm_span={"whole row": 1024, "across blocks": 512, "groups of 32": 128}[setting],
+              quant_group=32 if setting == "groups of 32" else 128)
+    kind = {"whole row": RB.KERNEL_MFMA_ROW, "across blocks": RB.KERNEL_MFMA_CROSS, "groups of 32": RB.KERNEL_MFMA_SUB}[setting]
+    results = []
+    caches = []
+    for batch, cap, T, layer in ((3, 1000, 700, 0), (2, 300, 290, 1)):
+        cfg = R.RkvConfig(batch=batch, max_tokens=cap, **kw)
+        perm = calibrated_perm(w, cfg, offset_variant=True)
+        k, v, _, q = P.make_case(w, cfg, T, layer=layer, sink_positions=[])
+        cache = R.RkvCache(cfg)
+        cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+        cache.quantize_append(P.gpu(k), P.gpu(v))
+        assert cache.decode_kernel() == kind
+        ref, lse_ref = cache.decode_attention(P.gpu(q), want_lse=True)
+        caches.append((cache, P.gpu(q), ref, lse_ref))
+    torch.cuda.synchronize()
+    print(f"[case] static work space, {setting}: batch 3 x 700 tokens, then batch 2 x 290 tokens", flush=True)
+    for cache, q, ref, lse_ref in caches:
+        out, lse = torch.full_like(ref, float("nan")), torch.full_like(lse_ref, float("nan"))
+        cache.decode_attention_static(q, out, lse=lse)
+        results.append((out, lse))
+    torch.cuda.synchronize()
+    for (cache, q, ref, lse_ref), (out, lse) in zip(caches, results):
+        assert torch.equal(out, ref) and torch.equal(lse, lse_ref)
+
+
 def test_static_work_space_rejects_what_does_not_fit():
     """Batch 64 x 64 heads x 4096 tokens needs 37 MB of partials: RKV_ESCRATCH, nothing enqueued,
     and the call with a work space of the caller's still works."""
