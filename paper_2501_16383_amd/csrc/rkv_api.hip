@@ -582,8 +582,8 @@ RKV_EXPORT int rkv_decode_step(rkv_cache* cache, const void* dev_k, const void* 
     return rc != RKV_OK ? rc : rkv_decode_attention(cache, dev_q, dev_q_pos, dev_out, dev_lse, dev_scratch, stream);
   }
   hipStream_t s = (hipStream_t)stream;
-  // (the cross-block and sub-group variants of the decode kernel take one query head per workgroup)
-  const int share = rkv_mfma_variant(cache) == RKV_KERNEL_MFMA ? rkv_mfma_share(cache->v.Hq / cache->v.Hkv) : 1;
+  // (the sub-group variant of the decode kernel takes one query head per workgroup)
+  const int share = rkv_mfma_variant(cache) == RKV_KERNEL_MFMA_SUB ? 1 : rkv_mfma_share(cache->v.Hq / cache->v.Hkv);
   int rc = rkv_launch_step_mfma(cache, (const __half*)dev_k, (const __half*)dev_v, (const __half*)dev_q, dev_q_pos,
                                 (float*)dev_scratch, share, s);
   if (rc == RKV_OK && cache->ragged) rc = rkv_launch_lens(cache, -1, 1, s);

@@ -1095,7 +1095,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   const bool xb = mfma_cross_block(c) || sg;
   const bool row = rkv_scores_path(c);
   if ((xb || row) && multi) return RKV_EINVAL;              // the scores kernel serves one query token per step
-  const int share = xb ? 1 : rkv_mfma_share(rep);           // (cross-block, sub-groups: one query head per workgroup)
+  const int share = sg ? 1 : rkv_mfma_share(rep);           // (groups of 64 / 32: one query head per workgroup)
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
   const int nch = (v.len + MF_CH - 1) / MF_CH;
