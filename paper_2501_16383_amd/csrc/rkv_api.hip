@@ -41,8 +41,6 @@ static int check_config(const rkv_config* c, bool need_capacity) {
   if (c->head_dim != RKV_D) return RKV_EINVAL;
   if (c->quant_group != 128 && c->quant_group != 64 && c->quant_group != 32) return RKV_EINVAL;
   if (c->bits < 2 || c->bits > 4) return RKV_EINVAL;
-  // (keys_rotated is a path of the matrix-core append kernel, which takes groups of 64 / 32 with 2-bit codes)
-  if (c->quant_group != 128 && c->keys_rotated && c->bits != 2) return RKV_EINVAL;
   if (c->clip_ratio != 1.0f) return RKV_EINVAL;
   if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads != 0) return RKV_EINVAL;
   if (c->n_q_heads / c->n_kv_heads > 8) return RKV_EINVAL;

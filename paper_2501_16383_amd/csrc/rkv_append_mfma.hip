@@ -140,7 +140,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   constexpr bool HI = HB == 2, H1 = HB == 1;
   constexpr float QMAX = HI ? 15.0f : (H1 ? 7.0f : 3.0f), INV_QMAX = HI ? 0.06666667f : (H1 ? 0.14285715f : 0.33333334f);
   constexpr int NSB = SUB ? SUB : 1, GM = G * NSB;      // quantization blocks per 128-block, per rotation group
-  static_assert(SUB == 0 || (HB == 0 && !XW), "groups of 64 / 32: 2-bit codes, reorder inside the heads");
+  static_assert(SUB == 0 || !XW, "groups of 64 / 32: reorder inside the heads");
   static_assert(!XW || HB == 0, "a reorder across blocks: 2-bit codes");
   constexpr bool OWN = SUB != 0 || XW;          // every element looks up its own quantization block (keys)
   __shared__ uint32_t meta[32 * GM];
@@ -317,10 +317,20 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
             const float4 pr = s_par[col * GMP + (SUB ? a * SUB : 0) + (int)((gsel[a] >> (2 * (4 * ppl + rr))) & 3u)];
-            const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + 3.0f);
+            const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + QMAX);
             word += (__float_as_uint(c) - __float_as_uint(pr.z)) << (16 * ppl + 4 * rr);
           }
-        img[pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = word << (2 * pph);
+        // (a code per nibble; wider codes: the bits above the low two go to their plane, as below)
+        const int io = pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d;
+        if constexpr (HI) {
+          img[io] = (word & 0x33333333u) << (2 * pph);
+          imgh[io] = ((word >> 2) & 0x33333333u) << (2 * pph);
+        } else if constexpr (H1) {
+          img[io] = (word & 0x33333333u) << (2 * pph);
+          imgh[(2 * pph + d) * (64 * G) + ((io - pph * (128 * G) - d) >> 1)] = ((word >> 2) & 0x11111111u) << (2 * d + pph);
+        } else {
+          img[io] = word << (2 * pph);
+        }
       }
     } else {
       // Eq. 6-9 on y = (raw rotation) / sqrt(n): min and max scale exactly (rounding is monotone),
@@ -787,8 +797,8 @@ bool rkv_append_mfma_supported(const rkv_cache* c) {
   // 2-bit codes, or wider ones (a second plane), in groups of 128; a reorder across 128-blocks
   // inside the rotation groups with 2-bit codes
   if (!c->blocks_aligned && !(c->in_groups && v.hb == 0 && !c->cfg.keys_rotated)) return false;
-  // groups of 64 / 32: 2-bit codes, a reorder inside the heads
-  if (v.qg != 128 && !(c->blocks_aligned && v.hb == 0)) return false;
+  // groups of 64 / 32: a reorder inside the heads (codes of 2, 3 or 4 bits)
+  if (v.qg != 128 && !c->blocks_aligned) return false;
   return (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 
@@ -817,23 +827,19 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
       hipLaunchKernelGGL(k_append_row_keys<2>, dim3(2 * max_slabs, v.B), dim3(256), dyn, s, v, k, n_new, slab0);
       hipLaunchKernelGGL(k_append_values<2>, dim3(max_slabs, v.NRG, v.B), dim3(256), 0, s, v, vv, n_new, slab0);
     }
-  } else if (v.qg == 64) {
-    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-    else hipLaunchKernelGGL((k_append_mfma<2, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  } else if (v.qg == 32) {
-    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0, false, 4>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-    else hipLaunchKernelGGL((k_append_mfma<2, 0, false, 4>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  } else if (!c->blocks_aligned) {
-    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-    else hipLaunchKernelGGL((k_append_mfma<2, 0, true>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  } else if (v.hb == 2) {
-    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-    else hipLaunchKernelGGL((k_append_mfma<2, 2>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  } else if (v.hb == 1) {
-    if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 1>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-    else hipLaunchKernelGGL((k_append_mfma<2, 1>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  } else if (v.g == 4) hipLaunchKernelGGL((k_append_mfma<4, 0>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
-  else hipLaunchKernelGGL((k_append_mfma<2, 0>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0);
+  } else {
+    // (G, bits above the low two, cross-block flag, sub-blocks per head)
+#define RKV_AP(G_, H_, X_, S_) hipLaunchKernelGGL((k_append_mfma<G_, H_, X_, S_>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0)
+#define RKV_AP_G(H_, X_, S_) do { if (v.g == 4) RKV_AP(4, H_, X_, S_); else RKV_AP(2, H_, X_, S_); } while (0)
+#define RKV_AP_H(X_, S_) do { if (v.hb == 2) RKV_AP_G(2, X_, S_); else if (v.hb == 1) RKV_AP_G(1, X_, S_); else RKV_AP_G(0, X_, S_); } while (0)
+    if (v.qg == 64) RKV_AP_H(false, 2);
+    else if (v.qg == 32) RKV_AP_H(false, 4);
+    else if (!c->blocks_aligned) RKV_AP_G(0, true, 0);
+    else RKV_AP_H(false, 0);
+#undef RKV_AP_H
+#undef RKV_AP_G
+#undef RKV_AP
+  }
   if (c->ev_stop) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
   return rkv_check_launch();
 }
@@ -846,22 +852,16 @@ int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const 
   int max_slabs = 1;                                        // one token touches one slab of its sequence
   const int n_append = 3 * max_slabs, rep = v.Hq / v.Hkv;
   dim3 grid(n_append + v.g * rep / 2, v.NRG, v.B);
-  if (v.qg == 64) {
-    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-    else hipLaunchKernelGGL((k_step_mfma<2, 0, false, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  } else if (v.qg == 32) {
-    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0, false, 4>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-    else hipLaunchKernelGGL((k_step_mfma<2, 0, false, 4>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  } else if (!c->blocks_aligned) {
-    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-    else hipLaunchKernelGGL((k_step_mfma<2, 0, true>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  } else if (v.hb == 2) {
-    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-    else hipLaunchKernelGGL((k_step_mfma<2, 2>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  } else if (v.hb == 1) {
-    if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 1>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-    else hipLaunchKernelGGL((k_step_mfma<2, 1>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  } else if (v.g == 4) hipLaunchKernelGGL((k_step_mfma<4, 0>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
-  else hipLaunchKernelGGL((k_step_mfma<2, 0>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share);
+#define RKV_ST(G_, H_, X_, S_) \
+  hipLaunchKernelGGL((k_step_mfma<G_, H_, X_, S_>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share)
+#define RKV_ST_G(H_, X_, S_) do { if (v.g == 4) RKV_ST(4, H_, X_, S_); else RKV_ST(2, H_, X_, S_); } while (0)
+#define RKV_ST_H(X_, S_) do { if (v.hb == 2) RKV_ST_G(2, X_, S_); else if (v.hb == 1) RKV_ST_G(1, X_, S_); else RKV_ST_G(0, X_, S_); } while (0)
+  if (v.qg == 64) RKV_ST_H(false, 2);
+  else if (v.qg == 32) RKV_ST_H(false, 4);
+  else if (!c->blocks_aligned) RKV_ST_G(0, true, 0);
+  else RKV_ST_H(false, 0);
+#undef RKV_ST_H
+#undef RKV_ST_G
+#undef RKV_ST
   return rkv_check_launch();
 }

@@ -275,7 +275,8 @@ __global__ void __launch_bounds__(256, (HB && G == 4) ? MF_OCC_HI : MF_OCC) k_de
   __shared__ __attribute__((aligned(16))) uint32_t s_ks[LM ? MF_CH * GP : 1], s_vm[LM ? MF_CH * G : 1];
   static_assert(SUB == 0 || PRE, "groups of 64 / 32 run on precomputed scores");
   static_assert(!ALU || (!META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
-  static_assert(!PRE || (HB == 0 && !MULTI && !ALU), "precomputed scores: plain 2-bit layout, one query token");
+  static_assert(!PRE || (!MULTI && !ALU), "precomputed scores: one query token");
+  static_assert(!PRE || HB == 0 || SUB != 0, "precomputed scores with wider codes: groups of 64 / 32");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -1031,16 +1032,18 @@ typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int,
 static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool alu) {
   const RkvView& v = c->v;
   // precomputed scores (groups of 64 / 32; a reorder over the whole row): softmax and value phases only
-#define RKV_MF_PRE(G_, R_, S_) (v.meta8 ? k_decode_mfma<G_, R_, false, true, 0, S_, false, true> : k_decode_mfma<G_, R_, false, false, 0, S_, false, true>)
-  if (rkv_scores_local(c) && v.qg < 128) {
+#define RKV_MF_PRE(G_, R_, S_, H_) (v.meta8 ? k_decode_mfma<G_, R_, false, true, H_, S_, false, true> : k_decode_mfma<G_, R_, false, false, H_, S_, false, true>)
+#define RKV_MF_PRE_SUB(G_, H_) (sub == 4 ? RKV_MF_PRE(G_, 1, 4, H_) : RKV_MF_PRE(G_, 1, 2, H_))
+  if (rkv_scores_local(c) && v.qg < 128) {                  // (groups of 64 / 32: codes of 2, 3 or 4 bits)
     const int sub = 128 / v.qg;
-    if (v.g == 4) return sub == 4 ? RKV_MF_PRE(4, 1, 4) : RKV_MF_PRE(4, 1, 2);
-    return sub == 4 ? RKV_MF_PRE(2, 1, 4) : RKV_MF_PRE(2, 1, 2);
+    if (v.g == 4) return v.hb == 2 ? RKV_MF_PRE_SUB(4, 2) : v.hb == 1 ? RKV_MF_PRE_SUB(4, 1) : RKV_MF_PRE_SUB(4, 0);
+    return v.hb == 2 ? RKV_MF_PRE_SUB(2, 2) : v.hb == 1 ? RKV_MF_PRE_SUB(2, 1) : RKV_MF_PRE_SUB(2, 0);
   }
   if (rkv_scores_path(c)) {                                 // (a reorder over the whole row, or across blocks inside the rotation groups)
-    if (v.g == 4) return share == 1 ? RKV_MF_PRE(4, 1, 0) : RKV_MF_PRE(4, 2, 0);
-    return share == 1 ? RKV_MF_PRE(2, 1, 0) : RKV_MF_PRE(2, 2, 0);
+    if (v.g == 4) return share == 1 ? RKV_MF_PRE(4, 1, 0, 0) : RKV_MF_PRE(4, 2, 0, 0);
+    return share == 1 ? RKV_MF_PRE(2, 1, 0, 0) : RKV_MF_PRE(2, 2, 0, 0);
   }
+#undef RKV_MF_PRE_SUB
 #undef RKV_MF_PRE
 #ifdef RKV_DEV_FEW_VARIANTS
   // developer builds: only the plain 2-bit variants of four-head rotation groups (quick to compile)

@@ -384,20 +384,26 @@ __device__ __forceinline__ void rs2_settle(float (&q)[2][4]) {
 // dynamic LDS: [4 waves][NG * 4 entries][16 tokens] dwords, [4 waves][G * rep][16] float partial sums, [G * rep][128] float
 // queries, [4 waves][4 * G * 8] dwords of block bytes, 64 sink positions
 // LOCAL: groups of 64 / 32 with the reorder inside the heads - the table holds the rotation group's own v.gm blocks
-template <int G, int STYLE, bool LOCAL>
-__global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const float* __restrict__ qr, float* __restrict__ sc, int rep) {
+// HB = 1, 2 (with LOCAL): codes of 3 and 4 bits, c = c_lo + 4 c_hi.  A wave's table gets a second half for the
+// plane of upper bits, with entries s * 4 c_hi, and every step looks up both planes and runs its products
+// twice onto the same accumulators (the rotation is linear).
+template <int G, int STYLE, bool LOCAL, int HB = 0>
+__global__ void __launch_bounds__(256, HB ? 2 : RS2_OCC) k_scores_row2(RkvView v, const float* __restrict__ qr, float* __restrict__ sc, int rep) {
+  static_assert(HB == 0 || LOCAL, "wider codes: the table of the rotation group's own blocks");
   constexpr int n = 128 * G;
+  constexpr int NPL = HB ? 2 : 1;                       // planes of code bits, each with its half of the table
   // (no static LDS in this kernel: the tables start where the workgroup's LDS starts, so that a table's byte
   // address >> 8 plus a block index stays below 256 for rows of up to RS2_MAX_NG blocks)
   extern __shared__ __attribute__((aligned(256))) unsigned char dyn2[];
   const int NG = LOCAL ? v.gm : v.E >> 7, nqh = G * rep;   // blocks in a wave's table
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  uint32_t* s_tab = reinterpret_cast<uint32_t*>(dyn2) + (size_t)wave * NG * 64;
-  float* s_pd = reinterpret_cast<float*>(dyn2 + (size_t)4 * NG * 256) + wave * nqh * 16;
-  const float* s_qp = reinterpret_cast<const float*>(dyn2 + (size_t)4 * NG * 256 + (size_t)4 * nqh * 64);
+  const int NGT = NG * NPL;                              // blocks of a wave's table, both halves
+  uint32_t* s_tab = reinterpret_cast<uint32_t*>(dyn2) + (size_t)wave * NGT * 64;
+  float* s_pd = reinterpret_cast<float*>(dyn2 + (size_t)4 * NGT * 256) + wave * nqh * 16;
+  const float* s_qp = reinterpret_cast<const float*>(dyn2 + (size_t)4 * NGT * 256 + (size_t)4 * nqh * 64);
   // [wave][q][head][dword dw][shift ksh]: four channels' quantization blocks, a byte each, plus (the wave's table >> 8)
-  uint32_t* s_g4 = reinterpret_cast<uint32_t*>(dyn2 + (size_t)4 * NG * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4);
+  uint32_t* s_g4 = reinterpret_cast<uint32_t*>(dyn2 + (size_t)4 * NGT * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4);
   int* s_sink = reinterpret_cast<int*>(s_g4 + 4 * 4 * G * 8);
   const int chunk = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
   const int len = rkv_len(v, b);
@@ -420,7 +426,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
   const int g4hi = kq >> 1, g4lo = kq & 1, qu = lane & 3;
   const int rounds = (v.NRG + 3) >> 2;
 
-  uint4 cw[G / 2];
+  uint4 cw[G / 2], cwh[HB ? G / 2 : 1];
   uint32_t mw[RS2_MPRE][G];
   uint32_t ml[4] = {0, 0, 0, 0};
   const int bpl = LOCAL ? (v.gm >= 4 ? v.gm >> 2 : 1) : 0;                // blocks per lane group (1, 2 or 4; with two blocks, lane groups 0 and 1 take one each)
@@ -432,6 +438,18 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     const uint4* kt = reinterpret_cast<const uint4*>(v.kc + rkv_k_tilebase(v, b, rg, tt >> 4));
 #pragma unroll
     for (int bp = 0; bp < G / 2; ++bp) cw[bp] = rkv_ld_stream(kt + 64 * bp + lane);
+    if constexpr (HB == 2) {                               // the plane of the upper two bits: the layout of the lower one
+      const uint4* kth = reinterpret_cast<const uint4*>(v.kh + rkv_k_tilebase(v, b, rg, tt >> 4));
+#pragma unroll
+      for (int bp = 0; bp < G / 2; ++bp) cwh[bp] = rkv_ld_stream(kth + 64 * bp + lane);
+    } else if constexpr (HB == 1) {                        // the plane of third bits: one dword per pair of code dwords
+      const uint2* kth = reinterpret_cast<const uint2*>(v.kh + (rkv_k_tilebase(v, b, rg, tt >> 4) >> 1));
+#pragma unroll
+      for (int bp = 0; bp < G / 2; ++bp) {
+        const uint2 u = rkv_ld_stream(kth + 64 * bp + lane);
+        cwh[bp] = make_uint4(u.x, u.y, 0, 0);
+      }
+    }
     if constexpr (LOCAL) {
       // the token's v.gm entries of this rotation group: a quarter of them per lane group
       if (v.meta8) {                                       // v.gm scale bytes, then v.gm zero-point bytes
@@ -498,7 +516,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     for (int j = 0; j < 4; ++j) w |= (uint32_t)(v.gid[rg * n + c0 + 2 * j] - (LOCAL ? rg * v.gm : 0)) << (8 * j);
     const uint32_t tab0 = (uint32_t)(uintptr_t)(rs2_lds_u8*)dyn2;     // LDS byte address of the first table (a multiple of 256)
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) s_g4[ww * (4 * G * 8) + tid] = w + (((tab0 >> 8) + (uint32_t)(ww * NG)) * 0x01010101u);
+    for (int ww = 0; ww < 4; ++ww) s_g4[ww * (4 * G * 8) + tid] = w + (((tab0 >> 8) + (uint32_t)(ww * NGT)) * 0x01010101u);
   }
   {
     float* qp = const_cast<float*>(s_qp);
@@ -507,11 +525,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
   __syncthreads();
 
   // the four table entries of one quantization block of the lane's token
-  auto put_block = [&](int blk, uint32_t word) {
-    float s_, z_;
-    rkv_unpack_meta(word, s_, z_);                         // (8-bit metadata were turned into this form when they were fetched)
-    s_ *= 0.015625f;
-    const float u0 = s_ * (0.f - z_), u1 = s_ * (1.f - z_), u2 = s_ * (2.f - z_), u3 = s_ * (3.f - z_);
+  auto put_four = [&](int blk, float u0, float u1, float u2, float u3) {
     const uint32_t h01 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(u0, u1));
     const uint32_t h23 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(u2, u3));
     float l0, l1, l2, l3;                                   // what the fp16 number misses (exact)
@@ -526,6 +540,13 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
     e[16] = __builtin_amdgcn_perm(l01, h01, 0x07060302u);
     e[32] = __builtin_amdgcn_perm(l23, h23, 0x05040100u);
     e[48] = __builtin_amdgcn_perm(l23, h23, 0x07060302u);
+  };
+  auto put_block = [&](int blk, uint32_t word) {
+    float s_, z_;
+    rkv_unpack_meta(word, s_, z_);                         // (8-bit metadata were turned into this form when they were fetched)
+    s_ *= 0.015625f;
+    put_four(blk, s_ * (0.f - z_), s_ * (1.f - z_), s_ * (2.f - z_), s_ * (3.f - z_));
+    if constexpr (HB != 0) put_four(NG + blk, 0.f, s_ * 4.f, s_ * 8.f, s_ * 12.f);   // the upper bits' share s * 4 c_hi
   };
 
   for (int it = 0; it < RS2_TILES; ++it) {
@@ -571,9 +592,10 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
           ang[mq][x] = *reinterpret_cast<const float4*>(rrow + (roff + j));
         }
     }
-    const uint4 cw0 = cw[0];
-    uint4 cw1 = cw0;
+    const uint4 cw0 = cw[0], ch0 = cwh[0];
+    uint4 cw1 = cw0, ch1 = ch0;
     if constexpr (G == 4) cw1 = cw[1];
+    if constexpr (G == 4 && HB != 0) ch1 = cwh[1];
     asm volatile("" ::: "memory");                        // (the LDS unit takes a wave's accesses in program order)
     __builtin_amdgcn_wave_barrier();
 #if RS2_EARLY
@@ -589,6 +611,9 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
         const int h = 2 * ph + hh;
         const uint4 cwp = ph == 0 ? cw0 : cw1;
         const uint32_t wd[2] = {hh ? cwp.z : cwp.x, hh ? cwp.w : cwp.y};
+        const uint4 chp = ph == 0 ? ch0 : ch1;
+        // upper plane: two dwords like the lower one's (4-bit codes), or the pair's dword of third bits
+        const uint32_t wdh[2] = {HB == 1 ? (hh ? chp.y : chp.x) : (hh ? chp.z : chp.x), HB == 1 ? (hh ? chp.y : chp.x) : (hh ? chp.w : chp.y)};
         const uint4* gp = reinterpret_cast<const uint4*>(s_g4 + wave * (4 * G * 8) + (kq * G + h) * 8);
         const uint4 gA = gp[0], gB = gp[1];
         const uint32_t g4w[8] = {gA.x, gA.y, gA.z, gA.w, gB.x, gB.y, gB.z, gB.w};
@@ -597,16 +622,25 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
 #endif
 #pragma unroll
         for (int sh = 0; sh < 8; sh += RS2_LOOK) {         // look-ups of RS2_LOOK steps, then their products
+#pragma unroll
+         for (int pl = 0; pl < NPL; ++pl) {                // (wider codes: the plane of the low two bits, then the upper one)
           uint32_t bv[RS2_LOOK][4];
 #pragma unroll
           for (int sl = 0; sl < RS2_LOOK; ++sl) {
             const int s = sh + sl, dw = s >> 2, ksh = s & 3;
             // LDS byte address of (block, code, token) = (table >> 8 + block) << 8 | code << 6 | token << 2: the low bytes of four
             // channels at once, then one byte permute per channel puts the block above
-            const uint32_t low4 = ((wd[dw] << (6 - 2 * ksh)) & 0xC0C0C0C0u) | tokrep;
+            uint32_t low4 = ((wd[dw] << (6 - 2 * ksh)) & 0xC0C0C0C0u) | tokrep;
+            uint32_t gw = g4w[s];
+            if (pl == 1) {
+              gw += (uint32_t)NG * 0x01010101u;            // the table's upper half
+              if constexpr (HB == 2) low4 = ((wdh[dw] << (6 - 2 * ksh)) & 0xC0C0C0C0u) | tokrep;
+              // third bit of code m = 4 j + ksh of dword dw: bit 8 j + 4 (ksh >> 1) + 2 dw + (ksh & 1) of the pair's dword
+              else low4 = (((wdh[dw] >> (4 * (ksh >> 1) + 2 * dw + (ksh & 1))) & 0x01010101u) << 6) | tokrep;
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              const uint32_t addr = __builtin_amdgcn_perm(g4w[s], low4, 0x0c0c0000u | ((4u + j) << 8) | j);
+              const uint32_t addr = __builtin_amdgcn_perm(gw, low4, 0x0c0c0000u | ((4u + j) << 8) | j);
               bv[sl][j] = *reinterpret_cast<const rs2_lds_u32*>((uintptr_t)addr);
             }
           }
@@ -620,7 +654,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
             for (int bb = 0; bb < 4; ++bb) {
               const int neg = (((bb >> 1) & (ksh & 1)) ^ ((bb & 1) & (ksh >> 1))) & 1;
               const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-              wpart[dw][bb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg ? A_neg : A_pos, B, ksh == 0 ? zero4 : wpart[dw][bb], 0, 0, 0);
+              wpart[dw][bb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg ? A_neg : A_pos, B, (ksh == 0 && pl == 0) ? zero4 : wpart[dw][bb], 0, 0, 0);
             }
 #else
 #pragma unroll
@@ -628,10 +662,11 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
               // input bits 4, 3, 0 = dw, ksh & 1, ksh >> 1 against the tile's bits 4, 3, 0 = mt >> 2, (mt >> 1) & 1, mt & 1
               const int neg = (((mt >> 2) & dw) ^ (((mt >> 1) & 1) & (ksh & 1)) ^ ((mt & 1) & (ksh >> 1))) & 1;
               const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-              acc[hh][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg ? A_neg : A_pos, B, s == 0 ? zero4 : acc[hh][mt], 0, 0, 0);
+              acc[hh][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg ? A_neg : A_pos, B, (s == 0 && pl == 0) ? zero4 : acc[hh][mt], 0, 0, 0);
             }
 #endif
           }
+         }
         }
 #if RS2_HALVES
         // bit 4 of the tile against the dword: the last stage of the transform in the lane
@@ -736,7 +771,7 @@ __global__ void __launch_bounds__(256, RS2_OCC) k_scores_row2(RkvView v, const f
 }
 
 static size_t row2_dynamic_lds(const RkvView& v, bool local) {
-  const int nqh = v.g * (v.Hq / v.Hkv), NG = local ? v.gm : v.E >> 7;
+  const int nqh = v.g * (v.Hq / v.Hkv), NG = (local ? v.gm : v.E >> 7) * (v.hb ? 2 : 1);   // (wider codes: a table half per plane)
   return (size_t)4 * NG * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4 + (size_t)4 * 4 * v.g * 8 * 4 + 256;
 }
 static bool row2_applies(const RkvView& v) {
@@ -767,9 +802,9 @@ bool rkv_row_supported(const rkv_cache* c) {
 // 177, 292 and 160 us against 162, 175 and 153).
 bool rkv_scores_local(const rkv_cache* c) {
   const RkvView& v = c->v;
-  const bool sub = c->blocks_aligned && v.qg < 128;
-  const bool cross = !c->blocks_aligned && c->in_groups && v.qg == 128;
-  return (sub || cross) && v.hb == 0 && (v.g == 2 || v.g == 4) && row2_dynamic_lds(v, true) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
+  const bool sub = c->blocks_aligned && v.qg < 128;                         // (2-, 3- or 4-bit codes)
+  const bool cross = !c->blocks_aligned && c->in_groups && v.qg == 128 && v.hb == 0;
+  return (sub || cross) && (v.g == 2 || v.g == 4) && row2_dynamic_lds(v, true) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
 }
 bool rkv_scores_path(const rkv_cache* c) { return rkv_row_supported(c) || rkv_scores_local(c); }
 
@@ -789,7 +824,13 @@ int rkv_launch_scores_row(const rkv_cache* c, const float* qr, float* sc, hipStr
     const size_t dyn = row2_dynamic_lds(v, local);
     dim3 grid((v.len + RS2_CHUNK - 1) / RS2_CHUNK, v.NRG, v.B);
     void (*fn)(RkvView, const float*, float*, int);
-    if (local)
+    if (local && v.hb == 2)
+      fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, true, 2> : k_scores_row2<4, 1, true, 2>)
+                    : (v.rope_style == 0 ? k_scores_row2<2, 0, true, 2> : k_scores_row2<2, 1, true, 2>);
+    else if (local && v.hb == 1)
+      fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, true, 1> : k_scores_row2<4, 1, true, 1>)
+                    : (v.rope_style == 0 ? k_scores_row2<2, 0, true, 1> : k_scores_row2<2, 1, true, 1>);
+    else if (local)
       fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, true> : k_scores_row2<4, 1, true>)
                     : (v.rope_style == 0 ? k_scores_row2<2, 0, true> : k_scores_row2<2, 1, true>);
     else

@@ -459,7 +459,8 @@ def export_host(cache):
 
 @pytest.mark.parametrize("meta_format,bits,with_sinks,group,span", [(0, 2, True, 128, 128), (0, 2, False, 128, 128), (1, 2, True, 128, 128),
                                                                    (0, 4, True, 128, 128), (1, 3, False, 128, 128), (0, 2, False, 64, 128),
-                                                                   (0, 2, True, 32, 128), (0, 2, False, 128, 512)])
+                                                                   (0, 2, True, 32, 128), (0, 2, False, 128, 512), (1, 3, False, 64, 128),
+                                                                   (0, 4, False, 32, 128)])
 def test_full_size_config2_sampled(meta_format, bits, with_sinks, group, span):
     """Configuration 2 (the throughput target) at full size (batch 16, 40 heads, context 4096), in the launch
     configuration bench.py times: bulk append of 4095 tokens, then one rkv_decode_step (the last
@@ -861,7 +862,7 @@ def test_fold_rotation_matches_oracle():
 
 
 @pytest.mark.parametrize("g,bits,group,fmt", [(4, 2, 128, 0), (2, 2, 128, 0), (4, 4, 128, 0), (2, 3, 128, 0), (4, 2, 64, 0), (2, 2, 32, 0),
-                                              (4, 2, 32, 0), (4, 2, 64, 1), (2, 2, 32, 1)])
+                                              (4, 2, 32, 0), (4, 2, 64, 1), (2, 2, 32, 1), (4, 4, 64, 0), (2, 3, 32, 1)])
 def test_rotated_keys_path(g, bits, group, fmt):
     """The deployment shape of Sec. 4.2: keys arrive already rotated and reordered (folded weights),
     the write half only quantizes and packs.  Codes under the tie protocol (the input is exact, so
@@ -891,7 +892,12 @@ def test_rotated_keys_path(g, bits, group, fmt):
     # (Eq. 8's division by 3 is a multiplication by the rounded reciprocal on the GPU: within 2^-23 of an
     # fp16 rounding boundary the stored scale may differ by one ulp, which the protocol allows in the
     # blocks it marks ambiguous; with four times the blocks, groups of 32 meet a couple of those)
-    assert sk["mismatched_scales"] <= (0 if group == 128 else min(4, sk["ambiguous_groups"]))
+    # (FP8 scales are rounded up: where a block's range is exactly 7 or 15 times an E4M3 number - the input is fp16 here,
+    # 30 of this case's 9600 blocks - the product with 1/7 or 1/15 rounded to fp32, 0.75 and 0.87 ulp above the
+    # quotient, can land just above that number and take the next step; 1/3 rounded lies 2^-25 above, which the
+    # product's own rounding always absorbs.  The protocol counts such blocks as ambiguous.)
+    cap = 4 if bits == 2 or fmt == 0 else 40
+    assert sk["mismatched_scales"] <= (0 if group == 128 else min(cap, sk["ambiguous_groups"]))
     s = {kk: vv.cpu().numpy() for kk, vv in cache.export_sinks().items()}
     for b in range(2):
         assert s["count"][b] == len(oc.sink_pos[b])
@@ -1127,7 +1133,7 @@ def test_shared_scratch_reused_across_caches():
             assert torch.equal(out, refs[i]), f"repetition {rep}, cache {i}"
 
 
-@pytest.mark.parametrize("bits,group", [(2, 128), (3, 128), (4, 128), (2, 64), (2, 32)])
+@pytest.mark.parametrize("bits,group", [(2, 128), (3, 128), (4, 128), (2, 64), (2, 32), (3, 32), (4, 64)])
 def test_sequences_of_different_lengths(bits, group):
     """(With 2-bit codes and with 3- and 4-bit codes, which the matrix-core kernels read as two planes;
     with 2-bit codes in groups of 64 and 32, which take their sub-group variants.)
@@ -1314,7 +1320,9 @@ def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
                                                       (2, 32, 2, 8, 0, 128), (4, 32, 1, 8, 1, 128), (3, 64, 8, 16, 1, 128),
                                                       (4, 64, 4, 8, 0, 512), (3, 32, 2, 8, 0, 1024), (4, 128, 2, 16, 1, 128),
                                                       (4, 128, 4, 32, 0, 128), (3, 128, 2, 16, 1, 128), (3, 128, 4, 32, 0, 128),
-                                                      (2, 32, 4, 16, 0, 128), (2, 64, 2, 8, 0, 128)])
+                                                      (2, 32, 4, 16, 0, 128), (2, 64, 2, 8, 0, 128), (4, 64, 4, 8, 0, 128),
+                                                      (3, 32, 2, 8, 1, 128), (4, 32, 4, 16, 1, 128), (3, 64, 4, 8, 0, 128),
+                                                      (4, 32, 2, 16, 0, 128), (3, 64, 2, 16, 1, 128)])
 def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     """3- and 4-bit codes and quantization groups of 64 and 32 channels (Sec. 5.1; Tables
     tab:ablation and tab:quantgrani) through the write half, the export and dequantize views and
@@ -1332,9 +1340,9 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     if span != 128:
         perm = calibrated_perm(w, R.RkvConfig(perm_span=span, **kw), offset_variant=True)
         assert not np.array_equal(perm // group, np.arange(cfg.E) // group)
-    # wider codes in groups of 128 are read by the matrix-core decode kernel as two planes, 2-bit codes in
-    # smaller groups by its sub-group variant
-    on_matrix_cores = g in (2, 4) and span == 128 and ((bits in (3, 4) and group == 128) or bits == 2)
+    # wider codes in groups of 128 are read by the matrix-core decode kernel as two planes, codes in
+    # smaller groups by its sub-group variant (scores from the scores kernel, one table half per plane)
+    on_matrix_cores = g in (2, 4) and span == 128
     # half of the cases without any retained fp16 row, so that the compressed stream alone decides the outputs
     cache, oc, q = full_check(w, cfg, 213, perm=perm, chunks=[0, 100, 101, 102, 213], paths=(1, 2) if on_matrix_cores else (1, 0),
                               sink_positions=[] if (hq + group + bits) % 3 != 0 else None)
@@ -1507,7 +1515,7 @@ def test_randomly_drawn_configurations(seed):
             if kind == "plain":
                 group, span = 128, 128
             elif kind == "groups":
-                bits, group, span = 2, rnd.choice([64, 32]), 128
+                bits, group, span = rnd.choice([2, 2, 3, 4]), rnd.choice([64, 32]), 128
             elif kind == "across blocks":
                 bits, group, span = 2, 128, 128 * g
             else:
@@ -1562,7 +1570,7 @@ def test_randomly_drawn_steps_lengths_and_query_counts(seed):
             if kind == "plain":
                 group, span = 128, 128
             elif kind == "groups":
-                bits, group, span = 2, rnd.choice([64, 32]), 128
+                bits, group, span = rnd.choice([2, 2, 3, 4]), rnd.choice([64, 32]), 128
             elif kind == "across blocks":
                 bits, group, span = 2, 128, 128 * g
             else:
