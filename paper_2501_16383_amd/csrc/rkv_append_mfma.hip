@@ -109,11 +109,11 @@ __device__ __forceinline__ void fused_round_consts(float zero, float& base, floa
 // value waves of a slab, each contribute one bit in four to a dword of it.
 // HB = 2: 4-bit codes.  The same arithmetic with 15 steps; the upper two bits of every code go to a
 // second plane with the layout of the first (a second image in LDS, written the same way).
-// XW: the reorder crosses 128-blocks inside the rotation group (2-bit codes): a rotated channel's
+// XW: the reorder crosses 128-blocks inside the rotation group: a rotated channel's
 // quantization block is looked up (gid), the minima and maxima are kept per quantization block,
 // and every element takes the parameters of its own block.  Codes stay where they are - by
 // rotated channel - so only the key role differs.
-// SUB = 2 or 4: quantization groups of 64 or 32 channels (2-bit codes, either metadata format, reorder
+// SUB = 2 or 4: quantization groups of 64 or 32 channels (either metadata format, reorder
 // inside the heads): a rotated 128-block holds SUB quantization blocks, block head * SUB + sub of
 // the rotation group, and a rotated channel's sub-block follows from its reordered position (the
 // same per-cache table, 2 bits per channel).  Keys: the minima and maxima of a token's G * SUB
@@ -141,7 +141,6 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   constexpr float QMAX = HI ? 15.0f : (H1 ? 7.0f : 3.0f), INV_QMAX = HI ? 0.06666667f : (H1 ? 0.14285715f : 0.33333334f);
   constexpr int NSB = SUB ? SUB : 1, GM = G * NSB;      // quantization blocks per 128-block, per rotation group
   static_assert(SUB == 0 || !XW, "groups of 64 / 32: reorder inside the heads");
-  static_assert(!XW || HB == 0, "a reorder across blocks: 2-bit codes");
   constexpr bool OWN = SUB != 0 || XW;          // every element looks up its own quantization block (keys)
   __shared__ uint32_t meta[32 * GM];
   __shared__ float2 s_mm[OWN ? 1 : 2][OWN ? 1 : 2][OWN ? 1 : 16][OWN ? 1 : G];   // [dword half][product pair][token][head] (min, max) of a quarter block
@@ -794,9 +793,9 @@ int rkv_append_mfma_variant(const rkv_cache* c) {
 bool rkv_append_mfma_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
   if (append_row(c)) return true;
-  // 2-bit codes, or wider ones (a second plane), in groups of 128; a reorder across 128-blocks
-  // inside the rotation groups with 2-bit codes
-  if (!c->blocks_aligned && !(c->in_groups && v.hb == 0 && !c->cfg.keys_rotated)) return false;
+  // 2-bit codes, or wider ones (a second plane); a reorder across 128-blocks inside the rotation groups
+  // with keys in the original basis
+  if (!c->blocks_aligned && !(c->in_groups && !c->cfg.keys_rotated)) return false;
   // groups of 64 / 32: a reorder inside the heads (codes of 2, 3 or 4 bits)
   if (v.qg != 128 && !c->blocks_aligned) return false;
   return (v.g == 2 || v.g == 4) && v.v_rotate == 0;
@@ -834,7 +833,7 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
 #define RKV_AP_H(X_, S_) do { if (v.hb == 2) RKV_AP_G(2, X_, S_); else if (v.hb == 1) RKV_AP_G(1, X_, S_); else RKV_AP_G(0, X_, S_); } while (0)
     if (v.qg == 64) RKV_AP_H(false, 2);
     else if (v.qg == 32) RKV_AP_H(false, 4);
-    else if (!c->blocks_aligned) RKV_AP_G(0, true, 0);
+    else if (!c->blocks_aligned) RKV_AP_H(true, 0);
     else RKV_AP_H(false, 0);
 #undef RKV_AP_H
 #undef RKV_AP_G
@@ -858,7 +857,7 @@ int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const 
 #define RKV_ST_H(X_, S_) do { if (v.hb == 2) RKV_ST_G(2, X_, S_); else if (v.hb == 1) RKV_ST_G(1, X_, S_); else RKV_ST_G(0, X_, S_); } while (0)
   if (v.qg == 64) RKV_ST_H(false, 2);
   else if (v.qg == 32) RKV_ST_H(false, 4);
-  else if (!c->blocks_aligned) RKV_ST_G(0, true, 0);
+  else if (!c->blocks_aligned) RKV_ST_H(true, 0);
   else RKV_ST_H(false, 0);
 #undef RKV_ST_H
 #undef RKV_ST_G

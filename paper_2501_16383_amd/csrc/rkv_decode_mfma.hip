@@ -222,7 +222,8 @@ __device__ __forceinline__ float wave_allreduce(float x) {
 // scores come from k_scores_row2 (a key phase of SUB masked passes over the sub-blocks was the
 // first design and measured slower); here every value head has SUB (scale, zero-point) pairs per
 // token, so the softmax phase makes SUB sets of weight digits and a wave of the value phase takes
-// the set of the sub-block its 32 channels lie in.
+// the set of the sub-block its 32 channels lie in.  (HB composes with SUB and PRE: the value phase's plane of
+// upper bits does not depend on where the scores and the weights come from.)
 // ALU: measurement only.  The same kernel with the cache stream - K codes, K metadata, V codes,
 // V metadata - replaced by values made up in registers (from the lane number and a kernel
 // argument, so that nothing folds at compile time): what the arithmetic alone costs when no byte
@@ -276,7 +277,6 @@ __global__ void __launch_bounds__(256, (HB && G == 4) ? MF_OCC_HI : MF_OCC) k_de
   static_assert(SUB == 0 || PRE, "groups of 64 / 32 run on precomputed scores");
   static_assert(!ALU || (!META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
   static_assert(!PRE || (!MULTI && !ALU), "precomputed scores: one query token");
-  static_assert(!PRE || HB == 0 || SUB != 0, "precomputed scores with wider codes: groups of 64 / 32");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -1040,8 +1040,10 @@ static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool a
     return v.hb == 2 ? RKV_MF_PRE_SUB(2, 2) : v.hb == 1 ? RKV_MF_PRE_SUB(2, 1) : RKV_MF_PRE_SUB(2, 0);
   }
   if (rkv_scores_path(c)) {                                 // (a reorder over the whole row, or across blocks inside the rotation groups)
-    if (v.g == 4) return share == 1 ? RKV_MF_PRE(4, 1, 0, 0) : RKV_MF_PRE(4, 2, 0, 0);
-    return share == 1 ? RKV_MF_PRE(2, 1, 0, 0) : RKV_MF_PRE(2, 2, 0, 0);
+#define RKV_MF_PRE_X(G_, R_) (v.hb == 2 ? RKV_MF_PRE(G_, R_, 0, 2) : v.hb == 1 ? RKV_MF_PRE(G_, R_, 0, 1) : RKV_MF_PRE(G_, R_, 0, 0))
+    if (v.g == 4) return share == 1 ? RKV_MF_PRE_X(4, 1) : RKV_MF_PRE_X(4, 2);
+    return share == 1 ? RKV_MF_PRE_X(2, 1) : RKV_MF_PRE_X(2, 2);
+#undef RKV_MF_PRE_X
   }
 #undef RKV_MF_PRE_SUB
 #undef RKV_MF_PRE

@@ -803,7 +803,7 @@ bool rkv_row_supported(const rkv_cache* c) {
 bool rkv_scores_local(const rkv_cache* c) {
   const RkvView& v = c->v;
   const bool sub = c->blocks_aligned && v.qg < 128;                         // (2-, 3- or 4-bit codes)
-  const bool cross = !c->blocks_aligned && c->in_groups && v.qg == 128 && v.hb == 0;
+  const bool cross = !c->blocks_aligned && c->in_groups && v.qg == 128;
   return (sub || cross) && (v.g == 2 || v.g == 4) && row2_dynamic_lds(v, true) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
 }
 bool rkv_scores_path(const rkv_cache* c) { return rkv_row_supported(c) || rkv_scores_local(c); }
