@@ -59,10 +59,10 @@ typedef struct rkv_config {
                         /* 3- and 4-bit codes in groups of 128 run on the matrix-core kernels    */
                         /* like 2-bit ones (the bits above the low two as a second plane);       */
                         /* groups of 64 / 32 have variants of the matrix-core kernels for every  */
-                        /* code width and either metadata format with a reorder inside the heads */
-                        /* (with a reorder across blocks those groups take the general kernels,  */
-                        /* which means no rkv_quantize_append_ragged and a two-kernel            */
-                        /* rkv_decode_step)                                                      */
+                        /* code width and either metadata format with a reorder inside the       */
+                        /* rotation groups (with a reorder over the whole row those groups take  */
+                        /* the general kernels, which means no rkv_quantize_append_ragged and a  */
+                        /* two-kernel rkv_decode_step)                                           */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
                         /* printed sorts the whole row).  The append kernel for a reorder across */
@@ -179,9 +179,8 @@ int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, 
  *   dev_k, dev_v    [batch][n_new_max][n_kv_heads][head_dim] fp16; rows beyond host_n_new[b] are not read
  *   host_n_new      [batch] int32 in host memory, 0 <= host_n_new[b] <= n_new_max; read before the call returns
  *   dev_sink_mask   [batch][n_new_max] uint8 or NULL
- * Needs a configuration the matrix-core append kernel covers (reorder inside blocks of 128 - or,
- * with groups of 128, inside the rotation groups, or with 2-bit codes anywhere in the row -, rot_heads 2 or 4,
- * v_rotate 0; quant_group 64 or 32 only with a reorder inside blocks of 128),
+ * Needs a configuration the matrix-core append kernel covers (a reorder inside the rotation groups -
+ * or, with 2-bit codes and groups of 128, anywhere in the row -, rot_heads 2 or 4, v_rotate 0),
  * else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
  * max_tokens (nothing is appended then).  rkv_import_codes returns RKV_ESTATE on such a cache;
  * the export and dequantize views cover rkv_cache_length tokens for every sequence, and what they
@@ -262,9 +261,9 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
 /* Choose the decode kernel: 0 = automatic (default), 1 = force the general kernel (any supported
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
  * the configuration is outside what it covers: a reorder across rotation groups, rot_heads 1 or
- * 8; a reorder across blocks of 128 inside the rotation groups only with groups of 128 and one
- * query token per step, one over the whole row only with 2-bit codes besides; quant_group 64 or 32
- * only with a reorder inside the heads and one query token per step).
+ * 8; a reorder across blocks of 128 inside the rotation groups only with one query token per
+ * step, one over the whole row only with 2-bit codes in groups of 128 besides; quant_group 64 or 32
+ * only with one query token per step).
  * 3 = measurement only: the matrix-core kernel with the cache stream (codes and metadata of keys
  * and values) replaced by values made up in registers, i.e. the time its arithmetic takes when no
  * byte of the cache has to arrive - the ceiling the vector and matrix units set.  Outputs are

@@ -129,7 +129,7 @@ static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int 
   for (int c = 0; c < E && in_groups; ++c)
     if (inv[c] / n != c / n) in_groups = 0;
   *in_groups_out = in_groups;
-  const bool cross = in_groups && !aligned && qg == 128, subs = aligned && qg < 128 && (g == 2 || g == 4);
+  const bool cross = in_groups && !aligned, subs = aligned && qg < 128 && (g == 2 || g == 4);
   if (!in_groups && !aligned && qg == 128 && (g == 2 || g == 4)) {
     // a reorder over the whole row: the row's quantization block of every rotated channel, as bytes in the
     // order the append kernel's lanes hold them
@@ -149,11 +149,13 @@ static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int 
     for (int c = 0; c < n; ++c) {                            // rotated channel of the group
       const int blk = c >> 7, kap = c & 127, q = kap >> 5;
       const int pos = inv[rg * n + c] - rg * n;              // reordered position within the group
-      const int pass = subs ? (pos & 127) / qg : pos >> 7;
+      const int pass = subs ? (pos & 127) / qg : pos / qg;
       // per (wave, lane group, rotated block) 2 bits for each of a lane's 8 channels: the quantization
-      // block within the group, or the sub-block within the head
+      // block within the group, or the sub-block within the head (4 bits each for a reorder across blocks
+      // with groups of 64 / 32: any of the group's g * 128 / quant_group <= 16 blocks)
+      const int gb = (cross && qg < 128) ? 4 : 2;
       const int w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);     // 2 (wave & 1) + (wave >> 1) = w8
-      xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)pass << (2 * (kap & 7));
+      xgsel[(((size_t)rg * 4 + wave) * 4 + q) * g + blk] |= (uint32_t)pass << (gb * (kap & 7));
     }
   }
   RKV_HIP_CHECK(hipMemcpyAsync(v.xgsel, xgsel.data(), xgsel.size() * 4, hipMemcpyHostToDevice, s));

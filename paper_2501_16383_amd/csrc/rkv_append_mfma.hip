@@ -113,8 +113,9 @@ __device__ __forceinline__ void fused_round_consts(float zero, float& base, floa
 // quantization block is looked up (gid), the minima and maxima are kept per quantization block,
 // and every element takes the parameters of its own block.  Codes stay where they are - by
 // rotated channel - so only the key role differs.
-// SUB = 2 or 4: quantization groups of 64 or 32 channels (either metadata format, reorder
-// inside the heads): a rotated 128-block holds SUB quantization blocks, block head * SUB + sub of
+// SUB = 2 or 4: quantization groups of 64 or 32 channels (either metadata format; with XW the reorder may
+// cross the heads of the rotation group, and a channel's block is any of its G * SUB, 4 bits in the table;
+// else it stays inside the heads): a rotated 128-block holds SUB quantization blocks, block head * SUB + sub of
 // the rotation group, and a rotated channel's sub-block follows from its reordered position (the
 // same per-cache table, 2 bits per channel).  Keys: the minima and maxima of a token's G * SUB
 // blocks are gathered with LDS float atomics (every element goes to its own block's pair), one
@@ -140,7 +141,9 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
   constexpr bool HI = HB == 2, H1 = HB == 1;
   constexpr float QMAX = HI ? 15.0f : (H1 ? 7.0f : 3.0f), INV_QMAX = HI ? 0.06666667f : (H1 ? 0.14285715f : 0.33333334f);
   constexpr int NSB = SUB ? SUB : 1, GM = G * NSB;      // quantization blocks per 128-block, per rotation group
-  static_assert(SUB == 0 || !XW, "groups of 64 / 32: reorder inside the heads");
+  // bits of a channel's block number in the per-cache table, and what is added to it: the sub-block of the
+  // channel's own head (2 bits, plus head * SUB), or any block of the rotation group (2 bits; 4 with sub-blocks)
+  constexpr int GB = (XW && SUB) ? 4 : 2;
   constexpr bool OWN = SUB != 0 || XW;          // every element looks up its own quantization block (keys)
   __shared__ uint32_t meta[32 * GM];
   __shared__ float2 s_mm[OWN ? 1 : 2][OWN ? 1 : 2][OWN ? 1 : 16][OWN ? 1 : G];   // [dword half][product pair][token][head] (min, max) of a quarter block
@@ -269,7 +272,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
-            const int blk = (q * 16 + col) * GMP + (SUB ? h * SUB : 0) + (int)((gsel[h] >> (2 * (4 * ppl + rr))) & 3u);
+            const int blk = (q * 16 + col) * GMP + ((SUB && !XW) ? h * SUB : 0) + (int)((gsel[h] >> (GB * (4 * ppl + rr))) & ((1u << GB) - 1u));
             lds_fmin(&s_mn[blk], acc[h][ppl][rr]);
             lds_fmax(&s_mx[blk], acc[h][ppl][rr]);
           }
@@ -315,7 +318,7 @@ __device__ __forceinline__ void append_mfma_body(const RkvView& v, const __half*
         for (int ppl = 0; ppl < 2; ++ppl)
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
-            const float4 pr = s_par[col * GMP + (SUB ? a * SUB : 0) + (int)((gsel[a] >> (2 * (4 * ppl + rr))) & 3u)];
+            const float4 pr = s_par[col * GMP + ((SUB && !XW) ? a * SUB : 0) + (int)((gsel[a] >> (GB * (4 * ppl + rr))) & ((1u << GB) - 1u))];
             const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + QMAX);
             word += (__float_as_uint(c) - __float_as_uint(pr.z)) << (16 * ppl + 4 * rr);
           }
@@ -797,7 +800,7 @@ bool rkv_append_mfma_supported(const rkv_cache* c) {
   // with keys in the original basis
   if (!c->blocks_aligned && !(c->in_groups && !c->cfg.keys_rotated)) return false;
   // groups of 64 / 32: a reorder inside the heads (codes of 2, 3 or 4 bits)
-  if (v.qg != 128 && !c->blocks_aligned) return false;
+  if (v.qg != 128 && !c->blocks_aligned && !c->in_groups) return false;   // (or inside the rotation groups)
   return (v.g == 2 || v.g == 4) && v.v_rotate == 0;
 }
 
@@ -831,8 +834,10 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
 #define RKV_AP(G_, H_, X_, S_) hipLaunchKernelGGL((k_append_mfma<G_, H_, X_, S_>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0)
 #define RKV_AP_G(H_, X_, S_) do { if (v.g == 4) RKV_AP(4, H_, X_, S_); else RKV_AP(2, H_, X_, S_); } while (0)
 #define RKV_AP_H(X_, S_) do { if (v.hb == 2) RKV_AP_G(2, X_, S_); else if (v.hb == 1) RKV_AP_G(1, X_, S_); else RKV_AP_G(0, X_, S_); } while (0)
-    if (v.qg == 64) RKV_AP_H(false, 2);
-    else if (v.qg == 32) RKV_AP_H(false, 4);
+    if (v.qg == 64 && c->blocks_aligned) RKV_AP_H(false, 2);
+    else if (v.qg == 32 && c->blocks_aligned) RKV_AP_H(false, 4);
+    else if (v.qg == 64) RKV_AP_H(true, 2);
+    else if (v.qg == 32) RKV_AP_H(true, 4);
     else if (!c->blocks_aligned) RKV_AP_H(true, 0);
     else RKV_AP_H(false, 0);
 #undef RKV_AP_H
@@ -855,8 +860,10 @@ int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* vv, const 
   hipLaunchKernelGGL((k_step_mfma<G_, H_, X_, S_>), grid, dim3(256), 0, s, v, k, vv, v.len >> 5, n_append, q, q_pos, qr, share)
 #define RKV_ST_G(H_, X_, S_) do { if (v.g == 4) RKV_ST(4, H_, X_, S_); else RKV_ST(2, H_, X_, S_); } while (0)
 #define RKV_ST_H(X_, S_) do { if (v.hb == 2) RKV_ST_G(2, X_, S_); else if (v.hb == 1) RKV_ST_G(1, X_, S_); else RKV_ST_G(0, X_, S_); } while (0)
-  if (v.qg == 64) RKV_ST_H(false, 2);
-  else if (v.qg == 32) RKV_ST_H(false, 4);
+  if (v.qg == 64 && c->blocks_aligned) RKV_ST_H(false, 2);
+  else if (v.qg == 32 && c->blocks_aligned) RKV_ST_H(false, 4);
+  else if (v.qg == 64) RKV_ST_H(true, 2);
+  else if (v.qg == 32) RKV_ST_H(true, 4);
   else if (!c->blocks_aligned) RKV_ST_H(true, 0);
   else RKV_ST_H(false, 0);
 #undef RKV_ST_H

@@ -1008,10 +1008,10 @@ static bool mfma_cross_block(const rkv_cache* c) {
   return !c->blocks_aligned && c->in_groups && v.qg == 128 && rkv_scores_local(c);
 }
 
-// groups of 64 / 32 with the reorder inside the heads: the same route
+// groups of 64 / 32 with the reorder inside the rotation groups: the same route
 static bool mfma_sub_groups(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return c->blocks_aligned && v.qg < 128 && rkv_scores_local(c);
+  return v.qg < 128 && rkv_scores_local(c);
 }
 
 int rkv_mfma_variant(const rkv_cache* c) {

@@ -795,14 +795,14 @@ bool rkv_row_supported(const rkv_cache* c) {
   return row_dynamic_lds(v) + fixed <= 80 * 1024 && v.NRG <= 32;
 }
 
-// Groups of 64 / 32 with the reorder inside the heads, and a reorder across 128-blocks inside the
-// rotation groups, take the same route (scores from k_scores_row2 with the rotation group's own
+// Groups of 64 / 32, and a reorder across 128-blocks inside the rotation groups (with either group size),
+// take the same route (scores from k_scores_row2 with the rotation group's own
 // blocks in the table, then the softmax and value phases of the matrix-core kernel): key phases of
 // masked passes over the blocks, the first design, cost more (measured on config 2's geometry:
 // 177, 292 and 160 us against 162, 175 and 153).
 bool rkv_scores_local(const rkv_cache* c) {
   const RkvView& v = c->v;
-  const bool sub = c->blocks_aligned && v.qg < 128;                         // (2-, 3- or 4-bit codes)
+  const bool sub = (c->blocks_aligned || c->in_groups) && v.qg < 128;       // (2-, 3- or 4-bit codes)
   const bool cross = !c->blocks_aligned && c->in_groups && v.qg == 128;
   return (sub || cross) && (v.g == 2 || v.g == 4) && row2_dynamic_lds(v, true) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
 }

@@ -39,8 +39,8 @@
 // 3- and 4-bit codes in groups of 128 run on the matrix-core kernels (k_append_mfma<.., HB>,
 // k_decode_mfma<.., HB>: the planes above the low two bits go through the same products); groups
 // of 64 / 32 are read through the scores kernel of rkv_decode_row.hip and the matrix-core decode
-// kernel's softmax and value phases (a reorder inside the heads; any code width, either metadata format) and by
-// the general kernel otherwise.
+// kernel's softmax and value phases (a reorder inside the rotation groups; any code width, either metadata
+// format) and by the general kernel otherwise.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
