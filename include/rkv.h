@@ -250,10 +250,11 @@ int rkv_decode_step(rkv_cache* cache, const void* dev_k, const void* dev_v, cons
  *   dev_lse    [batch][n_queries][n_q_heads] fp32, or NULL
  *   dev_scratch >= n_queries * scratch_bytes of rkv_query_sizes
  * Runs on the plain matrix-core decode kernel where the configuration has it (reorder inside
- * blocks of 128, rot_heads 2 or 4, groups of 128); any other configuration takes the general
- * kernel, which serves at most 8 (query token, query head) pairs per KV head: RKV_EINVAL beyond
- * that, or when rkv_set_decode_path(2) forces a matrix-core kernel the configuration does not
- * have for several query tokens; RKV_ESTATE on an empty cache. */
+ * blocks of 128, rot_heads 2 or 4, groups of 128).  The matrix-core variants that take their
+ * scores from the scores kernel (groups of 64 / 32, reorders across blocks) serve at most 8
+ * (query token, query head) pairs per KV head, and so does the general kernel, which takes what
+ * is left: RKV_EINVAL beyond that, or when rkv_set_decode_path(2) forces a matrix-core kernel the
+ * configuration does not have for this many query tokens; RKV_ESTATE on an empty cache. */
 #define RKV_MAX_QUERIES 64
 int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_t* dev_q_pos, int32_t n_queries,
                                float* dev_out, float* dev_lse, void* dev_scratch, void* stream);
@@ -261,9 +262,9 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
 /* Choose the decode kernel: 0 = automatic (default), 1 = force the general kernel (any supported
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
  * the configuration is outside what it covers: a reorder across rotation groups, rot_heads 1 or
- * 8; a reorder across blocks of 128 inside the rotation groups only with one query token per
- * step, one over the whole row only with 2-bit codes in groups of 128 besides; quant_group 64 or 32
- * only with one query token per step).
+ * 8; a reorder over the whole row only with 2-bit codes in groups of 128; several query tokens
+ * per step with a reorder across blocks of 128 or with quant_group 64 or 32 only up to 8 (query
+ * token, query head) pairs per KV head).
  * 3 = measurement only: the matrix-core kernel with the cache stream (codes and metadata of keys
  * and values) replaced by values made up in registers, i.e. the time its arithmetic takes when no
  * byte of the cache has to arrive - the ceiling the vector and matrix units set.  Outputs are

@@ -377,9 +377,11 @@ RKV_EXPORT int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries) {
   if (!cache || n_queries < 0 || n_queries > RKV_MAX_QUERIES) return RKV_EINVAL;
   const int kind = rkv_mfma_supported(cache) ? rkv_mfma_variant(cache) : RKV_KERNEL_GENERAL;
   if (n_queries > 0) {
-    // several query tokens per step: the plain matrix-core kernel, else the general one, which serves up to
-    // 8 (query token, query head) pairs per KV head
+    // several query tokens per step: the plain matrix-core kernel; else the configuration's variant or the
+    // general kernel, which serve up to 8 (query token, query head) pairs per KV head
     if (kind == RKV_KERNEL_MFMA && cache->decode_path != 1) return kind;
+    // (the variants that take their scores from the scores kernel: up to 8 rows per KV head there too)
+    if (kind != RKV_KERNEL_GENERAL && kind != RKV_KERNEL_MFMA && cache->decode_path != 1 && rkv_scores_multi_ok(cache, n_queries)) return kind;
     if (cache->decode_path >= 2) return RKV_EINVAL;
     return (cache->v.Hq / cache->v.Hkv) * n_queries <= 8 ? RKV_KERNEL_GENERAL : RKV_EINVAL;
   }

@@ -276,7 +276,7 @@ __global__ void __launch_bounds__(256, (HB && G == 4) ? MF_OCC_HI : MF_OCC) k_de
   __shared__ __attribute__((aligned(16))) uint32_t s_ks[LM ? MF_CH * GP : 1], s_vm[LM ? MF_CH * G : 1];
   static_assert(SUB == 0 || PRE, "groups of 64 / 32 run on precomputed scores");
   static_assert(!ALU || (!META8 && HB == 0 && !MULTI), "the arithmetic-only measurement exists for the plain 2-bit variants");
-  static_assert(!PRE || (!MULTI && !ALU), "precomputed scores: one query token");
+  static_assert(!PRE || !ALU, "precomputed scores: no arithmetic-only measurement");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -438,7 +438,10 @@ __global__ void __launch_bounds__(256, (HB && G == 4) ? MF_OCC_HI : MF_OCC) k_de
 #pragma unroll
         for (int rri = 0; rri < REP; ++rri) {
           const int qh = (rg * G + a) * rep + rrg * REP + rri;
-          pre[a * REP + rri] = t0 + tid < len ? qt[((size_t)b * v.Hq + qh) * v.Tpad + t0 + tid] : -INFINITY;
+          bool seen = t0 + tid < len;
+          // (several query tokens: virtual head rrg * REP + rri of its KV head belongs to query token (that / heads per token))
+          if constexpr (MULTI) seen = seen && t0 + tid <= q_lim[b * nq + (rrg * REP + rri) / (rep / nq)];
+          pre[a * REP + rri] = seen ? qt[((size_t)b * v.Hq + qh) * v.Tpad + t0 + tid] : -INFINITY;
         }
       uint4* a4 = reinterpret_cast<uint4*>(s_A_raw);
       for (int i = tid; i < (int)(SA_BYTES / 16); i += 256) a4[i] = make_uint4(0, 0, 0, 0);
@@ -1032,7 +1035,8 @@ typedef void (*RkvDecodeFn)(RkvView, const float*, float*, int, const int*, int,
 static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool alu) {
   const RkvView& v = c->v;
   // precomputed scores (groups of 64 / 32; a reorder over the whole row): softmax and value phases only
-#define RKV_MF_PRE(G_, R_, S_, H_) (v.meta8 ? k_decode_mfma<G_, R_, false, true, H_, S_, false, true> : k_decode_mfma<G_, R_, false, false, H_, S_, false, true>)
+#define RKV_MF_PRE_M(G_, R_, S_, H_, M_) (v.meta8 ? k_decode_mfma<G_, R_, M_, true, H_, S_, false, true> : k_decode_mfma<G_, R_, M_, false, H_, S_, false, true>)
+#define RKV_MF_PRE(G_, R_, S_, H_) (multi ? RKV_MF_PRE_M(G_, R_, S_, H_, true) : RKV_MF_PRE_M(G_, R_, S_, H_, false))
 #define RKV_MF_PRE_SUB(G_, H_) (sub == 4 ? RKV_MF_PRE(G_, 1, 4, H_) : RKV_MF_PRE(G_, 1, 2, H_))
   if (rkv_scores_local(c) && v.qg < 128) {                  // (groups of 64 / 32: codes of 2, 3 or 4 bits)
     const int sub = 128 / v.qg;
@@ -1047,6 +1051,7 @@ static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool a
   }
 #undef RKV_MF_PRE_SUB
 #undef RKV_MF_PRE
+#undef RKV_MF_PRE_M
 #ifdef RKV_DEV_FEW_VARIANTS
   // developer builds: only the plain 2-bit variants of four-head rotation groups (quick to compile)
   if (multi || v.g != 4 || v.hb || v.meta8 || !c->blocks_aligned || v.qg != 128) abort();
@@ -1099,7 +1104,7 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
   const bool sg = mfma_sub_groups(c);
   const bool xb = mfma_cross_block(c) || sg;
   const bool row = rkv_scores_path(c);
-  if ((xb || row) && multi) return RKV_EINVAL;              // the scores kernel serves one query token per step
+  if (row && multi && !rkv_scores_multi_ok(c, nq)) return RKV_EINVAL;   // (the scores kernel serves 8 rows per KV head)
   const int share = sg ? 1 : rkv_mfma_share(rep);           // (groups of 64 / 32: one query head per workgroup)
   if (!q_prepared) rkv_launch_prep_q(v, q, q_pos, c->cur_k ? 1 : 0, qr, share, nq, s);
   float* qt = qr + (size_t)v.B * v.Hq * RKV_D;              // lane-ordered copy written by k_prep_q
@@ -1125,13 +1130,13 @@ int rkv_launch_decode_mfma(rkv_cache* c, const __half* q, const int* q_pos, int 
     if (c->decode_path == 3) return RKV_EINVAL;
     float* sc = (float*)((char*)part + rkv_partial_bytes(v.B, v.Hq, (int)v.Tpad));
     if (timed) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
-    const int rc = rkv_launch_scores_row(c, qr, sc, s);
+    const int rc = rkv_launch_scores_row(c, v, qr, sc, s);
     if (rc != RKV_OK) return rc;
     if (nch > 0)
-      hipLaunchKernelGGL(pick_kernel(c, false, share, false), grid, dim3(256), 0, s, v, (const float*)sc, part, nch, (const int*)nullptr, nq,
-                         ns, recip(ns), recip(v.NRG));
+      hipLaunchKernelGGL(pick_kernel(c, multi, share, false), grid, dim3(256), 0, s, v, (const float*)sc, part, nch,
+                         multi ? q_pos : (const int*)nullptr, nq, ns, recip(ns), recip(v.NRG));
     if (timed) RKV_HIP_CHECK(hipEventRecord(c->ev_stop, s));
-    rkv_launch_merge(v, qr, part, nch, MF_CH, c->cur_k, c->cur_v, nullptr, nq, out, lse, s);
+    rkv_launch_merge(v, qr, part, nch, MF_CH, c->cur_k, c->cur_v, multi ? q_pos : nullptr, nq, out, lse, s);
     return rkv_check_launch();
   }
   if (nch > 0) {                                            // (an empty cache has only the current token)

@@ -813,9 +813,21 @@ size_t rkv_row_scores_bytes(int batch, int n_q_heads, int max_tokens) {
   return (size_t)batch * n_q_heads * Tpad * 4;
 }
 
-// scores of every cached token for every query head of `v` (one query token per sequence, prepared queries qr)
-int rkv_launch_scores_row(const rkv_cache* c, const float* qr, float* sc, hipStream_t s) {
-  const RkvView& v = c->v;
+// Several query tokens per step: the scores kernel sees them as further query heads of a KV head (virtual
+// heads, as the matrix-core kernel does); it serves up to 8 rows per KV head, in its table-per-wave form.
+bool rkv_scores_multi_ok(const rkv_cache* c, int n_queries) {
+  if (!rkv_scores_path(c)) return false;
+  RkvView v = c->v;
+  v.Hq *= n_queries;
+  if (v.Hq / v.Hkv > 8) return false;
+  const bool local = rkv_scores_local(c);
+  if (!local && !row2_applies(v)) return false;
+  return row2_dynamic_lds(v, local) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
+}
+
+// scores of every cached token for every query head of `v` (prepared queries qr)
+// v: the cache's view, with virtual heads where several query tokens are served
+int rkv_launch_scores_row(const rkv_cache* c, const RkvView& v, const float* qr, float* sc, hipStream_t s) {
   if (!rkv_scores_path(c)) return RKV_EINVAL;
   const int rep = v.Hq / v.Hkv;
   if (v.len == 0) return RKV_OK;

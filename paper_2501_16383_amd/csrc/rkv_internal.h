@@ -303,7 +303,8 @@ bool rkv_scores_local(const rkv_cache* c);   // groups of 32 inside the heads: s
 bool rkv_scores_path(const rkv_cache* c);    // either of the two
 int rkv_append_mfma_variant(const rkv_cache* c);   // RKV_KERNEL_* of the matrix-core append kernel a cache takes
 size_t rkv_row_scores_bytes(int batch, int n_q_heads, int max_tokens);
-int rkv_launch_scores_row(const rkv_cache* c, const float* qr, float* sc, hipStream_t s);
+int rkv_launch_scores_row(const rkv_cache* c, const RkvView& v, const float* qr, float* sc, hipStream_t s);
+bool rkv_scores_multi_ok(const rkv_cache* c, int n_queries);   // several query tokens per step on that route
 size_t rkv_partial_bytes(int batch, int n_q_heads, int Tpad);
 int rkv_launch_step_mfma(rkv_cache* c, const __half* k, const __half* v, const __half* q, const int* q_pos, float* qr, int share,
                          hipStream_t s);

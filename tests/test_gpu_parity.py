@@ -174,24 +174,29 @@ def test_reorder_across_blocks(span_kind):
         assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_MFMA_ROW
 
 
-def check_multi_on_general_kernel(cache, oc, q, hq, hkv, tag):
+def check_two_query_tokens(cache, oc, q, hq, hkv, tag):
     """Two causal query tokens per sequence on a configuration without the plain matrix-core kernel:
-    rkv_decode_attention_multi takes the general kernel (at most 8 (query token, query head) pairs
-    per KV head; refused beyond).  Against the oracle on the GPU's own codes."""
+    rkv_decode_attention_multi takes the configuration's own route (the scores kernel sees the query
+    tokens as further query heads; at most 8 (query token, query head) pairs per KV head, refused
+    beyond), and the general kernel when that is forced.  Both against the oracle on the GPU's own codes."""
     q2 = np.stack([q, q[::-1].copy()], axis=1)
     q_pos = np.array([[600, 601], [300, 612]], dtype=np.int32)
     if (hq // hkv) * 2 > 8:
         with pytest.raises(R.RkvError):
             cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
         return
-    assert cache.decode_kernel(2) == RB.KERNEL_GENERAL
-    out, lse = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos), want_lse=True)
-    torch.cuda.synchronize()
     ref, lse_ref = O.decode_attention_multi(oracle_from_export(oc, P.export_numpy(cache)), q2, q_pos)
-    e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
-    le = float(np.abs(lse.cpu().numpy() - lse_ref).max())
-    print(f"[parity] {tag}: two query tokens on the general kernel: out err {e:.3e} lse err {le:.3e}", flush=True)
-    assert e <= ATT_TOL and le <= LSE_TOL
+    for path in (0, 1):
+        cache.set_decode_path(path)
+        assert cache.decode_kernel(2) == (cache.decode_kernel() if path == 0 else RB.KERNEL_GENERAL)
+        assert path == 1 or cache.decode_kernel(2) != RB.KERNEL_GENERAL
+        out, lse = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos), want_lse=True)
+        torch.cuda.synchronize()
+        e = P.attention_error(out.cpu().numpy().astype(np.float64), ref)
+        le = float(np.abs(lse.cpu().numpy() - lse_ref).max())
+        print(f"[parity] {tag}: two query tokens, path {path}: out err {e:.3e} lse err {le:.3e}", flush=True)
+        assert e <= ATT_TOL and le <= LSE_TOL
+    cache.set_decode_path(0)
 
 
 @pytest.mark.parametrize("g,hq,style", [(4, 8, 0), (2, 8, 0), (4, 32, 0), (2, 16, 1), (4, 8, 1), (4, 64, 0)])
@@ -223,7 +228,7 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
     ref, _ = O.decode_attention(oracle_from_export(oc, P.export_numpy(cache)), q)
     assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
     cache.set_decode_path(0)
-    check_multi_on_general_kernel(cache, oc, q, hq, 8, f"whole-row reorder g={g} hq={hq}")
+    check_two_query_tokens(cache, oc, q, hq, 8, f"whole-row reorder g={g} hq={hq}")
     # against the general kernel on the same cache, and on the work space built into the library
     cache.set_decode_path(1)
     o_gen, l_gen = cache.decode_attention(P.gpu(q), want_lse=True)
@@ -308,10 +313,11 @@ def test_reorder_inside_rotation_group_on_matrix_cores(g, hq, style, fmt):
     ref, _ = O.decode_attention(oracle_from_export(oc, P.export_numpy(cache)), q)
     assert P.attention_error(out.cpu().numpy().astype(np.float64), ref) <= ATT_TOL
     cache.set_decode_path(0)
-    check_multi_on_general_kernel(cache, oc, q, hq, 8, f"cross-block reorder g={g} hq={hq} fmt={fmt}")
+    check_two_query_tokens(cache, oc, q, hq, 8, f"cross-block reorder g={g} hq={hq} fmt={fmt}")
     cache.set_decode_path(2)
-    with pytest.raises(R.RkvError):                              # (no matrix-core variant for several query tokens here)
-        cache.decode_attention_multi(P.gpu(np.stack([q, q], axis=1)), P.gpu(np.array([[600, 601], [600, 601]], dtype=np.int32)))
+    if (hq // 8) * 2 > 8:                                        # (beyond 8 rows per KV head: refused, not mis-computed)
+        with pytest.raises(R.RkvError):
+            cache.decode_attention_multi(P.gpu(np.stack([q, q], axis=1)), P.gpu(np.array([[600, 601], [600, 601]], dtype=np.int32)))
     # sequences of different lengths, and the one-call step against the two calls, bit for bit
     k, v, mask = S.make_kv(w, 40, batch=2)
     a, b = R.RkvCache(cfg), R.RkvCache(cfg)
@@ -1216,14 +1222,14 @@ def test_sequences_of_different_lengths(bits, group):
             ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
             e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
             assert e <= ATT_TOL, f"two query tokens, b={b}: {e}"
-    else:                       # the sub-group variant of the decode kernel takes one query token per step: the general kernel serves
-        assert cache.decode_kernel(2) == RB.KERNEL_GENERAL
+    else:                       # the sub-group variant: the scores kernel takes the query tokens as further query heads
+        assert cache.decode_kernel(2) == RB.KERNEL_MFMA_SUB
         out = cache.decode_attention_multi(P.gpu(q2), P.gpu(q_pos))
         torch.cuda.synchronize()
         for b in range(B):
             ref, _ = O.decode_attention_multi(ocg[b], q2[b:b + 1], q_pos[b:b + 1])
             e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
-            assert e <= ATT_TOL, f"two query tokens on the general kernel, b={b}: {e}"
+            assert e <= ATT_TOL, f"two query tokens on the sub-group variant, b={b}: {e}"
     # what the entry point refuses
     with pytest.raises(R.RkvError) as ei:
         cache.quantize_append_ragged(P.gpu(np.zeros((B, 50, 8, 128), np.float16)), P.gpu(np.zeros((B, 50, 8, 128), np.float16)), [1, 1, 50])
