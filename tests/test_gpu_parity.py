@@ -1681,3 +1681,68 @@ def test_randomly_drawn_steps_lengths_and_query_counts(seed):
                 ref, _ = O.decode_attention_multi(ocg[s_], qn[s_:s_ + 1], q_pos[s_:s_ + 1])
                 e = P.attention_error(out[s_:s_ + 1].cpu().numpy().astype(np.float64), ref)
                 assert e <= ATT_TOL, f"{nq} query tokens, sequence {s_}: {e}"
+
+
+@pytest.mark.parametrize("setting,g,hq,bits,group,fmt,nq", [("whole row", 4, 8, 2, 128, 0, 4), ("whole row", 2, 16, 2, 128, 1, 3),
+                                                          ("across blocks", 4, 16, 4, 128, 0, 2), ("across blocks", 2, 8, 2, 64, 1, 4),
+                                                          ("inside heads", 4, 8, 3, 32, 1, 3), ("inside heads", 2, 32, 2, 64, 0, 2),
+                                                          ("inside heads", 4, 8, 4, 32, 0, 8)])
+def test_several_query_tokens_on_the_scores_kernel_routes(setting, g, hq, bits, group, fmt, nq):
+    """rkv_decode_attention_multi where the scores come from the scores kernel (reorders across
+    blocks, groups of 64 / 32, wider codes on those routes): causal query tokens at the end of the
+    cache and one far behind it, GQA, sequences of different lengths, retained rows behind a query's
+    position; the configuration's own route and the general kernel against the oracle on the GPU's
+    codes.  Eight (query token, query head) pairs per KV head is the limit."""
+    hkv = 8
+    rep = hq // hkv
+    w = small("cfg1", n_q_heads=hq, n_kv_heads=hkv)
+    span = {"whole row": 128 * hkv, "across blocks": 128 * g, "inside heads": 128}[setting]
+    kw = dict(batch=2, n_q_heads=hq, n_kv_heads=hkv, max_tokens=420, max_sinks=4, rot_heads=g, meta_format=fmt)
+    cfg = R.RkvConfig(bits=bits, quant_group=group, perm_span=span, **kw)
+    perm = calibrated_perm(w, R.RkvConfig(perm_span=span, **kw), offset_variant=span != 128)
+    lens = [401, 150]
+    data = [S.make_kv(w, lens[b], batch=1, layer=b, sink_positions=[0, 3, lens[b] - 2]) for b in range(2)]
+    cache = R.RkvCache(cfg)
+    cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
+    ocs = [O.cache_new(P.oracle_cfg(dataclasses.replace(cfg, batch=1)), perm) for _ in range(2)]
+    k = np.zeros((2, max(lens), hkv, 128), np.float16)
+    v = np.zeros_like(k)
+    m = np.zeros((2, max(lens)), np.uint8)
+    for b in range(2):
+        kb, vb, mb = data[b]
+        k[b, :lens[b]], v[b, :lens[b]], m[b, :lens[b]] = kb[0], vb[0], mb[0]
+        O.quantize_append(ocs[b], kb, vb, mb)
+    if setting == "whole row":           # (per-sequence lengths need the plain, sub-group or cross-block append kernel)
+        lens = [401, 401]
+        cache.quantize_append(P.gpu(np.repeat(k[:1], 2, axis=0)), P.gpu(np.repeat(v[:1], 2, axis=0)), P.gpu(np.repeat(m[:1], 2, axis=0)))
+        ocs[1] = ocs[0]
+    else:
+        cache.quantize_append_ragged(P.gpu(k), P.gpu(v), lens, P.gpu(m))
+    torch.cuda.synchronize()
+    want = {"whole row": RB.KERNEL_MFMA_ROW, "across blocks": RB.KERNEL_MFMA_CROSS if group == 128 else RB.KERNEL_MFMA_SUB,
+            "inside heads": RB.KERNEL_MFMA_SUB}[setting]
+    gexp = P.export_numpy(cache)
+    ocg = [oracle_from_export(ocs[b], {name: arr[b:b + 1, :lens[b]] for name, arr in gexp.items()}) for b in range(2)]
+    qn = np.stack([S.make_q(w, batch=2, step=j) for j in range(nq)], axis=1)
+    # the last query tokens of each sequence, the first of them moved far back (behind the retained row near the end)
+    q_pos = np.array([[lens[b] - nq + j for j in range(nq)] for b in range(2)], dtype=np.int32)
+    q_pos[:, 0] = [37, 5]
+    if rep * nq > 8:
+        assert want != RB.KERNEL_MFMA
+        with pytest.raises(R.RkvError):
+            cache.decode_attention_multi(P.gpu(qn), P.gpu(q_pos))
+        nq = 8 // rep
+        qn, q_pos = qn[:, :nq].copy(), q_pos[:, :nq].copy()
+    refs = [O.decode_attention_multi(ocg[b], qn[b:b + 1], q_pos[b:b + 1]) for b in range(2)]
+    for path in (0, 1):
+        cache.set_decode_path(path)
+        assert cache.decode_kernel(nq) == (want if path == 0 else RB.KERNEL_GENERAL)
+        print(f"[case] {nq} query tokens, {setting}, g={g} hq={hq} bits={bits} group={group}, path {path}", flush=True)
+        out, lse = cache.decode_attention_multi(P.gpu(qn), P.gpu(q_pos), want_lse=True)
+        torch.cuda.synchronize()
+        for b in range(2):
+            ref, lse_ref = refs[b]
+            e = P.attention_error(out[b:b + 1].cpu().numpy().astype(np.float64), ref)
+            le = float(np.abs(lse[b:b + 1].cpu().numpy() - lse_ref).max())
+            print(f"[parity] path {path} sequence {b}: out err {e:.3e} lse err {le:.3e}", flush=True)
+            assert e <= ATT_TOL and le <= max(LSE_TOL, 2e-6 * float(np.abs(lse_ref).max()))
