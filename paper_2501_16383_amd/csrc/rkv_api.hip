@@ -58,9 +58,9 @@ static int check_config(const rkv_config* c, bool need_capacity) {
   {
     // the general append kernel keeps the images of max(perm_span, n) channels of a tile in LDS
     // (rkv_launch_append): that must fit a compute unit.  It is not what runs where every reorder
-    // has a matrix-core append kernel (2-bit codes in groups of 128, rotation over 2 or 4 heads, keys
+    // has a matrix-core append kernel (groups of 128, rotation over 2 or 4 heads, keys
     // and values as they come; the whole-row variant holds per-block tables for up to 127 blocks)
-    const bool always_matrix = c->bits == 2 && c->quant_group == 128 && (c->rot_heads == 2 || c->rot_heads == 4) &&
+    const bool always_matrix = c->quant_group == 128 && (c->rot_heads == 2 || c->rot_heads == 4) &&
                                !c->v_rotate && !c->keys_rotated && c->n_kv_heads <= 127;
     const size_t U = c->perm_span > n ? c->perm_span : n;
     const size_t lds = 24 * U + (c->bits == 4 ? 8 * U : c->bits == 3 ? 6 * U : 0);

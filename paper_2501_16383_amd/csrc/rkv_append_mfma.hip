@@ -574,13 +574,13 @@ __global__ void __launch_bounds__(256, (HB || XW || SUB) ? 4 : 6) k_append_mfma(
 }
 
 // the value role alone (grid x = slabs): the keys of a reorder over the whole row have a kernel of their own
-template <int G>
-__global__ void __launch_bounds__(256, 6) k_append_values(RkvView v, const __half* __restrict__ vin, int n_new, int slab0) {
-  append_mfma_body<G, 0, false, 0>(v, nullptr, vin, n_new, slab0, 3 * blockIdx.x + 2, blockIdx.y, blockIdx.z);
+template <int G, int HB = 0>
+__global__ void __launch_bounds__(256, HB ? 4 : 6) k_append_values(RkvView v, const __half* __restrict__ vin, int n_new, int slab0) {
+  append_mfma_body<G, HB, false, 0>(v, nullptr, vin, n_new, slab0, 3 * blockIdx.x + 2, blockIdx.y, blockIdx.z);
 }
 
 // Keys under a reorder over the whole token row (perm_span = n_kv_heads * 128, Alg. 1 as printed;
-// 2-bit codes in groups of 128).  A rotated channel then belongs to any of the row's E / 128
+// groups of 128; HB as in k_append_mfma: codes of 3 or 4 bits, the bits above the low two to their plane).  A rotated channel then belongs to any of the row's E / 128
 // quantization blocks, so a block's minimum and maximum (Eq. 8-9) need the rotated values of all
 // rotation groups of the token.  One workgroup = (sequence, tile of 16 tokens) takes the groups one
 // after the other, twice: the first pass rotates (H_128 on fp16 matrix products, H_g in the lane,
@@ -592,9 +592,11 @@ __global__ void __launch_bounds__(256, 6) k_append_values(RkvView v, const __hal
 // lane's channels comes from a per-cache table of bytes (xgid8, written by rkv_set_perm).
 // dynamic LDS: [NG][16 tokens] float minima, the same of maxima, [NG][16] float4 parameters (block-major: the 16
 // tokens of a row of lanes, which share their channels and hence their blocks, touch 16 different LDS banks).
-template <int G>
+template <int G, int HB = 0>
 __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __half* __restrict__ kin, int n_new, int slab0) {
   constexpr int n = 128 * G;
+  constexpr bool HI = HB == 2, H1 = HB == 1;
+  constexpr float QMAX = HI ? 15.0f : (H1 ? 7.0f : 3.0f), INV_QMAX = HI ? 0.06666667f : (H1 ? 0.14285715f : 0.33333334f);
   constexpr int ROW16 = 16 * G, STRIDE16 = ROW16 + 1;
   __shared__ __attribute__((aligned(16))) uint32_t lds[16 * STRIDE16 * 4];
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_row[];
@@ -603,6 +605,7 @@ __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __h
   float* s_mx = s_mn + 16 * NGP;
   float4* s_par = reinterpret_cast<float4*>(dyn_row + (size_t)2 * 16 * NGP * 4);      // (128 NGP bytes in: 16-byte aligned)
   __shared__ uint32_t img[2 * 128 * G];        // the tile image of one rotation group, in two halves (see k_append_mfma)
+  __shared__ uint32_t imgh[HB ? 2 * 128 * G : 1];   // the upper plane's: two halves (4-bit codes) or four quarter-size pieces (3-bit)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int b = blockIdx.y, ti = blockIdx.x & 1;
@@ -720,7 +723,7 @@ __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __h
   for (int e = tid; e < 16 * NG; e += 256) {
     const int tk = e & 15, bk = e >> 4;
     float sc, zero_b, inv, base_b, add_b;
-    quant_params_nodiv(s_mn[e] * rs, s_mx[e] * rs, sc, zero_b, inv, v.meta8);
+    quant_params_nodiv(s_mn[e] * rs, s_mx[e] * rs, sc, zero_b, inv, v.meta8, INV_QMAX);
     fused_round_consts(zero_b, base_b, add_b);
     s_par[e] = make_float4(inv * rs, add_b, base_b, 0.f);
     const int tau = 16 * ti + tk;
@@ -743,21 +746,42 @@ __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __h
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           const float4 pr = s_par[(int)(((ppl ? gb.y : gb.x) >> (8 * rr)) & 0xffu) * 16 + col];
-          const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + 3.0f);
+          const float c = __builtin_amdgcn_fmed3f(fmaf(acc[a][ppl][rr], pr.x, pr.y), pr.z, pr.z + QMAX);
           word += (__float_as_uint(c) - __float_as_uint(pr.z)) << (16 * ppl + 4 * rr);
         }
-      words[a] = word << (2 * pph);
+      words[a] = word;                                     // a code per nibble
     }
     // (the previous group's image was stored before this group's first barrier)
 #pragma unroll
-    for (int a = 0; a < G; ++a) img[pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d] = words[a];
+    for (int a = 0; a < G; ++a) {
+      const int io = pph * (128 * G) + ((((a >> 1) * 4 + q) * 16 + col) * 4) + (a & 1) * 2 + d;
+      if constexpr (HI) {
+        img[io] = (words[a] & 0x33333333u) << (2 * pph);
+        imgh[io] = ((words[a] >> 2) & 0x33333333u) << (2 * pph);
+      } else if constexpr (H1) {
+        img[io] = (words[a] & 0x33333333u) << (2 * pph);
+        imgh[(2 * pph + d) * (64 * G) + ((io - pph * (128 * G) - d) >> 1)] = ((words[a] >> 2) & 0x11111111u) << (2 * d + pph);
+      } else {
+        img[io] = words[a] << (2 * pph);
+      }
+    }
     __syncthreads();                                       // the image is complete; the rows are read: the next group's may come
 #pragma unroll
     for (int k = 0; k < (128 * G + 255) / 256; ++k) {
       const int off = tid + 256 * k;
       if (off < 128 * G) {
         const int t = ts + ti * 16 + rkv_k_tile_token(G, off);
-        if (t >= t_lo && t < t_hi) rkv_st_stream(&v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], img[off] | img[128 * G + off]);
+        if (t >= t_lo && t < t_hi) {
+          rkv_st_stream(&v.kc[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], img[off] | img[128 * G + off]);
+          if constexpr (HI) rkv_st_stream(&v.kh[rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off], imgh[off] | imgh[128 * G + off]);
+          if constexpr (H1) {
+            if (!(off & 1)) {
+              const int o2 = off >> 1;
+              rkv_st_stream(&v.kh[(rkv_k_tilebase(v, b, rg, 2 * slab + ti) + off) >> 1],
+                            imgh[o2] | imgh[64 * G + o2] | imgh[128 * G + o2] | imgh[192 * G + o2]);
+            }
+          }
+        }
       }
     }
   }
@@ -786,7 +810,7 @@ __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* _
 // a reorder over the whole row: k_append_row_keys + k_append_values
 static bool append_row(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return !c->blocks_aligned && !c->in_groups && v.qg == 128 && v.hb == 0 && (v.g == 2 || v.g == 4) && v.v_rotate == 0 &&
+  return !c->blocks_aligned && !c->in_groups && v.qg == 128 && (v.g == 2 || v.g == 4) && v.v_rotate == 0 &&
          !c->cfg.keys_rotated && (size_t)384 * ((v.E >> 7) | 1) <= 48 * 1024;
 }
 int rkv_append_mfma_variant(const rkv_cache* c) {
@@ -822,13 +846,17 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (append_row(c)) {
     const size_t dyn = (size_t)384 * ((v.E >> 7) | 1);
+#define RKV_AP_ROW(G_, H_)                                                                                                        \
+  do {                                                                                                                            \
+    hipLaunchKernelGGL((k_append_row_keys<G_, H_>), dim3(2 * max_slabs, v.B), dim3(256), dyn, s, v, k, n_new, slab0);             \
+    hipLaunchKernelGGL((k_append_values<G_, H_>), dim3(max_slabs, v.NRG, v.B), dim3(256), 0, s, v, vv, n_new, slab0);             \
+  } while (0)
     if (v.g == 4) {
-      hipLaunchKernelGGL(k_append_row_keys<4>, dim3(2 * max_slabs, v.B), dim3(256), dyn, s, v, k, n_new, slab0);
-      hipLaunchKernelGGL(k_append_values<4>, dim3(max_slabs, v.NRG, v.B), dim3(256), 0, s, v, vv, n_new, slab0);
+      if (v.hb == 2) RKV_AP_ROW(4, 2); else if (v.hb == 1) RKV_AP_ROW(4, 1); else RKV_AP_ROW(4, 0);
     } else {
-      hipLaunchKernelGGL(k_append_row_keys<2>, dim3(2 * max_slabs, v.B), dim3(256), dyn, s, v, k, n_new, slab0);
-      hipLaunchKernelGGL(k_append_values<2>, dim3(max_slabs, v.NRG, v.B), dim3(256), 0, s, v, vv, n_new, slab0);
+      if (v.hb == 2) RKV_AP_ROW(2, 2); else if (v.hb == 1) RKV_AP_ROW(2, 1); else RKV_AP_ROW(2, 0);
     }
+#undef RKV_AP_ROW
   } else {
     // (G, bits above the low two, cross-block flag, sub-blocks per head)
 #define RKV_AP(G_, H_, X_, S_) hipLaunchKernelGGL((k_append_mfma<G_, H_, X_, S_>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0)

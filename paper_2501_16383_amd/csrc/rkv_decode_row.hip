@@ -387,11 +387,14 @@ __device__ __forceinline__ void rs2_settle(float (&q)[2][4]) {
 // HB = 1, 2 (with LOCAL): codes of 3 and 4 bits, c = c_lo + 4 c_hi.  A wave's table gets a second half for the
 // plane of upper bits, with entries s * 4 c_hi, and every step looks up both planes and runs its products
 // twice onto the same accumulators (the rotation is linear).
+// HB = 1, 2 without LOCAL (a reorder over the whole row, where two table halves would not fit): this launch
+// takes the plane of upper bits alone - the table holds s * 4 c_hi - and adds its scores to those a launch
+// with HB = 0 has left in the buffer.
 template <int G, int STYLE, bool LOCAL, int HB = 0>
-__global__ void __launch_bounds__(256, HB ? 2 : RS2_OCC) k_scores_row2(RkvView v, const float* __restrict__ qr, float* __restrict__ sc, int rep) {
-  static_assert(HB == 0 || LOCAL, "wider codes: the table of the rotation group's own blocks");
+__global__ void __launch_bounds__(256, (HB && LOCAL) ? 2 : RS2_OCC) k_scores_row2(RkvView v, const float* __restrict__ qr, float* __restrict__ sc, int rep) {
   constexpr int n = 128 * G;
-  constexpr int NPL = HB ? 2 : 1;                       // planes of code bits, each with its half of the table
+  constexpr bool UPPER = HB != 0 && !LOCAL;             // the upper plane's launch of a pair
+  constexpr int NPL = (HB && LOCAL) ? 2 : 1;            // planes of code bits in this launch, each with its half of the table
   // (no static LDS in this kernel: the tables start where the workgroup's LDS starts, so that a table's byte
   // address >> 8 plus a block index stays below 256 for rows of up to RS2_MAX_NG blocks)
   extern __shared__ __attribute__((aligned(256))) unsigned char dyn2[];
@@ -545,8 +548,8 @@ __global__ void __launch_bounds__(256, HB ? 2 : RS2_OCC) k_scores_row2(RkvView v
     float s_, z_;
     rkv_unpack_meta(word, s_, z_);                         // (8-bit metadata were turned into this form when they were fetched)
     s_ *= 0.015625f;
-    put_four(blk, s_ * (0.f - z_), s_ * (1.f - z_), s_ * (2.f - z_), s_ * (3.f - z_));
-    if constexpr (HB != 0) put_four(NG + blk, 0.f, s_ * 4.f, s_ * 8.f, s_ * 12.f);   // the upper bits' share s * 4 c_hi
+    if constexpr (!UPPER) put_four(blk, s_ * (0.f - z_), s_ * (1.f - z_), s_ * (2.f - z_), s_ * (3.f - z_));
+    if constexpr (HB != 0) put_four(UPPER ? blk : NG + blk, 0.f, s_ * 4.f, s_ * 8.f, s_ * 12.f);   // the upper bits' share s * 4 c_hi
   };
 
   for (int it = 0; it < RS2_TILES; ++it) {
@@ -632,8 +635,8 @@ __global__ void __launch_bounds__(256, HB ? 2 : RS2_OCC) k_scores_row2(RkvView v
             // channels at once, then one byte permute per channel puts the block above
             uint32_t low4 = ((wd[dw] << (6 - 2 * ksh)) & 0xC0C0C0C0u) | tokrep;
             uint32_t gw = g4w[s];
-            if (pl == 1) {
-              gw += (uint32_t)NG * 0x01010101u;            // the table's upper half
+            if (UPPER || pl == 1) {
+              if (pl == 1) gw += (uint32_t)NG * 0x01010101u;   // the table's upper half
               if constexpr (HB == 2) low4 = ((wdh[dw] << (6 - 2 * ksh)) & 0xC0C0C0C0u) | tokrep;
               // third bit of code m = 4 j + ksh of dword dw: bit 8 j + 4 (ksh >> 1) + 2 dw + (ksh & 1) of the pair's dword
               else low4 = (((wdh[dw] >> (4 * (ksh >> 1) + 2 * dw + (ksh & 1))) & 0x01010101u) << 6) | tokrep;
@@ -764,14 +767,15 @@ __global__ void __launch_bounds__(256, HB ? 2 : RS2_OCC) k_scores_row2(RkvView v
         bool sink = false;
         for (int k = 0; k < cnt; ++k) sink |= (s_sink[k] == tk);
         float* srow = sc + ((size_t)b * v.Hq + (size_t)rg * nqh) * v.Tpad + tt;
-        srow[(uint32_t)(hr * v.Tpad + (i & 15))] = sink ? -INFINITY : s_pd[i] * out_scale;
+        float* dst = &srow[(uint32_t)(hr * v.Tpad + (i & 15))];
+        *dst = sink ? -INFINITY : (UPPER ? *dst + s_pd[i] * out_scale : s_pd[i] * out_scale);
       }
     }
   }
 }
 
 static size_t row2_dynamic_lds(const RkvView& v, bool local) {
-  const int nqh = v.g * (v.Hq / v.Hkv), NG = (local ? v.gm : v.E >> 7) * (v.hb ? 2 : 1);   // (wider codes: a table half per plane)
+  const int nqh = v.g * (v.Hq / v.Hkv), NG = local ? v.gm * (v.hb ? 2 : 1) : v.E >> 7;   // (wider codes, own blocks: a table half per plane)
   return (size_t)4 * NG * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4 + (size_t)4 * 4 * v.g * 8 * 4 + 256;
 }
 static bool row2_applies(const RkvView& v) {
@@ -779,7 +783,7 @@ static bool row2_applies(const RkvView& v) {
 }
 
 // Whether a cache takes this path: a reorder that leaves the rotation groups (else the plain kernel or
-// rkv_scores_local's route serves it), 2-bit codes in groups of 128, rot_heads 2 or 4 (8-bit metadata where the
+// rkv_scores_local's route serves it), groups of 128, rot_heads 2 or 4 (8-bit metadata and wider codes where the
 // table-per-wave kernel applies).
 static size_t row_dynamic_lds(const RkvView& v) {
   const int nqh = v.g * (v.Hq / v.Hkv), NG = v.E >> 7;
@@ -788,8 +792,8 @@ static size_t row_dynamic_lds(const RkvView& v) {
 
 bool rkv_row_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  if (c->blocks_aligned || c->in_groups || v.qg != 128 || v.hb != 0 || !(v.g == 2 || v.g == 4)) return false;
-  if (v.meta8 && !row2_applies(v)) return false;           // (8-bit metadata: the table-per-wave kernel only)
+  if (c->blocks_aligned || c->in_groups || v.qg != 128 || !(v.g == 2 || v.g == 4)) return false;
+  if ((v.meta8 || v.hb) && !row2_applies(v)) return false; // (8-bit metadata, wider codes: the table-per-wave kernel only)
   // two workgroups per compute unit must fit its LDS; a tile's metadata: at most 32 rotation groups
   const size_t fixed = (size_t)2 * 16 * (16 * v.g + 1) * 16 + (size_t)144 * v.g * 4 + 256;
   return row_dynamic_lds(v) + fixed <= 80 * 1024 && v.NRG <= 32;
@@ -850,6 +854,16 @@ int rkv_launch_scores_row(const rkv_cache* c, const RkvView& v, const float* qr,
                     : (v.rope_style == 0 ? k_scores_row2<2, 0, false> : k_scores_row2<2, 1, false>);
     if (dyn > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
     hipLaunchKernelGGL(fn, grid, dim3(256), dyn, s, v, qr, sc, rep);
+    if (!local && v.hb) {                                  // the plane of upper bits: a launch of its own, onto the same scores
+      if (v.hb == 2)
+        fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, false, 2> : k_scores_row2<4, 1, false, 2>)
+                      : (v.rope_style == 0 ? k_scores_row2<2, 0, false, 2> : k_scores_row2<2, 1, false, 2>);
+      else
+        fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, false, 1> : k_scores_row2<4, 1, false, 1>)
+                      : (v.rope_style == 0 ? k_scores_row2<2, 0, false, 1> : k_scores_row2<2, 1, false, 1>);
+      if (dyn > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
+      hipLaunchKernelGGL(fn, grid, dim3(256), dyn, s, v, qr, sc, rep);
+    }
     return rkv_check_launch();
   }
   const size_t dyn = row_dynamic_lds(v);

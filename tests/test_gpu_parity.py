@@ -270,19 +270,22 @@ def test_reorder_over_the_whole_row_on_matrix_cores(g, hq, style):
         assert P.attention_error(o_rag[bb:bb + 1].cpu().numpy().astype(np.float64), ref) <= ATT_TOL
 
 
-@pytest.mark.parametrize("heads", [64, 60])
-def test_whole_row_reorder_with_many_heads(heads):
+@pytest.mark.parametrize("heads,bits", [(64, 2), (60, 2), (60, 4), (64, 3)])
+def test_whole_row_reorder_with_many_heads(heads, bits):
     """A row of 64 KV heads (8192 channels, 64 quantization blocks) under a reorder over the whole
     row: beyond what the general append kernel's LDS holds (53 heads), within what the matrix-core
     kernels for this reorder serve; both read paths against the oracle.  64 blocks take the scores
     kernel that stages rows in LDS, 60 the one with a table per wave (61 KB of tables: more dynamic
-    LDS than a launch gets without asking)."""
+    LDS than a launch gets without asking).  Wider codes: the write half serves them at any of these
+    sizes, the read half up to 63 blocks (64 blocks: the general decode kernel)."""
     w = small("cfg1", n_q_heads=heads, n_kv_heads=heads)
-    cfg = R.RkvConfig(batch=1, n_q_heads=heads, n_kv_heads=heads, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=heads * 128)
-    perm = calibrated_perm(w, cfg, offset_variant=True)
-    cache, _, _ = full_check(w, cfg, 90, perm=perm, chunks=[0, 40, 41, 90], paths=(1, 2), sink_positions=[])
+    cfg = R.RkvConfig(batch=1, n_q_heads=heads, n_kv_heads=heads, max_tokens=128, max_sinks=4, rot_heads=4, perm_span=heads * 128,
+                      bits=bits)
+    perm = calibrated_perm(w, dataclasses.replace(cfg, bits=2), offset_variant=True)
+    fast_read = bits == 2 or heads < 64
+    cache, _, _ = full_check(w, cfg, 90, perm=perm, chunks=[0, 40, 41, 90], paths=(1, 2) if fast_read else (1, 0), sink_positions=[])
     cache.set_decode_path(0)
-    assert cache.decode_kernel() == RB.KERNEL_MFMA_ROW and cache.append_kernel() == RB.KERNEL_MFMA_ROW
+    assert cache.decode_kernel() == (RB.KERNEL_MFMA_ROW if fast_read else RB.KERNEL_GENERAL) and cache.append_kernel() == RB.KERNEL_MFMA_ROW
 
 
 @pytest.mark.parametrize("g,hq,style,fmt", [(4, 8, 0, 0), (2, 8, 0, 0), (4, 32, 0, 0), (2, 16, 1, 0), (4, 8, 1, 0), (4, 8, 0, 1), (2, 16, 0, 1)])
@@ -525,20 +528,21 @@ def test_full_size_config2_sampled(meta_format, bits, with_sinks, group, span):
                     meta_format=meta_format, bits=bits, group=group, span=span)
 
 
-@pytest.mark.parametrize("with_sinks", [False, True])
-def test_full_size_config2_whole_row_reorder_sampled(with_sinks):
+@pytest.mark.parametrize("with_sinks,bits", [(False, 2), (True, 2), (False, 4), (False, 3)])
+def test_full_size_config2_whole_row_reorder_sampled(with_sinks, bits):
     """Configuration 2's geometry with the reorder over the whole token row (perm_span = 5120:
     Alg. 1 as printed), at full size: bulk append, then decode attention on the path bench.py
     times for this setting (scores kernel + matrix-core decode kernel).  With such a reorder a
     quantization block mixes channels of every rotation group, so the oracle recomputes whole
     sequences (two of the sixteen, all 40 heads): codes under the tie protocol, then attention on
-    the GPU's own codes."""
+    the GPU's own codes.  Also with 4- and 3-bit codes (the scores kernel then runs once per plane
+    of code bits)."""
     w = S.WORKLOADS["cfg2"]
     T = w.context
     n_keep = 4 if with_sinks else 0
     cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=n_keep,
-                      rot_heads=4, perm_span=w.n_kv_heads * 128)
-    perm = calibrated_perm(w, cfg, offset_variant=True)
+                      rot_heads=4, perm_span=w.n_kv_heads * 128, bits=bits)
+    perm = calibrated_perm(w, dataclasses.replace(cfg, bits=2), offset_variant=True)
     assert not np.array_equal(perm // 512, np.arange(cfg.E) // 512)
     cache = R.RkvCache(cfg)
     cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
@@ -570,12 +574,13 @@ def test_full_size_config2_whole_row_reorder_sampled(with_sinks):
         O.quantize_append(oc, kb, vb, mb if with_sinks else None)
         g = {}
         for name in ("k", "v"):
-            g[name + "_codes"] = O.unpack_canonical(exp[name + "_codes"][b:b + 1], 2)
+            g[name + "_codes"] = O.unpack_canonical(exp[name + "_codes"][b:b + 1], bits)
             g[name + "_scale"] = exp[name + "_scale"][b:b + 1].astype(np.float64)
             g[name + "_zero"] = exp[name + "_zero"][b:b + 1].astype(np.float64)
         P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"],
-                        f"whole-row full size b={b} K", rot_span=cfg.E)    # (a block's members come from any rotation group)
-        P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], f"whole-row full size b={b} V")
+                        f"whole-row full size b={b} K", rot_span=cfg.E, bits=bits)    # (a block's members come from any rotation group)
+        P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], f"whole-row full size b={b} V",
+                        bits=bits)
         for name, val in g.items():                            # attention on the GPU's own codes
             setattr(oc, name, val)
         ref, lse_ref = O.decode_attention(oc, q[b:b + 1])
@@ -1331,7 +1336,8 @@ def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
                                                       (4, 32, 2, 16, 0, 128), (3, 64, 2, 16, 1, 128), (4, 128, 4, 8, 0, 512),
                                                       (3, 128, 2, 16, 1, 256), (3, 128, 4, 32, 0, 512), (4, 128, 2, 8, 1, 256),
                                                       (2, 64, 4, 8, 0, 512), (2, 32, 2, 16, 1, 256), (2, 32, 4, 16, 0, 512),
-                                                      (3, 32, 4, 8, 1, 512), (4, 64, 2, 8, 0, 256)])
+                                                      (3, 32, 4, 8, 1, 512), (4, 64, 2, 8, 0, 256), (4, 128, 4, 8, 0, 1024),
+                                                      (3, 128, 2, 16, 1, 1024), (3, 128, 4, 32, 0, 1024), (4, 128, 2, 8, 1, 1024)])
 def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     """3- and 4-bit codes and quantization groups of 64 and 32 channels (Sec. 5.1; Tables
     tab:ablation and tab:quantgrani) through the write half, the export and dequantize views and
@@ -1351,7 +1357,7 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
         assert not np.array_equal(perm // group, np.arange(cfg.E) // group)
     # wider codes in groups of 128 are read by the matrix-core decode kernel as two planes, codes in
     # smaller groups by its sub-group variant (scores from the scores kernel, one table half per plane)
-    on_matrix_cores = g in (2, 4) and span in (128, 128 * g)
+    on_matrix_cores = g in (2, 4) and (span in (128, 128 * g) or group == 128)     # (span 1024: the whole row)
     # half of the cases without any retained fp16 row, so that the compressed stream alone decides the outputs
     cache, oc, q = full_check(w, cfg, 213, perm=perm, chunks=[0, 100, 101, 102, 213], paths=(1, 2) if on_matrix_cores else (1, 0),
                               sink_positions=[] if (hq + group + bits) % 3 != 0 else None)
@@ -1362,7 +1368,8 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
             cache.decode_attention(P.gpu(q))
     cache.set_decode_path(0)
     if on_matrix_cores:
-        want = RB.KERNEL_MFMA_SUB if group != 128 else RB.KERNEL_MFMA_CROSS if span != 128 else RB.KERNEL_MFMA
+        want = (RB.KERNEL_MFMA_SUB if group != 128 else RB.KERNEL_MFMA_ROW if span == 1024 else RB.KERNEL_MFMA_CROSS if span != 128
+                else RB.KERNEL_MFMA)
         assert cache.append_kernel() == want and cache.decode_kernel() == want
     # one more single-token step through rkv_decode_step (the two calls, on this setting)
     k1, v1, _ = S.make_kv(w, 1, batch=2, stream=5, sink_positions=[])
@@ -1528,7 +1535,7 @@ def test_randomly_drawn_configurations(seed):
             elif kind == "across blocks":
                 bits, group, span = rnd.choice([2, 2, 3, 4]), rnd.choice([128, 128, 64, 32]), 128 * g
             else:
-                bits, group, span = 2, 128, 128 * hkv
+                bits, group, span = rnd.choice([2, 2, 3, 4]), 128, 128 * hkv
         B = rnd.choice([1, 2, 3])
         T = rnd.choice([1, 15, 16, 17, 63, 64, 65, 100, 255, 256, 257, rnd.randint(1, 600), rnd.randint(200, 900)])
         sinks = rnd.choice([0, 4, 2])
@@ -1583,7 +1590,7 @@ def test_randomly_drawn_steps_lengths_and_query_counts(seed):
             elif kind == "across blocks":
                 bits, group, span = rnd.choice([2, 2, 3, 4]), rnd.choice([128, 128, 64, 32]), 128 * g
             else:
-                bits, group, span = 2, 128, 128 * hkv
+                bits, group, span = rnd.choice([2, 2, 3, 4]), 128, 128 * hkv
         B, sinks = rnd.choice([1, 2, 3, 4]), rnd.choice([0, 4, 2])
         t_max = rnd.choice([1, 16, 17, 64, 65, 255, 256, 257, rnd.randint(1, 500), rnd.randint(100, 700)])
         lens = [t_max] * B

@@ -109,13 +109,15 @@ def test_physical_layout_is_a_bijection(lib, g, heads, tokens):
             assert all(len(v) == 1 for v in words.values()) and len(words) == g * 128     # token-minor: one word per channel
 
 
-@pytest.mark.parametrize("heads,bits,ok", [(52, 2, True), (56, 2, True), (124, 2, True), (128, 2, False), (40, 4, True), (44, 4, False),
-                                           (52, 3, False), (40, 3, True)])
-def test_whole_row_reorder_is_bounded_by_the_append_kernels_lds(lib, heads, bits, ok):
-    """A reorder over the whole row with wider codes runs on the append kernel that stages the row
-    in LDS: shapes beyond a compute unit's 160 KB fail at rkv_query_sizes, not at the first append.
-    With 2-bit codes the matrix-core append kernel for such a reorder serves up to 127 KV heads."""
-    cfg = R.RkvConfig(batch=1, n_q_heads=heads, n_kv_heads=heads, max_tokens=128, perm_span=heads * 128, bits=bits)
+@pytest.mark.parametrize("heads,bits,group,ok", [(52, 2, 128, True), (124, 2, 128, True), (128, 2, 128, False), (44, 4, 128, True),
+                                                 (124, 3, 128, True), (128, 4, 128, False), (52, 2, 64, True), (56, 2, 64, False),
+                                                 (40, 4, 32, True), (44, 4, 32, False), (52, 3, 64, False), (40, 3, 32, True)])
+def test_whole_row_reorder_is_bounded_by_the_append_kernels_lds(lib, heads, bits, group, ok):
+    """A reorder over the whole row with groups of 64 / 32 runs on the append kernel that stages the
+    row in LDS: shapes beyond a compute unit's 160 KB fail at rkv_query_sizes, not at the first
+    append.  With groups of 128 the matrix-core append kernel for such a reorder serves up to 127
+    KV heads, whatever the code width."""
+    cfg = R.RkvConfig(batch=1, n_q_heads=heads, n_kv_heads=heads, max_tokens=128, perm_span=heads * 128, bits=bits, quant_group=group)
     if ok:
         R.query_sizes(cfg)
     else:
@@ -123,4 +125,4 @@ def test_whole_row_reorder_is_bounded_by_the_append_kernels_lds(lib, heads, bits
             R.query_sizes(cfg)
         assert ei.value.code == binding.RKV_EINVAL
     # the same head count is fine when the reorder stays inside the rotation groups
-    R.query_sizes(R.RkvConfig(batch=1, n_q_heads=heads, n_kv_heads=heads, max_tokens=128, perm_span=512, bits=bits))
+    R.query_sizes(R.RkvConfig(batch=1, n_q_heads=heads, n_kv_heads=heads, max_tokens=128, perm_span=512, bits=bits, quant_group=group))
