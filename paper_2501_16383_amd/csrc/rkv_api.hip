@@ -130,14 +130,14 @@ static int build_xtables(rkv_cache* cache, const std::vector<int32_t>& inv, int 
     if (inv[c] / n != c / n) in_groups = 0;
   *in_groups_out = in_groups;
   const bool cross = in_groups && !aligned, subs = aligned && qg < 128 && (g == 2 || g == 4);
-  if (!in_groups && !aligned && qg == 128 && (g == 2 || g == 4)) {
+  if (!in_groups && !aligned && (g == 2 || g == 4) && E / qg <= 255) {
     // a reorder over the whole row: the row's quantization block of every rotated channel, as bytes in the
     // order the append kernel's lanes hold them
     std::vector<uint8_t> x8((size_t)nrg * 16 * g * 8, 0);
     for (int rg = 0; rg < nrg; ++rg)
       for (int c = 0; c < n; ++c) {
         const int blk = c >> 7, kap = c & 127, q = kap >> 5, w8 = (kap >> 3) & 3, wave = (w8 >> 1) | ((w8 & 1) << 1);
-        x8[((((size_t)rg * 4 + wave) * 4 + q) * g + blk) * 8 + (kap & 7)] = (uint8_t)(inv[rg * n + c] >> 7);
+        x8[((((size_t)rg * 4 + wave) * 4 + q) * g + blk) * 8 + (kap & 7)] = (uint8_t)(inv[rg * n + c] / qg);
       }
     RKV_HIP_CHECK(hipMemcpyAsync((void*)v.xgid8, x8.data(), x8.size(), hipMemcpyHostToDevice, s));
     RKV_HIP_CHECK(hipStreamSynchronize(s));

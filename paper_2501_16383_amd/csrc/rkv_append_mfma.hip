@@ -574,9 +574,9 @@ __global__ void __launch_bounds__(256, (HB || XW || SUB) ? 4 : 6) k_append_mfma(
 }
 
 // the value role alone (grid x = slabs): the keys of a reorder over the whole row have a kernel of their own
-template <int G, int HB = 0>
-__global__ void __launch_bounds__(256, HB ? 4 : 6) k_append_values(RkvView v, const __half* __restrict__ vin, int n_new, int slab0) {
-  append_mfma_body<G, HB, false, 0>(v, nullptr, vin, n_new, slab0, 3 * blockIdx.x + 2, blockIdx.y, blockIdx.z);
+template <int G, int HB = 0, int SUB = 0>
+__global__ void __launch_bounds__(256, (HB || SUB) ? 4 : 6) k_append_values(RkvView v, const __half* __restrict__ vin, int n_new, int slab0) {
+  append_mfma_body<G, HB, false, SUB>(v, nullptr, vin, n_new, slab0, 3 * blockIdx.x + 2, blockIdx.y, blockIdx.z);
 }
 
 // Keys under a reorder over the whole token row (perm_span = n_kv_heads * 128, Alg. 1 as printed;
@@ -600,7 +600,7 @@ __global__ void __launch_bounds__(256, 3) k_append_row_keys(RkvView v, const __h
   constexpr int ROW16 = 16 * G, STRIDE16 = ROW16 + 1;
   __shared__ __attribute__((aligned(16))) uint32_t lds[16 * STRIDE16 * 4];
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_row[];
-  const int NG = v.E >> 7, NGP = NG | 1;       // (the allocation counts NGP blocks)
+  const int NG = v.NG, NGP = NG | 1;           // the row's quantization blocks (of 128, 64 or 32 positions); the allocation counts NGP
   float* s_mn = reinterpret_cast<float*>(dyn_row);
   float* s_mx = s_mn + 16 * NGP;
   float4* s_par = reinterpret_cast<float4*>(dyn_row + (size_t)2 * 16 * NGP * 4);      // (128 NGP bytes in: 16-byte aligned)
@@ -810,8 +810,9 @@ __global__ void __launch_bounds__(256, 4) k_step_mfma(RkvView v, const __half* _
 // a reorder over the whole row: k_append_row_keys + k_append_values
 static bool append_row(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return !c->blocks_aligned && !c->in_groups && v.qg == 128 && (v.g == 2 || v.g == 4) && v.v_rotate == 0 &&
-         !c->cfg.keys_rotated && (size_t)384 * ((v.E >> 7) | 1) <= 48 * 1024;
+  // (a block's number is a byte in the kernel's table; its dynamic LDS beside 26 KB of static)
+  return !c->blocks_aligned && !c->in_groups && (v.g == 2 || v.g == 4) && v.v_rotate == 0 &&
+         !c->cfg.keys_rotated && v.NG <= 255 && (size_t)384 * (v.NG | 1) <= 120 * 1024;
 }
 int rkv_append_mfma_variant(const rkv_cache* c) {
   return append_row(c) ? RKV_KERNEL_MFMA_ROW : c->v.qg != 128 ? RKV_KERNEL_MFMA_SUB : c->blocks_aligned ? RKV_KERNEL_MFMA : RKV_KERNEL_MFMA_CROSS;
@@ -845,11 +846,14 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
   dim3 grid(3 * max_slabs, v.NRG, v.B);
   if (c->ev_start) RKV_HIP_CHECK(hipEventRecord(c->ev_start, s));
   if (append_row(c)) {
-    const size_t dyn = (size_t)384 * ((v.E >> 7) | 1);
+    const size_t dyn = (size_t)384 * (v.NG | 1);
+#define RKV_AP_VAL(G_, H_, S_) hipLaunchKernelGGL((k_append_values<G_, H_, S_>), dim3(max_slabs, v.NRG, v.B), dim3(256), 0, s, v, vv, n_new, slab0)
 #define RKV_AP_ROW(G_, H_)                                                                                                        \
   do {                                                                                                                            \
+    if (dyn > 48 * 1024)                                                                                                          \
+      RKV_HIP_CHECK(hipFuncSetAttribute((const void*)k_append_row_keys<G_, H_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn)); \
     hipLaunchKernelGGL((k_append_row_keys<G_, H_>), dim3(2 * max_slabs, v.B), dim3(256), dyn, s, v, k, n_new, slab0);             \
-    hipLaunchKernelGGL((k_append_values<G_, H_>), dim3(max_slabs, v.NRG, v.B), dim3(256), 0, s, v, vv, n_new, slab0);             \
+    if (v.qg == 64) RKV_AP_VAL(G_, H_, 2); else if (v.qg == 32) RKV_AP_VAL(G_, H_, 4); else RKV_AP_VAL(G_, H_, 0);                \
   } while (0)
     if (v.g == 4) {
       if (v.hb == 2) RKV_AP_ROW(4, 2); else if (v.hb == 1) RKV_AP_ROW(4, 1); else RKV_AP_ROW(4, 0);
@@ -857,6 +861,7 @@ int rkv_launch_append_mfma(rkv_cache* c, const __half* k, const __half* vv, int 
       if (v.hb == 2) RKV_AP_ROW(2, 2); else if (v.hb == 1) RKV_AP_ROW(2, 1); else RKV_AP_ROW(2, 0);
     }
 #undef RKV_AP_ROW
+#undef RKV_AP_VAL
   } else {
     // (G, bits above the low two, cross-block flag, sub-blocks per head)
 #define RKV_AP(G_, H_, X_, S_) hipLaunchKernelGGL((k_append_mfma<G_, H_, X_, S_>), grid, dim3(256), 0, s, v, k, vv, n_new, slab0)
