@@ -99,7 +99,9 @@ def compare_codes(pre: np.ndarray, o_codes, o_scale, o_zero, g_codes, g_scale, g
         assert np.all(np.abs(g_scale - o_scale) <= np.abs(ulp) + 0.0), f"{what}: scale off by more than one fp16 ulp"
         assert np.all(np.abs(g_zero - o_zero) <= 1.0), f"{what}: zero off by more than 1"
     # a scale one E4M3 step (up to 1/8) apart moves the largest code by up to top / 8
-    code_slack = 1 + (int(np.ceil(top / 8.0)) if meta_format == 1 and bits > 2 else 0)
+    # (2-bit codes too: 3/8 of a step from the scale, one from the zero-point that moves with it, and both roundings
+    # near a half gave 2 in one of some 3000 randomly drawn cases - the block's range / 3 was 11.0000006)
+    code_slack = 1 + (int(np.ceil(top / 8.0)) if meta_format == 1 else 0)
     assert np.all(np.abs(oc - gc) <= code_slack), f"{what}: a code is off by more than {code_slack}"
     recon = g_scale[..., None] * (gc - g_zero[..., None])
     slack = 1e-5 * np.maximum(np.abs(mx), np.abs(mn))[..., None]
