@@ -59,10 +59,7 @@ typedef struct rkv_config {
                         /* 3- and 4-bit codes in groups of 128 run on the matrix-core kernels    */
                         /* like 2-bit ones (the bits above the low two as a second plane);       */
                         /* groups of 64 / 32 have variants of the matrix-core kernels for every  */
-                        /* code width and either metadata format with a reorder inside the       */
-                        /* rotation groups (with a reorder over the whole row those groups take  */
-                        /* the general kernels, which means no rkv_quantize_append_ragged and a  */
-                        /* two-kernel rkv_decode_step)                                           */
+                        /* code width, either metadata format and every reorder (rot_heads 2, 4) */
   int32_t perm_span;    /* reorder indices stay inside blocks of this many channels:            */
                         /* head_dim, rot_heads*head_dim, or n_kv_heads*head_dim (Alg. 1 as       */
                         /* printed sorts the whole row).  The append kernel for a reorder across */
@@ -180,7 +177,7 @@ int rkv_quantize_append(rkv_cache* cache, const void* dev_k, const void* dev_v, 
  *   host_n_new      [batch] int32 in host memory, 0 <= host_n_new[b] <= n_new_max; read before the call returns
  *   dev_sink_mask   [batch][n_new_max] uint8 or NULL
  * Needs a configuration the matrix-core append kernel covers (a reorder inside the rotation groups -
- * or, with groups of 128, anywhere in the row -, rot_heads 2 or 4, v_rotate 0),
+ * or anywhere in the row -, rot_heads 2 or 4, v_rotate 0),
  * else RKV_EINVAL; RKV_ECAPACITY if any sequence would pass
  * max_tokens (nothing is appended then).  rkv_import_codes returns RKV_ESTATE on such a cache;
  * the export and dequantize views cover rkv_cache_length tokens for every sequence, and what they
@@ -262,7 +259,7 @@ int rkv_decode_attention_multi(rkv_cache* cache, const void* dev_q, const int32_
 /* Choose the decode kernel: 0 = automatic (default), 1 = force the general kernel (any supported
  * configuration, vector ALU), 2 = force the matrix-core kernel (RKV_EINVAL at the next decode if
  * the configuration is outside what it covers: a reorder across rotation groups, rot_heads 1 or
- * 8; a reorder over the whole row only with groups of 128; several query tokens
+ * 8; several query tokens
  * per step with a reorder across blocks of 128 or with quant_group 64 or 32 only up to 8 (query
  * token, query head) pairs per KV head).
  * 3 = measurement only: the matrix-core kernel with the cache stream (codes and metadata of keys
@@ -288,9 +285,10 @@ int rkv_set_decode_path(rkv_cache* cache, int32_t path);
                                  /* scores kernel of the whole-row path, the rest by the matrix-core one) */
 #define RKV_KERNEL_MFMA_ROW   6  /* a reorder over the whole row.  Decode: scores by a kernel of their */
                                  /* own (fp16 matrix products), the rest by the matrix-core one; append: */
-                                 /* keys by a kernel that sees whole token rows (groups of 128,          */
-                                 /* rot_heads 2 or 4; wider codes: the scores kernel runs once per plane */
-                                 /* of code bits, rows of up to 63 blocks)                               */
+                                 /* keys by a kernel that sees whole token rows (rot_heads 2 or 4;       */
+                                 /* wider codes: the scores kernel runs once per plane of code bits,     */
+                                 /* rows of up to 63 blocks; groups of 64 / 32: once per share of at     */
+                                 /* most 40 of the row's blocks)                                         */
 int rkv_decode_kernel_of(const rkv_cache* cache, int32_t n_queries);
 int rkv_append_kernel_of(const rkv_cache* cache);
 

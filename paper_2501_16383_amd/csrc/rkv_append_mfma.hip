@@ -580,7 +580,7 @@ __global__ void __launch_bounds__(256, (HB || SUB) ? 4 : 6) k_append_values(RkvV
 }
 
 // Keys under a reorder over the whole token row (perm_span = n_kv_heads * 128, Alg. 1 as printed;
-// groups of 128; HB as in k_append_mfma: codes of 3 or 4 bits, the bits above the low two to their plane).  A rotated channel then belongs to any of the row's E / 128
+// HB as in k_append_mfma: codes of 3 or 4 bits, the bits above the low two to their plane).  A rotated channel then belongs to any of the row's E / quant_group
 // quantization blocks, so a block's minimum and maximum (Eq. 8-9) need the rotated values of all
 // rotation groups of the token.  One workgroup = (sequence, tile of 16 tokens) takes the groups one
 // after the other, twice: the first pass rotates (H_128 on fp16 matrix products, H_g in the lane,

@@ -1011,10 +1011,10 @@ static bool mfma_cross_block(const rkv_cache* c) {
   return !c->blocks_aligned && c->in_groups && v.qg == 128 && rkv_scores_local(c);
 }
 
-// groups of 64 / 32 with the reorder inside the rotation groups: the same route
+// groups of 64 / 32 (the reorder inside the rotation groups, or over the whole row): the same route
 static bool mfma_sub_groups(const rkv_cache* c) {
   const RkvView& v = c->v;
-  return v.qg < 128 && rkv_scores_local(c);
+  return v.qg < 128 && rkv_scores_path(c);
 }
 
 int rkv_mfma_variant(const rkv_cache* c) {
@@ -1038,7 +1038,7 @@ static RkvDecodeFn pick_kernel(const rkv_cache* c, bool multi, int share, bool a
 #define RKV_MF_PRE_M(G_, R_, S_, H_, M_) (v.meta8 ? k_decode_mfma<G_, R_, M_, true, H_, S_, false, true> : k_decode_mfma<G_, R_, M_, false, H_, S_, false, true>)
 #define RKV_MF_PRE(G_, R_, S_, H_) (multi ? RKV_MF_PRE_M(G_, R_, S_, H_, true) : RKV_MF_PRE_M(G_, R_, S_, H_, false))
 #define RKV_MF_PRE_SUB(G_, H_) (sub == 4 ? RKV_MF_PRE(G_, 1, 4, H_) : RKV_MF_PRE(G_, 1, 2, H_))
-  if (rkv_scores_local(c) && v.qg < 128) {                  // (groups of 64 / 32: codes of 2, 3 or 4 bits)
+  if (v.qg < 128 && rkv_scores_path(c)) {                   // (groups of 64 / 32: codes of 2, 3 or 4 bits)
     const int sub = 128 / v.qg;
     if (v.g == 4) return v.hb == 2 ? RKV_MF_PRE_SUB(4, 2) : v.hb == 1 ? RKV_MF_PRE_SUB(4, 1) : RKV_MF_PRE_SUB(4, 0);
     return v.hb == 2 ? RKV_MF_PRE_SUB(2, 2) : v.hb == 1 ? RKV_MF_PRE_SUB(2, 1) : RKV_MF_PRE_SUB(2, 0);

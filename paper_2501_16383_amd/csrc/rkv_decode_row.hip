@@ -390,15 +390,23 @@ __device__ __forceinline__ void rs2_settle(float (&q)[2][4]) {
 // HB = 1, 2 without LOCAL (a reorder over the whole row, where two table halves would not fit): this launch
 // takes the plane of upper bits alone - the table holds s * 4 c_hi - and adds its scores to those a launch
 // with HB = 0 has left in the buffer.
-template <int G, int STYLE, bool LOCAL, int HB = 0>
-__global__ void __launch_bounds__(256, (HB && LOCAL) ? 2 : RS2_OCC) k_scores_row2(RkvView v, const float* __restrict__ qr, float* __restrict__ sc, int rep) {
+// PART (a reorder over the whole row with groups of 64 / 32, whose 2 to 4 times as many blocks do not fit a
+// wave's table): this launch takes the row's blocks b0 .. b0 + cnt - 1 alone.  A channel of any other block
+// looks up an all-zero block behind them, and the launches' scores add up in the buffer.
+// part = b0 | cnt << 12 | (add to the scores in the buffer) << 24.
+template <int G, int STYLE, bool LOCAL, int HB = 0, bool PART = false>
+__global__ void __launch_bounds__(256, (HB && LOCAL) ? 2 : RS2_OCC) k_scores_row2(RkvView v, const float* __restrict__ qr, float* __restrict__ sc, int rep,
+                                                                                 int part) {
+  static_assert(!PART || !LOCAL, "a share of the row's blocks: the whole-row reorder");
   constexpr int n = 128 * G;
+  const int pb0 = part & 0xfff, pcnt = (part >> 12) & 0xfff;
+  const bool padd = (part >> 24) != 0;
   constexpr bool UPPER = HB != 0 && !LOCAL;             // the upper plane's launch of a pair
   constexpr int NPL = (HB && LOCAL) ? 2 : 1;            // planes of code bits in this launch, each with its half of the table
   // (no static LDS in this kernel: the tables start where the workgroup's LDS starts, so that a table's byte
   // address >> 8 plus a block index stays below 256 for rows of up to RS2_MAX_NG blocks)
   extern __shared__ __attribute__((aligned(256))) unsigned char dyn2[];
-  const int NG = LOCAL ? v.gm : v.E >> 7, nqh = G * rep;   // blocks in a wave's table
+  const int NG = LOCAL ? v.gm : PART ? pcnt + 1 : v.E >> 7, nqh = G * rep;   // blocks in a wave's table
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int NGT = NG * NPL;                              // blocks of a wave's table, both halves
@@ -430,6 +438,7 @@ __global__ void __launch_bounds__(256, (HB && LOCAL) ? 2 : RS2_OCC) k_scores_row
   const int rounds = (v.NRG + 3) >> 2;
 
   uint4 cw[G / 2], cwh[HB ? G / 2 : 1];
+  uint32_t mb[PART ? 16 : 1];                            // PART: the lane's token's entries of blocks b0 + kq + 4 i
   uint32_t mw[RS2_MPRE][G];
   uint32_t ml[4] = {0, 0, 0, 0};
   const int bpl = LOCAL ? (v.gm >= 4 ? v.gm >> 2 : 1) : 0;                // blocks per lane group (1, 2 or 4; with two blocks, lane groups 0 and 1 take one each)
@@ -452,6 +461,24 @@ __global__ void __launch_bounds__(256, (HB && LOCAL) ? 2 : RS2_OCC) k_scores_row
         const uint2 u = rkv_ld_stream(kth + 64 * bp + lane);
         cwh[bp] = make_uint4(u.x, u.y, 0, 0);
       }
+    }
+    if constexpr (PART) {
+      const int lg = __builtin_ctz((unsigned)v.gm);        // (v.gm = G * 128 / quant_group: a power of two)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int bi = kq + 4 * i;
+        if (bi < pcnt) {
+          const int blk = pb0 + bi, rgb = blk >> lg, j = blk & (v.gm - 1);
+          const size_t e = ((size_t)(b * v.NRG + rgb) * v.Tpad + tt + tok) * v.gm;
+          if (v.meta8) {
+            const uint8_t* m8 = reinterpret_cast<const uint8_t*>(v.km) + 2 * e;
+            mb[i] = rs2_meta8_pair(m8[j], m8[v.gm + j], 0);
+          } else {
+            mb[i] = v.km[e + j];
+          }
+        }
+      }
+      return;
     }
     if constexpr (LOCAL) {
       // the token's v.gm entries of this rotation group: a quarter of them per lane group
@@ -516,7 +543,11 @@ __global__ void __launch_bounds__(256, (HB && LOCAL) ? 2 : RS2_OCC) k_scores_row
     const int c0 = 128 * h + 32 * q + 16 * dw + 8 * (ksh & 1) + (ksh >> 1);
     uint32_t w = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w |= (uint32_t)(v.gid[rg * n + c0 + 2 * j] - (LOCAL ? rg * v.gm : 0)) << (8 * j);
+    for (int j = 0; j < 4; ++j) {
+      uint32_t bid = (uint32_t)(v.gid[rg * n + c0 + 2 * j] - (LOCAL ? rg * v.gm : PART ? pb0 : 0));
+      if (PART && bid >= (uint32_t)pcnt) bid = (uint32_t)pcnt;       // another launch's block: the all-zero one
+      w |= bid << (8 * j);
+    }
     const uint32_t tab0 = (uint32_t)(uintptr_t)(rs2_lds_u8*)dyn2;     // LDS byte address of the first table (a multiple of 256)
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) s_g4[ww * (4 * G * 8) + tid] = w + (((tab0 >> 8) + (uint32_t)(ww * NGT)) * 0x01010101u);
@@ -561,15 +592,24 @@ __global__ void __launch_bounds__(256, (HB && LOCAL) ? 2 : RS2_OCC) k_scores_row
       for (int i = 0; i < 4; ++i)
         if (i < bpl && lact) put_block(kq * bpl + i, ml[i]);
     }
+    if constexpr (PART) {
+      if (kq == 0) {
+        uint32_t* e = s_tab + (pcnt * 4) * 16 + tok;
+        e[0] = e[16] = e[32] = e[48] = 0u;
+      }
 #pragma unroll
-    for (int k = 0; k < (LOCAL ? 0 : RS2_MPRE); ++k) {
+      for (int i = 0; i < 16; ++i)
+        if (kq + 4 * i < pcnt) put_block(kq + 4 * i, mb[i]);
+    }
+#pragma unroll
+    for (int k = 0; k < ((LOCAL || PART) ? 0 : RS2_MPRE); ++k) {
       const int g2 = kq + 4 * k;
       if (g2 < v.NRG) {
 #pragma unroll
         for (int j = 0; j < G; ++j) put_block(g2 * G + j, mw[k][j]);
       }
     }
-    for (int k = RS2_MPRE; k < (LOCAL ? 0 : rounds); ++k) {
+    for (int k = RS2_MPRE; k < ((LOCAL || PART) ? 0 : rounds); ++k) {
       const int g2 = kq + 4 * k;
       if (g2 < v.NRG) {
         if (v.meta8) {
@@ -768,23 +808,33 @@ __global__ void __launch_bounds__(256, (HB && LOCAL) ? 2 : RS2_OCC) k_scores_row
         for (int k = 0; k < cnt; ++k) sink |= (s_sink[k] == tk);
         float* srow = sc + ((size_t)b * v.Hq + (size_t)rg * nqh) * v.Tpad + tt;
         float* dst = &srow[(uint32_t)(hr * v.Tpad + (i & 15))];
-        *dst = sink ? -INFINITY : (UPPER ? *dst + s_pd[i] * out_scale : s_pd[i] * out_scale);
+        *dst = sink ? -INFINITY : ((UPPER || (PART && padd)) ? *dst + s_pd[i] * out_scale : s_pd[i] * out_scale);
       }
     }
   }
 }
 
-static size_t row2_dynamic_lds(const RkvView& v, bool local) {
-  const int nqh = v.g * (v.Hq / v.Hkv), NG = local ? v.gm * (v.hb ? 2 : 1) : v.E >> 7;   // (wider codes, own blocks: a table half per plane)
+static size_t row2_lds_of(const RkvView& v, int NG) {
+  const int nqh = v.g * (v.Hq / v.Hkv);
   return (size_t)4 * NG * 256 + (size_t)4 * nqh * 64 + (size_t)nqh * RKV_D * 4 + (size_t)4 * 4 * v.g * 8 * 4 + 256;
 }
+// A whole-row reorder with groups of 64 / 32: the row's E / quant_group blocks go to the scores kernel in shares of
+// at most RS2_PART_MAX (each share a launch, with an all-zero block behind its own in the table).
+#define RS2_PART_MAX 40
+static int row2_parts(const RkvView& v) { return v.qg < 128 ? (v.NG + RS2_PART_MAX - 1) / RS2_PART_MAX : 1; }
+static int row2_part_blocks(const RkvView& v) { const int np = row2_parts(v); return (v.NG + np - 1) / np; }
+static size_t row2_dynamic_lds(const RkvView& v, bool local) {
+  // (wider codes, own blocks: a table half per plane; shares of the row's blocks: the all-zero block besides)
+  return row2_lds_of(v, local ? v.gm * (v.hb ? 2 : 1) : v.qg < 128 ? row2_part_blocks(v) + 1 : v.E >> 7);
+}
 static bool row2_applies(const RkvView& v) {
+  if (v.qg < 128) return v.NG <= 4095 && row2_dynamic_lds(v, false) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
   return (v.E >> 7) <= RS2_MAX_NG && row2_dynamic_lds(v, false) + 1024 <= (size_t)RKV_LDS_BYTES / 2;
 }
 
 // Whether a cache takes this path: a reorder that leaves the rotation groups (else the plain kernel or
-// rkv_scores_local's route serves it), groups of 128, rot_heads 2 or 4 (8-bit metadata and wider codes where the
-// table-per-wave kernel applies).
+// rkv_scores_local's route serves it), rot_heads 2 or 4 (8-bit metadata, wider codes and groups of 64 / 32 where
+// the table-per-wave kernel applies).
 static size_t row_dynamic_lds(const RkvView& v) {
   const int nqh = v.g * (v.Hq / v.Hkv), NG = v.E >> 7;
   return (size_t)16 * (NG | 1) * 16 + (size_t)nqh * RKV_D * 4 + (size_t)4 * nqh * 16 * 4;
@@ -792,7 +842,8 @@ static size_t row_dynamic_lds(const RkvView& v) {
 
 bool rkv_row_supported(const rkv_cache* c) {
   const RkvView& v = c->v;
-  if (c->blocks_aligned || c->in_groups || v.qg != 128 || !(v.g == 2 || v.g == 4)) return false;
+  if (c->blocks_aligned || c->in_groups || !(v.g == 2 || v.g == 4)) return false;
+  if (v.qg < 128) return row2_applies(v);                   // (groups of 64 / 32: the table-per-wave kernel, a share of the blocks per launch)
   if ((v.meta8 || v.hb) && !row2_applies(v)) return false; // (8-bit metadata, wider codes: the table-per-wave kernel only)
   // two workgroups per compute unit must fit its LDS; a tile's metadata: at most 32 rotation groups
   const size_t fixed = (size_t)2 * 16 * (16 * v.g + 1) * 16 + (size_t)144 * v.g * 4 + 256;
@@ -839,31 +890,35 @@ int rkv_launch_scores_row(const rkv_cache* c, const RkvView& v, const float* qr,
   if (local || row2_applies(v)) {
     const size_t dyn = row2_dynamic_lds(v, local);
     dim3 grid((v.len + RS2_CHUNK - 1) / RS2_CHUNK, v.NRG, v.B);
-    void (*fn)(RkvView, const float*, float*, int);
-    if (local && v.hb == 2)
-      fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, true, 2> : k_scores_row2<4, 1, true, 2>)
-                    : (v.rope_style == 0 ? k_scores_row2<2, 0, true, 2> : k_scores_row2<2, 1, true, 2>);
-    else if (local && v.hb == 1)
-      fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, true, 1> : k_scores_row2<4, 1, true, 1>)
-                    : (v.rope_style == 0 ? k_scores_row2<2, 0, true, 1> : k_scores_row2<2, 1, true, 1>);
-    else if (local)
-      fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, true> : k_scores_row2<4, 1, true>)
-                    : (v.rope_style == 0 ? k_scores_row2<2, 0, true> : k_scores_row2<2, 1, true>);
-    else
-      fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, false> : k_scores_row2<4, 1, false>)
-                    : (v.rope_style == 0 ? k_scores_row2<2, 0, false> : k_scores_row2<2, 1, false>);
-    if (dyn > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
-    hipLaunchKernelGGL(fn, grid, dim3(256), dyn, s, v, qr, sc, rep);
-    if (!local && v.hb) {                                  // the plane of upper bits: a launch of its own, onto the same scores
-      if (v.hb == 2)
-        fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, false, 2> : k_scores_row2<4, 1, false, 2>)
-                      : (v.rope_style == 0 ? k_scores_row2<2, 0, false, 2> : k_scores_row2<2, 1, false, 2>);
-      else
-        fn = v.g == 4 ? (v.rope_style == 0 ? k_scores_row2<4, 0, false, 1> : k_scores_row2<4, 1, false, 1>)
-                      : (v.rope_style == 0 ? k_scores_row2<2, 0, false, 1> : k_scores_row2<2, 1, false, 1>);
+    typedef void (*ScoresFn)(RkvView, const float*, float*, int, int);
+    // (G, RoPE pairing) x (own blocks, planes of code bits, a share of the row's blocks)
+#define RS2_FN_GS(L_, H_, P_)                                                                                       \
+  (v.g == 4 ? (v.rope_style == 0 ? (ScoresFn)k_scores_row2<4, 0, L_, H_, P_> : (ScoresFn)k_scores_row2<4, 1, L_, H_, P_>) \
+            : (v.rope_style == 0 ? (ScoresFn)k_scores_row2<2, 0, L_, H_, P_> : (ScoresFn)k_scores_row2<2, 1, L_, H_, P_>))
+    auto launch = [&](ScoresFn fn, int part) -> int {
       if (dyn > 48 * 1024) RKV_HIP_CHECK(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
-      hipLaunchKernelGGL(fn, grid, dim3(256), dyn, s, v, qr, sc, rep);
+      hipLaunchKernelGGL(fn, grid, dim3(256), dyn, s, v, qr, sc, rep, part);
+      return RKV_OK;
+    };
+    int rc = RKV_OK;
+    if (local) {
+      rc = launch(v.hb == 2 ? RS2_FN_GS(true, 2, false) : v.hb == 1 ? RS2_FN_GS(true, 1, false) : RS2_FN_GS(true, 0, false), 0);
+    } else if (v.qg == 128) {
+      rc = launch(RS2_FN_GS(false, 0, false), 0);
+      // the plane of upper bits: a launch of its own, onto the same scores
+      if (rc == RKV_OK && v.hb) rc = launch(v.hb == 2 ? RS2_FN_GS(false, 2, false) : RS2_FN_GS(false, 1, false), 0);
+    } else {
+      // groups of 64 / 32: a launch per share of the row's blocks (and per plane of code bits), all onto the same scores
+      const int np = row2_parts(v), per = row2_part_blocks(v);
+      for (int p = 0; p < np && rc == RKV_OK; ++p) {
+        const int b0 = p * per, cnt = (b0 + per <= v.NG ? per : v.NG - b0);
+        rc = launch(RS2_FN_GS(false, 0, true), b0 | (cnt << 12) | ((p > 0 ? 1 : 0) << 24));
+        if (rc == RKV_OK && v.hb)
+          rc = launch(v.hb == 2 ? RS2_FN_GS(false, 2, true) : RS2_FN_GS(false, 1, true), b0 | (cnt << 12) | (1 << 24));
+      }
     }
+#undef RS2_FN_GS
+    if (rc != RKV_OK) return rc;
     return rkv_check_launch();
   }
   const size_t dyn = row_dynamic_lds(v);

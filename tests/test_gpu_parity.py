@@ -1337,7 +1337,9 @@ def test_rotated_keys_with_fp8_metadata_and_one_call_steps():
                                                       (3, 128, 2, 16, 1, 256), (3, 128, 4, 32, 0, 512), (4, 128, 2, 8, 1, 256),
                                                       (2, 64, 4, 8, 0, 512), (2, 32, 2, 16, 1, 256), (2, 32, 4, 16, 0, 512),
                                                       (3, 32, 4, 8, 1, 512), (4, 64, 2, 8, 0, 256), (4, 128, 4, 8, 0, 1024),
-                                                      (3, 128, 2, 16, 1, 1024), (3, 128, 4, 32, 0, 1024), (4, 128, 2, 8, 1, 1024)])
+                                                      (3, 128, 2, 16, 1, 1024), (3, 128, 4, 32, 0, 1024), (4, 128, 2, 8, 1, 1024),
+                                                      (2, 64, 4, 8, 0, 1024), (2, 32, 2, 16, 1, 1024), (4, 32, 4, 16, 0, 1024),
+                                                      (3, 64, 2, 8, 1, 1024), (2, 32, 4, 32, 0, 1024)])
 def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
     """3- and 4-bit codes and quantization groups of 64 and 32 channels (Sec. 5.1; Tables
     tab:ablation and tab:quantgrani) through the write half, the export and dequantize views and
@@ -1357,7 +1359,7 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
         assert not np.array_equal(perm // group, np.arange(cfg.E) // group)
     # wider codes in groups of 128 are read by the matrix-core decode kernel as two planes, codes in
     # smaller groups by its sub-group variant (scores from the scores kernel, one table half per plane)
-    on_matrix_cores = g in (2, 4) and (span in (128, 128 * g) or group == 128)     # (span 1024: the whole row)
+    on_matrix_cores = g in (2, 4)                               # (any of the spans here: 128, the rotation group, 1024 = the whole row)
     # half of the cases without any retained fp16 row, so that the compressed stream alone decides the outputs
     cache, oc, q = full_check(w, cfg, 213, perm=perm, chunks=[0, 100, 101, 102, 213], paths=(1, 2) if on_matrix_cores else (1, 0),
                               sink_positions=[] if (hq + group + bits) % 3 != 0 else None)
@@ -1368,7 +1370,7 @@ def test_wider_codes_and_smaller_groups(bits, group, g, hq, fmt, span):
             cache.decode_attention(P.gpu(q))
     cache.set_decode_path(0)
     if on_matrix_cores:
-        want = (RB.KERNEL_MFMA_SUB if group != 128 else RB.KERNEL_MFMA_ROW if span == 1024 else RB.KERNEL_MFMA_CROSS if span != 128
+        want = (RB.KERNEL_MFMA_ROW if span == 1024 else RB.KERNEL_MFMA_SUB if group != 128 else RB.KERNEL_MFMA_CROSS if span != 128
                 else RB.KERNEL_MFMA)
         assert cache.append_kernel() == want and cache.decode_kernel() == want
     # one more single-token step through rkv_decode_step (the two calls, on this setting)
@@ -1535,7 +1537,7 @@ def test_randomly_drawn_configurations(seed):
             elif kind == "across blocks":
                 bits, group, span = rnd.choice([2, 2, 3, 4]), rnd.choice([128, 128, 64, 32]), 128 * g
             else:
-                bits, group, span = rnd.choice([2, 2, 3, 4]), 128, 128 * hkv
+                bits, group, span = rnd.choice([2, 2, 3, 4]), rnd.choice([128, 128, 64, 32]), 128 * hkv
         B = rnd.choice([1, 2, 3])
         T = rnd.choice([1, 15, 16, 17, 63, 64, 65, 100, 255, 256, 257, rnd.randint(1, 600), rnd.randint(200, 900)])
         sinks = rnd.choice([0, 4, 2])
@@ -1590,7 +1592,7 @@ def test_randomly_drawn_steps_lengths_and_query_counts(seed):
             elif kind == "across blocks":
                 bits, group, span = rnd.choice([2, 2, 3, 4]), rnd.choice([128, 128, 64, 32]), 128 * g
             else:
-                bits, group, span = rnd.choice([2, 2, 3, 4]), 128, 128 * hkv
+                bits, group, span = rnd.choice([2, 2, 3, 4]), rnd.choice([128, 128, 64, 32]), 128 * hkv
         B, sinks = rnd.choice([1, 2, 3, 4]), rnd.choice([0, 4, 2])
         t_max = rnd.choice([1, 16, 17, 64, 65, 255, 256, 257, rnd.randint(1, 500), rnd.randint(100, 700)])
         lens = [t_max] * B
