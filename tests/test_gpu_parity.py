@@ -528,21 +528,21 @@ def test_full_size_config2_sampled(meta_format, bits, with_sinks, group, span):
                     meta_format=meta_format, bits=bits, group=group, span=span)
 
 
-@pytest.mark.parametrize("with_sinks,bits", [(False, 2), (True, 2), (False, 4), (False, 3)])
-def test_full_size_config2_whole_row_reorder_sampled(with_sinks, bits):
+@pytest.mark.parametrize("with_sinks,bits,group", [(False, 2, 128), (True, 2, 128), (False, 4, 128), (False, 3, 128), (False, 2, 64)])
+def test_full_size_config2_whole_row_reorder_sampled(with_sinks, bits, group):
     """Configuration 2's geometry with the reorder over the whole token row (perm_span = 5120:
     Alg. 1 as printed), at full size: bulk append, then decode attention on the path bench.py
     times for this setting (scores kernel + matrix-core decode kernel).  With such a reorder a
     quantization block mixes channels of every rotation group, so the oracle recomputes whole
     sequences (two of the sixteen, all 40 heads): codes under the tie protocol, then attention on
     the GPU's own codes.  Also with 4- and 3-bit codes (the scores kernel then runs once per plane
-    of code bits)."""
+    of code bits) and with groups of 64 (once per share of the row's 80 blocks)."""
     w = S.WORKLOADS["cfg2"]
     T = w.context
     n_keep = 4 if with_sinks else 0
     cfg = R.RkvConfig(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, max_tokens=T, max_sinks=n_keep,
-                      rot_heads=4, perm_span=w.n_kv_heads * 128, bits=bits)
-    perm = calibrated_perm(w, dataclasses.replace(cfg, bits=2), offset_variant=True)
+                      rot_heads=4, perm_span=w.n_kv_heads * 128, bits=bits, quant_group=group)
+    perm = calibrated_perm(w, dataclasses.replace(cfg, bits=2, quant_group=128), offset_variant=True)
     assert not np.array_equal(perm // 512, np.arange(cfg.E) // 512)
     cache = R.RkvCache(cfg)
     cache.set_perm(P.gpu(np.asarray(perm, dtype=np.int32)))
@@ -578,9 +578,9 @@ def test_full_size_config2_whole_row_reorder_sampled(with_sinks, bits):
             g[name + "_scale"] = exp[name + "_scale"][b:b + 1].astype(np.float64)
             g[name + "_zero"] = exp[name + "_zero"][b:b + 1].astype(np.float64)
         P.compare_codes(oc.k_rot, oc.k_codes, oc.k_scale, oc.k_zero, g["k_codes"], g["k_scale"], g["k_zero"],
-                        f"whole-row full size b={b} K", rot_span=cfg.E, bits=bits)    # (a block's members come from any rotation group)
+                        f"whole-row full size b={b} K", rot_span=cfg.E, bits=bits, group=group)    # (a block's members come from any rotation group)
         P.compare_codes(oc.v_in, oc.v_codes, oc.v_scale, oc.v_zero, g["v_codes"], g["v_scale"], g["v_zero"], f"whole-row full size b={b} V",
-                        bits=bits)
+                        bits=bits, group=group)
         for name, val in g.items():                            # attention on the GPU's own codes
             setattr(oc, name, val)
         ref, lse_ref = O.decode_attention(oc, q[b:b + 1])
